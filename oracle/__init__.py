@@ -1,0 +1,187 @@
+"""ctypes binding of the CPU oracle (oracle/hca_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+cpu_baseline leg of bench.py.  The product package never imports this module
+and this module never imports the product package.
+
+All arrays are numpy, host memory, canonical layouts:
+  keys / values / queries   uint16 views of fp16 data
+  codes  uint8  [R, cap, D*bits/8]   scale, zero  uint16 [R, cap, D/gs]
+R = batch * kv_heads rows; query head r*G+g belongs to row r.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = C.CDLL(path)
+        L.hco_h2f.restype = C.c_float
+        L.hco_h2f.argtypes = [C.c_uint16]
+        L.hco_f2h.restype = C.c_uint16
+        L.hco_f2h.argtypes = [C.c_float]
+        L.hco_num_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _u16(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16:
+        a = a.view(np.uint16)
+    assert a.dtype == np.uint16, a.dtype
+    return a
+
+
+def _i64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int64))
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def num_threads():
+    return int(lib().hco_num_threads())
+
+
+def h2f(bits):
+    return float(lib().hco_h2f(int(bits)))
+
+
+def f2h(x):
+    return int(lib().hco_f2h(float(x)))
+
+
+class Cache:
+    """Canonical quantised key cache for R rows."""
+
+    def __init__(self, R, cap, D=128, bits=4, gs=32):
+        self.R, self.cap, self.D, self.bits, self.gs = R, cap, D, bits, gs
+        self.NG, self.CB = D // gs, D * bits // 8
+        self.codes = np.zeros((R, cap, self.CB), np.uint8)
+        self.scale = np.zeros((R, cap, self.NG), np.uint16)
+        self.zero = np.zeros((R, cap, self.NG), np.uint16)
+        self.n = np.zeros(R, np.int64)
+
+    def copy(self):
+        o = Cache(self.R, self.cap, self.D, self.bits, self.gs)
+        o.codes[...] = self.codes
+        o.scale[...] = self.scale
+        o.zero[...] = self.zero
+        o.n[...] = self.n
+        return o
+
+
+def attention_exact(q, K, V, sm_scale):
+    """Eq. 1 in fp64 for one head.  q [D], K [n,D], V [n,D] fp16."""
+    q, K, V = _u16(q), _u16(K), _u16(V)
+    n, D = K.shape
+    y = np.zeros(D, np.float64)
+    _check(lib().hco_attention_exact(_p(q), _p(K), _p(V), C.c_int64(n), C.c_int(D),
+                                     C.c_double(sm_scale), _p(y)), "attention_exact")
+    return y
+
+
+def quantize(cache, k_new):
+    """Append k_new [R,T,D] fp16 to the cache at slots n..n+T-1."""
+    k_new = _u16(k_new)
+    R, T, D = k_new.shape
+    assert R == cache.R and D == cache.D
+    _check(lib().hco_quantize(_p(k_new), C.c_int64(R), C.c_int64(T), C.c_int(D),
+                              C.c_int(cache.bits), C.c_int(cache.gs), C.c_int64(cache.cap),
+                              _p(cache.n), _p(cache.codes), _p(cache.scale), _p(cache.zero)),
+           "quantize")
+    cache.n += T
+
+
+def dequantize(cache):
+    khat = np.zeros((cache.R, cache.cap, cache.D), np.float32)
+    _check(lib().hco_dequantize(_p(cache.codes), _p(cache.scale), _p(cache.zero),
+                                C.c_int64(cache.R), C.c_int(cache.D), C.c_int(cache.bits),
+                                C.c_int(cache.gs), C.c_int64(cache.cap), _p(cache.n), _p(khat)),
+           "dequantize")
+    return khat
+
+
+def query_fixed(q):
+    """q [D] fp16 -> (qfx int32 [D], s)."""
+    q = _u16(q)
+    qfx = np.zeros(q.shape[0], np.int32)
+    s = C.c_int32(0)
+    _check(lib().hco_query_fixed(_p(q), C.c_int(q.shape[0]), _p(qfx), C.byref(s)), "query_fixed")
+    return qfx, int(s.value)
+
+
+def score(cache, q, want_z=True):
+    """q [R*G, D] fp16 -> (sel [R,cap] fp32, z [R*G,cap] fp32 or None)."""
+    q = _u16(q)
+    G = q.shape[0] // cache.R
+    sel = np.zeros((cache.R, cache.cap), np.float32)
+    z = np.zeros((cache.R * G, cache.cap), np.float32) if want_z else None
+    _check(lib().hco_score(_p(q), _p(cache.codes), _p(cache.scale), _p(cache.zero),
+                           C.c_int64(cache.R), C.c_int(G), C.c_int(cache.D), C.c_int(cache.bits),
+                           C.c_int(cache.gs), C.c_int64(cache.cap), _p(cache.n), _p(sel), _p(z)),
+           "score")
+    return sel, z
+
+
+def topk(sel, n, k):
+    """sel [R,cap] fp32, n [R] -> (idx int32 [R,k] ascending, -1 padded; count int32 [R])."""
+    sel = np.ascontiguousarray(sel, np.float32)
+    R, cap = sel.shape
+    n = _i64(n)
+    idx = np.zeros((R, max(k, 1)), np.int32)[:, :k].copy()
+    idx = np.ascontiguousarray(idx)
+    count = np.zeros(R, np.int32)
+    _check(lib().hco_topk(_p(sel), C.c_int64(R), C.c_int64(cap), _p(n), C.c_int64(k),
+                          _p(idx), _p(count)), "topk")
+    return idx, count
+
+
+def attend(cache, q, idx, count, pos, V, sm_scale, acc=None, want_w=False):
+    """V [R, vrows, D] fp16; pos int32 [R,cap].  Returns (y [R*G,D] fp32, w or None).
+    acc (fp32 [R,cap]) is updated in place when given."""
+    q, V = _u16(q), _u16(V)
+    G = q.shape[0] // cache.R
+    idx = np.ascontiguousarray(idx, np.int32)
+    count = np.ascontiguousarray(count, np.int32)
+    pos = np.ascontiguousarray(pos, np.int32)
+    k = idx.shape[1]
+    y = np.zeros((cache.R * G, cache.D), np.float32)
+    w = np.zeros((cache.R * G, k), np.float32) if want_w else None
+    if acc is not None:
+        assert acc.dtype == np.float32 and acc.flags.c_contiguous
+    _check(lib().hco_attend(_p(q), _p(cache.codes), _p(cache.scale), _p(cache.zero),
+                            C.c_int64(cache.R), C.c_int(G), C.c_int(cache.D), C.c_int(cache.bits),
+                            C.c_int(cache.gs), C.c_int64(cache.cap), _p(idx), _p(count),
+                            C.c_int64(k), _p(pos), _p(V), C.c_int64(V.shape[1]),
+                            C.c_float(sm_scale), _p(y), _p(w), _p(acc)), "attend")
+    return y, w
+
+
+def evict(cache, acc, pos, M, n_protect):
+    """Compacts cache / acc / pos in place.  Returns kept int32 [R,M] (-1 padded)."""
+    assert acc.dtype == np.float32 and acc.flags.c_contiguous
+    assert pos.dtype == np.int32 and pos.flags.c_contiguous
+    kept = np.zeros((cache.R, M), np.int32)
+    n_new = np.zeros(cache.R, np.int64)
+    _check(lib().hco_evict(_p(cache.codes), _p(cache.scale), _p(cache.zero), _p(acc), _p(pos),
+                           C.c_int64(cache.R), C.c_int(cache.D), C.c_int(cache.bits),
+                           C.c_int(cache.gs), C.c_int64(cache.cap), _p(cache.n), C.c_int64(M),
+                           C.c_int64(n_protect), _p(kept), _p(n_new)), "evict")
+    cache.n[...] = n_new
+    return kept

@@ -1,0 +1,25 @@
+"""Compile the CPU oracle (plain C, gcc) into oracle/libhca_oracle.so.
+
+Flags matter: -ffp-contract=off keeps every fp32 operation a single rounded IEEE
+operation (the oracle's bit-level definition depends on it); no fast-math.
+"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SRC = os.path.join(HERE, "hca_oracle.c")
+LIB = os.path.join(HERE, "libhca_oracle.so")
+
+
+def build(force: bool = True) -> str:
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+        return LIB
+    cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+           "-fPIC", "-shared", "-Wall", "-Wextra", "-o", LIB, SRC, "-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force="--if-stale" not in sys.argv))
