@@ -1,0 +1,157 @@
+/*
+ * hca.h: C ABI of libhca.so, the decode-time heterogeneous attention path of
+ * HCAttention (arXiv 2507.19823) for one AMD MI355X (gfx950).
+ *
+ * The path evaluates the paper's Eq. 2,
+ *     y~ = F_evict(softmax(q . Q(K)^T / sqrt(d))) . F_evict(V),
+ * in four steps: compress keys (Q), score the query against the whole compressed
+ * key cache (Sec. 3.2 "GPU part", Eq. 3), select the highest-scoring tokens
+ * (the sorted prefix of Sec. 3.2 / Eq. 4, here with k given), and form the
+ * softmax-weighted sum over the selected values only (Eq. 5), the values living
+ * in pinned host memory (Sec. 3.2 "CPU part": value offloading) or in an HBM
+ * slice.  A fifth call keeps the cache bounded by accumulated-score eviction.
+ *
+ * Conventions
+ *  - Every call returns an int32_t status: HCA_OK or a negative HCA_ERR_*.
+ *    Arguments are validated on the host before any device work; a call that
+ *    returns an error has launched nothing.  No exception crosses the boundary.
+ *  - "device" pointers are HBM addresses valid on the current HIP device;
+ *    "host" pointers are ordinary host memory read during the call;
+ *    "pinned" pointers are host memory allocated with hipHostMalloc (or a
+ *    pinned torch tensor) and are dereferenced by GPU kernels.
+ *  - The caller owns every buffer.  The library allocates no device memory;
+ *    scratch space comes from the `workspace` argument, at least
+ *    hca_workspace_bytes() bytes, 256-byte aligned, private to the call while
+ *    it is in flight (two calls that may overlap need two workspaces).
+ *  - Calls are asynchronous: they enqueue work on `stream` (a hipStream_t
+ *    passed as void*, NULL = the default stream) and return.  They never
+ *    synchronise the device.
+ *  - Shapes: query head hq belongs to KV head hq / (n_q_heads / n_kv_heads).
+ *    A "row" is one (sequence, KV head) pair, r = b * n_kv_heads + h.
+ *  - n_resident is a host array [batch]: tokens currently in the cache of each
+ *    sequence (equal for all KV heads of a sequence).
+ *  - Supported shapes: head_dim 128; (bits, group) = (4, 32) or (2, 64);
+ *    n_q_heads / n_kv_heads in {1, 2, 4}.  Anything else: HCA_ERR_UNSUPPORTED.
+ *  - Inputs must be finite (no NaN / Inf); the result is unspecified otherwise.
+ */
+#ifndef HCA_H_
+#define HCA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HCA_OK 0
+#define HCA_ERR_BAD_ARG (-1)     /* null pointer, negative size, inconsistent shape */
+#define HCA_ERR_UNSUPPORTED (-2) /* shape outside the supported set */
+#define HCA_ERR_CAPACITY (-3)    /* append past capacity, k or M out of range */
+#define HCA_ERR_HIP (-4)         /* a HIP call failed; see hca_last_hip_error() */
+
+typedef struct {
+  int32_t batch;      /* sequences */
+  int32_t n_q_heads;  /* query heads per sequence */
+  int32_t n_kv_heads; /* KV heads per sequence */
+  int32_t head_dim;   /* d of Eq. 1; 128 */
+  int32_t bits;       /* bits per key code */
+  int32_t group;      /* channels sharing one scale / zero */
+  int64_t capacity;   /* max resident tokens per (sequence, KV head) */
+} hca_shape;
+
+/* Library version string (static storage). */
+const char* hca_version(void);
+
+/* hipError_t of the most recent failing HIP call made by this thread (0 if none). */
+int32_t hca_last_hip_error(void);
+
+/* Bytes of the compressed key cache for `shape` (codes + scales + zeros of all
+ * rows, in the library's private tiled layout); 0 if the shape is unsupported.
+ * Sec. 3.3 "Compression ratio": the code part is head_dim*bits/8 bytes per token
+ * per KV head, i.e. 1/4 (4-bit) or 1/8 (2-bit) of the fp16 keys. */
+size_t hca_kcache_bytes(const hca_shape* shape);
+
+/* Workspace bytes sufficient for any call with top-k <= k_max and eviction
+ * keep-count <= m_max on this shape. */
+size_t hca_workspace_bytes(const hca_shape* shape, int64_t k_max, int64_t m_max);
+
+/* Step 1, Q(K) of Eq. 2: quantise T new tokens per row and append them at slots
+ * n_resident[b] .. n_resident[b]+T-1.
+ *   k_new_f16   device, fp16 [batch, n_kv_heads, T, head_dim], contiguous
+ *   kcache      device, hca_kcache_bytes() bytes, updated in place
+ * Per (token, group): zero = min, scale = fp16((max-min)/(2^bits-1)) (1.0 if that
+ * is 0), code = clamp(rint((x-zero)*(1/scale)), 0, 2^bits-1).
+ * The caller adds T to n_resident afterwards.
+ * Errors: HCA_ERR_CAPACITY if n_resident[b]+T > capacity. */
+int32_t hca_quantize_keys(const hca_shape* shape, void* kcache, const void* k_new_f16,
+                          int64_t T, const int64_t* n_resident, void* stream);
+
+/* Step 2, z~ = q . Q(K)^T of Eq. 2 / Eq. 3 for every resident token, keys
+ * dequantised on the fly.  The query is first mapped to 15-bit fixed point per
+ * head (qfx = rint(q * 2^s), |qfx| < 2^14) so that each group's dot product is an
+ * exact integer; then z~ = 2^-s * sum_g fma(scale_g, D_g, zero_g * Q_g).
+ *   q_f16   device, fp16 [batch, n_q_heads, head_dim]
+ *   sel     device, fp32 [batch, n_kv_heads, capacity]; sel[r][j] = max over the
+ *           query heads of row r of z~[hq][j], written for j < n_resident
+ *   z_opt   device, fp32 [batch, n_q_heads, capacity] or NULL: every z~ */
+int32_t hca_score_qkeys(const hca_shape* shape, const void* kcache, const void* q_f16,
+                        const int64_t* n_resident, float* sel, float* z_opt,
+                        void* workspace, void* stream);
+
+/* Step 3a, the sorted prefix Pi_k of Sec. 3.2 with k fixed: per row the
+ * k' = min(k, n_resident) slots with the largest sel, ties broken towards the
+ * lower slot, reported in ascending slot order.
+ *   idx    device, int32 [batch, n_kv_heads, k]; entries past k' are left untouched
+ *   count  device, int32 [batch, n_kv_heads] = k'
+ * Errors: HCA_ERR_CAPACITY if k < 1 or k > capacity. */
+int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resident,
+                 int32_t k, int32_t* idx, int32_t* count, void* workspace, void* stream);
+
+/* Step 3b, Eq. 5 with the softmax taken over the selected set: for each query
+ * head, l_i = z~[idx_i] * sm_scale (z~ recomputed from the codes),
+ * a = softmax(l), y = sum_i a_i * V[pos[idx_i]].
+ *   idx, count  device, as written by hca_topk (k = row stride of idx)
+ *   pos         device, int32 [batch, n_kv_heads, capacity]: value row of each slot
+ *   v_host      pinned, fp16 [batch, n_kv_heads, host_stride, head_dim]; serves value
+ *               rows < n_host_rows (may be NULL if n_host_rows == 0)
+ *   v_hbm       device, fp16 [batch, n_kv_heads, hbm_stride, head_dim]; serves value
+ *               row v >= n_host_rows at index v - n_host_rows (may be NULL if unused)
+ *   y           device, fp32 [batch, n_q_heads, head_dim]
+ *   acc_opt     device, fp32 [batch, n_kv_heads, capacity] or NULL:
+ *               acc[idx_i] += sum over the row's query heads of max(a_i, 1e-30)
+ *   gather_stream  the value rows are first gathered into the workspace on this
+ *               stream (ordered after `stream`'s work enqueued so far); `stream`
+ *               then waits for the gather.  May equal `stream`. */
+int32_t hca_sparse_attend(const hca_shape* shape, const void* kcache, const void* q_f16,
+                          const int32_t* idx, const int32_t* count, int32_t k,
+                          const int32_t* pos,
+                          const void* v_host, int64_t host_stride, int64_t n_host_rows,
+                          const void* v_hbm, int64_t hbm_stride,
+                          float sm_scale, float* y, float* acc_opt,
+                          void* workspace, void* gather_stream, void* stream);
+
+/* Step 4, accumulated-score eviction.  Rows with n_resident > M keep their newest
+ * n_protect slots and, of the others, the M - n_protect with the highest acc (ties
+ * towards the lower slot); the kept slots move, in ascending old-slot order, to
+ * slots 0..M-1 of kcache, acc and pos.  Rows of sequences with n_resident <= M are
+ * left unchanged.  The caller then sets n_resident[b] = min(n_resident[b], M).
+ *   kept_opt  device, int32 [batch, n_kv_heads, M] or NULL: old slot of each new slot
+ *             (written only for rows that were compacted)
+ * Errors: HCA_ERR_CAPACITY if M < 1, M > capacity or n_protect > M. */
+int32_t hca_evict(const hca_shape* shape, void* kcache, float* acc, int32_t* pos,
+                  const int64_t* n_resident, int64_t M, int64_t n_protect,
+                  int32_t* kept_opt, void* workspace, void* stream);
+
+/* Test / debug: export the cache in canonical row-major form.
+ *   codes  device, uint8 [batch, n_kv_heads, capacity, head_dim*bits/8]; channel c in bits
+ *          [(c*bits)%8, +bits) of byte c*bits/8
+ *   scale_f16, zero_f16  device, fp16 [batch, n_kv_heads, capacity, head_dim/group]
+ * Only slots < n_resident are written. */
+int32_t hca_export_kcache(const hca_shape* shape, const void* kcache, const int64_t* n_resident,
+                          uint8_t* codes, void* scale_f16, void* zero_f16, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HCA_H_ */

@@ -1,0 +1,143 @@
+"""Thin ctypes binding of libhca.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point (include/hca.h).
+Tensors are torch tensors whose data_ptr() is handed over; streams are torch.cuda.Stream
+objects (or None for the current stream).  No step of the path runs in Python, and there is
+no fallback: a missing library raises at import of the first call.
+"""
+import ctypes as C
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhca.so")
+
+HCA_OK = 0
+ERRORS = {-1: "HCA_ERR_BAD_ARG", -2: "HCA_ERR_UNSUPPORTED", -3: "HCA_ERR_CAPACITY", -4: "HCA_ERR_HIP"}
+
+
+class HcaError(RuntimeError):
+    def __init__(self, what, code, hip=0):
+        self.code = code
+        super().__init__(f"{what}: {ERRORS.get(code, code)}" + (f" (hipError {hip})" if code == -4 else ""))
+
+
+class hca_shape(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("bits", C.c_int32), ("group", C.c_int32),
+                ("capacity", C.c_int64)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        sp = C.POINTER(hca_shape)
+        L.hca_version.restype = C.c_char_p
+        L.hca_last_hip_error.restype = i32
+        L.hca_kcache_bytes.restype = C.c_size_t
+        L.hca_kcache_bytes.argtypes = [sp]
+        L.hca_workspace_bytes.restype = C.c_size_t
+        L.hca_workspace_bytes.argtypes = [sp, i64, i64]
+        L.hca_quantize_keys.restype = i32
+        L.hca_quantize_keys.argtypes = [sp, vp, vp, i64, vp, vp]
+        L.hca_score_qkeys.restype = i32
+        L.hca_score_qkeys.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
+        L.hca_topk.restype = i32
+        L.hca_topk.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp]
+        L.hca_sparse_attend.restype = i32
+        L.hca_sparse_attend.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, i64, i64, vp, i64, f32, vp, vp,
+                                        vp, vp, vp]
+        L.hca_evict.restype = i32
+        L.hca_evict.argtypes = [sp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        L.hca_export_kcache.restype = i32
+        L.hca_export_kcache.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+def make_shape(batch, n_q_heads, n_kv_heads, capacity, bits=4, group=32, head_dim=128):
+    return hca_shape(batch, n_q_heads, n_kv_heads, head_dim, bits, group, capacity)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(s):
+    if s is None:
+        s = torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _nres(n_resident, batch):
+    arr = (C.c_int64 * batch)(*[int(x) for x in n_resident])
+    return arr
+
+
+def _check(rc, what):
+    if rc != HCA_OK:
+        raise HcaError(what, rc, lib().hca_last_hip_error())
+
+
+def hca_version():
+    return lib().hca_version().decode()
+
+
+def hca_kcache_bytes(shape):
+    return int(lib().hca_kcache_bytes(C.byref(shape)))
+
+
+def hca_workspace_bytes(shape, k_max, m_max):
+    return int(lib().hca_workspace_bytes(C.byref(shape), int(k_max), int(m_max)))
+
+
+def hca_quantize_keys(shape, kcache, k_new_f16, T, n_resident, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_quantize_keys(C.byref(shape), _ptr(kcache), _ptr(k_new_f16), int(T), nr, _stream(stream)),
+           "hca_quantize_keys")
+
+
+def hca_score_qkeys(shape, kcache, q_f16, n_resident, sel, z_opt=None, workspace=None, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_score_qkeys(C.byref(shape), _ptr(kcache), _ptr(q_f16), nr, _ptr(sel), _ptr(z_opt),
+                                 _ptr(workspace), _stream(stream)), "hca_score_qkeys")
+
+
+def hca_topk(shape, sel, n_resident, k, idx, count, workspace, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_topk(C.byref(shape), _ptr(sel), nr, int(k), _ptr(idx), _ptr(count), _ptr(workspace),
+                          _stream(stream)), "hca_topk")
+
+
+def hca_sparse_attend(shape, kcache, q_f16, idx, count, k, pos, v_host, host_stride, n_host_rows, v_hbm,
+                      hbm_stride, sm_scale, y, acc_opt, workspace, gather_stream=None, stream=None):
+    st = _stream(stream)
+    gst = st if gather_stream is None else _stream(gather_stream)
+    _check(lib().hca_sparse_attend(C.byref(shape), _ptr(kcache), _ptr(q_f16), _ptr(idx), _ptr(count), int(k),
+                                   _ptr(pos), _ptr(v_host), int(host_stride), int(n_host_rows), _ptr(v_hbm),
+                                   int(hbm_stride), float(sm_scale), _ptr(y), _ptr(acc_opt), _ptr(workspace),
+                                   gst, st), "hca_sparse_attend")
+
+
+def hca_evict(shape, kcache, acc, pos, n_resident, M, n_protect, kept_opt, workspace, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_evict(C.byref(shape), _ptr(kcache), _ptr(acc), _ptr(pos), nr, int(M), int(n_protect),
+                           _ptr(kept_opt), _ptr(workspace), _stream(stream)), "hca_evict")
+
+
+def hca_export_kcache(shape, kcache, n_resident, codes, scale_f16, zero_f16, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_export_kcache(C.byref(shape), _ptr(kcache), nr, _ptr(codes), _ptr(scale_f16),
+                                   _ptr(zero_f16), _stream(stream)), "hca_export_kcache")

@@ -1,0 +1,190 @@
+// Step 4: accumulated-score eviction with stable compaction.  The keep-set is the newest
+// n_protect slots plus the M - n_protect highest accumulated scores among the others (ties
+// towards the lower slot); kept slots move to the front in ascending old-slot order.
+#include "hca_internal.h"
+
+namespace hca {
+
+struct EvictWs {
+  void* select;      // select engine workspace
+  int32_t* kept;     // [rows][M] when the caller passes no buffer
+  uint8_t* codes;    // [rows][mblk][1024] staging of the compacted code blocks
+  uint8_t* meta;     // [rows][mblk][256]
+  float* acc;        // [rows][M]
+  int32_t* pos;      // [rows][M]
+};
+
+static int64_t mblk_of(const Layout& L, int64_t M) { return (M + L.tpb - 1) / L.tpb; }
+
+size_t evict_workspace_bytes(const Layout& L, int64_t M) {
+  const int64_t mb = mblk_of(L, M);
+  size_t b = select_workspace_bytes(L.rows, L.cap);
+  b += align_up((int64_t)L.rows * M * 4, 256);
+  b += align_up((int64_t)L.rows * mb * kBlockBytes, 256);
+  b += align_up((int64_t)L.rows * mb * kMetaBytes, 256);
+  b += 2 * align_up((int64_t)L.rows * M * 4, 256);
+  return b;
+}
+
+static void carve(EvictWs* e, void* ws, const Layout& L, int64_t M) {
+  const int64_t mb = mblk_of(L, M);
+  uint8_t* w = (uint8_t*)ws;
+  e->select = w;         w += select_workspace_bytes(L.rows, L.cap);
+  e->kept = (int32_t*)w; w += align_up((int64_t)L.rows * M * 4, 256);
+  e->codes = w;          w += align_up((int64_t)L.rows * mb * kBlockBytes, 256);
+  e->meta = w;           w += align_up((int64_t)L.rows * mb * kMetaBytes, 256);
+  e->acc = (float*)w;    w += align_up((int64_t)L.rows * M * 4, 256);
+  e->pos = (int32_t*)w;
+}
+
+// Ordered pass over all resident slots of a row: writes kept[position] = old slot.
+__global__ __launch_bounds__(256) void evict_positions(const float* __restrict__ acc, int64_t stride, int64_t chunk,
+                                                       int nchunks, int n_kv_heads, SelRows sr, NRes nr,
+                                                       const uint32_t* __restrict__ state,
+                                                       const uint32_t* __restrict__ coff, int64_t M,
+                                                       int32_t* __restrict__ kept) {
+  __shared__ uint32_t wsum[2][4];
+  const int row = blockIdx.y;
+  const int b = row / n_kv_heads;
+  const int64_t want = sr.want[b];
+  if (want < 0) return;
+  const int64_t nsel = sr.nsel[b], n = nr.n[b];
+  const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  if (c0 >= n) return;
+  int64_t c1 = c0 + chunk;
+  if (c1 > n) c1 = n;
+  const uint32_t T = state[4 * row], req = state[4 * row + 1];
+  uint32_t base_g = coff[((int64_t)row * nchunks + blockIdx.x) * 2];
+  uint32_t base_e = coff[((int64_t)row * nchunks + blockIdx.x) * 2 + 1];
+  const float* v = acc + (int64_t)row * stride;
+  int32_t* out = kept + (int64_t)row * M;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  for (int64_t s0 = c0; s0 < c1; s0 += 1024) {
+    const int64_t j0 = s0 + 4 * threadIdx.x;
+    bool fg[4], fe[4];
+    uint32_t ng = 0, ne = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t j = j0 + i;
+      uint32_t key = 0;
+      const bool in = j < nsel;
+      if (in) key = order_key(v[j]);
+      fg[i] = in && key > T;
+      fe[i] = in && key == T;
+      ng += fg[i]; ne += fe[i];
+    }
+    uint32_t ig = ng, ie = ne;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t ag = __shfl_up(ig, o), ae = __shfl_up(ie, o);
+      if (lane >= o) { ig += ag; ie += ae; }
+    }
+    if (lane == 63) { wsum[0][w] = ig; wsum[1][w] = ie; }
+    __syncthreads();
+    uint32_t pg = base_g + ig - ng, pe = base_e + ie - ne;
+    for (int x = 0; x < w; ++x) { pg += wsum[0][x]; pe += wsum[1][x]; }
+    const uint32_t tot_g = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
+    const uint32_t tot_e = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t j = j0 + i;
+      if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)j;
+      if (j >= nsel && j < n) out[want + (j - nsel)] = (int32_t)j;  // protected newest slots
+      pg += fg[i]; pe += fe[i];
+    }
+    base_g += tot_g; base_e += tot_e;
+    __syncthreads();
+  }
+}
+
+// kept[d] -> staging slot d.  One thread per (d, j) 16-byte (4-bit) or 8-byte (2-bit) piece.
+template <int BITS>
+__global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __restrict__ kcache,
+                                                    const float* __restrict__ acc, const int32_t* __restrict__ pos,
+                                                    int n_kv_heads, SelRows sr, int64_t M, int64_t mblk,
+                                                    const int32_t* __restrict__ kept, EvictWs e) {
+  const int row = blockIdx.y;
+  if (sr.want[row / n_kv_heads] < 0) return;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t d = gid >> 2;
+  const int j = (int)(gid & 3);
+  if (d >= M) return;
+  const int64_t s = kept[(int64_t)row * M + d];
+  const uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
+  const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
+  uint8_t* cdst = e.codes + (int64_t)row * mblk * kBlockBytes;
+  uint8_t* mdst = e.meta + (int64_t)row * mblk * kMetaBytes;
+  if (BITS == 4) {
+    const uint4 w = *reinterpret_cast<const uint4*>(crow + (s >> 4) * kBlockBytes + ((s & 15) + 16 * j) * 16);
+    *reinterpret_cast<uint4*>(cdst + (d >> 4) * kBlockBytes + ((d & 15) + 16 * j) * 16) = w;
+    if (j == 0)
+      *reinterpret_cast<uint4*>(mdst + (d >> 4) * kMetaBytes + (d & 15) * 16) =
+          *reinterpret_cast<const uint4*>(mrow + (s >> 4) * kMetaBytes + (s & 15) * 16);
+  } else {
+    const uint2 w = *reinterpret_cast<const uint2*>(crow + (s >> 5) * kBlockBytes + ((s & 15) + 16 * j) * 16 +
+                                                    8 * ((s >> 4) & 1));
+    *reinterpret_cast<uint2*>(cdst + (d >> 5) * kBlockBytes + ((d & 15) + 16 * j) * 16 + 8 * ((d >> 4) & 1)) = w;
+    if (j == 0)
+      *reinterpret_cast<uint2*>(mdst + (d >> 5) * kMetaBytes + (d & 31) * 8) =
+          *reinterpret_cast<const uint2*>(mrow + (s >> 5) * kMetaBytes + (s & 31) * 8);
+  }
+  if (j == 1) e.acc[(int64_t)row * M + d] = acc[(int64_t)row * L.cap + s];
+  if (j == 2) e.pos[(int64_t)row * M + d] = pos[(int64_t)row * L.cap + s];
+}
+
+// staging -> front of the cache (whole blocks; slots past M in the last block are dead).
+__global__ __launch_bounds__(256) void evict_copyback(Layout L, uint8_t* __restrict__ kcache, float* __restrict__ acc,
+                                                      int32_t* __restrict__ pos, int n_kv_heads, SelRows sr,
+                                                      int64_t M, int64_t mblk, EvictWs e) {
+  const int row = blockIdx.y;
+  if (sr.want[row / n_kv_heads] < 0) return;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  uint4* cdst = reinterpret_cast<uint4*>(kcache + (int64_t)row * L.codes_row_bytes());
+  uint4* mdst = reinterpret_cast<uint4*>(kcache + L.meta_off + (int64_t)row * L.meta_row_bytes());
+  const uint4* csrc = reinterpret_cast<const uint4*>(e.codes + (int64_t)row * mblk * kBlockBytes);
+  const uint4* msrc = reinterpret_cast<const uint4*>(e.meta + (int64_t)row * mblk * kMetaBytes);
+  if (gid < mblk * (kBlockBytes / 16)) cdst[gid] = csrc[gid];
+  if (gid < mblk * (kMetaBytes / 16)) mdst[gid] = msrc[gid];
+  if (gid < M) {
+    acc[(int64_t)row * L.cap + gid] = e.acc[(int64_t)row * M + gid];
+    pos[(int64_t)row * L.cap + gid] = e.pos[(int64_t)row * M + gid];
+  }
+}
+
+int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+                     int64_t M, int64_t n_protect, int32_t* kept, void* ws, hipStream_t st) {
+  SelRows sr;
+  bool any = false;
+  for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
+  for (int b = 0; b < L.batch; ++b) {
+    if (nr.n[b] > M) {
+      sr.nsel[b] = nr.n[b] - n_protect;
+      sr.want[b] = M - n_protect;
+      any = true;
+    }
+  }
+  if (!any) return HCA_OK;
+  EvictWs e;
+  carve(&e, ws, L, M);
+  if (kept == nullptr) kept = e.kept;
+  const int64_t mblk = mblk_of(L, M);
+  SelectPlan p;
+  select_plan(&p, e.select, L.rows, nmax);
+  int32_t rc = select_run(p, acc, L.cap, L.rows, L.n_kv_heads, sr, st);
+  if (rc != HCA_OK) return rc;
+  dim3 g((unsigned)p.nchunks, (unsigned)L.rows);
+  evict_positions<<<g, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kept);
+  dim3 gg((unsigned)((M * 4 + 255) / 256), (unsigned)L.rows);
+  if (L.bits == 4)
+    evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, kept, e);
+  else
+    evict_gather<2><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, kept, e);
+  int64_t items = mblk * (kBlockBytes / 16);
+  if (items < M) items = M;
+  dim3 gc((unsigned)((items + 255) / 256), (unsigned)L.rows);
+  evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, e);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+}  // namespace hca

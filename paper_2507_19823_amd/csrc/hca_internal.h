@@ -1,0 +1,67 @@
+// Host-side declarations shared by the translation units of libhca.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/hca.h"
+#include "hca_device.h"
+
+namespace hca {
+
+// Records a failing HIP status for hca_last_hip_error() and maps it to HCA_ERR_HIP.
+int32_t hip_fail(hipError_t e);
+#define HCA_HIP(call)                                  \
+  do {                                                 \
+    hipError_t e_ = (call);                            \
+    if (e_ != hipSuccess) return ::hca::hip_fail(e_);  \
+  } while (0)
+
+// Validates `shape` and fills the layout; returns HCA_OK or an error code.
+int32_t make_layout(const hca_shape* shape, Layout* L);
+// Copies n_resident (host, [batch]) into `out` after range checks against the capacity.
+int32_t load_nres(const Layout& L, const int64_t* n_resident, NRes* out, int64_t* nmax);
+
+inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Radix-select engine (select.hip): per row, finds the `want[r]`-th largest key among
+// slots [0, nsel[r]) and per-chunk counts, so that a following ordered pass can emit the
+// selected slots in ascending order.  See select.hip for the workspace carve-up.
+struct SelectPlan {
+  int64_t chunk;     // slots per chunk (one workgroup)
+  int32_t nchunks;   // chunks per row (<= 1024)
+  // workspace sub-buffers (device pointers)
+  uint32_t* hist;    // [rows][3][2048]
+  uint32_t* state;   // [rows][4]: key prefix, remaining count, (unused), (unused)
+  uint32_t* ccount;  // [rows][nchunks][2]  (#greater, #equal) per chunk
+  uint32_t* coff;    // [rows][nchunks][2]  exclusive prefix of ccount
+};
+struct SelRows {     // per-sequence selection parameters, by value
+  int64_t nsel[kMaxBatch];   // slots [0, nsel) take part
+  int64_t want[kMaxBatch];   // how many to select among them (0 < want <= nsel, or 0 = skip row)
+};
+size_t select_workspace_bytes(int rows, int64_t nmax);
+void select_plan(SelectPlan* p, void* ws, int rows, int64_t nmax);
+// Enqueues the selection passes over `vals` ([rows][stride] fp32).  Afterwards, for row r:
+// state[r][0] = threshold key T, state[r][1] = number of slots with key == T to take (lowest first),
+// coff = exclusive chunk prefixes of (#key > T, #key == T).
+int32_t select_run(const SelectPlan& p, const float* vals, int64_t stride, int rows, int n_kv_heads,
+                   const SelRows& sr, hipStream_t st);
+
+int32_t launch_quantize(const Layout& L, void* kcache, const void* k_new, int64_t T, const NRes& nr,
+                        hipStream_t st);
+int32_t launch_export(const Layout& L, const void* kcache, const NRes& nr, uint8_t* codes, void* scale,
+                      void* zero, hipStream_t st);
+int32_t launch_score(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                     float* sel, float* z_opt, hipStream_t st);
+int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
+                    int32_t* idx, int32_t* count, void* ws, hipStream_t st);
+size_t attend_workspace_bytes(const Layout& L, int64_t k);
+int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                      const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,
+                      int64_t host_stride, int64_t n_host_rows, const void* v_hbm, int64_t hbm_stride,
+                      float sm_scale, float* y, float* acc_opt, void* ws, hipStream_t gst, hipStream_t st);
+size_t evict_workspace_bytes(const Layout& L, int64_t M);
+int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr,
+                     int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, hipStream_t st);
+
+}  // namespace hca

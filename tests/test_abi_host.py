@@ -1,0 +1,73 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes follow the layout, and invalid arguments are rejected before any device work."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2507_19823_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    binding.lib()
+    return binding
+
+
+def test_every_declared_symbol_is_exported(B):
+    hdr = open(os.path.join(ROOT, "include", "hca.h")).read()
+    names = set(re.findall(r"\b(hca_[a-z_]+)\s*\(", hdr))
+    assert {"hca_quantize_keys", "hca_score_qkeys", "hca_topk", "hca_sparse_attend", "hca_evict"} <= names
+    for n in names:
+        assert hasattr(B.lib(), n), n
+    assert B.hca_version().startswith("hca")
+
+
+def test_cache_bytes_follow_the_layout(B):
+    # 4-bit / group 32: 64 B codes + 16 B scale/zero per token and KV head; blocks of 16 tokens
+    s = B.make_shape(1, 32, 8, 1 << 20)
+    assert B.hca_kcache_bytes(s) == 8 * (1 << 20) * 80
+    # 2-bit / group 64: 32 + 8 B; blocks of 32 tokens; capacity rounded up to a block
+    s = B.make_shape(2, 8, 2, 33, bits=2, group=64)
+    assert B.hca_kcache_bytes(s) == 4 * 2 * (1024 + 256)
+    assert B.hca_workspace_bytes(s, 8, 8) > 0
+
+
+@pytest.mark.parametrize("kw", [dict(bits=3), dict(bits=8), dict(group=64), dict(head_dim=64),
+                                dict(n_q_heads=64), dict(batch=65)])
+def test_unsupported_shapes(B, kw):
+    base = dict(batch=1, n_q_heads=32, n_kv_heads=8, capacity=1024, bits=4, group=32, head_dim=128)
+    base.update(kw)
+    s = B.make_shape(**base)
+    assert B.hca_kcache_bytes(s) == 0
+    assert B.lib().hca_score_qkeys(C.byref(s), 1, 1, (C.c_int64 * 65)(), 1, None, None, None) == -2
+
+
+def test_bad_arguments_are_rejected_on_the_host(B):
+    L = B.lib()
+    s = B.make_shape(1, 32, 8, 1024)
+    n = (C.c_int64 * 1)(100)
+    one = C.c_void_p(256)      # never dereferenced: validation fails first
+    assert L.hca_quantize_keys(C.byref(s), None, one, 1, n, None) == -1
+    assert L.hca_quantize_keys(C.byref(s), one, one, 925, n, None) == -3          # 100 + 925 > 1024
+    assert L.hca_quantize_keys(C.byref(s), one, one, -1, n, None) == -1
+    assert L.hca_score_qkeys(C.byref(s), one, one, None, one, None, None, None) == -1
+    assert L.hca_topk(C.byref(s), one, n, 0, one, one, one, None) == -3
+    assert L.hca_topk(C.byref(s), one, n, 1025, one, one, one, None) == -3
+    assert L.hca_topk(C.byref(s), one, n, 8, one, one, None, None) == -1
+    assert L.hca_evict(C.byref(s), one, one, one, n, 0, 0, None, one, None) == -3
+    assert L.hca_evict(C.byref(s), one, one, one, n, 10, 11, None, one, None) == -3
+    assert L.hca_evict(C.byref(s), one, one, one, n, 200, 0, None, one, None) == 0   # n <= M: nothing to do
+    bad = (C.c_int64 * 1)(2000)
+    assert L.hca_score_qkeys(C.byref(s), one, one, bad, one, None, None, None) == -3
+    neg = (C.c_int64 * 1)(-1)
+    assert L.hca_score_qkeys(C.byref(s), one, one, neg, one, None, None, None) == -1
+    assert L.hca_sparse_attend(C.byref(s), one, one, one, one, 8, one, None, 0, 0, None, 0,
+                               C.c_float(1.0), one, None, one, None, None) == -1
+    s2 = B.make_shape(1, 32, 7, 1024)
+    assert L.hca_score_qkeys(C.byref(s2), one, one, n, one, None, None, None) == -1   # 32 % 7 != 0

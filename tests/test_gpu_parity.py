@@ -1,0 +1,351 @@
+"""GPU parity: every stage of the HIP path against the CPU oracle on the same seeded inputs.
+Integer results (codes, scale/zero bits, scores as produced by exact integer dots, index sets,
+eviction decisions) must match bit for bit; the attention output within 2e-3 max relative error."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3   # max_c |y_gpu - y_oracle| / max_c |y_oracle| per head (spec tolerance)
+
+
+@pytest.fixture(scope="module")
+def H():
+    import paper_2507_19823_amd as H
+    assert torch.cuda.is_available(), "GPU tests need the MI355X"
+    H.lib()
+    return H
+
+
+def _state(H, w, cap=None, want_z=True, k_max=None, m_max=None):
+    from paper_2507_19823_amd.session import LayerState
+    cap = cap or w.n
+    return LayerState(w.batch, w.n_q_heads, w.n_kv_heads, cap, w.bits, w.group, k_max=k_max or w.k,
+                      m_max=m_max, want_z=want_z)
+
+
+def _rows(t):
+    """[B, H, ...] torch tensor -> numpy [B*H, ...]"""
+    a = t.detach().cpu().numpy()
+    return a.reshape(a.shape[0] * a.shape[1], *a.shape[2:])
+
+
+def _ocache(oracle, w, cap):
+    return oracle.Cache(w.batch * w.n_kv_heads, cap, 128, w.bits, w.group)
+
+
+def _cmp_cache(st, oc):
+    codes, scale, zero = st.export()
+    torch.cuda.synchronize()
+    for r in range(oc.R):
+        n = int(oc.n[r])
+        assert st.n[r // st.hkv] == n
+        assert np.array_equal(_rows(codes)[r, :n], oc.codes[r, :n]), f"codes differ in row {r}"
+        assert np.array_equal(_rows(scale).view(np.uint16)[r, :n], oc.scale[r, :n]), f"scales differ in row {r}"
+        assert np.array_equal(_rows(zero).view(np.uint16)[r, :n], oc.zero[r, :n]), f"zeros differ in row {r}"
+
+
+def _rel_err(y, ref):
+    return float(np.max(np.abs(y - ref).max(-1) / np.maximum(np.abs(ref).max(-1), 1e-30)))
+
+
+@pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
+def test_quantize_bit_exact_with_ragged_appends(H, oracle, bits, gs):
+    w = S.Workload("q", 50 + bits, 2, 8, 2, 1200, bits, gs, 64)
+    d = S.make_layer(w, want_values=False)
+    keys = d["keys"]
+    # special groups: constant, signed-zero minimum, huge range, subnormal step
+    keys[0, 0, 3, :] = 0.75
+    keys[0, 0, 4, :64] = 0.0
+    keys[0, 0, 4, 0] = -0.0
+    keys[0, 1, 5, 0] = 65504.0
+    keys[0, 1, 5, 1] = -65504.0
+    keys[1, 0, 6, :] = 0.0
+    keys[1, 0, 6, 7] = 6e-8
+    cap = 1210
+    st = _state(H, w, cap=cap)
+    oc = _ocache(oracle, w, cap)
+    kd = keys.cuda()
+    for a, b in ((0, 777), (777, 778), (778, 1000), (1000, 1200)):      # unaligned appends, T = 1 included
+        st.quantize(kd[:, :, a:b].contiguous())
+        oracle.quantize(oc, _rows(keys[:, :, a:b]))
+    _cmp_cache(st, oc)
+    with pytest.raises(H.HcaError) as e:
+        st.quantize(kd[:, :, :11].contiguous())
+    assert e.value.code == -3
+
+
+@pytest.mark.parametrize("bits,gs,G", [(4, 32, 4), (2, 64, 4), (4, 32, 1), (4, 32, 2), (2, 64, 1)])
+def test_scores_bit_exact(H, oracle, bits, gs, G):
+    w = S.Workload("s", 60 + bits + G, 2, 2 * G, 2, 3000 + 7, bits, gs, 64)
+    d = S.make_layer(w, want_values=False)
+    st = _state(H, w)
+    oc = _ocache(oracle, w, w.n)
+    st.quantize(d["keys"].cuda())
+    oracle.quantize(oc, _rows(d["keys"]))
+    q = d["q"].clone()
+    q[0, 0] = 0                       # an all-zero query head
+    q[1, 1] = q[1, 1] * 1e-4          # tiny magnitudes (large fixed-point shift)
+    st.score(q.cuda())
+    torch.cuda.synchronize()
+    sel, z = oracle.score(oc, q.numpy().reshape(-1, 128))
+    zg = st.z.cpu().numpy().reshape(-1, w.n)
+    assert np.array_equal(zg, z)
+    assert np.array_equal(_rows(st.sel), sel)
+
+
+def test_scores_different_lengths_per_sequence(H, oracle):
+    w = S.Workload("s2", 71, 3, 12, 3, 900, 4, 32, 32)
+    d = S.make_layer(w, want_values=False)
+    st = _state(H, w)
+    oc = _ocache(oracle, w, w.n)
+    lens = [900, 0, 37]
+    kd = d["keys"].cuda()
+    # all sequences receive the same appends; n_resident then cuts each one to its own length
+    st.quantize(kd)
+    oracle.quantize(oc, _rows(d["keys"]))
+    st.n = lens
+    oc.n[...] = np.repeat(lens, 3)
+    st.sel.fill_(-7.0)
+    st.score(d["q"].cuda())
+    st.topk(32)
+    torch.cuda.synchronize()
+    sel, _ = oracle.score(oc, d["q"].numpy().reshape(-1, 128), want_z=False)
+    idx, count = oracle.topk(sel, oc.n, 32)
+    sg = _rows(st.sel)
+    for r in range(9):
+        n = lens[r // 3]
+        assert np.array_equal(sg[r, :n], sel[r, :n])
+        assert np.all(sg[r, n:] == -7.0)                 # nothing written past n_resident
+        c = int(_rows(st.count[..., None])[r, 0])
+        assert c == count[r] == min(32, n)
+        assert np.array_equal(_rows(st.idx)[r, :c], idx[r, :c])
+
+
+@pytest.mark.parametrize("case", ["random", "all_equal", "two_valued", "signed_zero", "few_distinct", "sorted_desc"])
+@pytest.mark.parametrize("n,k", [(5000, 1), (5000, 256), (5000, 4999), (5000, 5000), (70000, 2048), (1, 1), (300, 1000)])
+def test_topk_bit_exact_including_ties(H, oracle, case, n, k):
+    rng = np.random.default_rng(n * 7 + k)
+    rows = 4
+    if case == "random":
+        v = rng.standard_normal((rows, n)).astype(np.float32) * 100
+    elif case == "all_equal":
+        v = np.full((rows, n), -3.25, np.float32)
+    elif case == "two_valued":
+        v = rng.integers(0, 2, (rows, n)).astype(np.float32)
+    elif case == "signed_zero":
+        v = np.zeros((rows, n), np.float32)
+        v[:, ::3] = -0.0
+        v[:, 1::7] = 1e-38
+        v[:, 2::11] = -1e-38
+    elif case == "few_distinct":
+        v = rng.integers(-20, 20, (rows, n)).astype(np.float32) * 0.5
+    else:
+        v = -np.sort(-rng.standard_normal((rows, n)).astype(np.float32), axis=1)
+    from paper_2507_19823_amd import binding as B
+    cap = n + 5
+    kk = min(k, cap)
+    shape = B.make_shape(2, 8, 2, cap)
+    sel = torch.full((4, cap), 1e30, dtype=torch.float32)
+    sel[:, :n] = torch.from_numpy(v)
+    sel = sel.cuda()
+    idx = torch.full((4, kk), -9, dtype=torch.int32, device="cuda")
+    count = torch.full((4,), -9, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(shape, kk, 1), dtype=torch.uint8, device="cuda")
+    B.hca_topk(shape, sel, [n, n], kk, idx, count, ws)
+    torch.cuda.synchronize()
+    ridx, rcount = oracle.topk(sel.cpu().numpy(), np.full(4, n), kk)
+    c = min(kk, n)
+    assert np.all(count.cpu().numpy() == c) and np.all(rcount == c)
+    assert np.array_equal(idx.cpu().numpy()[:, :c], ridx[:, :c])
+    assert np.all(idx.cpu().numpy()[:, c:] == -9)          # entries past k' untouched
+
+
+@pytest.mark.parametrize("cfg,host_rows", [(1, "all"), (1, "none"), (2, "half")])
+def test_pipeline_configs_against_oracle(H, oracle, cfg, host_rows):
+    """BASELINE configs 1 and 2 end to end: quantise -> score -> top-k -> attend (-> evict)."""
+    w = S.CONFIGS[cfg]
+    d = S.make_layer(w)
+    R, G, n = w.batch * w.n_kv_heads, w.gqa, w.n
+    st = _state(H, w, want_z=False)
+    oc = _ocache(oracle, w, n)
+    st.quantize(d["keys"].cuda())
+    oracle.quantize(oc, _rows(d["keys"]))
+    _cmp_cache(st, oc)
+    qd = d["q"].cuda()
+    st.score(qd)
+    st.topk(w.k)
+    nh = {"all": n, "none": 0, "half": n // 2}[host_rows]
+    v = d["values"]
+    v_host = v[:, :, :nh].contiguous().pin_memory() if nh > 0 else None
+    v_hbm = v[:, :, nh:].contiguous().cuda() if nh < n else None
+    side = torch.cuda.Stream()
+    st.attend(qd, v_host, nh, v_hbm, use_acc=True, gather_stream=side)
+    torch.cuda.synchronize()
+
+    q16 = d["q"].numpy().reshape(-1, 128)
+    sel, _ = oracle.score(oc, q16, want_z=False)
+    assert np.array_equal(_rows(st.sel), sel)
+    idx, count = oracle.topk(sel, oc.n, w.k)
+    assert np.array_equal(_rows(st.idx), idx)
+    assert np.array_equal(st.count.cpu().numpy().reshape(-1), count)
+    pos = np.tile(np.arange(n, dtype=np.int32), (R, 1))
+    acc = np.zeros((R, n), np.float32)
+    y, _ = oracle.attend(oc, q16, idx, count, pos, _rows(v), st.sm_scale, acc=acc)
+    yg = st.y.cpu().numpy().reshape(-1, 128)
+    assert _rel_err(yg, y) <= TOL
+    accg = _rows(st.acc)
+    assert np.allclose(accg, acc, rtol=1e-4, atol=1e-7)
+    assert np.array_equal(accg > 0, acc > 0)
+
+    if w.evict_keep:
+        M = w.evict_keep
+        kept = torch.full((w.batch, w.n_kv_heads, M), -1, dtype=torch.int32, device="cuda")
+        # eviction decisions from the GPU's own accumulated scores vs the oracle's from its own:
+        # after one step fewer than M slots were ever selected, so ties (acc == 0) decide the rest
+        assert int((acc > 0).sum(1).max()) < M
+        st.evict(M, 0, kept)
+        torch.cuda.synchronize()
+        posn = pos.copy()
+        okept = oracle.evict(oc, acc, posn, M, 0)
+        assert np.array_equal(_rows(kept), okept)
+        _cmp_cache(st, oc)
+        assert np.array_equal(_rows(st.pos)[:, :M], posn[:, :M])
+        assert np.allclose(_rows(st.acc)[:, :M], acc[:, :M], rtol=1e-4, atol=1e-7)
+
+
+@pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
+@pytest.mark.parametrize("n,M,Rp", [(5000, 3000, 0), (5000, 3000, 100), (5000, 5000, 16), (4000, 5000, 16),
+                                    (5000, 17, 17), (5000, 1, 0), (70001, 35000, 1)])
+def test_evict_bit_exact_stagewise(H, oracle, bits, gs, n, M, Rp):
+    """Same accumulated scores on both sides (many ties): identical keep lists and compacted state."""
+    w = S.Workload("e", 80 + bits, 2, 4, 2, n, bits, gs, 16)
+    rng = np.random.default_rng(n + M + Rp)
+    d = S.make_layer(w, want_values=False)
+    cap = n + 3
+    st = _state(H, w, cap=cap, m_max=max(M, 1))
+    oc = _ocache(oracle, w, cap)
+    st.quantize(d["keys"].cuda())
+    oracle.quantize(oc, _rows(d["keys"]))
+    R = 4
+    acc = np.zeros((R, cap), np.float32)
+    acc[:, :n] = rng.integers(0, 5, (R, n)).astype(np.float32) * 0.125
+    acc[1, :n] = rng.random(n).astype(np.float32)
+    acc[2, :n] = 0.0
+    pos = np.zeros((R, cap), np.int32)
+    pos[:, :n] = rng.permutation(n).astype(np.int32)[None]
+    st.acc.copy_(torch.from_numpy(acc.reshape(2, 2, cap)))
+    st.pos.copy_(torch.from_numpy(pos.reshape(2, 2, cap)))
+    kept = torch.full((2, 2, M), -5, dtype=torch.int32, device="cuda")
+    st.evict(M, Rp, kept)
+    torch.cuda.synchronize()
+    okept = oracle.evict(oc, acc, pos, M, Rp)
+    m = min(n, M)
+    if n > M:
+        assert np.array_equal(_rows(kept), okept)
+    else:
+        assert np.all(_rows(kept) == -5)                   # rows left alone are not reported
+    _cmp_cache(st, oc)
+    assert np.array_equal(_rows(st.acc)[:, :m], acc[:, :m])
+    assert np.array_equal(_rows(st.pos)[:, :m], pos[:, :m])
+
+
+def test_decode_loop_with_appends_and_eviction(H, oracle):
+    """Config-3-like loop at reduced length: append one token per step, attend, evict every 4 steps;
+    the GPU state is compared with the oracle after every step (stage-wise on acc)."""
+    w = S.Workload("loop", 3, 2, 8, 2, 2000, 4, 32, 128, evict_keep=2000, evict_every=4, steps=12)
+    d = S.make_layer(w)
+    R, n0 = w.batch * w.n_kv_heads, w.n
+    cap = n0 + 8
+    vcap = n0 + w.steps
+    st = _state(H, w, cap=cap, want_z=False)
+    oc = _ocache(oracle, w, cap)
+    st.quantize(d["keys"].cuda())
+    oracle.quantize(oc, _rows(d["keys"]))
+    v_host = torch.zeros(w.batch, w.n_kv_heads, vcap, 128, dtype=torch.float16).pin_memory()
+    v_host[:, :, :n0] = d["values"]
+    pos = np.zeros((R, cap), np.int32)
+    pos[:, :n0] = np.arange(n0)
+    acc = np.zeros((R, cap), np.float32)
+    for step in range(w.steps):
+        k_new, v_new, q = S.make_step(w, 0, step)
+        n = st.n[0]
+        v_host[:, :, n0 + step] = v_new[:, :, 0]
+        st.pos[:, :, n] = n0 + step
+        st.acc[:, :, n] = 0
+        pos[:, n] = n0 + step
+        acc[:, n] = 0
+        st.quantize(k_new.cuda())
+        oracle.quantize(oc, _rows(k_new))
+        qd = q.cuda()
+        st.score(qd)
+        st.topk(w.k)
+        st.attend(qd, v_host, vcap, None, use_acc=True)
+        torch.cuda.synchronize()
+        q16 = q.numpy().reshape(-1, 128)
+        sel, _ = oracle.score(oc, q16, want_z=False)
+        idx, count = oracle.topk(sel, oc.n, w.k)
+        assert np.array_equal(_rows(st.idx), idx), f"step {step}"
+        y, _ = oracle.attend(oc, q16, idx, count, pos, _rows(v_host), st.sm_scale, acc=acc)
+        assert _rel_err(st.y.cpu().numpy().reshape(-1, 128), y) <= TOL
+        assert np.allclose(_rows(st.acc), acc, rtol=1e-4, atol=1e-7)
+        # stage-wise: continue from identical accumulated scores so that decisions stay comparable
+        st.acc.copy_(torch.from_numpy(acc.reshape(w.batch, w.n_kv_heads, cap)))
+        if (step + 1) % w.evict_every == 0:
+            st.evict(w.evict_keep, w.evict_every)
+            torch.cuda.synchronize()
+            oracle.evict(oc, acc, pos, w.evict_keep, w.evict_every)
+            assert st.n[0] == w.evict_keep == oc.n[0]
+            _cmp_cache(st, oc)
+            m = w.evict_keep
+            assert np.array_equal(_rows(st.pos)[:, :m], pos[:, :m])
+            assert np.array_equal(_rows(st.acc)[:, :m], acc[:, :m])
+
+
+def test_empty_cache_and_tiny_k(H, oracle):
+    w = S.Workload("z", 9, 1, 4, 1, 40, 4, 32, 8)
+    d = S.make_layer(w)
+    st = _state(H, w, cap=64)
+    qd = d["q"].cuda()
+    vh = torch.zeros(1, 1, 64, 128, dtype=torch.float16).pin_memory()
+    st.score(qd)                      # n = 0: nothing to do
+    st.topk(8)
+    st.attend(qd, vh, 64, None)
+    torch.cuda.synchronize()
+    assert int(st.count.sum()) == 0 and float(st.y.abs().sum()) == 0.0
+    st.quantize(d["keys"][:, :, :3].cuda())     # n = 3 < k
+    oc = _ocache(oracle, w, 64)
+    oracle.quantize(oc, _rows(d["keys"][:, :, :3]))
+    vh[:, :, :3] = d["values"][:, :, :3]
+    st.score(qd)
+    st.topk(8)
+    st.attend(qd, vh, 64, None)
+    torch.cuda.synchronize()
+    assert st.count.cpu().tolist() == [[3]]
+    assert st.idx.cpu().numpy().reshape(-1)[:3].tolist() == [0, 1, 2]
+    q16 = d["q"].numpy().reshape(-1, 128)
+    sel, _ = oracle.score(oc, q16, want_z=False)
+    idx, count = oracle.topk(sel, oc.n, 8)
+    y, _ = oracle.attend(oc, q16, idx, count, np.arange(64, dtype=np.int32)[None], _rows(vh), st.sm_scale)
+    assert _rel_err(st.y.cpu().numpy().reshape(-1, 128), y) <= TOL
+
+
+def test_kernels_are_deterministic(H):
+    w = S.CONFIGS[1]
+    d = S.make_layer(w)
+    outs = []
+    for _ in range(2):
+        st = _state(H, w, want_z=True)
+        st.quantize(d["keys"].cuda())
+        st.score(d["q"].cuda())
+        st.topk(w.k)
+        st.attend(d["q"].cuda(), None, 0, d["values"].cuda())
+        torch.cuda.synchronize()
+        outs.append((st.kcache.cpu(), st.z.cpu(), st.idx.cpu().clone(), st.y.cpu()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
