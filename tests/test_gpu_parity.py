@@ -227,7 +227,7 @@ def test_evict_bit_exact_stagewise(H, oracle, bits, gs, n, M, Rp):
     w = S.Workload("e", 80 + bits, 2, 4, 2, n, bits, gs, 16)
     rng = np.random.default_rng(n + M + Rp)
     d = S.make_layer(w, want_values=False)
-    cap = n + 3
+    cap = max(n, M) + 3
     st = _state(H, w, cap=cap, m_max=max(M, 1))
     oc = _ocache(oracle, w, cap)
     st.quantize(d["keys"].cuda())
@@ -308,7 +308,7 @@ def test_decode_loop_with_appends_and_eviction(H, oracle):
 
 
 def test_empty_cache_and_tiny_k(H, oracle):
-    w = S.Workload("z", 9, 1, 4, 1, 40, 4, 32, 8)
+    w = S.Workload("z", 9, 1, 4, 1, 40, 4, 32, 8, planted=4)
     d = S.make_layer(w)
     st = _state(H, w, cap=64)
     qd = d["q"].cuda()
