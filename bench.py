@@ -1,0 +1,298 @@
+#!/usr/bin/env python3
+"""Decode-step benchmark of the HCAttention hot path on one MI355X.
+
+A step is one decode step of the whole path over every layer of the workload: append + quantise
+the new key (a1), scan the key cache (a2), top-k (a3), gather the selected values from pinned host
+memory and attend (a4), and, every `evict_every` steps, accumulated-score eviction (a5).
+Inputs are synthetic and seeded (synth_inputs.py) and resident (keys in HBM, values in pinned host
+memory) before the timed region starts.
+
+Prints one JSON line (see README for the fields).
+"""
+import argparse
+import faulthandler
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Model:
+    """All layers of one workload: per-layer key cache / acc / pos / host values, shared scratch."""
+
+    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2):
+        import torch
+        from paper_2507_19823_amd import binding as B
+        self.torch, self.B, self.w = torch, B, w
+        self.L = layers
+        self.n0 = w.n
+        self.evict_every = evict_every
+        self.cap = w.n + max(evict_every, 1) + 16
+        self.vnew = total_steps + 16                  # value rows of appended tokens live in an HBM slice
+        self.shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, self.cap, w.bits, w.group)
+        self.rows = w.batch * w.n_kv_heads
+        dev = "cuda"
+        kb = B.hca_kcache_bytes(self.shape)
+        self.kcache = [torch.empty(kb, dtype=torch.uint8, device=dev) for _ in range(layers)]
+        self.acc = [torch.zeros(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev)
+                    for _ in range(layers)]
+        self.pos = [torch.arange(self.cap, dtype=torch.int32, device=dev).repeat(w.batch, w.n_kv_heads, 1).contiguous()
+                    for _ in range(layers)]
+        self.v_host = [None] * layers
+        self.v_hbm = [torch.zeros(w.batch, w.n_kv_heads, self.vnew, 128, dtype=torch.float16, device=dev)
+                      for _ in range(layers)]
+        wsb = B.hca_workspace_bytes(self.shape, w.k, self.n0)
+        self.pipe = []
+        for _ in range(n_pipe):
+            self.pipe.append(dict(
+                sel=torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev),
+                idx=torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev),
+                count=torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev),
+                ws=torch.empty(wsb, dtype=torch.uint8, device=dev)))
+        self.y = torch.zeros(layers, w.batch, w.n_q_heads, 128, dtype=torch.float32, device=dev)
+        self.n = [[0] * w.batch for _ in range(layers)]
+        self.sm_scale = 1.0 / (128.0 ** 0.5)
+        self.step_count = 0
+
+    def build(self, phys_value_layers):
+        """Generate each layer's context on the GPU, quantise it into the key cache (bulk a1) and park
+        the values in pinned host memory.  Returns seconds spent in the bulk quantise calls."""
+        import synth_inputs as S
+        torch, B, w = self.torch, self.B, self.w
+        tq = 0.0
+        for l in range(self.L):
+            d = S.make_layer(w, l, device="cuda", want_values=(l < phys_value_layers))
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            B.hca_quantize_keys(self.shape, self.kcache[l], d["keys"], w.n, self.n[l], None, None, None)
+            torch.cuda.synchronize()
+            tq += time.perf_counter() - t0
+            self.n[l] = [w.n] * w.batch
+            vh = None
+            if l < phys_value_layers:
+                try:
+                    vh = torch.empty(w.batch, w.n_kv_heads, w.n, 128, dtype=torch.float16, pin_memory=True)
+                except RuntimeError as e:          # the box refuses more pinned memory: share from here on
+                    log(f"pinned allocation for layer {l} refused ({str(e).splitlines()[0]}); "
+                        f"mapping logical layers onto {l} physical value layers")
+                    phys_value_layers = l
+            if vh is not None:
+                vh.copy_(d["values"])
+                self.v_host[l] = vh
+            else:
+                self.v_host[l] = self.v_host[l % phys_value_layers]   # logical layer shares a physical store
+            if l == 0:
+                self.layer0 = {k: (v.cpu() if v is not None and hasattr(v, "cpu") else v) for k, v in d.items()}
+            del d
+        self.phys = phys_value_layers
+        return tq
+
+    def make_steps(self, total_steps):
+        """Pre-generate the appended token and the query of every (step, layer); values go to the host store."""
+        import synth_inputs as S
+        torch, w = self.torch, self.w
+        self.k_new, self.q = [], []
+        for t in range(total_steps):
+            ks, qs = [], []
+            for l in range(self.L):
+                k_new, v_new, q = S.make_step(w, l, t)
+                self.v_hbm[l][:, :, t] = v_new[:, :, 0].cuda()
+                ks.append(k_new)
+                qs.append(q)
+            self.k_new.append(torch.stack(ks).cuda())
+            self.q.append(torch.stack(qs).cuda())
+        torch.cuda.synchronize()
+
+    def layer_step(self, l, t, st, gst, pipe, ev=None):
+        """One layer of decode step t on stream st (gather on gst)."""
+        B, w = self.B, self.w
+        n = self.n[l]
+        B.hca_quantize_keys(self.shape, self.kcache[l], self.k_new[t][l], 1, n, self.acc[l], self.pos[l],
+                            [self.n0 + t] * w.batch, st)
+        n = [x + 1 for x in n]
+        q = self.q[t][l]
+        if ev is not None:
+            ev[0].record(st)
+        B.hca_score_qkeys(self.shape, self.kcache[l], q, n, pipe["sel"], None, None, st)
+        if ev is not None:
+            ev[1].record(st)
+        B.hca_topk(self.shape, pipe["sel"], n, w.k, pipe["idx"], pipe["count"], pipe["ws"], st)
+        vh = self.v_host[l]
+        B.hca_sparse_attend(self.shape, self.kcache[l], q, pipe["idx"], pipe["count"], w.k, self.pos[l],
+                            vh, vh.shape[2], vh.shape[2], self.v_hbm[l], self.vnew, self.sm_scale, self.y[l], self.acc[l],
+                            pipe["ws"], gst, st)
+        if self.evict_every and (t + 1) % self.evict_every == 0:
+            B.hca_evict(self.shape, self.kcache[l], self.acc[l], self.pos[l], n, self.n0, self.evict_every,
+                        None, pipe["ws"], st)
+            n = [min(x, self.n0) for x in n]
+        self.n[l] = n
+
+
+def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
+    """Times the oracle, as it stands, on layer 0 of the same workload: consecutive decode steps
+    (append one token, score every resident token, top-k, attend with accumulated-score update)
+    until about `budget_s` seconds of CPU work are done."""
+    import numpy as np
+    import oracle
+    import synth_inputs as S
+    d = model.layer0
+    R = w.batch * w.n_kv_heads
+    oc = oracle.Cache(R, w.n + max_steps, 128, w.bits, w.group)
+    t0 = time.perf_counter()
+    oracle.quantize(oc, d["keys"].numpy().reshape(R, w.n, 128))
+    t_build = time.perf_counter() - t0
+    V = np.zeros((R, w.n + max_steps, 128), np.float16)
+    V[:, :w.n] = d["values"].numpy().reshape(R, w.n, 128)
+    pos = np.tile(np.arange(w.n + max_steps, dtype=np.int32), (R, 1))
+    acc = np.zeros((R, w.n + max_steps), np.float32)
+    parts = np.zeros(4)
+    steps, scored = 0, 0
+    while steps < max_steps and parts.sum() < budget_s:
+        k_new, v_new, q = S.make_step(w, 0, steps)
+        V[:, w.n + steps] = v_new.numpy().reshape(R, 128)
+        q16 = q.numpy().reshape(-1, 128)
+        t0 = time.perf_counter()
+        oracle.quantize(oc, k_new.numpy().reshape(R, 1, 128))
+        t1 = time.perf_counter()
+        sel, _ = oracle.score(oc, q16, want_z=False)
+        t2 = time.perf_counter()
+        idx, count = oracle.topk(sel, oc.n, w.k)
+        t3 = time.perf_counter()
+        oracle.attend(oc, q16, idx, count, pos, V, model.sm_scale, acc=acc)
+        t4 = time.perf_counter()
+        parts += (t1 - t0, t2 - t1, t3 - t2, t4 - t3)
+        steps += 1
+        scored += w.batch * int(oc.n[0])
+    total = float(parts.sum())
+    return {
+        "value": scored / total, "unit": "tokens/s",
+        "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"{steps} consecutive decode steps of ONE layer (layer 0) of {w.name}, every resident token of "
+                  f"all {w.n_kv_heads} KV heads scored per step, no eviction (append {parts[0]:.3f}s, score "
+                  f"{parts[1]:.3f}s, top-k {parts[2]:.3f}s, attend {parts[3]:.3f}s); the oracle's own bulk "
+                  f"quantise of the context ({t_build:.1f}s) is not in the timed part",
+        "seconds": total,
+    }
+
+
+def main():
+    faulthandler.enable()
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=16)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=4, help="BASELINE config id (2, 3, 4 or 5)")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
+    ap.add_argument("--host-gib", type=float, default=60.0,
+                    help="pinned host memory budget for values (the GPU boxes refuse more than 65 GiB in total)")
+    ap.add_argument("--evict-every", type=int, default=16)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true", help="single stream, no gather/score overlap")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
+              "(one process, one MI355X, no collectives).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    B.lib()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+
+    w = S.CONFIGS[args.config]
+    L = args.layers or w.layers
+    # host link: peak (one large pinned copy) and the gather as the path issues it
+    main_s = [torch.cuda.Stream(), torch.cuda.Stream()]
+    gath_s = [torch.cuda.Stream(), torch.cuda.Stream()]
+    _ = [x.cuda_stream for x in main_s + gath_s]
+    big = torch.empty(1 << 28, dtype=torch.uint8, pin_memory=True)
+    dbig = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    dbig.copy_(big, non_blocking=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(16):
+        dbig.copy_(big, non_blocking=True)
+    torch.cuda.synchronize()
+    link_peak = 16 * (1 << 28) / (time.perf_counter() - t0) / 1e9
+    del dbig
+
+    total_steps = args.steps + args.warmup
+    model = Model(w, L, args.evict_every, total_steps)
+    layer_v_gib = w.batch * w.n_kv_heads * w.n * 256 / 2 ** 30
+    phys = max(1, min(L, int(args.host_gib / layer_v_gib)))
+    t0 = time.perf_counter()
+    tq = model.build(phys)
+    model.make_steps(total_steps)
+    phys = model.phys
+    log(f"setup {time.perf_counter() - t0:.1f}s: {L} layers, {phys} physical value layers "
+        f"({phys * layer_v_gib:.1f} GiB pinned), bulk quantise {tq:.3f}s")
+    bulk_tokens = L * w.batch * w.n_kv_heads * w.n
+    code_bytes = 128 * w.bits // 8 + (128 // w.group) * 4
+
+    if args.no_overlap:
+        main_s = [main_s[0], main_s[0]]
+        gath_s = [main_s[0], main_s[0]]
+
+    def step(t, events=None):
+        for l in range(L):
+            p = l & 1
+            ev = None
+            if events is not None:
+                ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                events.append(ev)
+            model.layer_step(l, t, main_s[p], gath_s[p], model.pipe[p], ev)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    log("warmup done")
+    events = []
+    t0 = time.perf_counter()
+    for t in range(args.warmup, total_steps):
+        step(t, events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    log(f"timed region done: {dt:.3f}s for {args.steps} steps")
+    ms_per_step = dt * 1e3 / args.steps
+    tokens_per_step = w.batch * w.n * L
+    value = tokens_per_step / (dt / args.steps)
+
+    scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
+    scan_bytes = w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + 4)
+    achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "context tokens scored/s", "value": value, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8xint4->int32, fp32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "context": w.n, "layers": L, "q_heads": w.n_q_heads,
+                   "kv_heads": w.n_kv_heads, "key_bits": w.bits, "group": w.group, "top_k": w.k,
+                   "evict_every": args.evict_every, "values": "context rows in pinned host fp16, appended rows in an HBM slice",
+                   "physical_value_layers": phys, "overlap": not args.no_overlap},
+        "per_layer_latency_ms": ms_per_step / L,
+        "bulk_quantize_tokens_per_s": bulk_tokens / tq,
+        "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
+        "host_link_peak_GBs": link_peak,
+        "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = run_cpu_baseline(model, w)
+    print(json.dumps(out), flush=True)
+    log("result printed")
+
+
+if __name__ == "__main__":
+    main()

@@ -82,10 +82,17 @@ size_t hca_workspace_bytes(const hca_shape* shape, int64_t k_max, int64_t m_max)
  *   kcache      device, hca_kcache_bytes() bytes, updated in place
  * Per (token, group): zero = min, scale = fp16((max-min)/(2^bits-1)) (1.0 if that
  * is 0), code = clamp(rint((x-zero)*(1/scale)), 0, 2^bits-1).
+ * Slot bookkeeping for the new tokens is fused in when acc_opt / pos_opt are given:
+ *   acc_opt     device, fp32 [batch, n_kv_heads, capacity] or NULL: acc[slot] = 0
+ *   pos_opt     device, int32 [batch, n_kv_heads, capacity] or NULL:
+ *               pos[slot of new token t] = value_row0[b] + t
+ *   value_row0  host, int64 [batch]: value-store row of each sequence's first new token
+ *               (required iff pos_opt is given)
  * The caller adds T to n_resident afterwards.
  * Errors: HCA_ERR_CAPACITY if n_resident[b]+T > capacity. */
 int32_t hca_quantize_keys(const hca_shape* shape, void* kcache, const void* k_new_f16,
-                          int64_t T, const int64_t* n_resident, void* stream);
+                          int64_t T, const int64_t* n_resident, float* acc_opt, int32_t* pos_opt,
+                          const int64_t* value_row0, void* stream);
 
 /* Step 2, z~ = q . Q(K)^T of Eq. 2 / Eq. 3 for every resident token, keys
  * dequantised on the fly.  The query is first mapped to 15-bit fixed point per

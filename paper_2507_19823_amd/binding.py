@@ -47,7 +47,7 @@ def lib():
         L.hca_workspace_bytes.restype = C.c_size_t
         L.hca_workspace_bytes.argtypes = [sp, i64, i64]
         L.hca_quantize_keys.restype = i32
-        L.hca_quantize_keys.argtypes = [sp, vp, vp, i64, vp, vp]
+        L.hca_quantize_keys.argtypes = [sp, vp, vp, i64, vp, vp, vp, vp, vp]
         L.hca_score_qkeys.restype = i32
         L.hca_score_qkeys.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.hca_topk.restype = i32
@@ -103,10 +103,12 @@ def hca_workspace_bytes(shape, k_max, m_max):
     return int(lib().hca_workspace_bytes(C.byref(shape), int(k_max), int(m_max)))
 
 
-def hca_quantize_keys(shape, kcache, k_new_f16, T, n_resident, stream=None):
+def hca_quantize_keys(shape, kcache, k_new_f16, T, n_resident, acc_opt=None, pos_opt=None, value_row0=None,
+                      stream=None):
     nr = _nres(n_resident, shape.batch)
-    _check(lib().hca_quantize_keys(C.byref(shape), _ptr(kcache), _ptr(k_new_f16), int(T), nr, _stream(stream)),
-           "hca_quantize_keys")
+    vr = None if value_row0 is None else _nres(value_row0, shape.batch)
+    _check(lib().hca_quantize_keys(C.byref(shape), _ptr(kcache), _ptr(k_new_f16), int(T), nr, _ptr(acc_opt),
+                                   _ptr(pos_opt), vr, _stream(stream)), "hca_quantize_keys")
 
 
 def hca_score_qkeys(shape, kcache, q_f16, n_resident, sel, z_opt=None, workspace=None, stream=None):

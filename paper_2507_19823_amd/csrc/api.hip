@@ -81,7 +81,8 @@ size_t hca_workspace_bytes(const hca_shape* shape, int64_t k_max, int64_t m_max)
 }
 
 int32_t hca_quantize_keys(const hca_shape* shape, void* kcache, const void* k_new_f16, int64_t T,
-                          const int64_t* n_resident, void* stream) {
+                          const int64_t* n_resident, float* acc_opt, int32_t* pos_opt,
+                          const int64_t* value_row0, void* stream) {
   Layout L;
   int32_t rc = make_layout(shape, &L);
   if (rc != HCA_OK) return rc;
@@ -92,7 +93,16 @@ int32_t hca_quantize_keys(const hca_shape* shape, void* kcache, const void* k_ne
   if (rc != HCA_OK) return rc;
   for (int b = 0; b < L.batch; ++b)
     if (nr.n[b] + T > L.cap) return HCA_ERR_CAPACITY;
-  return launch_quantize(L, kcache, k_new_f16, T, nr, (hipStream_t)stream);
+  NRes vrow0;
+  for (int b = 0; b < kMaxBatch; ++b) vrow0.n[b] = 0;
+  if (pos_opt != nullptr) {
+    if (value_row0 == nullptr) return HCA_ERR_BAD_ARG;
+    for (int b = 0; b < L.batch; ++b) {
+      if (value_row0[b] < 0 || value_row0[b] + T > (int64_t)INT32_MAX) return HCA_ERR_BAD_ARG;
+      vrow0.n[b] = value_row0[b];
+    }
+  }
+  return launch_quantize(L, kcache, k_new_f16, T, nr, acc_opt, pos_opt, vrow0, (hipStream_t)stream);
 }
 
 int32_t hca_score_qkeys(const hca_shape* shape, const void* kcache, const void* q_f16,

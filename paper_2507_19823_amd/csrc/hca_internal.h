@@ -48,7 +48,7 @@ int32_t select_run(const SelectPlan& p, const float* vals, int64_t stride, int r
                    const SelRows& sr, hipStream_t st);
 
 int32_t launch_quantize(const Layout& L, void* kcache, const void* k_new, int64_t T, const NRes& nr,
-                        hipStream_t st);
+                        float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st);
 int32_t launch_export(const Layout& L, const void* kcache, const NRes& nr, uint8_t* codes, void* scale,
                       void* zero, hipStream_t st);
 int32_t launch_score(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,

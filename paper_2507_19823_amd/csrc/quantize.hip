@@ -9,7 +9,8 @@ namespace hca {
 // [32j, 32j+32) and [128+32j, 128+32j+32) of the token's 256-byte fp16 row.
 template <int BITS>
 __global__ __launch_bounds__(256) void quantize_kernel(Layout L, uint8_t* __restrict__ kcache,
-                                                       const uint16_t* __restrict__ k_new, int64_t T, NRes nr) {
+                                                       const uint16_t* __restrict__ k_new, int64_t T, NRes nr,
+                                                       float* __restrict__ acc, int32_t* __restrict__ pos, NRes vrow0) {
   constexpr int QMAX = (1 << BITS) - 1;
   const int row = blockIdx.y;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -76,6 +77,8 @@ __global__ __launch_bounds__(256) void quantize_kernel(Layout L, uint8_t* __rest
   const int64_t slot = nr.n[row / L.n_kv_heads] + tc;
   uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
   uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
+  if (live && j == 1 && acc != nullptr) acc[(int64_t)row * L.cap + slot] = 0.0f;
+  if (live && j == 2 && pos != nullptr) pos[(int64_t)row * L.cap + slot] = (int32_t)(vrow0.n[row / L.n_kv_heads] + tt);
   if (BITS == 4) {
     const uint32_t o0 = __shfl_xor(meta[0], 32), o1 = __shfl_xor(meta[1], 32);
     if (live) {
@@ -154,13 +157,13 @@ __global__ __launch_bounds__(256) void export_kernel(Layout L, const uint8_t* __
 }
 
 int32_t launch_quantize(const Layout& L, void* kcache, const void* k_new, int64_t T, const NRes& nr,
-                        hipStream_t st) {
+                        float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st) {
   if (T == 0) return HCA_OK;
   dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows);
   if (L.bits == 4)
-    quantize_kernel<4><<<grid, 256, 0, st>>>(L, (uint8_t*)kcache, (const uint16_t*)k_new, T, nr);
+    quantize_kernel<4><<<grid, 256, 0, st>>>(L, (uint8_t*)kcache, (const uint16_t*)k_new, T, nr, acc_opt, pos_opt, vrow0);
   else
-    quantize_kernel<2><<<grid, 256, 0, st>>>(L, (uint8_t*)kcache, (const uint16_t*)k_new, T, nr);
+    quantize_kernel<2><<<grid, 256, 0, st>>>(L, (uint8_t*)kcache, (const uint16_t*)k_new, T, nr, acc_opt, pos_opt, vrow0);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

@@ -40,9 +40,13 @@ class LayerState:
         self.n = [0] * batch
         self.sm_scale = 1.0 / math.sqrt(128.0)
 
-    def quantize(self, k_new, stream=None):
+    def quantize(self, k_new, value_row0=None, stream=None):
+        """Append k_new [B,Hkv,T,D]; with value_row0 (one int per sequence) also resets acc and sets pos."""
         T = k_new.shape[2]
-        B.hca_quantize_keys(self.shape, self.kcache, k_new, T, self.n, stream)
+        if value_row0 is None:
+            B.hca_quantize_keys(self.shape, self.kcache, k_new, T, self.n, None, None, None, stream)
+        else:
+            B.hca_quantize_keys(self.shape, self.kcache, k_new, T, self.n, self.acc, self.pos, value_row0, stream)
         self.n = [x + T for x in self.n]
 
     def score(self, q, stream=None):

@@ -53,9 +53,10 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     s = B.make_shape(1, 32, 8, 1024)
     n = (C.c_int64 * 1)(100)
     one = C.c_void_p(256)      # never dereferenced: validation fails first
-    assert L.hca_quantize_keys(C.byref(s), None, one, 1, n, None) == -1
-    assert L.hca_quantize_keys(C.byref(s), one, one, 925, n, None) == -3          # 100 + 925 > 1024
-    assert L.hca_quantize_keys(C.byref(s), one, one, -1, n, None) == -1
+    assert L.hca_quantize_keys(C.byref(s), None, one, 1, n, None, None, None, None) == -1
+    assert L.hca_quantize_keys(C.byref(s), one, one, 925, n, None, None, None, None) == -3          # 100 + 925 > 1024
+    assert L.hca_quantize_keys(C.byref(s), one, one, -1, n, None, None, None, None) == -1
+    assert L.hca_quantize_keys(C.byref(s), one, one, 1, n, None, one, None, None) == -1   # pos without value_row0
     assert L.hca_score_qkeys(C.byref(s), one, one, None, one, None, None, None) == -1
     assert L.hca_topk(C.byref(s), one, n, 0, one, one, one, None) == -3
     assert L.hca_topk(C.byref(s), one, n, 1025, one, one, one, None) == -3

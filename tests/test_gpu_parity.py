@@ -276,11 +276,10 @@ def test_decode_loop_with_appends_and_eviction(H, oracle):
         k_new, v_new, q = S.make_step(w, 0, step)
         n = st.n[0]
         v_host[:, :, n0 + step] = v_new[:, :, 0]
-        st.pos[:, :, n] = n0 + step
-        st.acc[:, :, n] = 0
+        st.acc[:, :, n] = 123.0                      # stale value the fused append must clear
         pos[:, n] = n0 + step
         acc[:, n] = 0
-        st.quantize(k_new.cuda())
+        st.quantize(k_new.cuda(), value_row0=[n0 + step] * w.batch)
         oracle.quantize(oc, _rows(k_new))
         qd = q.cuda()
         st.score(qd)
