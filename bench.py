@@ -50,14 +50,16 @@ class Model:
         self.v_host = [None] * layers
         self.v_hbm = [torch.zeros(w.batch, w.n_kv_heads, self.vnew, 128, dtype=torch.float16, device=dev)
                       for _ in range(layers)]
-        wsb = B.hca_workspace_bytes(self.shape, w.k, self.n0)
+        self.sel = torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev)
+        self.ws_main = torch.empty(B.hca_workspace_bytes(self.shape, w.k, self.n0), dtype=torch.uint8, device=dev)
+        wsa = B.hca_workspace_bytes(self.shape, w.k, 1)
         self.pipe = []
         for _ in range(n_pipe):
             self.pipe.append(dict(
-                sel=torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev),
                 idx=torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev),
                 count=torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev),
-                ws=torch.empty(wsb, dtype=torch.uint8, device=dev)))
+                ws=torch.empty(wsa, dtype=torch.uint8, device=dev),
+                sel_done=torch.cuda.Event(), gather_done=torch.cuda.Event()))
         self.y = torch.zeros(layers, w.batch, w.n_q_heads, 128, dtype=torch.float32, device=dev)
         self.n = [[0] * w.batch for _ in range(layers)]
         self.sm_scale = 1.0 / (128.0 ** 0.5)
@@ -112,29 +114,65 @@ class Model:
             self.q.append(torch.stack(qs).cuda())
         torch.cuda.synchronize()
 
-    def layer_step(self, l, t, st, gst, pipe, ev=None):
-        """One layer of decode step t on stream st (gather on gst)."""
+    def scan_select(self, l, t, st, pipe, ev=None):
+        """a1 + a2 + a3 of layer l, decode step t, on stream st."""
         B, w = self.B, self.w
         n = self.n[l]
         B.hca_quantize_keys(self.shape, self.kcache[l], self.k_new[t][l], 1, n, self.acc[l], self.pos[l],
                             [self.n0 + t] * w.batch, st)
         n = [x + 1 for x in n]
-        q = self.q[t][l]
+        self.n[l] = n
         if ev is not None:
             ev[0].record(st)
-        B.hca_score_qkeys(self.shape, self.kcache[l], q, n, pipe["sel"], None, None, st)
+        B.hca_score_qkeys(self.shape, self.kcache[l], self.q[t][l], n, self.sel, None, None, st)
         if ev is not None:
             ev[1].record(st)
-        B.hca_topk(self.shape, pipe["sel"], n, w.k, pipe["idx"], pipe["count"], pipe["ws"], st)
+        B.hca_topk(self.shape, self.sel, n, w.k, pipe["idx"], pipe["count"], self.ws_main, st)
+
+    def gather(self, l, gst, pipe):
+        """host-link half of a4: selected value rows -> staging, on the gather stream."""
         vh = self.v_host[l]
-        B.hca_sparse_attend(self.shape, self.kcache[l], q, pipe["idx"], pipe["count"], w.k, self.pos[l],
-                            vh, vh.shape[2], vh.shape[2], self.v_hbm[l], self.vnew, self.sm_scale, self.y[l], self.acc[l],
-                            pipe["ws"], gst, st)
+        self.B.hca_gather_values(self.shape, pipe["idx"], pipe["count"], self.w.k, self.pos[l], vh, vh.shape[2],
+                                 vh.shape[2], self.v_hbm[l], self.vnew, pipe["ws"], gst)
+
+    def attend_evict(self, l, t, st, pipe):
+        """compute half of a4 (+ accumulated scores) and, when due, a5."""
+        B, w = self.B, self.w
+        B.hca_attend_gathered(self.shape, self.kcache[l], self.q[t][l], pipe["idx"], pipe["count"], w.k,
+                              self.sm_scale, self.y[l], self.acc[l], pipe["ws"], st)
         if self.evict_every and (t + 1) % self.evict_every == 0:
-            B.hca_evict(self.shape, self.kcache[l], self.acc[l], self.pos[l], n, self.n0, self.evict_every,
-                        None, pipe["ws"], st)
-            n = [min(x, self.n0) for x in n]
-        self.n[l] = n
+            B.hca_evict(self.shape, self.kcache[l], self.acc[l], self.pos[l], self.n[l], self.n0,
+                        self.evict_every, None, self.ws_main, st)
+            self.n[l] = [min(x, self.n0) for x in self.n[l]]
+
+    def decode_step(self, t, main, side, overlap=True, events=None):
+        """One decode step over all layers.  With overlap, the gather of layer l runs on the side stream
+        under the key scan and top-k of layer l+1; the main stream never waits for the host link
+        except right before the attend that needs it."""
+        prev = None
+        for l in range(self.L):
+            pipe = self.pipe[l & 1]
+            ev = None
+            if events is not None:
+                ev = events[l]
+            self.scan_select(l, t, main, pipe, ev)
+            if overlap:
+                pipe["sel_done"].record(main)
+                side.wait_event(pipe["sel_done"])
+                self.gather(l, side, pipe)
+                pipe["gather_done"].record(side)
+                if prev is not None:
+                    pp = self.pipe[prev & 1]
+                    main.wait_event(pp["gather_done"])
+                    self.attend_evict(prev, t, main, pp)
+                prev = l
+            else:
+                self.gather(l, main, pipe)
+                self.attend_evict(l, t, main, pipe)
+        if prev is not None:
+            pp = self.pipe[prev & 1]
+            main.wait_event(pp["gather_done"])
+            self.attend_evict(prev, t, main, pp)
 
 
 def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
@@ -239,33 +277,25 @@ def main():
     bulk_tokens = L * w.batch * w.n_kv_heads * w.n
     code_bytes = 128 * w.bits // 8 + (128 // w.group) * 4
 
-    if args.no_overlap:
-        main_s = [main_s[0], main_s[0]]
-        gath_s = [main_s[0], main_s[0]]
-
-    def step(t, events=None):
-        for l in range(L):
-            p = l & 1
-            ev = None
-            if events is not None:
-                ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                events.append(ev)
-            model.layer_step(l, t, main_s[p], gath_s[p], model.pipe[p], ev)
+    main, side = main_s[0], gath_s[0]
+    overlap = not args.no_overlap
 
     for t in range(args.warmup):
-        step(t)
+        model.decode_step(t, main, side, overlap)
     torch.cuda.synchronize()
     log("warmup done")
-    events = []
+    events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
+              for _ in range(args.steps)]
     t0 = time.perf_counter()
     for t in range(args.warmup, total_steps):
-        step(t, events)
+        model.decode_step(t, main, side, overlap, events[t - args.warmup])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     log(f"timed region done: {dt:.3f}s for {args.steps} steps")
     ms_per_step = dt * 1e3 / args.steps
     tokens_per_step = w.batch * w.n * L
     value = tokens_per_step / (dt / args.steps)
+    events = [e for step_events in events for e in step_events]
 
     scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
     scan_bytes = w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + 4)

@@ -63,6 +63,11 @@ typedef struct {
 /* Library version string (static storage). */
 const char* hca_version(void);
 
+/* Overrides a launch-shape knob (process-wide; for tuning and profiling, not needed for
+ * correct results).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth".
+ * Returns HCA_ERR_BAD_ARG for an unknown name. */
+int32_t hca_tune(const char* name, int32_t value);
+
 /* hipError_t of the most recent failing HIP call made by this thread (0 if none). */
 int32_t hca_last_hip_error(void);
 
@@ -137,6 +142,19 @@ int32_t hca_sparse_attend(const hca_shape* shape, const void* kcache, const void
                           const void* v_hbm, int64_t hbm_stride,
                           float sm_scale, float* y, float* acc_opt,
                           void* workspace, void* gather_stream, void* stream);
+
+/* The two halves of hca_sparse_attend, for callers that overlap the host-link gather of one
+ * layer with the key scan of the next (Sec. 3.2: the value side runs off the GPU's critical
+ * path).  hca_gather_values copies the selected value rows into `workspace` on `stream`;
+ * hca_attend_gathered, called later with the same idx / count / k / workspace and ordered
+ * after the gather by the caller (event or same stream), computes y and updates acc_opt.
+ * Arguments as in hca_sparse_attend. */
+int32_t hca_gather_values(const hca_shape* shape, const int32_t* idx, const int32_t* count, int32_t k,
+                          const int32_t* pos, const void* v_host, int64_t host_stride, int64_t n_host_rows,
+                          const void* v_hbm, int64_t hbm_stride, void* workspace, void* stream);
+int32_t hca_attend_gathered(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
+                            const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
+                            void* workspace, void* stream);
 
 /* Step 4, accumulated-score eviction.  Rows with n_resident > M keep their newest
  * n_protect slots and, of the others, the M - n_protect with the highest acc (ties

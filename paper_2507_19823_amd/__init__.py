@@ -1,5 +1,5 @@
 """HCAttention decode hot path for MI355X: HIP kernels behind a C ABI (libhca.so) and a thin
 ctypes binding with the same names."""
-from .binding import (HcaError, hca_evict, hca_export_kcache, hca_kcache_bytes, hca_quantize_keys,  # noqa: F401
+from .binding import (HcaError, hca_attend_gathered, hca_evict, hca_gather_values, hca_export_kcache, hca_kcache_bytes, hca_quantize_keys,  # noqa: F401
                       hca_score_qkeys, hca_shape, hca_sparse_attend, hca_topk, hca_version,
                       hca_workspace_bytes, lib, make_shape)

@@ -42,6 +42,8 @@ def lib():
         sp = C.POINTER(hca_shape)
         L.hca_version.restype = C.c_char_p
         L.hca_last_hip_error.restype = i32
+        L.hca_tune.restype = i32
+        L.hca_tune.argtypes = [C.c_char_p, i32]
         L.hca_kcache_bytes.restype = C.c_size_t
         L.hca_kcache_bytes.argtypes = [sp]
         L.hca_workspace_bytes.restype = C.c_size_t
@@ -55,6 +57,10 @@ def lib():
         L.hca_sparse_attend.restype = i32
         L.hca_sparse_attend.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, i64, i64, vp, i64, f32, vp, vp,
                                         vp, vp, vp]
+        L.hca_gather_values.restype = i32
+        L.hca_gather_values.argtypes = [sp, vp, vp, i32, vp, vp, i64, i64, vp, i64, vp, vp]
+        L.hca_attend_gathered.restype = i32
+        L.hca_attend_gathered.argtypes = [sp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp]
         L.hca_evict.restype = i32
         L.hca_evict.argtypes = [sp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
         L.hca_export_kcache.restype = i32
@@ -95,6 +101,10 @@ def hca_version():
     return lib().hca_version().decode()
 
 
+def hca_tune(name, value):
+    _check(lib().hca_tune(name.encode(), int(value)), "hca_tune")
+
+
 def hca_kcache_bytes(shape):
     return int(lib().hca_kcache_bytes(C.byref(shape)))
 
@@ -131,6 +141,19 @@ def hca_sparse_attend(shape, kcache, q_f16, idx, count, k, pos, v_host, host_str
                                    _ptr(pos), _ptr(v_host), int(host_stride), int(n_host_rows), _ptr(v_hbm),
                                    int(hbm_stride), float(sm_scale), _ptr(y), _ptr(acc_opt), _ptr(workspace),
                                    gst, st), "hca_sparse_attend")
+
+
+def hca_gather_values(shape, idx, count, k, pos, v_host, host_stride, n_host_rows, v_hbm, hbm_stride, workspace,
+                      stream=None):
+    _check(lib().hca_gather_values(C.byref(shape), _ptr(idx), _ptr(count), int(k), _ptr(pos), _ptr(v_host),
+                                   int(host_stride), int(n_host_rows), _ptr(v_hbm), int(hbm_stride),
+                                   _ptr(workspace), _stream(stream)), "hca_gather_values")
+
+
+def hca_attend_gathered(shape, kcache, q_f16, idx, count, k, sm_scale, y, acc_opt, workspace, stream=None):
+    _check(lib().hca_attend_gathered(C.byref(shape), _ptr(kcache), _ptr(q_f16), _ptr(idx), _ptr(count), int(k),
+                                     float(sm_scale), _ptr(y), _ptr(acc_opt), _ptr(workspace), _stream(stream)),
+           "hca_attend_gathered")
 
 
 def hca_evict(shape, kcache, acc, pos, n_resident, M, n_protect, kept_opt, workspace, stream=None):

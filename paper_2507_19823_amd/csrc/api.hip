@@ -7,6 +7,11 @@ namespace hca {
 
 static thread_local int32_t g_last_hip = 0;
 
+Tuning& tuning() {
+  static Tuning t;
+  return t;
+}
+
 int32_t hip_fail(hipError_t e) {
   g_last_hip = (int32_t)e;
   return HCA_ERR_HIP;
@@ -58,6 +63,17 @@ extern "C" {
 
 const char* hca_version(void) { return "hca 0.1 (gfx950)"; }
 
+int32_t hca_tune(const char* name, int32_t value) {
+  if (name == nullptr) return HCA_ERR_BAD_ARG;
+  Tuning& t = tuning();
+  if (!strcmp(name, "gather_wgs")) t.gather_wgs = value;
+  else if (!strcmp(name, "gather_unroll")) t.gather_unroll = value;
+  else if (!strcmp(name, "score_bpw")) t.score_bpw = value;
+  else if (!strcmp(name, "score_depth")) t.score_depth = value;
+  else return HCA_ERR_BAD_ARG;
+  return HCA_OK;
+}
+
 int32_t hca_last_hip_error(void) { return g_last_hip; }
 
 size_t hca_kcache_bytes(const hca_shape* shape) {
@@ -73,7 +89,7 @@ size_t hca_workspace_bytes(const hca_shape* shape, int64_t k_max, int64_t m_max)
   if (m_max < 1) m_max = 1;
   if (k_max > L.cap) k_max = L.cap;
   if (m_max > L.cap) m_max = L.cap;
-  size_t a = select_workspace_bytes(L.rows, L.cap);
+  size_t a = topk_workspace_bytes(L.rows);
   size_t b = attend_workspace_bytes(L, k_max);
   size_t c = evict_workspace_bytes(L, m_max);
   size_t m = a > b ? a : b;
@@ -151,6 +167,35 @@ int32_t hca_sparse_attend(const hca_shape* shape, const void* kcache, const void
   return launch_attend(L, kcache, q_f16, idx, count, k, pos, v_host, host_stride, n_host_rows, v_hbm,
                        hbm_stride, sm_scale, y, acc_opt, workspace, (hipStream_t)gather_stream,
                        (hipStream_t)stream);
+}
+
+int32_t hca_gather_values(const hca_shape* shape, const int32_t* idx, const int32_t* count, int32_t k,
+                          const int32_t* pos, const void* v_host, int64_t host_stride, int64_t n_host_rows,
+                          const void* v_hbm, int64_t hbm_stride, void* workspace, void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (idx == nullptr || count == nullptr || pos == nullptr || workspace == nullptr) return HCA_ERR_BAD_ARG;
+  if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
+  if (n_host_rows < 0 || host_stride < 0 || hbm_stride < 0) return HCA_ERR_BAD_ARG;
+  if (n_host_rows > 0 && (v_host == nullptr || host_stride < n_host_rows)) return HCA_ERR_BAD_ARG;
+  if (v_host == nullptr && v_hbm == nullptr) return HCA_ERR_BAD_ARG;
+  return launch_gather(L, idx, count, k, pos, v_host, host_stride, n_host_rows, v_hbm, hbm_stride, workspace,
+                       (hipStream_t)stream);
+}
+
+int32_t hca_attend_gathered(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
+                            const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
+                            void* workspace, void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (kcache == nullptr || q_f16 == nullptr || idx == nullptr || count == nullptr || y == nullptr ||
+      workspace == nullptr)
+    return HCA_ERR_BAD_ARG;
+  if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
+  return launch_attend_gathered(L, kcache, q_f16, idx, count, k, sm_scale, y, acc_opt, workspace,
+                                (hipStream_t)stream);
 }
 
 int32_t hca_evict(const hca_shape* shape, void* kcache, float* acc, int32_t* pos, const int64_t* n_resident,

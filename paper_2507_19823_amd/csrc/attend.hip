@@ -35,22 +35,40 @@ static void carve(AttendWs* a, void* ws, const Layout& L, int64_t k) {
 }
 
 // 16 threads move one 256-byte value row; rows below n_host_rows are read straight from
-// pinned host memory over the host link (zero-copy), the others from the HBM slice.
+// pinned host memory over the host link (zero-copy), the others from the HBM slice.  The grid
+// is deliberately small and persistent: the host link saturates with a few hundred KiB in
+// flight, and more outstanding host reads than that only clog the memory pipeline for the
+// HBM-bound kernels that run beside the gather.
+template <int UNROLL>
 __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__ idx, const int32_t* __restrict__ count,
                                                      int32_t k, const int32_t* __restrict__ pos, int64_t cap,
                                                      const uint4* __restrict__ v_host, int64_t host_stride,
                                                      int64_t n_host_rows, const uint4* __restrict__ v_hbm,
-                                                     int64_t hbm_stride, uint4* __restrict__ vstage) {
-  const int row = blockIdx.y;
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t i = gid >> 4;
-  const int part = (int)(gid & 15);
-  if (i >= count[row]) return;
-  const int32_t slot = idx[(int64_t)row * k + i];
-  const int64_t v = pos[(int64_t)row * cap + slot];
-  const uint4* src = (v < n_host_rows) ? v_host + ((int64_t)row * host_stride + v) * 16
-                                       : v_hbm + ((int64_t)row * hbm_stride + (v - n_host_rows)) * 16;
-  vstage[((int64_t)row * k + i) * 16 + part] = src[part];
+                                                     int64_t hbm_stride, uint4* __restrict__ vstage,
+                                                     int wgs) {
+  const int row = blockIdx.y, wg = blockIdx.x;
+  const int cnt = count[row];
+  const int part = threadIdx.x & 15;
+  const int64_t step = (int64_t)wgs * 16;                 // value rows per sweep of the row's workgroups
+  for (int64_t i0 = (int64_t)wg * 16 + (threadIdx.x >> 4); i0 < cnt; i0 += step * UNROLL) {
+    uint4 v[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t i = i0 + u * step;
+      if (i < cnt) {
+        const int32_t slot = idx[(int64_t)row * k + i];
+        const int64_t vr = pos[(int64_t)row * cap + slot];
+        const uint4* src = (vr < n_host_rows) ? v_host + ((int64_t)row * host_stride + vr) * 16
+                                              : v_hbm + ((int64_t)row * hbm_stride + (vr - n_host_rows)) * 16;
+        v[u] = src[part];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t i = i0 + u * step;
+      if (i < cnt) vstage[((int64_t)row * k + i) * 16 + part] = v[u];
+    }
+  }
 }
 
 template <int BITS>
@@ -82,27 +100,41 @@ __global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* _
   const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
   const int32_t* ridx = idx + (int64_t)row * k;
 
-  // 1. logits of the chunk: wave w scores tiles w, w+4, ... (16 selected tokens each)
-  for (int tile = w; tile * 16 < nvalid; tile += 4) {
-    const int i = tile * 16 + t;
-    const int ii = i < nvalid ? i : nvalid - 1;
-    const int64_t slot = ridx[i0 + ii];
-    float zv;
-    if constexpr (BITS == 4) {
-      const int64_t blk = slot >> 4;
-      const int tl = (int)(slot & 15);
-      const uint4 wv = *reinterpret_cast<const uint4*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16);
-      const uint4 mv = *reinterpret_cast<const uint4*>(mrow + blk * kMetaBytes + tl * 16);
-      zv = score_block4(op, wv, mv);
-    } else {
-      const int64_t blk = slot >> 5;
-      const int u = (int)((slot >> 4) & 1), tl = (int)(slot & 15);
-      const uint2 wv = *reinterpret_cast<const uint2*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16 + 8 * u);
-      const uint2 mv = *reinterpret_cast<const uint2*>(mrow + blk * kMetaBytes + (16 * u + tl) * 8);
-      zv = score_tile2(op, wv.x, wv.y, mv);
+  // 1. logits of the chunk: wave w scores tiles w, w+4, w+8, w+12 (16 selected tokens each).
+  //    All slot numbers are fetched first, then all code / meta pieces, so that the wave has its
+  //    whole share of the random reads in flight at once.
+  {
+    int64_t slot[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int i = (w + 4 * x) * 16 + t;
+      slot[x] = ridx[i0 + (i < nvalid ? i : nvalid - 1)];
     }
-    // lane (t, hd = j) holds z~ of head j for selected token i
-    lg[j][i] = zv * sm_scale;
+    uint4 wv[4], mv[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      if constexpr (BITS == 4) {
+        const int64_t blk = slot[x] >> 4;
+        const int tl = (int)(slot[x] & 15);
+        wv[x] = *reinterpret_cast<const uint4*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16);
+        mv[x] = *reinterpret_cast<const uint4*>(mrow + blk * kMetaBytes + tl * 16);
+      } else {
+        const int64_t blk = slot[x] >> 5;
+        const int u = (int)((slot[x] >> 4) & 1), tl = (int)(slot[x] & 15);
+        const uint2 c = *reinterpret_cast<const uint2*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16 + 8 * u);
+        const uint2 m = *reinterpret_cast<const uint2*>(mrow + blk * kMetaBytes + (16 * u + tl) * 8);
+        wv[x] = uint4{c.x, c.y, 0, 0};
+        mv[x] = uint4{m.x, m.y, 0, 0};
+      }
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      float zv;
+      if constexpr (BITS == 4) zv = score_block4(op, wv[x], mv[x]);
+      else zv = score_tile2(op, wv[x].x, wv[x].y, uint2{mv[x].x, mv[x].y});
+      // lane (t, hd = j) holds z~ of head j for selected token (w + 4x)*16 + t
+      lg[j][(w + 4 * x) * 16 + t] = zv * sm_scale;
+    }
   }
   __syncthreads();
 
@@ -126,21 +158,55 @@ __global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* _
   }
   __syncthreads();
 
-  // 3. weighted value sum: wave w takes tokens w, w+4, ...; lane owns channels 2*lane, 2*lane+1
-  float acc[4][2] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};
-  const uint32_t* vs = reinterpret_cast<const uint32_t*>(a.vstage) + ((int64_t)row * k + i0) * 64 + lane;
-  for (int i = w; i < nvalid; i += 4) {
-    const uint32_t pr = vs[(int64_t)i * 64];
-    const float v0 = h2f(pr & 0xffffu), v1 = h2f(pr >> 16);
+  // 3. weighted value sum.  Wave w owns tokens [64w, 64w+64) of the chunk; one load instruction
+  //    fetches 4 staged rows (lane>>4 picks the row, lane&15 its 16-byte part) and 8 of them are
+  //    issued before the first is used.
+  float acc[4][8];
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-      const float p = lg[h][i];
-      acc[h][0] = fmaf(p, v0, acc[h][0]);
-      acc[h][1] = fmaf(p, v1, acc[h][1]);
+  for (int h = 0; h < 4; ++h)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[h][c] = 0.f;
+  const int part = lane & 15, sub = lane >> 4;
+  const uint4* vs = reinterpret_cast<const uint4*>(a.vstage) + ((int64_t)row * k + i0) * 16 + part;
+  for (int it = 0; it < 16; it += 8) {
+    uint4 rv[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const int i = 64 * w + 4 * (it + x) + sub;
+      rv[x] = vs[(int64_t)(i < nvalid ? i : nvalid - 1) * 16];
+    }
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const int i = 64 * w + 4 * (it + x) + sub;
+      if (i < nvalid) {
+        const uint32_t wd[4] = {rv[x].x, rv[x].y, rv[x].z, rv[x].w};
+        float v[8];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { v[2 * c] = h2f(wd[c] & 0xffffu); v[2 * c + 1] = h2f(wd[c] >> 16); }
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+          const float p = lg[h][i];
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[h][c] = fmaf(p, v[c], acc[h][c]);
+        }
+      }
     }
   }
 #pragma unroll
-  for (int h = 0; h < 4; ++h) { red[w][h][2 * lane] = acc[h][0]; red[w][h][2 * lane + 1] = acc[h][1]; }
+  for (int h = 0; h < 4; ++h)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      float x = acc[h][c];
+      x += __shfl_xor(x, 16);
+      x += __shfl_xor(x, 32);
+      acc[h][c] = x;
+    }
+  if (sub == 0) {
+#pragma unroll
+    for (int h = 0; h < 4; ++h)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) red[w][h][8 * part + c] = acc[h][c];
+  }
   __syncthreads();
   for (int c = threadIdx.x; c < 4 * kHeadDim; c += 256) {
     const int h = c >> 7, d = c & 127;
@@ -210,34 +276,35 @@ static hipEvent_t next_event(hipError_t* err) {
   return ring[i];
 }
 
-int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
-                      const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,
-                      int64_t host_stride, int64_t n_host_rows, const void* v_hbm, int64_t hbm_stride,
-                      float sm_scale, float* y, float* acc_opt, void* ws, hipStream_t gst, hipStream_t st) {
+int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
+                      const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
+                      int64_t hbm_stride, void* ws, hipStream_t st) {
+  AttendWs a;
+  carve(&a, ws, L, k);
+  const Tuning& tn = tuning();
+  int64_t wgs = ((int64_t)k + 15) / 16;                  // one workgroup per 16 rows at most
+  int64_t lim = tn.gather_wgs > 0 ? tn.gather_wgs : 8;   // per (sequence, KV head)
+  if (wgs > lim) wgs = lim;
+  dim3 g((unsigned)wgs, (unsigned)L.rows);
+  const uint4 *vh = (const uint4*)v_host, *vd = (const uint4*)v_hbm;
+#define HCA_GATHER(U)                                                                                              \
+  gather_values<U><<<g, 256, 0, st>>>(idx, count, k, pos, L.cap, vh, host_stride, n_host_rows, vd, hbm_stride, \
+                                      (uint4*)a.vstage, (int)wgs)
+  if (tn.gather_unroll >= 4) HCA_GATHER(4);
+  else if (tn.gather_unroll >= 2) HCA_GATHER(2);
+  else HCA_GATHER(1);
+#undef HCA_GATHER
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                               const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
+                               void* ws, hipStream_t st) {
   AttendWs a;
   carve(&a, ws, L, k);
   const int ns = nsplit_of(k);
   if (ns > 64) return HCA_ERR_CAPACITY;
-  if (gst != st) {
-    hipError_t e;
-    hipEvent_t ev = next_event(&e);
-    if (e != hipSuccess) return hip_fail(e);
-    HCA_HIP(hipEventRecord(ev, st));
-    HCA_HIP(hipStreamWaitEvent(gst, ev, 0));
-  }
-  {
-    dim3 g((unsigned)(((int64_t)k * 16 + 255) / 256), (unsigned)L.rows);
-    gather_values<<<g, 256, 0, gst>>>(idx, count, k, pos, L.cap, (const uint4*)v_host, host_stride, n_host_rows,
-                                      (const uint4*)v_hbm, hbm_stride, (uint4*)a.vstage);
-    HCA_HIP(hipGetLastError());
-  }
-  if (gst != st) {
-    hipError_t e;
-    hipEvent_t ev = next_event(&e);
-    if (e != hipSuccess) return hip_fail(e);
-    HCA_HIP(hipEventRecord(ev, gst));
-    HCA_HIP(hipStreamWaitEvent(st, ev, 0));
-  }
   dim3 gp((unsigned)ns, (unsigned)L.rows);
   if (L.bits == 4)
     attend_partial<4><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
@@ -247,6 +314,30 @@ int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const 
   attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
+}
+
+int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                      const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,
+                      int64_t host_stride, int64_t n_host_rows, const void* v_hbm, int64_t hbm_stride,
+                      float sm_scale, float* y, float* acc_opt, void* ws, hipStream_t gst, hipStream_t st) {
+  if (nsplit_of(k) > 64) return HCA_ERR_CAPACITY;
+  if (gst != st) {
+    hipError_t e;
+    hipEvent_t ev = next_event(&e);
+    if (e != hipSuccess) return hip_fail(e);
+    HCA_HIP(hipEventRecord(ev, st));
+    HCA_HIP(hipStreamWaitEvent(gst, ev, 0));
+  }
+  int32_t rc = launch_gather(L, idx, count, k, pos, v_host, host_stride, n_host_rows, v_hbm, hbm_stride, ws, gst);
+  if (rc != HCA_OK) return rc;
+  if (gst != st) {
+    hipError_t e;
+    hipEvent_t ev = next_event(&e);
+    if (e != hipSuccess) return hip_fail(e);
+    HCA_HIP(hipEventRecord(ev, gst));
+    HCA_HIP(hipStreamWaitEvent(st, ev, 0));
+  }
+  return launch_attend_gathered(L, kcache, q, idx, count, k, sm_scale, y, acc_opt, ws, st);
 }
 
 }  // namespace hca

@@ -21,6 +21,15 @@ int32_t make_layout(const hca_shape* shape, Layout* L);
 // Copies n_resident (host, [batch]) into `out` after range checks against the capacity.
 int32_t load_nres(const Layout& L, const int64_t* n_resident, NRes* out, int64_t* nmax);
 
+// Launch-shape knobs (defaults chosen by measurement on MI355X; hca_tune() overrides them).
+struct Tuning {
+  int gather_wgs = 0;      // workgroups of the value gather per row (0 = default)
+  int gather_unroll = 4;   // rows in flight per thread
+  int score_bpw = 0;       // 1 KiB code blocks per wave (0 = automatic)
+  int score_depth = 4;     // blocks fetched ahead per wave (2, 4 or 8)
+};
+Tuning& tuning();
+
 inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 // Radix-select engine (select.hip): per row, finds the `want[r]`-th largest key among
@@ -40,6 +49,7 @@ struct SelRows {     // per-sequence selection parameters, by value
   int64_t want[kMaxBatch];   // how many to select among them (0 < want <= nsel, or 0 = skip row)
 };
 size_t select_workspace_bytes(int rows, int64_t nmax);
+size_t topk_workspace_bytes(int rows);
 void select_plan(SelectPlan* p, void* ws, int rows, int64_t nmax);
 // Enqueues the selection passes over `vals` ([rows][stride] fp32).  Afterwards, for row r:
 // state[r][0] = threshold key T, state[r][1] = number of slots with key == T to take (lowest first),
@@ -60,6 +70,12 @@ int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const 
                       const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,
                       int64_t host_stride, int64_t n_host_rows, const void* v_hbm, int64_t hbm_stride,
                       float sm_scale, float* y, float* acc_opt, void* ws, hipStream_t gst, hipStream_t st);
+int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
+                      const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
+                      int64_t hbm_stride, void* ws, hipStream_t st);
+int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                               const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
+                               void* ws, hipStream_t st);
 size_t evict_workspace_bytes(const Layout& L, int64_t M);
 int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr,
                      int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, hipStream_t st);

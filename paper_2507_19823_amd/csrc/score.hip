@@ -90,19 +90,28 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
   const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
   // aim at ~16 waves per SIMD over the whole chip when the cache is large, >= 4 blocks per wave
   const int64_t total = nblocks * L.rows;
+  const Tuning& tn = tuning();
   int64_t bpw = total / (256 * 4 * 16);
   if (bpw < 4) bpw = 4;
   if (bpw > 32) bpw = 32;
+  if (tn.score_bpw > 0) bpw = tn.score_bpw;
   dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
   const uint8_t* kc = (const uint8_t*)kcache;
   const uint16_t* qq = (const uint16_t*)q;
+#define HCA_SCORE(B, Z, U) score_kernel<B, Z, U><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, z_opt)
+#define HCA_SCORE_U(B, Z)                                  \
+  do {                                                     \
+    if (tn.score_depth >= 8) HCA_SCORE(B, Z, 8);           \
+    else if (tn.score_depth >= 4) HCA_SCORE(B, Z, 4);      \
+    else HCA_SCORE(B, Z, 2);                               \
+  } while (0)
   if (L.bits == 4) {
-    if (z_opt) score_kernel<4, true, 4><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, z_opt);
-    else       score_kernel<4, false, 4><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, nullptr);
+    if (z_opt) HCA_SCORE_U(4, true); else HCA_SCORE_U(4, false);
   } else {
-    if (z_opt) score_kernel<2, true, 4><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, z_opt);
-    else       score_kernel<2, false, 4><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, nullptr);
+    if (z_opt) HCA_SCORE_U(2, true); else HCA_SCORE_U(2, false);
   }
+#undef HCA_SCORE_U
+#undef HCA_SCORE
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

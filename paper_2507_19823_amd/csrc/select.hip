@@ -202,12 +202,14 @@ int32_t select_run(const SelectPlan& p, const float* vals, int64_t stride, int r
 __global__ __launch_bounds__(256) void topk_emit(const float* __restrict__ vals, int64_t stride, int64_t chunk,
                                                  int nchunks, int n_kv_heads, SelRows sr,
                                                  const uint32_t* __restrict__ state, const uint32_t* __restrict__ coff,
-                                                 int32_t k, int32_t* __restrict__ idx, int32_t* __restrict__ count) {
+                                                 int32_t k, int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                 bool only_flagged) {
   __shared__ uint32_t wsum[2][4];
   const int row = blockIdx.y;
   const int64_t want = sr.want[row / n_kv_heads];
   if (blockIdx.x == 0 && threadIdx.x == 0) count[row] = want > 0 ? (int32_t)want : 0;
   if (want <= 0) return;
+  if (only_flagged && state[4 * row + 3] == 0) return;   // this row was emitted from its lists
   const int64_t nsel = sr.nsel[row / n_kv_heads];
   const int64_t c0 = (int64_t)blockIdx.x * chunk;
   if (c0 >= nsel) return;
@@ -219,40 +221,424 @@ __global__ __launch_bounds__(256) void topk_emit(const float* __restrict__ vals,
   const float* v = vals + (int64_t)row * stride;
   int32_t* out = idx + (int64_t)row * k;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  for (int64_t s0 = c0; s0 < c1; s0 += 1024) {
-    const int64_t j0 = s0 + 4 * threadIdx.x;
-    bool fg[4], fe[4];
-    uint32_t ng = 0, ne = 0;
+  for (int64_t s0 = c0; s0 < c1; s0 += 4096) {
+    // four sub-tiles of 1024 slots, 4 consecutive slots per thread in each; loads first
+    float f[4][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t j = j0 + i;
-      uint32_t key = 0;
-      const bool in = j < c1;
-      if (in) key = order_key(v[j]);
-      fg[i] = in && key > T;
-      fe[i] = in && key == T;
-      ng += fg[i]; ne += fe[i];
-    }
-    // exclusive scan of (ng, ne) across the workgroup
-    uint32_t ig = ng, ie = ne;
+    for (int g = 0; g < 4; ++g)
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const uint32_t ag = __shfl_up(ig, o), ae = __shfl_up(ie, o);
-      if (lane >= o) { ig += ag; ie += ae; }
+      for (int i = 0; i < 4; ++i) {
+        const int64_t j = s0 + g * 1024 + 4 * threadIdx.x + i;
+        f[g][i] = v[j < c1 ? j : c1 - 1];
+      }
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int64_t j0 = s0 + g * 1024 + 4 * threadIdx.x;
+      bool fg[4], fe[4];
+      uint32_t ng = 0, ne = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool in = j0 + i < c1;
+        const uint32_t key = order_key(f[g][i]);
+        fg[i] = in && key > T;
+        fe[i] = in && key == T;
+        ng += fg[i]; ne += fe[i];
+      }
+      // exclusive scan of (ng, ne) across the workgroup
+      uint32_t ig = ng, ie = ne;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t ag = __shfl_up(ig, o), ae = __shfl_up(ie, o);
+        if (lane >= o) { ig += ag; ie += ae; }
+      }
+      if (lane == 63) { wsum[0][w] = ig; wsum[1][w] = ie; }
+      __syncthreads();
+      uint32_t pg = base_g + ig - ng, pe = base_e + ie - ne;
+      for (int x = 0; x < w; ++x) { pg += wsum[0][x]; pe += wsum[1][x]; }
+      const uint32_t tot_g = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
+      const uint32_t tot_e = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)(j0 + i);
+        pg += fg[i]; pe += fe[i];
+      }
+      base_g += tot_g; base_e += tot_e;
+      __syncthreads();
     }
-    if (lane == 63) { wsum[0][w] = ig; wsum[1][w] = ie; }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// Top-k fast path: one 12-bit histogram pass finds the bin b* that holds the k-th largest key;
+// a second pass counts, per chunk, the slots above that bin and collects the (few) slots inside
+// it as (key, slot) candidates; one workgroup per row then finishes the radix select on the
+// candidates only and turns the counts into chunk offsets for the ordered emit.
+constexpr int kBins12 = 4096;
+constexpr int kCandPerChunk = 512;  // candidates kept per chunk; a chunk with more makes the row be re-read
+constexpr int kMaxChunks = 1024;
+
+struct TopkWs {
+  uint32_t* hist;    // [rows][4096]
+  uint32_t* ncand;   // [rows][1024] candidates found per chunk (may exceed kCandPerChunk: overflow)
+  uint32_t* state;   // [rows][4]: T (after resolve), r_eq / remaining, b*, too-many-candidates flag
+  uint32_t* above;   // [rows][1024] slots above bin b* per chunk
+  uint32_t* coff;    // [rows][1024][2]
+  uint2* cand;       // [rows][1024][kCandPerChunk]
+};
+
+size_t topk_workspace_bytes(int rows) {
+  size_t b = 0;
+  b += align_up((int64_t)rows * kBins12 * 4, 256);
+  b += align_up((int64_t)rows * kMaxChunks * 4, 256);
+  b += align_up((int64_t)rows * 4 * 4, 256);
+  b += align_up((int64_t)rows * 1024 * 4, 256);
+  b += align_up((int64_t)rows * 1024 * 2 * 4, 256);
+  b += align_up((int64_t)rows * kMaxChunks * kCandPerChunk * 8, 256);
+  return b;
+}
+
+static void topk_carve(TopkWs* t, void* ws, int rows) {
+  uint8_t* w = (uint8_t*)ws;
+  t->hist = (uint32_t*)w;  w += align_up((int64_t)rows * kBins12 * 4, 256);
+  t->ncand = (uint32_t*)w; w += align_up((int64_t)rows * kMaxChunks * 4, 256);
+  t->state = (uint32_t*)w; w += align_up((int64_t)rows * 4 * 4, 256);
+  t->above = (uint32_t*)w; w += align_up((int64_t)rows * 1024 * 4, 256);
+  t->coff = (uint32_t*)w;  w += align_up((int64_t)rows * 1024 * 2 * 4, 256);
+  t->cand = (uint2*)w;
+}
+
+__global__ void tk_zero(uint32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// exclusive prefix sum of one value per thread over a 256-thread workgroup
+__device__ __forceinline__ uint32_t block_scan_excl_256(uint32_t v, uint32_t* wsum /*[4]*/) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t a = __shfl_up(inc, o);
+    if (lane >= o) inc += a;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int x = 0; x < w; ++x) base += wsum[x];
+  __syncthreads();
+  return base + inc - v;
+}
+
+// Keys of the 16 slots s0 + x*256 + tid (x = 0..15) of a 4096-slot tile, all loads issued before
+// any use; slots at or past `end` yield valid[x] = false.
+__device__ __forceinline__ void load_tile_keys(const float* __restrict__ v, int64_t s0, int64_t end,
+                                               uint32_t (&key)[16], bool (&valid)[16]) {
+  float f[16];
+#pragma unroll
+  for (int x = 0; x < 16; ++x) {
+    const int64_t j = s0 + x * 256 + threadIdx.x;
+    valid[x] = j < end;
+    f[x] = v[valid[x] ? j : end - 1];
+  }
+#pragma unroll
+  for (int x = 0; x < 16; ++x) key[x] = order_key(f[x]);
+}
+
+// 12-bit histogram of a row's keys.
+__global__ __launch_bounds__(256) void tk_hist(const float* __restrict__ vals, int64_t stride, int64_t chunk,
+                                               int n_kv_heads, SelRows sr, TopkWs t) {
+  __shared__ uint32_t lh[kBins12];
+  const int row = blockIdx.y;
+  const int64_t want = sr.want[row / n_kv_heads];
+  if (want <= 0) return;
+  const int64_t nsel = sr.nsel[row / n_kv_heads];
+  const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  if (c0 >= nsel) return;
+  int64_t c1 = c0 + chunk;
+  if (c1 > nsel) c1 = nsel;
+  for (int i = threadIdx.x; i < kBins12; i += 256) lh[i] = 0;
+  __syncthreads();
+  const float* v = vals + (int64_t)row * stride;
+  for (int64_t s0 = c0; s0 < c1; s0 += 4096) {
+    uint32_t key[16];
+    bool valid[16];
+    load_tile_keys(v, s0, c1, key, valid);
+#pragma unroll
+    for (int x = 0; x < 16; ++x)
+      if (valid[x]) atomicAdd(&lh[key[x] >> 20], 1u);
+  }
+  __syncthreads();
+  uint32_t* gh = t.hist + (int64_t)row * kBins12;
+  for (int i = threadIdx.x; i < kBins12; i += 256) {
+    const uint32_t c = lh[i];
+    if (c) atomicAdd(&gh[i], c);
+  }
+}
+
+// One workgroup per row: locates the bin b* of the `want`-th largest key (bins scanned from the
+// top) and leaves (still-to-take, b*, too-many-candidates flag) in state.
+__global__ __launch_bounds__(256) void tk_findbin(int n_kv_heads, SelRows sr, TopkWs t) {
+  __shared__ uint32_t wsum[4];
+  const int row = blockIdx.x;
+  const int64_t want = sr.want[row / n_kv_heads];
+  if (want <= 0) return;
+  const uint32_t* gh = t.hist + (int64_t)row * kBins12;
+  uint32_t h[16], sum = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { h[i] = gh[kBins12 - 1 - (16 * threadIdx.x + i)]; sum += h[i]; }
+  uint32_t running = block_scan_excl_256(sum, wsum);
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (running < (uint32_t)want && (uint32_t)want <= running + h[i]) {
+      t.state[4 * row + 1] = (uint32_t)want - running;                 // still to take inside the bin
+      t.state[4 * row + 2] = kBins12 - 1 - (16 * threadIdx.x + i);     // b*
+      t.state[4 * row + 3] = 0u;                                       // set by tk_collect on overflow
+    }
+    running += h[i];
+  }
+}
+
+// Second pass over the row.  Every chunk writes, in slot order, the (key, slot) pairs of its slots
+// in bin b* or above into its own list, and counts the ones strictly above the bin.  Lists are
+// per chunk so that no two workgroups ever contend for an append position.
+__global__ __launch_bounds__(256) void tk_collect(const float* __restrict__ vals, int64_t stride, int64_t chunk,
+                                                  int n_kv_heads, SelRows sr, TopkWs t) {
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t pc[64], po[64];
+  __shared__ uint32_t s_total;
+  const int row = blockIdx.y;
+  const int64_t want = sr.want[row / n_kv_heads];
+  if (want <= 0) return;
+  const int64_t nsel = sr.nsel[row / n_kv_heads];
+  const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  const uint32_t bin = t.state[4 * row + 2];
+  uint32_t* ncand = t.ncand + (int64_t)row * kMaxChunks + blockIdx.x;
+  if (c0 >= nsel) {
+    if (threadIdx.x == 0) { t.above[(int64_t)row * 1024 + blockIdx.x] = 0; *ncand = 0; }
+    return;
+  }
+  int64_t c1 = c0 + chunk;
+  if (c1 > nsel) c1 = nsel;
+  const float* v = vals + (int64_t)row * stride;
+  uint2* dst = t.cand + ((int64_t)row * kMaxChunks + blockIdx.x) * kCandPerChunk;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint32_t cnt = 0, base = 0;
+  for (int64_t s0 = c0; s0 < c1; s0 += 4096) {
+    uint32_t key[16];
+    bool valid[16];
+    load_tile_keys(v, s0, c1, key, valid);
+    // slot order inside the tile is (x, wave, lane): one ballot per (x, wave), prefix over the 64 of them
+    uint64_t mask[16];
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      const uint32_t b = key[x] >> 20;
+      cnt += valid[x] && b > bin;
+      mask[x] = __ballot(valid[x] && b >= bin);
+      if (lane == 0) pc[x * 4 + w] = (uint32_t)__popcll(mask[x]);
+    }
     __syncthreads();
-    uint32_t pg = base_g + ig - ng, pe = base_e + ie - ne;
-    for (int x = 0; x < w; ++x) { pg += wsum[0][x]; pe += wsum[1][x]; }
-    const uint32_t tot_g = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
-    const uint32_t tot_e = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+    if (w == 0) {
+      const uint32_t mine = pc[lane];
+      uint32_t inc = mine;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)(j0 + i);
-      pg += fg[i]; pe += fe[i];
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t a2 = __shfl_up(inc, o);
+        if (lane >= o) inc += a2;
+      }
+      po[lane] = inc - mine;
+      if (lane == 63) s_total = inc;
     }
-    base_g += tot_g; base_e += tot_e;
     __syncthreads();
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      if ((mask[x] >> lane) & 1) {
+        const uint32_t at = base + po[x * 4 + w] + (uint32_t)__popcll(mask[x] & ((1ull << lane) - 1));
+        if (at < (uint32_t)kCandPerChunk) dst[at] = uint2{key[x], (uint32_t)(s0 + x * 256 + threadIdx.x)};
+      }
+    }
+    base += s_total;
+    __syncthreads();
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) cnt += __shfl_xor(cnt, o);
+  if (lane == 0) wsum[w] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    t.above[(int64_t)row * 1024 + blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+    *ncand = base;
+    if (base > (uint32_t)kCandPerChunk) t.state[4 * row + 3] = 1u;   // benign race: all writers store 1
+  }
+}
+
+// exclusive prefix sum of one value per thread over a 1024-thread workgroup
+__device__ __forceinline__ uint32_t block_scan_excl_1024(uint32_t v, uint32_t* wsum /*[16]*/) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t a = __shfl_up(inc, o);
+    if (lane >= o) inc += a;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int x = 0; x < w; ++x) base += wsum[x];
+  __syncthreads();
+  return base + inc - v;
+}
+
+// One workgroup per row: finishes the select inside bin b* (two 10-bit passes over the
+// candidates, or over the whole row when there were too many to keep) and builds the chunk
+// offsets of (#key > T, #key == T) for the ordered emit.
+constexpr int kResolveLds = 5120;   // candidates staged in LDS by tk_resolve (40 KiB)
+
+__global__ __launch_bounds__(1024) void tk_resolve(const float* __restrict__ vals, int64_t stride, int64_t chunk,
+                                                   int nchunks, int n_kv_heads, SelRows sr, TopkWs t) {
+  __shared__ uint32_t h[1024], e[1024], wsum[16];
+  __shared__ uint32_t s_prefix, s_rem, s_n;
+  __shared__ uint2 lc[kResolveLds];
+  const int row = blockIdx.x;
+  if (sr.want[row / n_kv_heads] <= 0) return;
+  const int64_t nsel = sr.nsel[row / n_kv_heads];
+  const uint32_t bin = t.state[4 * row + 2];
+  const bool rescan = t.state[4 * row + 3] != 0;
+  const uint2* cand = t.cand + (int64_t)row * kMaxChunks * kCandPerChunk;
+  const uint32_t* ncand = t.ncand + (int64_t)row * kMaxChunks;
+  const float* v = vals + (int64_t)row * stride;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  uint32_t prefix = bin << 20, rem = t.state[4 * row + 1];
+  // Stage the list entries that lie in bin b* into LDS (order is irrelevant here).
+  h[tid] = (!rescan && tid < nchunks) ? ncand[tid] : 0;
+  if (tid == 0) s_n = 0;
+  __syncthreads();
+  bool staged = !rescan;
+  if (!rescan) {
+    for (int c0 = 0; c0 < nchunks; c0 += 64) {          // 16 waves x 4 chunks per sweep, loads first
+      uint2 ent[4][8];
+      uint32_t m[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c = c0 + wv * 4 + u;
+        m[u] = c < nchunks ? h[c] : 0;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+          if (lane + 64 * r < m[u]) ent[u][r] = cand[(int64_t)c * kCandPerChunk + lane + 64 * r];
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+          if (lane + 64 * r < m[u] && (ent[u][r].x >> 20) == bin) {
+            const uint32_t at = atomicAdd(&s_n, 1u);
+            if (at < (uint32_t)kResolveLds) lc[at] = ent[u][r];
+          }
+    }
+    __syncthreads();
+    staged = s_n <= (uint32_t)kResolveLds;
+  }
+  const uint32_t nst = s_n;
+  __syncthreads();
+  // visit(f): calls f(key, slot) for every slot of the row whose key lies in bin b*
+  auto visit = [&](auto&& f) {
+    if (staged) {
+      for (uint32_t i = tid; i < nst; i += 1024) f(lc[i].x, lc[i].y);
+    } else if (!rescan) {
+      for (int c = wv; c < nchunks; c += 16) {
+        const uint32_t m = ncand[c];
+        for (uint32_t i = lane; i < m; i += 64) {
+          const uint2 e2 = cand[(int64_t)c * kCandPerChunk + i];
+          if ((e2.x >> 20) == bin) f(e2.x, e2.y);
+        }
+      }
+    } else {
+      for (int64_t i = tid; i < nsel; i += 1024) {
+        const uint32_t key = order_key(v[i]);
+        if ((key >> 20) == bin) f(key, (uint32_t)i);
+      }
+    }
+  };
+  for (int pass = 0; pass < 2; ++pass) {
+    const int shift = pass == 0 ? 10 : 0;
+    h[tid] = 0;
+    __syncthreads();
+    visit([&](uint32_t key, uint32_t) {
+      if ((key >> (shift + 10)) == (prefix >> (shift + 10))) atomicAdd(&h[(key >> shift) & 1023u], 1u);
+    });
+    __syncthreads();
+    const uint32_t mine = h[1023 - tid];                    // thread tid owns bin 1023 - tid
+    const uint32_t running = block_scan_excl_1024(mine, wsum);
+    if (running < rem && rem <= running + mine) {
+      s_prefix = prefix | ((uint32_t)(1023 - tid) << shift);
+      s_rem = rem - running;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    rem = s_rem;
+    __syncthreads();
+  }
+  const uint32_t T = prefix;
+  h[tid] = 0;
+  e[tid] = 0;
+  __syncthreads();
+  visit([&](uint32_t key, uint32_t slot) {
+    if (key > T) atomicAdd(&h[slot / chunk], 1u);
+    else if (key == T) atomicAdd(&e[slot / chunk], 1u);
+  });
+  __syncthreads();
+  const uint32_t g = (tid < nchunks) ? t.above[(int64_t)row * 1024 + tid] + h[tid] : 0;
+  const uint32_t q = (tid < nchunks) ? e[tid] : 0;
+  const uint32_t og = block_scan_excl_1024(g, wsum);
+  const uint32_t oe = block_scan_excl_1024(q, wsum);
+  if (tid < nchunks) {
+    t.coff[((int64_t)row * nchunks + tid) * 2] = og;
+    t.coff[((int64_t)row * nchunks + tid) * 2 + 1] = oe;
+  }
+  if (tid == 0) { t.state[4 * row] = T; t.state[4 * row + 1] = rem; }
+}
+
+// Ordered emit from the per-chunk lists (already in slot order): no further pass over the row.
+// Rows whose lists overflowed are left to topk_emit, which re-reads the row.
+__global__ __launch_bounds__(256) void tk_emit_lists(int nchunks, int n_kv_heads, SelRows sr, TopkWs t, int32_t k,
+                                                     int32_t* __restrict__ idx, int32_t* __restrict__ count) {
+  __shared__ uint32_t wsum[2][4];
+  const int row = blockIdx.y;
+  const int64_t want = sr.want[row / n_kv_heads];
+  if (blockIdx.x == 0 && threadIdx.x == 0) count[row] = want > 0 ? (int32_t)want : 0;
+  if (want <= 0) return;
+  if (t.state[4 * row + 3] != 0) return;
+  const uint32_t m = t.ncand[(int64_t)row * kMaxChunks + blockIdx.x];
+  if (m == 0) return;
+  const uint32_t T = t.state[4 * row], req = t.state[4 * row + 1];
+  const uint32_t base_g = t.coff[((int64_t)row * nchunks + blockIdx.x) * 2];
+  const uint32_t base_e = t.coff[((int64_t)row * nchunks + blockIdx.x) * 2 + 1];
+  const uint2* src = t.cand + ((int64_t)row * kMaxChunks + blockIdx.x) * kCandPerChunk;
+  int32_t* out = idx + (int64_t)row * k;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint2 en[2];
+  bool fg[2], fe[2];
+  uint32_t ng = 0, ne = 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const uint32_t p = 2 * threadIdx.x + i;
+    en[i] = src[p < m ? p : m - 1];
+    fg[i] = p < m && en[i].x > T;
+    fe[i] = p < m && en[i].x == T;
+    ng += fg[i]; ne += fe[i];
+  }
+  uint32_t ig = ng, ie = ne;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t ag = __shfl_up(ig, o), ae = __shfl_up(ie, o);
+    if (lane >= o) { ig += ag; ie += ae; }
+  }
+  if (lane == 63) { wsum[0][w] = ig; wsum[1][w] = ie; }
+  __syncthreads();
+  uint32_t pg = base_g + ig - ng, pe = base_e + ie - ne;
+  for (int x = 0; x < w; ++x) { pg += wsum[0][x]; pe += wsum[1][x]; }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)en[i].y;
+    pg += fg[i]; pe += fe[i];
   }
 }
 
@@ -265,14 +651,32 @@ int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t n
     sr.want[b] = nr.n[b] < k ? nr.n[b] : k;
     if (sr.want[b] == 0) sr.want[b] = -1;
   }
-  SelectPlan p;
-  select_plan(&p, ws, L.rows, nmax > 0 ? nmax : 1);
-  if (nmax > 0) {
-    int32_t rc = select_run(p, sel, L.cap, L.rows, L.n_kv_heads, sr, st);
-    if (rc != HCA_OK) return rc;
+  TopkWs t;
+  topk_carve(&t, ws, L.rows);
+  SelectPlan p;   // chunk geometry only
+  {
+    const int64_t n = nmax > 0 ? nmax : 1;
+    int64_t chunk = align_up((n + 1023) / 1024, 1024);
+    if (chunk < 4096) chunk = 4096;
+    p.chunk = chunk;
+    p.nchunks = (int32_t)((n + chunk - 1) / chunk);
   }
   dim3 g((unsigned)p.nchunks, (unsigned)L.rows);
-  topk_emit<<<g, 256, 0, st>>>(sel, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, p.state, p.coff, k, idx, count);
+  if (nmax > 0) {
+    const int64_t nz = (int64_t)L.rows * kBins12;
+    tk_zero<<<(unsigned)((nz + 255) / 256), 256, 0, st>>>(t.hist, nz);
+    // fewer, larger workgroups for the histogram: each flushes its bins with global atomics, and
+    // atomics to one address serialise
+    dim3 gh((unsigned)((p.nchunks + 3) / 4), (unsigned)L.rows);
+    tk_hist<<<gh, 256, 0, st>>>(sel, L.cap, 4 * p.chunk, L.n_kv_heads, sr, t);
+    tk_findbin<<<L.rows, 256, 0, st>>>(L.n_kv_heads, sr, t);
+    tk_collect<<<g, 256, 0, st>>>(sel, L.cap, p.chunk, L.n_kv_heads, sr, t);
+    tk_resolve<<<L.rows, 1024, 0, st>>>(sel, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, t);
+  }
+  if (nmax > 0) tk_emit_lists<<<g, 256, 0, st>>>(p.nchunks, L.n_kv_heads, sr, t, k, idx, count);
+  // rows whose lists overflowed (selection of a large share of the row, or mass ties) are emitted
+  // by re-reading the row; for all other rows this launch returns at once
+  topk_emit<<<g, 256, 0, st>>>(sel, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, t.state, t.coff, k, idx, count, true);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
