@@ -26,7 +26,7 @@ struct Tuning {
   int gather_wgs = 0;      // workgroups of the value gather per row (0 = default)
   int gather_unroll = 4;   // rows in flight per thread
   int score_bpw = 0;       // 1 KiB code blocks per wave (0 = automatic)
-  int score_depth = 4;     // blocks fetched ahead per wave (2, 4 or 8)
+  int score_depth = 8;     // blocks fetched ahead per wave (4 or 8)
 };
 Tuning& tuning();
 

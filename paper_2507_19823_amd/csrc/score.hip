@@ -4,82 +4,153 @@
 
 namespace hca {
 
-// Work split: grid.y = row, grid.x = chunk; a workgroup has 4 waves and each wave scans
-// `bpw` consecutive 1 KiB code blocks.  U blocks are fetched ahead of use to keep several KiB
-// per wave in flight.
+// max of two finite floats (plain v_max_f32: the inputs are never NaN, so no canonicalisation)
+__device__ __forceinline__ float fmax_raw(float a, float b) {
+  float r;
+  asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+  return r;
+}
+
+// max over the four 16-lane rows of a wave (the four query heads of a token), result on every lane
+__device__ __forceinline__ float max_over_heads(float x) {
+  const uint32_t xi = __float_as_uint(x);
+  const auto r16 = __builtin_amdgcn_permlane16_swap(xi, xi, false, false);   // rows {0,1} and {2,3}
+  const float m = fmax_raw(__uint_as_float(r16[0]), __uint_as_float(r16[1]));
+  const uint32_t mi = __float_as_uint(m);
+  const auto r32 = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);   // halves
+  return fmax_raw(__uint_as_float(r32[0]), __uint_as_float(r32[1]));
+}
+
+// 16-byte load with the non-temporal hint: the code stream is read once per decode step and
+// should not displace anything in the caches.
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+  const v4i v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p));
+  return uint4{(uint32_t)v.x, (uint32_t)v.y, (uint32_t)v.z, (uint32_t)v.w};
+}
+
+// All-gather over the four 16-lane rows of a wave: returns, on every lane, the values that the
+// lanes of the same column hold in rows 0..3.
+__device__ __forceinline__ uint4 allgather_rows(uint32_t v) {
+  const auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);        // [r0 r0 r2 r2], [r1 r1 r3 r3]
+  const auto b = __builtin_amdgcn_permlane32_swap(a[0], a[0], false, false);  // r0 everywhere, r2 everywhere
+  const auto c = __builtin_amdgcn_permlane32_swap(a[1], a[1], false, false);  // r1 everywhere, r3 everywhere
+  return uint4{b[0], c[0], b[1], c[1]};
+}
+
+// Work split: grid.y = row, grid.x = chunk; a workgroup has 4 waves and each wave scans `bpw`
+// consecutive 1 KiB code blocks, U at a time: U code loads (16 B per lane, the lane's own MFMA
+// operand bytes) and U meta loads (4 B per lane, then an all-gather over the four lanes of a
+// token) are issued before the first block is scored, and the selection scores of four 16-token
+// tiles leave in one 256-byte store.  Block indices are wave-uniform (scalar registers).
 template <int BITS, bool WRITE_Z, int U>
 __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __restrict__ kcache,
                                                     const uint16_t* __restrict__ q, NRes nr, int bpw,
                                                     float* __restrict__ sel, float* __restrict__ z) {
+  static_assert(U % 4 == 0, "stores are batched four tiles at a time");
   __shared__ QShared sh;
   const int row = blockIdx.y;
   const int64_t n = nr.n[row / L.n_kv_heads];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int64_t nblocks = (n + L.tpb - 1) / L.tpb;
-  const int64_t wave_first = ((int64_t)blockIdx.x * 4 + w) * bpw;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nblocks = (int)((n + L.tpb - 1) / L.tpb);
   if ((int64_t)blockIdx.x * 4 * bpw >= nblocks) return;  // whole workgroup past the end
-  load_query(q, row, L.gqa, L.group, &sh);
-  QOperand<BITS> op;
-  build_operand<BITS>(&sh, &op);
-  int64_t wave_end = wave_first + bpw;
+  const int wave_first = (blockIdx.x * 4 + w) * bpw;
+  int wave_end = wave_first + bpw;
   if (wave_end > nblocks) wave_end = nblocks;
+  if (wave_end < wave_first) wave_end = wave_first;
 
-  const uint4* cbase = reinterpret_cast<const uint4*>(kcache + (int64_t)row * L.codes_row_bytes()) + lane;
-  const uint8_t* mbase = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
+  QOperand<BITS> op;                          // filled in after the first loads are in flight
   const int t = lane & 15, hd = lane >> 4;
+  const uint4* cptr = reinterpret_cast<const uint4*>(kcache + (int64_t)row * L.codes_row_bytes()) + lane;
+  // this lane's dword of a 256-byte meta block: 4-bit: dword hd of token t (16 B per token);
+  // 2-bit: dword hd&1 of token 16*(hd>>1) + t (8 B per token)
+  const uint32_t* mptr = reinterpret_cast<const uint32_t*>(kcache + L.meta_off + (int64_t)row * L.meta_row_bytes()) +
+                         (BITS == 4 ? 4 * t + hd : 2 * (16 * (hd >> 1) + t) + (hd & 1));
   float* selrow = sel + (int64_t)row * L.cap;
-  float* zrow = WRITE_Z ? z + ((int64_t)row * L.gqa + hd) * L.cap : nullptr;
+  float* zrow = WRITE_Z ? z + ((int64_t)row * L.gqa + hd) * L.cap + t : nullptr;
+  const bool head_live = hd < L.gqa;
+  const int ntok = (int)n;
 
-  for (int64_t b0 = wave_first; b0 < wave_end; b0 += U) {
-    uint4 wv[U];
-    uint4 mv[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      int64_t b = b0 + u;
-      if (b >= wave_end) b = wave_end - 1;   // clamp: reload a valid block, result discarded
-      wv[u] = cbase[b * 64];
-      if (BITS == 4) {
-        mv[u] = *reinterpret_cast<const uint4*>(mbase + b * kMetaBytes + t * 16);
-      } else {                               // tokens t (tile 0) and 16+t (tile 1)
-        const uint2 m0 = *reinterpret_cast<const uint2*>(mbase + b * kMetaBytes + t * 8);
-        const uint2 m1 = *reinterpret_cast<const uint2*>(mbase + b * kMetaBytes + (16 + t) * 8);
-        mv[u] = uint4{m0.x, m0.y, m1.x, m1.y};
+  // scores block b; returns the per-token max over heads of its tile(s) (on every lane)
+  auto score_one = [&](int b, uint4 wv, uint32_t mword, float& best0, float& best1) {
+    const uint4 mv = allgather_rows(mword);
+    if constexpr (BITS == 4) {
+      const float zv = score_block4(op, wv, mv);
+      best0 = max_over_heads(head_live ? zv : -INFINITY);
+      best1 = best0;
+      if (WRITE_Z && head_live && b * 16 + t < ntok) zrow[b * 16] = zv;
+    } else {
+      const float z0 = score_tile2(op, wv.x, wv.y, uint2{mv.x, mv.y});
+      const float z1 = score_tile2(op, wv.z, wv.w, uint2{mv.z, mv.w});
+      best0 = max_over_heads(head_live ? z0 : -INFINITY);
+      best1 = max_over_heads(head_live ? z1 : -INFINITY);
+      if (WRITE_Z && head_live) {
+        if (b * 32 + t < ntok) zrow[b * 32] = z0;
+        if (b * 32 + 16 + t < ntok) zrow[b * 32 + 16] = z1;
       }
     }
+  };
+  // the lane in row hd stores tile hd of four consecutive tiles starting at token tok0
+  auto store4 = [&](int tok0, float v0, float v1, float v2, float v3) {
+    const float v = hd == 0 ? v0 : (hd == 1 ? v1 : (hd == 2 ? v2 : v3));
+    const int tok = tok0 + lane;                          // 16*hd + t == lane
+    if (tok < ntok) selrow[tok] = v;
+  };
+
+  // Software pipeline over groups of U blocks: the loads of group g+1 are issued before group g is
+  // scored and stored.  Loads and stores retire through one in-order counter, so a wait for a load
+  // issued after a store would also wait for that store's acknowledgement; issuing the next loads
+  // first keeps every store younger than the loads the wave waits for.
+  auto fetch = [&](int g0, uint4 (&wv)[U], uint32_t (&mw)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t b = b0 + u;
-      if (b >= wave_end) break;
-      if constexpr (BITS == 4) {
-        const float zv = score_block4(op, wv[u], mv[u]);
-        float best = (hd < L.gqa) ? zv : -INFINITY;
-        best = fmaxf(best, __shfl_xor(best, 16));
-        best = fmaxf(best, __shfl_xor(best, 32));
-        const int64_t tok = b * 16 + t;
-        if (tok < n) {
-          if (hd == 0) selrow[tok] = best;
-          if (WRITE_Z && hd < L.gqa) zrow[tok] = zv;
-        }
-      } else {
-        const QOperand<2>& o2 = op;
-        const float z0 = score_tile2(o2, wv[u].x, wv[u].y, uint2{mv[u].x, mv[u].y});
-        const float z1 = score_tile2(o2, wv[u].z, wv[u].w, uint2{mv[u].z, mv[u].w});
-        float b0v = (hd < L.gqa) ? z0 : -INFINITY;
-        float b1v = (hd < L.gqa) ? z1 : -INFINITY;
-        b0v = fmaxf(b0v, __shfl_xor(b0v, 16));
-        b1v = fmaxf(b1v, __shfl_xor(b1v, 16));
-        b0v = fmaxf(b0v, __shfl_xor(b0v, 32));
-        b1v = fmaxf(b1v, __shfl_xor(b1v, 32));
-        const int64_t tok0 = b * 32 + t, tok1 = tok0 + 16;
-        if (tok0 < n) {
-          if (hd == 0) selrow[tok0] = b0v;
-          if (WRITE_Z && hd < L.gqa) zrow[tok0] = z0;
-        }
-        if (tok1 < n) {
-          if (hd == 0) selrow[tok1] = b1v;
-          if (WRITE_Z && hd < L.gqa) zrow[tok1] = z1;
-        }
-      }
+      wv[u] = load_stream16(&cptr[(int64_t)(g0 + u) * 64]);
+      mw[u] = __builtin_nontemporal_load(&mptr[(int64_t)(g0 + u) * 64]);
+    }
+  };
+  auto consume = [&](int g0, const uint4 (&wv)[U], const uint32_t (&mw)[U]) {
+    float lo[U], hi[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) score_one(g0 + u, wv[u], mw[u], lo[u], hi[u]);
+    if constexpr (BITS == 4) {
+#pragma unroll
+      for (int u = 0; u < U; u += 4) store4((g0 + u) * 16, lo[u], lo[u + 1], lo[u + 2], lo[u + 3]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < U; u += 2) store4((g0 + u) * 32, lo[u], hi[u], lo[u + 1], hi[u + 1]);
+    }
+  };
+  int b0 = wave_first;
+  const int ngroups = (wave_end - wave_first) / U;
+  uint4 wa[U], wb[U];
+  uint32_t ma[U], mb[U];
+  if (ngroups > 0) fetch(b0, wa, ma);        // first loads go out before the query is prepared
+  load_query(q, row, L.gqa, L.group, &sh);
+  build_operand<BITS>(&sh, &op);
+  if (ngroups > 0) {
+    int g = 0;
+    for (; g + 2 <= ngroups; g += 2) {
+      fetch(b0 + U, wb, mb);
+      consume(b0, wa, ma);
+      if (g + 2 < ngroups) fetch(b0 + 2 * U, wa, ma);
+      consume(b0 + U, wb, mb);
+      b0 += 2 * U;
+    }
+    if (g < ngroups) {          // odd group count: the last group is already in wa / ma
+      consume(b0, wa, ma);
+      b0 += U;
+    }
+  }
+  for (; b0 < wave_end; ++b0) {              // tail: one block at a time
+    const uint4 wv = load_stream16(&cptr[(int64_t)b0 * 64]);
+    const uint32_t mw = __builtin_nontemporal_load(&mptr[(int64_t)b0 * 64]);
+    float lo, hi;
+    score_one(b0, wv, mw, lo, hi);
+    if constexpr (BITS == 4) {
+      if (hd == 0 && b0 * 16 + t < ntok) selrow[b0 * 16 + t] = lo;
+    } else {
+      if (hd == 0 && b0 * 32 + t < ntok) selrow[b0 * 32 + t] = lo;
+      if (hd == 1 && b0 * 32 + 16 + t < ntok) selrow[b0 * 32 + 16 + t] = hi;
     }
   }
 }
@@ -93,7 +164,7 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
   const Tuning& tn = tuning();
   int64_t bpw = total / (256 * 4 * 16);
   if (bpw < 4) bpw = 4;
-  if (bpw > 32) bpw = 32;
+  if (bpw > 16) bpw = 16;
   if (tn.score_bpw > 0) bpw = tn.score_bpw;
   dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
   const uint8_t* kc = (const uint8_t*)kcache;
@@ -102,8 +173,7 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
 #define HCA_SCORE_U(B, Z)                                  \
   do {                                                     \
     if (tn.score_depth >= 8) HCA_SCORE(B, Z, 8);           \
-    else if (tn.score_depth >= 4) HCA_SCORE(B, Z, 4);      \
-    else HCA_SCORE(B, Z, 2);                               \
+    else HCA_SCORE(B, Z, 4);                               \
   } while (0)
   if (L.bits == 4) {
     if (z_opt) HCA_SCORE_U(4, true); else HCA_SCORE_U(4, false);
