@@ -175,6 +175,61 @@ class Model:
             self.attend_evict(prev, t, main, pp)
 
 
+def per_layer_latency(cfg, main, side, link_peak, iters=8):
+    """One layer of BASELINE config `cfg`, decode steps issued back to back on one stream with no
+    overlap between layers: time from query ready to y ready (quantise-append, scan, top-k, gather,
+    attend).  For config 5 the cache is first evicted to its 50% cap, as the config says."""
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    w = S.CONFIGS[cfg]
+    warm = 3
+    m = Model(w, 1, 0, iters + warm)
+    m.build(1)
+    m.make_steps(iters + warm)
+    t = 0
+    for _ in range(2):
+        m.decode_step(t, main, side, overlap=False)
+        t += 1
+    resident = w.n + 2
+    if cfg == 5:
+        B.hca_evict(m.shape, m.kcache[0], m.acc[0], m.pos[0], m.n[0], w.evict_keep, 2, None, m.ws_main, main)
+        m.n[0] = [w.evict_keep] * w.batch
+        resident = w.evict_keep
+    m.decode_step(t, main, side, overlap=False)
+    t += 1
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    sc = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))] for _ in range(iters)]
+    for i in range(iters):
+        ev[i][0].record(main)
+        m.decode_step(t + i, main, side, overlap=False, events=sc[i])
+        ev[i][1].record(main)
+    torch.cuda.synchronize()
+    lat = sorted(a.elapsed_time(b) for a, b in ev)[iters // 2]
+    scan = sorted(x[0][0].elapsed_time(x[0][1]) for x in sc)[iters // 2]
+    code_bytes = 128 * w.bits // 8 + (128 // w.group) * 4
+    scan_bytes = w.batch * w.n_kv_heads * (resident + iters // 2) * (code_bytes + 4)
+    # the gather alone, as the path issues it
+    pipe = m.pipe[0]
+    g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    g0.record(main)
+    for _ in range(iters):
+        m.gather(0, main, pipe)
+    g1.record(main)
+    torch.cuda.synchronize()
+    gms = g0.elapsed_time(g1) / iters
+    gbytes = w.batch * w.n_kv_heads * w.k * 256
+    out = {"workload": w.name, "resident_tokens": resident, "ms_per_layer": lat,
+           "key_scan_ms": scan, "key_scan_GBs": scan_bytes / scan / 1e6, "key_scan_frac_of_hbm_peak": scan_bytes / scan / 1e6 / HBM_PEAK_GBS,
+           "gather_ms": gms, "gather_GBs": gbytes / gms / 1e6, "gather_frac_of_link_peak": gbytes / gms / 1e6 / link_peak}
+    del m
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()
+    return out
+
+
 def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
     """Times the oracle, as it stands, on layer 0 of the same workload: consecutive decode steps
     (append one token, score every resident token, top-k, attend with accumulated-score update)
@@ -235,6 +290,7 @@ def main():
     ap.add_argument("--evict-every", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="single stream, no gather/score overlap")
+    ap.add_argument("--no-latency", action="store_true", help="skip the per-layer latency probes at 128K / 1M / 4M")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -263,6 +319,12 @@ def main():
     torch.cuda.synchronize()
     link_peak = 16 * (1 << 28) / (time.perf_counter() - t0) / 1e9
     del dbig
+
+    latency = {}
+    if not args.no_latency:
+        for name, c in (("128K", 3), ("1M", 4), ("4M", 5)):
+            latency[name] = per_layer_latency(c, main_s[0], gath_s[0], link_peak)
+            log(f"latency probe {name}: {latency[name]['ms_per_layer']:.3f} ms per layer")
 
     total_steps = args.steps + args.warmup
     model = Model(w, L, args.evict_every, total_steps)
@@ -310,7 +372,8 @@ def main():
                    "kv_heads": w.n_kv_heads, "key_bits": w.bits, "group": w.group, "top_k": w.k,
                    "evict_every": args.evict_every, "values": "context rows in pinned host fp16, appended rows in an HBM slice",
                    "physical_value_layers": phys, "overlap": not args.no_overlap},
-        "per_layer_latency_ms": ms_per_step / L,
+        "pipelined_ms_per_layer": ms_per_step / L,
+        "per_layer_decode_latency": latency,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,

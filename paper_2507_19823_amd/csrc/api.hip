@@ -89,7 +89,7 @@ size_t hca_workspace_bytes(const hca_shape* shape, int64_t k_max, int64_t m_max)
   if (m_max < 1) m_max = 1;
   if (k_max > L.cap) k_max = L.cap;
   if (m_max > L.cap) m_max = L.cap;
-  size_t a = topk_workspace_bytes(L.rows);
+  size_t a = topk_workspace_bytes(L.rows, L.cap);
   size_t b = attend_workspace_bytes(L, k_max);
   size_t c = evict_workspace_bytes(L, m_max);
   size_t m = a > b ? a : b;

@@ -49,7 +49,7 @@ struct SelRows {     // per-sequence selection parameters, by value
   int64_t want[kMaxBatch];   // how many to select among them (0 < want <= nsel, or 0 = skip row)
 };
 size_t select_workspace_bytes(int rows, int64_t nmax);
-size_t topk_workspace_bytes(int rows);
+size_t topk_workspace_bytes(int rows, int64_t cap);
 void select_plan(SelectPlan* p, void* ws, int rows, int64_t nmax);
 // Enqueues the selection passes over `vals` ([rows][stride] fp32).  Afterwards, for row r:
 // state[r][0] = threshold key T, state[r][1] = number of slots with key == T to take (lowest first),

@@ -197,107 +197,52 @@ int32_t select_run(const SelectPlan& p, const float* vals, int64_t stride, int r
   return HCA_OK;
 }
 
-// Ordered emit for top-k: each workgroup walks its chunk in slot order, 1024 slots per step
-// (4 consecutive slots per thread), and writes the selected slots at their final positions.
-__global__ __launch_bounds__(256) void topk_emit(const float* __restrict__ vals, int64_t stride, int64_t chunk,
-                                                 int nchunks, int n_kv_heads, SelRows sr,
-                                                 const uint32_t* __restrict__ state, const uint32_t* __restrict__ coff,
-                                                 int32_t k, int32_t* __restrict__ idx, int32_t* __restrict__ count,
-                                                 bool only_flagged) {
-  __shared__ uint32_t wsum[2][4];
-  const int row = blockIdx.y;
-  const int64_t want = sr.want[row / n_kv_heads];
-  if (blockIdx.x == 0 && threadIdx.x == 0) count[row] = want > 0 ? (int32_t)want : 0;
-  if (want <= 0) return;
-  if (only_flagged && state[4 * row + 3] == 0) return;   // this row was emitted from its lists
-  const int64_t nsel = sr.nsel[row / n_kv_heads];
-  const int64_t c0 = (int64_t)blockIdx.x * chunk;
-  if (c0 >= nsel) return;
-  int64_t c1 = c0 + chunk;
-  if (c1 > nsel) c1 = nsel;
-  const uint32_t T = state[4 * row], req = state[4 * row + 1];
-  uint32_t base_g = coff[((int64_t)row * nchunks + blockIdx.x) * 2];
-  uint32_t base_e = coff[((int64_t)row * nchunks + blockIdx.x) * 2 + 1];
-  const float* v = vals + (int64_t)row * stride;
-  int32_t* out = idx + (int64_t)row * k;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  for (int64_t s0 = c0; s0 < c1; s0 += 4096) {
-    // four sub-tiles of 1024 slots, 4 consecutive slots per thread in each; loads first
-    float f[4][4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int64_t j = s0 + g * 1024 + 4 * threadIdx.x + i;
-        f[g][i] = v[j < c1 ? j : c1 - 1];
-      }
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int64_t j0 = s0 + g * 1024 + 4 * threadIdx.x;
-      bool fg[4], fe[4];
-      uint32_t ng = 0, ne = 0;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bool in = j0 + i < c1;
-        const uint32_t key = order_key(f[g][i]);
-        fg[i] = in && key > T;
-        fe[i] = in && key == T;
-        ng += fg[i]; ne += fe[i];
-      }
-      // exclusive scan of (ng, ne) across the workgroup
-      uint32_t ig = ng, ie = ne;
-#pragma unroll
-      for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t ag = __shfl_up(ig, o), ae = __shfl_up(ie, o);
-        if (lane >= o) { ig += ag; ie += ae; }
-      }
-      if (lane == 63) { wsum[0][w] = ig; wsum[1][w] = ie; }
-      __syncthreads();
-      uint32_t pg = base_g + ig - ng, pe = base_e + ie - ne;
-      for (int x = 0; x < w; ++x) { pg += wsum[0][x]; pe += wsum[1][x]; }
-      const uint32_t tot_g = wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
-      const uint32_t tot_e = wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)(j0 + i);
-        pg += fg[i]; pe += fe[i];
-      }
-      base_g += tot_g; base_e += tot_e;
-      __syncthreads();
-    }
-  }
-}
-
 // ---------------------------------------------------------------------------------------
 // Top-k fast path: one 12-bit histogram pass finds the bin b* that holds the k-th largest key;
 // a second pass counts, per chunk, the slots above that bin and collects the (few) slots inside
 // it as (key, slot) candidates; one workgroup per row then finishes the radix select on the
 // candidates only and turns the counts into chunk offsets for the ordered emit.
 constexpr int kBins12 = 4096;
-constexpr int kCandPerChunk = 512;  // candidates kept per chunk; a chunk with more makes the row be re-read
 constexpr int kMaxChunks = 1024;
 
 struct TopkWs {
-  uint32_t* hist;    // [rows][4096]
-  uint32_t* ncand;   // [rows][1024] candidates found per chunk (may exceed kCandPerChunk: overflow)
-  uint32_t* state;   // [rows][4]: T (after resolve), r_eq / remaining, b*, too-many-candidates flag
-  uint32_t* above;   // [rows][1024] slots above bin b* per chunk
-  uint32_t* coff;    // [rows][1024][2]
-  uint2* cand;       // [rows][1024][kCandPerChunk]
+  uint32_t* hist;      // [rows][4096]
+  uint32_t* ncand;     // [rows][1024] entries in each chunk's list
+  uint32_t* state;     // [rows][4]: T (after resolve), r_eq / still-to-take, b*, unused
+  uint32_t* above;     // [rows][1024] slots strictly above bin b* per chunk
+  uint32_t* coff;      // [rows][1024][2]
+  uint2* cand;         // [rows][row_entries]: chunk c owns entries [c*chunk, (c+1)*chunk)
+  int64_t row_entries;
 };
 
-size_t topk_workspace_bytes(int rows) {
+// chunk geometry for a row of n slots: at most 1024 chunks, each a multiple of 1024 slots, >= 4096
+static void chunk_geometry(int64_t n, int64_t* chunk, int32_t* nchunks) {
+  if (n < 1) n = 1;
+  int64_t c = align_up((n + 1023) / 1024, 1024);
+  if (c < 4096) c = 4096;
+  *chunk = c;
+  *nchunks = (int32_t)((n + c - 1) / c);
+}
+
+static int64_t list_entries_per_row(int64_t cap) {
+  int64_t chunk;
+  int32_t nchunks;
+  chunk_geometry(cap, &chunk, &nchunks);
+  return align_up(cap, 1024) + 2 * chunk;     // nchunks(n) * chunk(n) < n + chunk(n) <= this, for any n <= cap
+}
+
+size_t topk_workspace_bytes(int rows, int64_t cap) {
   size_t b = 0;
   b += align_up((int64_t)rows * kBins12 * 4, 256);
   b += align_up((int64_t)rows * kMaxChunks * 4, 256);
   b += align_up((int64_t)rows * 4 * 4, 256);
   b += align_up((int64_t)rows * 1024 * 4, 256);
   b += align_up((int64_t)rows * 1024 * 2 * 4, 256);
-  b += align_up((int64_t)rows * kMaxChunks * kCandPerChunk * 8, 256);
+  b += align_up((int64_t)rows * list_entries_per_row(cap) * 8, 256);
   return b;
 }
 
-static void topk_carve(TopkWs* t, void* ws, int rows) {
+static void topk_carve(TopkWs* t, void* ws, int rows, int64_t cap) {
   uint8_t* w = (uint8_t*)ws;
   t->hist = (uint32_t*)w;  w += align_up((int64_t)rows * kBins12 * 4, 256);
   t->ncand = (uint32_t*)w; w += align_up((int64_t)rows * kMaxChunks * 4, 256);
@@ -305,6 +250,7 @@ static void topk_carve(TopkWs* t, void* ws, int rows) {
   t->above = (uint32_t*)w; w += align_up((int64_t)rows * 1024 * 4, 256);
   t->coff = (uint32_t*)w;  w += align_up((int64_t)rows * 1024 * 2 * 4, 256);
   t->cand = (uint2*)w;
+  t->row_entries = list_entries_per_row(cap);
 }
 
 __global__ void tk_zero(uint32_t* p, int64_t n) {
@@ -392,15 +338,15 @@ __global__ __launch_bounds__(256) void tk_findbin(int n_kv_heads, SelRows sr, To
     if (running < (uint32_t)want && (uint32_t)want <= running + h[i]) {
       t.state[4 * row + 1] = (uint32_t)want - running;                 // still to take inside the bin
       t.state[4 * row + 2] = kBins12 - 1 - (16 * threadIdx.x + i);     // b*
-      t.state[4 * row + 3] = 0u;                                       // set by tk_collect on overflow
     }
     running += h[i];
   }
 }
 
 // Second pass over the row.  Every chunk writes, in slot order, the (key, slot) pairs of its slots
-// in bin b* or above into its own list, and counts the ones strictly above the bin.  Lists are
-// per chunk so that no two workgroups ever contend for an append position.
+// in bin b* or above into its own list (room for the whole chunk, so it cannot overflow), and
+// counts the ones strictly above the bin.  Lists are per chunk so that no two workgroups ever
+// contend for an append position.
 __global__ __launch_bounds__(256) void tk_collect(const float* __restrict__ vals, int64_t stride, int64_t chunk,
                                                   int n_kv_heads, SelRows sr, TopkWs t) {
   __shared__ uint32_t wsum[4];
@@ -420,7 +366,7 @@ __global__ __launch_bounds__(256) void tk_collect(const float* __restrict__ vals
   int64_t c1 = c0 + chunk;
   if (c1 > nsel) c1 = nsel;
   const float* v = vals + (int64_t)row * stride;
-  uint2* dst = t.cand + ((int64_t)row * kMaxChunks + blockIdx.x) * kCandPerChunk;
+  uint2* dst = t.cand + (int64_t)row * t.row_entries + (int64_t)blockIdx.x * chunk;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   uint32_t cnt = 0, base = 0;
   for (int64_t s0 = c0; s0 < c1; s0 += 4096) {
@@ -453,7 +399,7 @@ __global__ __launch_bounds__(256) void tk_collect(const float* __restrict__ vals
     for (int x = 0; x < 16; ++x) {
       if ((mask[x] >> lane) & 1) {
         const uint32_t at = base + po[x * 4 + w] + (uint32_t)__popcll(mask[x] & ((1ull << lane) - 1));
-        if (at < (uint32_t)kCandPerChunk) dst[at] = uint2{key[x], (uint32_t)(s0 + x * 256 + threadIdx.x)};
+        dst[at] = uint2{key[x], (uint32_t)(s0 + x * 256 + threadIdx.x)};
       }
     }
     base += s_total;
@@ -466,7 +412,6 @@ __global__ __launch_bounds__(256) void tk_collect(const float* __restrict__ vals
   if (threadIdx.x == 0) {
     t.above[(int64_t)row * 1024 + blockIdx.x] = wsum[0] + wsum[1] + wsum[2] + wsum[3];
     *ncand = base;
-    if (base > (uint32_t)kCandPerChunk) t.state[4 * row + 3] = 1u;   // benign race: all writers store 1
   }
 }
 
@@ -492,69 +437,61 @@ __device__ __forceinline__ uint32_t block_scan_excl_1024(uint32_t v, uint32_t* w
 // offsets of (#key > T, #key == T) for the ordered emit.
 constexpr int kResolveLds = 5120;   // candidates staged in LDS by tk_resolve (40 KiB)
 
-__global__ __launch_bounds__(1024) void tk_resolve(const float* __restrict__ vals, int64_t stride, int64_t chunk,
-                                                   int nchunks, int n_kv_heads, SelRows sr, TopkWs t) {
-  __shared__ uint32_t h[1024], e[1024], wsum[16];
+// One workgroup per row: finishes the select inside bin b* (two 10-bit passes over the list
+// entries that lie in that bin) and builds the chunk offsets of (#key > T, #key == T) for the
+// ordered emit.
+__global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr, TopkWs t) {
+  __shared__ uint32_t h[1024], e[1024], cnt[1024], wsum[16];
   __shared__ uint32_t s_prefix, s_rem, s_n;
   __shared__ uint2 lc[kResolveLds];
   const int row = blockIdx.x;
   if (sr.want[row / n_kv_heads] <= 0) return;
-  const int64_t nsel = sr.nsel[row / n_kv_heads];
   const uint32_t bin = t.state[4 * row + 2];
-  const bool rescan = t.state[4 * row + 3] != 0;
-  const uint2* cand = t.cand + (int64_t)row * kMaxChunks * kCandPerChunk;
-  const uint32_t* ncand = t.ncand + (int64_t)row * kMaxChunks;
-  const float* v = vals + (int64_t)row * stride;
+  const uint2* cand = t.cand + (int64_t)row * t.row_entries;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   uint32_t prefix = bin << 20, rem = t.state[4 * row + 1];
-  // Stage the list entries that lie in bin b* into LDS (order is irrelevant here).
-  h[tid] = (!rescan && tid < nchunks) ? ncand[tid] : 0;
+  cnt[tid] = tid < nchunks ? t.ncand[(int64_t)row * kMaxChunks + tid] : 0;
   if (tid == 0) s_n = 0;
   __syncthreads();
-  bool staged = !rescan;
-  if (!rescan) {
-    for (int c0 = 0; c0 < nchunks; c0 += 64) {          // 16 waves x 4 chunks per sweep, loads first
+  // sweep(f): f(key, slot) for every list entry of the row that lies in bin b*.  Each wave takes 4
+  // chunks per step and issues up to 8 loads per chunk before using any of them.
+  auto sweep = [&](auto&& f) {
+    for (int c0 = 0; c0 < nchunks; c0 += 64) {
       uint2 ent[4][8];
       uint32_t m[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int c = c0 + wv * 4 + u;
-        m[u] = c < nchunks ? h[c] : 0;
+        m[u] = c < nchunks ? cnt[c] : 0;
 #pragma unroll
         for (int r = 0; r < 8; ++r)
-          if (lane + 64 * r < m[u]) ent[u][r] = cand[(int64_t)c * kCandPerChunk + lane + 64 * r];
+          if (lane + 64 * r < m[u]) ent[u][r] = cand[(int64_t)c * chunk + lane + 64 * r];
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 4; ++u) {
 #pragma unroll
         for (int r = 0; r < 8; ++r)
-          if (lane + 64 * r < m[u] && (ent[u][r].x >> 20) == bin) {
-            const uint32_t at = atomicAdd(&s_n, 1u);
-            if (at < (uint32_t)kResolveLds) lc[at] = ent[u][r];
-          }
+          if (lane + 64 * r < m[u] && (ent[u][r].x >> 20) == bin) f(ent[u][r].x, ent[u][r].y);
+        const int c = c0 + wv * 4 + u;
+        for (uint32_t i = 512 + lane; i < m[u]; i += 64) {      // long lists (clustered heavy hitters)
+          const uint2 x = cand[(int64_t)c * chunk + i];
+          if ((x.x >> 20) == bin) f(x.x, x.y);
+        }
+      }
     }
-    __syncthreads();
-    staged = s_n <= (uint32_t)kResolveLds;
-  }
-  const uint32_t nst = s_n;
+  };
+  sweep([&](uint32_t key, uint32_t slot) {
+    const uint32_t at = atomicAdd(&s_n, 1u);
+    if (at < (uint32_t)kResolveLds) lc[at] = uint2{key, slot};
+  });
   __syncthreads();
-  // visit(f): calls f(key, slot) for every slot of the row whose key lies in bin b*
+  const uint32_t nst = s_n;
+  const bool staged = nst <= (uint32_t)kResolveLds;
   auto visit = [&](auto&& f) {
     if (staged) {
       for (uint32_t i = tid; i < nst; i += 1024) f(lc[i].x, lc[i].y);
-    } else if (!rescan) {
-      for (int c = wv; c < nchunks; c += 16) {
-        const uint32_t m = ncand[c];
-        for (uint32_t i = lane; i < m; i += 64) {
-          const uint2 e2 = cand[(int64_t)c * kCandPerChunk + i];
-          if ((e2.x >> 20) == bin) f(e2.x, e2.y);
-        }
-      }
     } else {
-      for (int64_t i = tid; i < nsel; i += 1024) {
-        const uint32_t key = order_key(v[i]);
-        if ((key >> 20) == bin) f(key, (uint32_t)i);
-      }
+      sweep(f);
     }
   };
   for (int pass = 0; pass < 2; ++pass) {
@@ -597,48 +534,53 @@ __global__ __launch_bounds__(1024) void tk_resolve(const float* __restrict__ val
 }
 
 // Ordered emit from the per-chunk lists (already in slot order): no further pass over the row.
-// Rows whose lists overflowed are left to topk_emit, which re-reads the row.
-__global__ __launch_bounds__(256) void tk_emit_lists(int nchunks, int n_kv_heads, SelRows sr, TopkWs t, int32_t k,
-                                                     int32_t* __restrict__ idx, int32_t* __restrict__ count) {
+//   selected(j) = key_j > T  or  (key_j == T and #{i < j : key_i == T} < r_eq)
+//   position(j) = #{i < j : key_i > T} + min(#{i < j : key_i == T}, r_eq)
+__global__ __launch_bounds__(256) void tk_emit_lists(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr, TopkWs t,
+                                                     int32_t k, int32_t* __restrict__ idx, int32_t* __restrict__ count) {
   __shared__ uint32_t wsum[2][4];
   const int row = blockIdx.y;
   const int64_t want = sr.want[row / n_kv_heads];
   if (blockIdx.x == 0 && threadIdx.x == 0) count[row] = want > 0 ? (int32_t)want : 0;
   if (want <= 0) return;
-  if (t.state[4 * row + 3] != 0) return;
   const uint32_t m = t.ncand[(int64_t)row * kMaxChunks + blockIdx.x];
   if (m == 0) return;
   const uint32_t T = t.state[4 * row], req = t.state[4 * row + 1];
-  const uint32_t base_g = t.coff[((int64_t)row * nchunks + blockIdx.x) * 2];
-  const uint32_t base_e = t.coff[((int64_t)row * nchunks + blockIdx.x) * 2 + 1];
-  const uint2* src = t.cand + ((int64_t)row * kMaxChunks + blockIdx.x) * kCandPerChunk;
+  uint32_t base_g = t.coff[((int64_t)row * nchunks + blockIdx.x) * 2];
+  uint32_t base_e = t.coff[((int64_t)row * nchunks + blockIdx.x) * 2 + 1];
+  const uint2* src = t.cand + (int64_t)row * t.row_entries + (int64_t)blockIdx.x * chunk;
   int32_t* out = idx + (int64_t)row * k;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  uint2 en[2];
-  bool fg[2], fe[2];
-  uint32_t ng = 0, ne = 0;
+  for (uint32_t p0 = 0; p0 < m; p0 += 512) {
+    uint2 en[2];
+    bool fg[2], fe[2];
+    uint32_t ng = 0, ne = 0;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const uint32_t p = 2 * threadIdx.x + i;
-    en[i] = src[p < m ? p : m - 1];
-    fg[i] = p < m && en[i].x > T;
-    fe[i] = p < m && en[i].x == T;
-    ng += fg[i]; ne += fe[i];
-  }
-  uint32_t ig = ng, ie = ne;
+    for (int i = 0; i < 2; ++i) {
+      const uint32_t p = p0 + 2 * threadIdx.x + i;
+      en[i] = src[p < m ? p : m - 1];
+      fg[i] = p < m && en[i].x > T;
+      fe[i] = p < m && en[i].x == T;
+      ng += fg[i]; ne += fe[i];
+    }
+    uint32_t ig = ng, ie = ne;
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint32_t ag = __shfl_up(ig, o), ae = __shfl_up(ie, o);
-    if (lane >= o) { ig += ag; ie += ae; }
-  }
-  if (lane == 63) { wsum[0][w] = ig; wsum[1][w] = ie; }
-  __syncthreads();
-  uint32_t pg = base_g + ig - ng, pe = base_e + ie - ne;
-  for (int x = 0; x < w; ++x) { pg += wsum[0][x]; pe += wsum[1][x]; }
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t ag = __shfl_up(ig, o), ae = __shfl_up(ie, o);
+      if (lane >= o) { ig += ag; ie += ae; }
+    }
+    if (lane == 63) { wsum[0][w] = ig; wsum[1][w] = ie; }
+    __syncthreads();
+    uint32_t pg = base_g + ig - ng, pe = base_e + ie - ne;
+    for (int x = 0; x < w; ++x) { pg += wsum[0][x]; pe += wsum[1][x]; }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)en[i].y;
-    pg += fg[i]; pe += fe[i];
+    for (int i = 0; i < 2; ++i) {
+      if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)en[i].y;
+      pg += fg[i]; pe += fe[i];
+    }
+    base_g += wsum[0][0] + wsum[0][1] + wsum[0][2] + wsum[0][3];
+    base_e += wsum[1][0] + wsum[1][1] + wsum[1][2] + wsum[1][3];
+    __syncthreads();
   }
 }
 
@@ -652,31 +594,23 @@ int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t n
     if (sr.want[b] == 0) sr.want[b] = -1;
   }
   TopkWs t;
-  topk_carve(&t, ws, L.rows);
-  SelectPlan p;   // chunk geometry only
-  {
-    const int64_t n = nmax > 0 ? nmax : 1;
-    int64_t chunk = align_up((n + 1023) / 1024, 1024);
-    if (chunk < 4096) chunk = 4096;
-    p.chunk = chunk;
-    p.nchunks = (int32_t)((n + chunk - 1) / chunk);
-  }
-  dim3 g((unsigned)p.nchunks, (unsigned)L.rows);
+  topk_carve(&t, ws, L.rows, L.cap);
+  int64_t chunk;
+  int32_t nchunks;
+  chunk_geometry(nmax, &chunk, &nchunks);
+  dim3 g((unsigned)nchunks, (unsigned)L.rows);
   if (nmax > 0) {
     const int64_t nz = (int64_t)L.rows * kBins12;
     tk_zero<<<(unsigned)((nz + 255) / 256), 256, 0, st>>>(t.hist, nz);
     // fewer, larger workgroups for the histogram: each flushes its bins with global atomics, and
     // atomics to one address serialise
-    dim3 gh((unsigned)((p.nchunks + 3) / 4), (unsigned)L.rows);
-    tk_hist<<<gh, 256, 0, st>>>(sel, L.cap, 4 * p.chunk, L.n_kv_heads, sr, t);
+    dim3 gh((unsigned)((nchunks + 3) / 4), (unsigned)L.rows);
+    tk_hist<<<gh, 256, 0, st>>>(sel, L.cap, 4 * chunk, L.n_kv_heads, sr, t);
     tk_findbin<<<L.rows, 256, 0, st>>>(L.n_kv_heads, sr, t);
-    tk_collect<<<g, 256, 0, st>>>(sel, L.cap, p.chunk, L.n_kv_heads, sr, t);
-    tk_resolve<<<L.rows, 1024, 0, st>>>(sel, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, t);
+    tk_collect<<<g, 256, 0, st>>>(sel, L.cap, chunk, L.n_kv_heads, sr, t);
+    tk_resolve<<<L.rows, 1024, 0, st>>>(chunk, nchunks, L.n_kv_heads, sr, t);
   }
-  if (nmax > 0) tk_emit_lists<<<g, 256, 0, st>>>(p.nchunks, L.n_kv_heads, sr, t, k, idx, count);
-  // rows whose lists overflowed (selection of a large share of the row, or mass ties) are emitted
-  // by re-reading the row; for all other rows this launch returns at once
-  topk_emit<<<g, 256, 0, st>>>(sel, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, t.state, t.coff, k, idx, count, true);
+  tk_emit_lists<<<g, 256, 0, st>>>(chunk, nchunks, L.n_kv_heads, sr, t, k, idx, count);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
