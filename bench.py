@@ -90,7 +90,7 @@ class Model:
             if vh is not None:
                 vh.copy_(d["values"])
                 self.v_host[l] = vh
-            else:
+            elif phys_value_layers > 0:
                 self.v_host[l] = self.v_host[l % phys_value_layers]   # logical layer shares a physical store
             if l == 0:
                 self.layer0 = {k: (v.cpu() if v is not None and hasattr(v, "cpu") else v) for k, v in d.items()}
@@ -230,6 +230,34 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8):
     return out
 
 
+def scan_only(w, iters):
+    """Key-scan kernel alone on one layer (two cache copies alternate), preceded by a plain 1 GiB
+    device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the counters (profiles/)."""
+    import torch
+    from paper_2507_19823_amd import binding as B
+    m = Model(w, 2, 0, 1)
+    m.build(0)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)                                    # calibration dispatch: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    q = m.layer0["q"].cuda()
+    for i in range(3):
+        B.hca_score_qkeys(m.shape, m.kcache[i & 1], q, m.n[0], m.sel, None, None)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        B.hca_score_qkeys(m.shape, m.kcache[i & 1], q, m.n[0], m.sel, None, None)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    code_bytes = 128 * w.bits // 8 + (128 // w.group) * 4
+    by = w.batch * w.n_kv_heads * w.n * (code_bytes + 4)
+    print(json.dumps({"mode": "scan", "workload": w.name, "ms": ms, "bytes_per_launch": by,
+                      "GBs": by / ms / 1e6, "frac": by / ms / 1e6 / HBM_PEAK_GBS}), flush=True)
+
+
 def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
     """Times the oracle, as it stands, on layer 0 of the same workload: consecutive decode steps
     (append one token, score every resident token, top-k, attend with accumulated-score update)
@@ -291,6 +319,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true", help="single stream, no gather/score overlap")
     ap.add_argument("--no-latency", action="store_true", help="skip the per-layer latency probes at 128K / 1M / 4M")
+    ap.add_argument("--mode", default="step", choices=["step", "scan"],
+                    help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -305,6 +335,8 @@ def main():
 
     w = S.CONFIGS[args.config]
     L = args.layers or w.layers
+    if args.mode == "scan":
+        return scan_only(w, args.steps)
     # host link: peak (one large pinned copy) and the gather as the path issues it
     main_s = [torch.cuda.Stream(), torch.cuda.Stream()]
     gath_s = [torch.cuda.Stream(), torch.cuda.Stream()]
@@ -363,6 +395,12 @@ def main():
     scan_bytes = w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + 4)
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
 
+    traffic = None
+    pmc = os.path.join(ROOT, "profiles", "score_kernel_cfg4_1m_pmc.md")
+    if args.config == 4 and os.path.exists(pmc):     # measured with rocprofv3 --pmc, see that file
+        for line in open(pmc):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = int(line.split(":")[1])
     out = {
         "metric": "context tokens scored/s", "value": value, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -378,7 +416,7 @@ def main():
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,
         "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes},
     }
     if not args.no_cpu_baseline:
