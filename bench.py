@@ -50,16 +50,21 @@ class Model:
         self.v_host = [None] * layers
         self.v_hbm = [torch.zeros(w.batch, w.n_kv_heads, self.vnew, 128, dtype=torch.float16, device=dev)
                       for _ in range(layers)]
-        self.sel = torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev)
+        self.sels = [torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev) for _ in range(3)]
+        self.sel = self.sels[0]
+        self.sel_ev = [dict(score_done=torch.cuda.Event(), sel_free=torch.cuda.Event()) for _ in range(3)]
         self.ws_main = torch.empty(B.hca_workspace_bytes(self.shape, w.k, self.n0), dtype=torch.uint8, device=dev)
+        self.ws_topk = torch.empty(B.hca_workspace_bytes(self.shape, w.k, 1), dtype=torch.uint8, device=dev)
         wsa = B.hca_workspace_bytes(self.shape, w.k, 1)
         self.pipe = []
-        for _ in range(n_pipe):
+        for _ in range(4):
             self.pipe.append(dict(
                 idx=torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev),
                 count=torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev),
                 ws=torch.empty(wsa, dtype=torch.uint8, device=dev),
-                sel_done=torch.cuda.Event(), gather_done=torch.cuda.Event()))
+                sel_done=torch.cuda.Event(), gather_done=torch.cuda.Event(),
+                topk_done=torch.cuda.Event(), pipe_free=torch.cuda.Event()))
+        self.layer_done = [torch.cuda.Event() for _ in range(layers)]
         self.y = torch.zeros(layers, w.batch, w.n_q_heads, 128, dtype=torch.float32, device=dev)
         self.n = [[0] * w.batch for _ in range(layers)]
         self.sm_scale = 1.0 / (128.0 ** 0.5)
@@ -116,6 +121,11 @@ class Model:
 
     def scan_select(self, l, t, st, pipe, ev=None):
         """a1 + a2 + a3 of layer l, decode step t, on stream st."""
+        self.scan(l, t, st, self.sel, ev)
+        self.B.hca_topk(self.shape, self.sel, self.n[l], self.w.k, pipe["idx"], pipe["count"], self.ws_main, st)
+
+    def scan(self, l, t, st, sel, ev=None):
+        """a1 + a2 of layer l, decode step t, on stream st: append the new key, scan the cache."""
         B, w = self.B, self.w
         n = self.n[l]
         B.hca_quantize_keys(self.shape, self.kcache[l], self.k_new[t][l], 1, n, self.acc[l], self.pos[l],
@@ -124,10 +134,9 @@ class Model:
         self.n[l] = n
         if ev is not None:
             ev[0].record(st)
-        B.hca_score_qkeys(self.shape, self.kcache[l], self.q[t][l], n, self.sel, None, None, st)
+        B.hca_score_qkeys(self.shape, self.kcache[l], self.q[t][l], n, sel, None, None, st)
         if ev is not None:
             ev[1].record(st)
-        B.hca_topk(self.shape, self.sel, n, w.k, pipe["idx"], pipe["count"], self.ws_main, st)
 
     def gather(self, l, gst, pipe):
         """host-link half of a4: selected value rows -> staging, on the gather stream."""
@@ -144,6 +153,32 @@ class Model:
             B.hca_evict(self.shape, self.kcache[l], self.acc[l], self.pos[l], self.n[l], self.n0,
                         self.evict_every, None, self.ws_main, st)
             self.n[l] = [min(x, self.n0) for x in self.n[l]]
+
+    def decode_step_staged(self, t, sa, sb, sg, sc, events=None):
+        """One decode step over all layers as a four-stage pipeline across layers, one stream per stage:
+        sa: append + key scan, sb: top-k, sg: host-link gather, sc: attend (+ eviction when due).
+        Layer l's stages follow each other through events; different layers overlap, so the step is
+        paced by its slowest stage (the gather) instead of by the sum of the stages."""
+        B, w = self.B, self.w
+        for l in range(self.L):
+            s3, pipe = self.sel_ev[l % 3], self.pipe[l % 4]
+            sel = self.sels[l % 3]
+            sa.wait_event(s3["sel_free"])            # top-k of the previous user of this score buffer
+            sa.wait_event(self.layer_done[l])        # this layer's attend / evict of the previous step
+            self.scan(l, t, sa, sel, None if events is None else events[l])
+            s3["score_done"].record(sa)
+            sb.wait_event(s3["score_done"])
+            sb.wait_event(pipe["pipe_free"])         # attend of the previous user of idx / staging
+            B.hca_topk(self.shape, sel, self.n[l], w.k, pipe["idx"], pipe["count"], self.ws_topk, sb)
+            s3["sel_free"].record(sb)
+            pipe["topk_done"].record(sb)
+            sg.wait_event(pipe["topk_done"])
+            self.gather(l, sg, pipe)
+            pipe["gather_done"].record(sg)
+            sc.wait_event(pipe["gather_done"])
+            self.attend_evict(l, t, sc, pipe)
+            pipe["pipe_free"].record(sc)
+            self.layer_done[l].record(sc)
 
     def decode_step(self, t, main, side, overlap=True, events=None):
         """One decode step over all layers.  With overlap, the gather of layer l runs on the side stream
@@ -317,7 +352,8 @@ def main():
                     help="pinned host memory budget for values (the GPU boxes refuse more than 65 GiB in total)")
     ap.add_argument("--evict-every", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-overlap", action="store_true", help="single stream, no gather/score overlap")
+    ap.add_argument("--pipeline", default="staged", choices=["staged", "gather", "none"],
+                    help="staged: four stages across layers on four streams; gather: only the gather overlaps; none: serial")
     ap.add_argument("--no-latency", action="store_true", help="skip the per-layer latency probes at 128K / 1M / 4M")
     ap.add_argument("--mode", default="step", choices=["step", "scan"],
                     help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration")
@@ -338,9 +374,12 @@ def main():
     if args.mode == "scan":
         return scan_only(w, args.steps)
     # host link: peak (one large pinned copy) and the gather as the path issues it
-    main_s = [torch.cuda.Stream(), torch.cuda.Stream()]
-    gath_s = [torch.cuda.Stream(), torch.cuda.Stream()]
-    _ = [x.cuda_stream for x in main_s + gath_s]
+    # The boxes expose 4 hardware queues per process and HIP deals streams onto them round-robin, so
+    # exactly four streams are used (the default one included): one per pipeline stage, none shared.
+    main_s = [torch.cuda.current_stream()]
+    gath_s = [torch.cuda.Stream()]
+    extra = [torch.cuda.Stream(), torch.cuda.Stream()]
+    _ = [x.cuda_stream for x in main_s + gath_s + extra]
     big = torch.empty(1 << 28, dtype=torch.uint8, pin_memory=True)
     dbig = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
     dbig.copy_(big, non_blocking=True)
@@ -372,20 +411,26 @@ def main():
     code_bytes = 128 * w.bits // 8 + (128 // w.group) * 4
 
     main, side = main_s[0], gath_s[0]
-    overlap = not args.no_overlap
+
+    def run_step(t, ev=None):
+        if args.pipeline == "staged":
+            model.decode_step_staged(t, main, extra[0], side, extra[1], ev)
+        else:
+            model.decode_step(t, main, side, args.pipeline == "gather", ev)
 
     for t in range(args.warmup):
-        model.decode_step(t, main, side, overlap)
+        run_step(t)
     torch.cuda.synchronize()
     log("warmup done")
     events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
               for _ in range(args.steps)]
     t0 = time.perf_counter()
     for t in range(args.warmup, total_steps):
-        model.decode_step(t, main, side, overlap, events[t - args.warmup])
+        run_step(t, events[t - args.warmup])
+    host_dt = time.perf_counter() - t0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    log(f"timed region done: {dt:.3f}s for {args.steps} steps")
+    log(f"timed region done: {dt:.3f}s for {args.steps} steps (host enqueue {host_dt:.3f}s)")
     ms_per_step = dt * 1e3 / args.steps
     tokens_per_step = w.batch * w.n * L
     value = tokens_per_step / (dt / args.steps)
@@ -409,7 +454,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "context": w.n, "layers": L, "q_heads": w.n_q_heads,
                    "kv_heads": w.n_kv_heads, "key_bits": w.bits, "group": w.group, "top_k": w.k,
                    "evict_every": args.evict_every, "values": "context rows in pinned host fp16, appended rows in an HBM slice",
-                   "physical_value_layers": phys, "overlap": not args.no_overlap},
+                   "physical_value_layers": phys, "pipeline": args.pipeline},
         "pipelined_ms_per_layer": ms_per_step / L,
         "per_layer_decode_latency": latency,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,

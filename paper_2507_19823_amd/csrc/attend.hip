@@ -222,19 +222,27 @@ __global__ __launch_bounds__(256) void attend_merge(Layout L, const int32_t* __r
                                                     int nsplit, float* __restrict__ y, float* __restrict__ acc) {
   __shared__ float fm[4], fz[4];
   __shared__ float wgt[4][64];  // nsplit <= 64
+  __shared__ float pm[64][4], pz[64][4];
   const int row = blockIdx.y;
   const int cnt = count[row];
   const float* pmz = a.pmz + ((int64_t)row * nsplit * 4) * 2;
+  // all chunk (max, sum) pairs are fetched by separate threads in one go, then reduced from LDS
+  if (threadIdx.x < 4 * nsplit) {
+    const float2 v = reinterpret_cast<const float2*>(pmz)[threadIdx.x];   // index = split*4 + head
+    pm[threadIdx.x >> 2][threadIdx.x & 3] = v.x;
+    pz[threadIdx.x >> 2][threadIdx.x & 3] = v.y;
+  }
+  __syncthreads();
   if (threadIdx.x < 4) {
     const int h = threadIdx.x;
     float m = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) m = fmaxf(m, pmz[(s * 4 + h) * 2]);
+    for (int sp = 0; sp < nsplit; ++sp) m = fmaxf(m, pm[sp][h]);
     float z = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-      const float ms = pmz[(s * 4 + h) * 2];
+    for (int sp = 0; sp < nsplit; ++sp) {
+      const float ms = pm[sp][h];
       const float e = (ms == -INFINITY) ? 0.f : expf(ms - m);
-      wgt[h][s] = e;
-      z += e * pmz[(s * 4 + h) * 2 + 1];
+      wgt[h][sp] = e;
+      z += e * pz[sp][h];
     }
     fm[h] = m; fz[h] = z;
   }
@@ -243,8 +251,15 @@ __global__ __launch_bounds__(256) void attend_merge(Layout L, const int32_t* __r
     for (int c = threadIdx.x; c < L.gqa * kHeadDim; c += 256) {
       const int h = c >> 7, d = c & 127;
       float s = 0.f;
-      for (int sp = 0; sp < nsplit; ++sp)
-        s = fmaf(wgt[h][sp], a.py[(((int64_t)row * nsplit + sp) * 4 + h) * kHeadDim + d], s);
+      const float* src = a.py + ((int64_t)row * nsplit * 4 + h) * kHeadDim + d;
+      for (int s0 = 0; s0 < nsplit; s0 += 16) {      // 16 independent loads per batch
+        float v[16];
+#pragma unroll
+        for (int x = 0; x < 16; ++x) v[x] = (s0 + x < nsplit) ? src[(int64_t)(s0 + x) * 4 * kHeadDim] : 0.f;
+#pragma unroll
+        for (int x = 0; x < 16; ++x)
+          if (s0 + x < nsplit) s = fmaf(wgt[h][s0 + x], v[x], s);
+      }
       y[((int64_t)row * L.gqa + h) * kHeadDim + d] = cnt > 0 ? s / fz[h] : 0.f;
     }
   } else if (acc != nullptr) {
