@@ -47,6 +47,10 @@ class Model:
                     for _ in range(layers)]
         self.pos = [torch.arange(self.cap, dtype=torch.int32, device=dev).repeat(w.batch, w.n_kv_heads, 1).contiguous()
                     for _ in range(layers)]
+        # one spare (cache, acc, pos) set: eviction writes the compacted layer into it and the buffers swap
+        self.spare = (torch.empty(kb, dtype=torch.uint8, device=dev),
+                      torch.zeros(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev),
+                      torch.zeros(w.batch, w.n_kv_heads, self.cap, dtype=torch.int32, device=dev))
         self.v_host = [None] * layers
         self.v_hbm = [torch.zeros(w.batch, w.n_kv_heads, self.vnew, 128, dtype=torch.float16, device=dev)
                       for _ in range(layers)]
@@ -150,8 +154,11 @@ class Model:
         B.hca_attend_gathered(self.shape, self.kcache[l], self.q[t][l], pipe["idx"], pipe["count"], w.k,
                               self.sm_scale, self.y[l], self.acc[l], pipe["ws"], st)
         if self.evict_every and (t + 1) % self.evict_every == 0:
+            sk, sa_, sp = self.spare
             B.hca_evict(self.shape, self.kcache[l], self.acc[l], self.pos[l], self.n[l], self.n0,
-                        self.evict_every, None, self.ws_main, st)
+                        self.evict_every, None, self.ws_main, sk, sa_, sp, st)
+            self.spare = (self.kcache[l], self.acc[l], self.pos[l])
+            self.kcache[l], self.acc[l], self.pos[l] = sk, sa_, sp
             self.n[l] = [min(x, self.n0) for x in self.n[l]]
 
     def decode_step_staged(self, t, sa, sb, sg, sc, events=None):
@@ -228,7 +235,8 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8):
         t += 1
     resident = w.n + 2
     if cfg == 5:
-        B.hca_evict(m.shape, m.kcache[0], m.acc[0], m.pos[0], m.n[0], w.evict_keep, 2, None, m.ws_main, main)
+        B.hca_evict(m.shape, m.kcache[0], m.acc[0], m.pos[0], m.n[0], w.evict_keep, 2, None, m.ws_main,
+                    None, None, None, main)
         m.n[0] = [w.evict_keep] * w.batch
         resident = w.evict_keep
     m.decode_step(t, main, side, overlap=False)

@@ -159,14 +159,24 @@ int32_t hca_attend_gathered(const hca_shape* shape, const void* kcache, const vo
 /* Step 4, accumulated-score eviction.  Rows with n_resident > M keep their newest
  * n_protect slots and, of the others, the M - n_protect with the highest acc (ties
  * towards the lower slot); the kept slots move, in ascending old-slot order, to
- * slots 0..M-1 of kcache, acc and pos.  Rows of sequences with n_resident <= M are
- * left unchanged.  The caller then sets n_resident[b] = min(n_resident[b], M).
+ * slots 0..M-1 of kcache, acc and pos.  The caller then sets
+ * n_resident[b] = min(n_resident[b], M).
+ * Two modes:
+ *   in place (kcache_dst == acc_dst == pos_dst == NULL): the compacted rows are staged
+ *     in the workspace and copied back; rows of sequences with n_resident <= M are
+ *     left untouched;
+ *   out of place (all three given, distinct from the sources): the compacted rows are
+ *     written straight into a second cache / acc / pos of the same shape, rows with
+ *     n_resident <= M are carried over unchanged, and the caller swaps the buffers
+ *     afterwards.  This halves the bytes moved; one spare buffer serves any number of
+ *     layers, the source of one eviction being the spare of the next.
  *   kept_opt  device, int32 [batch, n_kv_heads, M] or NULL: old slot of each new slot
  *             (written only for rows that were compacted)
  * Errors: HCA_ERR_CAPACITY if M < 1, M > capacity or n_protect > M. */
 int32_t hca_evict(const hca_shape* shape, void* kcache, float* acc, int32_t* pos,
                   const int64_t* n_resident, int64_t M, int64_t n_protect,
-                  int32_t* kept_opt, void* workspace, void* stream);
+                  int32_t* kept_opt, void* workspace, void* kcache_dst, float* acc_dst,
+                  int32_t* pos_dst, void* stream);
 
 /* Test / debug: export the cache in canonical row-major form.
  *   codes  device, uint8 [batch, n_kv_heads, capacity, head_dim*bits/8]; channel c in bits

@@ -62,7 +62,7 @@ def lib():
         L.hca_attend_gathered.restype = i32
         L.hca_attend_gathered.argtypes = [sp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp]
         L.hca_evict.restype = i32
-        L.hca_evict.argtypes = [sp, vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        L.hca_evict.argtypes = [sp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
         L.hca_export_kcache.restype = i32
         L.hca_export_kcache.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         _lib = L
@@ -156,10 +156,12 @@ def hca_attend_gathered(shape, kcache, q_f16, idx, count, k, sm_scale, y, acc_op
            "hca_attend_gathered")
 
 
-def hca_evict(shape, kcache, acc, pos, n_resident, M, n_protect, kept_opt, workspace, stream=None):
+def hca_evict(shape, kcache, acc, pos, n_resident, M, n_protect, kept_opt, workspace, kcache_dst=None, acc_dst=None,
+              pos_dst=None, stream=None):
     nr = _nres(n_resident, shape.batch)
     _check(lib().hca_evict(C.byref(shape), _ptr(kcache), _ptr(acc), _ptr(pos), nr, int(M), int(n_protect),
-                           _ptr(kept_opt), _ptr(workspace), _stream(stream)), "hca_evict")
+                           _ptr(kept_opt), _ptr(workspace), _ptr(kcache_dst), _ptr(acc_dst), _ptr(pos_dst),
+                           _stream(stream)), "hca_evict")
 
 
 def hca_export_kcache(shape, kcache, n_resident, codes, scale_f16, zero_f16, stream=None):

@@ -199,17 +199,23 @@ int32_t hca_attend_gathered(const hca_shape* shape, const void* kcache, const vo
 }
 
 int32_t hca_evict(const hca_shape* shape, void* kcache, float* acc, int32_t* pos, const int64_t* n_resident,
-                  int64_t M, int64_t n_protect, int32_t* kept_opt, void* workspace, void* stream) {
+                  int64_t M, int64_t n_protect, int32_t* kept_opt, void* workspace, void* kcache_dst,
+                  float* acc_dst, int32_t* pos_dst, void* stream) {
   Layout L;
   int32_t rc = make_layout(shape, &L);
   if (rc != HCA_OK) return rc;
   if (kcache == nullptr || acc == nullptr || pos == nullptr || workspace == nullptr) return HCA_ERR_BAD_ARG;
   if (M < 1 || M > L.cap || n_protect < 0 || n_protect > M) return HCA_ERR_CAPACITY;
+  if (kcache_dst != nullptr && (acc_dst == nullptr || pos_dst == nullptr || kcache_dst == kcache ||
+                                acc_dst == acc || pos_dst == pos))
+    return HCA_ERR_BAD_ARG;
+  if (kcache_dst == nullptr && (acc_dst != nullptr || pos_dst != nullptr)) return HCA_ERR_BAD_ARG;
   NRes nr;
   int64_t nmax;
   rc = load_nres(L, n_resident, &nr, &nmax);
   if (rc != HCA_OK) return rc;
-  return launch_evict(L, kcache, acc, pos, nr, nmax, M, n_protect, kept_opt, workspace, (hipStream_t)stream);
+  return launch_evict(L, kcache, acc, pos, nr, nmax, M, n_protect, kept_opt, workspace, kcache_dst, acc_dst,
+                      pos_dst, (hipStream_t)stream);
 }
 
 int32_t hca_export_kcache(const hca_shape* shape, const void* kcache, const int64_t* n_resident,

@@ -14,6 +14,13 @@ struct EvictWs {
   int32_t* pos;      // [rows][M]
 };
 
+// where the compacted rows go: the staging area of the workspace, or a second cache given by the caller
+struct EvictDst {
+  uint8_t* codes; int64_t codes_row;   // row stride in bytes
+  uint8_t* meta;  int64_t meta_row;
+  float* acc; int32_t* pos; int64_t ap_row;   // row stride in elements
+};
+
 static int64_t mblk_of(const Layout& L, int64_t M) { return (M + L.tpb - 1) / L.tpb; }
 
 size_t evict_workspace_bytes(const Layout& L, int64_t M) {
@@ -101,8 +108,8 @@ __global__ __launch_bounds__(256) void evict_positions(const float* __restrict__
 template <int BITS>
 __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __restrict__ kcache,
                                                     const float* __restrict__ acc, const int32_t* __restrict__ pos,
-                                                    int n_kv_heads, SelRows sr, int64_t M, int64_t mblk,
-                                                    const int32_t* __restrict__ kept, EvictWs e) {
+                                                    int n_kv_heads, SelRows sr, int64_t M,
+                                                    const int32_t* __restrict__ kept, EvictDst e) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -112,8 +119,8 @@ __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __r
   const int64_t s = kept[(int64_t)row * M + d];
   const uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
   const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
-  uint8_t* cdst = e.codes + (int64_t)row * mblk * kBlockBytes;
-  uint8_t* mdst = e.meta + (int64_t)row * mblk * kMetaBytes;
+  uint8_t* cdst = e.codes + (int64_t)row * e.codes_row;
+  uint8_t* mdst = e.meta + (int64_t)row * e.meta_row;
   if (BITS == 4) {
     const uint4 w = *reinterpret_cast<const uint4*>(crow + (s >> 4) * kBlockBytes + ((s & 15) + 16 * j) * 16);
     *reinterpret_cast<uint4*>(cdst + (d >> 4) * kBlockBytes + ((d & 15) + 16 * j) * 16) = w;
@@ -128,8 +135,8 @@ __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __r
       *reinterpret_cast<uint2*>(mdst + (d >> 5) * kMetaBytes + (d & 31) * 8) =
           *reinterpret_cast<const uint2*>(mrow + (s >> 5) * kMetaBytes + (s & 31) * 8);
   }
-  if (j == 1) e.acc[(int64_t)row * M + d] = acc[(int64_t)row * L.cap + s];
-  if (j == 2) e.pos[(int64_t)row * M + d] = pos[(int64_t)row * L.cap + s];
+  if (j == 1) e.acc[(int64_t)row * e.ap_row + d] = acc[(int64_t)row * L.cap + s];
+  if (j == 2) e.pos[(int64_t)row * e.ap_row + d] = pos[(int64_t)row * L.cap + s];
 }
 
 // staging -> front of the cache (whole blocks; slots past M in the last block are dead).
@@ -151,8 +158,30 @@ __global__ __launch_bounds__(256) void evict_copyback(Layout L, uint8_t* __restr
   }
 }
 
+// Out-of-place mode: rows that are not compacted (n <= M) are carried over unchanged.
+__global__ __launch_bounds__(256) void evict_carry_rows(Layout L, const uint8_t* __restrict__ src, const float* __restrict__ acc,
+                                                        const int32_t* __restrict__ pos, int n_kv_heads, SelRows sr,
+                                                        NRes nr, EvictDst e) {
+  const int row = blockIdx.y;
+  if (sr.want[row / n_kv_heads] >= 0) return;         // compacted rows are written by evict_gather
+  const int64_t n = nr.n[row / n_kv_heads];
+  const int64_t nblk = (n + L.tpb - 1) / L.tpb;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const uint4* cs = reinterpret_cast<const uint4*>(src + (int64_t)row * L.codes_row_bytes());
+  const uint4* ms = reinterpret_cast<const uint4*>(src + L.meta_off + (int64_t)row * L.meta_row_bytes());
+  uint4* cd = reinterpret_cast<uint4*>(e.codes + (int64_t)row * e.codes_row);
+  uint4* md = reinterpret_cast<uint4*>(e.meta + (int64_t)row * e.meta_row);
+  if (gid < nblk * (kBlockBytes / 16)) cd[gid] = cs[gid];
+  if (gid < nblk * (kMetaBytes / 16)) md[gid] = ms[gid];
+  if (gid < n) {
+    e.acc[(int64_t)row * e.ap_row + gid] = acc[(int64_t)row * L.cap + gid];
+    e.pos[(int64_t)row * e.ap_row + gid] = pos[(int64_t)row * L.cap + gid];
+  }
+}
+
 int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
-                     int64_t M, int64_t n_protect, int32_t* kept, void* ws, hipStream_t st) {
+                     int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst, float* acc_dst,
+                     int32_t* pos_dst, hipStream_t st) {
   SelRows sr;
   bool any = false;
   for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
@@ -163,11 +192,32 @@ int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, co
       any = true;
     }
   }
-  if (!any) return HCA_OK;
+  const bool oop = kcache_dst != nullptr;
   EvictWs e;
   carve(&e, ws, L, M);
-  if (kept == nullptr) kept = e.kept;
   const int64_t mblk = mblk_of(L, M);
+  EvictDst d;
+  if (oop) {
+    d.codes = (uint8_t*)kcache_dst;            d.codes_row = L.codes_row_bytes();
+    d.meta = (uint8_t*)kcache_dst + L.meta_off; d.meta_row = L.meta_row_bytes();
+    d.acc = acc_dst; d.pos = pos_dst; d.ap_row = L.cap;
+  } else {
+    d.codes = e.codes; d.codes_row = mblk * kBlockBytes;
+    d.meta = e.meta;   d.meta_row = mblk * kMetaBytes;
+    d.acc = e.acc; d.pos = e.pos; d.ap_row = M;
+  }
+  if (oop && nmax > 0) {
+    const int64_t nblk = (nmax + L.tpb - 1) / L.tpb;
+    int64_t items = nblk * (kBlockBytes / 16);
+    if (items < nmax) items = nmax;
+    dim3 gr((unsigned)((items + 255) / 256), (unsigned)L.rows);
+    evict_carry_rows<<<gr, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, nr, d);
+  }
+  if (!any) {
+    if (oop) HCA_HIP(hipGetLastError());
+    return HCA_OK;
+  }
+  if (kept == nullptr) kept = e.kept;
   SelectPlan p;
   select_plan(&p, e.select, L.rows, nmax);
   int32_t rc = select_run(p, acc, L.cap, L.rows, L.n_kv_heads, sr, st);
@@ -176,13 +226,15 @@ int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, co
   evict_positions<<<g, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kept);
   dim3 gg((unsigned)((M * 4 + 255) / 256), (unsigned)L.rows);
   if (L.bits == 4)
-    evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, kept, e);
+    evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, kept, d);
   else
-    evict_gather<2><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, kept, e);
-  int64_t items = mblk * (kBlockBytes / 16);
-  if (items < M) items = M;
-  dim3 gc((unsigned)((items + 255) / 256), (unsigned)L.rows);
-  evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, e);
+    evict_gather<2><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, kept, d);
+  if (!oop) {
+    int64_t items = mblk * (kBlockBytes / 16);
+    if (items < M) items = M;
+    dim3 gc((unsigned)((items + 255) / 256), (unsigned)L.rows);
+    evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, e);
+  }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

@@ -78,6 +78,7 @@ int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* 
                                void* ws, hipStream_t st);
 size_t evict_workspace_bytes(const Layout& L, int64_t M);
 int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr,
-                     int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, hipStream_t st);
+                     int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst,
+                     float* acc_dst, int32_t* pos_dst, hipStream_t st);
 
 }  // namespace hca

@@ -61,14 +61,34 @@ __global__ __launch_bounds__(256) void sel_hist(const float* __restrict__ vals, 
   __syncthreads();
   const uint32_t prefix = state[4 * row];
   const float* v = vals + (int64_t)row * stride;
-  for (int64_t j = c0 + threadIdx.x; j < c1; j += 256) {
-    const uint32_t key = order_key(v[j]);
-    if (PASS == 0) {
-      atomicAdd(&lh[key >> 21], 1u);
-    } else if (PASS == 1) {
-      if ((key >> 21) == (prefix >> 21)) atomicAdd(&lh[(key >> 10) & 2047u], 1u);
-    } else {
-      if ((key >> 10) == (prefix >> 10)) atomicAdd(&lh[key & 1023u], 1u);
+  const int lane = threadIdx.x & 63;
+  for (int64_t j0 = c0; j0 < c1; j0 += 256) {
+    const int64_t j = j0 + threadIdx.x;
+    bool hit = j < c1;
+    uint32_t bin = 0;
+    if (hit) {
+      const uint32_t key = order_key(v[j]);
+      if (PASS == 0) {
+        bin = key >> 21;
+      } else if (PASS == 1) {
+        hit = (key >> 21) == (prefix >> 21);
+        bin = (key >> 10) & 2047u;
+      } else {
+        hit = (key >> 10) == (prefix >> 10);
+        bin = key & 1023u;
+      }
+    }
+    // accumulated scores are mostly equal (0), so a whole wave usually lands in one bin: one
+    // atomic for the wave instead of 64 on the same LDS word
+    const uint64_t m = __ballot(hit);
+    if (m != 0) {
+      const int leader = __ffsll((unsigned long long)m) - 1;
+      const uint32_t b0 = __shfl(bin, leader);
+      if (__ballot(hit && bin != b0) == 0) {
+        if (lane == leader) atomicAdd(&lh[b0], (uint32_t)__popcll(m));
+      } else if (hit) {
+        atomicAdd(&lh[bin], 1u);
+      }
     }
   }
   __syncthreads();

@@ -65,9 +65,20 @@ class LayerState:
                             n_host_rows, v_hbm, ds, self.sm_scale, self.y, self.acc if use_acc else None,
                             self.ws, gather_stream, stream)
 
-    def evict(self, M, n_protect, kept=None, stream=None):
-        B.hca_evict(self.shape, self.kcache, self.acc, self.pos, self.n, M, n_protect, kept, self.ws, stream)
+    def evict(self, M, n_protect, kept=None, stream=None, spare=None):
+        """In place, or (spare = (kcache, acc, pos) of the same shapes) out of place followed by a swap;
+        the old buffers are returned as the next spare."""
+        if spare is None:
+            B.hca_evict(self.shape, self.kcache, self.acc, self.pos, self.n, M, n_protect, kept, self.ws,
+                        None, None, None, stream)
+            out = None
+        else:
+            B.hca_evict(self.shape, self.kcache, self.acc, self.pos, self.n, M, n_protect, kept, self.ws,
+                        spare[0], spare[1], spare[2], stream)
+            out = (self.kcache, self.acc, self.pos)
+            self.kcache, self.acc, self.pos = spare
         self.n = [min(x, M) for x in self.n]
+        return out
 
     def export(self):
         cb = 128 * self.shape.bits // 8

@@ -61,9 +61,11 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert L.hca_topk(C.byref(s), one, n, 0, one, one, one, None) == -3
     assert L.hca_topk(C.byref(s), one, n, 1025, one, one, one, None) == -3
     assert L.hca_topk(C.byref(s), one, n, 8, one, one, None, None) == -1
-    assert L.hca_evict(C.byref(s), one, one, one, n, 0, 0, None, one, None) == -3
-    assert L.hca_evict(C.byref(s), one, one, one, n, 10, 11, None, one, None) == -3
-    assert L.hca_evict(C.byref(s), one, one, one, n, 200, 0, None, one, None) == 0   # n <= M: nothing to do
+    assert L.hca_evict(C.byref(s), one, one, one, n, 0, 0, None, one, None, None, None, None) == -3
+    assert L.hca_evict(C.byref(s), one, one, one, n, 10, 11, None, one, None, None, None, None) == -3
+    assert L.hca_evict(C.byref(s), one, one, one, n, 200, 0, None, one, None, None, None, None) == 0   # n <= M: nothing to do
+    assert L.hca_evict(C.byref(s), one, one, one, n, 50, 0, None, one, one, None, None, None) == -1  # dst without acc/pos
+    assert L.hca_evict(C.byref(s), one, one, one, n, 50, 0, None, one, one, one, one, None) == -1    # dst aliases src
     bad = (C.c_int64 * 1)(2000)
     assert L.hca_score_qkeys(C.byref(s), one, one, bad, one, None, None, None) == -3
     neg = (C.c_int64 * 1)(-1)

@@ -219,10 +219,11 @@ def test_pipeline_configs_against_oracle(H, oracle, cfg, host_rows):
         assert np.allclose(_rows(st.acc)[:, :M], acc[:, :M], rtol=1e-4, atol=1e-7)
 
 
+@pytest.mark.parametrize("mode", ["inplace", "spare"])
 @pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
 @pytest.mark.parametrize("n,M,Rp", [(5000, 3000, 0), (5000, 3000, 100), (5000, 5000, 16), (4000, 5000, 16),
                                     (5000, 17, 17), (5000, 1, 0), (70001, 35000, 1)])
-def test_evict_bit_exact_stagewise(H, oracle, bits, gs, n, M, Rp):
+def test_evict_bit_exact_stagewise(H, oracle, bits, gs, n, M, Rp, mode):
     """Same accumulated scores on both sides (many ties): identical keep lists and compacted state."""
     w = S.Workload("e", 80 + bits, 2, 4, 2, n, bits, gs, 16)
     rng = np.random.default_rng(n + M + Rp)
@@ -242,7 +243,12 @@ def test_evict_bit_exact_stagewise(H, oracle, bits, gs, n, M, Rp):
     st.acc.copy_(torch.from_numpy(acc.reshape(2, 2, cap)))
     st.pos.copy_(torch.from_numpy(pos.reshape(2, 2, cap)))
     kept = torch.full((2, 2, M), -5, dtype=torch.int32, device="cuda")
-    st.evict(M, Rp, kept)
+    if mode == "spare":
+        spare = (torch.full_like(st.kcache, 0xAB), torch.full_like(st.acc, -1.0), torch.full_like(st.pos, -1))
+        old = st.evict(M, Rp, kept, spare=spare)
+        assert old is not None and st.kcache is spare[0]
+    else:
+        st.evict(M, Rp, kept)
     torch.cuda.synchronize()
     okept = oracle.evict(oc, acc, pos, M, Rp)
     m = min(n, M)
