@@ -161,6 +161,41 @@ class Model:
             self.kcache[l], self.acc[l], self.pos[l] = sk, sa_, sp
             self.n[l] = [min(x, self.n0) for x in self.n[l]]
 
+    def native_pipeline(self, sa, sb, sg, sc, timing_slots):
+        """Hands the four streams and the pipeline buffers to the library's step driver."""
+        import ctypes as C
+        B, w = self.B, self.w
+        d = B.hca_pipeline_desc()
+        d.stream_scan, d.stream_topk = sa.cuda_stream, sb.cuda_stream
+        d.stream_gather, d.stream_attend = sg.cuda_stream, sc.cuda_stream
+        for i in range(3):
+            d.sel[i] = self.sels[i].data_ptr()
+        for i in range(4):
+            d.idx[i] = self.pipe[i]["idx"].data_ptr()
+            d.count[i] = self.pipe[i]["count"].data_ptr()
+            d.ws_attend[i] = self.pipe[i]["ws"].data_ptr()
+        d.ws_topk, d.ws_evict = self.ws_topk.data_ptr(), self.ws_main.data_ptr()
+        d.spare_kcache, d.spare_acc, d.spare_pos = (x.data_ptr() for x in self.spare)
+        self.pl = B.hca_pipeline_create(self.shape, self.L, d, timing_slots)
+        self.pl_layers = (B.hca_layer * self.L)()
+        for l in range(self.L):
+            ly = self.pl_layers[l]
+            ly.kcache, ly.acc, ly.pos = self.kcache[l].data_ptr(), self.acc[l].data_ptr(), self.pos[l].data_ptr()
+            ly.v_host, ly.v_hbm = self.v_host[l].data_ptr(), self.v_hbm[l].data_ptr()
+            ly.y = self.y[l].data_ptr()
+        self.pl_n = (C.c_int64 * (self.L * w.batch))(*[x for l in range(self.L) for x in self.n[l]])
+
+    def decode_step_native(self, t, timing_slot=-1):
+        """One decode step through hca_pipeline_step (same kernels as decode_step_staged)."""
+        w = self.w
+        for l in range(self.L):
+            self.pl_layers[l].k_new = self.k_new[t][l].data_ptr()
+            self.pl_layers[l].q = self.q[t][l].data_ptr()
+        evict = self.n0 if (self.evict_every and (t + 1) % self.evict_every == 0) else 0
+        vh = self.v_host[0]
+        self.B.hca_pipeline_step(self.pl, self.pl_layers, self.pl_n, self.n0 + t, w.k, vh.shape[2], vh.shape[2],
+                                 self.vnew, self.sm_scale, evict, self.evict_every, timing_slot)
+
     def decode_step_staged(self, t, sa, sb, sg, sc, events=None):
         """One decode step over all layers as a four-stage pipeline across layers, one stream per stage:
         sa: append + key scan, sb: top-k, sg: host-link gather, sc: attend (+ eviction when due).
@@ -360,8 +395,9 @@ def main():
                     help="pinned host memory budget for values (the GPU boxes refuse more than 65 GiB in total)")
     ap.add_argument("--evict-every", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--pipeline", default="staged", choices=["staged", "gather", "none"],
-                    help="staged: four stages across layers on four streams; gather: only the gather overlaps; none: serial")
+    ap.add_argument("--pipeline", default="native", choices=["native", "staged", "gather", "none"],
+                    help="native: the library's four-stage step driver; staged: the same pipeline enqueued from Python; "
+                         "gather: only the gather overlaps; none: serial")
     ap.add_argument("--no-latency", action="store_true", help="skip the per-layer latency probes at 128K / 1M / 4M")
     ap.add_argument("--mode", default="step", choices=["step", "scan"],
                     help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration")
@@ -420,8 +456,13 @@ def main():
 
     main, side = main_s[0], gath_s[0]
 
+    if args.pipeline == "native":
+        model.native_pipeline(main, extra[0], side, extra[1], args.steps)
+
     def run_step(t, ev=None):
-        if args.pipeline == "staged":
+        if args.pipeline == "native":
+            model.decode_step_native(t, -1 if ev is None else t - args.warmup)
+        elif args.pipeline == "staged":
             model.decode_step_staged(t, main, extra[0], side, extra[1], ev)
         else:
             model.decode_step(t, main, side, args.pipeline == "gather", ev)
@@ -442,9 +483,12 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     tokens_per_step = w.batch * w.n * L
     value = tokens_per_step / (dt / args.steps)
-    events = [e for step_events in events for e in step_events]
-
-    scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
+    if args.pipeline == "native":
+        per = [x for slot in range(args.steps) for x in B.hca_pipeline_scan_ms(model.pl, slot, L)]
+        scan_ms = sum(per) / len(per)
+    else:
+        events = [e for step_events in events for e in step_events]
+        scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
     scan_bytes = w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + 4)
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
 

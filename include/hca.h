@@ -178,6 +178,55 @@ int32_t hca_evict(const hca_shape* shape, void* kcache, float* acc, int32_t* pos
                   int32_t* kept_opt, void* workspace, void* kcache_dst, float* acc_dst,
                   int32_t* pos_dst, void* stream);
 
+/* ---- Step driver -------------------------------------------------------------------------
+ * One decode step over all layers of a model, enqueued as a four-stage pipeline across layers:
+ * (append + key scan) | top-k | host-link gather | (attend + eviction), one stream per stage,
+ * the stages of a layer chained by events, different layers overlapping (Sec. 3.2: the value
+ * side runs beside the GPU's scoring, not after it).  It issues exactly the kernels of the
+ * per-step calls above; it exists because enqueueing ~15 launches per layer from a scripting
+ * language costs more than the kernels take.  Legal only when the queries of all layers exist
+ * before the step (benchmarks with synthetic queries; speculative / batched serving). */
+typedef struct {
+  void* kcache; float* acc; int32_t* pos;   /* device; swapped with the spare set when the layer is evicted */
+  const void* k_new;                        /* device, fp16 [batch, n_kv_heads, 1, head_dim]: this step's key */
+  const void* q;                            /* device, fp16 [batch, n_q_heads, head_dim] */
+  const void* v_host;                       /* pinned value store (rows < n_host_rows) or NULL */
+  const void* v_hbm;                        /* device value slice (rows >= n_host_rows) or NULL */
+  float* y;                                 /* device, fp32 [batch, n_q_heads, head_dim] */
+} hca_layer;
+
+typedef struct {
+  void *stream_scan, *stream_topk, *stream_gather, *stream_attend;   /* four distinct hipStream_t */
+  float* sel[3];                 /* device, fp32 [batch, n_kv_heads, capacity] each */
+  int32_t* idx[4];               /* device, int32 [batch, n_kv_heads, k] each */
+  int32_t* count[4];             /* device, int32 [batch, n_kv_heads] each */
+  void* ws_attend[4];            /* device, hca_workspace_bytes(shape, k, 1) each */
+  void* ws_topk;                 /* device, hca_workspace_bytes(shape, k, 1) */
+  void* ws_evict;                /* device, hca_workspace_bytes(shape, k, M); NULL if eviction is never asked for */
+  void* spare_kcache; float* spare_acc; int32_t* spare_pos;   /* spare set for out-of-place eviction, or NULL */
+} hca_pipeline_desc;
+
+typedef struct hca_pipeline hca_pipeline;
+
+/* Creates the driver (host object + HIP events; no device memory).  timing_slots > 0 reserves
+ * that many sets of timing events around the key-scan launches.  NULL on bad arguments. */
+hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, const hca_pipeline_desc* desc,
+                                  int32_t timing_slots);
+void hca_pipeline_destroy(hca_pipeline* p);
+
+/* Enqueues one decode step.  layers: host array [n_layers], updated when buffers swap on eviction.
+ * n_resident: host, int64 [n_layers][batch], updated (+1 for the appended token, then min(., evict_M)).
+ * value_row0: value-store row of the appended token (all sequences).  evict_M == 0: no eviction this
+ * step; otherwise layers with n_resident > evict_M are evicted to evict_M after their attend.
+ * timing_slot < 0: no timing. */
+int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_resident, int64_t value_row0, int32_t k,
+                          int64_t host_stride, int64_t n_host_rows, int64_t hbm_stride, float sm_scale,
+                          int64_t evict_M, int64_t n_protect, int32_t timing_slot);
+
+/* After the device has finished the step recorded in `timing_slot`: duration of each layer's
+ * key-scan launch in milliseconds, ms[n_layers] (host). */
+int32_t hca_pipeline_scan_ms(hca_pipeline* p, int32_t timing_slot, float* ms);
+
 /* Test / debug: export the cache in canonical row-major form.
  *   codes  device, uint8 [batch, n_kv_heads, capacity, head_dim*bits/8]; channel c in bits
  *          [(c*bits)%8, +bits) of byte c*bits/8

@@ -29,6 +29,19 @@ class hca_shape(C.Structure):
                 ("capacity", C.c_int64)]
 
 
+class hca_layer(C.Structure):
+    _fields_ = [("kcache", C.c_void_p), ("acc", C.c_void_p), ("pos", C.c_void_p), ("k_new", C.c_void_p),
+                ("q", C.c_void_p), ("v_host", C.c_void_p), ("v_hbm", C.c_void_p), ("y", C.c_void_p)]
+
+
+class hca_pipeline_desc(C.Structure):
+    _fields_ = [("stream_scan", C.c_void_p), ("stream_topk", C.c_void_p), ("stream_gather", C.c_void_p),
+                ("stream_attend", C.c_void_p), ("sel", C.c_void_p * 3), ("idx", C.c_void_p * 4),
+                ("count", C.c_void_p * 4), ("ws_attend", C.c_void_p * 4), ("ws_topk", C.c_void_p),
+                ("ws_evict", C.c_void_p), ("spare_kcache", C.c_void_p), ("spare_acc", C.c_void_p),
+                ("spare_pos", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -63,6 +76,15 @@ def lib():
         L.hca_attend_gathered.argtypes = [sp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp]
         L.hca_evict.restype = i32
         L.hca_evict.argtypes = [sp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.hca_pipeline_create.restype = vp
+        L.hca_pipeline_create.argtypes = [sp, i32, C.POINTER(hca_pipeline_desc), i32]
+        L.hca_pipeline_destroy.restype = None
+        L.hca_pipeline_destroy.argtypes = [vp]
+        L.hca_pipeline_step.restype = i32
+        L.hca_pipeline_step.argtypes = [vp, C.POINTER(hca_layer), C.POINTER(i64), i64, i32, i64, i64, i64, f32, i64,
+                                        i64, i32]
+        L.hca_pipeline_scan_ms.restype = i32
+        L.hca_pipeline_scan_ms.argtypes = [vp, i32, C.POINTER(f32)]
         L.hca_export_kcache.restype = i32
         L.hca_export_kcache.argtypes = [sp, vp, vp, vp, vp, vp, vp]
         _lib = L
@@ -168,3 +190,28 @@ def hca_export_kcache(shape, kcache, n_resident, codes, scale_f16, zero_f16, str
     nr = _nres(n_resident, shape.batch)
     _check(lib().hca_export_kcache(C.byref(shape), _ptr(kcache), nr, _ptr(codes), _ptr(scale_f16),
                                    _ptr(zero_f16), _stream(stream)), "hca_export_kcache")
+
+
+def hca_pipeline_create(shape, n_layers, desc, timing_slots=0):
+    h = lib().hca_pipeline_create(C.byref(shape), int(n_layers), C.byref(desc), int(timing_slots))
+    if not h:
+        raise HcaError("hca_pipeline_create", -1)
+    return h
+
+
+def hca_pipeline_destroy(handle):
+    lib().hca_pipeline_destroy(handle)
+
+
+def hca_pipeline_step(handle, layers, n_resident, value_row0, k, host_stride, n_host_rows, hbm_stride, sm_scale,
+                      evict_M=0, n_protect=0, timing_slot=-1):
+    """layers: ctypes array of hca_layer; n_resident: ctypes int64 array [n_layers * batch] (both updated)."""
+    _check(lib().hca_pipeline_step(handle, layers, n_resident, int(value_row0), int(k), int(host_stride),
+                                   int(n_host_rows), int(hbm_stride), float(sm_scale), int(evict_M), int(n_protect),
+                                   int(timing_slot)), "hca_pipeline_step")
+
+
+def hca_pipeline_scan_ms(handle, timing_slot, n_layers):
+    out = (C.c_float * n_layers)()
+    _check(lib().hca_pipeline_scan_ms(handle, int(timing_slot), out), "hca_pipeline_scan_ms")
+    return list(out)

@@ -1,0 +1,154 @@
+// Host-side step driver: one decode step over all layers as a four-stage pipeline across layers
+// (append + key scan | top-k | host-link gather | attend + eviction), one HIP stream per stage,
+// stages of a layer chained by events.  Pure enqueue logic around the launchers of the other
+// translation units; nothing here touches data.
+#include <vector>
+
+#include "hca_internal.h"
+
+struct hca_pipeline {
+  hca::Layout L;
+  int n_layers;
+  hca_pipeline_desc d;
+  hipEvent_t score_done[3], sel_free[3];
+  hipEvent_t topk_done[4], gather_done[4], pipe_free[4];
+  std::vector<hipEvent_t> layer_done;
+  std::vector<hipEvent_t> t0, t1;   // timing events around the scan launches: [slots][layers]
+  int timing_slots;
+};
+
+using namespace hca;
+
+extern "C" {
+
+hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, const hca_pipeline_desc* desc,
+                                  int32_t timing_slots) {
+  Layout L;
+  if (make_layout(shape, &L) != HCA_OK || desc == nullptr || n_layers < 1 || timing_slots < 0) return nullptr;
+  for (int i = 0; i < 3; ++i) if (desc->sel[i] == nullptr) return nullptr;
+  for (int i = 0; i < 4; ++i)
+    if (desc->idx[i] == nullptr || desc->count[i] == nullptr || desc->ws_attend[i] == nullptr) return nullptr;
+  if (desc->ws_topk == nullptr) return nullptr;
+  hca_pipeline* p = new hca_pipeline();
+  p->L = L;
+  p->n_layers = n_layers;
+  p->d = *desc;
+  p->timing_slots = timing_slots;
+  bool ok = true;
+  auto mk = [&](hipEvent_t* e, unsigned flags) { ok = ok && hipEventCreateWithFlags(e, flags) == hipSuccess; };
+  for (int i = 0; i < 3; ++i) { mk(&p->score_done[i], hipEventDisableTiming); mk(&p->sel_free[i], hipEventDisableTiming); }
+  for (int i = 0; i < 4; ++i) {
+    mk(&p->topk_done[i], hipEventDisableTiming);
+    mk(&p->gather_done[i], hipEventDisableTiming);
+    mk(&p->pipe_free[i], hipEventDisableTiming);
+  }
+  p->layer_done.resize(n_layers);
+  for (int l = 0; l < n_layers; ++l) mk(&p->layer_done[l], hipEventDisableTiming);
+  p->t0.resize((size_t)timing_slots * n_layers);
+  p->t1.resize((size_t)timing_slots * n_layers);
+  for (size_t i = 0; i < p->t0.size(); ++i) { mk(&p->t0[i], hipEventDefault); mk(&p->t1[i], hipEventDefault); }
+  if (!ok) { delete p; return nullptr; }   // events already made are left to process teardown
+  return p;
+}
+
+void hca_pipeline_destroy(hca_pipeline* p) {
+  if (p == nullptr) return;
+  for (int i = 0; i < 3; ++i) { (void)hipEventDestroy(p->score_done[i]); (void)hipEventDestroy(p->sel_free[i]); }
+  for (int i = 0; i < 4; ++i) {
+    (void)hipEventDestroy(p->topk_done[i]);
+    (void)hipEventDestroy(p->gather_done[i]);
+    (void)hipEventDestroy(p->pipe_free[i]);
+  }
+  for (auto e : p->layer_done) (void)hipEventDestroy(e);
+  for (auto e : p->t0) (void)hipEventDestroy(e);
+  for (auto e : p->t1) (void)hipEventDestroy(e);
+  delete p;
+}
+
+int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_resident, int64_t value_row0, int32_t k,
+                          int64_t host_stride, int64_t n_host_rows, int64_t hbm_stride, float sm_scale,
+                          int64_t evict_M, int64_t n_protect, int32_t timing_slot) {
+  if (p == nullptr || layers == nullptr || n_resident == nullptr) return HCA_ERR_BAD_ARG;
+  const Layout& L = p->L;
+  if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
+  if (evict_M != 0 && (evict_M < 1 || evict_M > L.cap || n_protect < 0 || n_protect > evict_M)) return HCA_ERR_CAPACITY;
+  if (evict_M != 0 && (p->d.ws_evict == nullptr || p->d.spare_kcache == nullptr || p->d.spare_acc == nullptr ||
+                       p->d.spare_pos == nullptr))
+    return HCA_ERR_BAD_ARG;
+  if (timing_slot >= p->timing_slots) return HCA_ERR_BAD_ARG;
+  hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk;
+  hipStream_t sg = (hipStream_t)p->d.stream_gather, sc = (hipStream_t)p->d.stream_attend;
+  NRes vrow0;
+  for (int b = 0; b < kMaxBatch; ++b) vrow0.n[b] = value_row0;
+  for (int l = 0; l < p->n_layers; ++l) {
+    hca_layer& ly = layers[l];
+    int64_t* nl = n_resident + (int64_t)l * L.batch;
+    if (ly.kcache == nullptr || ly.acc == nullptr || ly.pos == nullptr || ly.k_new == nullptr || ly.q == nullptr ||
+        ly.y == nullptr)
+      return HCA_ERR_BAD_ARG;
+    NRes nr;
+    int64_t nmax;
+    int32_t rc = load_nres(L, nl, &nr, &nmax);
+    if (rc != HCA_OK) return rc;
+    for (int b = 0; b < L.batch; ++b)
+      if (nr.n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;
+    const int s3 = l % 3, s4 = l % 4;
+    // stage 1: append + key scan
+    HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[s3], 0));     // top-k of the previous user of this score buffer
+    HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l], 0));    // this layer's attend / evict of the previous step
+    rc = launch_quantize(L, ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa);
+    if (rc != HCA_OK) return rc;
+    for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
+    nmax += 1;
+    if (timing_slot >= 0) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
+    rc = launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa);
+    if (rc != HCA_OK) return rc;
+    if (timing_slot >= 0) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
+    HCA_HIP(hipEventRecord(p->score_done[s3], sa));
+    // stage 2: top-k
+    HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
+    HCA_HIP(hipStreamWaitEvent(sb, p->pipe_free[s4], 0));    // attend of the previous user of idx / staging
+    rc = launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb);
+    if (rc != HCA_OK) return rc;
+    HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
+    HCA_HIP(hipEventRecord(p->topk_done[s4], sb));
+    // stage 3: host-link gather
+    HCA_HIP(hipStreamWaitEvent(sg, p->topk_done[s4], 0));
+    rc = launch_gather(L, p->d.idx[s4], p->d.count[s4], k, ly.pos, ly.v_host, host_stride, n_host_rows, ly.v_hbm,
+                       hbm_stride, p->d.ws_attend[s4], sg);
+    if (rc != HCA_OK) return rc;
+    HCA_HIP(hipEventRecord(p->gather_done[s4], sg));
+    // stage 4: attend (+ eviction into the spare buffers, which then swap with the layer's)
+    HCA_HIP(hipStreamWaitEvent(sc, p->gather_done[s4], 0));
+    rc = launch_attend_gathered(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, sm_scale, ly.y, ly.acc,
+                                p->d.ws_attend[s4], sc);
+    if (rc != HCA_OK) return rc;
+    if (evict_M != 0) {
+      bool any = false;
+      for (int b = 0; b < L.batch; ++b) any = any || nr.n[b] > evict_M;
+      if (any) {
+        rc = launch_evict(L, ly.kcache, ly.acc, ly.pos, nr, nmax, evict_M, n_protect, nullptr, p->d.ws_evict,
+                          p->d.spare_kcache, p->d.spare_acc, p->d.spare_pos, sc);
+        if (rc != HCA_OK) return rc;
+        void* ok = ly.kcache; float* oa = ly.acc; int32_t* op = ly.pos;
+        ly.kcache = p->d.spare_kcache; ly.acc = p->d.spare_acc; ly.pos = p->d.spare_pos;
+        p->d.spare_kcache = ok; p->d.spare_acc = oa; p->d.spare_pos = op;
+        for (int b = 0; b < L.batch; ++b) if (nl[b] > evict_M) nl[b] = evict_M;
+      }
+    }
+    HCA_HIP(hipEventRecord(p->pipe_free[s4], sc));
+    HCA_HIP(hipEventRecord(p->layer_done[l], sc));
+  }
+  return HCA_OK;
+}
+
+int32_t hca_pipeline_scan_ms(hca_pipeline* p, int32_t timing_slot, float* ms) {
+  if (p == nullptr || ms == nullptr || timing_slot < 0 || timing_slot >= p->timing_slots) return HCA_ERR_BAD_ARG;
+  for (int l = 0; l < p->n_layers; ++l) {
+    const size_t i = (size_t)timing_slot * p->n_layers + l;
+    HCA_HIP(hipEventElapsedTime(&ms[l], p->t0[i], p->t1[i]));
+  }
+  return HCA_OK;
+}
+
+}  // extern "C"

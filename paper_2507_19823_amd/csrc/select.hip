@@ -473,27 +473,26 @@ __global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, i
   cnt[tid] = tid < nchunks ? t.ncand[(int64_t)row * kMaxChunks + tid] : 0;
   if (tid == 0) s_n = 0;
   __syncthreads();
-  // sweep(f): f(key, slot) for every list entry of the row that lies in bin b*.  Each wave takes 4
-  // chunks per step and issues up to 8 loads per chunk before using any of them.
+  // sweep(f): f(key, slot) for every list entry of the row that lies in bin b*.  Each wave takes 16
+  // chunks per step and fetches the first 64 entries of all of them in one batch of loads (most
+  // lists are shorter than that), so a step costs one memory round trip; longer lists follow.
   auto sweep = [&](auto&& f) {
-    for (int c0 = 0; c0 < nchunks; c0 += 64) {
-      uint2 ent[4][8];
-      uint32_t m[4];
+    for (int c0 = 0; c0 < nchunks; c0 += 256) {
+      uint2 ent[16];
+      uint32_t m[16];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int c = c0 + wv * 4 + u;
+      for (int u = 0; u < 16; ++u) {
+        const int c = c0 + wv * 16 + u;
         m[u] = c < nchunks ? cnt[c] : 0;
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-          if (lane + 64 * r < m[u]) ent[u][r] = cand[(int64_t)c * chunk + lane + 64 * r];
+        if ((uint32_t)lane < m[u]) ent[u] = cand[(int64_t)c * chunk + lane];
       }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r)
-          if (lane + 64 * r < m[u] && (ent[u][r].x >> 20) == bin) f(ent[u][r].x, ent[u][r].y);
-        const int c = c0 + wv * 4 + u;
-        for (uint32_t i = 512 + lane; i < m[u]; i += 64) {      // long lists (clustered heavy hitters)
+      for (int u = 0; u < 16; ++u)
+        if ((uint32_t)lane < m[u] && (ent[u].x >> 20) == bin) f(ent[u].x, ent[u].y);
+#pragma unroll 1
+      for (int u = 0; u < 16; ++u) {
+        const int c = c0 + wv * 16 + u;
+        for (uint32_t i = 64 + lane; i < m[u]; i += 64) {      // long lists (clustered heavy hitters)
           const uint2 x = cand[(int64_t)c * chunk + i];
           if ((x.x >> 20) == bin) f(x.x, x.y);
         }
