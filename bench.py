@@ -36,7 +36,7 @@ class Model:
         self.L = layers
         self.n0 = w.n
         self.evict_every = evict_every
-        self.cap = w.n + max(evict_every, 1) + 16
+        self.cap = w.n + (evict_every if evict_every else total_steps) + 16
         self.vnew = total_steps + 16                  # value rows of appended tokens live in an HBM slice
         self.shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, self.cap, w.bits, w.group)
         self.rows = w.batch * w.n_kv_heads
@@ -153,7 +153,7 @@ class Model:
         B, w = self.B, self.w
         B.hca_attend_gathered(self.shape, self.kcache[l], self.q[t][l], pipe["idx"], pipe["count"], w.k,
                               self.sm_scale, self.y[l], self.acc[l], pipe["ws"], st)
-        if self.evict_every and (t + 1) % self.evict_every == 0:
+        if self.evict_due(l, t):
             sk, sa_, sp = self.spare
             B.hca_evict(self.shape, self.kcache[l], self.acc[l], self.pos[l], self.n[l], self.n0,
                         self.evict_every, None, self.ws_main, sk, sa_, sp, st)
@@ -191,10 +191,16 @@ class Model:
         for l in range(self.L):
             self.pl_layers[l].k_new = self.k_new[t][l].data_ptr()
             self.pl_layers[l].q = self.q[t][l].data_ptr()
-        evict = self.n0 if (self.evict_every and (t + 1) % self.evict_every == 0) else 0
+        import ctypes as C
+        evict = (C.c_int64 * self.L)(*[self.n0 if self.evict_due(l, t) else 0 for l in range(self.L)])
         vh = self.v_host[0]
         self.B.hca_pipeline_step(self.pl, self.pl_layers, self.pl_n, self.n0 + t, w.k, vh.shape[2], vh.shape[2],
                                  self.vnew, self.sm_scale, evict, self.evict_every, timing_slot)
+
+    def evict_due(self, l, t):
+        """Every layer is evicted once per `evict_every` steps; the layers are staggered over the period
+        so that each step carries its share instead of one step carrying all of them."""
+        return bool(self.evict_every) and (t + 1 + l) % self.evict_every == 0
 
     def decode_step_staged(self, t, sa, sb, sg, sc, events=None):
         """One decode step over all layers as a four-stage pipeline across layers, one stream per stage:

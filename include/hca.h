@@ -216,12 +216,13 @@ void hca_pipeline_destroy(hca_pipeline* p);
 
 /* Enqueues one decode step.  layers: host array [n_layers], updated when buffers swap on eviction.
  * n_resident: host, int64 [n_layers][batch], updated (+1 for the appended token, then min(., evict_M)).
- * value_row0: value-store row of the appended token (all sequences).  evict_M == 0: no eviction this
- * step; otherwise layers with n_resident > evict_M are evicted to evict_M after their attend.
- * timing_slot < 0: no timing. */
+ * value_row0: value-store row of the appended token (all sequences).  evict_M: host, int64 [n_layers]
+ * or NULL; layer l with evict_M[l] != 0 and n_resident > evict_M[l] is evicted to evict_M[l] after its
+ * attend (callers stagger the layers over the steps of an eviction period so that no step carries all
+ * of them).  timing_slot < 0: no timing. */
 int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_resident, int64_t value_row0, int32_t k,
                           int64_t host_stride, int64_t n_host_rows, int64_t hbm_stride, float sm_scale,
-                          int64_t evict_M, int64_t n_protect, int32_t timing_slot);
+                          const int64_t* evict_M, int64_t n_protect, int32_t timing_slot);
 
 /* After the device has finished the step recorded in `timing_slot`: duration of each layer's
  * key-scan launch in milliseconds, ms[n_layers] (host). */

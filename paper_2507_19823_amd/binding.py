@@ -81,8 +81,8 @@ def lib():
         L.hca_pipeline_destroy.restype = None
         L.hca_pipeline_destroy.argtypes = [vp]
         L.hca_pipeline_step.restype = i32
-        L.hca_pipeline_step.argtypes = [vp, C.POINTER(hca_layer), C.POINTER(i64), i64, i32, i64, i64, i64, f32, i64,
-                                        i64, i32]
+        L.hca_pipeline_step.argtypes = [vp, C.POINTER(hca_layer), C.POINTER(i64), i64, i32, i64, i64, i64, f32,
+                                        C.POINTER(i64), i64, i32]
         L.hca_pipeline_scan_ms.restype = i32
         L.hca_pipeline_scan_ms.argtypes = [vp, i32, C.POINTER(f32)]
         L.hca_export_kcache.restype = i32
@@ -204,10 +204,11 @@ def hca_pipeline_destroy(handle):
 
 
 def hca_pipeline_step(handle, layers, n_resident, value_row0, k, host_stride, n_host_rows, hbm_stride, sm_scale,
-                      evict_M=0, n_protect=0, timing_slot=-1):
-    """layers: ctypes array of hca_layer; n_resident: ctypes int64 array [n_layers * batch] (both updated)."""
+                      evict_M=None, n_protect=0, timing_slot=-1):
+    """layers: ctypes array of hca_layer; n_resident: ctypes int64 array [n_layers * batch] (both updated);
+    evict_M: ctypes int64 array [n_layers] (0 = leave that layer alone) or None."""
     _check(lib().hca_pipeline_step(handle, layers, n_resident, int(value_row0), int(k), int(host_stride),
-                                   int(n_host_rows), int(hbm_stride), float(sm_scale), int(evict_M), int(n_protect),
+                                   int(n_host_rows), int(hbm_stride), float(sm_scale), evict_M, int(n_protect),
                                    int(timing_slot)), "hca_pipeline_step")
 
 

@@ -108,14 +108,14 @@ __global__ __launch_bounds__(256) void evict_positions(const float* __restrict__
 template <int BITS>
 __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __restrict__ kcache,
                                                     const float* __restrict__ acc, const int32_t* __restrict__ pos,
-                                                    int n_kv_heads, SelRows sr, int64_t M,
+                                                    int n_kv_heads, SelRows sr, int64_t M, int64_t d0, int64_t d1,
                                                     const int32_t* __restrict__ kept, EvictDst e) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t d = gid >> 2;
+  const int64_t d = d0 + (gid >> 2);
   const int j = (int)(gid & 3);
-  if (d >= M) return;
+  if (d >= d1) return;
   const int64_t s = kept[(int64_t)row * M + d];
   const uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
   const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
@@ -179,64 +179,126 @@ __global__ __launch_bounds__(256) void evict_carry_rows(Layout L, const uint8_t*
   }
 }
 
-int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
-                     int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst, float* acc_dst,
-                     int32_t* pos_dst, hipStream_t st) {
+// Eviction in two host-visible phases so that a step driver can interleave the pieces with other
+// work on the same stream: prepare (keep-set selection, positions, carry-over of untouched rows)
+// and move (destination slots [d0, d1) of the compaction; d1 == M finishes, with the copy-back
+// when the eviction is in place).
+struct EvictPlan {
   SelRows sr;
-  bool any = false;
+  EvictWs e;
+  EvictDst d;
+  int32_t* kept;
+  int64_t M, mblk;
+  bool oop, any;
+};
+
+static int32_t evict_prepare(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+                             int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst,
+                             float* acc_dst, int32_t* pos_dst, hipStream_t st, EvictPlan* pl) {
+  SelRows& sr = pl->sr;
+  pl->any = false;
   for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
   for (int b = 0; b < L.batch; ++b) {
     if (nr.n[b] > M) {
       sr.nsel[b] = nr.n[b] - n_protect;
       sr.want[b] = M - n_protect;
-      any = true;
+      pl->any = true;
     }
   }
-  const bool oop = kcache_dst != nullptr;
-  EvictWs e;
-  carve(&e, ws, L, M);
-  const int64_t mblk = mblk_of(L, M);
-  EvictDst d;
-  if (oop) {
+  pl->oop = kcache_dst != nullptr;
+  pl->M = M;
+  carve(&pl->e, ws, L, M);
+  pl->mblk = mblk_of(L, M);
+  EvictDst& d = pl->d;
+  if (pl->oop) {
     d.codes = (uint8_t*)kcache_dst;            d.codes_row = L.codes_row_bytes();
     d.meta = (uint8_t*)kcache_dst + L.meta_off; d.meta_row = L.meta_row_bytes();
     d.acc = acc_dst; d.pos = pos_dst; d.ap_row = L.cap;
   } else {
-    d.codes = e.codes; d.codes_row = mblk * kBlockBytes;
-    d.meta = e.meta;   d.meta_row = mblk * kMetaBytes;
-    d.acc = e.acc; d.pos = e.pos; d.ap_row = M;
+    d.codes = pl->e.codes; d.codes_row = pl->mblk * kBlockBytes;
+    d.meta = pl->e.meta;   d.meta_row = pl->mblk * kMetaBytes;
+    d.acc = pl->e.acc; d.pos = pl->e.pos; d.ap_row = M;
   }
-  if (oop && nmax > 0) {
+  if (pl->oop && nmax > 0) {
     const int64_t nblk = (nmax + L.tpb - 1) / L.tpb;
     int64_t items = nblk * (kBlockBytes / 16);
     if (items < nmax) items = nmax;
     dim3 gr((unsigned)((items + 255) / 256), (unsigned)L.rows);
     evict_carry_rows<<<gr, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, nr, d);
   }
-  if (!any) {
-    if (oop) HCA_HIP(hipGetLastError());
+  if (!pl->any) {
+    if (pl->oop) HCA_HIP(hipGetLastError());
     return HCA_OK;
   }
-  if (kept == nullptr) kept = e.kept;
+  pl->kept = kept != nullptr ? kept : pl->e.kept;
   SelectPlan p;
-  select_plan(&p, e.select, L.rows, nmax);
+  select_plan(&p, pl->e.select, L.rows, nmax);
   int32_t rc = select_run(p, acc, L.cap, L.rows, L.n_kv_heads, sr, st);
   if (rc != HCA_OK) return rc;
   dim3 g((unsigned)p.nchunks, (unsigned)L.rows);
-  evict_positions<<<g, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kept);
-  dim3 gg((unsigned)((M * 4 + 255) / 256), (unsigned)L.rows);
+  evict_positions<<<g, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, pl->kept);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+static int32_t evict_move(const Layout& L, void* kcache, float* acc, int32_t* pos, const EvictPlan& pl, int64_t d0,
+                          int64_t d1, hipStream_t st) {
+  if (!pl.any || d1 <= d0) return HCA_OK;
+  dim3 gg((unsigned)(((d1 - d0) * 4 + 255) / 256), (unsigned)L.rows);
   if (L.bits == 4)
-    evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, kept, d);
+    evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, d0, d1, pl.kept, pl.d);
   else
-    evict_gather<2><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, kept, d);
-  if (!oop) {
-    int64_t items = mblk * (kBlockBytes / 16);
-    if (items < M) items = M;
+    evict_gather<2><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, d0, d1, pl.kept, pl.d);
+  if (!pl.oop && d1 == pl.M) {
+    int64_t items = pl.mblk * (kBlockBytes / 16);
+    if (items < pl.M) items = pl.M;
     dim3 gc((unsigned)((items + 255) / 256), (unsigned)L.rows);
-    evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, sr, M, mblk, e);
+    evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, pl.mblk, pl.e);
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
+}
+
+int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+                     int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst, float* acc_dst,
+                     int32_t* pos_dst, hipStream_t st) {
+  EvictPlan pl;
+  int32_t rc = evict_prepare(L, kcache, acc, pos, nr, nmax, M, n_protect, kept, ws, kcache_dst, acc_dst, pos_dst, st, &pl);
+  if (rc != HCA_OK) return rc;
+  return evict_move(L, kcache, acc, pos, pl, 0, M, st);
+}
+
+// Sliced eviction for the step driver (out of place only): slice 0 prepares, every slice moves its
+// share of the destination slots.
+int32_t launch_evict_slice(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+                           int64_t M, int64_t n_protect, void* ws, void* kcache_dst, float* acc_dst,
+                           int32_t* pos_dst, int slice, int nslices, hipStream_t st) {
+  // the plan is a pure function of the arguments, so it is rebuilt for every slice; only slice 0 launches
+  // the preparation kernels
+  EvictPlan pl;
+  if (slice == 0) {
+    int32_t rc = evict_prepare(L, kcache, acc, pos, nr, nmax, M, n_protect, nullptr, ws, kcache_dst, acc_dst, pos_dst, st, &pl);
+    if (rc != HCA_OK) return rc;
+  } else {
+    SelRows& sr = pl.sr;
+    pl.any = false;
+    for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
+    for (int b = 0; b < L.batch; ++b)
+      if (nr.n[b] > M) { sr.nsel[b] = nr.n[b] - n_protect; sr.want[b] = M - n_protect; pl.any = true; }
+    pl.oop = true;
+    pl.M = M;
+    carve(&pl.e, ws, L, M);
+    pl.mblk = mblk_of(L, M);
+    pl.kept = pl.e.kept;
+    pl.d.codes = (uint8_t*)kcache_dst;             pl.d.codes_row = L.codes_row_bytes();
+    pl.d.meta = (uint8_t*)kcache_dst + L.meta_off;  pl.d.meta_row = L.meta_row_bytes();
+    pl.d.acc = acc_dst; pl.d.pos = pos_dst; pl.d.ap_row = L.cap;
+  }
+  const int64_t per = (M + nslices - 1) / nslices;
+  const int64_t d0 = per * slice;
+  int64_t d1 = d0 + per;
+  if (d1 > M) d1 = M;
+  return evict_move(L, kcache, acc, pos, pl, d0, d1, st);
 }
 
 }  // namespace hca

@@ -81,4 +81,8 @@ int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, co
                      int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst,
                      float* acc_dst, int32_t* pos_dst, hipStream_t st);
 
+int32_t launch_evict_slice(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+                           int64_t M, int64_t n_protect, void* ws, void* kcache_dst, float* acc_dst,
+                           int32_t* pos_dst, int slice, int nslices, hipStream_t st);
+
 }  // namespace hca

@@ -17,6 +17,15 @@ struct hca_pipeline {
   int timing_slots;
 };
 
+// an eviction in progress: its slices go out one at a time behind the attends of the following layers
+struct EvictJob {
+  bool active = false;
+  int layer = 0, next_slice = 0;
+  hca::NRes nr;
+  int64_t nmax = 0, M = 0;
+};
+constexpr int kEvictSlices = 6;
+
 using namespace hca;
 
 extern "C" {
@@ -67,19 +76,39 @@ void hca_pipeline_destroy(hca_pipeline* p) {
 
 int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_resident, int64_t value_row0, int32_t k,
                           int64_t host_stride, int64_t n_host_rows, int64_t hbm_stride, float sm_scale,
-                          int64_t evict_M, int64_t n_protect, int32_t timing_slot) {
+                          const int64_t* evict_M, int64_t n_protect, int32_t timing_slot) {
   if (p == nullptr || layers == nullptr || n_resident == nullptr) return HCA_ERR_BAD_ARG;
   const Layout& L = p->L;
   if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
-  if (evict_M != 0 && (evict_M < 1 || evict_M > L.cap || n_protect < 0 || n_protect > evict_M)) return HCA_ERR_CAPACITY;
-  if (evict_M != 0 && (p->d.ws_evict == nullptr || p->d.spare_kcache == nullptr || p->d.spare_acc == nullptr ||
-                       p->d.spare_pos == nullptr))
-    return HCA_ERR_BAD_ARG;
+  for (int l = 0; evict_M != nullptr && l < p->n_layers; ++l) {
+    if (evict_M[l] == 0) continue;
+    if (evict_M[l] < 1 || evict_M[l] > L.cap || n_protect < 0 || n_protect > evict_M[l]) return HCA_ERR_CAPACITY;
+    if (p->d.ws_evict == nullptr || p->d.spare_kcache == nullptr || p->d.spare_acc == nullptr ||
+        p->d.spare_pos == nullptr)
+      return HCA_ERR_BAD_ARG;
+  }
   if (timing_slot >= p->timing_slots) return HCA_ERR_BAD_ARG;
   hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk;
   hipStream_t sg = (hipStream_t)p->d.stream_gather, sc = (hipStream_t)p->d.stream_attend;
   NRes vrow0;
   for (int b = 0; b < kMaxBatch; ++b) vrow0.n[b] = value_row0;
+  EvictJob job;
+  // enqueues the next slice of `j` on the attend stream; the last slice swaps the layer's buffers with
+  // the spare set and releases the layer for the next step
+  auto advance = [&](EvictJob& j) -> int32_t {
+    hca_layer& jl = layers[j.layer];
+    int32_t rc = launch_evict_slice(L, jl.kcache, jl.acc, jl.pos, j.nr, j.nmax, j.M, n_protect, p->d.ws_evict,
+                                    p->d.spare_kcache, p->d.spare_acc, p->d.spare_pos, j.next_slice, kEvictSlices, sc);
+    if (rc != HCA_OK) return rc;
+    if (++j.next_slice == kEvictSlices) {
+      void* ok = jl.kcache; float* oa = jl.acc; int32_t* op = jl.pos;
+      jl.kcache = p->d.spare_kcache; jl.acc = p->d.spare_acc; jl.pos = p->d.spare_pos;
+      p->d.spare_kcache = ok; p->d.spare_acc = oa; p->d.spare_pos = op;
+      HCA_HIP(hipEventRecord(p->layer_done[j.layer], sc));
+      j.active = false;
+    }
+    return HCA_OK;
+  };
   for (int l = 0; l < p->n_layers; ++l) {
     hca_layer& ly = layers[l];
     int64_t* nl = n_resident + (int64_t)l * L.batch;
@@ -123,21 +152,32 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     rc = launch_attend_gathered(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, sm_scale, ly.y, ly.acc,
                                 p->d.ws_attend[s4], sc);
     if (rc != HCA_OK) return rc;
-    if (evict_M != 0) {
+    const int64_t M = evict_M != nullptr ? evict_M[l] : 0;
+    HCA_HIP(hipEventRecord(p->pipe_free[s4], sc));
+    bool starts_job = false;
+    if (M != 0) {
       bool any = false;
-      for (int b = 0; b < L.batch; ++b) any = any || nr.n[b] > evict_M;
+      for (int b = 0; b < L.batch; ++b) any = any || nr.n[b] > M;
       if (any) {
-        rc = launch_evict(L, ly.kcache, ly.acc, ly.pos, nr, nmax, evict_M, n_protect, nullptr, p->d.ws_evict,
-                          p->d.spare_kcache, p->d.spare_acc, p->d.spare_pos, sc);
-        if (rc != HCA_OK) return rc;
-        void* ok = ly.kcache; float* oa = ly.acc; int32_t* op = ly.pos;
-        ly.kcache = p->d.spare_kcache; ly.acc = p->d.spare_acc; ly.pos = p->d.spare_pos;
-        p->d.spare_kcache = ok; p->d.spare_acc = oa; p->d.spare_pos = op;
-        for (int b = 0; b < L.batch; ++b) if (nl[b] > evict_M) nl[b] = evict_M;
+        // one spare set: finish a job still in flight before the next one starts
+        while (job.active) {
+          rc = advance(job);
+          if (rc != HCA_OK) return rc;
+        }
+        job.active = true; job.layer = l; job.next_slice = 0; job.nr = nr; job.nmax = nmax; job.M = M;
+        starts_job = true;
+        for (int b = 0; b < L.batch; ++b) if (nl[b] > M) nl[b] = M;
       }
     }
-    HCA_HIP(hipEventRecord(p->pipe_free[s4], sc));
-    HCA_HIP(hipEventRecord(p->layer_done[l], sc));
+    if (job.active) {                      // one slice of the eviction in flight rides behind this attend
+      rc = advance(job);
+      if (rc != HCA_OK) return rc;
+    }
+    if (!starts_job) HCA_HIP(hipEventRecord(p->layer_done[l], sc));   // else the job's last slice records it
+  }
+  while (job.active) {                     // the step ends with every started eviction fully enqueued
+    int32_t rc = advance(job);
+    if (rc != HCA_OK) return rc;
   }
   return HCA_OK;
 }

@@ -354,3 +354,105 @@ def test_kernels_are_deterministic(H):
         outs.append((st.kcache.cpu(), st.z.cpu(), st.idx.cpu().clone(), st.y.cpu()))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
+
+
+def test_native_step_driver_matches_oracle(H, oracle):
+    """hca_pipeline_step over 3 layers, 12 decode steps, staggered sliced eviction every 4 steps:
+    every layer's output, resident count and final cache state against the oracle run layer by layer."""
+    import ctypes as C
+    from paper_2507_19823_amd import binding as B
+    Lr, steps, E = 3, 12, 4
+    w = S.Workload("drv", 7, 2, 8, 2, 1500, 4, 32, 96)
+    R, n0 = w.batch * w.n_kv_heads, w.n
+    cap, vnew = n0 + E + 16, steps + 4
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    dev = "cuda"
+    kb = B.hca_kcache_bytes(shape)
+    data = [S.make_layer(w, l) for l in range(Lr)]
+    kc = [torch.zeros(kb, dtype=torch.uint8, device=dev) for _ in range(Lr + 1)]
+    acc = [torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev) for _ in range(Lr + 1)]
+    pos = [torch.arange(cap, dtype=torch.int32, device=dev).repeat(w.batch, w.n_kv_heads, 1).contiguous()
+           for _ in range(Lr + 1)]
+    vh = [d["values"].contiguous().pin_memory() for d in data]
+    vd = [torch.zeros(w.batch, w.n_kv_heads, vnew, 128, dtype=torch.float16, device=dev) for _ in range(Lr)]
+    y = torch.zeros(Lr, w.batch, w.n_q_heads, 128, dtype=torch.float32, device=dev)
+    ocs, oacc, opos, oV = [], [], [], []
+    for l in range(Lr):
+        B.hca_quantize_keys(shape, kc[l], data[l]["keys"].cuda(), n0, [0] * w.batch)
+        oc = oracle.Cache(R, cap, 128, 4, 32)
+        oracle.quantize(oc, _rows(data[l]["keys"]))
+        ocs.append(oc)
+        oacc.append(np.zeros((R, cap), np.float32))
+        p = np.zeros((R, cap), np.int32)
+        p[:] = np.arange(cap)
+        opos.append(p)
+        V = np.zeros((R, n0 + vnew, 128), np.float16)
+        V[:, :n0] = _rows(data[l]["values"])
+        oV.append(V)
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    d = B.hca_pipeline_desc()
+    d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
+    wsb = B.hca_workspace_bytes(shape, w.k, n0)
+    keep = []
+    for i in range(3):
+        t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev); keep.append(t); d.sel[i] = t.data_ptr()
+    for i in range(4):
+        a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
+        b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
+        c = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+        keep += [a, b, c]
+        d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), c.data_ptr()
+    wt, we = torch.zeros(wsb, dtype=torch.uint8, device=dev), torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
+    d.spare_kcache, d.spare_acc, d.spare_pos = kc[Lr].data_ptr(), acc[Lr].data_ptr(), pos[Lr].data_ptr()
+    pl = B.hca_pipeline_create(shape, Lr, d, 0)
+    layers = (B.hca_layer * Lr)()
+    for l in range(Lr):
+        layers[l].kcache, layers[l].acc, layers[l].pos = kc[l].data_ptr(), acc[l].data_ptr(), pos[l].data_ptr()
+        layers[l].v_host, layers[l].v_hbm, layers[l].y = vh[l].data_ptr(), vd[l].data_ptr(), y[l].data_ptr()
+    nres = (C.c_int64 * (Lr * w.batch))(*([n0] * (Lr * w.batch)))
+    sm = 1.0 / math.sqrt(128.0)
+    for t in range(steps):
+        ins = [S.make_step(w, l, t) for l in range(Lr)]
+        kn = [x[0].cuda() for x in ins]
+        qs = [x[2].cuda() for x in ins]
+        for l in range(Lr):
+            vd[l][:, :, t] = ins[l][1][:, :, 0].cuda()
+            layers[l].k_new, layers[l].q = kn[l].data_ptr(), qs[l].data_ptr()
+        due = [(t + 1 + l) % E == 0 for l in range(Lr)]
+        ev = (C.c_int64 * Lr)(*[n0 if x else 0 for x in due])
+        torch.cuda.synchronize()
+        B.hca_pipeline_step(pl, layers, nres, n0 + t, w.k, n0, n0, vnew, sm, ev, E, -1)
+        torch.cuda.synchronize()
+        for l in range(Lr):
+            oc = ocs[l]
+            n = int(oc.n[0])
+            oV[l][:, n0 + t] = _rows(ins[l][1])[:, 0]
+            opos[l][:, n] = n0 + t
+            oacc[l][:, n] = 0
+            oracle.quantize(oc, _rows(ins[l][0]))
+            q16 = ins[l][2].numpy().reshape(-1, 128)
+            sel, _ = oracle.score(oc, q16, want_z=False)
+            idx, count = oracle.topk(sel, oc.n, w.k)
+            yo, _ = oracle.attend(oc, q16, idx, count, opos[l], oV[l], np.float32(sm), acc=oacc[l])
+            assert _rel_err(y[l].cpu().numpy().reshape(-1, 128), yo) <= TOL, f"step {t} layer {l}"
+            if due[l]:
+                # stage-wise: the oracle evicts on its own accumulated scores; both sides must keep the same slots
+                oracle.evict(oc, oacc[l], opos[l], n0, E)
+            assert nres[l * w.batch] == int(oc.n[0]), f"step {t} layer {l}"
+    # final cache state of every layer (pointers may have swapped with the spare set)
+    bufs = {kc[i].data_ptr(): (kc[i], acc[i], pos[i]) for i in range(Lr + 1)}
+    for l in range(Lr):
+        k_t, a_t, p_t = bufs[layers[l].kcache]
+        assert layers[l].acc == a_t.data_ptr() and layers[l].pos == p_t.data_ptr()
+        n = int(ocs[l].n[0])
+        cb = torch.zeros(w.batch, w.n_kv_heads, cap, 64, dtype=torch.uint8, device=dev)
+        sc = torch.zeros(w.batch, w.n_kv_heads, cap, 4, dtype=torch.float16, device=dev)
+        zr = torch.zeros_like(sc)
+        B.hca_export_kcache(shape, k_t, [n] * w.batch, cb, sc, zr)
+        torch.cuda.synchronize()
+        assert np.array_equal(_rows(cb)[:, :n], ocs[l].codes[:, :n])
+        assert np.array_equal(_rows(sc).view(np.uint16)[:, :n], ocs[l].scale[:, :n])
+        assert np.array_equal(_rows(p_t)[:, :n], opos[l][:, :n])
+        assert np.allclose(_rows(a_t)[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-6)
+    B.hca_pipeline_destroy(pl)
