@@ -175,6 +175,10 @@ class Model:
             d.count[i] = self.pipe[i]["count"].data_ptr()
             d.ws_attend[i] = self.pipe[i]["ws"].data_ptr()
         d.ws_topk, d.ws_evict = self.ws_topk.data_ptr(), self.ws_main.data_ptr()
+        if timing_slots > 0:
+            pairs = B.hca_scan_stamp_pairs(self.shape, self.cap)
+            self.stamps = self.torch.zeros(timing_slots, self.L, pairs, 2, dtype=self.torch.int64, device="cuda")
+            d.scan_stamps, d.scan_stamp_pairs = self.stamps.data_ptr(), pairs
         d.spare_kcache, d.spare_acc, d.spare_pos = (x.data_ptr() for x in self.spare)
         self.pl = B.hca_pipeline_create(self.shape, self.L, d, timing_slots)
         self.pl_layers = (B.hca_layer * self.L)()
@@ -405,6 +409,8 @@ def main():
                     help="native: the library's four-stage step driver; staged: the same pipeline enqueued from Python; "
                          "gather: only the gather overlaps; none: serial")
     ap.add_argument("--no-latency", action="store_true", help="skip the per-layer latency probes at 128K / 1M / 4M")
+    ap.add_argument("--stages", type=int, default=4, choices=[3, 4],
+                    help="native pipeline: 4 = scan | top-k | gather | attend; 3 = top-k shares the scan stream")
     ap.add_argument("--mode", default="step", choices=["step", "scan"],
                     help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration")
     args = ap.parse_args()
@@ -463,7 +469,7 @@ def main():
     main, side = main_s[0], gath_s[0]
 
     if args.pipeline == "native":
-        model.native_pipeline(main, extra[0], side, extra[1], args.steps)
+        model.native_pipeline(main, main if args.stages == 3 else extra[0], side, extra[1], args.steps)
 
     def run_step(t, ev=None):
         if args.pipeline == "native":
@@ -489,9 +495,17 @@ def main():
     ms_per_step = dt * 1e3 / args.steps
     tokens_per_step = w.batch * w.n * L
     value = tokens_per_step / (dt / args.steps)
+    bracket_ms = None
     if args.pipeline == "native":
+        # event bracket around each scan launch (includes the wait for the other stages' kernels to make
+        # room) and the kernel's own duration from the per-wave wall-clock stamps (first start to last end)
         per = [x for slot in range(args.steps) for x in B.hca_pipeline_scan_ms(model.pl, slot, L)]
-        scan_ms = sum(per) / len(per)
+        bracket_ms = sum(per) / len(per)
+        st_ = model.stamps
+        starts = torch.where(st_[..., 0] > 0, st_[..., 0], torch.full_like(st_[..., 0], 1 << 62)).amin(-1)
+        ends = st_[..., 1].amax(-1)
+        khz = B.hca_wall_clock_khz()
+        scan_ms = float((ends - starts).double().mean()) / khz
     else:
         events = [e for step_events in events for e in step_events]
         scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
@@ -520,7 +534,8 @@ def main():
         "host_link_peak_GBs": link_peak,
         "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes},
+                     "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes,
+                     "avg_event_bracket_ms": bracket_ms},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = run_cpu_baseline(model, w)

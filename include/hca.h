@@ -204,6 +204,10 @@ typedef struct {
   void* ws_topk;                 /* device, hca_workspace_bytes(shape, k, 1) */
   void* ws_evict;                /* device, hca_workspace_bytes(shape, k, M); NULL if eviction is never asked for */
   void* spare_kcache; float* spare_acc; int32_t* spare_pos;   /* spare set for out-of-place eviction, or NULL */
+  /* optional profiling of the key scan: device, uint64 [timing_slots][n_layers][scan_stamp_pairs][2];
+     every wave of a timed scan launch stores its start and end wall-clock tick there (zero-filled by the
+     caller; entries left 0 belong to waves that had nothing to do).  NULL: off. */
+  void* scan_stamps; int64_t scan_stamp_pairs;
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;
@@ -223,6 +227,11 @@ void hca_pipeline_destroy(hca_pipeline* p);
 int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_resident, int64_t value_row0, int32_t k,
                           int64_t host_stride, int64_t n_host_rows, int64_t hbm_stride, float sm_scale,
                           const int64_t* evict_M, int64_t n_protect, int32_t timing_slot);
+
+/* (start, end) pairs a key-scan launch over n_tokens resident tokens may write into scan_stamps. */
+int64_t hca_scan_stamp_pairs(const hca_shape* shape, int64_t n_tokens);
+/* Rate of the wall clock behind scan_stamps in kHz (0 if unknown). */
+int32_t hca_wall_clock_khz(void);
 
 /* After the device has finished the step recorded in `timing_slot`: duration of each layer's
  * key-scan launch in milliseconds, ms[n_layers] (host). */

@@ -39,7 +39,7 @@ class hca_pipeline_desc(C.Structure):
                 ("stream_attend", C.c_void_p), ("sel", C.c_void_p * 3), ("idx", C.c_void_p * 4),
                 ("count", C.c_void_p * 4), ("ws_attend", C.c_void_p * 4), ("ws_topk", C.c_void_p),
                 ("ws_evict", C.c_void_p), ("spare_kcache", C.c_void_p), ("spare_acc", C.c_void_p),
-                ("spare_pos", C.c_void_p)]
+                ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64)]
 
 
 _lib = None
@@ -83,6 +83,9 @@ def lib():
         L.hca_pipeline_step.restype = i32
         L.hca_pipeline_step.argtypes = [vp, C.POINTER(hca_layer), C.POINTER(i64), i64, i32, i64, i64, i64, f32,
                                         C.POINTER(i64), i64, i32]
+        L.hca_scan_stamp_pairs.restype = i64
+        L.hca_scan_stamp_pairs.argtypes = [sp, i64]
+        L.hca_wall_clock_khz.restype = i32
         L.hca_pipeline_scan_ms.restype = i32
         L.hca_pipeline_scan_ms.argtypes = [vp, i32, C.POINTER(f32)]
         L.hca_export_kcache.restype = i32
@@ -216,3 +219,11 @@ def hca_pipeline_scan_ms(handle, timing_slot, n_layers):
     out = (C.c_float * n_layers)()
     _check(lib().hca_pipeline_scan_ms(handle, int(timing_slot), out), "hca_pipeline_scan_ms")
     return list(out)
+
+
+def hca_scan_stamp_pairs(shape, n_tokens):
+    return int(lib().hca_scan_stamp_pairs(C.byref(shape), int(n_tokens)))
+
+
+def hca_wall_clock_khz():
+    return int(lib().hca_wall_clock_khz())

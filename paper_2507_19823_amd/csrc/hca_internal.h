@@ -62,7 +62,8 @@ int32_t launch_quantize(const Layout& L, void* kcache, const void* k_new, int64_
 int32_t launch_export(const Layout& L, const void* kcache, const NRes& nr, uint8_t* codes, void* scale,
                       void* zero, hipStream_t st);
 int32_t launch_score(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                     float* sel, float* z_opt, hipStream_t st);
+                     float* sel, float* z_opt, hipStream_t st, uint64_t* stamps = nullptr);
+int64_t score_stamp_pairs(const Layout& L, int64_t nmax);
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
                     int32_t* idx, int32_t* count, void* ws, hipStream_t st);
 size_t attend_workspace_bytes(const Layout& L, int64_t k);

@@ -130,7 +130,12 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
     nmax += 1;
     if (timing_slot >= 0) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
-    rc = launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa);
+    uint64_t* stamps = nullptr;
+    if (timing_slot >= 0 && p->d.scan_stamps != nullptr) {
+      if (p->d.scan_stamp_pairs < score_stamp_pairs(L, nmax)) return HCA_ERR_CAPACITY;
+      stamps = (uint64_t*)p->d.scan_stamps + ((int64_t)timing_slot * p->n_layers + l) * p->d.scan_stamp_pairs * 2;
+    }
+    rc = launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps);
     if (rc != HCA_OK) return rc;
     if (timing_slot >= 0) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
     HCA_HIP(hipEventRecord(p->score_done[s3], sa));
@@ -180,6 +185,19 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (rc != HCA_OK) return rc;
   }
   return HCA_OK;
+}
+
+int64_t hca_scan_stamp_pairs(const hca_shape* shape, int64_t n_tokens) {
+  Layout L;
+  if (make_layout(shape, &L) != HCA_OK || n_tokens < 0) return 0;
+  return score_stamp_pairs(L, n_tokens);
+}
+
+int32_t hca_wall_clock_khz(void) {
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess) return 0;
+  return khz;
 }
 
 int32_t hca_pipeline_scan_ms(hca_pipeline* p, int32_t timing_slot, float* ms) {

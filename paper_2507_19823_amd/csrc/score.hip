@@ -45,7 +45,8 @@ __device__ __forceinline__ uint4 allgather_rows(uint32_t v) {
 template <int BITS, bool WRITE_Z, int U>
 __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __restrict__ kcache,
                                                     const uint16_t* __restrict__ q, NRes nr, int bpw,
-                                                    float* __restrict__ sel, float* __restrict__ z) {
+                                                    float* __restrict__ sel, float* __restrict__ z,
+                                                    uint64_t* __restrict__ stamps) {
   static_assert(U % 4 == 0, "stores are batched four tiles at a time");
   __shared__ QShared sh;
   const int row = blockIdx.y;
@@ -54,6 +55,9 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nblocks = (int)((n + L.tpb - 1) / L.tpb);
   if ((int64_t)blockIdx.x * 4 * bpw >= nblocks) return;  // whole workgroup past the end
+  // optional profiling: every wave leaves its start and end time (constant-rate wall clock)
+  uint64_t* stamp = stamps ? stamps + (((int64_t)row * gridDim.x + blockIdx.x) * 4 + w) * 2 : nullptr;
+  if (stamp && lane == 0) stamp[0] = wall_clock64();
   const int wave_first = (blockIdx.x * 4 + w) * bpw;
   int wave_end = wave_first + bpw;
   if (wave_end > nblocks) wave_end = nblocks;
@@ -153,10 +157,17 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
       if (hd == 1 && b0 * 32 + 16 + t < ntok) selrow[b0 * 32 + 16 + t] = hi;
     }
   }
+  if (stamp && lane == 0) stamp[1] = wall_clock64();
+}
+
+// number of (start, end) stamp pairs a scan launch over nmax tokens writes at most
+int64_t score_stamp_pairs(const Layout& L, int64_t nmax) {
+  const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
+  return (nblocks / 4 + 1) * 4 * L.rows;      // >= grid.x * 4 waves * rows for any blocks-per-wave >= 4
 }
 
 int32_t launch_score(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                     float* sel, float* z_opt, hipStream_t st) {
+                     float* sel, float* z_opt, hipStream_t st, uint64_t* stamps) {
   if (nmax == 0) return HCA_OK;
   const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
   // aim at ~16 waves per SIMD over the whole chip when the cache is large, >= 4 blocks per wave
@@ -169,7 +180,7 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
   dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
   const uint8_t* kc = (const uint8_t*)kcache;
   const uint16_t* qq = (const uint16_t*)q;
-#define HCA_SCORE(B, Z, U) score_kernel<B, Z, U><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, z_opt)
+#define HCA_SCORE(B, Z, U) score_kernel<B, Z, U><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, z_opt, stamps)
 #define HCA_SCORE_U(B, Z)                                  \
   do {                                                     \
     if (tn.score_depth >= 8) HCA_SCORE(B, Z, 8);           \
