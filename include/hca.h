@@ -201,7 +201,8 @@ typedef struct {
   int32_t* idx[4];               /* device, int32 [batch, n_kv_heads, k] each */
   int32_t* count[4];             /* device, int32 [batch, n_kv_heads] each */
   void* ws_attend[4];            /* device, hca_workspace_bytes(shape, k, 1) each */
-  void* ws_topk;                 /* device, hca_workspace_bytes(shape, k, 1) */
+  void* ws_topk;                 /* device, hca_workspace_bytes(shape, k, 1); owned by the driver from
+                                    hca_pipeline_create on (it keeps a histogram there between steps) */
   void* ws_evict;                /* device, hca_workspace_bytes(shape, k, M); NULL if eviction is never asked for */
   void* spare_kcache; float* spare_acc; int32_t* spare_pos;   /* spare set for out-of-place eviction, or NULL */
   /* optional profiling of the key scan: device, uint64 [timing_slots][n_layers][scan_stamp_pairs][2];

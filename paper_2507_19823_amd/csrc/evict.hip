@@ -219,7 +219,9 @@ static int32_t evict_prepare(const Layout& L, void* kcache, float* acc, int32_t*
     d.meta = pl->e.meta;   d.meta_row = pl->mblk * kMetaBytes;
     d.acc = pl->e.acc; d.pos = pl->e.pos; d.ap_row = M;
   }
-  if (pl->oop && nmax > 0) {
+  bool carry = false;                      // any row that is not compacted?
+  for (int b = 0; b < L.batch; ++b) carry = carry || nr.n[b] <= M;
+  if (pl->oop && carry && nmax > 0) {
     const int64_t nblk = (nmax + L.tpb - 1) / L.tpb;
     int64_t items = nblk * (kBlockBytes / 16);
     if (items < nmax) items = nmax;

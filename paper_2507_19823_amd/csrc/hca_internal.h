@@ -26,7 +26,7 @@ struct Tuning {
   int gather_wgs = 0;      // workgroups of the value gather per row (0 = default)
   int gather_unroll = 4;   // rows in flight per thread
   int score_bpw = 0;       // 1 KiB code blocks per wave (0 = automatic)
-  int score_depth = 8;     // blocks fetched ahead per wave (4 or 8)
+  int score_depth = 0;     // blocks fetched ahead per wave (4 or 8; 0 = 8 for 4-bit codes, 4 for 2-bit)
 };
 Tuning& tuning();
 
@@ -65,7 +65,8 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
                      float* sel, float* z_opt, hipStream_t st, uint64_t* stamps = nullptr);
 int64_t score_stamp_pairs(const Layout& L, int64_t nmax);
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
-                    int32_t* idx, int32_t* count, void* ws, hipStream_t st);
+                    int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean = false);
+size_t topk_hist_bytes(int rows);
 size_t attend_workspace_bytes(const Layout& L, int64_t k);
 int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                       const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,

@@ -57,6 +57,11 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   p->t1.resize((size_t)timing_slots * n_layers);
   for (size_t i = 0; i < p->t0.size(); ++i) { mk(&p->t0[i], hipEventDefault); mk(&p->t1[i], hipEventDefault); }
   if (!ok) { delete p; return nullptr; }   // events already made are left to process teardown
+  // the top-k histogram at the head of ws_topk starts clean and is kept clean by every selection
+  if (hipMemsetAsync(desc->ws_topk, 0, topk_hist_bytes(L.rows), (hipStream_t)desc->stream_topk) != hipSuccess) {
+    delete p;
+    return nullptr;
+  }
   return p;
 }
 
@@ -142,7 +147,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     // stage 2: top-k
     HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
     HCA_HIP(hipStreamWaitEvent(sb, p->pipe_free[s4], 0));    // attend of the previous user of idx / staging
-    rc = launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb);
+    rc = launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb, true);
     if (rc != HCA_OK) return rc;
     HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
     HCA_HIP(hipEventRecord(p->topk_done[s4], sb));

@@ -175,15 +175,19 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
   const Tuning& tn = tuning();
   int64_t bpw = total / (256 * 4 * 16);
   if (bpw < 4) bpw = 4;
-  if (bpw > 16) bpw = 16;
+  // measured best on MI355X: 4-bit codes 8 blocks ahead, 16 per wave; 2-bit codes (two tiles per block,
+  // more registers) 4 ahead, 32 per wave
+  const int64_t bpw_max = L.bits == 4 ? 16 : 32;
+  if (bpw > bpw_max) bpw = bpw_max;
   if (tn.score_bpw > 0) bpw = tn.score_bpw;
+  const int depth = tn.score_depth > 0 ? tn.score_depth : (L.bits == 4 ? 8 : 4);
   dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
   const uint8_t* kc = (const uint8_t*)kcache;
   const uint16_t* qq = (const uint16_t*)q;
 #define HCA_SCORE(B, Z, U) score_kernel<B, Z, U><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, z_opt, stamps)
 #define HCA_SCORE_U(B, Z)                                  \
   do {                                                     \
-    if (tn.score_depth >= 8) HCA_SCORE(B, Z, 8);           \
+    if (depth >= 8) HCA_SCORE(B, Z, 8);                    \
     else HCA_SCORE(B, Z, 4);                               \
   } while (0)
   if (L.bits == 4) {

@@ -348,10 +348,15 @@ __global__ __launch_bounds__(256) void tk_findbin(int n_kv_heads, SelRows sr, To
   const int row = blockIdx.x;
   const int64_t want = sr.want[row / n_kv_heads];
   if (want <= 0) return;
-  const uint32_t* gh = t.hist + (int64_t)row * kBins12;
+  uint32_t* gh = t.hist + (int64_t)row * kBins12;
   uint32_t h[16], sum = 0;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) { h[i] = gh[kBins12 - 1 - (16 * threadIdx.x + i)]; sum += h[i]; }
+  for (int i = 0; i < 16; ++i) {
+    const int b = kBins12 - 1 - (16 * threadIdx.x + i);
+    h[i] = gh[b];
+    gh[b] = 0;                 // leave the histogram clean for the next selection on this workspace
+    sum += h[i];
+  }
   uint32_t running = block_scan_excl_256(sum, wsum);
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
@@ -603,8 +608,10 @@ __global__ __launch_bounds__(256) void tk_emit_lists(int64_t chunk, int nchunks,
   }
 }
 
+size_t topk_hist_bytes(int rows) { return (size_t)rows * kBins12 * 4; }
+
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
-                    int32_t* idx, int32_t* count, void* ws, hipStream_t st) {
+                    int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean) {
   SelRows sr;
   for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
   for (int b = 0; b < L.batch; ++b) {
@@ -620,7 +627,9 @@ int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t n
   dim3 g((unsigned)nchunks, (unsigned)L.rows);
   if (nmax > 0) {
     const int64_t nz = (int64_t)L.rows * kBins12;
-    tk_zero<<<(unsigned)((nz + 255) / 256), 256, 0, st>>>(t.hist, nz);
+    // the histogram sits at the start of the workspace; tk_findbin clears what it reads, so a caller
+    // that zeroed it once and uses the workspace for nothing else (the step driver) skips this launch
+    if (!hist_clean) tk_zero<<<(unsigned)((nz + 255) / 256), 256, 0, st>>>(t.hist, nz);
     // fewer, larger workgroups for the histogram: each flushes its bins with global atomics, and
     // atomics to one address serialise
     dim3 gh((unsigned)((nchunks + 3) / 4), (unsigned)L.rows);
