@@ -456,3 +456,54 @@ def test_native_step_driver_matches_oracle(H, oracle):
         assert np.array_equal(_rows(p_t)[:, :n], opos[l][:, :n])
         assert np.allclose(_rows(a_t)[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-6)
     B.hca_pipeline_destroy(pl)
+
+
+@pytest.mark.parametrize("bits,gs,G,k,n", [(2, 64, 4, 512, 9000), (2, 64, 2, 100, 3001), (4, 32, 2, 16384, 20000),
+                                           (4, 32, 1, 1, 100), (2, 64, 1, 777, 777)])
+def test_small_pipelines_other_shapes(H, oracle, bits, gs, G, k, n):
+    """2-bit codes, 1 / 2 / 4 query heads per KV head, k = 1, k = n and the largest supported k."""
+    w = S.Workload("p", 200 + bits + G, 2, 2 * G, 2, n, bits, gs, k, planted=4)
+    d = S.make_layer(w)
+    R = w.batch * w.n_kv_heads
+    st = _state(H, w, want_z=True)
+    oc = _ocache(oracle, w, n)
+    st.quantize(d["keys"].cuda())
+    oracle.quantize(oc, _rows(d["keys"]))
+    qd = d["q"].cuda()
+    st.score(qd)
+    st.topk(k)
+    nh = n // 3
+    vh = d["values"][:, :, :nh].contiguous().pin_memory()
+    vd = d["values"][:, :, nh:].contiguous().cuda()
+    st.attend(qd, vh, nh, vd, use_acc=True, gather_stream=torch.cuda.Stream())
+    torch.cuda.synchronize()
+    q16 = d["q"].numpy().reshape(-1, 128)
+    sel, z = oracle.score(oc, q16)
+    assert np.array_equal(st.z.cpu().numpy().reshape(-1, n), z)
+    idx, count = oracle.topk(sel, oc.n, k)
+    assert np.array_equal(_rows(st.idx), idx)
+    pos = np.tile(np.arange(n, dtype=np.int32), (R, 1))
+    acc = np.zeros((R, n), np.float32)
+    y, _ = oracle.attend(oc, q16, idx, count, pos, _rows(d["values"]), st.sm_scale, acc=acc)
+    assert _rel_err(st.y.cpu().numpy().reshape(-1, 128), y) <= TOL
+    assert np.allclose(_rows(st.acc), acc, rtol=1e-4, atol=1e-7)
+
+
+def test_clustered_heavy_hitters_in_one_chunk(H, oracle):
+    """All the large scores sit in one 4096-slot chunk (what eviction produces when it packs the ever-selected
+    tokens together): the chunk's candidate list is long, the result must not change."""
+    from paper_2507_19823_amd import binding as B
+    rng = np.random.default_rng(5)
+    n, k = 40000, 3000
+    v = rng.standard_normal((4, n)).astype(np.float32)
+    v[:, 36000:40000] += 6.0                      # ~4000 of the top values in the last chunk
+    v[1, 36000:39000] = 7.5                       # and a mass tie there
+    shape = B.make_shape(2, 8, 2, n)
+    sel = torch.from_numpy(v).cuda()
+    idx = torch.full((4, k), -9, dtype=torch.int32, device="cuda")
+    count = torch.zeros(4, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(shape, k, 1), dtype=torch.uint8, device="cuda")
+    B.hca_topk(shape, sel, [n, n], k, idx, count, ws)
+    torch.cuda.synchronize()
+    ridx, _ = oracle.topk(v, np.full(4, n), k)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
