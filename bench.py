@@ -29,7 +29,7 @@ def log(*a):
 class Model:
     """All layers of one workload: per-layer key cache / acc / pos / host values, shared scratch."""
 
-    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2):
+    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3):
         import torch
         from paper_2507_19823_amd import binding as B
         self.torch, self.B, self.w = torch, B, w
@@ -54,7 +54,8 @@ class Model:
         self.v_host = [None] * layers
         self.v_hbm = [torch.zeros(w.batch, w.n_kv_heads, self.vnew, 128, dtype=torch.float16, device=dev)
                       for _ in range(layers)]
-        self.sels = [torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev) for _ in range(3)]
+        self.sels = [torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev)
+                     for _ in range(max(3, n_sel))]
         self.sel = self.sels[0]
         self.sel_ev = [dict(score_done=torch.cuda.Event(), sel_free=torch.cuda.Event()) for _ in range(3)]
         self.ws_main = torch.empty(B.hca_workspace_bytes(self.shape, w.k, self.n0), dtype=torch.uint8, device=dev)
@@ -161,15 +162,17 @@ class Model:
             self.kcache[l], self.acc[l], self.pos[l] = sk, sa_, sp
             self.n[l] = [min(x, self.n0) for x in self.n[l]]
 
-    def native_pipeline(self, sa, sb, sg, sc, timing_slots):
+    def native_pipeline(self, sa, sb, sg, sc, timing_slots, timing_stride=1):
         """Hands the four streams and the pipeline buffers to the library's step driver."""
         import ctypes as C
         B, w = self.B, self.w
         d = B.hca_pipeline_desc()
         d.stream_scan, d.stream_topk = sa.cuda_stream, sb.cuda_stream
         d.stream_gather, d.stream_attend = sg.cuda_stream, sc.cuda_stream
-        for i in range(3):
-            d.sel[i] = self.sels[i].data_ptr()
+        for i, sbuf in enumerate(self.sels):
+            d.sel[i] = sbuf.data_ptr()
+        d.n_sel = len(self.sels)
+        d.timing_layer_stride = timing_stride
         for i in range(4):
             d.idx[i] = self.pipe[i]["idx"].data_ptr()
             d.count[i] = self.pipe[i]["count"].data_ptr()
@@ -318,6 +321,77 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8):
     return out
 
 
+def per_layer_latency_grouped(cfg, groups, streams, iters=8):
+    """One layer of BASELINE config `cfg` with its rows (sequences x KV heads) cut into `groups` parts that
+    go through the four stages as a pipeline: the gather of one part overlaps the scan of the next.  Unlike
+    the overlap across layers this is legal in a real model, where the next layer's query does not exist yet:
+    all parts belong to the same layer and use the same query.  The parts are handed to the step driver as its
+    "layers".  The enqueue of the whole layer is hidden behind a spinning gate kernel on the scan stream, as a
+    serving loop would hide it behind the preceding non-attention work; the time runs from the gate's end to
+    the last part's y."""
+    import dataclasses
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    w = S.CONFIGS[cfg]
+    gb = min(groups, w.batch)
+    gh = groups // gb
+    assert gb * gh == groups and w.batch % gb == 0 and w.n_kv_heads % gh == 0
+    wg = dataclasses.replace(w, name=f"{w.name}/{groups}parts", batch=w.batch // gb,
+                             n_q_heads=w.n_q_heads // gh, n_kv_heads=w.n_kv_heads // gh)
+    warm = 3
+    m = Model(wg, groups, 0, iters + warm, n_sel=groups)
+    m.build(groups)
+    m.make_steps(iters + warm)
+    sa, sb, sg, sc = streams
+    m.native_pipeline(sa, sb, sg, sc, 0)
+    t = 0
+    for _ in range(2):
+        m.decode_step_native(t)
+        t += 1
+    torch.cuda.synchronize()
+    if cfg == 5:
+        for l in range(groups):
+            n_l = [m.pl_n[l * wg.batch + b] for b in range(wg.batch)]
+            B.hca_evict(m.shape, m.kcache[l], m.acc[l], m.pos[l], n_l, w.evict_keep, 2, None, m.ws_main,
+                        None, None, None, sa)
+            for b in range(wg.batch):
+                m.pl_n[l * wg.batch + b] = w.evict_keep
+        torch.cuda.synchronize()
+    m.decode_step_native(t)
+    t += 1
+    torch.cuda.synchronize()
+    # gate length: long enough for the host to enqueue every part
+    with torch.cuda.stream(sa):
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record(sa)
+        torch.cuda._sleep(1_000_000)
+        c1.record(sa)
+    torch.cuda.synchronize()
+    cycles_per_ms = 1_000_000 / c0.elapsed_time(c1)
+    gate = int(cycles_per_ms * (0.5 + 0.35 * groups))
+    lat = []
+    for i in range(iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(sa):
+            torch.cuda._sleep(gate)
+        e0.record(sa)
+        h0 = time.perf_counter()
+        m.decode_step_native(t + i)
+        host_ms = (time.perf_counter() - h0) * 1e3
+        e1.record(sc)
+        torch.cuda.synchronize()
+        lat.append((e0.elapsed_time(e1), host_ms))
+    lat.sort()
+    ms, host_ms = lat[iters // 2]
+    B.hca_pipeline_destroy(m.pl)
+    del m
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()
+    return {"parts": groups, "ms_per_layer": ms, "host_enqueue_ms": host_ms, "gate_ms": gate / cycles_per_ms}
+
+
 def scan_only(w, iters):
     """Key-scan kernel alone on one layer (two cache copies alternate), preceded by a plain 1 GiB
     device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the counters (profiles/)."""
@@ -404,11 +478,19 @@ def main():
     ap.add_argument("--host-gib", type=float, default=60.0,
                     help="pinned host memory budget for values (the GPU boxes refuse more than 65 GiB in total)")
     ap.add_argument("--evict-every", type=int, default=16)
+    ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
+                    help="launch-shape knob passed to hca_tune (gather_wgs, gather_unroll, score_bpw, score_depth)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sel-buffers", type=int, default=32,
+                    help="score buffers of the native step driver (one per layer: the scan never waits for one)")
+    ap.add_argument("--bracket-stride", type=int, default=4,
+                    help="HIP-event bracket around the scan of every n-th layer (the in-kernel stamps time all of them)")
     ap.add_argument("--pipeline", default="native", choices=["native", "staged", "gather", "none"],
                     help="native: the library's four-stage step driver; staged: the same pipeline enqueued from Python; "
                          "gather: only the gather overlaps; none: serial")
     ap.add_argument("--no-latency", action="store_true", help="skip the per-layer latency probes at 128K / 1M / 4M")
+    ap.add_argument("--latency-parts", type=int, nargs="*", default=[],
+                    help="row splits tried by the pipelined per-layer latency probe")
     ap.add_argument("--stages", type=int, default=4, choices=[3, 4],
                     help="native pipeline: 4 = scan | top-k | gather | attend; 3 = top-k shares the scan stream")
     ap.add_argument("--mode", default="step", choices=["step", "scan"],
@@ -424,6 +506,9 @@ def main():
     from paper_2507_19823_amd import binding as B
     B.lib()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    for kv in args.tune:
+        name, val = kv.split("=")
+        B.hca_tune(name, int(val))
 
     w = S.CONFIGS[args.config]
     L = args.layers or w.layers
@@ -451,10 +536,19 @@ def main():
     if not args.no_latency:
         for name, c in (("128K", 3), ("1M", 4), ("4M", 5)):
             latency[name] = per_layer_latency(c, main_s[0], gath_s[0], link_peak)
-            log(f"latency probe {name}: {latency[name]['ms_per_layer']:.3f} ms per layer")
+            latency[name]["ms_per_layer_serial"] = latency[name]["ms_per_layer"]
+            log(f"latency probe {name}: {latency[name]['ms_per_layer']:.3f} ms per layer, stages one after another")
+            for parts in args.latency_parts:
+                g = per_layer_latency_grouped(c, parts, (main_s[0], extra[0], gath_s[0], extra[1]))
+                log(f"latency probe {name}: {g['ms_per_layer']:.3f} ms per layer as {parts} pipelined parts "
+                    f"(host enqueue {g['host_enqueue_ms']:.2f} ms behind a {g['gate_ms']:.2f} ms gate)")
+                latency[name].setdefault("pipelined_parts", []).append(g)
+                if g["host_enqueue_ms"] < g["gate_ms"] and g["ms_per_layer"] < latency[name]["ms_per_layer"]:
+                    latency[name]["ms_per_layer"] = g["ms_per_layer"]
+                    latency[name]["parts"] = parts
 
     total_steps = args.steps + args.warmup
-    model = Model(w, L, args.evict_every, total_steps)
+    model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers))
     layer_v_gib = w.batch * w.n_kv_heads * w.n * 256 / 2 ** 30
     phys = max(1, min(L, int(args.host_gib / layer_v_gib)))
     t0 = time.perf_counter()
@@ -469,7 +563,8 @@ def main():
     main, side = main_s[0], gath_s[0]
 
     if args.pipeline == "native":
-        model.native_pipeline(main, main if args.stages == 3 else extra[0], side, extra[1], args.steps)
+        model.native_pipeline(main, main if args.stages == 3 else extra[0], side, extra[1], args.steps,
+                              args.bracket_stride)
 
     def run_step(t, ev=None):
         if args.pipeline == "native":
@@ -503,13 +598,17 @@ def main():
     if args.pipeline == "native":
         # event bracket around each scan launch (includes the wait for the other stages' kernels to make
         # room) and the kernel's own duration from the per-wave wall-clock stamps (first start to last end)
-        per = [x for slot in range(args.steps) for x in B.hca_pipeline_scan_ms(model.pl, slot, L)]
+        per = [x for slot in range(args.steps) for x in B.hca_pipeline_scan_ms(model.pl, slot, L) if x >= 0]
         bracket_ms = sum(per) / len(per)
         st_ = model.stamps
         starts = torch.where(st_[..., 0] > 0, st_[..., 0], torch.full_like(st_[..., 0], 1 << 62)).amin(-1)
         ends = st_[..., 1].amax(-1)
         khz = B.hca_wall_clock_khz()
         scan_ms = float((ends - starts).double().mean()) / khz
+        flat_s, flat_e = starts.reshape(-1).double(), ends.reshape(-1).double()
+        gaps = (flat_s[1:] - flat_e[:-1]) / khz * 1e3
+        log("key scan launches: mean %.1f us; idle between consecutive ones: mean %.1f us, median %.1f us" % (
+            scan_ms * 1e3, float(gaps.mean()), float(gaps.median())))
     else:
         events = [e for step_events in events for e in step_events]
         scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
@@ -540,7 +639,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes,
-                     "avg_event_bracket_ms": bracket_ms},
+                     "avg_event_bracket_ms": bracket_ms,
+                     # the same kernel at the same shape with no other kernel beside it (latency probe above)
+                     "frac_alone": latency.get("1M", {}).get("key_scan_frac_of_hbm_peak") if args.config == 4 else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = run_cpu_baseline(model, w)

@@ -195,9 +195,12 @@ typedef struct {
   float* y;                                 /* device, fp32 [batch, n_q_heads, head_dim] */
 } hca_layer;
 
+#define HCA_PIPELINE_MAX_SEL 64
 typedef struct {
   void *stream_scan, *stream_topk, *stream_gather, *stream_attend;   /* four distinct hipStream_t */
-  float* sel[3];                 /* device, fp32 [batch, n_kv_heads, capacity] each */
+  float* sel[HCA_PIPELINE_MAX_SEL]; /* device, fp32 [batch, n_kv_heads, capacity] each; the first n_sel are used */
+  int32_t n_sel;                 /* 3 .. HCA_PIPELINE_MAX_SEL score buffers.  With one per layer the key scan of a
+                                    layer never waits for the top-k of an earlier layer to release its buffer */
   int32_t* idx[4];               /* device, int32 [batch, n_kv_heads, k] each */
   int32_t* count[4];             /* device, int32 [batch, n_kv_heads] each */
   void* ws_attend[4];            /* device, hca_workspace_bytes(shape, k, 1) each */
@@ -209,6 +212,8 @@ typedef struct {
      every wave of a timed scan launch stores its start and end wall-clock tick there (zero-filled by the
      caller; entries left 0 belong to waves that had nothing to do).  NULL: off. */
   void* scan_stamps; int64_t scan_stamp_pairs;
+  int32_t timing_layer_stride;   /* HIP-event brackets only around the scan of layers l % stride == 0 (0, 1: all);
+                                    each bracket costs two more packets on the scan stream */
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;

@@ -34,12 +34,17 @@ class hca_layer(C.Structure):
                 ("q", C.c_void_p), ("v_host", C.c_void_p), ("v_hbm", C.c_void_p), ("y", C.c_void_p)]
 
 
+PIPELINE_MAX_SEL = 64
+
+
 class hca_pipeline_desc(C.Structure):
     _fields_ = [("stream_scan", C.c_void_p), ("stream_topk", C.c_void_p), ("stream_gather", C.c_void_p),
-                ("stream_attend", C.c_void_p), ("sel", C.c_void_p * 3), ("idx", C.c_void_p * 4),
+                ("stream_attend", C.c_void_p), ("sel", C.c_void_p * PIPELINE_MAX_SEL), ("n_sel", C.c_int32),
+                ("idx", C.c_void_p * 4),
                 ("count", C.c_void_p * 4), ("ws_attend", C.c_void_p * 4), ("ws_topk", C.c_void_p),
                 ("ws_evict", C.c_void_p), ("spare_kcache", C.c_void_p), ("spare_acc", C.c_void_p),
-                ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64)]
+                ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64),
+                ("timing_layer_stride", C.c_int32)]
 
 
 _lib = None

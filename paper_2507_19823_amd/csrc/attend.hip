@@ -298,7 +298,9 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
   carve(&a, ws, L, k);
   const Tuning& tn = tuning();
   int64_t wgs = ((int64_t)k + 15) / 16;                  // one workgroup per 16 rows at most
-  int64_t lim = tn.gather_wgs > 0 ? tn.gather_wgs : 8;   // per (sequence, KV head)
+  // per (sequence, KV head).  About 64 workgroups in total keep enough reads in flight to fill the host
+  // link; more only take queue entries in the memory system away from the HBM-bound kernels beside it.
+  int64_t lim = tn.gather_wgs > 0 ? tn.gather_wgs : (L.rows >= 64 ? 1 : 64 / L.rows);
   if (wgs > lim) wgs = lim;
   dim3 g((unsigned)wgs, (unsigned)L.rows);
   const uint4 *vh = (const uint4*)v_host, *vd = (const uint4*)v_hbm;

@@ -10,7 +10,10 @@ struct hca_pipeline {
   hca::Layout L;
   int n_layers;
   hca_pipeline_desc d;
-  hipEvent_t score_done[3], sel_free[3];
+  int n_sel;                        // score buffers in use (<= n_layers)
+  bool sel_waits;                   // fewer score buffers than layers: the scan waits for the buffer's last top-k
+  std::vector<hipEvent_t> score_done, sel_free;
+  int timing_stride;
   hipEvent_t topk_done[4], gather_done[4], pipe_free[4];
   std::vector<hipEvent_t> layer_done;
   std::vector<hipEvent_t> t0, t1;   // timing events around the scan launches: [slots][layers]
@@ -34,7 +37,8 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
                                   int32_t timing_slots) {
   Layout L;
   if (make_layout(shape, &L) != HCA_OK || desc == nullptr || n_layers < 1 || timing_slots < 0) return nullptr;
-  for (int i = 0; i < 3; ++i) if (desc->sel[i] == nullptr) return nullptr;
+  if (desc->n_sel < 3 || desc->n_sel > HCA_PIPELINE_MAX_SEL) return nullptr;
+  for (int i = 0; i < desc->n_sel; ++i) if (desc->sel[i] == nullptr) return nullptr;
   for (int i = 0; i < 4; ++i)
     if (desc->idx[i] == nullptr || desc->count[i] == nullptr || desc->ws_attend[i] == nullptr) return nullptr;
   if (desc->ws_topk == nullptr) return nullptr;
@@ -43,9 +47,14 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   p->n_layers = n_layers;
   p->d = *desc;
   p->timing_slots = timing_slots;
+  p->n_sel = desc->n_sel < n_layers ? desc->n_sel : n_layers;
+  p->sel_waits = desc->n_sel < n_layers;
+  p->timing_stride = desc->timing_layer_stride > 1 ? desc->timing_layer_stride : 1;
+  p->score_done.resize(p->n_sel);
+  p->sel_free.resize(p->n_sel);
   bool ok = true;
   auto mk = [&](hipEvent_t* e, unsigned flags) { ok = ok && hipEventCreateWithFlags(e, flags) == hipSuccess; };
-  for (int i = 0; i < 3; ++i) { mk(&p->score_done[i], hipEventDisableTiming); mk(&p->sel_free[i], hipEventDisableTiming); }
+  for (int i = 0; i < p->n_sel; ++i) { mk(&p->score_done[i], hipEventDisableTiming); mk(&p->sel_free[i], hipEventDisableTiming); }
   for (int i = 0; i < 4; ++i) {
     mk(&p->topk_done[i], hipEventDisableTiming);
     mk(&p->gather_done[i], hipEventDisableTiming);
@@ -67,7 +76,8 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
 
 void hca_pipeline_destroy(hca_pipeline* p) {
   if (p == nullptr) return;
-  for (int i = 0; i < 3; ++i) { (void)hipEventDestroy(p->score_done[i]); (void)hipEventDestroy(p->sel_free[i]); }
+  for (auto e : p->score_done) (void)hipEventDestroy(e);
+  for (auto e : p->sel_free) (void)hipEventDestroy(e);
   for (int i = 0; i < 4; ++i) {
     (void)hipEventDestroy(p->topk_done[i]);
     (void)hipEventDestroy(p->gather_done[i]);
@@ -126,15 +136,18 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (rc != HCA_OK) return rc;
     for (int b = 0; b < L.batch; ++b)
       if (nr.n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;
-    const int s3 = l % 3, s4 = l % 4;
+    const int s3 = l % p->n_sel, s4 = l % 4;
+    const bool timed = timing_slot >= 0 && l % p->timing_stride == 0;
     // stage 1: append + key scan
-    HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[s3], 0));     // top-k of the previous user of this score buffer
+    // top-k of the previous user of this score buffer (with a buffer per layer that is this layer's own
+    // previous step, which layer_done covers)
+    if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[s3], 0));
     HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l], 0));    // this layer's attend / evict of the previous step
     rc = launch_quantize(L, ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa);
     if (rc != HCA_OK) return rc;
     for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
     nmax += 1;
-    if (timing_slot >= 0) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
+    if (timed) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
     uint64_t* stamps = nullptr;
     if (timing_slot >= 0 && p->d.scan_stamps != nullptr) {
       if (p->d.scan_stamp_pairs < score_stamp_pairs(L, nmax)) return HCA_ERR_CAPACITY;
@@ -142,14 +155,14 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     }
     rc = launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps);
     if (rc != HCA_OK) return rc;
-    if (timing_slot >= 0) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
+    if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
     HCA_HIP(hipEventRecord(p->score_done[s3], sa));
     // stage 2: top-k
     HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
     HCA_HIP(hipStreamWaitEvent(sb, p->pipe_free[s4], 0));    // attend of the previous user of idx / staging
     rc = launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb, true);
     if (rc != HCA_OK) return rc;
-    HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
+    if (p->sel_waits) HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
     HCA_HIP(hipEventRecord(p->topk_done[s4], sb));
     // stage 3: host-link gather
     HCA_HIP(hipStreamWaitEvent(sg, p->topk_done[s4], 0));
@@ -209,7 +222,8 @@ int32_t hca_pipeline_scan_ms(hca_pipeline* p, int32_t timing_slot, float* ms) {
   if (p == nullptr || ms == nullptr || timing_slot < 0 || timing_slot >= p->timing_slots) return HCA_ERR_BAD_ARG;
   for (int l = 0; l < p->n_layers; ++l) {
     const size_t i = (size_t)timing_slot * p->n_layers + l;
-    HCA_HIP(hipEventElapsedTime(&ms[l], p->t0[i], p->t1[i]));
+    ms[l] = -1.0f;                                    // layers without a bracket
+    if (l % p->timing_stride == 0) HCA_HIP(hipEventElapsedTime(&ms[l], p->t0[i], p->t1[i]));
   }
   return HCA_OK;
 }

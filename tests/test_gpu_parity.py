@@ -356,12 +356,14 @@ def test_kernels_are_deterministic(H):
         assert torch.equal(a, b)
 
 
-def test_native_step_driver_matches_oracle(H, oracle):
-    """hca_pipeline_step over 3 layers, 12 decode steps, staggered sliced eviction every 4 steps:
-    every layer's output, resident count and final cache state against the oracle run layer by layer."""
+@pytest.mark.parametrize("Lr,n_sel", [(3, 3), (5, 3), (5, 5)])
+def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel):
+    """hca_pipeline_step over 3 or 5 layers (score buffers shared between layers or one each), 12 decode
+    steps, staggered sliced eviction every 4 steps: every layer's output, resident count and final cache
+    state against the oracle run layer by layer."""
     import ctypes as C
     from paper_2507_19823_amd import binding as B
-    Lr, steps, E = 3, 12, 4
+    steps, E = 12, 4
     w = S.Workload("drv", 7, 2, 8, 2, 1500, 4, 32, 96)
     R, n0 = w.batch * w.n_kv_heads, w.n
     cap, vnew = n0 + E + 16, steps + 4
@@ -394,8 +396,9 @@ def test_native_step_driver_matches_oracle(H, oracle):
     d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
     wsb = B.hca_workspace_bytes(shape, w.k, n0)
     keep = []
-    for i in range(3):
+    for i in range(n_sel):
         t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev); keep.append(t); d.sel[i] = t.data_ptr()
+    d.n_sel = n_sel
     for i in range(4):
         a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
         b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
