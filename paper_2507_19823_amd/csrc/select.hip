@@ -495,11 +495,16 @@ __global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, i
       for (int u = 0; u < 16; ++u)
         if ((uint32_t)lane < m[u] && (ent[u].x >> 20) == bin) f(ent[u].x, ent[u].y);
 #pragma unroll 1
-      for (int u = 0; u < 16; ++u) {
+      for (int u = 0; u < 16; ++u) {      // long lists (clustered heavy hitters, mass ties): 8 loads in flight
         const int c = c0 + wv * 16 + u;
-        for (uint32_t i = 64 + lane; i < m[u]; i += 64) {      // long lists (clustered heavy hitters)
-          const uint2 x = cand[(int64_t)c * chunk + i];
-          if ((x.x >> 20) == bin) f(x.x, x.y);
+        for (uint32_t i0 = 64 + lane; i0 < m[u] + lane; i0 += 512) {
+          uint2 x[8];
+#pragma unroll
+          for (int v = 0; v < 8; ++v)
+            if (i0 + 64 * v < m[u]) x[v] = cand[(int64_t)c * chunk + i0 + 64 * v];
+#pragma unroll
+          for (int v = 0; v < 8; ++v)
+            if (i0 + 64 * v < m[u] && (x[v].x >> 20) == bin) f(x[v].x, x[v].y);
         }
       }
     }

@@ -128,7 +128,8 @@ def test_scores_different_lengths_per_sequence(H, oracle):
 
 
 @pytest.mark.parametrize("case", ["random", "all_equal", "two_valued", "signed_zero", "few_distinct", "sorted_desc"])
-@pytest.mark.parametrize("n,k", [(5000, 1), (5000, 256), (5000, 4999), (5000, 5000), (70000, 2048), (1, 1), (300, 1000)])
+@pytest.mark.parametrize("n,k", [(5000, 1), (5000, 256), (5000, 4999), (5000, 5000), (70000, 2048), (1, 1), (300, 1000),
+                                 ((1 << 20) + 7, 4096)])
 def test_topk_bit_exact_including_ties(H, oracle, case, n, k):
     rng = np.random.default_rng(n * 7 + k)
     rows = 4
