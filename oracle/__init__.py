@@ -185,3 +185,89 @@ def evict(cache, acc, pos, M, n_protect):
                            C.c_int64(n_protect), _p(kept), _p(n_new)), "evict")
     cache.n[...] = n_new
     return kept
+
+
+# ---- codebook form of the key path (hca_vq_oracle.c) -------------------------------------
+
+class VQCache:
+    """Index matrix P for R rows: uint16 [R, cap, g]; codebook C fp32 [n_kv, g, c, D/g]."""
+
+    def __init__(self, R, cap, codebook, D=128):
+        codebook = np.ascontiguousarray(codebook, np.float32)
+        self.n_kv, self.g, self.c, dbar = codebook.shape
+        assert self.g * dbar == D
+        self.R, self.cap, self.D, self.C = R, cap, D, codebook
+        self.P = np.zeros((R, cap, self.g), np.uint16)
+        self.n = np.zeros(R, np.int64)
+
+
+def vq_train(kval, g, c, init, iters, shared=False):
+    """kval [nval, D] fp16; init int32 [g, c] (or [c] when shared).  Returns (C fp32 [g,c,D/g],
+    inertia fp64 [iters+1])."""
+    kval = _u16(kval)
+    nval, D = kval.shape
+    init = np.ascontiguousarray(init, np.int32)
+    assert init.shape == ((c,) if shared else (g, c))
+    Cb = np.zeros((g, c, D // g), np.float32)
+    inertia = np.zeros(iters + 1, np.float64)
+    _check(lib().hco_vq_train(_p(kval), C.c_int64(nval), C.c_int(D), C.c_int(g), C.c_int(c), _p(init),
+                              C.c_int(iters), C.c_int(1 if shared else 0), _p(Cb), _p(inertia)), "vq_train")
+    return Cb, inertia
+
+
+def vq_assign(cache, k_new):
+    """Append k_new [R,T,D] fp16: nearest-centroid indices at slots n..n+T-1."""
+    k_new = _u16(k_new)
+    R, T, D = k_new.shape
+    assert R == cache.R and D == cache.D
+    _check(lib().hco_vq_assign(_p(k_new), C.c_int64(R), C.c_int64(T), C.c_int(D), C.c_int(cache.g),
+                               C.c_int(cache.c), C.c_int(cache.n_kv), _p(cache.C), C.c_int64(cache.cap),
+                               _p(cache.n), _p(cache.P)), "vq_assign")
+
+
+def vq_dequant(cache):
+    out = np.zeros((cache.R, cache.cap, cache.D), np.float32)
+    _check(lib().hco_vq_dequant(_p(cache.P), C.c_int64(cache.R), C.c_int(cache.D), C.c_int(cache.g),
+                                C.c_int(cache.c), C.c_int(cache.n_kv), _p(cache.C), C.c_int64(cache.cap),
+                                _p(cache.n), _p(out)), "vq_dequant")
+    return out
+
+
+def vq_lut(cache, q):
+    """q [R*G, D] fp16 -> T fp32 [R*G, g, c]."""
+    q = _u16(q)
+    G = q.shape[0] // cache.R
+    T = np.zeros((cache.R * G, cache.g, cache.c), np.float32)
+    _check(lib().hco_vq_lut(_p(q), C.c_int64(cache.R), C.c_int(G), C.c_int(cache.D), C.c_int(cache.g),
+                            C.c_int(cache.c), C.c_int(cache.n_kv), _p(cache.C), _p(T)), "vq_lut")
+    return T
+
+
+def vq_score(cache, T, want_z=True):
+    """T [R*G, g, c] -> (sel [R,cap] fp32, z [R*G,cap] fp32 or None)."""
+    T = np.ascontiguousarray(T, np.float32)
+    G = T.shape[0] // cache.R
+    sel = np.zeros((cache.R, cache.cap), np.float32)
+    z = np.zeros((cache.R * G, cache.cap), np.float32) if want_z else None
+    _check(lib().hco_vq_score(_p(T), _p(cache.P), C.c_int64(cache.R), C.c_int(G), C.c_int(cache.g),
+                              C.c_int(cache.c), C.c_int64(cache.cap), _p(cache.n), _p(sel), _p(z)), "vq_score")
+    return sel, z
+
+
+def vq_attend(cache, T, idx, count, pos, V, sm_scale, acc=None, want_w=False):
+    """As attend(), with the logits of Eq. 3 taken from the table T."""
+    T, V = np.ascontiguousarray(T, np.float32), _u16(V)
+    G = T.shape[0] // cache.R
+    idx = np.ascontiguousarray(idx, np.int32)
+    count = np.ascontiguousarray(count, np.int32)
+    pos = np.ascontiguousarray(pos, np.int32)
+    k = idx.shape[1]
+    y = np.zeros((cache.R * G, cache.D), np.float32)
+    w = np.zeros((cache.R * G, k), np.float32) if want_w else None
+    if acc is not None:
+        assert acc.dtype == np.float32 and acc.flags.c_contiguous
+    _check(lib().hco_vq_attend(_p(T), _p(cache.P), C.c_int64(cache.R), C.c_int(G), C.c_int(cache.D),
+                               C.c_int(cache.g), C.c_int(cache.c), C.c_int64(cache.cap), _p(idx), _p(count),
+                               C.c_int64(k), _p(pos), _p(V), C.c_int64(V.shape[1]), C.c_float(sm_scale),
+                               _p(y), _p(w), _p(acc)), "vq_attend")
+    return y, w

@@ -1,4 +1,4 @@
-"""Compile the CPU oracle (plain C, gcc) into oracle/libhca_oracle.so.
+"""Compile the CPU oracle (plain C, gcc: hca_oracle.c and hca_vq_oracle.c) into oracle/libhca_oracle.so.
 
 Flags matter: -ffp-contract=off keeps every fp32 operation a single rounded IEEE
 operation (the oracle's bit-level definition depends on it); no fast-math.
@@ -8,15 +8,15 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "hca_oracle.c")
+SRCS = [os.path.join(HERE, "hca_oracle.c"), os.path.join(HERE, "hca_vq_oracle.c")]
 LIB = os.path.join(HERE, "libhca_oracle.so")
 
 
 def build(force: bool = True) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
+    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= max(os.path.getmtime(x) for x in SRCS):
         return LIB
     cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
-           "-fPIC", "-shared", "-Wall", "-Wextra", "-o", LIB, SRC, "-lm"]
+           "-fPIC", "-shared", "-Wall", "-Wextra", "-o", LIB] + SRCS + ["-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 
