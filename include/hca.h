@@ -251,6 +251,74 @@ int32_t hca_pipeline_scan_ms(hca_pipeline* p, int32_t timing_slot, float* ms);
 int32_t hca_export_kcache(const hca_shape* shape, const void* kcache, const int64_t* n_resident,
                           uint8_t* codes, void* scale_f16, void* zero_f16, void* stream);
 
+/* ---- Codebook form of the key path ---------------------------------------------------------
+ * The paper's own compressor: grouped vector quantisation (Sec. 3.1) and table-lookup scores
+ * (Sec. 3.2, Eq. 3).  The head dimension is cut into g groups of dbar = head_dim / g channels, a
+ * token is stored as one centroid index per group (the matrix P), a query is first turned into the
+ * table T = qbar . C (one entry per group and centroid) and the score of a token is the sum over
+ * the groups of the table entries its indices select.  Top-k (hca_topk), the value gather
+ * (hca_gather_values) and eviction decisions are those of the uniform-code path and are called
+ * with the same hca_shape; its bits / group fields are not used by the hca_vq_* calls.
+ *
+ * Supported: head_dim 128, g in {32, 64}, 1 <= c <= 256 and g * c * n_q_heads/n_kv_heads <= 32768,
+ * so that indices are bytes and the whole table of a KV head (<= 128 KiB) sits in the LDS of the
+ * compute unit that scans it; a larger table would have to be gathered from L2 at about sixteen
+ * times the cost of streaming P from HBM.
+ *
+ * Arithmetic (the same on the oracle's side, so that indices, tables and scores match bit for bit):
+ *   distance  d = 0; channels of the group ascending: e = x - c; d = fmaf(e, e, d); nearest = smallest d,
+ *             ties to the lowest index
+ *   table     t = 0; channels ascending: t = fmaf(q, c, t)
+ *   score     z = T[0, P0]; z = z + T[i, Pi] for i = 1 .. g-1; selection score = max over the KV head's
+ *             query heads
+ * Layouts: centroids fp32 [n_kv_heads, g, c, dbar] (row (b, h) uses the codebook of KV head h);
+ * pcache uint8 [batch, n_kv_heads, capacity, g]; lut fp32 [batch, n_kv_heads, g, c, n_q_heads/n_kv_heads]. */
+typedef struct {
+  int32_t groups;             /* g */
+  int32_t codewords;          /* c */
+  const float* centroids;     /* device */
+} hca_vq_codebook;
+
+size_t hca_vq_pcache_bytes(const hca_shape* shape, const hca_vq_codebook* cb);
+size_t hca_vq_lut_bytes(const hca_shape* shape, const hca_vq_codebook* cb);
+
+/* Offline codebook training on the host (Sec. 3.1): Lloyd's k-means per group over the sub-vectors
+ * of a validation set.  Host pointers only, no device work, blocks until done.
+ *   kval_f16   host, fp16 [n_val, head_dim]
+ *   init       host, int32: shared == 0: [g, c] validation tokens whose sub-vectors seed group i's
+ *              centroids; shared != 0: [c] entries of the pool of all g * n_val sub-vectors (entry
+ *              t * g + i is sub-vector i of token t), one codebook trained on the pool and copied to
+ *              every group
+ *   iters      assignment + mean-update rounds; a centroid without members keeps its place
+ *   centroids  host out, fp32 [g, c, dbar]
+ *   inertia_opt host out, double [iters + 1] or NULL: k-means objective at each round's assignment and
+ *              after the last update
+ * Errors: HCA_ERR_BAD_ARG on bad sizes or seeds out of range. */
+int32_t hca_vq_train(const void* kval_f16, int64_t n_val, int32_t head_dim, int32_t groups, int32_t codewords,
+                     const int32_t* init, int32_t iters, int32_t shared, float* centroids, double* inertia_opt);
+
+/* Appends T tokens per row: nearest-centroid index of every group (Sec. 3.2, the matrix P).
+ * k_new_f16, n_resident, acc_opt, pos_opt, value_row0: as in hca_quantize_keys.
+ * Errors: HCA_ERR_CAPACITY if n_resident + T exceeds the capacity. */
+int32_t hca_vq_assign(const hca_shape* shape, const hca_vq_codebook* cb, void* pcache, const void* k_new_f16,
+                      int64_t T, const int64_t* n_resident, float* acc_opt, int32_t* pos_opt,
+                      const int64_t* value_row0, void* stream);
+
+/* Builds the table of every query head into `lut` (device, hca_vq_lut_bytes; kept for
+ * hca_vq_attend_gathered), then scores every resident token (Eq. 3).
+ *   sel    device, fp32 [batch, n_kv_heads, capacity]: max over the KV head's query heads; slots
+ *          >= n_resident are left untouched
+ *   z_opt  device, fp32 [batch, n_q_heads, capacity] or NULL */
+int32_t hca_vq_score(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache, const void* q_f16,
+                     const int64_t* n_resident, float* lut, float* sel, float* z_opt, void* stream);
+
+/* As hca_attend_gathered, with the logits of the selected tokens read from `lut` (Eq. 3) instead of
+ * recomputed from uniform codes: softmax over the selected set, weighted sum of the value rows that
+ * hca_gather_values left in `workspace`, optional accumulated-score update. */
+int32_t hca_vq_attend_gathered(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache,
+                               const float* lut, const int32_t* idx, const int32_t* count, int32_t k,
+                               float sm_scale, float* y, float* acc_opt, void* workspace, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -47,6 +47,10 @@ class hca_pipeline_desc(C.Structure):
                 ("timing_layer_stride", C.c_int32)]
 
 
+class hca_vq_codebook(C.Structure):
+    _fields_ = [("groups", C.c_int32), ("codewords", C.c_int32), ("centroids", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -95,6 +99,19 @@ def lib():
         L.hca_pipeline_scan_ms.argtypes = [vp, i32, C.POINTER(f32)]
         L.hca_export_kcache.restype = i32
         L.hca_export_kcache.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+        cbp = C.POINTER(hca_vq_codebook)
+        L.hca_vq_pcache_bytes.restype = C.c_size_t
+        L.hca_vq_pcache_bytes.argtypes = [sp, cbp]
+        L.hca_vq_lut_bytes.restype = C.c_size_t
+        L.hca_vq_lut_bytes.argtypes = [sp, cbp]
+        L.hca_vq_train.restype = i32
+        L.hca_vq_train.argtypes = [vp, i64, i32, i32, i32, vp, i32, i32, vp, vp]
+        L.hca_vq_assign.restype = i32
+        L.hca_vq_assign.argtypes = [sp, cbp, vp, vp, i64, vp, vp, vp, vp, vp]
+        L.hca_vq_score.restype = i32
+        L.hca_vq_score.argtypes = [sp, cbp, vp, vp, vp, vp, vp, vp, vp]
+        L.hca_vq_attend_gathered.restype = i32
+        L.hca_vq_attend_gathered.argtypes = [sp, cbp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp]
         _lib = L
     return _lib
 
@@ -232,3 +249,53 @@ def hca_scan_stamp_pairs(shape, n_tokens):
 
 def hca_wall_clock_khz():
     return int(lib().hca_wall_clock_khz())
+
+
+# ---- codebook form of the key path --------------------------------------------------------------
+
+def make_codebook(groups, codewords, centroids=None):
+    """centroids: device tensor fp32 [n_kv_heads, g, c, head_dim/g] (kept alive by the caller) or None."""
+    return hca_vq_codebook(int(groups), int(codewords), None if centroids is None else centroids.data_ptr())
+
+
+def hca_vq_pcache_bytes(shape, cb):
+    return int(lib().hca_vq_pcache_bytes(C.byref(shape), C.byref(cb)))
+
+
+def hca_vq_lut_bytes(shape, cb):
+    return int(lib().hca_vq_lut_bytes(C.byref(shape), C.byref(cb)))
+
+
+def hca_vq_train(kval, groups, codewords, init, iters, shared=False):
+    """kval: host fp16 array-like [n_val, head_dim] (numpy or CPU tensor); init: int32 [g, c] or [c].
+    Returns (centroids fp32 numpy [g, c, head_dim/g], inertia float64 numpy [iters+1])."""
+    import numpy as np
+    kval = np.ascontiguousarray(kval.numpy() if hasattr(kval, "numpy") else kval)
+    assert kval.dtype == np.float16 and kval.ndim == 2
+    n_val, D = kval.shape
+    init = np.ascontiguousarray(init, np.int32)
+    assert init.shape == ((codewords,) if shared else (groups, codewords))
+    cen = np.zeros((groups, codewords, D // groups), np.float32)
+    inertia = np.zeros(iters + 1, np.float64)
+    _check(lib().hca_vq_train(kval.ctypes.data_as(C.c_void_p), n_val, D, int(groups), int(codewords),
+                              init.ctypes.data_as(C.c_void_p), int(iters), 1 if shared else 0,
+                              cen.ctypes.data_as(C.c_void_p), inertia.ctypes.data_as(C.c_void_p)), "hca_vq_train")
+    return cen, inertia
+
+
+def hca_vq_assign(shape, cb, pcache, k_new, T, n_resident, acc=None, pos=None, value_row0=None, stream=None):
+    _check(lib().hca_vq_assign(C.byref(shape), C.byref(cb), _ptr(pcache), _ptr(k_new), int(T),
+                               _nres(n_resident, shape.batch), _ptr(acc), _ptr(pos),
+                               None if value_row0 is None else _nres(value_row0, shape.batch), _stream(stream)),
+           "hca_vq_assign")
+
+
+def hca_vq_score(shape, cb, pcache, q, n_resident, lut, sel, z=None, stream=None):
+    _check(lib().hca_vq_score(C.byref(shape), C.byref(cb), _ptr(pcache), _ptr(q), _nres(n_resident, shape.batch),
+                              _ptr(lut), _ptr(sel), _ptr(z), _stream(stream)), "hca_vq_score")
+
+
+def hca_vq_attend_gathered(shape, cb, pcache, lut, idx, count, k, sm_scale, y, acc, workspace, stream=None):
+    _check(lib().hca_vq_attend_gathered(C.byref(shape), C.byref(cb), _ptr(pcache), _ptr(lut), _ptr(idx), _ptr(count),
+                                        int(k), float(sm_scale), _ptr(y), _ptr(acc), _ptr(workspace), _stream(stream)),
+           "hca_vq_attend_gathered")

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhca.so")
-SOURCES = ["api.hip", "quantize.hip", "score.hip", "select.hip", "attend.hip", "evict.hip", "pipeline.hip"]
+SOURCES = ["api.hip", "quantize.hip", "score.hip", "select.hip", "attend.hip", "evict.hip", "pipeline.hip", "vq.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fhip-fp32-correctly-rounded-divide-sqrt", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form", "-Wall"]

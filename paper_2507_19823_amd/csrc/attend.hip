@@ -71,73 +71,28 @@ __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__
   }
 }
 
-template <int BITS>
-__global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* __restrict__ kcache,
-                                                      const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
-                                                      const int32_t* __restrict__ count, int32_t k, float sm_scale,
-                                                      AttendWs a, int nsplit) {
-  __shared__ QShared sh;
-  __shared__ float lg[4][kChunk];
-  __shared__ float red[4][4][kHeadDim];
-  __shared__ float hm[4], hz[4];
-  const int row = blockIdx.y, split = blockIdx.x;
-  const int cnt = count[row];
-  const int i0 = split * kChunk;
+// Shared memory of one chunk (256 selected tokens, up to 4 query heads) of the partial kernels.
+struct PartialShared {
+  float lg[4][kChunk];          // logits, then exp(logit - chunk max)
+  float red[4][4][kHeadDim];
+  float hm[4], hz[4];
+};
+
+// Writes the neutral partial of an empty chunk.
+__device__ __forceinline__ void partial_empty(float* pmz, float* py) {
+  if (threadIdx.x < 4) { pmz[2 * threadIdx.x] = -INFINITY; pmz[2 * threadIdx.x + 1] = 0.f; }
+  for (int c = threadIdx.x; c < 4 * kHeadDim; c += 256) py[c] = 0.f;
+}
+
+// Steps 2 and 3 of a chunk, after its logits sit in ps.lg (and a __syncthreads()): per-head chunk
+// max / exponentials / sum, then the weighted sum of the staged value rows.
+__device__ __forceinline__ void partial_softmax_sum(PartialShared& ps, const AttendWs& a, int row, int i0, int nvalid,
+                                                    int32_t k, float* pmz, float* py) {
+  auto& lg = ps.lg;
+  auto& red = ps.red;
+  auto& hm = ps.hm;
+  auto& hz = ps.hz;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int t = lane & 15, j = lane >> 4;
-  float* pmz = a.pmz + (((int64_t)row * nsplit + split) * 4) * 2;
-  float* py = a.py + (((int64_t)row * nsplit + split) * 4) * kHeadDim;
-  if (i0 >= cnt) {  // empty chunk: neutral partial
-    if (threadIdx.x < 4) { pmz[2 * threadIdx.x] = -INFINITY; pmz[2 * threadIdx.x + 1] = 0.f; }
-    for (int c = threadIdx.x; c < 4 * kHeadDim; c += 256) py[c] = 0.f;
-    return;
-  }
-  const int nvalid = (cnt - i0 < kChunk) ? cnt - i0 : kChunk;
-  load_query(q, row, L.gqa, L.group, &sh);
-  QOperand<BITS> op;
-  build_operand<BITS>(&sh, &op);
-  const uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
-  const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
-  const int32_t* ridx = idx + (int64_t)row * k;
-
-  // 1. logits of the chunk: wave w scores tiles w, w+4, w+8, w+12 (16 selected tokens each).
-  //    All slot numbers are fetched first, then all code / meta pieces, so that the wave has its
-  //    whole share of the random reads in flight at once.
-  {
-    int64_t slot[4];
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      const int i = (w + 4 * x) * 16 + t;
-      slot[x] = ridx[i0 + (i < nvalid ? i : nvalid - 1)];
-    }
-    uint4 wv[4], mv[4];
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      if constexpr (BITS == 4) {
-        const int64_t blk = slot[x] >> 4;
-        const int tl = (int)(slot[x] & 15);
-        wv[x] = *reinterpret_cast<const uint4*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16);
-        mv[x] = *reinterpret_cast<const uint4*>(mrow + blk * kMetaBytes + tl * 16);
-      } else {
-        const int64_t blk = slot[x] >> 5;
-        const int u = (int)((slot[x] >> 4) & 1), tl = (int)(slot[x] & 15);
-        const uint2 c = *reinterpret_cast<const uint2*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16 + 8 * u);
-        const uint2 m = *reinterpret_cast<const uint2*>(mrow + blk * kMetaBytes + (16 * u + tl) * 8);
-        wv[x] = uint4{c.x, c.y, 0, 0};
-        mv[x] = uint4{m.x, m.y, 0, 0};
-      }
-    }
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      float zv;
-      if constexpr (BITS == 4) zv = score_block4(op, wv[x], mv[x]);
-      else zv = score_tile2(op, wv[x].x, wv[x].y, uint2{mv[x].x, mv[x].y});
-      // lane (t, hd = j) holds z~ of head j for selected token (w + 4x)*16 + t
-      lg[j][(w + 4 * x) * 16 + t] = zv * sm_scale;
-    }
-  }
-  __syncthreads();
-
   // 2. per head (wave w = head w): chunk max, exponentials, chunk sum
   {
     float m = -INFINITY;
@@ -213,6 +168,135 @@ __global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* _
     py[c] = (red[0][h][d] + red[1][h][d]) + (red[2][h][d] + red[3][h][d]);
   }
   if (threadIdx.x < 4) { pmz[2 * threadIdx.x] = hm[threadIdx.x]; pmz[2 * threadIdx.x + 1] = hz[threadIdx.x]; }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* __restrict__ kcache,
+                                                      const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
+                                                      const int32_t* __restrict__ count, int32_t k, float sm_scale,
+                                                      AttendWs a, int nsplit) {
+  __shared__ QShared sh;
+  __shared__ PartialShared ps;
+  auto& lg = ps.lg;
+  const int row = blockIdx.y, split = blockIdx.x;
+  const int cnt = count[row];
+  const int i0 = split * kChunk;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int t = lane & 15, j = lane >> 4;
+  float* pmz = a.pmz + (((int64_t)row * nsplit + split) * 4) * 2;
+  float* py = a.py + (((int64_t)row * nsplit + split) * 4) * kHeadDim;
+  if (i0 >= cnt) {  // empty chunk: neutral partial
+    partial_empty(pmz, py);
+    return;
+  }
+  const int nvalid = (cnt - i0 < kChunk) ? cnt - i0 : kChunk;
+  load_query(q, row, L.gqa, L.group, &sh);
+  QOperand<BITS> op;
+  build_operand<BITS>(&sh, &op);
+  const uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
+  const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
+  const int32_t* ridx = idx + (int64_t)row * k;
+
+  // 1. logits of the chunk: wave w scores tiles w, w+4, w+8, w+12 (16 selected tokens each).
+  //    All slot numbers are fetched first, then all code / meta pieces, so that the wave has its
+  //    whole share of the random reads in flight at once.
+  {
+    int64_t slot[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      const int i = (w + 4 * x) * 16 + t;
+      slot[x] = ridx[i0 + (i < nvalid ? i : nvalid - 1)];
+    }
+    uint4 wv[4], mv[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      if constexpr (BITS == 4) {
+        const int64_t blk = slot[x] >> 4;
+        const int tl = (int)(slot[x] & 15);
+        wv[x] = *reinterpret_cast<const uint4*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16);
+        mv[x] = *reinterpret_cast<const uint4*>(mrow + blk * kMetaBytes + tl * 16);
+      } else {
+        const int64_t blk = slot[x] >> 5;
+        const int u = (int)((slot[x] >> 4) & 1), tl = (int)(slot[x] & 15);
+        const uint2 c = *reinterpret_cast<const uint2*>(crow + blk * kBlockBytes + (tl + 16 * j) * 16 + 8 * u);
+        const uint2 m = *reinterpret_cast<const uint2*>(mrow + blk * kMetaBytes + (16 * u + tl) * 8);
+        wv[x] = uint4{c.x, c.y, 0, 0};
+        mv[x] = uint4{m.x, m.y, 0, 0};
+      }
+    }
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      float zv;
+      if constexpr (BITS == 4) zv = score_block4(op, wv[x], mv[x]);
+      else zv = score_tile2(op, wv[x].x, wv[x].y, uint2{mv[x].x, mv[x].y});
+      // lane (t, hd = j) holds z~ of head j for selected token (w + 4x)*16 + t
+      lg[j][(w + 4 * x) * 16 + t] = zv * sm_scale;
+    }
+  }
+  __syncthreads();
+
+  partial_softmax_sum(ps, a, row, i0, nvalid, k, pmz, py);
+}
+
+// Table entry of one (group, centroid): the G query heads of the KV head, adjacent in memory.
+template <int G>
+__device__ __forceinline__ void load_entry(const float* p, float (&e)[G]) {
+  if constexpr (G == 4) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    e[0] = v.x; e[1] = v.y; e[2] = v.z; e[3] = v.w;
+  } else if constexpr (G == 2) {
+    const float2 v = *reinterpret_cast<const float2*>(p);
+    e[0] = v.x; e[1] = v.y;
+  } else {
+    e[0] = p[0];
+  }
+}
+
+// Codebook form: the logit of a selected token is the sum over the groups of the table entries
+// its indices select (Eq. 3), in group order.  Thread i of the chunk owns selected token i0 + i.
+template <int G>
+__global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t cap, const uint8_t* __restrict__ pcache,
+                                                         const float* __restrict__ lut, const int32_t* __restrict__ idx,
+                                                         const int32_t* __restrict__ count, int32_t k, float sm_scale,
+                                                         AttendWs a, int nsplit) {
+  __shared__ PartialShared ps;
+  const int row = blockIdx.y, split = blockIdx.x;
+  const int cnt = count[row];
+  const int i0 = split * kChunk;
+  float* pmz = a.pmz + (((int64_t)row * nsplit + split) * 4) * 2;
+  float* py = a.py + (((int64_t)row * nsplit + split) * 4) * kHeadDim;
+  if (i0 >= cnt) {
+    partial_empty(pmz, py);
+    return;
+  }
+  const int nvalid = (cnt - i0 < kChunk) ? cnt - i0 : kChunk;
+  {
+    const int i = threadIdx.x;
+    const int64_t slot = idx[(int64_t)row * k + i0 + (i < nvalid ? i : nvalid - 1)];
+    const uint8_t* pr = pcache + ((int64_t)row * cap + slot) * g;
+    const float* T = lut + (int64_t)row * g * c * G;
+    float z[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) z[h] = 0.f;
+    for (int i16 = 0; i16 < g; i16 += 16) {
+      const uint4 pw = *reinterpret_cast<const uint4*>(pr + i16);
+      const uint32_t wd[4] = {pw.x, pw.y, pw.z, pw.w};
+      float e[16][G];
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {            // 16 independent table reads in flight
+        const int code = (int)((wd[b >> 2] >> (8 * (b & 3))) & 255u);
+        load_entry<G>(T + ((int64_t)(i16 + b) * c + code) * G, e[b]);
+      }
+#pragma unroll
+      for (int b = 0; b < 16; ++b)
+#pragma unroll
+        for (int h = 0; h < G; ++h) z[h] = (i16 + b == 0) ? e[b][h] : z[h] + e[b][h];
+    }
+#pragma unroll
+    for (int h = 0; h < 4; ++h) ps.lg[h][i] = h < G ? z[h < G ? h : 0] * sm_scale : 0.f;
+  }
+  __syncthreads();
+  partial_softmax_sum(ps, a, row, i0, nvalid, k, pmz, py);
 }
 
 // Workgroup 0 of a row merges the chunk partials into y; workgroups 1.. add the final softmax
@@ -327,6 +411,23 @@ int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* 
     attend_partial<4><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
   else
     attend_partial<2><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
+  dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
+  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* pcache, const float* lut,
+                                  const int32_t* idx, const int32_t* count, int32_t k, float sm_scale, float* y,
+                                  float* acc_opt, void* ws, hipStream_t st) {
+  AttendWs a;
+  carve(&a, ws, L, k);
+  const int ns = nsplit_of(k);
+  if (ns > 64) return HCA_ERR_CAPACITY;
+  dim3 gp((unsigned)ns, (unsigned)L.rows);
+  if (L.gqa == 4) vq_attend_partial<4><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
+  else if (L.gqa == 2) vq_attend_partial<2><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
+  else vq_attend_partial<1><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
   dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
   attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt);
   HCA_HIP(hipGetLastError());

@@ -78,6 +78,14 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
 int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
                                void* ws, hipStream_t st);
+int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* pcache, const float* lut,
+                                  const int32_t* idx, const int32_t* count, int32_t k, float sm_scale, float* y,
+                                  float* acc_opt, void* ws, hipStream_t st);
+// codebook form of the key path (vq.hip)
+int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, uint8_t* pcache, const void* k_new,
+                         int64_t T, const NRes& nr, float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st);
+int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, const uint8_t* pcache, const void* q,
+                        const NRes& nr, int64_t nmax, float* lut, float* sel, float* z_opt, hipStream_t st);
 size_t evict_workspace_bytes(const Layout& L, int64_t M);
 int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr,
                      int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst,

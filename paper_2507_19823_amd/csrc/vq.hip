@@ -1,0 +1,402 @@
+// Codebook form of the key path: grouped vector quantisation (Sec. 3.1) and the table-lookup
+// scores of Sec. 3.2, Eq. 3.  A token is one centroid index per group (a byte: c <= 256), the query
+// becomes a table T[group][centroid][query head of the KV head] that sits in LDS while a workgroup
+// scans its share of the index matrix.  The host-side trainer is at the end of the file.
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstring>
+#include <thread>
+#include <vector>
+
+#include "hca_internal.h"
+
+namespace hca {
+
+// ------------------------------------------------------------------------------- assign ---
+// One wave = 64 tokens x one quad of 4 consecutive groups.  Every centroid read is wave-uniform
+// (scalar loads), the running minimum is per lane.  distance: e = x - c; d = fmaf(e, e, d) over the
+// group's channels in ascending order from d = 0; the first smallest wins.
+template <int DBAR>
+__global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_heads, int64_t cap,
+                                                        const float* __restrict__ centroids,
+                                                        uint8_t* __restrict__ pcache, const uint16_t* __restrict__ k_new,
+                                                        int64_t T, NRes nr, float* __restrict__ acc,
+                                                        int32_t* __restrict__ pos, NRes vrow0) {
+  const int row = blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const int quad = __builtin_amdgcn_readfirstlane((int)(blockIdx.z * 4 + (threadIdx.x >> 6)));
+  if (quad * 4 >= g) return;
+  const int64_t tt = (int64_t)blockIdx.x * 64 + lane;
+  const bool live = tt < T;
+  const int64_t tc = live ? tt : T - 1;
+  // the quad's 4 * DBAR channels of this lane's token
+  float x[4][DBAR];
+  {
+    const uint16_t* src = k_new + ((int64_t)row * T + tc) * kHeadDim + quad * 4 * DBAR;
+    if constexpr (DBAR == 4) {
+      const uint4 a = reinterpret_cast<const uint4*>(src)[0], b = reinterpret_cast<const uint4*>(src)[1];
+      const uint32_t wd[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        x[i >> 1][2 * (i & 1)] = h2f(wd[i] & 0xffffu);
+        x[i >> 1][2 * (i & 1) + 1] = h2f(wd[i] >> 16);
+      }
+    } else {
+      const uint4 a = reinterpret_cast<const uint4*>(src)[0];
+      const uint32_t wd[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        x[i][0] = h2f(wd[i] & 0xffffu);
+        x[i][1] = h2f(wd[i] >> 16);
+      }
+    }
+  }
+  const float* cb = centroids + ((int64_t)(row % n_kv_heads) * g + quad * 4) * c * DBAR;
+  uint32_t packed = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const float* cg = cb + (int64_t)u * c * DBAR;
+    float bd = INFINITY;
+    int best = 0;
+    for (int cc = 0; cc < c; ++cc) {
+      float d = 0.f;
+#pragma unroll
+      for (int dd = 0; dd < DBAR; ++dd) {
+        const float e = x[u][dd] - cg[cc * DBAR + dd];
+        d = fmaf(e, e, d);
+      }
+      if (d < bd || cc == 0) { bd = d; best = cc; }
+    }
+    packed |= (uint32_t)best << (8 * u);
+  }
+  if (!live) return;
+  const int b = row / n_kv_heads;
+  const int64_t slot = nr.n[b] + tt;
+  *reinterpret_cast<uint32_t*>(pcache + ((int64_t)row * cap + slot) * g + quad * 4) = packed;
+  if (quad == 0) {
+    if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
+    if (pos != nullptr) pos[(int64_t)row * cap + slot] = (int32_t)(vrow0.n[b] + tt);
+  }
+}
+
+// -------------------------------------------------------------------------------- table ---
+// T[row][i][cc][h] = qbar_i . C[i][cc] for the G query heads of the row: t = 0; t = fmaf(q, c, t) over
+// the group's channels in ascending order.  grid (g, rows), one thread per centroid.
+template <int G, int DBAR>
+__global__ __launch_bounds__(256) void vq_lut_kernel(int g, int c, int n_kv_heads, const float* __restrict__ centroids,
+                                                     const uint16_t* __restrict__ q, float* __restrict__ lut) {
+  const int i = blockIdx.x, row = blockIdx.y;
+  const int cc = threadIdx.x;
+  if (cc >= c) return;
+  const float* cv = centroids + (((int64_t)(row % n_kv_heads) * g + i) * c + cc) * DBAR;
+  float* out = lut + (((int64_t)row * g + i) * c + cc) * G;
+#pragma unroll
+  for (int h = 0; h < G; ++h) {
+    const uint16_t* qh = q + ((int64_t)row * G + h) * kHeadDim + i * DBAR;
+    float t = 0.f;
+#pragma unroll
+    for (int dd = 0; dd < DBAR; ++dd) t = fmaf(h2f(qh[dd]), cv[dd], t);
+    out[h] = t;
+  }
+}
+
+// --------------------------------------------------------------------------------- scan ---
+template <int G> struct EntryT;
+template <> struct EntryT<4> { using type = float4; };
+template <> struct EntryT<2> { using type = float2; };
+template <> struct EntryT<1> { using type = float; };
+
+template <int G>
+__device__ __forceinline__ void entry_add(float (&z)[G], const typename EntryT<G>::type& e, bool first) {
+  if constexpr (G == 4) {
+    z[0] = first ? e.x : z[0] + e.x; z[1] = first ? e.y : z[1] + e.y;
+    z[2] = first ? e.z : z[2] + e.z; z[3] = first ? e.w : z[3] + e.w;
+  } else if constexpr (G == 2) {
+    z[0] = first ? e.x : z[0] + e.x; z[1] = first ? e.y : z[1] + e.y;
+  } else {
+    z[0] = first ? e : z[0] + e;
+  }
+}
+
+// Eq. 3.  One workgroup of 1024 threads copies the row's table (g * c entries of G floats) into LDS,
+// then each thread scores one token at a time: NG index bytes (two or four 16-byte loads; a wave
+// reads 64 consecutive tokens = 2 or 4 KiB in one piece), NG table reads, the sum in group order.
+// With the largest supported table (128 KiB) one workgroup fits a compute unit, so the launch has
+// about one workgroup per unit and each takes an equal share of the row.
+template <int G, int NG>
+__global__ __launch_bounds__(1024) void vq_scan_kernel(int c, int64_t cap, const uint8_t* __restrict__ pcache,
+                                                       const float* __restrict__ lut, NRes nr, int n_kv_heads,
+                                                       int64_t per_wg, float* __restrict__ sel, float* __restrict__ z_out) {
+  using E = typename EntryT<G>::type;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  E* tab = reinterpret_cast<E*>(lds_raw);
+  const int row = blockIdx.y;
+  const int64_t n = nr.n[row / n_kv_heads];
+  const int64_t j0 = (int64_t)blockIdx.x * per_wg;
+  if (j0 >= n) return;
+  int64_t j1 = j0 + per_wg;
+  if (j1 > n) j1 = n;
+  {
+    const E* src = reinterpret_cast<const E*>(lut) + (int64_t)row * NG * c;
+    for (int i = threadIdx.x; i < NG * c; i += 1024) tab[i] = src[i];
+  }
+  __syncthreads();
+  const uint8_t* prow = pcache + (int64_t)row * cap * NG;
+  for (int64_t j = j0 + threadIdx.x; j < j1; j += 1024) {
+    uint4 pw[NG / 16];
+#pragma unroll
+    for (int v = 0; v < NG / 16; ++v) pw[v] = reinterpret_cast<const uint4*>(prow + j * NG)[v];
+    float z[G];
+#pragma unroll
+    for (int v = 0; v < NG / 16; ++v) {
+      const uint32_t wd[4] = {pw[v].x, pw[v].y, pw[v].z, pw[v].w};
+      E e[16];
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {
+        const int code = (int)((wd[b >> 2] >> (8 * (b & 3))) & 255u);
+        e[b] = tab[(16 * v + b) * c + code];
+      }
+#pragma unroll
+      for (int b = 0; b < 16; ++b) entry_add<G>(z, e[b], v == 0 && b == 0);
+    }
+    float best = z[0];
+#pragma unroll
+    for (int h = 1; h < G; ++h) best = fmaxf(best, z[h]);
+    sel[(int64_t)row * cap + j] = best;
+    if (z_out != nullptr) {
+#pragma unroll
+      for (int h = 0; h < G; ++h) z_out[((int64_t)row * G + h) * cap + j] = z[h];
+    }
+  }
+}
+
+int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, uint8_t* pcache, const void* k_new,
+                         int64_t T, const NRes& nr, float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st) {
+  if (T == 0) return HCA_OK;
+  dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 16));
+  const uint16_t* kn = (const uint16_t*)k_new;
+  if (g == 32)
+    vq_assign_kernel<4><<<grid, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+  else
+    vq_assign_kernel<2><<<grid, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+template <int G, int NG>
+static int32_t scan_launch(const Layout& L, int c, const uint8_t* pcache, const float* lut, const NRes& nr,
+                           int64_t nmax, float* sel, float* z_opt, hipStream_t st) {
+  const size_t lds = (size_t)NG * c * G * 4;
+  static bool raised = false;                       // per instantiation: tables beyond 64 KiB need the opt-in
+  if (lds > 64 * 1024 && !raised) {
+    HCA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vq_scan_kernel<G, NG>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    raised = true;
+  }
+  // about one workgroup per compute unit, each with at least 1024 tokens, shares a multiple of 1024
+  int64_t per_row = 256 / L.rows;
+  if (per_row < 1) per_row = 1;
+  int64_t per_wg = align_up((nmax + per_row - 1) / per_row, 1024);
+  const int64_t chunks = (nmax + per_wg - 1) / per_wg;
+  dim3 grid((unsigned)chunks, (unsigned)L.rows);
+  vq_scan_kernel<G, NG><<<grid, 1024, lds, st>>>(c, L.cap, pcache, lut, nr, L.n_kv_heads, per_wg, sel, z_opt);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, const uint8_t* pcache, const void* q,
+                        const NRes& nr, int64_t nmax, float* lut, float* sel, float* z_opt, hipStream_t st) {
+  const uint16_t* qq = (const uint16_t*)q;
+  dim3 gl((unsigned)g, (unsigned)L.rows);
+#define HCA_LUT(G, D) vq_lut_kernel<G, D><<<gl, 256, 0, st>>>(g, c, L.n_kv_heads, centroids, qq, lut)
+  if (g == 32) {
+    if (L.gqa == 4) HCA_LUT(4, 4); else if (L.gqa == 2) HCA_LUT(2, 4); else HCA_LUT(1, 4);
+  } else {
+    if (L.gqa == 4) HCA_LUT(4, 2); else if (L.gqa == 2) HCA_LUT(2, 2); else HCA_LUT(1, 2);
+  }
+#undef HCA_LUT
+  HCA_HIP(hipGetLastError());
+  if (nmax == 0) return HCA_OK;
+  if (g == 32) {
+    if (L.gqa == 4) return scan_launch<4, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    if (L.gqa == 2) return scan_launch<2, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    return scan_launch<1, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+  }
+  if (L.gqa == 4) return scan_launch<4, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+  if (L.gqa == 2) return scan_launch<2, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+  return scan_launch<1, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+}
+
+// Shape checks shared by the entry points: the uniform-code fields of the shape are not used here.
+static int32_t vq_layout(const hca_shape* shape, const hca_vq_codebook* cb, Layout* L, bool need_centroids) {
+  if (shape == nullptr || cb == nullptr) return HCA_ERR_BAD_ARG;
+  hca_shape s = *shape;
+  s.bits = 4;
+  s.group = 32;
+  int32_t rc = make_layout(&s, L);
+  if (rc != HCA_OK) return rc;
+  if (cb->groups != 32 && cb->groups != 64) return HCA_ERR_UNSUPPORTED;
+  if (cb->codewords < 1) return HCA_ERR_BAD_ARG;
+  if (cb->codewords > 256) return HCA_ERR_UNSUPPORTED;
+  if ((int64_t)cb->groups * cb->codewords * L->gqa > 32768) return HCA_ERR_UNSUPPORTED;   // table beyond 128 KiB of LDS
+  if (need_centroids && cb->centroids == nullptr) return HCA_ERR_BAD_ARG;
+  return HCA_OK;
+}
+
+// ------------------------------------------------------------------------------ trainer ---
+// Lloyd's k-means, one codebook per group (or one for the pooled sub-vectors), codebooks spread over
+// host threads.  Within a codebook everything runs in pool order, so the result does not depend on
+// the number of threads.
+static void train_one(const uint16_t* kval, int64_t nval, int D, int g, int c, int dbar, bool shared, int b,
+                      const int32_t* init, int iters, float* cb, double* iner, std::atomic<int>* bad) {
+  const int64_t npool = shared ? nval * g : nval;
+  std::vector<float> x((size_t)npool * dbar);
+  auto half = [](uint16_t h) -> float {
+    _Float16 v;
+    std::memcpy(&v, &h, 2);
+    return (float)v;
+  };
+  for (int64_t p = 0; p < npool; ++p) {
+    const int64_t t = shared ? p / g : p;
+    const int i = shared ? (int)(p % g) : b;
+    for (int dd = 0; dd < dbar; ++dd) x[(size_t)p * dbar + dd] = half(kval[t * D + i * dbar + dd]);
+  }
+  for (int cc = 0; cc < c; ++cc) {
+    int64_t s = init[cc];
+    if (s < 0 || s >= npool) { bad->store(1); s = 0; }
+    std::memcpy(cb + (size_t)cc * dbar, &x[(size_t)s * dbar], sizeof(float) * dbar);
+  }
+  std::vector<double> sum((size_t)c * dbar);
+  std::vector<int64_t> cnt((size_t)c);
+  for (int it = 0; it <= iters; ++it) {
+    std::fill(sum.begin(), sum.end(), 0.0);
+    std::fill(cnt.begin(), cnt.end(), (int64_t)0);
+    double obj = 0.0;
+    for (int64_t p = 0; p < npool; ++p) {
+      const float* xp = &x[(size_t)p * dbar];
+      int best = 0;
+      float bd = 0.f;
+      for (int cc = 0; cc < c; ++cc) {
+        const float* cv = cb + (size_t)cc * dbar;
+        float d = 0.f;
+        for (int dd = 0; dd < dbar; ++dd) {
+          const float e = xp[dd] - cv[dd];
+          d = std::fmaf(e, e, d);
+        }
+        if (cc == 0 || d < bd) { bd = d; best = cc; }
+      }
+      obj += (double)bd;
+      cnt[best] += 1;
+      for (int dd = 0; dd < dbar; ++dd) sum[(size_t)best * dbar + dd] += (double)xp[dd];
+    }
+    iner[it] = obj;
+    if (it == iters) break;
+    for (int cc = 0; cc < c; ++cc)
+      if (cnt[cc] > 0)
+        for (int dd = 0; dd < dbar; ++dd) cb[(size_t)cc * dbar + dd] = (float)(sum[(size_t)cc * dbar + dd] / (double)cnt[cc]);
+  }
+}
+
+}  // namespace hca
+
+using namespace hca;
+
+extern "C" {
+
+size_t hca_vq_pcache_bytes(const hca_shape* shape, const hca_vq_codebook* cb) {
+  Layout L;
+  if (vq_layout(shape, cb, &L, false) != HCA_OK) return 0;
+  return (size_t)L.rows * (size_t)L.cap * (size_t)cb->groups;
+}
+
+size_t hca_vq_lut_bytes(const hca_shape* shape, const hca_vq_codebook* cb) {
+  Layout L;
+  if (vq_layout(shape, cb, &L, false) != HCA_OK) return 0;
+  return (size_t)L.rows * cb->groups * cb->codewords * L.gqa * 4;
+}
+
+int32_t hca_vq_train(const void* kval_f16, int64_t n_val, int32_t head_dim, int32_t groups, int32_t codewords,
+                     const int32_t* init, int32_t iters, int32_t shared, float* centroids, double* inertia_opt) {
+  if (kval_f16 == nullptr || init == nullptr || centroids == nullptr) return HCA_ERR_BAD_ARG;
+  if (head_dim < 1 || groups < 1 || head_dim % groups != 0 || codewords < 1 || n_val < 1 || iters < 0)
+    return HCA_ERR_BAD_ARG;
+  const int dbar = head_dim / groups;
+  const int ncb = shared ? 1 : groups;
+  std::vector<double> iner((size_t)ncb * (iters + 1), 0.0);
+  std::atomic<int> bad{0};
+  std::atomic<int> next{0};
+  auto work = [&]() {
+    for (int b = next.fetch_add(1); b < ncb; b = next.fetch_add(1))
+      train_one((const uint16_t*)kval_f16, n_val, head_dim, groups, codewords, dbar, shared != 0, b,
+                init + (size_t)b * codewords, iters, centroids + (size_t)b * codewords * dbar,
+                &iner[(size_t)b * (iters + 1)], &bad);
+  };
+  unsigned nt = std::thread::hardware_concurrency();
+  if (nt < 1) nt = 1;
+  if (nt > 16) nt = 16;
+  if ((int)nt > ncb) nt = (unsigned)ncb;
+  std::vector<std::thread> pool;
+  for (unsigned t = 1; t < nt; ++t) pool.emplace_back(work);
+  work();
+  for (auto& th : pool) th.join();
+  if (shared)
+    for (int i = 1; i < groups; ++i)
+      std::memcpy(centroids + (size_t)i * codewords * dbar, centroids, sizeof(float) * (size_t)codewords * dbar);
+  if (inertia_opt != nullptr)
+    for (int it = 0; it <= iters; ++it) {
+      double s = 0.0;
+      for (int b = 0; b < ncb; ++b) s += iner[(size_t)b * (iters + 1) + it];
+      inertia_opt[it] = s;
+    }
+  return bad.load() ? HCA_ERR_BAD_ARG : HCA_OK;
+}
+
+int32_t hca_vq_assign(const hca_shape* shape, const hca_vq_codebook* cb, void* pcache, const void* k_new_f16,
+                      int64_t T, const int64_t* n_resident, float* acc_opt, int32_t* pos_opt,
+                      const int64_t* value_row0, void* stream) {
+  Layout L;
+  int32_t rc = vq_layout(shape, cb, &L, true);
+  if (rc != HCA_OK) return rc;
+  if (pcache == nullptr || T < 0 || (T > 0 && k_new_f16 == nullptr)) return HCA_ERR_BAD_ARG;
+  NRes nr, vrow0;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  for (int b = 0; b < L.batch; ++b)
+    if (nr.n[b] + T > L.cap) return HCA_ERR_CAPACITY;
+  for (int b = 0; b < kMaxBatch; ++b) vrow0.n[b] = 0;
+  for (int b = 0; b < L.batch; ++b) vrow0.n[b] = value_row0 ? value_row0[b] : nr.n[b];
+  return launch_vq_assign(L, cb->groups, cb->codewords, cb->centroids, (uint8_t*)pcache, k_new_f16, T, nr, acc_opt,
+                          pos_opt, vrow0, (hipStream_t)stream);
+}
+
+int32_t hca_vq_score(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache, const void* q_f16,
+                     const int64_t* n_resident, float* lut, float* sel, float* z_opt, void* stream) {
+  Layout L;
+  int32_t rc = vq_layout(shape, cb, &L, true);
+  if (rc != HCA_OK) return rc;
+  if (pcache == nullptr || q_f16 == nullptr || lut == nullptr || sel == nullptr) return HCA_ERR_BAD_ARG;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  return launch_vq_score(L, cb->groups, cb->codewords, cb->centroids, (const uint8_t*)pcache, q_f16, nr, nmax, lut,
+                         sel, z_opt, (hipStream_t)stream);
+}
+
+int32_t hca_vq_attend_gathered(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache,
+                               const float* lut, const int32_t* idx, const int32_t* count, int32_t k,
+                               float sm_scale, float* y, float* acc_opt, void* workspace, void* stream) {
+  Layout L;
+  int32_t rc = vq_layout(shape, cb, &L, false);
+  if (rc != HCA_OK) return rc;
+  if (pcache == nullptr || lut == nullptr || idx == nullptr || count == nullptr || y == nullptr ||
+      workspace == nullptr)
+    return HCA_ERR_BAD_ARG;
+  if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
+  return launch_vq_attend_gathered(L, cb->groups, cb->codewords, (const uint8_t*)pcache, lut, idx, count, k, sm_scale,
+                                   y, acc_opt, workspace, (hipStream_t)stream);
+}
+
+}  // extern "C"

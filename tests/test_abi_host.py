@@ -74,3 +74,55 @@ def test_bad_arguments_are_rejected_on_the_host(B):
                                C.c_float(1.0), one, None, one, None, None) == -1
     s2 = B.make_shape(1, 32, 7, 1024)
     assert L.hca_score_qkeys(C.byref(s2), one, one, n, one, None, None, None) == -1   # 32 % 7 != 0
+
+
+# ---- codebook form of the key path: host-side checks and the host-side trainer -------------------
+
+def test_vq_sizes_and_unsupported_shapes(B):
+    s = B.make_shape(2, 32, 8, 1000, bits=7, group=5)          # bits / group are not looked at by hca_vq_*
+    cb = B.make_codebook(32, 256)
+    assert B.hca_vq_pcache_bytes(s, cb) == 2 * 8 * 1000 * 32
+    assert B.hca_vq_lut_bytes(s, cb) == 2 * 8 * 32 * 256 * 4 * 4
+    assert B.hca_vq_pcache_bytes(s, B.make_codebook(64, 128)) == 2 * 8 * 1000 * 64
+    for g, c in ((16, 256), (32, 257), (64, 256), (32, 0)):     # 64 x 256 x 4 heads is beyond 128 KiB of LDS
+        assert B.hca_vq_pcache_bytes(s, B.make_codebook(g, c)) == 0
+    s1 = B.make_shape(1, 8, 8, 1000)                            # one query head per KV head: 64 x 256 fits
+    assert B.hca_vq_pcache_bytes(s1, B.make_codebook(64, 256)) == 8 * 1000 * 64
+
+
+def test_vq_bad_arguments_are_rejected_on_the_host(B):
+    L = B.lib()
+    s = B.make_shape(1, 32, 8, 1024)
+    one = C.c_void_p(256)
+    n = (C.c_int64 * 1)(1000)
+    cb = B.hca_vq_codebook(32, 256, 256)
+    nocb = B.hca_vq_codebook(32, 256, None)
+    assert L.hca_vq_assign(C.byref(s), C.byref(nocb), one, one, 1, n, None, None, None, None) == -1
+    assert L.hca_vq_assign(C.byref(s), C.byref(cb), None, one, 1, n, None, None, None, None) == -1
+    assert L.hca_vq_assign(C.byref(s), C.byref(cb), one, one, 25, n, None, None, None, None) == -3
+    assert L.hca_vq_score(C.byref(s), C.byref(cb), one, one, n, None, one, None, None) == -1
+    assert L.hca_vq_score(C.byref(s), C.byref(B.hca_vq_codebook(48, 256, 256)), one, one, n, one, one, None, None) == -2
+    assert L.hca_vq_attend_gathered(C.byref(s), C.byref(cb), one, one, one, one, 0, 1.0, one, None, one, None) == -3
+    assert L.hca_vq_train(None, 10, 128, 32, 4, one, 1, 0, one, None) == -1
+    assert L.hca_vq_train(one, 10, 128, 48, 4, one, 1, 0, one, None) == -1
+
+
+@pytest.mark.parametrize("g,c,shared", [(32, 64, False), (64, 16, False), (32, 24, True)])
+def test_vq_trainer_matches_the_oracle(B, g, c, shared):
+    """The library's host-side k-means and the oracle's follow the same definition in the same order,
+    so codebooks and objective values must be identical."""
+    import numpy as np
+    import oracle
+    rng = np.random.default_rng(g + c)
+    nval = 1200
+    kval = rng.standard_normal((nval, 128)).astype(np.float16)
+    init = (rng.choice(nval * g, c, replace=False) if shared else
+            np.stack([rng.choice(nval, c, replace=False) for _ in range(g)])).astype(np.int32)
+    cen, iner = B.hca_vq_train(kval, g, c, init, 5, shared)
+    ocen, oiner = oracle.vq_train(kval, g, c, init, 5, shared)
+    assert np.array_equal(cen, ocen)
+    assert np.allclose(iner, oiner, rtol=1e-12)
+    bad = init.copy()
+    bad.flat[0] = nval * g + 7
+    with pytest.raises(B.HcaError):
+        B.hca_vq_train(kval, g, c, bad, 1, shared)
