@@ -392,6 +392,73 @@ def per_layer_latency_grouped(cfg, groups, streams, iters=8):
     return {"parts": groups, "ms_per_layer": ms, "host_enqueue_ms": host_ms, "gate_ms": gate / cycles_per_ms}
 
 
+def vq_probe(w, iters, g=32, c=256):
+    """Codebook form of the key path on one layer of the workload: bulk assignment (tokens/s), table build
+    + lookup scan (time, bytes of the index matrix streamed + scores written against the HBM peak, and
+    table bytes read from LDS against the LDS peak), with the key-scan of the uniform 4-bit path beside it."""
+    import numpy as np
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    G = w.n_q_heads // w.n_kv_heads
+    cap = w.n + 16
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    d = S.make_layer(w, 0, device="cuda", want_values=False)
+    rng = np.random.default_rng(1000 * w.config + 7)
+    # codebooks from the library's host trainer on the first 8192 tokens of each KV head of sequence 0
+    t0 = time.perf_counter()
+    cen = []
+    for h in range(w.n_kv_heads):
+        kval = d["keys"][0, h, :8192].cpu().numpy()
+        init = np.stack([rng.choice(kval.shape[0], c, replace=False) for _ in range(g)]).astype(np.int32)
+        cen.append(B.hca_vq_train(kval, g, c, init, 4)[0])
+    t_train = time.perf_counter() - t0
+    cen = torch.from_numpy(np.stack(cen)).cuda()
+    cb = B.make_codebook(g, c, cen)
+    P = [torch.empty(B.hca_vq_pcache_bytes(shape, cb), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    lut = torch.empty(B.hca_vq_lut_bytes(shape, cb) // 4, dtype=torch.float32, device="cuda")
+    sel = torch.empty(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
+    n0 = [0] * w.batch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    B.hca_vq_assign(shape, cb, P[1], d["keys"], w.n, n0)
+    e0.record()
+    B.hca_vq_assign(shape, cb, P[0], d["keys"], w.n, n0)
+    e1.record()
+    torch.cuda.synchronize()
+    assign_ms = e0.elapsed_time(e1)
+    n = [w.n] * w.batch
+    q = d["q"]
+    for i in range(3):
+        B.hca_vq_score(shape, cb, P[i & 1], q, n, lut, sel)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(iters):
+        B.hca_vq_score(shape, cb, P[i & 1], q, n, lut, sel)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    rows = w.batch * w.n_kv_heads
+    hbm_bytes = rows * w.n * (g + 4)
+    lds_bytes = rows * w.n * g * G * 4
+    # LDS: 256 compute units x 256 B per clock (16-byte reads, measured: 4 clocks per conflict-free wave read)
+    # x 2.4 GHz.  Assignment: per centroid and channel one subtract and one fused multiply-add = 3 flop.
+    lds_peak = 256 * 256 * 2.4
+    assign_flop = rows * w.n * g * c * (128 // g) * 3
+    out = {"workload": w.name, "groups": g, "codewords": c, "train_s_host": t_train,
+           "assign_ms": assign_ms, "assign_token_heads_per_s": rows * w.n / assign_ms * 1e3,
+           "assign_roofline": {"bound": "alu", "achieved": assign_flop / assign_ms / 1e9, "peak": 157.3,
+                               "unit": "TFLOP/s", "frac": assign_flop / assign_ms / 1e9 / 157.3},
+           "score_ms": ms, "index_bytes_per_token_head": g,
+           "context_tokens_scored_per_s": w.batch * w.n / ms * 1e3,
+           "score_roofline": {"bound": "lds", "achieved": lds_bytes / ms / 1e6, "peak": lds_peak, "unit": "GB/s",
+                              "frac": lds_bytes / ms / 1e6 / lds_peak,
+                              "hbm_GBs": hbm_bytes / ms / 1e6, "hbm_frac": hbm_bytes / ms / 1e6 / HBM_PEAK_GBS}}
+    del P, lut, sel, d
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    return out
+
+
 def scan_only(w, iters):
     """Key-scan kernel alone on one layer (two cache copies alternate), preceded by a plain 1 GiB
     device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the counters (profiles/)."""
@@ -493,8 +560,9 @@ def main():
                     help="row splits tried by the pipelined per-layer latency probe")
     ap.add_argument("--stages", type=int, default=4, choices=[3, 4],
                     help="native pipeline: 4 = scan | top-k | gather | attend; 3 = top-k shares the scan stream")
-    ap.add_argument("--mode", default="step", choices=["step", "scan"],
-                    help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration")
+    ap.add_argument("--mode", default="step", choices=["step", "scan", "vq"],
+                    help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration; "
+                         "vq: the codebook form of the key path (assignment, table, lookup scan) on one layer")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -514,6 +582,9 @@ def main():
     L = args.layers or w.layers
     if args.mode == "scan":
         return scan_only(w, args.steps)
+    if args.mode == "vq":
+        print(json.dumps(dict(mode="vq", **vq_probe(w, args.steps))), flush=True)
+        return
     # host link: peak (one large pinned copy) and the gather as the path issues it
     # The boxes expose 4 hardware queues per process and HIP deals streams onto them round-robin, so
     # exactly four streams are used (the default one included): one per pipeline stage, none shared.
@@ -546,6 +617,11 @@ def main():
                 if g["host_enqueue_ms"] < g["gate_ms"] and g["ms_per_layer"] < latency[name]["ms_per_layer"]:
                     latency[name]["ms_per_layer"] = g["ms_per_layer"]
                     latency[name]["parts"] = parts
+
+    codebook = None
+    if not args.no_latency:
+        codebook = vq_probe(S.CONFIGS[4], 10)
+        log(f"codebook key path at 1M: table + lookup scan {codebook['score_ms']:.3f} ms per layer")
 
     total_steps = args.steps + args.warmup
     model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers))
@@ -633,6 +709,7 @@ def main():
                    "physical_value_layers": phys, "pipeline": args.pipeline},
         "pipelined_ms_per_layer": ms_per_step / L,
         "per_layer_decode_latency": latency,
+        "codebook_key_path": codebook,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,

@@ -96,3 +96,69 @@ def test_one_layer_at_full_size(oracle, cfg):
         assert np.array_equal(_rows(st.idx), idx)
         y, _ = oracle.attend(oc, q16, idx, count, pos, V, st.sm_scale)
         assert _rel_err(st.y.cpu().numpy().reshape(-1, 128), y) <= TOL
+
+
+def test_vq_one_layer_at_full_size(oracle):
+    """Codebook form at the shape bench.py --mode vq times (config 4 layer: 1 Mi tokens x 8 KV heads, g = 32,
+    c = 256).  The assignment is checked on a sample of tokens (the oracle's brute-force nearest-centroid
+    search over all 8 Mi token-heads would take minutes); scores, top-k and the attention output are
+    checked in full on an index matrix drawn by the test and handed to both sides."""
+    from paper_2507_19823_amd import binding as B
+    w = S.CONFIGS[4]
+    R, n, G, g, c, k = w.batch * w.n_kv_heads, w.n, w.gqa, 32, 256, w.k
+    cap = n + 32
+    rng = np.random.default_rng(4004)
+    d = S.make_layer(w, 0, device="cuda")
+    keys = d["keys"]
+    cen = np.stack([oracle.vq_train(keys[0, h, :4096].cpu().numpy(), g, c,
+                                    np.stack([rng.choice(4096, c, replace=False) for _ in range(g)]).astype(np.int32), 2)[0]
+                    for h in range(w.n_kv_heads)])
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    cend = torch.from_numpy(cen).cuda()
+    cb = B.make_codebook(g, c, cend)
+    P = torch.zeros(B.hca_vq_pcache_bytes(shape, cb), dtype=torch.uint8, device="cuda")
+    B.hca_vq_assign(shape, cb, P, keys, n, [0])
+    torch.cuda.synchronize()
+    Pg = P.view(R, cap, g)
+    # sample: the first and last 1100 tokens and 6000 random ones per row
+    pick = np.unique(np.concatenate([np.arange(1100), np.arange(n - 1100, n), rng.integers(0, n, 6000)]))
+    oc = oracle.VQCache(R, len(pick), cen)
+    oracle.vq_assign(oc, keys.view(R, n, 128)[:, torch.from_numpy(pick).cuda()].cpu().numpy())
+    assert np.array_equal(Pg[:, torch.from_numpy(pick).cuda()].cpu().numpy(), oc.P.astype(np.uint8)), "indices differ"
+    assert int(Pg[:, n:].max()) == 0
+    del oc
+
+    # scores / top-k / attend on a drawn index matrix (zipf-like code popularity, as trained codebooks show)
+    pop = rng.permutation(c)
+    Pr = pop[np.minimum((rng.pareto(1.2, (R, n, g)) * 8).astype(np.int64), c - 1)].astype(np.uint8)
+    Pg[:, :n] = torch.from_numpy(Pr).cuda()
+    oc = oracle.VQCache(R, cap, cen)
+    oc.P[:, :n] = Pr
+    oc.n[:] = n
+    q = d["q"]
+    lut = torch.empty(B.hca_vq_lut_bytes(shape, cb) // 4, dtype=torch.float32, device="cuda")
+    sel = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
+    idx = torch.zeros(w.batch, w.n_kv_heads, k, dtype=torch.int32, device="cuda")
+    count = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(shape, k, 1), dtype=torch.uint8, device="cuda")
+    pos = torch.arange(cap, dtype=torch.int32, device="cuda").repeat(w.batch, w.n_kv_heads, 1).contiguous()
+    acc = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
+    y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    v_host = torch.empty(w.batch, w.n_kv_heads, n, 128, dtype=torch.float16, pin_memory=True)
+    v_host.copy_(d["values"])
+    sm = 1.0 / np.sqrt(128.0)
+    B.hca_vq_score(shape, cb, P, q, [n], lut, sel, None)
+    B.hca_topk(shape, sel, [n], k, idx, count, ws)
+    B.hca_gather_values(shape, idx, count, k, pos, v_host, n, n, None, 0, ws)
+    B.hca_vq_attend_gathered(shape, cb, P, lut, idx, count, k, sm, y, acc, ws)
+    torch.cuda.synchronize()
+    T = oracle.vq_lut(oc, q.cpu().numpy().reshape(R * G, 128))
+    osel, _ = oracle.vq_score(oc, T, want_z=False)
+    assert np.array_equal(_rows(sel)[:, :n].view(np.uint32), osel[:, :n].view(np.uint32)), "selection scores differ"
+    oidx, ocount = oracle.topk(osel, oc.n, k)
+    assert np.array_equal(_rows(idx), oidx), "top-k index sets differ"
+    opos = np.tile(np.arange(cap, dtype=np.int32), (R, 1))
+    oacc = np.zeros((R, cap), np.float32)
+    oy, _ = oracle.vq_attend(oc, T, oidx, ocount, opos, v_host.numpy().reshape(R, n, 128), sm, acc=oacc)
+    assert _rel_err(y.cpu().numpy().reshape(-1, 128), oy) <= TOL
+    assert np.allclose(_rows(acc), oacc, rtol=1e-4, atol=1e-7)
