@@ -319,6 +319,16 @@ int32_t hca_vq_attend_gathered(const hca_shape* shape, const hca_vq_codebook* cb
                                const float* lut, const int32_t* idx, const int32_t* count, int32_t k,
                                float sm_scale, float* y, float* acc_opt, void* workspace, void* stream);
 
+/* hca_evict for a codebook cache: the same keep-set (newest n_protect slots, then the M - n_protect
+ * highest accumulated scores, ties to the lower slot) and the same stable compaction, applied to the
+ * index rows of pcache together with acc and pos.  In place (all three *_dst NULL) or into a second
+ * buffer set (all three given, distinct from the sources; rows with n_resident <= M are carried over
+ * unchanged).  workspace: hca_workspace_bytes(shape, k, M).  Afterwards n_resident = min(n_resident, M).
+ * Errors: HCA_ERR_CAPACITY if M < 1, M > capacity or n_protect > M. */
+int32_t hca_vq_evict(const hca_shape* shape, const hca_vq_codebook* cb, void* pcache, float* acc, int32_t* pos,
+                     const int64_t* n_resident, int64_t M, int64_t n_protect, int32_t* kept_opt, void* workspace,
+                     void* pcache_dst, float* acc_dst, int32_t* pos_dst, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

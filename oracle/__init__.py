@@ -271,3 +271,16 @@ def vq_attend(cache, T, idx, count, pos, V, sm_scale, acc=None, want_w=False):
                                C.c_int64(k), _p(pos), _p(V), C.c_int64(V.shape[1]), C.c_float(sm_scale),
                                _p(y), _p(w), _p(acc)), "vq_attend")
     return y, w
+
+
+def vq_evict(cache, acc, pos, M, n_protect):
+    """Compacts cache.P / acc / pos in place.  Returns kept int32 [R,M] (-1 padded)."""
+    assert acc.dtype == np.float32 and acc.flags.c_contiguous
+    assert pos.dtype == np.int32 and pos.flags.c_contiguous
+    kept = np.zeros((cache.R, M), np.int32)
+    n_new = np.zeros(cache.R, np.int64)
+    _check(lib().hco_vq_evict(_p(cache.P), _p(acc), _p(pos), C.c_int64(cache.R), C.c_int(cache.g),
+                              C.c_int64(cache.cap), _p(cache.n), C.c_int64(M), C.c_int64(n_protect),
+                              _p(kept), _p(n_new)), "vq_evict")
+    cache.n[...] = n_new
+    return kept

@@ -19,6 +19,8 @@
  *                    selection score (max over the query heads of the group)
  *   hco_vq_attend    softmax over the selected set and the weighted value sum of
  *                    Eq. 5 with the logits of Eq. 3; accumulated-score update
+ *   hco_vq_evict     keep-M by accumulated score with stable compaction of the
+ *                    index rows (the policy of hco_evict in hca_oracle.c)
  *
  * Indices are 0-based.  Everything that feeds an integer decision is single
  * fp32 operations in one fixed order (compile with -ffp-contract=off, no
@@ -294,4 +296,42 @@ int hco_vq_attend(const float* T, const uint16_t* P, int64_t R, int G, int D, in
     free(l); free(a); free(wsum);
   }
   return err ? HCO_ERR_BAD_ARG : HCO_OK;
+}
+
+/* --------------------------------------------------------------- evict --- */
+
+int hco_topk(const float* sel, int64_t R, int64_t cap, const int64_t* n, int64_t k, int32_t* idx,
+             int32_t* count);   /* hca_oracle.c */
+
+/* Accumulated-score eviction of a codebook cache: the keep-set and the order are those of
+ * hco_evict in hca_oracle.c (newest Rp slots kept; of the others the M - Rp highest acc, ties to
+ * the lower slot; kept slots move in ascending old-slot order to slots 0..M-1); the rows that
+ * move are index rows.  kept: [R][M] old slots (-1 past n_new[r]); rows with n <= M unchanged. */
+int hco_vq_evict(uint16_t* P, float* acc, int32_t* pos, int64_t R, int g, int64_t cap,
+                 const int64_t* n, int64_t M, int64_t Rp, int32_t* kept, int64_t* n_new) {
+  if (g < 1 || M < 0 || Rp < 0 || Rp > M) return HCO_ERR_BAD_ARG;
+  int err = 0;
+  for (int64_t r = 0; r < R; ++r) {
+    int64_t nr = n[r];
+    int32_t* kp = kept + r * M;
+    if (nr <= M) {
+      for (int64_t j = 0; j < M; ++j) kp[j] = j < nr ? (int32_t)j : -1;
+      n_new[r] = nr;
+      continue;
+    }
+    for (int64_t j = 0; j < nr; ++j) if (isnan(acc[r * cap + j])) err = 1;
+    int64_t nfree = nr - Rp;
+    int32_t c = 0;
+    if (M - Rp > 0 && hco_topk(acc + r * cap, 1, cap, &nfree, M - Rp, kp, &c) != HCO_OK) err = 1;
+    for (int64_t j = 0; j < Rp; ++j) kp[c + j] = (int32_t)(nfree + j);
+    for (int64_t d = 0; d < M; ++d) {           /* destination <= source, ascending: in place is safe */
+      int64_t s = kp[d];
+      if (s == d) continue;
+      memmove(P + (r * cap + d) * g, P + (r * cap + s) * g, sizeof(uint16_t) * (size_t)g);
+      acc[r * cap + d] = acc[r * cap + s];
+      pos[r * cap + d] = pos[r * cap + s];
+    }
+    n_new[r] = M;
+  }
+  return err ? HCO_ERR_NAN : HCO_OK;
 }

@@ -110,6 +110,8 @@ def lib():
         L.hca_vq_assign.argtypes = [sp, cbp, vp, vp, i64, vp, vp, vp, vp, vp]
         L.hca_vq_score.restype = i32
         L.hca_vq_score.argtypes = [sp, cbp, vp, vp, vp, vp, vp, vp, vp]
+        L.hca_vq_evict.restype = i32
+        L.hca_vq_evict.argtypes = [sp, cbp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
         L.hca_vq_attend_gathered.restype = i32
         L.hca_vq_attend_gathered.argtypes = [sp, cbp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp]
         _lib = L
@@ -299,3 +301,10 @@ def hca_vq_attend_gathered(shape, cb, pcache, lut, idx, count, k, sm_scale, y, a
     _check(lib().hca_vq_attend_gathered(C.byref(shape), C.byref(cb), _ptr(pcache), _ptr(lut), _ptr(idx), _ptr(count),
                                         int(k), float(sm_scale), _ptr(y), _ptr(acc), _ptr(workspace), _stream(stream)),
            "hca_vq_attend_gathered")
+
+
+def hca_vq_evict(shape, cb, pcache, acc, pos, n_resident, M, n_protect, kept, workspace, pcache_dst=None, acc_dst=None,
+                 pos_dst=None, stream=None):
+    _check(lib().hca_vq_evict(C.byref(shape), C.byref(cb), _ptr(pcache), _ptr(acc), _ptr(pos),
+                              _nres(n_resident, shape.batch), int(M), int(n_protect), _ptr(kept), _ptr(workspace),
+                              _ptr(pcache_dst), _ptr(acc_dst), _ptr(pos_dst), _stream(stream)), "hca_vq_evict")

@@ -270,6 +270,101 @@ int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, co
   return evict_move(L, kcache, acc, pos, pl, 0, M, st);
 }
 
+// ---- codebook caches: the rows that move are index rows of g bytes (g = 32 or 64) ------------
+// kept[d] -> destination slot d; one thread per 16-byte piece of a row.
+__global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const uint8_t* __restrict__ pcache,
+                                                       const float* __restrict__ acc, const int32_t* __restrict__ pos,
+                                                       int n_kv_heads, SelRows sr, int64_t M,
+                                                       const int32_t* __restrict__ kept, uint8_t* __restrict__ pdst,
+                                                       float* __restrict__ adst, int32_t* __restrict__ odst,
+                                                       int64_t dst_row) {
+  const int row = blockIdx.y;
+  if (sr.want[row / n_kv_heads] < 0) return;
+  const int pieces = g / 16;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t d = gid / pieces;
+  const int j = (int)(gid % pieces);
+  if (d >= M) return;
+  const int64_t s = kept[(int64_t)row * M + d];
+  reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * g)[j] =
+      reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * g)[j];
+  if (j == 0) adst[(int64_t)row * dst_row + d] = acc[(int64_t)row * cap + s];
+  if (j == 1) odst[(int64_t)row * dst_row + d] = pos[(int64_t)row * cap + s];
+}
+
+// Copies the first cnt[b] slots of every row that `which` selects from (src, row stride ssrc) to (dst, sdst):
+// the copy-back of an in-place eviction (compacted rows, cnt = M) and the carry-over of untouched rows
+// of an out-of-place one (cnt = n).
+__global__ __launch_bounds__(256) void vq_evict_copy_rows(int g, int n_kv_heads, SelRows sr, bool compacted, NRes cnt,
+                                                          const uint8_t* __restrict__ psrc, const float* __restrict__ asrc,
+                                                          const int32_t* __restrict__ osrc, int64_t ssrc,
+                                                          uint8_t* __restrict__ pdst, float* __restrict__ adst,
+                                                          int32_t* __restrict__ odst, int64_t sdst) {
+  const int row = blockIdx.y;
+  const int b = row / n_kv_heads;
+  if ((sr.want[b] >= 0) != compacted) return;
+  const int64_t m = cnt.n[b];
+  const int pieces = g / 16;
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (gid < m * pieces)
+    reinterpret_cast<uint4*>(pdst + (int64_t)row * sdst * g)[gid] =
+        reinterpret_cast<const uint4*>(psrc + (int64_t)row * ssrc * g)[gid];
+  if (gid < m) {
+    adst[(int64_t)row * sdst + gid] = asrc[(int64_t)row * ssrc + gid];
+    odst[(int64_t)row * sdst + gid] = osrc[(int64_t)row * ssrc + gid];
+  }
+}
+
+int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+                        int64_t M, int64_t n_protect, int32_t* kept, void* ws, uint8_t* pcache_dst, float* acc_dst,
+                        int32_t* pos_dst, hipStream_t st) {
+  SelRows sr;
+  bool any = false, carry = false;
+  for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
+  for (int b = 0; b < L.batch; ++b) {
+    if (nr.n[b] > M) {
+      sr.nsel[b] = nr.n[b] - n_protect;
+      sr.want[b] = M - n_protect;
+      any = true;
+    } else {
+      carry = true;
+    }
+  }
+  const bool oop = pcache_dst != nullptr;
+  EvictWs e;                                // the staging for 64 B of uniform codes per slot holds g <= 64 index bytes
+  carve(&e, ws, L, M);
+  const int pieces = g / 16;
+  if (oop && carry && nmax > 0) {
+    dim3 gr((unsigned)((nmax * pieces + 255) / 256), (unsigned)L.rows);
+    vq_evict_copy_rows<<<gr, 256, 0, st>>>(g, L.n_kv_heads, sr, false, nr, pcache, acc, pos, L.cap, pcache_dst, acc_dst,
+                                           pos_dst, L.cap);
+  }
+  if (!any) {
+    if (oop) HCA_HIP(hipGetLastError());
+    return HCA_OK;
+  }
+  int32_t* kp = kept != nullptr ? kept : e.kept;
+  SelectPlan p;
+  select_plan(&p, e.select, L.rows, nmax);
+  int32_t rc = select_run(p, acc, L.cap, L.rows, L.n_kv_heads, sr, st);
+  if (rc != HCA_OK) return rc;
+  dim3 g1((unsigned)p.nchunks, (unsigned)L.rows);
+  evict_positions<<<g1, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kp);
+  dim3 gg((unsigned)((M * pieces + 255) / 256), (unsigned)L.rows);
+  if (oop) {
+    vq_evict_gather<<<gg, 256, 0, st>>>(g, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, pcache_dst, acc_dst, pos_dst,
+                                        L.cap);
+  } else {
+    vq_evict_gather<<<gg, 256, 0, st>>>(g, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, e.codes, e.acc, e.pos, M);
+    NRes cnt;
+    for (int b = 0; b < kMaxBatch; ++b) cnt.n[b] = M;
+    vq_evict_copy_rows<<<gg, 256, 0, st>>>(g, L.n_kv_heads, sr, true, cnt, e.codes, e.acc, e.pos, M, pcache, acc, pos,
+                                           L.cap);
+  }
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
 // Sliced eviction for the step driver (out of place only): slice 0 prepares, every slice moves its
 // share of the destination slots.
 int32_t launch_evict_slice(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,

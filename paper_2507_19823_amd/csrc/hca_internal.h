@@ -86,6 +86,9 @@ int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, 
                          int64_t T, const NRes& nr, float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st);
 int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, const uint8_t* pcache, const void* q,
                         const NRes& nr, int64_t nmax, float* lut, float* sel, float* z_opt, hipStream_t st);
+int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+                        int64_t M, int64_t n_protect, int32_t* kept, void* ws, uint8_t* pcache_dst, float* acc_dst,
+                        int32_t* pos_dst, hipStream_t st);
 size_t evict_workspace_bytes(const Layout& L, int64_t M);
 int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, const NRes& nr,
                      int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, void* kcache_dst,

@@ -399,4 +399,23 @@ int32_t hca_vq_attend_gathered(const hca_shape* shape, const hca_vq_codebook* cb
                                    y, acc_opt, workspace, (hipStream_t)stream);
 }
 
+int32_t hca_vq_evict(const hca_shape* shape, const hca_vq_codebook* cb, void* pcache, float* acc, int32_t* pos,
+                     const int64_t* n_resident, int64_t M, int64_t n_protect, int32_t* kept_opt, void* workspace,
+                     void* pcache_dst, float* acc_dst, int32_t* pos_dst, void* stream) {
+  Layout L;
+  int32_t rc = vq_layout(shape, cb, &L, false);
+  if (rc != HCA_OK) return rc;
+  if (pcache == nullptr || acc == nullptr || pos == nullptr || workspace == nullptr) return HCA_ERR_BAD_ARG;
+  const bool oop = pcache_dst != nullptr || acc_dst != nullptr || pos_dst != nullptr;
+  if (oop && (pcache_dst == nullptr || acc_dst == nullptr || pos_dst == nullptr)) return HCA_ERR_BAD_ARG;
+  if (oop && (pcache_dst == pcache || acc_dst == acc || pos_dst == pos)) return HCA_ERR_BAD_ARG;
+  if (M < 1 || M > L.cap || n_protect < 0 || n_protect > M) return HCA_ERR_CAPACITY;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  return launch_vq_evict(L, cb->groups, (uint8_t*)pcache, acc, pos, nr, nmax, M, n_protect, kept_opt, workspace,
+                         (uint8_t*)pcache_dst, acc_dst, pos_dst, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -172,3 +172,51 @@ def test_vq_ragged_lengths_and_empty_rows(B, oracle):
     ig = st.idx.cpu().numpy().reshape(R, k)
     for r in range(R):
         assert np.array_equal(ig[r, :count[r]], idx[r, :count[r]])
+
+
+@pytest.mark.parametrize("mode", ["inplace", "spare"])
+@pytest.mark.parametrize("g,n,M,Rp", [(32, 5000, 3000, 16), (64, 1200, 700, 0), (32, 900, 900, 4), (32, 3000, 1, 1)])
+def test_vq_evict_matches_oracle(B, oracle, mode, g, n, M, Rp):
+    """Keep-set, compacted index rows, acc and pos against the oracle; one sequence is short enough to be
+    left alone (n <= M) and must come through unchanged, also into the spare buffers."""
+    rng = np.random.default_rng(n + M + Rp + g)
+    batch, hkv, G, c = 2, 2, 4, 64
+    R, cap = batch * hkv, n + 5
+    lens = [n, min(n, M) - (1 if M > 1 else 0)]
+    keys = rng.standard_normal((batch, hkv, n, D)).astype(np.float16)
+    cen = _codebook(oracle, rng, keys, hkv, g, c, iters=1)
+    st = _State(B, batch, hkv * G, hkv, cap, g, c, cen, 8)
+    st.assign(torch.from_numpy(keys))
+    oc = oracle.VQCache(R, cap, cen)
+    oracle.vq_assign(oc, keys.reshape(R, n, D))
+    oc.n[:] = np.repeat(lens, hkv)
+    acc = np.zeros((R, cap), np.float32)
+    acc[:, :n] = rng.integers(0, 5, (R, n)).astype(np.float32) * 0.5              # many ties
+    acc[1, :n] = rng.standard_normal(n).astype(np.float32) ** 2
+    pos = np.tile(rng.permutation(cap).astype(np.int32), (R, 1))
+    accd = torch.from_numpy(acc.reshape(batch, hkv, cap)).cuda()
+    posd = torch.from_numpy(pos.reshape(batch, hkv, cap)).cuda()
+    kept = torch.full((batch, hkv, M), -5, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(st.shape, 8, M), dtype=torch.uint8, device="cuda")
+    if mode == "spare":
+        P2 = torch.full_like(st.P, 0xAB)
+        acc2, pos2 = torch.full_like(accd, -1.0), torch.full_like(posd, -1)
+        B.hca_vq_evict(st.shape, st.cb, st.P, accd, posd, lens, M, Rp, kept, ws, P2, acc2, pos2)
+        Pout, aout, pout = P2, acc2, pos2
+    else:
+        B.hca_vq_evict(st.shape, st.cb, st.P, accd, posd, lens, M, Rp, kept, ws)
+        Pout, aout, pout = st.P, accd, posd
+    torch.cuda.synchronize()
+    okept = oracle.vq_evict(oc, acc, pos, M, Rp)
+    Pg = Pout.cpu().numpy().reshape(R, cap, g)
+    ag, pg = aout.cpu().numpy().reshape(R, cap), pout.cpu().numpy().reshape(R, cap)
+    kg = kept.cpu().numpy().reshape(R, M)
+    for r in range(R):
+        m = int(oc.n[r])
+        assert m == min(lens[r // hkv], M)
+        if lens[r // hkv] > M:
+            assert np.array_equal(kg[r], okept[r])
+        else:
+            assert np.all(kg[r] == -5)                       # rows left alone report nothing
+        assert np.array_equal(Pg[r, :m], oc.P[r, :m].astype(np.uint8))
+        assert np.array_equal(ag[r, :m], acc[r, :m]) and np.array_equal(pg[r, :m], pos[r, :m])

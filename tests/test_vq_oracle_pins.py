@@ -285,3 +285,41 @@ def test_index_matrix_footprint_matches_the_papers_ratios(oracle):
         vc = oracle.VQCache(3, 1000, np.zeros((1, g, 4, D // g), np.float32))
         assert vc.P.itemsize * 8 == gold["index_bits"]
         assert vc.P.nbytes / (3 * 1000 * gold["head_dim"] * 2) == gold[key]
+
+
+# ----------------------------------------------------------------- evict ---
+
+def _brute_evict(acc, n, M, Rp):
+    """Keep-set by a full stable sort: newest Rp slots plus the M - Rp highest acc among the others
+    (ties to the lower slot), in ascending slot order."""
+    if n <= M:
+        return list(range(n))
+    free = n - Rp
+    order = sorted(range(free), key=lambda j: (-float(acc[j]), j))[:M - Rp]
+    return sorted(order) + list(range(free, n))
+
+
+@pytest.mark.parametrize("n,M,Rp", [(64, 48, 0), (64, 48, 8), (50, 64, 4), (64, 1, 1), (33, 32, 32), (64, 17, 3)])
+def test_vq_evict_brute_force(oracle, n, M, Rp):
+    rng = np.random.default_rng(n * 100 + M + Rp)
+    R, g, cap = 3, 32, 70
+    vc = oracle.VQCache(R, cap, _codebook(rng, 1, g, 16))
+    oracle.vq_assign(vc, _keys(rng, R, n))
+    P0 = vc.P.copy()
+    acc = np.zeros((R, cap), np.float32)
+    acc[:, :n] = rng.integers(0, 6, (R, n)).astype(np.float32) * 0.25      # many ties
+    acc[2, :n] = rng.standard_normal(n).astype(np.float32) ** 2
+    pos = np.zeros((R, cap), np.int32)
+    pos[:, :n] = rng.permutation(1000)[:n].astype(np.int32)
+    acc0, pos0 = acc.copy(), pos.copy()
+    kept = oracle.vq_evict(vc, acc, pos, M, Rp)
+    for r in range(R):
+        ref = _brute_evict(acc0[r], n, M, Rp)
+        m = len(ref)
+        assert vc.n[r] == m == min(n, M)
+        assert list(kept[r, :m]) == ref and np.all(kept[r, m:] == -1)
+        assert np.array_equal(vc.P[r, :m], P0[r, ref])
+        assert np.array_equal(acc[r, :m], acc0[r, ref]) and np.array_equal(pos[r, :m], pos0[r, ref])
+    snap = vc.P.copy()
+    oracle.vq_evict(vc, acc, pos, M, Rp)                                    # idempotent once n <= M
+    assert np.array_equal(vc.P, snap)
