@@ -284,3 +284,27 @@ def vq_evict(cache, acc, pos, M, n_protect):
                               _p(kept), _p(n_new)), "vq_evict")
     cache.n[...] = n_new
     return kept
+
+
+# ---- the paper's selection rule, Eq. 4 (hca_topp_oracle.c) ---------------------------------------
+
+def topp_weight(u):
+    f = lib().hco_topp_weight
+    f.restype = C.c_uint64
+    f.argtypes = [C.c_float]
+    return int(f(float(u)))
+
+
+def topp(sel, n, sm_scale, tau, k_max):
+    """sel [R,cap] fp32 -> (idx int32 [R,k_max] ascending, -1 padded; count int32 [R] = min(k*, k_max);
+    kstar int64 [R]; mass uint64 [R,2] = (Theta, Z))."""
+    sel = np.ascontiguousarray(sel, np.float32)
+    R, cap = sel.shape
+    n = _i64(n)
+    idx = np.zeros((R, k_max), np.int32)
+    count = np.zeros(R, np.int32)
+    kstar = np.zeros(R, np.int64)
+    mass = np.zeros((R, 2), np.uint64)
+    _check(lib().hco_topp(_p(sel), C.c_int64(R), C.c_int64(cap), _p(n), C.c_float(sm_scale), C.c_double(tau),
+                          C.c_int64(k_max), _p(idx), _p(count), _p(kstar), _p(mass)), "topp")
+    return idx, count, kstar, mass

@@ -1,4 +1,4 @@
-"""Compile the CPU oracle (plain C, gcc: hca_oracle.c and hca_vq_oracle.c) into oracle/libhca_oracle.so.
+"""Compile the CPU oracle (plain C, gcc: hca_oracle.c, hca_vq_oracle.c, hca_topp_oracle.c) into oracle/libhca_oracle.so.
 
 Flags matter: -ffp-contract=off keeps every fp32 operation a single rounded IEEE
 operation (the oracle's bit-level definition depends on it); no fast-math.
@@ -8,7 +8,8 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRCS = [os.path.join(HERE, "hca_oracle.c"), os.path.join(HERE, "hca_vq_oracle.c")]
+SRCS = [os.path.join(HERE, "hca_oracle.c"), os.path.join(HERE, "hca_vq_oracle.c"),
+        os.path.join(HERE, "hca_topp_oracle.c")]
 LIB = os.path.join(HERE, "libhca_oracle.so")
 
 
