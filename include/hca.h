@@ -251,6 +251,25 @@ int32_t hca_pipeline_scan_ms(hca_pipeline* p, int32_t timing_slot, float* ms);
 int32_t hca_export_kcache(const hca_shape* shape, const void* kcache, const int64_t* n_resident,
                           uint8_t* codes, void* scale_f16, void* zero_f16, void* stream);
 
+/* ---- The paper's selection rule ---------------------------------------------------------------
+ * Sec. 3.2, Eq. 4: with the slots of a row sorted by score in descending order (ties towards the lower
+ * slot, as in hca_topk), keep the shortest prefix whose cumulative attention weight reaches tau.  The
+ * weights are a~_j = softmax_j(sel_j * sm_scale) over the row's resident slots, sel being the per-KV-head
+ * selection score of hca_score_qkeys / hca_vq_score.  So that the integer k* does not depend on the order
+ * of a floating-point sum, each weight is an integer: l = sel * sm_scale; u = l - max l; t = u * log2(e)
+ * (all fp32); 0 below t = -64; fl = floor(t), f = t - fl; p = 2^f by the degree-6 Taylor polynomial in f ln 2
+ * (Horner, fused multiply-adds); w = (uint64)(p * 2^31) >> -fl.  Z = sum w; Theta = max(1, floor(Z * floor(tau *
+ * 2^64) / 2^64)) (Theta = Z for tau >= 1); k* = least k with w_(1) + ... + w_(k) >= Theta.
+ *   k_max     the prefix is cut at k_max slots (capacity of idx); 1 <= k_max <= capacity
+ *   idx       device, int32 [batch, n_kv_heads, k_max]: selected slots in ascending order
+ *   count     device, int32 [batch, n_kv_heads]: min(k*, k_max); 0 for a sequence without resident slots
+ *   mass_opt  device, uint64 [batch, n_kv_heads, 2] or NULL: (Theta, Z) of each row
+ *   workspace device, hca_workspace_bytes(shape, k_max, 1)
+ * The result feeds hca_gather_values / hca_attend_gathered like the result of hca_topk (k = k_max).
+ * Errors: HCA_ERR_BAD_ARG unless tau > 0 and sm_scale > 0; HCA_ERR_CAPACITY for k_max out of range. */
+int32_t hca_topp(const hca_shape* shape, const float* sel, const int64_t* n_resident, float sm_scale, double tau,
+                 int32_t k_max, int32_t* idx, int32_t* count, uint64_t* mass_opt, void* workspace, void* stream);
+
 /* ---- Codebook form of the key path ---------------------------------------------------------
  * The paper's own compressor: grouped vector quantisation (Sec. 3.1) and table-lookup scores
  * (Sec. 3.2, Eq. 3).  The head dimension is cut into g groups of dbar = head_dim / g channels, a

@@ -76,6 +76,8 @@ def lib():
         L.hca_score_qkeys.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.hca_topk.restype = i32
         L.hca_topk.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp]
+        L.hca_topp.restype = i32
+        L.hca_topp.argtypes = [sp, vp, vp, f32, C.c_double, i32, vp, vp, vp, vp, vp]
         L.hca_sparse_attend.restype = i32
         L.hca_sparse_attend.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp, i64, i64, vp, i64, f32, vp, vp,
                                         vp, vp, vp]
@@ -308,3 +310,8 @@ def hca_vq_evict(shape, cb, pcache, acc, pos, n_resident, M, n_protect, kept, wo
     _check(lib().hca_vq_evict(C.byref(shape), C.byref(cb), _ptr(pcache), _ptr(acc), _ptr(pos),
                               _nres(n_resident, shape.batch), int(M), int(n_protect), _ptr(kept), _ptr(workspace),
                               _ptr(pcache_dst), _ptr(acc_dst), _ptr(pos_dst), _stream(stream)), "hca_vq_evict")
+
+
+def hca_topp(shape, sel, n_resident, sm_scale, tau, k_max, idx, count, mass=None, workspace=None, stream=None):
+    _check(lib().hca_topp(C.byref(shape), _ptr(sel), _nres(n_resident, shape.batch), float(sm_scale), float(tau),
+                          int(k_max), _ptr(idx), _ptr(count), _ptr(mass), _ptr(workspace), _stream(stream)), "hca_topp")

@@ -149,6 +149,21 @@ int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resi
   return launch_topk(L, sel, nr, nmax, k, idx, count, workspace, (hipStream_t)stream);
 }
 
+int32_t hca_topp(const hca_shape* shape, const float* sel, const int64_t* n_resident, float sm_scale, double tau,
+                 int32_t k_max, int32_t* idx, int32_t* count, uint64_t* mass_opt, void* workspace, void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (sel == nullptr || idx == nullptr || count == nullptr || workspace == nullptr) return HCA_ERR_BAD_ARG;
+  if (!(tau > 0.0) || !(sm_scale > 0.0f)) return HCA_ERR_BAD_ARG;
+  if (k_max < 1 || k_max > L.cap) return HCA_ERR_CAPACITY;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  return launch_topp(L, sel, nr, nmax, sm_scale, tau, k_max, idx, count, mass_opt, workspace, (hipStream_t)stream);
+}
+
 int32_t hca_sparse_attend(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
                           const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,
                           int64_t host_stride, int64_t n_host_rows, const void* v_hbm, int64_t hbm_stride,

@@ -67,6 +67,8 @@ int64_t score_stamp_pairs(const Layout& L, int64_t nmax);
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
                     int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean = false);
 size_t topk_hist_bytes(int rows);
+int32_t launch_topp(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, float sm_scale, double tau,
+                    int32_t k_max, int32_t* idx, int32_t* count, uint64_t* mass_opt, void* ws, hipStream_t st);
 size_t attend_workspace_bytes(const Layout& L, int64_t k);
 int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                       const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,

@@ -233,6 +233,11 @@ struct TopkWs {
   uint32_t* coff;      // [rows][1024][2]
   uint2* cand;         // [rows][row_entries]: chunk c owns entries [c*chunk, (c+1)*chunk)
   int64_t row_entries;
+  // cumulative-weight selection only
+  uint32_t* pcount;    // [rows][4096] slots per 12-bit bin
+  uint64_t* pmass;     // [rows][4096] integer weight per bin
+  uint64_t* pstate;    // [rows][4]: target still to reach, Theta, Z, (unused)
+  uint32_t* prow;      // [rows][4]: key of the row maximum, slots still allowed, selected count, (unused)
 };
 
 // chunk geometry for a row of n slots: at most 1024 chunks, each a multiple of 1024 slots, >= 4096
@@ -259,6 +264,10 @@ size_t topk_workspace_bytes(int rows, int64_t cap) {
   b += align_up((int64_t)rows * 1024 * 4, 256);
   b += align_up((int64_t)rows * 1024 * 2 * 4, 256);
   b += align_up((int64_t)rows * list_entries_per_row(cap) * 8, 256);
+  b += align_up((int64_t)rows * kBins12 * 4, 256);
+  b += align_up((int64_t)rows * kBins12 * 8, 256);
+  b += align_up((int64_t)rows * 4 * 8, 256);
+  b += align_up((int64_t)rows * 4 * 4, 256);
   return b;
 }
 
@@ -271,6 +280,11 @@ static void topk_carve(TopkWs* t, void* ws, int rows, int64_t cap) {
   t->coff = (uint32_t*)w;  w += align_up((int64_t)rows * 1024 * 2 * 4, 256);
   t->cand = (uint2*)w;
   t->row_entries = list_entries_per_row(cap);
+  w += align_up((int64_t)rows * t->row_entries * 8, 256);
+  t->pcount = (uint32_t*)w; w += align_up((int64_t)rows * kBins12 * 4, 256);
+  t->pmass = (uint64_t*)w;  w += align_up((int64_t)rows * kBins12 * 8, 256);
+  t->pstate = (uint64_t*)w; w += align_up((int64_t)rows * 4 * 8, 256);
+  t->prow = (uint32_t*)w;
 }
 
 __global__ void tk_zero(uint32_t* p, int64_t n) {
@@ -566,11 +580,13 @@ __global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, i
 //   selected(j) = key_j > T  or  (key_j == T and #{i < j : key_i == T} < r_eq)
 //   position(j) = #{i < j : key_i > T} + min(#{i < j : key_i == T}, r_eq)
 __global__ __launch_bounds__(256) void tk_emit_lists(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr, TopkWs t,
-                                                     int32_t k, int32_t* __restrict__ idx, int32_t* __restrict__ count) {
+                                                     int32_t k, int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                     bool count_from_state) {
   __shared__ uint32_t wsum[2][4];
   const int row = blockIdx.y;
   const int64_t want = sr.want[row / n_kv_heads];
-  if (blockIdx.x == 0 && threadIdx.x == 0) count[row] = want > 0 ? (int32_t)want : 0;
+  if (blockIdx.x == 0 && threadIdx.x == 0)
+    count[row] = want > 0 ? (count_from_state ? (int32_t)t.prow[4 * row + 2] : (int32_t)want) : 0;
   if (want <= 0) return;
   const uint32_t m = t.ncand[(int64_t)row * kMaxChunks + blockIdx.x];
   if (m == 0) return;
@@ -613,6 +629,345 @@ __global__ __launch_bounds__(256) void tk_emit_lists(int64_t chunk, int nchunks,
   }
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Cumulative-weight selection (Sec. 3.2, Eq. 4): the shortest prefix of the descending order whose
+// softmax weight reaches tau.  Weights are integers (fixed-order fp32 arithmetic, see tp_weight), so
+// the histogram sums below are exact and independent of the order in which atomics land.  The
+// radix walk is the top-k one with two running totals: it stops in the first bin / digit / equal-key
+// group where the weight reaches the target or the slot count reaches k_max.
+__device__ __forceinline__ float key_to_float(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+// Integer weight of a logit u <= 0 relative to the row maximum: about exp(u) * 2^31.
+//   t = u * log2(e); below -64 -> 0; fl = floor(t); f = t - fl in [0, 1) (exact);
+//   p = 2^f by a degree-6 polynomial in Horner form with fused multiply-adds, c_k = (ln 2)^k / k!;
+//   mant = (uint64)(p * 2^31) (truncated); w = mant >> -fl.
+__device__ __forceinline__ uint64_t tp_weight(float u) {
+  const float t = u * 1.44269504f;
+  if (!(t >= -64.0f)) return 0;
+  const float fl = floorf(t);
+  const float f = t - fl;
+  float p = 1.5403530e-4f;
+  p = fmaf(p, f, 1.3333558e-3f);
+  p = fmaf(p, f, 9.6181291e-3f);
+  p = fmaf(p, f, 5.5504109e-2f);
+  p = fmaf(p, f, 2.4022651e-1f);
+  p = fmaf(p, f, 6.9314718e-1f);
+  p = fmaf(p, f, 1.0f);
+  const uint64_t mant = (uint64_t)(p * 2147483648.0f);
+  const int sh = (int)(-fl);
+  return sh >= 64 ? 0 : mant >> sh;
+}
+
+__global__ void tp_init(TopkWs t, int rows) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < (int64_t)rows * kBins12) { t.pcount[i] = 0; t.pmass[i] = 0; }
+  if (i < rows * 4) { t.prow[i] = 0; t.pstate[i] = 0; }
+}
+
+// Row maximum of the scores, as an order key.
+__global__ __launch_bounds__(256) void tp_rowmax(const float* __restrict__ vals, int64_t stride, int64_t chunk,
+                                                 int n_kv_heads, SelRows sr, TopkWs t) {
+  __shared__ uint32_t wmax[4];
+  const int row = blockIdx.y;
+  if (sr.want[row / n_kv_heads] <= 0) return;
+  const int64_t nsel = sr.nsel[row / n_kv_heads];
+  const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  if (c0 >= nsel) return;
+  int64_t c1 = c0 + chunk;
+  if (c1 > nsel) c1 = nsel;
+  const float* v = vals + (int64_t)row * stride;
+  uint32_t best = 0;
+  for (int64_t s0 = c0; s0 < c1; s0 += 4096) {
+    uint32_t key[16];
+    bool valid[16];
+    load_tile_keys(v, s0, c1, key, valid);
+#pragma unroll
+    for (int x = 0; x < 16; ++x)
+      if (valid[x] && key[x] > best) best = key[x];
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const uint32_t other = __shfl_xor(best, o);
+    if (other > best) best = other;
+  }
+  if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = best;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int x = 1; x < 4; ++x) if (wmax[x] > best) best = wmax[x];
+    atomicMax(&t.prow[4 * row], best);
+  }
+}
+
+// 12-bit histogram of slot counts and integer weights.
+__global__ __launch_bounds__(256) void tp_hist(const float* __restrict__ vals, int64_t stride, int64_t chunk,
+                                               int n_kv_heads, SelRows sr, float sm_scale, TopkWs t) {
+  __shared__ uint32_t lc[kBins12];
+  __shared__ unsigned long long lm[kBins12];
+  const int row = blockIdx.y;
+  if (sr.want[row / n_kv_heads] <= 0) return;
+  const int64_t nsel = sr.nsel[row / n_kv_heads];
+  const int64_t c0 = (int64_t)blockIdx.x * chunk;
+  if (c0 >= nsel) return;
+  int64_t c1 = c0 + chunk;
+  if (c1 > nsel) c1 = nsel;
+  for (int i = threadIdx.x; i < kBins12; i += 256) { lc[i] = 0; lm[i] = 0; }
+  __syncthreads();
+  const float m = key_to_float(t.prow[4 * row]) * sm_scale;
+  const float* v = vals + (int64_t)row * stride;
+  for (int64_t s0 = c0; s0 < c1; s0 += 4096) {
+    uint32_t key[16];
+    bool valid[16];
+    load_tile_keys(v, s0, c1, key, valid);
+#pragma unroll
+    for (int x = 0; x < 16; ++x)
+      if (valid[x]) {
+        const uint64_t w = tp_weight(key_to_float(key[x]) * sm_scale - m);
+        atomicAdd(&lc[key[x] >> 20], 1u);
+        if (w) atomicAdd(&lm[key[x] >> 20], (unsigned long long)w);
+      }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < kBins12; i += 256) {
+    const uint32_t c = lc[i];
+    if (c) {
+      atomicAdd(&t.pcount[(int64_t)row * kBins12 + i], c);
+      const unsigned long long mm = lm[i];
+      if (mm) atomicAdd(reinterpret_cast<unsigned long long*>(&t.pmass[(int64_t)row * kBins12 + i]), mm);
+    }
+  }
+}
+
+// exclusive prefix sum of one 64-bit value per thread over a 256-thread workgroup; *total gets the sum
+__device__ __forceinline__ uint64_t block_scan_excl_256_u64(uint64_t v, uint64_t* wsum /*[4]*/, uint64_t* total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint64_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint64_t a = __shfl_up((unsigned long long)inc, o);
+    if (lane >= o) inc += a;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  uint64_t base = 0;
+  for (int x = 0; x < w; ++x) base += wsum[x];
+  *total = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+  __syncthreads();
+  return base + inc - v;
+}
+
+// One workgroup per row: Z, Theta, and the first bin (from the top) in which the running weight reaches
+// Theta or the running count reaches k_max.
+__global__ __launch_bounds__(256) void tp_findbin(int n_kv_heads, SelRows sr, uint64_t tau_fix, bool tau_one,
+                                                  uint32_t k_max, TopkWs t, uint64_t* __restrict__ mass_out) {
+  __shared__ uint64_t wsum64[4];
+  __shared__ uint32_t wsum[4];
+  const int row = blockIdx.x;
+  if (sr.want[row / n_kv_heads] <= 0) {
+    if (mass_out != nullptr && threadIdx.x < 2) mass_out[2 * row + threadIdx.x] = 0;
+    return;
+  }
+  uint32_t hc[16], csum = 0;
+  uint64_t hm[16], msum = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int b = kBins12 - 1 - (16 * threadIdx.x + i);
+    hc[i] = t.pcount[(int64_t)row * kBins12 + b];
+    hm[i] = t.pmass[(int64_t)row * kBins12 + b];
+    csum += hc[i];
+    msum += hm[i];
+  }
+  uint64_t Z;
+  uint64_t run_m = block_scan_excl_256_u64(msum, wsum64, &Z);
+  uint32_t run_c = block_scan_excl_256(csum, wsum);
+  uint64_t theta = tau_one ? Z : __umul64hi(Z, tau_fix);
+  if (theta < 1) theta = 1;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const bool before = run_m < theta && run_c < k_max;
+    const bool after = run_m + hm[i] >= theta || run_c + hc[i] >= k_max;
+    if (before && after && hc[i] > 0) {
+      t.state[4 * row + 2] = kBins12 - 1 - (16 * threadIdx.x + i);   // b*
+      t.pstate[4 * row] = theta - run_m;                              // weight still to reach inside the bin
+      t.prow[4 * row + 1] = k_max - run_c;                            // slots still allowed
+      t.prow[4 * row + 3] = run_c;                                    // slots above the bin
+    }
+    run_m += hm[i];
+    run_c += hc[i];
+  }
+  if (threadIdx.x == 0) {
+    t.pstate[4 * row + 1] = theta;
+    t.pstate[4 * row + 2] = Z;
+    if (mass_out != nullptr) { mass_out[2 * row] = theta; mass_out[2 * row + 1] = Z; }
+  }
+}
+
+// exclusive prefix sums over a 1024-thread workgroup (one value per thread)
+__device__ __forceinline__ uint64_t block_scan_excl_1024_u64(uint64_t v, uint64_t* wsum /*[16]*/) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint64_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint64_t a = __shfl_up((unsigned long long)inc, o);
+    if (lane >= o) inc += a;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  uint64_t base = 0;
+  for (int x = 0; x < w; ++x) base += wsum[x];
+  __syncthreads();
+  return base + inc - v;
+}
+
+// One workgroup per row: finishes the walk inside bin b* (two 10-bit digits, then the group of equal
+// keys, whose members all weigh the same) and builds the chunk offsets for the ordered emit.
+__global__ __launch_bounds__(1024) void tp_resolve(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr, float sm_scale,
+                                                   TopkWs t) {
+  __shared__ uint32_t h[1024], e[1024], cnt[1024], wsum[16];
+  __shared__ unsigned long long hm[1024];
+  __shared__ uint64_t wsum64[16];
+  __shared__ uint32_t s_prefix, s_krem, s_n;
+  __shared__ uint64_t s_mrem;
+  __shared__ uint2 lc[kResolveLds];
+  const int row = blockIdx.x;
+  if (sr.want[row / n_kv_heads] <= 0) return;
+  const uint32_t bin = t.state[4 * row + 2];
+  const uint2* cand = t.cand + (int64_t)row * t.row_entries;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const float m = key_to_float(t.prow[4 * row]) * sm_scale;
+  uint32_t prefix = bin << 20, krem = t.prow[4 * row + 1];
+  uint64_t mrem = t.pstate[4 * row];
+  cnt[tid] = tid < nchunks ? t.ncand[(int64_t)row * kMaxChunks + tid] : 0;
+  if (tid == 0) s_n = 0;
+  __syncthreads();
+  auto sweep = [&](auto&& f) {
+    for (int c0 = 0; c0 < nchunks; c0 += 256) {
+#pragma unroll 1
+      for (int u = 0; u < 16; ++u) {
+        const int c = c0 + wv * 16 + u;
+        const uint32_t mu = c < nchunks ? cnt[c] : 0;
+        for (uint32_t i0 = lane; i0 < mu + lane; i0 += 512) {
+          uint2 x[8];
+#pragma unroll
+          for (int v = 0; v < 8; ++v)
+            if (i0 + 64 * v < mu) x[v] = cand[(int64_t)c * chunk + i0 + 64 * v];
+#pragma unroll
+          for (int v = 0; v < 8; ++v)
+            if (i0 + 64 * v < mu && (x[v].x >> 20) == bin) f(x[v].x, x[v].y);
+        }
+      }
+    }
+  };
+  sweep([&](uint32_t key, uint32_t slot) {
+    const uint32_t at = atomicAdd(&s_n, 1u);
+    if (at < (uint32_t)kResolveLds) lc[at] = uint2{key, slot};
+  });
+  __syncthreads();
+  const uint32_t nst = s_n;
+  const bool staged = nst <= (uint32_t)kResolveLds;
+  auto visit = [&](auto&& f) {
+    if (staged) {
+      for (uint32_t i = tid; i < nst; i += 1024) f(lc[i].x, lc[i].y);
+    } else {
+      sweep(f);
+    }
+  };
+  uint32_t cnt_eq = 0;
+  for (int pass = 0; pass < 2; ++pass) {
+    const int shift = pass == 0 ? 10 : 0;
+    h[tid] = 0;
+    hm[tid] = 0;
+    __syncthreads();
+    visit([&](uint32_t key, uint32_t) {
+      if ((key >> (shift + 10)) == (prefix >> (shift + 10))) {
+        atomicAdd(&h[(key >> shift) & 1023u], 1u);
+        const uint64_t w = tp_weight(key_to_float(key) * sm_scale - m);
+        if (w) atomicAdd(&hm[(key >> shift) & 1023u], (unsigned long long)w);
+      }
+    });
+    __syncthreads();
+    const uint32_t mine_c = h[1023 - tid];                  // thread tid owns digit 1023 - tid
+    const uint64_t mine_m = hm[1023 - tid];
+    const uint32_t run_c = block_scan_excl_1024(mine_c, wsum);
+    const uint64_t run_m = block_scan_excl_1024_u64(mine_m, wsum64);
+    const bool before = run_m < mrem && run_c < krem;
+    const bool after = run_m + mine_m >= mrem || run_c + mine_c >= krem;
+    if (before && after && mine_c > 0) {
+      s_prefix = prefix | ((uint32_t)(1023 - tid) << shift);
+      s_mrem = mrem - run_m;
+      s_krem = krem - run_c;
+    }
+    __syncthreads();
+    prefix = s_prefix;
+    mrem = s_mrem;
+    krem = s_krem;
+    cnt_eq = h[(prefix >> shift) & 1023u];
+    __syncthreads();
+  }
+  const uint32_t T = prefix;
+  // the cnt_eq slots with key == T all weigh w_T: take the least r with r * w_T >= mrem, within the
+  // count limit
+  const uint64_t wT = tp_weight(key_to_float(T) * sm_scale - m);
+  uint64_t need = wT > 0 ? (mrem + wT - 1) / wT : (uint64_t)cnt_eq;
+  if (need > krem) need = krem;
+  if (need > cnt_eq) need = cnt_eq;
+  const uint32_t req = (uint32_t)need;
+  h[tid] = 0;
+  e[tid] = 0;
+  __syncthreads();
+  visit([&](uint32_t key, uint32_t slot) {
+    if (key > T) atomicAdd(&h[slot / chunk], 1u);
+    else if (key == T) atomicAdd(&e[slot / chunk], 1u);
+  });
+  __syncthreads();
+  const uint32_t g = (tid < nchunks) ? t.above[(int64_t)row * 1024 + tid] + h[tid] : 0;
+  const uint32_t q = (tid < nchunks) ? e[tid] : 0;
+  const uint32_t og = block_scan_excl_1024(g, wsum);
+  const uint32_t oe = block_scan_excl_1024(q, wsum);
+  if (tid < nchunks) {
+    t.coff[((int64_t)row * nchunks + tid) * 2] = og;
+    t.coff[((int64_t)row * nchunks + tid) * 2 + 1] = oe;
+  }
+  if (tid == nchunks - 1) t.prow[4 * row + 2] = og + g + req;      // selected slots: all above T plus req of the equal ones
+  if (tid == 0) { t.state[4 * row] = T; t.state[4 * row + 1] = req; }
+}
+
+int32_t launch_topp(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, float sm_scale, double tau,
+                    int32_t k_max, int32_t* idx, int32_t* count, uint64_t* mass_opt, void* ws, hipStream_t st) {
+  SelRows sr;
+  for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
+  for (int b = 0; b < L.batch; ++b) {
+    sr.nsel[b] = nr.n[b];
+    sr.want[b] = nr.n[b] > 0 ? k_max : -1;
+  }
+  TopkWs t;
+  topk_carve(&t, ws, L.rows, L.cap);
+  int64_t chunk;
+  int32_t nchunks;
+  chunk_geometry(nmax, &chunk, &nchunks);
+  dim3 g((unsigned)nchunks, (unsigned)L.rows);
+  const bool tau_one = tau >= 1.0;
+  const uint64_t tau_fix = tau_one ? 0 : (uint64_t)ldexp(tau, 64);
+  if (nmax > 0) {
+    const int64_t nz = (int64_t)L.rows * kBins12;
+    tp_init<<<(unsigned)((nz + 255) / 256), 256, 0, st>>>(t, L.rows);
+    dim3 gh((unsigned)((nchunks + 3) / 4), (unsigned)L.rows);
+    tp_rowmax<<<gh, 256, 0, st>>>(sel, L.cap, 4 * chunk, L.n_kv_heads, sr, t);
+    tp_hist<<<gh, 256, 0, st>>>(sel, L.cap, 4 * chunk, L.n_kv_heads, sr, sm_scale, t);
+    tp_findbin<<<L.rows, 256, 0, st>>>(L.n_kv_heads, sr, tau_fix, tau_one, (uint32_t)k_max, t, mass_opt);
+    tk_collect<<<g, 256, 0, st>>>(sel, L.cap, chunk, L.n_kv_heads, sr, t);
+    tp_resolve<<<L.rows, 1024, 0, st>>>(chunk, nchunks, L.n_kv_heads, sr, sm_scale, t);
+  } else if (mass_opt != nullptr) {
+    // no resident slot anywhere: only the per-row (Theta, Z) report has to be cleared
+    tp_findbin<<<L.rows, 256, 0, st>>>(L.n_kv_heads, sr, tau_fix, tau_one, (uint32_t)k_max, t, mass_opt);
+  }
+  tk_emit_lists<<<g, 256, 0, st>>>(chunk, nchunks, L.n_kv_heads, sr, t, k_max, idx, count, true);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
 size_t topk_hist_bytes(int rows) { return (size_t)rows * kBins12 * 4; }
 
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
@@ -643,7 +998,7 @@ int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t n
     tk_collect<<<g, 256, 0, st>>>(sel, L.cap, chunk, L.n_kv_heads, sr, t);
     tk_resolve<<<L.rows, 1024, 0, st>>>(chunk, nchunks, L.n_kv_heads, sr, t);
   }
-  tk_emit_lists<<<g, 256, 0, st>>>(chunk, nchunks, L.n_kv_heads, sr, t, k, idx, count);
+  tk_emit_lists<<<g, 256, 0, st>>>(chunk, nchunks, L.n_kv_heads, sr, t, k, idx, count, false);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
