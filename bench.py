@@ -459,6 +459,48 @@ def vq_probe(w, iters, g=32, c=256):
     return out
 
 
+def selection_probe(w, iters=10):
+    """Times the two selection calls on the scores of one real scan of the workload's first layer:
+    hca_topk (k fixed) and hca_topp (Eq. 4, tau = 0.9 and 0.99, cut at the same k)."""
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    cap = w.n + 16
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap, w.bits, w.group)
+    d = S.make_layer(w, 0, device="cuda", want_values=False)
+    kc = torch.empty(B.hca_kcache_bytes(shape), dtype=torch.uint8, device="cuda")
+    B.hca_quantize_keys(shape, kc, d["keys"], w.n, [0] * w.batch)
+    n = [w.n] * w.batch
+    sel = torch.empty(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
+    B.hca_score_qkeys(shape, kc, d["q"], n, sel)
+    idx = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device="cuda")
+    count = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+    sm = 1.0 / (128.0 ** 0.5)
+    out = {"workload": w.name, "k": w.k}
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(f):
+        for _ in range(2):
+            f()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    out["topk_ms"] = timed(lambda: B.hca_topk(shape, sel, n, w.k, idx, count, ws))
+    for tau in (0.9, 0.99):
+        ms = timed(lambda: B.hca_topp(shape, sel, n, sm, tau, w.k, idx, count, None, ws))
+        out[f"topp_tau{tau}"] = {"ms": ms, "selected_per_kv_head": count.cpu().reshape(-1).tolist()}
+    del kc, sel, d
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    return out
+
+
 def scan_only(w, iters):
     """Key-scan kernel alone on one layer (two cache copies alternate), preceded by a plain 1 GiB
     device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the counters (profiles/)."""
@@ -618,10 +660,12 @@ def main():
                     latency[name]["ms_per_layer"] = g["ms_per_layer"]
                     latency[name]["parts"] = parts
 
-    codebook = None
+    codebook = selection = None
     if not args.no_latency:
         codebook = vq_probe(S.CONFIGS[4], 10)
         log(f"codebook key path at 1M: table + lookup scan {codebook['score_ms']:.3f} ms per layer")
+        selection = selection_probe(S.CONFIGS[4])
+        log(f"selection at 1M: top-k {selection['topk_ms']:.3f} ms, Eq. 4 at tau 0.9 {selection['topp_tau0.9']['ms']:.3f} ms")
 
     total_steps = args.steps + args.warmup
     model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers))
@@ -710,6 +754,7 @@ def main():
         "pipelined_ms_per_layer": ms_per_step / L,
         "per_layer_decode_latency": latency,
         "codebook_key_path": codebook,
+        "selection": selection,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,

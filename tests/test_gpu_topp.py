@@ -91,3 +91,38 @@ def test_topp_at_one_million(B, oracle):
     for tau, k_max in ((0.9, 16384), (0.999, 16384), (0.5, 4096)):
         got = _run(B, v, [n], 8, 0.0884, tau, k_max)
         _check(oracle, v, [n], 8, 0.0884, tau, k_max, got)
+
+
+def test_decode_step_with_cumulative_weight_selection(B, oracle):
+    """scan -> hca_topp -> gather -> attend: the variable-length selection feeds the same attend calls."""
+    import synth_inputs as S
+    from paper_2507_19823_amd.session import LayerState
+    w = S.Workload("tp", 31, 2, 8, 2, 6000, 4, 32, 2048, planted=8)
+    d = S.make_layer(w)
+    R, n, k_max = w.batch * w.n_kv_heads, w.n, 2048
+    st = LayerState(w.batch, w.n_q_heads, w.n_kv_heads, n + 8, w.bits, w.group, k_max=k_max, m_max=1)
+    st.quantize(d["keys"].cuda())
+    qd = d["q"].cuda()
+    st.score(qd)
+    sm = st.sm_scale
+    B.hca_topp(st.shape, st.sel, st.n, sm, 0.97, k_max, st.idx, st.count, None, st.ws)
+    vh = d["values"].contiguous().pin_memory()
+    B.hca_gather_values(st.shape, st.idx, st.count, k_max, st.pos, vh, n, n, None, 0, st.ws)
+    B.hca_attend_gathered(st.shape, st.kcache, qd, st.idx, st.count, k_max, sm, st.y, st.acc, st.ws)
+    torch.cuda.synchronize()
+    oc = oracle.Cache(R, n + 8, 128, w.bits, w.group)
+    oracle.quantize(oc, d["keys"].numpy().reshape(R, n, 128))
+    q16 = d["q"].numpy().reshape(-1, 128)
+    sel, _ = oracle.score(oc, q16, want_z=False)
+    idx, count, kstar, _ = oracle.topp(sel, oc.n, sm, 0.97, k_max)
+    cg = st.count.cpu().numpy().reshape(R)
+    assert np.array_equal(cg, count) and 1 <= count.min() and len(set(count.tolist())) > 1   # really variable
+    ig = st.idx.cpu().numpy().reshape(R, k_max)
+    for r in range(R):
+        assert np.array_equal(ig[r, :count[r]], idx[r, :count[r]])
+    pos = np.tile(np.arange(n + 8, dtype=np.int32), (R, 1))
+    acc = np.zeros((R, n + 8), np.float32)
+    y, _ = oracle.attend(oc, q16, idx, count, pos, d["values"].numpy().reshape(R, n, 128), sm, acc=acc)
+    yg = st.y.cpu().numpy().reshape(-1, 128)
+    assert float(np.max(np.abs(yg - y).max(-1) / np.maximum(np.abs(y).max(-1), 1e-30))) <= 2e-3
+    assert np.allclose(st.acc.cpu().numpy().reshape(R, -1), acc, rtol=1e-4, atol=1e-7)
