@@ -152,9 +152,20 @@ def topk(sel, n, k):
     return idx, count
 
 
-def attend(cache, q, idx, count, pos, V, sm_scale, acc=None, want_w=False):
+def lse(z, R, n, sm_scale):
+    """z [R*G, cap] fp32 -> log-sum-exp of z * sm_scale over the resident tokens, fp32 [R*G]."""
+    z = np.ascontiguousarray(z, np.float32)
+    G = z.shape[0] // R
+    out = np.zeros(R * G, np.float32)
+    _check(lib().hco_lse(_p(z), C.c_int64(R), C.c_int(G), C.c_int64(z.shape[1]), _p(_i64(n)), C.c_float(sm_scale),
+                         _p(out)), "lse")
+    return out
+
+
+def attend(cache, q, idx, count, pos, V, sm_scale, acc=None, want_w=False, lse=None):
     """V [R, vrows, D] fp16; pos int32 [R,cap].  Returns (y [R*G,D] fp32, w or None).
-    acc (fp32 [R,cap]) is updated in place when given."""
+    acc (fp32 [R,cap]) is updated in place when given.  lse (fp32 [R*G]): the paper's weights (Eq. 5),
+    normalised over all resident tokens instead of over the selected set."""
     q, V = _u16(q), _u16(V)
     G = q.shape[0] // cache.R
     idx = np.ascontiguousarray(idx, np.int32)
@@ -169,7 +180,8 @@ def attend(cache, q, idx, count, pos, V, sm_scale, acc=None, want_w=False):
                             C.c_int64(cache.R), C.c_int(G), C.c_int(cache.D), C.c_int(cache.bits),
                             C.c_int(cache.gs), C.c_int64(cache.cap), _p(idx), _p(count),
                             C.c_int64(k), _p(pos), _p(V), C.c_int64(V.shape[1]),
-                            C.c_float(sm_scale), _p(y), _p(w), _p(acc)), "attend")
+                            C.c_float(sm_scale), _p(y), _p(w), _p(acc),
+                            _p(None if lse is None else np.ascontiguousarray(lse, np.float32))), "attend")
     return y, w
 
 

@@ -17,8 +17,11 @@
  *   hco_topk              the sorted prefix Pi_k of Sec. 3.2 ("sort in
  *                         descending order"), with k given instead of derived
  *                         from tau (Eq. 4)
+ *   hco_lse               log of the softmax denominator over all resident tokens
+ *                         (Sec. 3.2), per query head
  *   hco_attend            softmax over the selected set and the weighted value
- *                         sum of Eq. 5; also the accumulated-score update
+ *                         sum of Eq. 5 (optionally with the paper's own weights,
+ *                         normalised over all tokens); accumulated-score update
  *   hco_evict             keep-M by accumulated score with stable compaction
  *
  * Precision.  Everything that feeds an integer decision (codes, the selection
@@ -276,6 +279,26 @@ int hco_score(const uint16_t* q, const uint8_t* codes, const uint16_t* scale,
   return err ? HCO_ERR_NAN : HCO_OK;
 }
 
+/* Softmax denominator over ALL resident tokens, per query head (Sec. 3.2: a~ = softmax(z~ / sqrt(d)) is
+ * taken over the whole sequence before anything is selected):
+ *   lse[hq] = log sum_{j < n} exp(z[hq][j] * sm_scale)      (fp32 product, fp64 exp / sum / log, cast to fp32)
+ * z: [R*G][cap] as written by hco_score; rows without resident tokens give -inf. */
+int hco_lse(const float* z, int64_t R, int G, int64_t cap, const int64_t* n, float sm_scale, float* lse) {
+  if (G < 1 || G > 16) return HCO_ERR_BAD_ARG;
+  for (int64_t hq = 0; hq < R * G; ++hq) {
+    int64_t nr = n[hq / G];
+    float m = -INFINITY;
+    for (int64_t j = 0; j < nr; ++j) {
+      float l = z[hq * cap + j] * sm_scale;
+      if (l > m) m = l;
+    }
+    double acc = 0.0;
+    for (int64_t j = 0; j < nr; ++j) acc += exp((double)(z[hq * cap + j] * sm_scale) - (double)m);
+    lse[hq] = nr > 0 ? (float)((double)m + log(acc)) : -INFINITY;
+  }
+  return HCO_OK;
+}
+
 /* -------------------------------------------------------------- top-k --- */
 
 typedef struct { float v; int32_t i; } hco_pair;
@@ -328,12 +351,14 @@ int hco_topk(const float* sel, int64_t R, int64_t cap, const int64_t* n, int64_t
  *   y   = sum_i a_i * V[r][pos[idx_i]]           (fp64, cast to fp32)
  * V: [R][vrows][D] fp16.  pos: [R][cap] int32 maps a resident slot to its value row.
  * w_opt: [R*G][k] fp32 softmax weights, or NULL.
- * acc_opt: [R][cap] fp32, acc[idx_i] += sum_g max((float)a_i, 1e-30f), or NULL. */
+ * acc_opt: [R][cap] fp32, acc[idx_i] += sum_g max((float)a_i, 1e-30f), or NULL.
+ * lse_opt: [R*G] fp32 or NULL.  Given, the weights are the paper's own (Eq. 5): a_i = exp(l_i - lse),
+ * the softmax over ALL resident tokens restricted to the selected ones, not renormalised. */
 int hco_attend(const uint16_t* q, const uint8_t* codes, const uint16_t* scale,
                const uint16_t* zero, int64_t R, int G, int D, int bits, int gs, int64_t cap,
                const int32_t* idx, const int32_t* count, int64_t k, const int32_t* pos,
                const uint16_t* V, int64_t vrows, float sm_scale,
-               float* y, float* w_opt, float* acc_opt) {
+               float* y, float* w_opt, float* acc_opt, const float* lse_opt) {
   if (!shape_ok(D, bits, gs) || G <= 0 || G > 16) return HCO_ERR_BAD_ARG;
   const int NG = D / gs, CB = D * bits / 8;
   int err = 0;
@@ -358,6 +383,7 @@ int hco_attend(const uint16_t* q, const uint8_t* codes, const uint16_t* scale,
       }
       double Z = 0.0;
       for (int i = 0; i < kk; ++i) { a[i] = exp((double)l[i] - (double)m); Z += a[i]; }
+      if (lse_opt) Z = exp((double)lse_opt[hq] - (double)m);     /* denominator over all resident tokens */
       double yy[512];
       for (int c = 0; c < D; ++c) yy[c] = 0.0;
       for (int i = 0; i < kk; ++i) {

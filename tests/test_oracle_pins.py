@@ -480,3 +480,43 @@ def test_evict_pos_composition(oracle):
         oracle.evict(c, acc, pos, 20, 4)
         alive = [alive[j] for j in ref]
         assert list(pos[0, :int(c.n[0])]) == alive
+
+
+# ------------------------------------------- the paper's un-renormalised weights (Eq. 5) ---
+
+def test_lse_and_global_weights_against_numpy(oracle):
+    """lse over all resident tokens against numpy's logsumexp; with it, attend uses softmax_all(l)[selected]
+    (Sec. 3.2, Eq. 5: the selected weights are not renormalised), checked against numpy in fp64; with every
+    token selected both forms coincide."""
+    rng = np.random.default_rng(808)
+    R, G, n, k, D = 2, 4, 300, 25, 128
+    c = oracle.Cache(R, n + 6, D, 4, 32)
+    oracle.quantize(c, _keys(rng, R, n))
+    q = (2 * rng.standard_normal((R * G, D))).astype(np.float16)
+    V = rng.standard_normal((R, n + 6, D)).astype(np.float16)
+    sel, z = oracle.score(c, q)
+    sm = 0.11
+    L = oracle.lse(z, R, c.n, sm)
+    l64 = z[:, :n].astype(np.float32) * np.float32(sm)
+    ref = np.log(np.exp(l64.astype(np.float64) - l64.max(1, keepdims=True)).sum(1)) + l64.max(1)
+    assert np.allclose(L, ref, rtol=1e-6, atol=1e-6)
+    idx, count = oracle.topk(sel, c.n, k)
+    pos = np.tile(np.arange(n + 6, dtype=np.int32), (R, 1))
+    acc = np.zeros((R, n + 6), np.float32)
+    y, w = oracle.attend(c, q, idx, count, pos, V, sm, acc=acc, want_w=True, lse=L)
+    acc_ref = np.zeros((R, n + 6))
+    for hq in range(R * G):
+        r = hq // G
+        a_all = np.exp(l64[hq].astype(np.float64) - ref[hq])                     # softmax over all n
+        assert abs(a_all.sum() - 1) < 1e-9
+        a = a_all[idx[r]]
+        assert np.allclose(w[hq], a, rtol=1e-5, atol=1e-12) and w[hq].sum() < 1
+        assert np.allclose(y[hq], a @ V[r, idx[r]].astype(np.float64), rtol=1e-5, atol=1e-7)
+        acc_ref[r, idx[r]] += a
+    assert np.allclose(acc, acc_ref, rtol=1e-5, atol=1e-12)
+    # k = n: the two normalisations agree and both are standard attention over the dequantised keys
+    idx, count = oracle.topk(sel, c.n, n)
+    ya, _ = oracle.attend(c, q, idx, count, pos, V, sm)
+    yb, _ = oracle.attend(c, q, idx, count, pos, V, sm, lse=L)
+    assert np.allclose(ya, yb, rtol=1e-5, atol=1e-7)
+    assert np.all(np.isneginf(oracle.lse(z, R, [0, 0], sm)))
