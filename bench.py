@@ -491,6 +491,9 @@ def selection_probe(w, iters=10):
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
+    lse = torch.zeros(w.batch, w.n_q_heads, dtype=torch.float32, device="cuda")
+    out["scan_ms"] = timed(lambda: B.hca_score_qkeys(shape, kc, d["q"], n, sel))
+    out["scan_with_lse_ms"] = timed(lambda: B.hca_score_qkeys_lse(shape, kc, d["q"], n, sm, sel, lse, ws))
     out["topk_ms"] = timed(lambda: B.hca_topk(shape, sel, n, w.k, idx, count, ws))
     for tau in (0.9, 0.99):
         ms = timed(lambda: B.hca_topp(shape, sel, n, sm, tau, w.k, idx, count, None, ws))

@@ -270,6 +270,21 @@ int32_t hca_export_kcache(const hca_shape* shape, const void* kcache, const int6
 int32_t hca_topp(const hca_shape* shape, const float* sel, const int64_t* n_resident, float sm_scale, double tau,
                  int32_t k_max, int32_t* idx, int32_t* count, uint64_t* mass_opt, void* workspace, void* stream);
 
+/* The paper's own weights (Sec. 3.2, Eq. 5): a~ = softmax(z~ / sqrt(d)) is taken over ALL resident tokens
+ * and the weights of the selected ones are used as they are, not renormalised over the selected set.
+ * hca_score_qkeys_lse is hca_score_qkeys with a second output, the log of that softmax's denominator,
+ *   lse  device, fp32 [batch, n_q_heads]: log sum_{j < n_resident} exp(z~[hq][j] * sm_scale); -inf for a
+ *        sequence without resident tokens
+ *   workspace  device, hca_workspace_bytes(shape, 1, 1)
+ * and hca_attend_gathered_global is hca_attend_gathered with the weights exp(l_i - lse[hq]): y is shorter than
+ * the renormalised one by the factor (weight mass of the selected tokens), acc_opt accumulates the same weights. */
+int32_t hca_score_qkeys_lse(const hca_shape* shape, const void* kcache, const void* q_f16,
+                            const int64_t* n_resident, float sm_scale, float* sel, float* lse, void* workspace,
+                            void* stream);
+int32_t hca_attend_gathered_global(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
+                                   const int32_t* count, int32_t k, float sm_scale, const float* lse, float* y,
+                                   float* acc_opt, void* workspace, void* stream);
+
 /* ---- Codebook form of the key path ---------------------------------------------------------
  * The paper's own compressor: grouped vector quantisation (Sec. 3.1) and table-lookup scores
  * (Sec. 3.2, Eq. 3).  The head dimension is cut into g groups of dbar = head_dim / g channels, a

@@ -76,6 +76,10 @@ def lib():
         L.hca_score_qkeys.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.hca_topk.restype = i32
         L.hca_topk.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp]
+        L.hca_score_qkeys_lse.restype = i32
+        L.hca_score_qkeys_lse.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, vp]
+        L.hca_attend_gathered_global.restype = i32
+        L.hca_attend_gathered_global.argtypes = [sp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp, vp]
         L.hca_topp.restype = i32
         L.hca_topp.argtypes = [sp, vp, vp, f32, C.c_double, i32, vp, vp, vp, vp, vp]
         L.hca_sparse_attend.restype = i32
@@ -315,3 +319,15 @@ def hca_vq_evict(shape, cb, pcache, acc, pos, n_resident, M, n_protect, kept, wo
 def hca_topp(shape, sel, n_resident, sm_scale, tau, k_max, idx, count, mass=None, workspace=None, stream=None):
     _check(lib().hca_topp(C.byref(shape), _ptr(sel), _nres(n_resident, shape.batch), float(sm_scale), float(tau),
                           int(k_max), _ptr(idx), _ptr(count), _ptr(mass), _ptr(workspace), _stream(stream)), "hca_topp")
+
+
+def hca_score_qkeys_lse(shape, kcache, q_f16, n_resident, sm_scale, sel, lse, workspace, stream=None):
+    _check(lib().hca_score_qkeys_lse(C.byref(shape), _ptr(kcache), _ptr(q_f16), _nres(n_resident, shape.batch),
+                                     float(sm_scale), _ptr(sel), _ptr(lse), _ptr(workspace), _stream(stream)),
+           "hca_score_qkeys_lse")
+
+
+def hca_attend_gathered_global(shape, kcache, q_f16, idx, count, k, sm_scale, lse, y, acc, workspace, stream=None):
+    _check(lib().hca_attend_gathered_global(C.byref(shape), _ptr(kcache), _ptr(q_f16), _ptr(idx), _ptr(count), int(k),
+                                            float(sm_scale), _ptr(lse), _ptr(y), _ptr(acc), _ptr(workspace),
+                                            _stream(stream)), "hca_attend_gathered_global")

@@ -92,7 +92,9 @@ size_t hca_workspace_bytes(const hca_shape* shape, int64_t k_max, int64_t m_max)
   size_t a = topk_workspace_bytes(L.rows, L.cap);
   size_t b = attend_workspace_bytes(L, k_max);
   size_t c = evict_workspace_bytes(L, m_max);
+  size_t d = score_workspace_bytes(L);
   size_t m = a > b ? a : b;
+  if (d > m) m = d;
   return (m > c ? m : c) + 256;
 }
 
@@ -147,6 +149,36 @@ int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resi
   rc = load_nres(L, n_resident, &nr, &nmax);
   if (rc != HCA_OK) return rc;
   return launch_topk(L, sel, nr, nmax, k, idx, count, workspace, (hipStream_t)stream);
+}
+
+int32_t hca_score_qkeys_lse(const hca_shape* shape, const void* kcache, const void* q_f16,
+                            const int64_t* n_resident, float sm_scale, float* sel, float* lse, void* workspace,
+                            void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (kcache == nullptr || q_f16 == nullptr || sel == nullptr || lse == nullptr || workspace == nullptr)
+    return HCA_ERR_BAD_ARG;
+  if (!(sm_scale > 0.0f)) return HCA_ERR_BAD_ARG;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  return launch_score_lse(L, kcache, q_f16, nr, nmax, sm_scale, sel, lse, workspace, (hipStream_t)stream);
+}
+
+int32_t hca_attend_gathered_global(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
+                                   const int32_t* count, int32_t k, float sm_scale, const float* lse, float* y,
+                                   float* acc_opt, void* workspace, void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (kcache == nullptr || q_f16 == nullptr || idx == nullptr || count == nullptr || lse == nullptr || y == nullptr ||
+      workspace == nullptr)
+    return HCA_ERR_BAD_ARG;
+  if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
+  return launch_attend_gathered(L, kcache, q_f16, idx, count, k, sm_scale, y, acc_opt, workspace, (hipStream_t)stream,
+                                lse);
 }
 
 int32_t hca_topp(const hca_shape* shape, const float* sel, const int64_t* n_resident, float sm_scale, double tau,

@@ -301,9 +301,12 @@ __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t c
 
 // Workgroup 0 of a row merges the chunk partials into y; workgroups 1.. add the final softmax
 // weights of their 256 selected tokens to the accumulated scores.
+// With `lse` (log of the softmax denominator over ALL resident tokens, per query head) the weights are the
+// paper's own, exp(l_i - lse), not renormalised over the selected set (Sec. 3.2, Eq. 5).
 __global__ __launch_bounds__(256) void attend_merge(Layout L, const int32_t* __restrict__ idx,
                                                     const int32_t* __restrict__ count, int32_t k, AttendWs a,
-                                                    int nsplit, float* __restrict__ y, float* __restrict__ acc) {
+                                                    int nsplit, float* __restrict__ y, float* __restrict__ acc,
+                                                    const float* __restrict__ lse) {
   __shared__ float fm[4], fz[4];
   __shared__ float wgt[4][64];  // nsplit <= 64
   __shared__ float pm[64][4], pz[64][4];
@@ -328,6 +331,8 @@ __global__ __launch_bounds__(256) void attend_merge(Layout L, const int32_t* __r
       wgt[h][sp] = e;
       z += e * pz[sp][h];
     }
+    // global normalisation: sum_i exp(l_i - m) v_i / exp(lse - m)
+    if (lse != nullptr && h < L.gqa) z = expf(lse[(int64_t)row * L.gqa + h] - m);
     fm[h] = m; fz[h] = z;
   }
   __syncthreads();
@@ -401,7 +406,7 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
 
 int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
-                               void* ws, hipStream_t st) {
+                               void* ws, hipStream_t st, const float* lse) {
   AttendWs a;
   carve(&a, ws, L, k);
   const int ns = nsplit_of(k);
@@ -412,7 +417,7 @@ int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* 
   else
     attend_partial<2><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
   dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
-  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt);
+  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, lse);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -429,7 +434,7 @@ int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* 
   else if (L.gqa == 2) vq_attend_partial<2><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
   else vq_attend_partial<1><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
   dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
-  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt);
+  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, nullptr);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

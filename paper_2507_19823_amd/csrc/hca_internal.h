@@ -64,6 +64,9 @@ int32_t launch_export(const Layout& L, const void* kcache, const NRes& nr, uint8
 int32_t launch_score(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                      float* sel, float* z_opt, hipStream_t st, uint64_t* stamps = nullptr);
 int64_t score_stamp_pairs(const Layout& L, int64_t nmax);
+size_t score_workspace_bytes(const Layout& L);
+int32_t launch_score_lse(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                         float sm_scale, float* sel, float* lse_out, void* lse_ws, hipStream_t st);
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
                     int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean = false);
 size_t topk_hist_bytes(int rows);
@@ -79,7 +82,7 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
                       int64_t hbm_stride, void* ws, hipStream_t st);
 int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
-                               void* ws, hipStream_t st);
+                               void* ws, hipStream_t st, const float* lse = nullptr);
 int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* pcache, const float* lut,
                                   const int32_t* idx, const int32_t* count, int32_t k, float sm_scale, float* y,
                                   float* acc_opt, void* ws, hipStream_t st);

@@ -126,3 +126,63 @@ def test_decode_step_with_cumulative_weight_selection(B, oracle):
     yg = st.y.cpu().numpy().reshape(-1, 128)
     assert float(np.max(np.abs(yg - y).max(-1) / np.maximum(np.abs(y).max(-1), 1e-30))) <= 2e-3
     assert np.allclose(st.acc.cpu().numpy().reshape(R, -1), acc, rtol=1e-4, atol=1e-7)
+
+
+@pytest.mark.parametrize("bits,gs,G,n,k", [(4, 32, 4, 9000, 512), (2, 64, 4, 5000, 100), (4, 32, 2, 3001, 3001), (4, 32, 1, 70, 5)])
+def test_global_softmax_denominator_and_unrenormalised_weights(B, oracle, bits, gs, G, n, k):
+    """hca_score_qkeys_lse: the same selection scores as hca_score_qkeys plus lse over all resident tokens;
+    hca_attend_gathered_global: the paper's Eq. 5 weights.  Sequences of different length, one empty."""
+    import synth_inputs as S
+    rng = np.random.default_rng(n + k)
+    batch, hkv = 3, 2
+    R, cap = batch * hkv, n + 40
+    lens = [n, 0, n // 3]
+    shape = B.make_shape(batch, hkv * G, hkv, cap, bits, gs)
+    keys = rng.standard_normal((batch, hkv, n, 128)).astype(np.float16)
+    keys[..., 7] *= 8
+    vals = rng.standard_normal((batch, hkv, n, 128)).astype(np.float16)
+    q = (1.5 * rng.standard_normal((batch, hkv * G, 128))).astype(np.float16)
+    kc = torch.zeros(B.hca_kcache_bytes(shape), dtype=torch.uint8, device="cuda")
+    B.hca_quantize_keys(shape, kc, torch.from_numpy(keys).cuda(), n, [0] * batch)
+    sel = torch.full((batch, hkv, cap), -7.0, device="cuda")
+    sel2 = torch.full((batch, hkv, cap), -7.0, device="cuda")
+    lse = torch.full((batch, hkv * G), 123.0, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(shape, k, 1), dtype=torch.uint8, device="cuda")
+    qd = torch.from_numpy(q).cuda()
+    sm = 1.0 / np.sqrt(128.0)
+    B.hca_score_qkeys(shape, kc, qd, lens, sel2)
+    B.hca_score_qkeys_lse(shape, kc, qd, lens, sm, sel, lse, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(sel, sel2)
+    oc = oracle.Cache(R, cap, 128, bits, gs)
+    oracle.quantize(oc, keys.reshape(R, n, 128))
+    oc.n[:] = np.repeat(lens, hkv)
+    osel, oz = oracle.score(oc, q.reshape(R * G, 128))
+    olse = oracle.lse(oz, R, oc.n, sm)
+    lg = lse.cpu().numpy().reshape(R * G)
+    live = np.repeat(np.array(lens) > 0, hkv * G)
+    assert np.all(np.isneginf(lg[~live])) and np.all(np.isneginf(olse[~live]))
+    assert np.allclose(lg[live], olse[live], rtol=2e-6, atol=2e-5)
+
+    idx = torch.zeros(batch, hkv, k, dtype=torch.int32, device="cuda")
+    count = torch.zeros(batch, hkv, dtype=torch.int32, device="cuda")
+    pos = torch.arange(cap, dtype=torch.int32, device="cuda").repeat(batch, hkv, 1).contiguous()
+    acc = torch.zeros(batch, hkv, cap, device="cuda")
+    y = torch.zeros(batch, hkv * G, 128, device="cuda")
+    B.hca_topk(shape, sel, lens, k, idx, count, ws)
+    vh = torch.from_numpy(vals).contiguous().pin_memory()
+    B.hca_gather_values(shape, idx, count, k, pos, vh, n, n, None, 0, ws)
+    B.hca_attend_gathered_global(shape, kc, qd, idx, count, k, sm, lse, y, acc, ws)
+    torch.cuda.synchronize()
+    oidx, ocount = oracle.topk(osel, oc.n, k)
+    opos = np.tile(np.arange(cap, dtype=np.int32), (R, 1))
+    oacc = np.zeros((R, cap), np.float32)
+    oy, ow = oracle.attend(oc, q.reshape(R * G, 128), oidx, ocount, opos, vals.reshape(R, n, 128), sm, acc=oacc,
+                           want_w=True, lse=olse)
+    yg = y.cpu().numpy().reshape(R * G, 128)
+    assert np.all(yg[~live] == 0)
+    err = np.abs(yg[live] - oy[live]).max(-1) / np.maximum(np.abs(oy[live]).max(-1), 1e-30)
+    assert err.max() <= 2e-3
+    if k < n // 3:
+        assert ow[live].sum(1).max() < 0.999999        # the weights really are not renormalised
+    assert np.allclose(acc.cpu().numpy().reshape(R, cap), oacc, rtol=2e-4, atol=1e-7)
