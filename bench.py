@@ -7,7 +7,7 @@ memory and attend (a4), and, every `evict_every` steps, accumulated-score evicti
 Inputs are synthetic and seeded (synth_inputs.py) and resident (keys in HBM, values in pinned host
 memory) before the timed region starts.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line.
 """
 import argparse
 import faulthandler
@@ -266,7 +266,7 @@ class Model:
 
 
 def per_layer_latency(cfg, main, side, link_peak, iters=8):
-    """One layer of BASELINE config `cfg`, decode steps issued back to back on one stream with no
+    """One layer of workload `cfg` (synth_inputs.CONFIGS), decode steps issued back to back on one stream with no
     overlap between layers: time from query ready to y ready (quantise-append, scan, top-k, gather,
     attend).  For config 5 the cache is first evicted to its 50% cap, as the config says."""
     import torch
@@ -322,7 +322,7 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8):
 
 
 def per_layer_latency_grouped(cfg, groups, streams, iters=8):
-    """One layer of BASELINE config `cfg` with its rows (sequences x KV heads) cut into `groups` parts that
+    """One layer of workload `cfg` (synth_inputs.CONFIGS) with its rows (sequences x KV heads) cut into `groups` parts that
     go through the four stages as a pipeline: the gather of one part overlaps the scan of the next.  Unlike
     the overlap across layers this is legal in a real model, where the next layer's query does not exist yet:
     all parts belong to the same layer and use the same query.  The parts are handed to the step driver as its
@@ -585,7 +585,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=16)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=4, help="BASELINE config id (2, 3, 4 or 5)")
+    ap.add_argument("--config", type=int, default=4, help="workload id in synth_inputs.CONFIGS (2, 3, 4 or 5)")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers")
     ap.add_argument("--host-gib", type=float, default=60.0,
                     help="pinned host memory budget for values (the GPU boxes refuse more than 65 GiB in total)")

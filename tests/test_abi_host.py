@@ -126,3 +126,26 @@ def test_vq_trainer_matches_the_oracle(B, g, c, shared):
     bad.flat[0] = nval * g + 7
     with pytest.raises(B.HcaError):
         B.hca_vq_train(kval, g, c, bad, 1, shared)
+
+
+def test_tune_accepts_known_knobs_only(B):
+    for name in ("gather_wgs", "gather_unroll", "score_bpw", "score_depth"):
+        B.hca_tune(name, 0)
+    B.hca_tune("gather_unroll", 4)                 # back to the defaults
+    assert B.lib().hca_tune(b"no_such_knob", 1) == -1
+    assert B.lib().hca_tune(None, 1) == -1
+
+
+def test_topp_and_global_weight_arguments(B):
+    L = B.lib()
+    s = B.make_shape(1, 32, 8, 1024)
+    n = (C.c_int64 * 1)(100)
+    one = C.c_void_p(256)
+    assert L.hca_topp(C.byref(s), one, n, 0.1, C.c_double(0.0), 8, one, one, None, one, None) == -1      # tau must be > 0
+    assert L.hca_topp(C.byref(s), one, n, 0.0, C.c_double(0.5), 8, one, one, None, one, None) == -1      # sm_scale > 0
+    assert L.hca_topp(C.byref(s), one, n, 0.1, C.c_double(0.5), 0, one, one, None, one, None) == -3
+    assert L.hca_topp(C.byref(s), one, n, 0.1, C.c_double(0.5), 2000, one, one, None, one, None) == -3   # k_max > capacity
+    assert L.hca_topp(C.byref(s), None, n, 0.1, C.c_double(0.5), 8, one, one, None, one, None) == -1
+    assert L.hca_score_qkeys_lse(C.byref(s), one, one, n, 0.1, one, None, one, None) == -1
+    assert L.hca_score_qkeys_lse(C.byref(s), one, one, n, 0.1, one, one, None, None) == -1               # needs a workspace
+    assert L.hca_attend_gathered_global(C.byref(s), one, one, one, one, 8, 0.1, None, one, None, one, None) == -1

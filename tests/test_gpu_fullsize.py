@@ -1,4 +1,4 @@
-"""Full-size GPU parity in the launch configuration bench.py times: one layer of BASELINE config 4
+"""Full-size GPU parity in the launch configuration bench.py times: one layer of workload 4
 (1 Mi tokens, 4-bit / group 32, top-k 4096) and one layer of config 5 (4 Mi tokens, 2-bit / group 64,
 top-k 8192, eviction to 2 Mi), every output compared with the oracle run on the same inputs."""
 import numpy as np

@@ -169,7 +169,7 @@ def test_topk_bit_exact_including_ties(H, oracle, case, n, k):
 
 @pytest.mark.parametrize("cfg,host_rows", [(1, "all"), (1, "none"), (2, "half")])
 def test_pipeline_configs_against_oracle(H, oracle, cfg, host_rows):
-    """BASELINE configs 1 and 2 end to end: quantise -> score -> top-k -> attend (-> evict)."""
+    """Workloads 1 and 2 end to end: quantise -> score -> top-k -> attend (-> evict)."""
     w = S.CONFIGS[cfg]
     d = S.make_layer(w)
     R, G, n = w.batch * w.n_kv_heads, w.gqa, w.n
