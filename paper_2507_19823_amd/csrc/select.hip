@@ -309,6 +309,68 @@ __device__ __forceinline__ uint32_t block_scan_excl_256(uint32_t v, uint32_t* ws
   return base + inc - v;
 }
 
+// LDS counter updates, to be called by all lanes of a wave together.  When every participating lane
+// targets the same counter (ties, clustered scores) the wave issues one atomic instead of up to 64
+// serialised ones on the same word.
+__device__ __forceinline__ void lds_count(uint32_t* h, uint32_t bin, bool hit, bool aggregate) {
+  if (!aggregate) {                       // wave-uniform choice: short candidate sets do not pay for the ballots
+    if (hit) atomicAdd(&h[bin], 1u);
+    return;
+  }
+  const uint64_t m = __ballot(hit);
+  if (m == 0) return;
+  const int leader = __ffsll((unsigned long long)m) - 1;
+  const uint32_t b0 = __shfl(bin, leader);
+  if (__ballot(hit && bin != b0) == 0) {
+    if ((int)(threadIdx.x & 63) == leader) atomicAdd(&h[b0], (uint32_t)__popcll(m));
+  } else if (hit) {
+    atomicAdd(&h[bin], 1u);
+  }
+}
+
+// The same for a counter and an integer weight; one pair of atomics when all participating lanes hold the
+// same key (and therefore the same weight).
+__device__ __forceinline__ void lds_count_mass(uint32_t* h, unsigned long long* hm, uint32_t bin, uint32_t key,
+                                               uint64_t w, bool hit, bool aggregate) {
+  if (!aggregate) {
+    if (hit) {
+      atomicAdd(&h[bin], 1u);
+      if (w) atomicAdd(&hm[bin], (unsigned long long)w);
+    }
+    return;
+  }
+  const uint64_t m = __ballot(hit);
+  if (m == 0) return;
+  const int leader = __ffsll((unsigned long long)m) - 1;
+  const uint32_t k0 = __shfl(key, leader);
+  if (__ballot(hit && key != k0) == 0) {
+    if ((int)(threadIdx.x & 63) == leader) {
+      const uint32_t c = (uint32_t)__popcll(m);
+      atomicAdd(&h[bin], c);
+      if (w) atomicAdd(&hm[bin], (unsigned long long)w * c);
+    }
+  } else if (hit) {
+    atomicAdd(&h[bin], 1u);
+    if (w) atomicAdd(&hm[bin], (unsigned long long)w);
+  }
+}
+
+// Appends the participating lanes' (key, slot) pairs to an LDS list with one counter update per wave.
+__device__ __forceinline__ void lds_append(uint32_t* counter, uint2* list, uint32_t room, uint32_t key, uint32_t slot,
+                                           bool hit) {
+  const uint64_t m = __ballot(hit);
+  if (m == 0) return;
+  const int lane = threadIdx.x & 63;
+  const int leader = __ffsll((unsigned long long)m) - 1;
+  uint32_t base = 0;
+  if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+  base = __shfl(base, leader);
+  if (hit) {
+    const uint32_t at = base + (uint32_t)__popcll(m & ((1ull << lane) - 1));
+    if (at < room) list[at] = uint2{key, slot};
+  }
+}
+
 // Keys of the 16 slots s0 + x*256 + tid (x = 0..15) of a 4096-slot tile, all loads issued before
 // any use; slots at or past `end` yield valid[x] = false.
 __device__ __forceinline__ void load_tile_keys(const float* __restrict__ v, int64_t s0, int64_t end,
@@ -492,9 +554,10 @@ __global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, i
   cnt[tid] = tid < nchunks ? t.ncand[(int64_t)row * kMaxChunks + tid] : 0;
   if (tid == 0) s_n = 0;
   __syncthreads();
-  // sweep(f): f(key, slot) for every list entry of the row that lies in bin b*.  Each wave takes 16
-  // chunks per step and fetches the first 64 entries of all of them in one batch of loads (most
-  // lists are shorter than that), so a step costs one memory round trip; longer lists follow.
+  // sweep(f): f(key, slot, hit) over every list entry of the row, hit = the entry exists and lies in bin
+  // b*; f is called by all lanes of a wave together.  Each wave takes 16 chunks per step and fetches the
+  // first 64 entries of all of them in one batch of loads (most lists are shorter than that), so a step
+  // costs one memory round trip; longer lists follow, 8 loads in flight.
   auto sweep = [&](auto&& f) {
     for (int c0 = 0; c0 < nchunks; c0 += 256) {
       uint2 ent[16];
@@ -503,36 +566,89 @@ __global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, i
       for (int u = 0; u < 16; ++u) {
         const int c = c0 + wv * 16 + u;
         m[u] = c < nchunks ? cnt[c] : 0;
+        ent[u] = uint2{0, 0};
         if ((uint32_t)lane < m[u]) ent[u] = cand[(int64_t)c * chunk + lane];
       }
 #pragma unroll
-      for (int u = 0; u < 16; ++u)
-        if ((uint32_t)lane < m[u] && (ent[u].x >> 20) == bin) f(ent[u].x, ent[u].y);
+      for (int u = 0; u < 16; ++u) f(ent[u].x, ent[u].y, (uint32_t)lane < m[u] && (ent[u].x >> 20) == bin);
 #pragma unroll 1
-      for (int u = 0; u < 16; ++u) {      // long lists (clustered heavy hitters, mass ties): 8 loads in flight
+      for (int u = 0; u < 16; ++u) {      // long lists (clustered heavy hitters, mass ties)
         const int c = c0 + wv * 16 + u;
         for (uint32_t i0 = 64 + lane; i0 < m[u] + lane; i0 += 512) {
           uint2 x[8];
 #pragma unroll
-          for (int v = 0; v < 8; ++v)
+          for (int v = 0; v < 8; ++v) {
+            x[v] = uint2{0, 0};
             if (i0 + 64 * v < m[u]) x[v] = cand[(int64_t)c * chunk + i0 + 64 * v];
+          }
 #pragma unroll
-          for (int v = 0; v < 8; ++v)
-            if (i0 + 64 * v < m[u] && (x[v].x >> 20) == bin) f(x[v].x, x[v].y);
+          for (int v = 0; v < 8; ++v) f(x[v].x, x[v].y, i0 + 64 * v < m[u] && (x[v].x >> 20) == bin);
         }
       }
     }
   };
-  sweep([&](uint32_t key, uint32_t slot) {
-    const uint32_t at = atomicAdd(&s_n, 1u);
-    if (at < (uint32_t)kResolveLds) lc[at] = uint2{key, slot};
-  });
+  // staging: the in-bin entries go to the LDS list; one counter update per wave and batch of loads
+  {
+    const uint64_t lt = (1ull << lane) - 1;
+    auto stage = [&](const uint2* x, const bool* hit, int cntx) {
+      uint64_t mk[16];
+      uint32_t off[16], tot = 0;
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        if (u < cntx) { mk[u] = __ballot(hit[u]); off[u] = tot; tot += (uint32_t)__popcll(mk[u]); }
+      if (tot == 0) return;
+      uint32_t base = 0;
+      if (lane == 0) base = atomicAdd(&s_n, tot);
+      base = __shfl(base, 0);
+#pragma unroll
+      for (int u = 0; u < 16; ++u)
+        if (u < cntx && hit[u]) {
+          const uint32_t at = base + off[u] + (uint32_t)__popcll(mk[u] & lt);
+          if (at < (uint32_t)kResolveLds) lc[at] = x[u];
+        }
+    };
+    for (int c0 = 0; c0 < nchunks; c0 += 256) {
+      uint2 ent[16];
+      bool hit[16];
+      uint32_t m[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        const int c = c0 + wv * 16 + u;
+        m[u] = c < nchunks ? cnt[c] : 0;
+        ent[u] = uint2{0, 0};
+        if ((uint32_t)lane < m[u]) ent[u] = cand[(int64_t)c * chunk + lane];
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) hit[u] = (uint32_t)lane < m[u] && (ent[u].x >> 20) == bin;
+      stage(ent, hit, 16);
+#pragma unroll 1
+      for (int u = 0; u < 16; ++u) {
+        const int c = c0 + wv * 16 + u;
+        for (uint32_t i0 = 64 + lane; i0 < m[u] + lane; i0 += 512) {
+          uint2 x[8];
+          bool hx[8];
+#pragma unroll
+          for (int v = 0; v < 8; ++v) {
+            x[v] = uint2{0, 0};
+            if (i0 + 64 * v < m[u]) x[v] = cand[(int64_t)c * chunk + i0 + 64 * v];
+          }
+#pragma unroll
+          for (int v = 0; v < 8; ++v) hx[v] = i0 + 64 * v < m[u] && (x[v].x >> 20) == bin;
+          stage(x, hx, 8);
+        }
+      }
+    }
+  }
   __syncthreads();
   const uint32_t nst = s_n;
   const bool staged = nst <= (uint32_t)kResolveLds;
   auto visit = [&](auto&& f) {
     if (staged) {
-      for (uint32_t i = tid; i < nst; i += 1024) f(lc[i].x, lc[i].y);
+      for (uint32_t i0 = 0; i0 < nst; i0 += 1024) {
+        const bool hit = i0 + tid < nst;
+        const uint2 x = lc[hit ? i0 + tid : 0];
+        f(x.x, x.y, hit);
+      }
     } else {
       sweep(f);
     }
@@ -541,8 +657,8 @@ __global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, i
     const int shift = pass == 0 ? 10 : 0;
     h[tid] = 0;
     __syncthreads();
-    visit([&](uint32_t key, uint32_t) {
-      if ((key >> (shift + 10)) == (prefix >> (shift + 10))) atomicAdd(&h[(key >> shift) & 1023u], 1u);
+    visit([&](uint32_t key, uint32_t, bool hit) {
+      lds_count(h, (key >> shift) & 1023u, hit && (key >> (shift + 10)) == (prefix >> (shift + 10)), !staged);
     });
     __syncthreads();
     const uint32_t mine = h[1023 - tid];                    // thread tid owns bin 1023 - tid
@@ -560,9 +676,9 @@ __global__ __launch_bounds__(1024) void tk_resolve(int64_t chunk, int nchunks, i
   h[tid] = 0;
   e[tid] = 0;
   __syncthreads();
-  visit([&](uint32_t key, uint32_t slot) {
-    if (key > T) atomicAdd(&h[slot / chunk], 1u);
-    else if (key == T) atomicAdd(&e[slot / chunk], 1u);
+  visit([&](uint32_t key, uint32_t slot, bool hit) {
+    lds_count(h, (uint32_t)(slot / chunk), hit && key > T, !staged);
+    lds_count(e, (uint32_t)(slot / chunk), hit && key == T, !staged);
   });
   __syncthreads();
   const uint32_t g = (tid < nchunks) ? t.above[(int64_t)row * 1024 + tid] + h[tid] : 0;
@@ -851,25 +967,27 @@ __global__ __launch_bounds__(1024) void tp_resolve(int64_t chunk, int nchunks, i
         for (uint32_t i0 = lane; i0 < mu + lane; i0 += 512) {
           uint2 x[8];
 #pragma unroll
-          for (int v = 0; v < 8; ++v)
+          for (int v = 0; v < 8; ++v) {
+            x[v] = uint2{0, 0};
             if (i0 + 64 * v < mu) x[v] = cand[(int64_t)c * chunk + i0 + 64 * v];
+          }
 #pragma unroll
-          for (int v = 0; v < 8; ++v)
-            if (i0 + 64 * v < mu && (x[v].x >> 20) == bin) f(x[v].x, x[v].y);
+          for (int v = 0; v < 8; ++v) f(x[v].x, x[v].y, i0 + 64 * v < mu && (x[v].x >> 20) == bin);
         }
       }
     }
   };
-  sweep([&](uint32_t key, uint32_t slot) {
-    const uint32_t at = atomicAdd(&s_n, 1u);
-    if (at < (uint32_t)kResolveLds) lc[at] = uint2{key, slot};
-  });
+  sweep([&](uint32_t key, uint32_t slot, bool hit) { lds_append(&s_n, lc, (uint32_t)kResolveLds, key, slot, hit); });
   __syncthreads();
   const uint32_t nst = s_n;
   const bool staged = nst <= (uint32_t)kResolveLds;
   auto visit = [&](auto&& f) {
     if (staged) {
-      for (uint32_t i = tid; i < nst; i += 1024) f(lc[i].x, lc[i].y);
+      for (uint32_t i0 = 0; i0 < nst; i0 += 1024) {
+        const bool hit = i0 + tid < nst;
+        const uint2 x = lc[hit ? i0 + tid : 0];
+        f(x.x, x.y, hit);
+      }
     } else {
       sweep(f);
     }
@@ -880,12 +998,10 @@ __global__ __launch_bounds__(1024) void tp_resolve(int64_t chunk, int nchunks, i
     h[tid] = 0;
     hm[tid] = 0;
     __syncthreads();
-    visit([&](uint32_t key, uint32_t) {
-      if ((key >> (shift + 10)) == (prefix >> (shift + 10))) {
-        atomicAdd(&h[(key >> shift) & 1023u], 1u);
-        const uint64_t w = tp_weight(key_to_float(key) * sm_scale - m);
-        if (w) atomicAdd(&hm[(key >> shift) & 1023u], (unsigned long long)w);
-      }
+    visit([&](uint32_t key, uint32_t, bool hit) {
+      const bool in = hit && (key >> (shift + 10)) == (prefix >> (shift + 10));
+      const uint64_t w = in ? tp_weight(key_to_float(key) * sm_scale - m) : 0;
+      lds_count_mass(h, hm, (key >> shift) & 1023u, key, w, in, !staged);
     });
     __syncthreads();
     const uint32_t mine_c = h[1023 - tid];                  // thread tid owns digit 1023 - tid
@@ -917,9 +1033,9 @@ __global__ __launch_bounds__(1024) void tp_resolve(int64_t chunk, int nchunks, i
   h[tid] = 0;
   e[tid] = 0;
   __syncthreads();
-  visit([&](uint32_t key, uint32_t slot) {
-    if (key > T) atomicAdd(&h[slot / chunk], 1u);
-    else if (key == T) atomicAdd(&e[slot / chunk], 1u);
+  visit([&](uint32_t key, uint32_t slot, bool hit) {
+    lds_count(h, (uint32_t)(slot / chunk), hit && key > T, !staged);
+    lds_count(e, (uint32_t)(slot / chunk), hit && key == T, !staged);
   });
   __syncthreads();
   const uint32_t g = (tid < nchunks) ? t.above[(int64_t)row * 1024 + tid] + h[tid] : 0;
