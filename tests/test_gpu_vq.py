@@ -220,3 +220,69 @@ def test_vq_evict_matches_oracle(B, oracle, mode, g, n, M, Rp):
             assert np.all(kg[r] == -5)                       # rows left alone report nothing
         assert np.array_equal(Pg[r, :m], oc.P[r, :m].astype(np.uint8))
         assert np.array_equal(ag[r, :m], acc[r, :m]) and np.array_equal(pg[r, :m], pos[r, :m])
+
+
+def test_vq_decode_loop_with_appends_topp_and_eviction(B, oracle):
+    """The paper-faithful step on a codebook cache, twelve times over: append one token, table + scores,
+    cumulative-weight selection (Eq. 4), gather, attend with accumulated scores, eviction every 4 steps.
+    The GPU state is compared with the oracle after every step (stage-wise on acc)."""
+    import synth_inputs as S
+    w = S.Workload("vqloop", 5, 2, 8, 2, 2000, 4, 32, 160, evict_keep=2000, evict_every=4, steps=12)
+    d = S.make_layer(w)
+    rng = np.random.default_rng(55)
+    batch, hkv, G, g, c, k_max = w.batch, w.n_kv_heads, w.gqa, 32, 128, w.k
+    R, n0 = batch * hkv, w.n
+    cap, vcap = n0 + 8, n0 + w.steps
+    keys = d["keys"].numpy()
+    cen = _codebook(oracle, rng, keys, hkv, g, c)
+    st = _State(B, batch, hkv * G, hkv, cap, g, c, cen, k_max)
+    st.assign(d["keys"])
+    oc = oracle.VQCache(R, cap, cen)
+    oracle.vq_assign(oc, keys.reshape(R, n0, D))
+    v_host = torch.zeros(batch, hkv, vcap, D, dtype=torch.float16).pin_memory()
+    v_host[:, :, :n0] = d["values"]
+    pos = np.zeros((R, cap), np.int32)
+    pos[:, :n0] = np.arange(n0)
+    acc = np.zeros((R, cap), np.float32)
+    sm = 1.0 / np.sqrt(D)
+    ws_e = torch.empty(B.hca_workspace_bytes(st.shape, k_max, w.evict_keep), dtype=torch.uint8, device="cuda")
+    counts_seen = set()
+    for step in range(w.steps):
+        k_new, v_new, q = S.make_step(w, 0, step)
+        n = st.n[0]
+        v_host[:, :, n0 + step] = v_new[:, :, 0]
+        pos[:, n] = n0 + step
+        acc[:, n] = 0
+        st.assign(k_new, row0=[n0 + step] * batch)
+        oracle.vq_assign(oc, k_new.numpy().reshape(R, 1, D))
+        qd = q.cuda()
+        B.hca_vq_score(st.shape, st.cb, st.P, qd, st.n, st.lut, st.sel, None)
+        B.hca_topp(st.shape, st.sel, st.n, sm, 0.9, k_max, st.idx, st.count, None, st.ws)
+        B.hca_gather_values(st.shape, st.idx, st.count, k_max, st.pos, v_host, vcap, vcap, None, 0, st.ws)
+        B.hca_vq_attend_gathered(st.shape, st.cb, st.P, st.lut, st.idx, st.count, k_max, sm, st.y, st.acc, st.ws)
+        torch.cuda.synchronize()
+        T = oracle.vq_lut(oc, q.numpy().reshape(R * G, D))
+        sel, _ = oracle.vq_score(oc, T, want_z=False)
+        idx, count, _, _ = oracle.topp(sel, oc.n, sm, 0.9, k_max)
+        cg = st.count.cpu().numpy().reshape(R)
+        assert np.array_equal(cg, count), f"step {step}"
+        counts_seen |= set(count.tolist())
+        ig = st.idx.cpu().numpy().reshape(R, k_max)
+        for r in range(R):
+            assert np.array_equal(ig[r, :count[r]], idx[r, :count[r]]), f"step {step} row {r}"
+        y, _ = oracle.vq_attend(oc, T, idx, count, pos, v_host.numpy().reshape(R, vcap, D), sm, acc=acc)
+        assert _rel_err(st.y.cpu().numpy().reshape(R * G, D), y) <= TOL
+        nn = st.n[0]
+        assert np.allclose(st.acc.cpu().numpy().reshape(R, cap)[:, :nn], acc[:, :nn], rtol=1e-4, atol=1e-7)
+        st.acc.copy_(torch.from_numpy(acc.reshape(batch, hkv, cap)))            # stage-wise from here on
+        if (step + 1) % w.evict_every == 0:
+            B.hca_vq_evict(st.shape, st.cb, st.P, st.acc, st.pos, st.n, w.evict_keep, w.evict_every, None, ws_e)
+            st.n = [min(x, w.evict_keep) for x in st.n]
+            torch.cuda.synchronize()
+            oracle.vq_evict(oc, acc, pos, w.evict_keep, w.evict_every)
+            m = w.evict_keep
+            assert st.n[0] == m == oc.n[0]
+            assert np.array_equal(st.P_rows()[:, :m], oc.P[:, :m].astype(np.uint8))
+            assert np.array_equal(st.pos.cpu().numpy().reshape(R, cap)[:, :m], pos[:, :m])
+            assert np.array_equal(st.acc.cpu().numpy().reshape(R, cap)[:, :m], acc[:, :m])
+    assert len(counts_seen) > 1
