@@ -504,6 +504,81 @@ def selection_probe(w, iters=10):
     return out
 
 
+def paper_form_probe(w, layers=8, steps=6, g=32, c=256, tau=0.9):
+    """Decode steps in the paper's own form on `layers` layers of the workload: codebook key cache (Sec. 3.1),
+    table-lookup scores (Eq. 3), cumulative-weight selection (Eq. 4, cut at the workload's k), gather of the
+    selected value rows from pinned host memory, softmax-weighted sum.  One stream, calls in order; the
+    time per layer is what a layer costs when nothing overlaps.  With the synthetic planted queries the
+    selection keeps only a few tokens per head (the count is reported), so the gather is short here."""
+    import numpy as np
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    G = w.n_q_heads // w.n_kv_heads
+    cap = w.n + steps + 16
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    rng = np.random.default_rng(1000 * w.config + 11)
+    P, cens, cbs, vh, pos, acc, qs, kn = [], [], [], [], [], [], [], []
+    for l in range(layers):
+        d = S.make_layer(w, l, device="cuda", want_values=True)
+        cen = []
+        for h in range(w.n_kv_heads):
+            kval = d["keys"][0, h, :4096].cpu().numpy()
+            init = np.stack([rng.choice(kval.shape[0], c, replace=False) for _ in range(g)]).astype(np.int32)
+            cen.append(B.hca_vq_train(kval, g, c, init, 2)[0])
+        cens.append(torch.from_numpy(np.stack(cen)).cuda())
+        cbs.append(B.make_codebook(g, c, cens[-1]))
+        P.append(torch.empty(B.hca_vq_pcache_bytes(shape, cbs[-1]), dtype=torch.uint8, device="cuda"))
+        pos.append(torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.int32, device="cuda"))
+        acc.append(torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda"))
+        B.hca_vq_assign(shape, cbs[-1], P[-1], d["keys"], w.n, [0] * w.batch, acc[-1], pos[-1], [0] * w.batch)
+        v = torch.empty(w.batch, w.n_kv_heads, w.n, 128, dtype=torch.float16, pin_memory=True)
+        v.copy_(d["values"])
+        vh.append(v)
+        st = [S.make_step(w, l, t) for t in range(steps)]
+        kn.append([x[0].cuda() for x in st])
+        qs.append([x[2].cuda() for x in st])
+        del d
+    lut = torch.empty(B.hca_vq_lut_bytes(shape, cbs[0]) // 4, dtype=torch.float32, device="cuda")
+    sel = torch.empty(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
+    idx = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device="cuda")
+    count = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
+    y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    vnew = torch.zeros(w.batch, w.n_kv_heads, steps, 128, dtype=torch.float16, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+    sm = 1.0 / (128.0 ** 0.5)
+    kept = []
+
+    def step(t):
+        n = [w.n + t] * w.batch
+        for l in range(layers):
+            B.hca_vq_assign(shape, cbs[l], P[l], kn[l][t], 1, n, acc[l], pos[l], n)
+            n1 = [x + 1 for x in n]
+            B.hca_vq_score(shape, cbs[l], P[l], qs[l][t], n1, lut, sel)
+            B.hca_topp(shape, sel, n1, sm, tau, w.k, idx, count, None, ws)
+            B.hca_gather_values(shape, idx, count, w.k, pos[l], vh[l], w.n, w.n, vnew, steps, ws)
+            B.hca_vq_attend_gathered(shape, cbs[l], P[l], lut, idx, count, w.k, sm, y, acc[l], ws)
+
+    step(0)
+    torch.cuda.synchronize()
+    kept = count.cpu().reshape(-1).tolist()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for t in range(1, steps):
+        step(t)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / (steps - 1)
+    out = {"workload": w.name, "layers": layers, "groups": g, "codewords": c, "tau": tau, "k_cut": w.k,
+           "ms_per_layer": ms / layers, "context_tokens_scored_per_s": w.batch * w.n * layers / ms * 1e3,
+           "selected_per_kv_head_last_layer": kept}
+    del P, vh, lut, sel
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()
+    return out
+
+
 def scan_only(w, iters):
     """Key-scan kernel alone on one layer (two cache copies alternate), preceded by a plain 1 GiB
     device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the counters (profiles/)."""
@@ -663,10 +738,12 @@ def main():
                     latency[name]["ms_per_layer"] = g["ms_per_layer"]
                     latency[name]["parts"] = parts
 
-    codebook = selection = None
+    codebook = selection = paper_form = None
     if not args.no_latency:
         codebook = vq_probe(S.CONFIGS[4], 10)
         log(f"codebook key path at 1M: table + lookup scan {codebook['score_ms']:.3f} ms per layer")
+        paper_form = paper_form_probe(S.CONFIGS[4])
+        log(f"paper-form decode step at 1M: {paper_form['ms_per_layer']:.3f} ms per layer")
         selection = selection_probe(S.CONFIGS[4])
         log(f"selection at 1M: top-k {selection['topk_ms']:.3f} ms, Eq. 4 at tau 0.9 {selection['topp_tau0.9']['ms']:.3f} ms")
 
@@ -758,6 +835,7 @@ def main():
         "per_layer_decode_latency": latency,
         "codebook_key_path": codebook,
         "selection": selection,
+        "paper_form_step": paper_form,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,

@@ -80,6 +80,54 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
   }
 }
 
+// Few tokens per call (decode appends): one workgroup per (token, row); a wave takes every fourth group
+// and spreads the group's centroids over its lanes (lane, lane + 64, ...), then the lanes' candidates are
+// reduced by (distance, index): the smaller distance wins, equal distances go to the lower index - the
+// same winner as the ascending scan with a strict comparison.
+template <int DBAR>
+__global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int n_kv_heads, int64_t cap,
+                                                              const float* __restrict__ centroids,
+                                                              uint8_t* __restrict__ pcache,
+                                                              const uint16_t* __restrict__ k_new, int64_t T, NRes nr,
+                                                              float* __restrict__ acc, int32_t* __restrict__ pos,
+                                                              NRes vrow0) {
+  const int row = blockIdx.y;
+  const int64_t tt = blockIdx.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int b = row / n_kv_heads;
+  const int64_t slot = nr.n[b] + tt;
+  const uint16_t* src = k_new + ((int64_t)row * T + tt) * kHeadDim;
+  const float* cb = centroids + (int64_t)(row % n_kv_heads) * g * c * DBAR;
+  for (int i = w; i < g; i += 4) {
+    float x[DBAR];
+#pragma unroll
+    for (int dd = 0; dd < DBAR; ++dd) x[dd] = h2f(src[i * DBAR + dd]);
+    float bd = INFINITY;
+    int best = 0x7fffffff;
+    for (int cc = lane; cc < c; cc += 64) {
+      const float* cv = cb + ((int64_t)i * c + cc) * DBAR;
+      float d = 0.f;
+#pragma unroll
+      for (int dd = 0; dd < DBAR; ++dd) {
+        const float e = x[dd] - cv[dd];
+        d = fmaf(e, e, d);
+      }
+      if (d < bd || best == 0x7fffffff) { bd = d; best = cc; }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const float od = __shfl_xor(bd, o);
+      const int ob = __shfl_xor(best, o);
+      if (ob != 0x7fffffff && (best == 0x7fffffff || od < bd || (od == bd && ob < best))) { bd = od; best = ob; }
+    }
+    if (lane == 0) pcache[((int64_t)row * cap + slot) * g + i] = (uint8_t)best;
+  }
+  if (threadIdx.x == 0) {
+    if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
+    if (pos != nullptr) pos[(int64_t)row * cap + slot] = (int32_t)(vrow0.n[b] + tt);
+  }
+}
+
 // -------------------------------------------------------------------------------- table ---
 // T[row][i][cc][h] = qbar_i . C[i][cc] for the G query heads of the row: t = 0; t = fmaf(q, c, t) over
 // the group's channels in ascending order.  grid (g, rows), one thread per centroid.
@@ -174,8 +222,17 @@ __global__ __launch_bounds__(1024) void vq_scan_kernel(int c, int64_t cap, const
 int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, uint8_t* pcache, const void* k_new,
                          int64_t T, const NRes& nr, float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st) {
   if (T == 0) return HCA_OK;
-  dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 16));
   const uint16_t* kn = (const uint16_t*)k_new;
+  if (T <= 8) {                                     // decode appends: parallel over centroids, not over tokens
+    dim3 gs((unsigned)T, (unsigned)L.rows);
+    if (g == 32)
+      vq_assign_small_kernel<4><<<gs, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+    else
+      vq_assign_small_kernel<2><<<gs, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+    HCA_HIP(hipGetLastError());
+    return HCA_OK;
+  }
+  dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 16));
   if (g == 32)
     vq_assign_kernel<4><<<grid, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
   else
