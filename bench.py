@@ -579,6 +579,72 @@ def paper_form_probe(w, layers=8, steps=6, g=32, c=256, tau=0.9):
     return out
 
 
+def cpu_split_probe(w, threads=16, iters=6):
+    """The paper's CPU-GPU split of the value side on one layer of the workload, beside the graded gather
+    path: after scan + top-k, (a) hca_attend_weights writes fp16 weights and value-row numbers into pinned
+    host memory and hca_host_weighted_sum forms y on the host cores; (b) hca_gather_values +
+    hca_attend_gathered.  Reports link bytes per layer and the time of each form (stream time for the GPU
+    parts, wall clock for the host sum)."""
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    cap = w.n + 16
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap, w.bits, w.group)
+    d = S.make_layer(w, 0, device="cuda", want_values=True)
+    kc = torch.empty(B.hca_kcache_bytes(shape), dtype=torch.uint8, device="cuda")
+    B.hca_quantize_keys(shape, kc, d["keys"], w.n, [0] * w.batch)
+    n = [w.n] * w.batch
+    sel = torch.empty(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
+    idx = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device="cuda")
+    count = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
+    pos = torch.arange(cap, dtype=torch.int32, device="cuda").repeat(w.batch, w.n_kv_heads, 1).contiguous()
+    ws = torch.empty(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+    y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    vh = torch.empty(w.batch, w.n_kv_heads, w.n, 128, dtype=torch.float16, pin_memory=True)
+    vh.copy_(d["values"])
+    w16 = torch.zeros(w.batch, w.n_q_heads, w.k, dtype=torch.float16).pin_memory()
+    vrow = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32).pin_memory()
+    cnt_h = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32).pin_memory()
+    yh = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32)
+    sm = 1.0 / (128.0 ** 0.5)
+    B.hca_score_qkeys(shape, kc, d["q"], n, sel)
+    B.hca_topk(shape, sel, n, w.k, idx, count, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    gpu_ms, host_ms = [], []
+    for _ in range(iters):
+        e0.record()
+        B.hca_attend_weights(shape, kc, d["q"], idx, count, w.k, pos, sm, None, w16, vrow, None, ws)
+        cnt_h.copy_(count, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.hca_host_weighted_sum(shape, vrow, cnt_h, w.k, w16, vh, w.n, yh, threads)
+        host_ms.append((time.perf_counter() - t0) * 1e3)
+        gpu_ms.append(e0.elapsed_time(e1))
+    gath = []
+    for _ in range(iters):
+        e0.record()
+        B.hca_gather_values(shape, idx, count, w.k, pos, vh, w.n, w.n, None, 0, ws)
+        B.hca_attend_gathered(shape, kc, d["q"], idx, count, w.k, sm, y, None, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        gath.append(e0.elapsed_time(e1))
+    torch.cuda.synchronize()
+    diff = float((y.cpu() - yh).abs().max() / y.abs().max().cpu())
+    rows = w.batch * w.n_kv_heads
+    G = w.n_q_heads // w.n_kv_heads
+    out = {"workload": w.name, "k": w.k, "host_threads": threads,
+           "split_link_bytes_per_layer": rows * w.k * (4 + 2 * G), "gather_link_bytes_per_layer": rows * w.k * 256,
+           "split_gpu_weights_ms": sorted(gpu_ms)[iters // 2], "split_host_sum_ms": sorted(host_ms)[iters // 2],
+           "gather_plus_attend_ms": sorted(gath)[iters // 2], "max_rel_diff_between_the_two": diff}
+    del kc, sel, vh, d
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()
+    return out
+
+
 def scan_only(w, iters):
     """Key-scan kernel alone on one layer (two cache copies alternate), preceded by a plain 1 GiB
     device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the counters (profiles/)."""
@@ -738,12 +804,15 @@ def main():
                     latency[name]["ms_per_layer"] = g["ms_per_layer"]
                     latency[name]["parts"] = parts
 
-    codebook = selection = paper_form = None
+    codebook = selection = paper_form = cpu_split = None
     if not args.no_latency:
         codebook = vq_probe(S.CONFIGS[4], 10)
         log(f"codebook key path at 1M: table + lookup scan {codebook['score_ms']:.3f} ms per layer")
         paper_form = paper_form_probe(S.CONFIGS[4])
         log(f"paper-form decode step at 1M: {paper_form['ms_per_layer']:.3f} ms per layer")
+        cpu_split = cpu_split_probe(S.CONFIGS[4])
+        log(f"value side at 1M, k 4096: gather + attend {cpu_split['gather_plus_attend_ms']:.3f} ms; paper's split "
+            f"{cpu_split['split_gpu_weights_ms']:.3f} ms on the GPU + {cpu_split['split_host_sum_ms']:.3f} ms on the host")
         selection = selection_probe(S.CONFIGS[4])
         log(f"selection at 1M: top-k {selection['topk_ms']:.3f} ms, Eq. 4 at tau 0.9 {selection['topp_tau0.9']['ms']:.3f} ms")
 
@@ -836,6 +905,7 @@ def main():
         "codebook_key_path": codebook,
         "selection": selection,
         "paper_form_step": paper_form,
+        "value_side_cpu_split": cpu_split,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,

@@ -285,6 +285,32 @@ int32_t hca_attend_gathered_global(const hca_shape* shape, const void* kcache, c
                                    const int32_t* count, int32_t k, float sm_scale, const float* lse, float* y,
                                    float* acc_opt, void* workspace, void* stream);
 
+/* ---- The paper's CPU-GPU split of the value side ----------------------------------------------
+ * Sec. 3.2 "CPU part", Eq. 5, and Sec. 3.3 "Communication overhead": the values never leave host memory;
+ * per selected token only its value-row number and one 2-byte weight per query head cross the link, and the
+ * host forms the weighted sum.  (The graded path does the opposite: value rows come to the GPU,
+ * hca_gather_values.)
+ * hca_attend_weights: softmax weights of the selected tokens, as hca_attend_gathered computes them
+ * (renormalised over the selected set, or the paper's exp(l - lse) when lse_opt is given), rounded to fp16.
+ *   w_f16    device or pinned host, fp16 [batch, n_q_heads, k]: weight of selected token i for each query
+ *            head; 0 past count
+ *   vrow     device or pinned host, int32 [batch, n_kv_heads, k]: pos[idx[i]], the token's row in the value
+ *            store; -1 past count
+ *   acc_opt  as in hca_sparse_attend (the unrounded weights are accumulated)
+ *   workspace device, hca_workspace_bytes(shape, k, 1)
+ * hca_host_weighted_sum: host code, blocks until done: y[hq] = sum_i w[hq][i] * V[vrow[i]] in fp32.
+ *   vrow, count, w_f16  host-readable copies of the outputs above (count: int32 [batch, n_kv_heads])
+ *   v_host   host, fp16 [batch, n_kv_heads, host_stride, head_dim]
+ *   y        host, fp32 [batch, n_q_heads, head_dim]
+ *   n_threads  host threads to use (1 .. 64)
+ * Errors: HCA_ERR_CAPACITY if a value row lies outside host_stride. */
+int32_t hca_attend_weights(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
+                           const int32_t* count, int32_t k, const int32_t* pos, float sm_scale, const float* lse_opt,
+                           void* w_f16, int32_t* vrow, float* acc_opt, void* workspace, void* stream);
+int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* vrow, const int32_t* count, int32_t k,
+                              const void* w_f16, const void* v_host, int64_t host_stride, float* y,
+                              int32_t n_threads);
+
 /* ---- Codebook form of the key path ---------------------------------------------------------
  * The paper's own compressor: grouped vector quantisation (Sec. 3.1) and table-lookup scores
  * (Sec. 3.2, Eq. 3).  The head dimension is cut into g groups of dbar = head_dim / g channels, a

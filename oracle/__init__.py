@@ -320,3 +320,22 @@ def topp(sel, n, sm_scale, tau, k_max):
     _check(lib().hco_topp(_p(sel), C.c_int64(R), C.c_int64(cap), _p(n), C.c_float(sm_scale), C.c_double(tau),
                           C.c_int64(k_max), _p(idx), _p(count), _p(kstar), _p(mass)), "topp")
     return idx, count, kstar, mass
+
+
+# ---- the paper's CPU-side weighted sum (Sec. 3.2 "CPU part", Sec. 3.3: 2 bytes per weight) ----------
+
+def weighted_sum_f16(w, idx, count, pos, V):
+    """y [R*G, D] (fp64) = sum_i fp16(w[hq, i]) * V[r, pos[r, idx[r, i]]]: the weights cross the link as
+    2-byte values, the host sums.  w [R*G, k] fp32 (from attend(..., want_w=True)), V [R, vrows, D] fp16."""
+    w16 = np.asarray(w, np.float32).astype(np.float16).astype(np.float64)
+    R = idx.shape[0]
+    G = w16.shape[0] // R
+    V = np.asarray(V)
+    y = np.zeros((R * G, V.shape[2]), np.float64)
+    for r in range(R):
+        c = int(count[r])
+        rows = pos[r, idx[r, :c]]
+        vr = V[r, rows].astype(np.float64)
+        for h in range(G):
+            y[r * G + h] = w16[r * G + h, :c] @ vr
+    return y

@@ -80,6 +80,10 @@ def lib():
         L.hca_score_qkeys_lse.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, vp]
         L.hca_attend_gathered_global.restype = i32
         L.hca_attend_gathered_global.argtypes = [sp, vp, vp, vp, vp, i32, f32, vp, vp, vp, vp, vp]
+        L.hca_attend_weights.restype = i32
+        L.hca_attend_weights.argtypes = [sp, vp, vp, vp, vp, i32, vp, f32, vp, vp, vp, vp, vp, vp]
+        L.hca_host_weighted_sum.restype = i32
+        L.hca_host_weighted_sum.argtypes = [sp, vp, vp, i32, vp, vp, i64, vp, i32]
         L.hca_topp.restype = i32
         L.hca_topp.argtypes = [sp, vp, vp, f32, C.c_double, i32, vp, vp, vp, vp, vp]
         L.hca_sparse_attend.restype = i32
@@ -331,3 +335,15 @@ def hca_attend_gathered_global(shape, kcache, q_f16, idx, count, k, sm_scale, ls
     _check(lib().hca_attend_gathered_global(C.byref(shape), _ptr(kcache), _ptr(q_f16), _ptr(idx), _ptr(count), int(k),
                                             float(sm_scale), _ptr(lse), _ptr(y), _ptr(acc), _ptr(workspace),
                                             _stream(stream)), "hca_attend_gathered_global")
+
+
+def hca_attend_weights(shape, kcache, q_f16, idx, count, k, pos, sm_scale, lse, w_f16, vrow, acc, workspace, stream=None):
+    _check(lib().hca_attend_weights(C.byref(shape), _ptr(kcache), _ptr(q_f16), _ptr(idx), _ptr(count), int(k), _ptr(pos),
+                                    float(sm_scale), _ptr(lse), _ptr(w_f16), _ptr(vrow), _ptr(acc), _ptr(workspace),
+                                    _stream(stream)), "hca_attend_weights")
+
+
+def hca_host_weighted_sum(shape, vrow, count, k, w_f16, v_host, host_stride, y, n_threads=16):
+    """All tensors are CPU tensors (pinned or not); blocks until y is written."""
+    _check(lib().hca_host_weighted_sum(C.byref(shape), _ptr(vrow), _ptr(count), int(k), _ptr(w_f16), _ptr(v_host),
+                                       int(host_stride), _ptr(y), int(n_threads)), "hca_host_weighted_sum")

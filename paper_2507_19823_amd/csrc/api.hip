@@ -181,6 +181,20 @@ int32_t hca_attend_gathered_global(const hca_shape* shape, const void* kcache, c
                                 lse);
 }
 
+int32_t hca_attend_weights(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
+                           const int32_t* count, int32_t k, const int32_t* pos, float sm_scale, const float* lse_opt,
+                           void* w_f16, int32_t* vrow, float* acc_opt, void* workspace, void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (kcache == nullptr || q_f16 == nullptr || idx == nullptr || count == nullptr || pos == nullptr ||
+      w_f16 == nullptr || vrow == nullptr || workspace == nullptr)
+    return HCA_ERR_BAD_ARG;
+  if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
+  return launch_attend_weights(L, kcache, q_f16, idx, count, k, pos, sm_scale, lse_opt, w_f16, vrow, acc_opt, workspace,
+                               (hipStream_t)stream);
+}
+
 int32_t hca_topp(const hca_shape* shape, const float* sel, const int64_t* n_resident, float sm_scale, double tau,
                  int32_t k_max, int32_t* idx, int32_t* count, uint64_t* mass_opt, void* workspace, void* stream) {
   Layout L;

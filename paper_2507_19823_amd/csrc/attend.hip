@@ -86,6 +86,7 @@ __device__ __forceinline__ void partial_empty(float* pmz, float* py) {
 
 // Steps 2 and 3 of a chunk, after its logits sit in ps.lg (and a __syncthreads()): per-head chunk
 // max / exponentials / sum, then the weighted sum of the staged value rows.
+template <bool VALUES = true>
 __device__ __forceinline__ void partial_softmax_sum(PartialShared& ps, const AttendWs& a, int row, int i0, int nvalid,
                                                     int32_t k, float* pmz, float* py) {
   auto& lg = ps.lg;
@@ -112,6 +113,10 @@ __device__ __forceinline__ void partial_softmax_sum(PartialShared& ps, const Att
     if (lane == 0) { hm[w] = m; hz[w] = z; }
   }
   __syncthreads();
+  if constexpr (!VALUES) {   // weights only: the chunk's (max, sum) pairs and the stored logits are all that is needed
+    if (threadIdx.x < 4) { pmz[2 * threadIdx.x] = hm[threadIdx.x]; pmz[2 * threadIdx.x + 1] = hz[threadIdx.x]; }
+    return;
+  }
 
   // 3. weighted value sum.  Wave w owns tokens [64w, 64w+64) of the chunk; one load instruction
   //    fetches 4 staged rows (lane>>4 picks the row, lane&15 its 16-byte part) and 8 of them are
@@ -170,7 +175,7 @@ __device__ __forceinline__ void partial_softmax_sum(PartialShared& ps, const Att
   if (threadIdx.x < 4) { pmz[2 * threadIdx.x] = hm[threadIdx.x]; pmz[2 * threadIdx.x + 1] = hz[threadIdx.x]; }
 }
 
-template <int BITS>
+template <int BITS, bool VALUES = true>
 __global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* __restrict__ kcache,
                                                       const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
                                                       const int32_t* __restrict__ count, int32_t k, float sm_scale,
@@ -235,7 +240,7 @@ __global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* _
   }
   __syncthreads();
 
-  partial_softmax_sum(ps, a, row, i0, nvalid, k, pmz, py);
+  partial_softmax_sum<VALUES>(ps, a, row, i0, nvalid, k, pmz, py);
 }
 
 // Table entry of one (group, centroid): the G query heads of the KV head, adjacent in memory.
@@ -435,6 +440,70 @@ int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* 
   else vq_attend_partial<1><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
   dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
   attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, nullptr);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+// The paper's split (Sec. 3.2 "CPU part", Sec. 3.3 "Communication overhead"): only the selected tokens'
+// value-row numbers and weights leave the GPU (2 bytes per weight), the host forms the weighted sum.
+// One workgroup per chunk of 256 selected tokens merges the chunk (max, sum) pairs of the row and writes
+// fp16 weights [row * G + h][k], value rows [row][k] and, optionally, the accumulated scores.
+__global__ __launch_bounds__(256) void weights_finalize(Layout L, const int32_t* __restrict__ idx,
+                                                        const int32_t* __restrict__ count, int32_t k,
+                                                        const int32_t* __restrict__ pos, AttendWs a, int nsplit,
+                                                        const float* __restrict__ lse, uint16_t* __restrict__ w_out,
+                                                        int32_t* __restrict__ vrow_out, float* __restrict__ acc) {
+  __shared__ float fm[4], fz[4];
+  __shared__ float pm[64][4], pz[64][4];
+  const int row = blockIdx.y;
+  const int cnt = count[row];
+  const float* pmz = a.pmz + ((int64_t)row * nsplit * 4) * 2;
+  if (threadIdx.x < 4 * nsplit) {
+    const float2 v = reinterpret_cast<const float2*>(pmz)[threadIdx.x];
+    pm[threadIdx.x >> 2][threadIdx.x & 3] = v.x;
+    pz[threadIdx.x >> 2][threadIdx.x & 3] = v.y;
+  }
+  __syncthreads();
+  if (threadIdx.x < 4) {
+    const int h = threadIdx.x;
+    float m = -INFINITY;
+    for (int sp = 0; sp < nsplit; ++sp) m = fmaxf(m, pm[sp][h]);
+    float z = 0.f;
+    for (int sp = 0; sp < nsplit; ++sp) {
+      const float ms = pm[sp][h];
+      z += (ms == -INFINITY) ? 0.f : expf(ms - m) * pz[sp][h];
+    }
+    if (lse != nullptr && h < L.gqa) z = expf(lse[(int64_t)row * L.gqa + h] - m);
+    fm[h] = m; fz[h] = z;
+  }
+  __syncthreads();
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= k) return;
+  const bool live = i < cnt;
+  float wsum = 0.f;
+  for (int h = 0; h < L.gqa; ++h) {
+    const float p = live ? expf(a.logit[((int64_t)row * 4 + h) * k + i] - fm[h]) / fz[h] : 0.f;
+    w_out[((int64_t)row * L.gqa + h) * k + i] = f2h_bits(p);
+    wsum += fmaxf(p, 1e-30f);
+  }
+  const int32_t slot = live ? idx[(int64_t)row * k + i] : 0;
+  vrow_out[(int64_t)row * k + i] = live ? pos[(int64_t)row * L.cap + slot] : -1;
+  if (live && acc != nullptr) acc[(int64_t)row * L.cap + slot] += wsum;
+}
+
+int32_t launch_attend_weights(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                              const int32_t* count, int32_t k, const int32_t* pos, float sm_scale, const float* lse,
+                              void* w_out, int32_t* vrow_out, float* acc_opt, void* ws, hipStream_t st) {
+  AttendWs a;
+  carve(&a, ws, L, k);
+  const int ns = nsplit_of(k);
+  if (ns > 64) return HCA_ERR_CAPACITY;
+  dim3 gp((unsigned)ns, (unsigned)L.rows);
+  if (L.bits == 4)
+    attend_partial<4, false><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
+  else
+    attend_partial<2, false><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
+  weights_finalize<<<gp, 256, 0, st>>>(L, idx, count, k, pos, a, ns, lse, (uint16_t*)w_out, vrow_out, acc_opt);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

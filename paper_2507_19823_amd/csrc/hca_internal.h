@@ -83,6 +83,9 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
 int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
                                void* ws, hipStream_t st, const float* lse = nullptr);
+int32_t launch_attend_weights(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                              const int32_t* count, int32_t k, const int32_t* pos, float sm_scale, const float* lse,
+                              void* w_out, int32_t* vrow_out, float* acc_opt, void* ws, hipStream_t st);
 int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* pcache, const float* lut,
                                   const int32_t* idx, const int32_t* count, int32_t k, float sm_scale, float* y,
                                   float* acc_opt, void* ws, hipStream_t st);

@@ -149,3 +149,37 @@ def test_topp_and_global_weight_arguments(B):
     assert L.hca_score_qkeys_lse(C.byref(s), one, one, n, 0.1, one, None, one, None) == -1
     assert L.hca_score_qkeys_lse(C.byref(s), one, one, n, 0.1, one, one, None, None) == -1               # needs a workspace
     assert L.hca_attend_gathered_global(C.byref(s), one, one, one, one, 8, 0.1, None, one, None, one, None) == -1
+
+
+def test_host_weighted_sum_matches_numpy(B):
+    """The host half of the paper's CPU-GPU split runs without a GPU: weights (fp16) times value rows."""
+    import numpy as np
+    import torch
+    import oracle
+    rng = np.random.default_rng(3)
+    batch, hkv, G, k, vrows = 2, 3, 4, 300, 900
+    R = batch * hkv
+    shape = B.make_shape(batch, hkv * G, hkv, 1000)
+    V = rng.standard_normal((R, vrows, 128)).astype(np.float16)
+    count = rng.integers(0, k + 1, R).astype(np.int32)
+    count[0], count[1] = 0, k
+    idx = np.stack([np.sort(rng.choice(1000, k, replace=False)) for _ in range(R)]).astype(np.int32)
+    pos = np.stack([rng.permutation(1000) % vrows for _ in range(R)]).astype(np.int32)
+    w = rng.random((R * G, k)).astype(np.float32)
+    w /= w.sum(1, keepdims=True)
+    vrow = np.full((R, k), -1, np.int32)
+    w16 = np.zeros((R * G, k), np.float16)
+    for r in range(R):
+        vrow[r, :count[r]] = pos[r, idx[r, :count[r]]]
+        w16[r * G:(r + 1) * G, :count[r]] = w[r * G:(r + 1) * G, :count[r]].astype(np.float16)
+    ref = oracle.weighted_sum_f16(w, idx, count, pos, V)
+    for nt in (1, 5, 16):
+        y = torch.zeros(R * G, 128)
+        B.hca_host_weighted_sum(shape, torch.from_numpy(vrow), torch.from_numpy(count), k, torch.from_numpy(w16),
+                                torch.from_numpy(V), vrows, y, nt)
+        assert np.allclose(y.numpy(), ref, rtol=1e-4, atol=1e-5)
+    bad = vrow.copy()
+    bad[1, 0] = vrows
+    with pytest.raises(B.HcaError):
+        B.hca_host_weighted_sum(shape, torch.from_numpy(bad), torch.from_numpy(count), k, torch.from_numpy(w16),
+                                torch.from_numpy(V), vrows, torch.zeros(R * G, 128), 2)

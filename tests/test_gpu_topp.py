@@ -186,3 +186,63 @@ def test_global_softmax_denominator_and_unrenormalised_weights(B, oracle, bits, 
     if k < n // 3:
         assert ow[live].sum(1).max() < 0.999999        # the weights really are not renormalised
     assert np.allclose(acc.cpu().numpy().reshape(R, cap), oacc, rtol=2e-4, atol=1e-7)
+
+
+@pytest.mark.parametrize("bits,gs,G,n,k,use_lse", [(4, 32, 4, 9000, 512, False), (2, 64, 4, 5000, 300, True), (4, 32, 1, 700, 700, False)])
+def test_paper_split_weights_on_gpu_sum_on_host(B, oracle, bits, gs, G, n, k, use_lse):
+    """hca_attend_weights leaves fp16 weights and value-row numbers in pinned host memory;
+    hca_host_weighted_sum forms y from the host-resident values (the paper's CPU part)."""
+    rng = np.random.default_rng(n + k + bits)
+    batch, hkv = 2, 2
+    R, cap = batch * hkv, n + 8
+    shape = B.make_shape(batch, hkv * G, hkv, cap, bits, gs)
+    keys = rng.standard_normal((batch, hkv, n, 128)).astype(np.float16)
+    vals = rng.standard_normal((batch, hkv, n, 128)).astype(np.float16)
+    q = (1.5 * rng.standard_normal((batch, hkv * G, 128))).astype(np.float16)
+    kc = torch.zeros(B.hca_kcache_bytes(shape), dtype=torch.uint8, device="cuda")
+    B.hca_quantize_keys(shape, kc, torch.from_numpy(keys).cuda(), n, [0] * batch)
+    lens = [n, n - 123]
+    sel = torch.zeros(batch, hkv, cap, device="cuda")
+    lse = torch.zeros(batch, hkv * G, device="cuda")
+    ws = torch.empty(B.hca_workspace_bytes(shape, k, 1), dtype=torch.uint8, device="cuda")
+    qd = torch.from_numpy(q).cuda()
+    sm = 1.0 / np.sqrt(128.0)
+    B.hca_score_qkeys_lse(shape, kc, qd, lens, sm, sel, lse, ws)
+    idx = torch.zeros(batch, hkv, k, dtype=torch.int32, device="cuda")
+    count = torch.zeros(batch, hkv, dtype=torch.int32, device="cuda")
+    permv = rng.permutation(cap).astype(np.int32) % n
+    pos = torch.from_numpy(np.tile(permv, (R, 1)).reshape(batch, hkv, cap)).cuda()
+    acc = torch.zeros(batch, hkv, cap, device="cuda")
+    B.hca_topk(shape, sel, lens, k, idx, count, ws)
+    w16 = torch.zeros(batch, hkv * G, k, dtype=torch.float16).pin_memory()
+    vrow = torch.zeros(batch, hkv, k, dtype=torch.int32).pin_memory()
+    B.hca_attend_weights(shape, kc, qd, idx, count, k, pos, sm, lse if use_lse else None, w16, vrow, acc, ws)
+    torch.cuda.synchronize()
+    vh = torch.from_numpy(vals)
+    y = torch.zeros(batch, hkv * G, 128)
+    B.hca_host_weighted_sum(shape, vrow, count.cpu(), k, w16, vh, n, y, 8)
+
+    oc = oracle.Cache(R, cap, 128, bits, gs)
+    oracle.quantize(oc, keys.reshape(R, n, 128))
+    oc.n[:] = np.repeat(lens, hkv)
+    osel, oz = oracle.score(oc, q.reshape(R * G, 128))
+    olse = oracle.lse(oz, R, oc.n, sm) if use_lse else None
+    oidx, ocount = oracle.topk(osel, oc.n, k)
+    opos = np.tile(permv, (R, 1))
+    oacc = np.zeros((R, cap), np.float32)
+    oy, ow = oracle.attend(oc, q.reshape(R * G, 128), oidx, ocount, opos, vals.reshape(R, n, 128), sm, acc=oacc,
+                           want_w=True, lse=olse)
+    ig = idx.cpu().numpy().reshape(R, k)
+    for r in range(R):
+        assert np.array_equal(ig[r, :ocount[r]], oidx[r, :ocount[r]])
+    vg = vrow.numpy().reshape(R, k)
+    for r in range(R):
+        assert np.array_equal(vg[r, :ocount[r]], opos[r, oidx[r, :ocount[r]]]) and np.all(vg[r, ocount[r]:] == -1)
+    wg = w16.numpy().reshape(R * G, k).astype(np.float32)
+    assert np.allclose(wg, ow.astype(np.float16).astype(np.float32), rtol=2e-3, atol=1e-7)      # within an fp16 ulp
+    ref16 = oracle.weighted_sum_f16(ow, oidx, ocount, opos, vals.reshape(R, n, 128))
+    yg = y.numpy().reshape(R * G, 128)
+    scale = np.maximum(np.abs(oy).max(-1), 1e-30)
+    assert (np.abs(yg - ref16).max(-1) / scale).max() <= 1e-3
+    assert (np.abs(yg - oy).max(-1) / scale).max() <= 2e-3            # against the unrounded weights
+    assert np.allclose(acc.cpu().numpy().reshape(R, cap), oacc, rtol=2e-4, atol=1e-7)
