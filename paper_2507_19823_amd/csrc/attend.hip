@@ -60,13 +60,19 @@ __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__
         const int64_t vr = pos[(int64_t)row * cap + slot];
         const uint4* src = (vr < n_host_rows) ? v_host + ((int64_t)row * host_stride + vr) * 16
                                               : v_hbm + ((int64_t)row * hbm_stride + (vr - n_host_rows)) * 16;
-        v[u] = src[part];
+        // read-once rows, write-once staging: non-temporal both ways, so that neither side displaces or
+        // queues behind what the HBM-bound kernels beside the gather keep in the caches
+        const v4i t4 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(src + part));
+        v[u] = uint4{(uint32_t)t4.x, (uint32_t)t4.y, (uint32_t)t4.z, (uint32_t)t4.w};
       }
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const int64_t i = i0 + u * step;
-      if (i < cnt) vstage[((int64_t)row * k + i) * 16 + part] = v[u];
+      if (i < cnt) {
+        const v4i t4 = {(int)v[u].x, (int)v[u].y, (int)v[u].z, (int)v[u].w};
+        __builtin_nontemporal_store(t4, reinterpret_cast<v4i*>(vstage + ((int64_t)row * k + i) * 16 + part));
+      }
     }
   }
 }
