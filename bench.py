@@ -29,13 +29,14 @@ def log(*a):
 class Model:
     """All layers of one workload: per-layer key cache / acc / pos / host values, shared scratch."""
 
-    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3):
+    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3, evict_spare=False):
         import torch
         from paper_2507_19823_amd import binding as B
         self.torch, self.B, self.w = torch, B, w
         self.L = layers
         self.n0 = w.n
         self.evict_every = evict_every
+        self.evict_spare = evict_spare
         self.cap = w.n + (evict_every if evict_every else total_steps) + 16
         self.vnew = total_steps + 16                  # value rows of appended tokens live in an HBM slice
         self.shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, self.cap, w.bits, w.group)
@@ -182,7 +183,8 @@ class Model:
             pairs = B.hca_scan_stamp_pairs(self.shape, self.cap)
             self.stamps = self.torch.zeros(timing_slots, self.L, pairs, 2, dtype=self.torch.int64, device="cuda")
             d.scan_stamps, d.scan_stamp_pairs = self.stamps.data_ptr(), pairs
-        d.spare_kcache, d.spare_acc, d.spare_pos = (x.data_ptr() for x in self.spare)
+        if self.evict_spare:
+            d.spare_kcache, d.spare_acc, d.spare_pos = (x.data_ptr() for x in self.spare)
         self.pl = B.hca_pipeline_create(self.shape, self.L, d, timing_slots)
         self.pl_layers = (B.hca_layer * self.L)()
         for l in range(self.L):
@@ -733,6 +735,9 @@ def main():
     ap.add_argument("--evict-every", type=int, default=16)
     ap.add_argument("--tune", action="append", default=[], metavar="NAME=VALUE",
                     help="launch-shape knob passed to hca_tune (gather_wgs, gather_unroll, score_bpw, score_depth)")
+    ap.add_argument("--evict-spare", action="store_true",
+                    help="native pipeline: evict out of place into a spare buffer set, in slices behind the attends "
+                         "(default: in place, which moves only the slots from the first dropped one on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sel-buffers", type=int, default=32,
                     help="score buffers of the native step driver (one per layer: the scan never waits for one)")
@@ -817,7 +822,7 @@ def main():
         log(f"selection at 1M: top-k {selection['topk_ms']:.3f} ms, Eq. 4 at tau 0.9 {selection['topp_tau0.9']['ms']:.3f} ms")
 
     total_steps = args.steps + args.warmup
-    model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers))
+    model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers), evict_spare=args.evict_spare)
     layer_v_gib = w.batch * w.n_kv_heads * w.n * 256 / 2 ** 30
     phys = max(1, min(L, int(args.host_gib / layer_v_gib)))
     t0 = time.perf_counter()

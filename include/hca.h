@@ -207,7 +207,9 @@ typedef struct {
   void* ws_topk;                 /* device, hca_workspace_bytes(shape, k, 1); owned by the driver from
                                     hca_pipeline_create on (it keeps a histogram there between steps) */
   void* ws_evict;                /* device, hca_workspace_bytes(shape, k, M); NULL if eviction is never asked for */
-  void* spare_kcache; float* spare_acc; int32_t* spare_pos;   /* spare set for out-of-place eviction, or NULL */
+  void* spare_kcache; float* spare_acc; int32_t* spare_pos;   /* spare set for out-of-place eviction (all three), or all
+                                    NULL: layers are then compacted in place, which moves only the slots at and after
+                                    the first dropped one */
   /* optional profiling of the key scan: device, uint64 [timing_slots][n_layers][scan_stamp_pairs][2];
      every wave of a timed scan launch stores its start and end wall-clock tick there (zero-filled by the
      caller; entries left 0 belong to waves that had nothing to do).  NULL: off. */

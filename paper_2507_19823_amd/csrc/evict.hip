@@ -47,7 +47,7 @@ static void carve(EvictWs* e, void* ws, const Layout& L, int64_t M) {
 // Ordered pass over all resident slots of a row: writes kept[position] = old slot.
 __global__ __launch_bounds__(256) void evict_positions(const float* __restrict__ acc, int64_t stride, int64_t chunk,
                                                        int nchunks, int n_kv_heads, SelRows sr, NRes nr,
-                                                       const uint32_t* __restrict__ state,
+                                                       uint32_t* __restrict__ state,
                                                        const uint32_t* __restrict__ coff, int64_t M,
                                                        int32_t* __restrict__ kept) {
   __shared__ uint32_t wsum[2][4];
@@ -66,6 +66,7 @@ __global__ __launch_bounds__(256) void evict_positions(const float* __restrict__
   const float* v = acc + (int64_t)row * stride;
   int32_t* out = kept + (int64_t)row * M;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint32_t hole = 0xffffffffu;               // lowest slot this thread saw dropped
   for (int64_t s0 = c0; s0 < c1; s0 += 1024) {
     const int64_t j0 = s0 + 4 * threadIdx.x;
     bool fg[4], fe[4];
@@ -95,13 +96,22 @@ __global__ __launch_bounds__(256) void evict_positions(const float* __restrict__
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int64_t j = j0 + i;
-      if (fg[i] || (fe[i] && pe < req)) out[pg + (pe < req ? pe : req)] = (int32_t)j;
+      const bool take = fg[i] || (fe[i] && pe < req);
+      if (take) out[pg + (pe < req ? pe : req)] = (int32_t)j;
+      else if (j < nsel && (uint32_t)j < hole) hole = (uint32_t)j;
       if (j >= nsel && j < n) out[want + (j - nsel)] = (int32_t)j;  // protected newest slots
       pg += fg[i]; pe += fe[i];
     }
     base_g += tot_g; base_e += tot_e;
     __syncthreads();
   }
+  // every slot below the first dropped one keeps its place: the moves can start there
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const uint32_t other = __shfl_xor(hole, o);
+    if (other < hole) hole = other;
+  }
+  if (lane == 0 && hole != 0xffffffffu) atomicMin(&state[4 * row + 2], hole);
 }
 
 // kept[d] -> staging slot d.  One thread per (d, j) 16-byte (4-bit) or 8-byte (2-bit) piece.
@@ -109,13 +119,16 @@ template <int BITS>
 __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __restrict__ kcache,
                                                     const float* __restrict__ acc, const int32_t* __restrict__ pos,
                                                     int n_kv_heads, SelRows sr, int64_t M, int64_t d0, int64_t d1,
-                                                    const int32_t* __restrict__ kept, EvictDst e) {
+                                                    const int32_t* __restrict__ kept, EvictDst e,
+                                                    const uint32_t* __restrict__ first_hole) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t d = d0 + (gid >> 2);
   const int j = (int)(gid & 3);
   if (d >= d1) return;
+  // in place: slots below the block of the first dropped slot already hold their own data
+  if (first_hole != nullptr && d < (int64_t)(first_hole[4 * row + 2] & ~(uint32_t)(L.tpb - 1))) return;
   const int64_t s = kept[(int64_t)row * M + d];
   const uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
   const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
@@ -142,17 +155,20 @@ __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __r
 // staging -> front of the cache (whole blocks; slots past M in the last block are dead).
 __global__ __launch_bounds__(256) void evict_copyback(Layout L, uint8_t* __restrict__ kcache, float* __restrict__ acc,
                                                       int32_t* __restrict__ pos, int n_kv_heads, SelRows sr,
-                                                      int64_t M, int64_t mblk, EvictWs e) {
+                                                      int64_t M, int64_t mblk, EvictWs e,
+                                                      const uint32_t* __restrict__ first_hole) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t d_start = (int64_t)(first_hole[4 * row + 2] & ~(uint32_t)(L.tpb - 1));   // block-aligned
+  const int64_t b_start = d_start / L.tpb;
   uint4* cdst = reinterpret_cast<uint4*>(kcache + (int64_t)row * L.codes_row_bytes());
   uint4* mdst = reinterpret_cast<uint4*>(kcache + L.meta_off + (int64_t)row * L.meta_row_bytes());
   const uint4* csrc = reinterpret_cast<const uint4*>(e.codes + (int64_t)row * mblk * kBlockBytes);
   const uint4* msrc = reinterpret_cast<const uint4*>(e.meta + (int64_t)row * mblk * kMetaBytes);
-  if (gid < mblk * (kBlockBytes / 16)) cdst[gid] = csrc[gid];
-  if (gid < mblk * (kMetaBytes / 16)) mdst[gid] = msrc[gid];
-  if (gid < M) {
+  if (gid >= b_start * (kBlockBytes / 16) && gid < mblk * (kBlockBytes / 16)) cdst[gid] = csrc[gid];
+  if (gid >= b_start * (kMetaBytes / 16) && gid < mblk * (kMetaBytes / 16)) mdst[gid] = msrc[gid];
+  if (gid >= d_start && gid < M) {
     acc[(int64_t)row * L.cap + gid] = e.acc[(int64_t)row * M + gid];
     pos[(int64_t)row * L.cap + gid] = e.pos[(int64_t)row * M + gid];
   }
@@ -188,6 +204,7 @@ struct EvictPlan {
   EvictWs e;
   EvictDst d;
   int32_t* kept;
+  uint32_t* state;   // select state: [4 * row + 2] = lowest dropped slot of the row (after evict_positions)
   int64_t M, mblk;
   bool oop, any;
 };
@@ -238,6 +255,7 @@ static int32_t evict_prepare(const Layout& L, void* kcache, float* acc, int32_t*
   int32_t rc = select_run(p, acc, L.cap, L.rows, L.n_kv_heads, sr, st);
   if (rc != HCA_OK) return rc;
   dim3 g((unsigned)p.nchunks, (unsigned)L.rows);
+  pl->state = p.state;
   evict_positions<<<g, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, pl->kept);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
@@ -248,14 +266,16 @@ static int32_t evict_move(const Layout& L, void* kcache, float* acc, int32_t* po
   if (!pl.any || d1 <= d0) return HCA_OK;
   dim3 gg((unsigned)(((d1 - d0) * 4 + 255) / 256), (unsigned)L.rows);
   if (L.bits == 4)
-    evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, d0, d1, pl.kept, pl.d);
+    evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, d0, d1, pl.kept, pl.d,
+                                        pl.oop ? nullptr : pl.state);
   else
-    evict_gather<2><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, d0, d1, pl.kept, pl.d);
+    evict_gather<2><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, d0, d1, pl.kept, pl.d,
+                                        pl.oop ? nullptr : pl.state);
   if (!pl.oop && d1 == pl.M) {
     int64_t items = pl.mblk * (kBlockBytes / 16);
     if (items < pl.M) items = pl.M;
     dim3 gc((unsigned)((items + 255) / 256), (unsigned)L.rows);
-    evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, pl.mblk, pl.e);
+    evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, pl.mblk, pl.e, pl.state);
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
@@ -277,7 +297,7 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const
                                                        int n_kv_heads, SelRows sr, int64_t M,
                                                        const int32_t* __restrict__ kept, uint8_t* __restrict__ pdst,
                                                        float* __restrict__ adst, int32_t* __restrict__ odst,
-                                                       int64_t dst_row) {
+                                                       int64_t dst_row, const uint32_t* __restrict__ first_hole) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
   const int pieces = g / 16;
@@ -285,6 +305,7 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const
   const int64_t d = gid / pieces;
   const int j = (int)(gid % pieces);
   if (d >= M) return;
+  if (first_hole != nullptr && d < (int64_t)first_hole[4 * row + 2]) return;   // in place: this slot keeps its row
   const int64_t s = kept[(int64_t)row * M + d];
   reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * g)[j] =
       reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * g)[j];
@@ -295,7 +316,9 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const
 // Copies the first cnt[b] slots of every row that `which` selects from (src, row stride ssrc) to (dst, sdst):
 // the copy-back of an in-place eviction (compacted rows, cnt = M) and the carry-over of untouched rows
 // of an out-of-place one (cnt = n).
+// first_hole (in-place copy-back only): slots below the row's lowest dropped slot are left alone.
 __global__ __launch_bounds__(256) void vq_evict_copy_rows(int g, int n_kv_heads, SelRows sr, bool compacted, NRes cnt,
+                                                          const uint32_t* __restrict__ first_hole,
                                                           const uint8_t* __restrict__ psrc, const float* __restrict__ asrc,
                                                           const int32_t* __restrict__ osrc, int64_t ssrc,
                                                           uint8_t* __restrict__ pdst, float* __restrict__ adst,
@@ -306,10 +329,11 @@ __global__ __launch_bounds__(256) void vq_evict_copy_rows(int g, int n_kv_heads,
   const int64_t m = cnt.n[b];
   const int pieces = g / 16;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (gid < m * pieces)
+  const int64_t lo = first_hole != nullptr ? (int64_t)first_hole[4 * row + 2] : 0;
+  if (gid >= lo * pieces && gid < m * pieces)
     reinterpret_cast<uint4*>(pdst + (int64_t)row * sdst * g)[gid] =
         reinterpret_cast<const uint4*>(psrc + (int64_t)row * ssrc * g)[gid];
-  if (gid < m) {
+  if (gid >= lo && gid < m) {
     adst[(int64_t)row * sdst + gid] = asrc[(int64_t)row * ssrc + gid];
     odst[(int64_t)row * sdst + gid] = osrc[(int64_t)row * ssrc + gid];
   }
@@ -336,7 +360,7 @@ int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int
   const int pieces = g / 16;
   if (oop && carry && nmax > 0) {
     dim3 gr((unsigned)((nmax * pieces + 255) / 256), (unsigned)L.rows);
-    vq_evict_copy_rows<<<gr, 256, 0, st>>>(g, L.n_kv_heads, sr, false, nr, pcache, acc, pos, L.cap, pcache_dst, acc_dst,
+    vq_evict_copy_rows<<<gr, 256, 0, st>>>(g, L.n_kv_heads, sr, false, nr, nullptr, pcache, acc, pos, L.cap, pcache_dst, acc_dst,
                                            pos_dst, L.cap);
   }
   if (!any) {
@@ -353,13 +377,14 @@ int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int
   dim3 gg((unsigned)((M * pieces + 255) / 256), (unsigned)L.rows);
   if (oop) {
     vq_evict_gather<<<gg, 256, 0, st>>>(g, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, pcache_dst, acc_dst, pos_dst,
-                                        L.cap);
+                                        L.cap, nullptr);
   } else {
-    vq_evict_gather<<<gg, 256, 0, st>>>(g, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, e.codes, e.acc, e.pos, M);
+    vq_evict_gather<<<gg, 256, 0, st>>>(g, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, e.codes, e.acc, e.pos, M,
+                                        p.state);
     NRes cnt;
     for (int b = 0; b < kMaxBatch; ++b) cnt.n[b] = M;
-    vq_evict_copy_rows<<<gg, 256, 0, st>>>(g, L.n_kv_heads, sr, true, cnt, e.codes, e.acc, e.pos, M, pcache, acc, pos,
-                                           L.cap);
+    vq_evict_copy_rows<<<gg, 256, 0, st>>>(g, L.n_kv_heads, sr, true, cnt, p.state, e.codes, e.acc, e.pos, M, pcache, acc,
+                                           pos, L.cap);
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
@@ -387,6 +412,11 @@ int32_t launch_evict_slice(const Layout& L, void* kcache, float* acc, int32_t* p
     carve(&pl.e, ws, L, M);
     pl.mblk = mblk_of(L, M);
     pl.kept = pl.e.kept;
+    {
+      SelectPlan p;
+      select_plan(&p, pl.e.select, L.rows, nmax);
+      pl.state = p.state;
+    }
     pl.d.codes = (uint8_t*)kcache_dst;             pl.d.codes_row = L.codes_row_bytes();
     pl.d.meta = (uint8_t*)kcache_dst + L.meta_off;  pl.d.meta_row = L.meta_row_bytes();
     pl.d.acc = acc_dst; pl.d.pos = pos_dst; pl.d.ap_row = L.cap;

@@ -98,9 +98,9 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
   for (int l = 0; evict_M != nullptr && l < p->n_layers; ++l) {
     if (evict_M[l] == 0) continue;
     if (evict_M[l] < 1 || evict_M[l] > L.cap || n_protect < 0 || n_protect > evict_M[l]) return HCA_ERR_CAPACITY;
-    if (p->d.ws_evict == nullptr || p->d.spare_kcache == nullptr || p->d.spare_acc == nullptr ||
-        p->d.spare_pos == nullptr)
-      return HCA_ERR_BAD_ARG;
+    if (p->d.ws_evict == nullptr) return HCA_ERR_BAD_ARG;
+    const int spare = (p->d.spare_kcache != nullptr) + (p->d.spare_acc != nullptr) + (p->d.spare_pos != nullptr);
+    if (spare != 0 && spare != 3) return HCA_ERR_BAD_ARG;
   }
   if (timing_slot >= p->timing_slots) return HCA_ERR_BAD_ARG;
   hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk;
@@ -181,7 +181,15 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (M != 0) {
       bool any = false;
       for (int b = 0; b < L.batch; ++b) any = any || nr.n[b] > M;
-      if (any) {
+      if (any && p->d.spare_kcache == nullptr) {
+        // no spare buffers: compact in place behind this attend.  Rows below the first dropped slot keep
+        // their place, so when the dropped tokens sit near the end (the usual case: ties go against the
+        // higher slot) only the select passes and a short tail move are paid
+        rc = launch_evict(L, ly.kcache, ly.acc, ly.pos, nr, nmax, M, n_protect, nullptr, p->d.ws_evict, nullptr, nullptr,
+                          nullptr, sc);
+        if (rc != HCA_OK) return rc;
+        for (int b = 0; b < L.batch; ++b) if (nl[b] > M) nl[b] = M;
+      } else if (any) {
         // one spare set: finish a job still in flight before the next one starts
         while (job.active) {
           rc = advance(job);

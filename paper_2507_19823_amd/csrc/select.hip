@@ -42,6 +42,7 @@ __global__ void sel_init(uint32_t* hist, uint32_t* state, int rows, int n_kv_hea
     const int64_t want = sr.want[i / n_kv_heads];
     state[4 * i + 0] = (want == 0) ? 0xffffffffu : 0u;
     state[4 * i + 1] = want > 0 ? (uint32_t)want : 0u;
+    state[4 * i + 2] = 0xffffffffu;          // lowest slot that is not selected (filled in by the eviction's ordered pass)
   }
 }
 

@@ -357,11 +357,11 @@ def test_kernels_are_deterministic(H):
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("Lr,n_sel", [(3, 3), (5, 3), (5, 5)])
-def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel):
+@pytest.mark.parametrize("Lr,n_sel,spare", [(3, 3, True), (5, 3, True), (5, 5, True), (5, 5, False), (3, 3, False)])
+def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare):
     """hca_pipeline_step over 3 or 5 layers (score buffers shared between layers or one each), 12 decode
-    steps, staggered sliced eviction every 4 steps: every layer's output, resident count and final cache
-    state against the oracle run layer by layer."""
+    steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place): every layer's
+    output, resident count and final cache state against the oracle run layer by layer."""
     import ctypes as C
     from paper_2507_19823_amd import binding as B
     steps, E = 12, 4
@@ -408,7 +408,8 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel):
         d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), c.data_ptr()
     wt, we = torch.zeros(wsb, dtype=torch.uint8, device=dev), torch.zeros(wsb, dtype=torch.uint8, device=dev)
     d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
-    d.spare_kcache, d.spare_acc, d.spare_pos = kc[Lr].data_ptr(), acc[Lr].data_ptr(), pos[Lr].data_ptr()
+    if spare:
+        d.spare_kcache, d.spare_acc, d.spare_pos = kc[Lr].data_ptr(), acc[Lr].data_ptr(), pos[Lr].data_ptr()
     pl = B.hca_pipeline_create(shape, Lr, d, 0)
     layers = (B.hca_layer * Lr)()
     for l in range(Lr):
