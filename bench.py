@@ -84,11 +84,13 @@ class Model:
         tq = 0.0
         for l in range(self.L):
             d = S.make_layer(w, l, device="cuda", want_values=(l < phys_value_layers))
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
+            e0.record()
             B.hca_quantize_keys(self.shape, self.kcache[l], d["keys"], w.n, self.n[l], None, None, None)
+            e1.record()
             torch.cuda.synchronize()
-            tq += time.perf_counter() - t0
+            tq += e0.elapsed_time(e1) * 1e-3          # stream time of the call, not the host's wait for it
             self.n[l] = [w.n] * w.batch
             vh = None
             if l < phys_value_layers:

@@ -67,6 +67,15 @@ def test_quantize_bit_exact_with_ragged_appends(H, oracle, bits, gs):
     keys[0, 1, 5, 1] = -65504.0
     keys[1, 0, 6, :] = 0.0
     keys[1, 0, 6, 7] = 6e-8
+    # tiny ranges: the fp16 scale is subnormal and badly rounded, so unclamped codes would exceed qmax
+    rs = np.random.default_rng(9)
+    for t in range(20, 60):
+        step = rs.integers(1, 40)
+        tiny = (rs.integers(0, step + 1, 128) * 2.0 ** -24 * rs.choice([1, 3, 7])).astype(np.float16)
+        keys[1, 1, t] = torch.from_numpy(tiny * rs.choice([-1.0, 1.0]).astype(np.float16))
+    for t in range(60, 80):                 # exact .5 ties before rounding: codes must round to even
+        base = rs.standard_normal(128).astype(np.float16)
+        keys[0, 1, t] = torch.from_numpy(np.round(base * 4) / 4)
     cap = 1210
     st = _state(H, w, cap=cap)
     oc = _ocache(oracle, w, cap)
