@@ -772,7 +772,9 @@ def main():
         B.hca_tune(name, int(val))
 
     w = S.CONFIGS[args.config]
-    L = args.layers or w.layers
+    # a 32 Ki-token layer (20 MiB of codes) would sit in the last-level cache if it were scanned over and over:
+    # the small workload is run as 16 layers, i.e. 16 cache copies in rotation
+    L = args.layers or (16 if args.config == 2 else w.layers)
     if args.mode == "scan":
         return scan_only(w, args.steps)
     if args.mode == "vq":
