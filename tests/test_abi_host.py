@@ -183,3 +183,17 @@ def test_host_weighted_sum_matches_numpy(B):
     with pytest.raises(B.HcaError):
         B.hca_host_weighted_sum(shape, torch.from_numpy(bad), torch.from_numpy(count), k, torch.from_numpy(w16),
                                 torch.from_numpy(V), vrows, torch.zeros(R * G, 128), 2)
+
+
+def test_header_and_library_from_plain_c(B, tmp_path):
+    """include/hca.h compiles as C11 with gcc (no HIP, no C++), links against libhca.so and its host-side
+    checks run without a GPU."""
+    import subprocess
+    exe = tmp_path / "abi_from_c"
+    libdir = os.path.dirname(B.LIB_PATH)
+    subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c", "abi_from_c.c"), "-o", str(exe), "-L", libdir, "-lhca",
+                    f"-Wl,-rpath,{libdir}"], check=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "abi ok" in r.stdout
