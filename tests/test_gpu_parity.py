@@ -521,3 +521,16 @@ def test_clustered_heavy_hitters_in_one_chunk(H, oracle):
     torch.cuda.synchronize()
     ridx, _ = oracle.topk(v, np.full(4, n), k)
     assert np.array_equal(idx.cpu().numpy(), ridx)
+
+
+def test_decode_step_through_the_c_abi_without_torch(H):
+    """tests/c/decode_step_no_torch.cpp: hipMalloc / hipHostMalloc memory, libhca.so and the oracle's shared
+    object, no Python in the data path (the program is built by __graft_entry__.build())."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = os.path.join(root, "tests", "c", "bin", "decode_step_no_torch")
+    assert os.path.exists(exe), "run __graft_entry__.build() first"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "ok" in r.stdout
