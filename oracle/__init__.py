@@ -255,6 +255,16 @@ def vq_lut(cache, q):
     return T
 
 
+def vq_lut_fx(T):
+    """T [nq, g, c] fp32 -> (Tfx int32 [nq, g, c], sexp int32 [nq]): the tables on their power-of-two grids."""
+    T = np.ascontiguousarray(T, np.float32)
+    nq, g, c = T.shape
+    Tfx = np.zeros((nq, g, c), np.int32)
+    sexp = np.zeros(nq, np.int32)
+    _check(lib().hco_vq_lut_fx(_p(T), C.c_int64(nq), C.c_int(g), C.c_int(c), _p(Tfx), _p(sexp)), "vq_lut_fx")
+    return Tfx, sexp
+
+
 def vq_score(cache, T, want_z=True):
     """T [R*G, g, c] -> (sel [R,cap] fp32, z [R*G,cap] fp32 or None)."""
     T = np.ascontiguousarray(T, np.float32)

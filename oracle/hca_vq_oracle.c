@@ -23,12 +23,19 @@
  *                    index rows (the policy of hco_evict in hca_oracle.c)
  *
  * Indices are 0-based.  Everything that feeds an integer decision is single
- * fp32 operations in one fixed order (compile with -ffp-contract=off, no
- * fast-math):
+ * fp32 operations in one fixed order, or exact integer arithmetic (compile with
+ * -ffp-contract=off, no fast-math):
  *   distance   d = 0; for each channel of the group, ascending: t = x - c;
  *              d = fmaf(t, t, d).  Nearest = smallest d, ties to the lowest index.
  *   table      T = 0; for each channel ascending: T = fmaf(q, c, T).
- *   score      z = T[0, P0]; then z = z + T[i, Pi] for i = 1 .. g-1.
+ *   score      Eq. 3 is a sum of g table entries; the paper fixes neither its
+ *              precision nor its order.  Here the sum itself is exact: the table of
+ *              a query head is first put on one power-of-two grid,
+ *                s = 23 - floor(log2(max |T|))   (0 for an all-zero table),
+ *                Tfx = (int) rintf(ldexpf(T, s))  so that |Tfx| <= 2^24,
+ *              (24 bits for the largest entry, as many as fp32 keeps), then
+ *                z = ldexpf((float)(sum_i Tfx[i, P_i]), -s)
+ *              with the integer sum exact, hence the same in any order.
  * Centroid means, inertia, softmax and the weighted sum accumulate in fp64.
  *
  * Parity status.  Assignment, table and scores are pinned against brute force
@@ -219,32 +226,54 @@ int hco_vq_lut(const uint16_t* q, int64_t R, int G, int D, int g, int c, int n_k
 
 /* --------------------------------------------------------------- score --- */
 
-static float vq_score_one(const float* Thq, const uint16_t* prow, int g, int c) {
-  float z = Thq[prow[0]];
-  for (int i = 1; i < g; ++i) z = z + Thq[(size_t)i * c + prow[i]];
-  return z;
+/* Fixed-point image of the tables of nq query heads: T [nq][g][c] -> Tfx, sexp [nq].
+ * Returns HCO_ERR_NAN when a table holds a NaN or an infinity. */
+int hco_vq_lut_fx(const float* T, int64_t nq, int g, int c, int32_t* Tfx, int32_t* sexp) {
+  if (g < 1 || c < 1) return HCO_ERR_BAD_ARG;
+  const size_t per = (size_t)g * c;
+  for (int64_t hq = 0; hq < nq; ++hq) {
+    const float* t = T + (size_t)hq * per;
+    float amax = 0.0f;
+    for (size_t e = 0; e < per; ++e) {
+      if (isnan(t[e]) || isinf(t[e])) return HCO_ERR_NAN;
+      if (fabsf(t[e]) > amax) amax = fabsf(t[e]);
+    }
+    const int s = amax == 0.0f ? 0 : 23 - ilogbf(amax);
+    sexp[hq] = s;
+    for (size_t e = 0; e < per; ++e) Tfx[(size_t)hq * per + e] = (int32_t)rintf(ldexpf(t[e], s));
+  }
+  return HCO_OK;
+}
+
+static float vq_score_one(const int32_t* Tfx_hq, int s, const uint16_t* prow, int g, int c) {
+  int64_t sum = 0;
+  for (int i = 0; i < g; ++i) sum += Tfx_hq[(size_t)i * c + prow[i]];
+  return ldexpf((float)sum, -s);
 }
 
 /* sel [R][cap] (entries >= n[r] untouched), z_opt [R*G][cap] or NULL. */
 int hco_vq_score(const float* T, const uint16_t* P, int64_t R, int G, int g, int c, int64_t cap,
                  const int64_t* n, float* sel, float* z_opt) {
   if (g < 1 || c < 1 || G < 1 || G > 16) return HCO_ERR_BAD_ARG;
-  int err = 0;
+  int32_t* Tfx = (int32_t*)malloc(sizeof(int32_t) * (size_t)R * G * g * c);
+  int32_t* sexp = (int32_t*)malloc(sizeof(int32_t) * (size_t)R * G);
+  int rc = hco_vq_lut_fx(T, R * G, g, c, Tfx, sexp);
+  if (rc != HCO_OK) { free(Tfx); free(sexp); return rc; }
 #pragma omp parallel for schedule(static)
   for (int64_t r = 0; r < R; ++r) {
     for (int64_t j = 0; j < n[r]; ++j) {
       const uint16_t* prow = P + (r * cap + j) * g;
       float best = -INFINITY;
       for (int h = 0; h < G; ++h) {
-        float z = vq_score_one(T + (size_t)(r * G + h) * g * c, prow, g, c);
-        if (isnan(z)) err = 1;
+        float z = vq_score_one(Tfx + (size_t)(r * G + h) * g * c, sexp[r * G + h], prow, g, c);
         if (z_opt) z_opt[(r * G + h) * cap + j] = z;
         if (z > best) best = z;
       }
       sel[r * cap + j] = best;
     }
   }
-  return err ? HCO_ERR_NAN : HCO_OK;
+  free(Tfx); free(sexp);
+  return HCO_OK;
 }
 
 /* -------------------------------------------------------------- attend --- */
@@ -258,6 +287,10 @@ int hco_vq_attend(const float* T, const uint16_t* P, int64_t R, int G, int D, in
                   const int32_t* pos, const uint16_t* V, int64_t vrows, float sm_scale, float* y,
                   float* w_opt, float* acc_opt) {
   if (!vq_shape_ok(D, g, c) || G < 1 || G > 16) return HCO_ERR_BAD_ARG;
+  int32_t* Tfx = (int32_t*)malloc(sizeof(int32_t) * (size_t)R * G * g * c);
+  int32_t* sexp = (int32_t*)malloc(sizeof(int32_t) * (size_t)R * G);
+  int rc = hco_vq_lut_fx(T, R * G, g, c, Tfx, sexp);
+  if (rc != HCO_OK) { free(Tfx); free(sexp); return rc; }
   int err = 0;
 #pragma omp parallel for schedule(static)
   for (int64_t r = 0; r < R; ++r) {
@@ -270,7 +303,7 @@ int hco_vq_attend(const float* T, const uint16_t* P, int64_t R, int G, int D, in
       float m = -INFINITY;
       for (int i = 0; i < kk; ++i) {
         int64_t j = idx[r * k + i];
-        l[i] = vq_score_one(T + (size_t)hq * g * c, P + (r * cap + j) * g, g, c) * sm_scale;
+        l[i] = vq_score_one(Tfx + (size_t)hq * g * c, sexp[hq], P + (r * cap + j) * g, g, c) * sm_scale;
         if (l[i] > m) m = l[i];
       }
       double Z = 0.0;
@@ -295,6 +328,7 @@ int hco_vq_attend(const float* T, const uint16_t* P, int64_t R, int G, int D, in
       for (int i = 0; i < kk; ++i) acc_opt[r * cap + idx[r * k + i]] += wsum[i];
     free(l); free(a); free(wsum);
   }
+  free(Tfx); free(sexp);
   return err ? HCO_ERR_BAD_ARG : HCO_OK;
 }
 

@@ -109,6 +109,55 @@ def test_table_and_eq3_equal_q_dot_quantised_keys(oracle, g, c, G):
     assert np.all(sel[:, n:] == 0)
 
 
+def test_eq3_sum_is_exact_on_the_tables_grid(oracle):
+    """Eq. 3 as the oracle evaluates it: the sum over the groups is exact on a power-of-two grid that keeps 24 bits
+    of the table's largest entry.  Pins: (a) a table of small integers is summed without any rounding (plain
+    integer arithmetic is the reference); (b) the order of the groups does not matter, bit for bit; (c) against
+    the fp64 sum of the fp32 table the error stays within the grid's half steps plus one final rounding;
+    (d) an all-zero table scores 0 and a table with an infinity or a NaN is refused."""
+    rng = np.random.default_rng(5)
+    R, G, g, c, n = 2, 4, 32, 64, 300
+    vc = oracle.VQCache(R, n, np.zeros((1, g, c, D // g), np.float32))
+    vc.P[:, :n] = rng.integers(0, c, size=(R, n, g)).astype(np.uint16)
+    vc.n[:] = n
+    # (a) integers up to 2^20 in magnitude: 32 of them sum below 2^25, every partial result is an integer
+    Ti = rng.integers(-(1 << 20), 1 << 20, size=(R * G, g, c)).astype(np.float32)
+    _, z = oracle.vq_score(vc, Ti)
+    for hq in range(R * G):
+        ref = Ti[hq].astype(np.int64)[np.arange(g)[None, :], vc.P[hq // G, :n].astype(np.int64)].sum(1)
+        assert np.array_equal(z[hq, :n].astype(np.float64), ref.astype(np.float32).astype(np.float64))
+    # (b) + (c) Gaussian tables with entries over many binades
+    T = (rng.standard_normal((R * G, g, c)) * np.exp2(rng.integers(-12, 3, size=(R * G, g, c)))).astype(np.float32)
+    sel, z = oracle.vq_score(vc, T)
+    perm = rng.permutation(g)
+    vp = oracle.VQCache(R, n, np.zeros((1, g, c, D // g), np.float32))
+    vp.P[:, :n] = vc.P[:, :n][:, :, perm]
+    vp.n[:] = n
+    sel_p, z_p = oracle.vq_score(vp, np.ascontiguousarray(T[:, perm]))
+    assert np.array_equal(z.view(np.uint32), z_p.view(np.uint32))
+    assert np.array_equal(sel.view(np.uint32), sel_p.view(np.uint32))
+    Tfx, sexp = oracle.vq_lut_fx(T)
+    for hq in range(R * G):
+        amax = float(np.abs(T[hq]).max())
+        assert 2.0 ** 23 <= amax * 2.0 ** int(sexp[hq]) < 2.0 ** 24          # 24 bits for the largest entry
+        assert np.abs(Tfx[hq].astype(np.float64) - T[hq].astype(np.float64) * 2.0 ** int(sexp[hq])).max() <= 0.5
+        ref = T[hq].astype(np.float64)[np.arange(g)[None, :], vc.P[hq // G, :n].astype(np.int64)].sum(1)
+        bound = g * 0.5 * 2.0 ** -int(sexp[hq]) + np.abs(ref) * 2.0 ** -23
+        assert np.all(np.abs(z[hq, :n].astype(np.float64) - ref) <= bound)
+    # a table far below the normal range of the sums still resolves its entries
+    Tt = (T * np.float32(2.0 ** -100)).astype(np.float32)
+    _, zt = oracle.vq_score(vc, Tt)
+    assert np.array_equal(zt.astype(np.float64), z.astype(np.float64) * 2.0 ** -100)
+    # (d)
+    sel0, z0 = oracle.vq_score(vc, np.zeros_like(T))
+    assert np.all(z0 == 0) and np.all(sel0 == 0)
+    for bad in (np.inf, -np.inf, np.nan):
+        Tb = T.copy()
+        Tb[3, 5, 7] = bad
+        with pytest.raises(Exception):
+            oracle.vq_score(vc, Tb)
+
+
 def test_codebook_holding_every_subvector_reproduces_eq1(oracle):
     """With one centroid per distinct sub-vector the compressor is the identity, so the scores are the
     exact q . K and selecting every token gives standard attention (Eq. 1)."""
