@@ -331,10 +331,16 @@ int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* vrow, const
  *   distance  d = 0; channels of the group ascending: e = x - c; d = fmaf(e, e, d); nearest = smallest d,
  *             ties to the lowest index
  *   table     t = 0; channels ascending: t = fmaf(q, c, t)
- *   score     z = T[0, P0]; z = z + T[i, Pi] for i = 1 .. g-1; selection score = max over the KV head's
- *             query heads
+ *   score     the sum of Eq. 3 is exact: per query head s = 23 - floor(log2(max |T|)) (0 if T is all zero),
+ *             Tfx = (int) rintf(ldexpf(T, s)), z = ldexpf((float) sum_i Tfx[i, P_i], -s); selection score =
+ *             max over the KV head's query heads.  A table with a NaN or an infinity is an input error
+ *             (not detected).
  * Layouts: centroids fp32 [n_kv_heads, g, c, dbar] (row (b, h) uses the codebook of KV head h);
- * pcache uint8 [batch, n_kv_heads, capacity, g]; lut fp32 [batch, n_kv_heads, g, c, n_q_heads/n_kv_heads]. */
+ * pcache uint8 [batch, n_kv_heads, capacity, g], the g index bytes of a slot in a slot-dependent order:
+ * byte p of slot j holds the index of group 16 * (p / 16) + (p + j) % 16 (hca_vq_export_pcache undoes it);
+ * lut: fp32 T [batch, n_kv_heads, c, g, n_q_heads/n_kv_heads], then fp32 [batch, n_kv_heads, g, 4], the
+ * largest |T| per group and query head, then int32 [batch, n_kv_heads, 4], the exponents s of the row's
+ * query heads. */
 typedef struct {
   int32_t groups;             /* g */
   int32_t codewords;          /* c */
@@ -365,6 +371,12 @@ int32_t hca_vq_train(const void* kval_f16, int64_t n_val, int32_t head_dim, int3
 int32_t hca_vq_assign(const hca_shape* shape, const hca_vq_codebook* cb, void* pcache, const void* k_new_f16,
                       int64_t T, const int64_t* n_resident, float* acc_opt, int32_t* pos_opt,
                       const int64_t* value_row0, void* stream);
+
+/* Test / debug: the index rows in canonical order.
+ *   indices  device, uint8 [batch, n_kv_heads, capacity, g]: indices[.., j, i] = index of group i of slot j,
+ *            slots >= n_resident untouched */
+int32_t hca_vq_export_pcache(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache,
+                             const int64_t* n_resident, uint8_t* indices, void* stream);
 
 /* Builds the table of every query head into `lut` (device, hca_vq_lut_bytes; kept for
  * hca_vq_attend_gathered), then scores every resident token (Eq. 3).

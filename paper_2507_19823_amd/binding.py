@@ -120,6 +120,8 @@ def lib():
         L.hca_vq_assign.argtypes = [sp, cbp, vp, vp, i64, vp, vp, vp, vp, vp]
         L.hca_vq_score.restype = i32
         L.hca_vq_score.argtypes = [sp, cbp, vp, vp, vp, vp, vp, vp, vp]
+        L.hca_vq_export_pcache.restype = i32
+        L.hca_vq_export_pcache.argtypes = [sp, cbp, vp, vp, vp, vp]
         L.hca_vq_evict.restype = i32
         L.hca_vq_evict.argtypes = [sp, cbp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
         L.hca_vq_attend_gathered.restype = i32
@@ -305,6 +307,11 @@ def hca_vq_assign(shape, cb, pcache, k_new, T, n_resident, acc=None, pos=None, v
 def hca_vq_score(shape, cb, pcache, q, n_resident, lut, sel, z=None, stream=None):
     _check(lib().hca_vq_score(C.byref(shape), C.byref(cb), _ptr(pcache), _ptr(q), _nres(n_resident, shape.batch),
                               _ptr(lut), _ptr(sel), _ptr(z), _stream(stream)), "hca_vq_score")
+
+
+def hca_vq_export_pcache(shape, cb, pcache, n_resident, indices, stream=None):
+    _check(lib().hca_vq_export_pcache(C.byref(shape), C.byref(cb), _ptr(pcache), _nres(n_resident, shape.batch),
+                                      _ptr(indices), _stream(stream)), "hca_vq_export_pcache")
 
 
 def hca_vq_attend_gathered(shape, cb, pcache, lut, idx, count, k, sm_scale, y, acc, workspace, stream=None):

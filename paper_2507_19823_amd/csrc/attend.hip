@@ -264,7 +264,8 @@ __device__ __forceinline__ void load_entry(const float* p, float (&e)[G]) {
 }
 
 // Codebook form: the logit of a selected token is the sum over the groups of the table entries
-// its indices select (Eq. 3), in group order.  Thread i of the chunk owns selected token i0 + i.
+// its indices select (Eq. 3), added exactly on the table's power-of-two grid (the exponents that the
+// scan left behind the table in `lut`).  Thread i of the chunk owns selected token i0 + i.
 template <int G>
 __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t cap, const uint8_t* __restrict__ pcache,
                                                          const float* __restrict__ lut, const int32_t* __restrict__ idx,
@@ -286,9 +287,10 @@ __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t c
     const int64_t slot = idx[(int64_t)row * k + i0 + (i < nvalid ? i : nvalid - 1)];
     const uint8_t* pr = pcache + ((int64_t)row * cap + slot) * g;
     const float* T = lut + (int64_t)row * g * c * G;
-    float z[G];
+    const int32_t* sexp = reinterpret_cast<const int32_t*>(lut + (int64_t)gridDim.y * g * (c * G + 4)) + row * 4;
+    int s[G], zi[G];
 #pragma unroll
-    for (int h = 0; h < G; ++h) z[h] = 0.f;
+    for (int h = 0; h < G; ++h) { s[h] = sexp[h]; zi[h] = 0; }
     for (int i16 = 0; i16 < g; i16 += 16) {
       const uint4 pw = *reinterpret_cast<const uint4*>(pr + i16);
       const uint32_t wd[4] = {pw.x, pw.y, pw.z, pw.w};
@@ -296,13 +298,16 @@ __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t c
 #pragma unroll
       for (int b = 0; b < 16; ++b) {            // 16 independent table reads in flight
         const int code = (int)((wd[b >> 2] >> (8 * (b & 3))) & 255u);
-        load_entry<G>(T + ((int64_t)(i16 + b) * c + code) * G, e[b]);
+        load_entry<G>(T + ((int64_t)code * g + vq_group_at(i16 + b, slot)) * G, e[b]);
       }
 #pragma unroll
       for (int b = 0; b < 16; ++b)
 #pragma unroll
-        for (int h = 0; h < G; ++h) z[h] = (i16 + b == 0) ? e[b][h] : z[h] + e[b][h];
+        for (int h = 0; h < G; ++h) zi[h] += vq_fix(e[b][h], s[h]);
     }
+    float z[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) z[h] = ldexpf((float)zi[h], -s[h]);
 #pragma unroll
     for (int h = 0; h < 4; ++h) ps.lg[h][i] = h < G ? z[h < G ? h : 0] * sm_scale : 0.f;
   }

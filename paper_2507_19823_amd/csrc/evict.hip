@@ -290,6 +290,23 @@ int32_t launch_evict(const Layout& L, void* kcache, float* acc, int32_t* pos, co
   return evict_move(L, kcache, acc, pos, pl, 0, M, st);
 }
 
+// out byte p = in byte (p + r) % 16, 0 <= r < 16
+__device__ __forceinline__ uint4 rotate_bytes(uint4 x, int r) {
+  const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+  const int q = r >> 2;
+  uint32_t a[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    a[i] = q == 0 ? w[i] : q == 1 ? w[(i + 1) & 3] : q == 2 ? w[(i + 2) & 3] : w[(i + 3) & 3];
+  const uint32_t t = (uint32_t)(r & 3);
+  uint4 o;
+  o.x = __builtin_amdgcn_alignbyte(a[1], a[0], t);
+  o.y = __builtin_amdgcn_alignbyte(a[2], a[1], t);
+  o.z = __builtin_amdgcn_alignbyte(a[3], a[2], t);
+  o.w = __builtin_amdgcn_alignbyte(a[0], a[3], t);
+  return o;
+}
+
 // ---- codebook caches: the rows that move are index rows of g bytes (g = 32 or 64) ------------
 // kept[d] -> destination slot d; one thread per 16-byte piece of a row.
 __global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const uint8_t* __restrict__ pcache,
@@ -307,8 +324,9 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const
   if (d >= M) return;
   if (first_hole != nullptr && d < (int64_t)first_hole[4 * row + 2]) return;   // in place: this slot keeps its row
   const int64_t s = kept[(int64_t)row * M + d];
+  // the record's rotation follows its slot: byte p of slot d is byte (p + d - s) % 16 of slot s
   reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * g)[j] =
-      reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * g)[j];
+      rotate_bytes(reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * g)[j], (int)((d - s) & 15));
   if (j == 0) adst[(int64_t)row * dst_row + d] = acc[(int64_t)row * cap + s];
   if (j == 1) odst[(int64_t)row * dst_row + d] = pos[(int64_t)row * cap + s];
 }

@@ -49,6 +49,20 @@ __device__ __forceinline__ unsigned short f2h_bits(float x) {
   return __builtin_bit_cast(unsigned short, (_Float16)x);  // v_cvt_f16_f32, round to nearest even
 }
 
+// Codebook form: where the index of group `grp` sits in the stored record of slot `slot`, and back.
+__device__ __forceinline__ int vq_byte_of(int grp, int64_t slot) {
+  return (grp & ~15) | ((grp - (int)slot) & 15);
+}
+__device__ __forceinline__ int vq_group_at(int byte, int64_t slot) {
+  return (byte & ~15) | ((byte + (int)slot) & 15);
+}
+// Power-of-two grid of one query head's table: s = 23 - floor(log2(largest magnitude)) (0 for an all-zero
+// table), entry -> rint(entry * 2^s), at most 2^24 in magnitude, so that 64 of them add up exactly in 32 bits.
+__device__ __forceinline__ int vq_grid_exponent(float amax) {
+  return amax == 0.f ? 0 : 23 - ilogbf(amax);
+}
+__device__ __forceinline__ int vq_fix(float t, int s) { return (int)rintf(ldexpf(t, s)); }
+
 // Order-preserving map float -> uint32 (larger float <=> larger key), -0 treated as +0.
 __device__ __forceinline__ uint32_t order_key(float f) {
   uint32_t u = __float_as_uint(f);

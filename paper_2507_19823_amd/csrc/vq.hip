@@ -1,7 +1,13 @@
 // Codebook form of the key path: grouped vector quantisation (Sec. 3.1) and the table-lookup
 // scores of Sec. 3.2, Eq. 3.  A token is one centroid index per group (a byte: c <= 256), the query
-// becomes a table T[group][centroid][query head of the KV head] that sits in LDS while a workgroup
+// becomes a table T[centroid][group][query head of the KV head] that sits in LDS while a workgroup
 // scans its share of the index matrix.  The host-side trainer is at the end of the file.
+//
+// Index rows are stored rotated: byte p of the record of slot j holds the index of group
+// 16 * (p / 16) + (p + j) % 16  (vq_byte_of / vq_group_at in hca_device.h).  A thread of the scan reads
+// its token's bytes in storage order, so at any moment the 16 lanes that share one pass of a 16-byte
+// LDS read are on 16 different groups, and because a group's entries sit 16 bytes apart within a
+// centroid's 256-byte line those lanes hit 16 different sets of 4 banks whatever their indices are.
 #include <algorithm>
 #include <atomic>
 #include <cmath>
@@ -73,7 +79,9 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
   if (!live) return;
   const int b = row / n_kv_heads;
   const int64_t slot = nr.n[b] + tt;
-  *reinterpret_cast<uint32_t*>(pcache + ((int64_t)row * cap + slot) * g + quad * 4) = packed;
+  uint8_t* rec = pcache + ((int64_t)row * cap + slot) * g;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) rec[vq_byte_of(quad * 4 + u, slot)] = (uint8_t)(packed >> (8 * u));
   if (quad == 0) {
     if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
     if (pos != nullptr) pos[(int64_t)row * cap + slot] = (int32_t)(vrow0.n[b] + tt);
@@ -120,7 +128,7 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
       const int ob = __shfl_xor(best, o);
       if (ob != 0x7fffffff && (best == 0x7fffffff || od < bd || (od == bd && ob < best))) { bd = od; best = ob; }
     }
-    if (lane == 0) pcache[((int64_t)row * cap + slot) * g + i] = (uint8_t)best;
+    if (lane == 0) pcache[((int64_t)row * cap + slot) * g + vq_byte_of(i, slot)] = (uint8_t)best;
   }
   if (threadIdx.x == 0) {
     if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
@@ -129,94 +137,207 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
 }
 
 // -------------------------------------------------------------------------------- table ---
-// T[row][i][cc][h] = qbar_i . C[i][cc] for the G query heads of the row: t = 0; t = fmaf(q, c, t) over
-// the group's channels in ascending order.  grid (g, rows), one thread per centroid.
+// T[row][cc][i][h] = qbar_i . C[i][cc] for the G query heads of the row: t = 0; t = fmaf(q, c, t) over
+// the group's channels in ascending order.  grid (g, rows), one thread per centroid.  The workgroup also
+// leaves the largest magnitude of its group's entries, per head, in amax[row][i][4] for the scan.
 template <int G, int DBAR>
 __global__ __launch_bounds__(256) void vq_lut_kernel(int g, int c, int n_kv_heads, const float* __restrict__ centroids,
-                                                     const uint16_t* __restrict__ q, float* __restrict__ lut) {
+                                                     const uint16_t* __restrict__ q, float* __restrict__ lut,
+                                                     float* __restrict__ amax) {
+  __shared__ float wmax[4][4];
   const int i = blockIdx.x, row = blockIdx.y;
   const int cc = threadIdx.x;
-  if (cc >= c) return;
-  const float* cv = centroids + (((int64_t)(row % n_kv_heads) * g + i) * c + cc) * DBAR;
-  float* out = lut + (((int64_t)row * g + i) * c + cc) * G;
+  float m[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) m[h] = 0.f;
+  if (cc < c) {
+    const float* cv = centroids + (((int64_t)(row % n_kv_heads) * g + i) * c + cc) * DBAR;
+    float* out = lut + (((int64_t)row * c + cc) * g + i) * G;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+      const uint16_t* qh = q + ((int64_t)row * G + h) * kHeadDim + i * DBAR;
+      float t = 0.f;
+#pragma unroll
+      for (int dd = 0; dd < DBAR; ++dd) t = fmaf(h2f(qh[dd]), cv[dd], t);
+      out[h] = t;
+      m[h] = fabsf(t);
+    }
+  }
 #pragma unroll
   for (int h = 0; h < G; ++h) {
-    const uint16_t* qh = q + ((int64_t)row * G + h) * kHeadDim + i * DBAR;
-    float t = 0.f;
 #pragma unroll
-    for (int dd = 0; dd < DBAR; ++dd) t = fmaf(h2f(qh[dd]), cv[dd], t);
-    out[h] = t;
+    for (int o = 32; o >= 1; o >>= 1) m[h] = fmaxf(m[h], __shfl_xor(m[h], o));
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6][h] = m[h];
   }
+  __syncthreads();
+  if (threadIdx.x < G)
+    amax[((int64_t)row * g + i) * 4 + threadIdx.x] = fmaxf(fmaxf(wmax[0][threadIdx.x], wmax[1][threadIdx.x]),
+                                                           fmaxf(wmax[2][threadIdx.x], wmax[3][threadIdx.x]));
 }
 
 // --------------------------------------------------------------------------------- scan ---
 template <int G> struct EntryT;
-template <> struct EntryT<4> { using type = float4; };
-template <> struct EntryT<2> { using type = float2; };
-template <> struct EntryT<1> { using type = float; };
+template <> struct EntryT<4> { using type = float4; using fix = int4; };
+template <> struct EntryT<2> { using type = float2; using fix = int2; };
+template <> struct EntryT<1> { using type = float; using fix = int; };
 
 template <int G>
-__device__ __forceinline__ void entry_add(float (&z)[G], const typename EntryT<G>::type& e, bool first) {
+__device__ __forceinline__ void entry_absmax(float (&m)[G], const typename EntryT<G>::type& e) {
   if constexpr (G == 4) {
-    z[0] = first ? e.x : z[0] + e.x; z[1] = first ? e.y : z[1] + e.y;
-    z[2] = first ? e.z : z[2] + e.z; z[3] = first ? e.w : z[3] + e.w;
+    m[0] = fmaxf(m[0], fabsf(e.x)); m[1] = fmaxf(m[1], fabsf(e.y));
+    m[2] = fmaxf(m[2], fabsf(e.z)); m[3] = fmaxf(m[3], fabsf(e.w));
   } else if constexpr (G == 2) {
-    z[0] = first ? e.x : z[0] + e.x; z[1] = first ? e.y : z[1] + e.y;
+    m[0] = fmaxf(m[0], fabsf(e.x)); m[1] = fmaxf(m[1], fabsf(e.y));
   } else {
-    z[0] = first ? e : z[0] + e;
+    m[0] = fmaxf(m[0], fabsf(e));
+  }
+}
+template <int G>
+__device__ __forceinline__ typename EntryT<G>::fix entry_fix(const typename EntryT<G>::type& e, const int* s) {
+  typename EntryT<G>::fix r;
+  if constexpr (G == 4) {
+    r.x = vq_fix(e.x, s[0]); r.y = vq_fix(e.y, s[1]); r.z = vq_fix(e.z, s[2]); r.w = vq_fix(e.w, s[3]);
+  } else if constexpr (G == 2) {
+    r.x = vq_fix(e.x, s[0]); r.y = vq_fix(e.y, s[1]);
+  } else {
+    r = vq_fix(e, s[0]);
+  }
+  return r;
+}
+template <int G>
+__device__ __forceinline__ void entry_add2(int (&z)[G], const typename EntryT<G>::fix& a,
+                                           const typename EntryT<G>::fix& b) {
+  if constexpr (G == 4) {
+    z[0] = z[0] + a.x + b.x; z[1] = z[1] + a.y + b.y; z[2] = z[2] + a.z + b.z; z[3] = z[3] + a.w + b.w;
+  } else if constexpr (G == 2) {
+    z[0] = z[0] + a.x + b.x; z[1] = z[1] + a.y + b.y;
+  } else {
+    z[0] = z[0] + a + b;
   }
 }
 
-// Eq. 3.  One workgroup of 1024 threads copies the row's table (g * c entries of G floats) into LDS,
-// then each thread scores one token at a time: NG index bytes (two or four 16-byte loads; a wave
-// reads 64 consecutive tokens = 2 or 4 KiB in one piece), NG table reads, the sum in group order.
-// With the largest supported table (128 KiB) one workgroup fits a compute unit, so the launch has
-// about one workgroup per unit and each takes an equal share of the row.
+// Eq. 3.  One workgroup of 1024 threads reduces the per-group maxima to the largest magnitude of each
+// query head's table and copies the row's table (c * g entries of G floats) into LDS on that head's
+// power-of-two grid (24 bits for the largest entry, vq_fix).  Then each thread scores one
+// token at a time: NG index bytes (two or four 16-byte loads; a wave reads 64 consecutive tokens = 2 or
+// 4 KiB in one piece, the next token's bytes are on their way while this one's are looked up), NG table
+// reads, an exact integer sum - so the order of the additions is free and two entries go into one
+// three-operand add - and one conversion back to fp32.  With the largest supported table (128 KiB) one
+// workgroup fits a compute unit, so the launch has about one workgroup per unit and each takes an
+// equal share of the row.  Shares start at multiples of 1024 slots: a thread's tokens all have its own
+// lane number modulo 16, which makes the rotation of the index bytes a per-thread constant.
 template <int G, int NG>
 __global__ __launch_bounds__(1024) void vq_scan_kernel(int c, int64_t cap, const uint8_t* __restrict__ pcache,
-                                                       const float* __restrict__ lut, NRes nr, int n_kv_heads,
+                                                       float* __restrict__ lut, NRes nr, int n_kv_heads,
                                                        int64_t per_wg, float* __restrict__ sel, float* __restrict__ z_out) {
   using E = typename EntryT<G>::type;
+  using F = typename EntryT<G>::fix;
+  constexpr int ES = 4 * G;                              // bytes per table entry
+  constexpr int kAhead = 1;                              // tokens whose index bytes are in flight per thread (deeper: slower)
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  E* tab = reinterpret_cast<E*>(lds_raw);
+  __shared__ int sexp[4];
   const int row = blockIdx.y;
   const int64_t n = nr.n[row / n_kv_heads];
   const int64_t j0 = (int64_t)blockIdx.x * per_wg;
   if (j0 >= n) return;
   int64_t j1 = j0 + per_wg;
   if (j1 > n) j1 = n;
-  {
-    const E* src = reinterpret_cast<const E*>(lut) + (int64_t)row * NG * c;
-    for (int i = threadIdx.x; i < NG * c; i += 1024) tab[i] = src[i];
-  }
-  __syncthreads();
   const uint8_t* prow = pcache + (int64_t)row * cap * NG;
-  for (int64_t j = j0 + threadIdx.x; j < j1; j += 1024) {
-    uint4 pw[NG / 16];
+  int64_t j = j0 + threadIdx.x;
+  uint4 nx[kAhead][NG / 16];                             // the index bytes of this thread's next kAhead tokens
 #pragma unroll
-    for (int v = 0; v < NG / 16; ++v) pw[v] = reinterpret_cast<const uint4*>(prow + j * NG)[v];
-    float z[G];
+  for (int d = 0; d < kAhead; ++d)
+    if (j + 1024 * d < j1) {
 #pragma unroll
-    for (int v = 0; v < NG / 16; ++v) {
-      const uint32_t wd[4] = {pw[v].x, pw[v].y, pw[v].z, pw[v].w};
-      E e[16];
-#pragma unroll
-      for (int b = 0; b < 16; ++b) {
-        const int code = (int)((wd[b >> 2] >> (8 * (b & 3))) & 255u);
-        e[b] = tab[(16 * v + b) * c + code];
-      }
-#pragma unroll
-      for (int b = 0; b < 16; ++b) entry_add<G>(z, e[b], v == 0 && b == 0);
+      for (int v = 0; v < NG / 16; ++v) nx[d][v] = reinterpret_cast<const uint4*>(prow + (j + 1024 * d) * NG)[v];
     }
-    float best = z[0];
+  {
+    // exponents of the heads' grids from the per-group maxima the table kernel left behind the table
+    float* tail = lut + (int64_t)gridDim.y * NG * c * G;
+    if (threadIdx.x < 64) {
+      const float* am = tail + (int64_t)row * NG * 4;
+      const int h = threadIdx.x & 3, part = threadIdx.x >> 2;          // 16 lanes per head
+      float m = 0.f;
+      if (h < G)
+        for (int i = part; i < NG; i += 16) m = fmaxf(m, am[i * 4 + h]);
 #pragma unroll
-    for (int h = 1; h < G; ++h) best = fmaxf(best, z[h]);
-    sel[(int64_t)row * cap + j] = best;
-    if (z_out != nullptr) {
+      for (int o = 32; o >= 4; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+      if (threadIdx.x < G) {
+        const int s = vq_grid_exponent(m);
+        sexp[threadIdx.x] = s;
+        if (blockIdx.x == 0)                             // kept for the attend kernels
+          reinterpret_cast<int32_t*>(tail + (int64_t)gridDim.y * NG * 4)[row * 4 + threadIdx.x] = s;
+      }
+    }
+    __syncthreads();
+    int s[G];
 #pragma unroll
-      for (int h = 0; h < G; ++h) z_out[((int64_t)row * G + h) * cap + j] = z[h];
+    for (int h = 0; h < G; ++h) s[h] = sexp[h];
+    const E* src = reinterpret_cast<const E*>(lut) + (int64_t)row * NG * c;
+    F* tabi = reinterpret_cast<F*>(lds_raw);
+    for (int i = threadIdx.x; i < NG * c; i += 1024) tabi[i] = entry_fix<G>(src[i], s);
+    __syncthreads();
+  }
+  int sx[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) sx[h] = -sexp[h];
+  const uint32_t l16 = threadIdx.x & 15u;
+  uint32_t off[16];
+#pragma unroll
+  for (int b = 0; b < 16; ++b) off[b] = ((b + l16) & 15u) * ES;
+  for (; j < j1; j += 1024 * kAhead) {
+#pragma unroll
+    for (int d = 0; d < kAhead; ++d) {
+      const int64_t jj = j + 1024 * d;
+      if (jj >= j1) break;
+      uint4 pw[NG / 16];
+#pragma unroll
+      for (int v = 0; v < NG / 16; ++v) pw[v] = nx[d][v];
+      if (jj + 1024 * kAhead < j1) {
+#pragma unroll
+        for (int v = 0; v < NG / 16; ++v)
+          nx[d][v] = reinterpret_cast<const uint4*>(prow + (jj + 1024 * kAhead) * NG)[v];
+      }
+      int zi[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) zi[h] = 0;
+#pragma unroll
+      for (int v = 0; v < NG / 16; ++v) {
+        const uint32_t wd[4] = {pw[v].x, pw[v].y, pw[v].z, pw[v].w};
+        F e[16];                                         // sixteen table reads in flight
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+          const uint32_t code = (wd[b >> 2] >> (8 * (b & 3))) & 255u;
+          e[b] = *reinterpret_cast<const F*>(lds_raw + code * (NG * ES) + off[b] + 16 * v * ES);
+        }
+#pragma unroll
+        for (int b = 0; b < 16; b += 2) entry_add2<G>(zi, e[b], e[b + 1]);
+      }
+      float z[G];
+#pragma unroll
+      for (int h = 0; h < G; ++h) z[h] = ldexpf((float)zi[h], sx[h]);
+      float best = z[0];
+#pragma unroll
+      for (int h = 1; h < G; ++h) best = fmaxf(best, z[h]);
+      sel[(int64_t)row * cap + jj] = best;
+      if (z_out != nullptr) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) z_out[((int64_t)row * G + h) * cap + jj] = z[h];
+      }
     }
   }
+}
+
+// Canonical export of the index rows for tests: out[row][slot][group], slots < n_resident.
+__global__ __launch_bounds__(256) void vq_export_kernel(int g, int64_t cap, const uint8_t* __restrict__ pcache, NRes nr,
+                                                        int n_kv_heads, uint8_t* __restrict__ out) {
+  const int row = blockIdx.y;
+  const int64_t n = nr.n[row / n_kv_heads];
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t slot = gid / g;
+  const int i = (int)(gid % g);
+  if (slot >= n) return;
+  out[((int64_t)row * cap + slot) * g + i] = pcache[((int64_t)row * cap + slot) * g + vq_byte_of(i, slot)];
 }
 
 int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, uint8_t* pcache, const void* k_new,
@@ -242,13 +363,13 @@ int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, 
 }
 
 template <int G, int NG>
-static int32_t scan_launch(const Layout& L, int c, const uint8_t* pcache, const float* lut, const NRes& nr,
+static int32_t scan_launch(const Layout& L, int c, const uint8_t* pcache, float* lut, const NRes& nr,
                            int64_t nmax, float* sel, float* z_opt, hipStream_t st) {
   const size_t lds = (size_t)NG * c * G * 4;
   static bool raised = false;                       // per instantiation: tables beyond 64 KiB need the opt-in
   if (lds > 64 * 1024 && !raised) {
     HCA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vq_scan_kernel<G, NG>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));   // + 272 B static
     raised = true;
   }
   // about one workgroup per compute unit, each with at least 1024 tokens, shares a multiple of 1024
@@ -266,7 +387,8 @@ int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, c
                         const NRes& nr, int64_t nmax, float* lut, float* sel, float* z_opt, hipStream_t st) {
   const uint16_t* qq = (const uint16_t*)q;
   dim3 gl((unsigned)g, (unsigned)L.rows);
-#define HCA_LUT(G, D) vq_lut_kernel<G, D><<<gl, 256, 0, st>>>(g, c, L.n_kv_heads, centroids, qq, lut)
+  float* amax = lut + (int64_t)L.rows * g * c * L.gqa;   // [rows][g][4], then the exponents [rows][4]
+#define HCA_LUT(G, D) vq_lut_kernel<G, D><<<gl, 256, 0, st>>>(g, c, L.n_kv_heads, centroids, qq, lut, amax)
   if (g == 32) {
     if (L.gqa == 4) HCA_LUT(4, 4); else if (L.gqa == 2) HCA_LUT(2, 4); else HCA_LUT(1, 4);
   } else {
@@ -370,7 +492,7 @@ size_t hca_vq_pcache_bytes(const hca_shape* shape, const hca_vq_codebook* cb) {
 size_t hca_vq_lut_bytes(const hca_shape* shape, const hca_vq_codebook* cb) {
   Layout L;
   if (vq_layout(shape, cb, &L, false) != HCA_OK) return 0;
-  return (size_t)L.rows * cb->groups * cb->codewords * L.gqa * 4;
+  return (size_t)L.rows * cb->groups * cb->codewords * L.gqa * 4 + (size_t)L.rows * (cb->groups + 1) * 4 * sizeof(int32_t);
 }
 
 int32_t hca_vq_train(const void* kval_f16, int64_t n_val, int32_t head_dim, int32_t groups, int32_t codewords,
@@ -440,6 +562,24 @@ int32_t hca_vq_score(const hca_shape* shape, const hca_vq_codebook* cb, const vo
   if (rc != HCA_OK) return rc;
   return launch_vq_score(L, cb->groups, cb->codewords, cb->centroids, (const uint8_t*)pcache, q_f16, nr, nmax, lut,
                          sel, z_opt, (hipStream_t)stream);
+}
+
+int32_t hca_vq_export_pcache(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache,
+                             const int64_t* n_resident, uint8_t* indices, void* stream) {
+  Layout L;
+  int32_t rc = vq_layout(shape, cb, &L, false);
+  if (rc != HCA_OK) return rc;
+  if (pcache == nullptr || indices == nullptr) return HCA_ERR_BAD_ARG;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  if (nmax == 0) return HCA_OK;
+  dim3 grid((unsigned)((nmax * cb->groups + 255) / 256), (unsigned)L.rows);
+  vq_export_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(cb->groups, L.cap, (const uint8_t*)pcache, nr, L.n_kv_heads,
+                                                          indices);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
 }
 
 int32_t hca_vq_attend_gathered(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache,

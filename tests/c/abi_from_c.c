@@ -41,7 +41,7 @@ int main(void) {
   hca_vq_codebook cb;
   cb.groups = 32; cb.codewords = 256; cb.centroids = NULL;
   CHECK(hca_vq_pcache_bytes(&s, &cb) == (size_t)8 * (1 << 20) * 32);
-  CHECK(hca_vq_lut_bytes(&s, &cb) == (size_t)8 * 32 * 256 * 4 * 4);
+  CHECK(hca_vq_lut_bytes(&s, &cb) == (size_t)8 * 32 * 256 * 4 * 4 + 8 * 33 * 4 * 4);
   CHECK(hca_vq_assign(&s, &cb, p, p, 1, n, NULL, NULL, NULL, NULL) == HCA_ERR_BAD_ARG);   /* no centroids */
 
   /* the host-side trainer runs anywhere: two well separated points per group, two centroids */

@@ -2,6 +2,7 @@
 C11, no GPU needed) and decode_step_no_torch (hipcc, host code that calls libhca.so and the oracle)."""
 import os
 import subprocess
+import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(os.path.dirname(HERE))
@@ -9,6 +10,8 @@ BIN = os.path.join(HERE, "bin")
 
 
 def build():
+    if ROOT not in sys.path:
+        sys.path.insert(0, ROOT)
     from oracle import build as oracle_build
     os.makedirs(BIN, exist_ok=True)
     libdir = os.path.join(ROOT, "paper_2507_19823_amd")

@@ -82,7 +82,7 @@ def test_vq_sizes_and_unsupported_shapes(B):
     s = B.make_shape(2, 32, 8, 1000, bits=7, group=5)          # bits / group are not looked at by hca_vq_*
     cb = B.make_codebook(32, 256)
     assert B.hca_vq_pcache_bytes(s, cb) == 2 * 8 * 1000 * 32
-    assert B.hca_vq_lut_bytes(s, cb) == 2 * 8 * 32 * 256 * 4 * 4
+    assert B.hca_vq_lut_bytes(s, cb) == 2 * 8 * 32 * 256 * 4 * 4 + 2 * 8 * (32 + 1) * 4 * 4   # tables + per-group maxima + grid exponents
     assert B.hca_vq_pcache_bytes(s, B.make_codebook(64, 128)) == 2 * 8 * 1000 * 64
     for g, c in ((16, 256), (32, 257), (64, 256), (32, 0)):     # 64 x 256 x 4 heads is beyond 128 KiB of LDS
         assert B.hca_vq_pcache_bytes(s, B.make_codebook(g, c)) == 0
@@ -103,6 +103,7 @@ def test_vq_bad_arguments_are_rejected_on_the_host(B):
     assert L.hca_vq_score(C.byref(s), C.byref(cb), one, one, n, None, one, None, None) == -1
     assert L.hca_vq_score(C.byref(s), C.byref(B.hca_vq_codebook(48, 256, 256)), one, one, n, one, one, None, None) == -2
     assert L.hca_vq_attend_gathered(C.byref(s), C.byref(cb), one, one, one, one, 0, 1.0, one, None, one, None) == -3
+    assert L.hca_vq_export_pcache(C.byref(s), C.byref(cb), one, n, None, None) == -1
     assert L.hca_vq_train(None, 10, 128, 32, 4, one, 1, 0, one, None) == -1
     assert L.hca_vq_train(one, 10, 128, 48, 4, one, 1, 0, one, None) == -1
 

@@ -119,19 +119,25 @@ def test_vq_one_layer_at_full_size(oracle):
     P = torch.zeros(B.hca_vq_pcache_bytes(shape, cb), dtype=torch.uint8, device="cuda")
     B.hca_vq_assign(shape, cb, P, keys, n, [0])
     torch.cuda.synchronize()
-    Pg = P.view(R, cap, g)
+    Pg = torch.zeros(R, cap, g, dtype=torch.uint8, device="cuda")          # canonical order, by the library's export
+    B.hca_vq_export_pcache(shape, cb, P, [n], Pg)
+    torch.cuda.synchronize()
     # sample: the first and last 1100 tokens and 6000 random ones per row
     pick = np.unique(np.concatenate([np.arange(1100), np.arange(n - 1100, n), rng.integers(0, n, 6000)]))
     oc = oracle.VQCache(R, len(pick), cen)
     oracle.vq_assign(oc, keys.view(R, n, 128)[:, torch.from_numpy(pick).cuda()].cpu().numpy())
     assert np.array_equal(Pg[:, torch.from_numpy(pick).cuda()].cpu().numpy(), oc.P.astype(np.uint8)), "indices differ"
-    assert int(Pg[:, n:].max()) == 0
-    del oc
+    assert int(P.view(R, cap, g)[:, n:].max()) == 0
+    del oc, Pg
 
     # scores / top-k / attend on a drawn index matrix (zipf-like code popularity, as trained codebooks show)
     pop = rng.permutation(c)
     Pr = pop[np.minimum((rng.pareto(1.2, (R, n, g)) * 8).astype(np.int64), c - 1)].astype(np.uint8)
-    Pg[:, :n] = torch.from_numpy(Pr).cuda()
+    # stored order (documented in include/hca.h): byte p of slot j holds the index of group 16*(p//16) + (p+j)%16
+    pp, jj = np.arange(g)[None, :], np.arange(n)[:, None]
+    where = (pp & ~15) | ((pp + jj) & 15)
+    P.view(R, cap, g)[:, :n] = torch.from_numpy(np.take_along_axis(Pr, np.broadcast_to(where[None], Pr.shape), axis=2)).cuda()
+    del where
     oc = oracle.VQCache(R, cap, cen)
     oc.P[:, :n] = Pr
     oc.n[:] = n

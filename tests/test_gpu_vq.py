@@ -55,8 +55,20 @@ class _State:
                              self.n if row0 is None else row0)
         self.n = [x + T for x in self.n]
 
-    def P_rows(self):
-        return self.P.cpu().numpy().reshape(self.batch * self.hkv, self.cap, self.g)
+    def P_rows(self, P=None, n=None):
+        """Index rows in canonical order [R, cap, g] (the library stores a slot's bytes rotated by its slot number);
+        slots at or beyond n read 0xEE."""
+        out = torch.full((self.batch * self.hkv, self.cap, self.g), 0xEE, dtype=torch.uint8, device="cuda")
+        self.B.hca_vq_export_pcache(self.shape, self.cb, self.P if P is None else P, self.n if n is None else n, out)
+        return out.cpu().numpy()
+
+    def table(self):
+        """(T fp32 [R*G, g, c], exponents int32 [R*G]) from the library's lut buffer."""
+        R, G = self.batch * self.hkv, self.hq // self.hkv
+        flat = self.lut.cpu().numpy()
+        T = flat[:R * self.c * self.g * G].reshape(R, self.c, self.g, G).transpose(0, 3, 2, 1).reshape(R * G, self.g, self.c)
+        sexp = flat[R * self.g * (self.c * G + 4):].view(np.int32).reshape(R, 4)[:, :G].reshape(R * G)
+        return np.ascontiguousarray(T), sexp
 
 
 @pytest.mark.parametrize("g,c,G,hkv,batch", [(32, 256, 4, 2, 2), (64, 128, 4, 2, 1), (32, 17, 2, 3, 1), (64, 256, 1, 2, 2),
@@ -81,7 +93,8 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
     oracle.vq_assign(oc, keys.reshape(R, n, D)[:, :n_used])
     Pg = st.P_rows()
     assert np.array_equal(Pg[:, :n_used], oc.P[:, :n_used].astype(np.uint8))
-    assert np.all(Pg[:, n_used:] == 0xEE)                                   # nothing written past n
+    assert np.all(Pg[:, n_used:] == 0xEE)
+    assert np.all(st.P.cpu().numpy().reshape(R, cap, g)[:, n_used:] == 0xEE)  # nothing written past n
     assert np.array_equal(st.pos.cpu().numpy().reshape(R, cap)[:, :n_used], np.tile(np.arange(n_used), (R, 1)))
     assert np.all(st.acc.cpu().numpy().reshape(R, cap)[:, :n_used] == 0) and np.all(st.acc.cpu().numpy().reshape(R, cap)[:, n_used:] == 9)
 
@@ -89,8 +102,9 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
     B.hca_vq_score(st.shape, st.cb, st.P, torch.from_numpy(q).cuda(), st.n, st.lut, st.sel, st.z)
     torch.cuda.synchronize()
     T = oracle.vq_lut(oc, q.reshape(R * G, D))
-    lut = st.lut.cpu().numpy().reshape(R, g, c, G)
-    assert np.array_equal(lut.transpose(0, 3, 1, 2).reshape(R * G, g, c).view(np.uint32), T.view(np.uint32))
+    Tg, sg_exp = st.table()
+    assert np.array_equal(Tg.view(np.uint32), T.view(np.uint32))
+    assert np.array_equal(sg_exp, oracle.vq_lut_fx(T)[1])
     sel, z = oracle.vq_score(oc, T)
     zg = st.z.cpu().numpy().reshape(R * G, cap)
     sg = st.sel.cpu().numpy().reshape(R, cap)
@@ -208,7 +222,7 @@ def test_vq_evict_matches_oracle(B, oracle, mode, g, n, M, Rp):
         Pout, aout, pout = st.P, accd, posd
     torch.cuda.synchronize()
     okept = oracle.vq_evict(oc, acc, pos, M, Rp)
-    Pg = Pout.cpu().numpy().reshape(R, cap, g)
+    Pg = st.P_rows(Pout, [min(x, M) for x in lens])
     ag, pg = aout.cpu().numpy().reshape(R, cap), pout.cpu().numpy().reshape(R, cap)
     kg = kept.cpu().numpy().reshape(R, M)
     for r in range(R):
