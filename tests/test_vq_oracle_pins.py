@@ -144,6 +144,12 @@ def test_eq3_sum_is_exact_on_the_tables_grid(oracle):
         ref = T[hq].astype(np.float64)[np.arange(g)[None, :], vc.P[hq // G, :n].astype(np.int64)].sum(1)
         bound = g * 0.5 * 2.0 ** -int(sexp[hq]) + np.abs(ref) * 2.0 ** -23
         assert np.all(np.abs(z[hq, :n].astype(np.float64) - ref) <= bound)
+    # the grid follows the largest magnitude, whatever its sign: negating the table negates every score exactly
+    Ta = np.abs(T)
+    _, za = oracle.vq_score(vc, Ta)
+    _, zn = oracle.vq_score(vc, -Ta)
+    assert np.array_equal(zn.view(np.uint32), (-za).view(np.uint32))
+    assert np.array_equal(oracle.vq_lut_fx(-Ta)[1], oracle.vq_lut_fx(Ta)[1])
     # a table far below the normal range of the sums still resolves its entries
     Tt = (T * np.float32(2.0 ** -100)).astype(np.float32)
     _, zt = oracle.vq_score(vc, Tt)
