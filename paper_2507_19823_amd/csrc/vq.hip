@@ -366,12 +366,9 @@ template <int G, int NG>
 static int32_t scan_launch(const Layout& L, int c, const uint8_t* pcache, float* lut, const NRes& nr,
                            int64_t nmax, float* sel, float* z_opt, hipStream_t st) {
   const size_t lds = (size_t)NG * c * G * 4;
-  static bool raised = false;                       // per instantiation: tables beyond 64 KiB need the opt-in
-  if (lds > 64 * 1024 && !raised) {
+  if (lds > 64 * 1024)                              // tables beyond 64 KiB need the opt-in (per device; the call is cheap)
     HCA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vq_scan_kernel<G, NG>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));   // + 272 B static
-    raised = true;
-  }
   // about one workgroup per compute unit, each with at least 1024 tokens, shares a multiple of 1024
   int64_t per_row = 256 / L.rows;
   if (per_row < 1) per_row = 1;
