@@ -508,18 +508,19 @@ def selection_probe(w, iters=10):
     return out
 
 
-def paper_form_probe(w, layers=8, steps=6, g=32, c=256, tau=0.9):
+def paper_form_probe(w, streams, layers=8, steps=6, g=32, c=256, tau=0.9):
     """Decode steps in the paper's own form on `layers` layers of the workload: codebook key cache (Sec. 3.1),
     table-lookup scores (Eq. 3), cumulative-weight selection (Eq. 4, cut at the workload's k), gather of the
-    selected value rows from pinned host memory, softmax-weighted sum.  One stream, calls in order; the
-    time per layer is what a layer costs when nothing overlaps.  With the synthetic planted queries the
+    selected value rows from pinned host memory, softmax-weighted sum.  First on one stream, calls in order:
+    the time per layer is what a layer costs when nothing overlaps.  Then the same steps through the library's
+    step driver (four stages on `streams`, layers overlapping).  With the synthetic planted queries the
     selection keeps only a few tokens per head (the count is reported), so the gather is short here."""
     import numpy as np
     import torch
     import synth_inputs as S
     from paper_2507_19823_amd import binding as B
     G = w.n_q_heads // w.n_kv_heads
-    cap = w.n + steps + 16
+    cap = w.n + 2 * steps + 16
     shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
     rng = np.random.default_rng(1000 * w.config + 11)
     P, cens, cbs, vh, pos, acc, qs, kn = [], [], [], [], [], [], [], []
@@ -539,7 +540,7 @@ def paper_form_probe(w, layers=8, steps=6, g=32, c=256, tau=0.9):
         v = torch.empty(w.batch, w.n_kv_heads, w.n, 128, dtype=torch.float16, pin_memory=True)
         v.copy_(d["values"])
         vh.append(v)
-        st = [S.make_step(w, l, t) for t in range(steps)]
+        st = [S.make_step(w, l, t) for t in range(2 * steps)]
         kn.append([x[0].cuda() for x in st])
         qs.append([x[2].cuda() for x in st])
         del d
@@ -548,7 +549,7 @@ def paper_form_probe(w, layers=8, steps=6, g=32, c=256, tau=0.9):
     idx = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device="cuda")
     count = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
     y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
-    vnew = torch.zeros(w.batch, w.n_kv_heads, steps, 128, dtype=torch.float16, device="cuda")
+    vnew = torch.zeros(w.batch, w.n_kv_heads, 2 * steps, 128, dtype=torch.float16, device="cuda")
     ws = torch.empty(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
     sm = 1.0 / (128.0 ** 0.5)
     kept = []
@@ -560,7 +561,7 @@ def paper_form_probe(w, layers=8, steps=6, g=32, c=256, tau=0.9):
             n1 = [x + 1 for x in n]
             B.hca_vq_score(shape, cbs[l], P[l], qs[l][t], n1, lut, sel)
             B.hca_topp(shape, sel, n1, sm, tau, w.k, idx, count, None, ws)
-            B.hca_gather_values(shape, idx, count, w.k, pos[l], vh[l], w.n, w.n, vnew, steps, ws)
+            B.hca_gather_values(shape, idx, count, w.k, pos[l], vh[l], w.n, w.n, vnew, 2 * steps, ws)
             B.hca_vq_attend_gathered(shape, cbs[l], P[l], lut, idx, count, w.k, sm, y, acc[l], ws)
 
     step(0)
@@ -576,7 +577,51 @@ def paper_form_probe(w, layers=8, steps=6, g=32, c=256, tau=0.9):
     out = {"workload": w.name, "layers": layers, "groups": g, "codewords": c, "tau": tau, "k_cut": w.k,
            "ms_per_layer": ms / layers, "context_tokens_scored_per_s": w.batch * w.n * layers / ms * 1e3,
            "selected_per_kv_head_last_layer": kept}
-    del P, vh, lut, sel
+    # the same form through the step driver: steps `steps` .. 2 * steps - 1 on the caches as they stand
+    import ctypes as C
+    d = B.hca_pipeline_desc()
+    d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (x.cuda_stream for x in streams)
+    sels = [torch.empty(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda") for _ in range(layers)]
+    luts = [torch.empty(B.hca_vq_lut_bytes(shape, cbs[0]) // 4, dtype=torch.float32, device="cuda") for _ in range(layers)]
+    ys = torch.zeros(layers, w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
+    keep = []
+    for i, t_ in enumerate(sels):
+        d.sel[i] = t_.data_ptr()
+    d.n_sel = layers
+    for i in range(4):
+        a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device="cuda")
+        b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
+        cws = torch.empty(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+        keep += [a, b, cws]
+        d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), cws.data_ptr()
+    wt = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+    d.ws_topk = wt.data_ptr()
+    d.vq_groups, d.vq_codewords, d.topp_tau = g, c, tau
+    pl = B.hca_pipeline_create(shape, layers, d, 0)
+    ly = (B.hca_layer * layers)()
+    for l in range(layers):
+        ly[l].kcache, ly[l].acc, ly[l].pos = P[l].data_ptr(), acc[l].data_ptr(), pos[l].data_ptr()
+        ly[l].v_host, ly[l].v_hbm, ly[l].y = vh[l].data_ptr(), vnew.data_ptr(), ys[l].data_ptr()
+        ly[l].vq_centroids, ly[l].vq_lut = cens[l].data_ptr(), luts[l].data_ptr()
+    nres = (C.c_int64 * (layers * w.batch))(*([w.n + steps] * (layers * w.batch)))
+
+    def driver_step(t):
+        for l in range(layers):
+            ly[l].k_new, ly[l].q = kn[l][t].data_ptr(), qs[l][t].data_ptr()
+        B.hca_pipeline_step(pl, ly, nres, w.n + t, w.k, w.n, w.n, 2 * steps, sm, None, 0, -1)
+
+    torch.cuda.synchronize()
+    driver_step(steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps + 1, 2 * steps):
+        driver_step(t)
+    torch.cuda.synchronize()
+    ms_p = (time.perf_counter() - t0) * 1e3 / (steps - 1)
+    out["pipelined_ms_per_layer"] = ms_p / layers
+    out["pipelined_context_tokens_scored_per_s"] = w.batch * w.n * layers / ms_p * 1e3
+    B.hca_pipeline_destroy(pl)
+    del P, vh, lut, sel, sels, luts, keep, wt
     torch.cuda.synchronize()
     torch.cuda.empty_cache()
     torch._C._host_emptyCache()
@@ -817,8 +862,9 @@ def main():
     if not args.no_latency:
         codebook = vq_probe(S.CONFIGS[4], 10)
         log(f"codebook key path at 1M: table + lookup scan {codebook['score_ms']:.3f} ms per layer")
-        paper_form = paper_form_probe(S.CONFIGS[4])
-        log(f"paper-form decode step at 1M: {paper_form['ms_per_layer']:.3f} ms per layer")
+        paper_form = paper_form_probe(S.CONFIGS[4], (main_s[0], extra[0], gath_s[0], extra[1]))
+        log(f"paper-form decode step at 1M: {paper_form['ms_per_layer']:.3f} ms per layer on one stream, "
+            f"{paper_form['pipelined_ms_per_layer']:.3f} ms through the step driver")
         cpu_split = cpu_split_probe(S.CONFIGS[4])
         log(f"value side at 1M, k 4096: gather + attend {cpu_split['gather_plus_attend_ms']:.3f} ms; paper's split "
             f"{cpu_split['split_gpu_weights_ms']:.3f} ms on the GPU + {cpu_split['split_host_sum_ms']:.3f} ms on the host")

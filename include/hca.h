@@ -193,6 +193,11 @@ typedef struct {
   const void* v_host;                       /* pinned value store (rows < n_host_rows) or NULL */
   const void* v_hbm;                        /* device value slice (rows >= n_host_rows) or NULL */
   float* y;                                 /* device, fp32 [batch, n_q_heads, head_dim] */
+  /* codebook form only (hca_pipeline_desc.vq_groups > 0): kcache is then the layer's index cache
+     (hca_vq_pcache_bytes) */
+  const float* vq_centroids;                /* device, the layer's codebook, fp32 [n_kv_heads, g, c, dbar] */
+  float* vq_lut;                            /* device, hca_vq_lut_bytes: the layer's table, written by the scan
+                                               stage and read by its attend */
 } hca_layer;
 
 #define HCA_PIPELINE_MAX_SEL 64
@@ -216,6 +221,13 @@ typedef struct {
   void* scan_stamps; int64_t scan_stamp_pairs;
   int32_t timing_layer_stride;   /* HIP-event brackets only around the scan of layers l % stride == 0 (0, 1: all);
                                     each bracket costs two more packets on the scan stream */
+  /* The paper's own form of the step (Sec. 3.1, 3.2).  vq_groups > 0: the key side is the codebook form -
+     hca_vq_assign, hca_vq_score, hca_vq_attend_gathered, hca_vq_evict (in place: the spare_* fields must be
+     NULL) instead of their uniform-code counterparts, with the codebook shape given here and each layer's
+     centroids and table in its hca_layer.  topp_tau > 0: the selection is Eq. 4 (hca_topp with this tau and the
+     step's k as the cut-off) instead of top-k.  The two are independent. */
+  int32_t vq_groups, vq_codewords;
+  double topp_tau;
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;

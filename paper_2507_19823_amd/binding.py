@@ -31,7 +31,8 @@ class hca_shape(C.Structure):
 
 class hca_layer(C.Structure):
     _fields_ = [("kcache", C.c_void_p), ("acc", C.c_void_p), ("pos", C.c_void_p), ("k_new", C.c_void_p),
-                ("q", C.c_void_p), ("v_host", C.c_void_p), ("v_hbm", C.c_void_p), ("y", C.c_void_p)]
+                ("q", C.c_void_p), ("v_host", C.c_void_p), ("v_hbm", C.c_void_p), ("y", C.c_void_p),
+                ("vq_centroids", C.c_void_p), ("vq_lut", C.c_void_p)]
 
 
 PIPELINE_MAX_SEL = 64
@@ -44,7 +45,8 @@ class hca_pipeline_desc(C.Structure):
                 ("count", C.c_void_p * 4), ("ws_attend", C.c_void_p * 4), ("ws_topk", C.c_void_p),
                 ("ws_evict", C.c_void_p), ("spare_kcache", C.c_void_p), ("spare_acc", C.c_void_p),
                 ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64),
-                ("timing_layer_stride", C.c_int32)]
+                ("timing_layer_stride", C.c_int32), ("vq_groups", C.c_int32), ("vq_codewords", C.c_int32),
+                ("topp_tau", C.c_double)]
 
 
 class hca_vq_codebook(C.Structure):

@@ -42,6 +42,13 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   for (int i = 0; i < 4; ++i)
     if (desc->idx[i] == nullptr || desc->count[i] == nullptr || desc->ws_attend[i] == nullptr) return nullptr;
   if (desc->ws_topk == nullptr) return nullptr;
+  if (desc->vq_groups != 0) {                // codebook form: same limits as the hca_vq_* calls; eviction in place
+    if (desc->vq_groups != 32 && desc->vq_groups != 64) return nullptr;
+    if (desc->vq_codewords < 1 || desc->vq_codewords > 256) return nullptr;
+    if ((int64_t)desc->vq_groups * desc->vq_codewords * L.gqa > 32768) return nullptr;
+    if (desc->spare_kcache != nullptr || desc->spare_acc != nullptr || desc->spare_pos != nullptr) return nullptr;
+  }
+  if (!(desc->topp_tau >= 0.0)) return nullptr;
   hca_pipeline* p = new hca_pipeline();
   p->L = L;
   p->n_layers = n_layers;
@@ -103,6 +110,8 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (spare != 0 && spare != 3) return HCA_ERR_BAD_ARG;
   }
   if (timing_slot >= p->timing_slots) return HCA_ERR_BAD_ARG;
+  const int vg = p->d.vq_groups, vc = p->d.vq_codewords;
+  const bool vq = vg > 0;
   hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk;
   hipStream_t sg = (hipStream_t)p->d.stream_gather, sc = (hipStream_t)p->d.stream_attend;
   NRes vrow0;
@@ -130,6 +139,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (ly.kcache == nullptr || ly.acc == nullptr || ly.pos == nullptr || ly.k_new == nullptr || ly.q == nullptr ||
         ly.y == nullptr)
       return HCA_ERR_BAD_ARG;
+    if (vq && (ly.vq_centroids == nullptr || ly.vq_lut == nullptr)) return HCA_ERR_BAD_ARG;
     NRes nr;
     int64_t nmax;
     int32_t rc = load_nres(L, nl, &nr, &nmax);
@@ -143,24 +153,30 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     // previous step, which layer_done covers)
     if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[s3], 0));
     HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l], 0));    // this layer's attend / evict of the previous step
-    rc = launch_quantize(L, ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa);
+    rc = vq ? launch_vq_assign(L, vg, vc, ly.vq_centroids, (uint8_t*)ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa)
+            : launch_quantize(L, ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa);
     if (rc != HCA_OK) return rc;
     for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
     nmax += 1;
     if (timed) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
     uint64_t* stamps = nullptr;
-    if (timing_slot >= 0 && p->d.scan_stamps != nullptr) {
+    if (!vq && timing_slot >= 0 && p->d.scan_stamps != nullptr) {
       if (p->d.scan_stamp_pairs < score_stamp_pairs(L, nmax)) return HCA_ERR_CAPACITY;
       stamps = (uint64_t*)p->d.scan_stamps + ((int64_t)timing_slot * p->n_layers + l) * p->d.scan_stamp_pairs * 2;
     }
-    rc = launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps);
+    rc = vq ? launch_vq_score(L, vg, vc, ly.vq_centroids, (const uint8_t*)ly.kcache, ly.q, nr, nmax, ly.vq_lut,
+                              p->d.sel[s3], nullptr, sa)
+            : launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps);
     if (rc != HCA_OK) return rc;
     if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
     HCA_HIP(hipEventRecord(p->score_done[s3], sa));
     // stage 2: top-k
     HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
     HCA_HIP(hipStreamWaitEvent(sb, p->pipe_free[s4], 0));    // attend of the previous user of idx / staging
-    rc = launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb, true);
+    rc = p->d.topp_tau > 0.0
+             ? launch_topp(L, p->d.sel[s3], nr, nmax, sm_scale, p->d.topp_tau, k, p->d.idx[s4], p->d.count[s4], nullptr,
+                           p->d.ws_topk, sb)
+             : launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb, true);
     if (rc != HCA_OK) return rc;
     if (p->sel_waits) HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
     HCA_HIP(hipEventRecord(p->topk_done[s4], sb));
@@ -172,8 +188,10 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     HCA_HIP(hipEventRecord(p->gather_done[s4], sg));
     // stage 4: attend (+ eviction into the spare buffers, which then swap with the layer's)
     HCA_HIP(hipStreamWaitEvent(sc, p->gather_done[s4], 0));
-    rc = launch_attend_gathered(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, sm_scale, ly.y, ly.acc,
-                                p->d.ws_attend[s4], sc);
+    rc = vq ? launch_vq_attend_gathered(L, vg, vc, (const uint8_t*)ly.kcache, ly.vq_lut, p->d.idx[s4], p->d.count[s4], k,
+                                        sm_scale, ly.y, ly.acc, p->d.ws_attend[s4], sc)
+            : launch_attend_gathered(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, sm_scale, ly.y, ly.acc,
+                                     p->d.ws_attend[s4], sc);
     if (rc != HCA_OK) return rc;
     const int64_t M = evict_M != nullptr ? evict_M[l] : 0;
     HCA_HIP(hipEventRecord(p->pipe_free[s4], sc));
@@ -185,8 +203,10 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
         // no spare buffers: compact in place behind this attend.  Rows below the first dropped slot keep
         // their place, so when the dropped tokens sit near the end (the usual case: ties go against the
         // higher slot) only the select passes and a short tail move are paid
-        rc = launch_evict(L, ly.kcache, ly.acc, ly.pos, nr, nmax, M, n_protect, nullptr, p->d.ws_evict, nullptr, nullptr,
-                          nullptr, sc);
+        rc = vq ? launch_vq_evict(L, vg, (uint8_t*)ly.kcache, ly.acc, ly.pos, nr, nmax, M, n_protect, nullptr,
+                                  p->d.ws_evict, nullptr, nullptr, nullptr, sc)
+                : launch_evict(L, ly.kcache, ly.acc, ly.pos, nr, nmax, M, n_protect, nullptr, p->d.ws_evict, nullptr,
+                               nullptr, nullptr, sc);
         if (rc != HCA_OK) return rc;
         for (int b = 0; b < L.batch; ++b) if (nl[b] > M) nl[b] = M;
       } else if (any) {

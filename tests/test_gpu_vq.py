@@ -300,3 +300,115 @@ def test_vq_decode_loop_with_appends_topp_and_eviction(B, oracle):
             assert np.array_equal(st.pos.cpu().numpy().reshape(R, cap)[:, :m], pos[:, :m])
             assert np.array_equal(st.acc.cpu().numpy().reshape(R, cap)[:, :m], acc[:, :m])
     assert len(counts_seen) > 1
+
+
+@pytest.mark.parametrize("tau,Lr,n_sel", [(0.0, 3, 3), (0.9, 3, 3), (0.9, 5, 3), (0.97, 4, 4)])
+def test_native_step_driver_in_the_papers_form(B, oracle, tau, Lr, n_sel):
+    """hca_pipeline_step with a codebook cache per layer (and Eq. 4 selection when tau > 0) over 3 to 5 layers,
+    12 decode steps, staggered in-place eviction every 4 steps: every layer's output, resident count and final
+    index rows / pos / acc against the oracle run layer by layer."""
+    import ctypes as C
+    import math
+    import synth_inputs as S
+    steps, E = 12, 4
+    w = S.Workload("vqdrv", 9, 2, 8, 2, 1500, 4, 32, 96)
+    batch, hkv, G, g, c = w.batch, w.n_kv_heads, w.gqa, 32, 64
+    R, n0 = batch * hkv, w.n
+    cap, vnew = n0 + E + 16, steps + 4
+    shape = B.make_shape(batch, w.n_q_heads, hkv, cap)
+    rng = np.random.default_rng(77)
+    data = [S.make_layer(w, l) for l in range(Lr)]
+    cens = [_codebook(oracle, rng, data[l]["keys"].numpy(), hkv, g, c, iters=1) for l in range(Lr)]
+    cend = [torch.from_numpy(x).cuda() for x in cens]
+    cbs = [B.make_codebook(g, c, x) for x in cend]
+    P = [torch.zeros(B.hca_vq_pcache_bytes(shape, cbs[0]), dtype=torch.uint8, device="cuda") for _ in range(Lr)]
+    lut = [torch.zeros(B.hca_vq_lut_bytes(shape, cbs[0]) // 4, dtype=torch.float32, device="cuda") for _ in range(Lr)]
+    acc = [torch.zeros(batch, hkv, cap, dtype=torch.float32, device="cuda") for _ in range(Lr)]
+    pos = [torch.arange(cap, dtype=torch.int32, device="cuda").repeat(batch, hkv, 1).contiguous() for _ in range(Lr)]
+    vh = [d["values"].contiguous().pin_memory() for d in data]
+    vd = [torch.zeros(batch, hkv, vnew, D, dtype=torch.float16, device="cuda") for _ in range(Lr)]
+    y = torch.zeros(Lr, batch, w.n_q_heads, D, dtype=torch.float32, device="cuda")
+    ocs, oacc, opos, oV = [], [], [], []
+    for l in range(Lr):
+        B.hca_vq_assign(shape, cbs[l], P[l], data[l]["keys"].cuda(), n0, [0] * batch)
+        oc = oracle.VQCache(R, cap, cens[l])
+        oracle.vq_assign(oc, data[l]["keys"].numpy().reshape(R, n0, D))
+        ocs.append(oc)
+        oacc.append(np.zeros((R, cap), np.float32))
+        p = np.zeros((R, cap), np.int32)
+        p[:] = np.arange(cap)
+        opos.append(p)
+        V = np.zeros((R, n0 + vnew, D), np.float16)
+        V[:, :n0] = data[l]["values"].numpy().reshape(R, n0, D)
+        oV.append(V)
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    d = B.hca_pipeline_desc()
+    d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
+    wsb = B.hca_workspace_bytes(shape, w.k, n0)
+    keep = []
+    for i in range(n_sel):
+        t = torch.zeros(batch, hkv, cap, dtype=torch.float32, device="cuda")
+        keep.append(t)
+        d.sel[i] = t.data_ptr()
+    d.n_sel = n_sel
+    for i in range(4):
+        a = torch.zeros(batch, hkv, w.k, dtype=torch.int32, device="cuda")
+        b = torch.zeros(batch, hkv, dtype=torch.int32, device="cuda")
+        cws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+        keep += [a, b, cws]
+        d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), cws.data_ptr()
+    wt, we = torch.zeros(wsb, dtype=torch.uint8, device="cuda"), torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
+    d.vq_groups, d.vq_codewords, d.topp_tau = g, c, tau
+    pl = B.hca_pipeline_create(shape, Lr, d, 0)
+    layers = (B.hca_layer * Lr)()
+    for l in range(Lr):
+        layers[l].kcache, layers[l].acc, layers[l].pos = P[l].data_ptr(), acc[l].data_ptr(), pos[l].data_ptr()
+        layers[l].v_host, layers[l].v_hbm, layers[l].y = vh[l].data_ptr(), vd[l].data_ptr(), y[l].data_ptr()
+        layers[l].vq_centroids, layers[l].vq_lut = cend[l].data_ptr(), lut[l].data_ptr()
+    nres = (C.c_int64 * (Lr * batch))(*([n0] * (Lr * batch)))
+    sm = 1.0 / math.sqrt(float(D))
+    counts_seen = set()
+    for t in range(steps):
+        ins = [S.make_step(w, l, t) for l in range(Lr)]
+        kn = [x[0].cuda() for x in ins]
+        qs = [x[2].cuda() for x in ins]
+        for l in range(Lr):
+            vd[l][:, :, t] = ins[l][1][:, :, 0].cuda()
+            layers[l].k_new, layers[l].q = kn[l].data_ptr(), qs[l].data_ptr()
+        due = [(t + 1 + l) % E == 0 for l in range(Lr)]
+        ev = (C.c_int64 * Lr)(*[n0 if x else 0 for x in due])
+        torch.cuda.synchronize()
+        B.hca_pipeline_step(pl, layers, nres, n0 + t, w.k, n0, n0, vnew, sm, ev, E, -1)
+        torch.cuda.synchronize()
+        for l in range(Lr):
+            oc = ocs[l]
+            n = int(oc.n[0])
+            oV[l][:, n0 + t] = ins[l][1].numpy().reshape(R, 1, D)[:, 0]
+            opos[l][:, n] = n0 + t
+            oacc[l][:, n] = 0
+            oracle.vq_assign(oc, ins[l][0].numpy().reshape(R, 1, D))
+            q16 = ins[l][2].numpy().reshape(R * G, D)
+            T = oracle.vq_lut(oc, q16)
+            sel, _ = oracle.vq_score(oc, T, want_z=False)
+            if tau > 0:
+                idx, count, _, _ = oracle.topp(sel, oc.n, sm, tau, w.k)
+            else:
+                idx, count = oracle.topk(sel, oc.n, w.k)
+            counts_seen |= set(count.tolist())
+            yo, _ = oracle.vq_attend(oc, T, idx, count, opos[l], oV[l], sm, acc=oacc[l])
+            assert _rel_err(y[l].cpu().numpy().reshape(R * G, D), yo) <= TOL, f"step {t} layer {l}"
+            if due[l]:
+                oracle.vq_evict(oc, oacc[l], opos[l], n0, E)
+            assert nres[l * batch] == int(oc.n[0]), f"step {t} layer {l}"
+    if tau > 0:
+        assert len(counts_seen) > 1
+    for l in range(Lr):
+        n = int(ocs[l].n[0])
+        out = torch.zeros(R, cap, g, dtype=torch.uint8, device="cuda")
+        B.hca_vq_export_pcache(shape, cbs[l], P[l], [n] * batch, out)
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy()[:, :n], ocs[l].P[:, :n].astype(np.uint8))
+        assert np.array_equal(pos[l].cpu().numpy().reshape(R, cap)[:, :n], opos[l][:, :n])
+        assert np.allclose(acc[l].cpu().numpy().reshape(R, cap)[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-6)
+    B.hca_pipeline_destroy(pl)
