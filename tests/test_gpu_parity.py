@@ -366,11 +366,13 @@ def test_kernels_are_deterministic(H):
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("Lr,n_sel,spare", [(3, 3, True), (5, 3, True), (5, 5, True), (5, 5, False), (3, 3, False)])
-def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare):
-    """hca_pipeline_step over 3 or 5 layers (score buffers shared between layers or one each), 12 decode
-    steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place): every layer's
-    output, resident count and final cache state against the oracle run layer by layer."""
+@pytest.mark.parametrize("Lr,n_sel,spare,tau", [(3, 3, True, 0.0), (5, 3, True, 0.0), (5, 5, True, 0.0), (5, 5, False, 0.0),
+                                                 (3, 3, False, 0.0), (4, 4, False, 0.9), (3, 3, True, 0.95)])
+def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau):
+    """hca_pipeline_step over 3 to 5 layers (score buffers shared between layers or one each), 12 decode
+    steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k or the
+    cumulative-weight selection of Eq. 4 (tau > 0): every layer's output, resident count and final cache state
+    against the oracle run layer by layer."""
     import ctypes as C
     from paper_2507_19823_amd import binding as B
     steps, E = 12, 4
@@ -419,6 +421,7 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare):
     d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
     if spare:
         d.spare_kcache, d.spare_acc, d.spare_pos = kc[Lr].data_ptr(), acc[Lr].data_ptr(), pos[Lr].data_ptr()
+    d.topp_tau = tau
     pl = B.hca_pipeline_create(shape, Lr, d, 0)
     layers = (B.hca_layer * Lr)()
     for l in range(Lr):
@@ -447,7 +450,10 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare):
             oracle.quantize(oc, _rows(ins[l][0]))
             q16 = ins[l][2].numpy().reshape(-1, 128)
             sel, _ = oracle.score(oc, q16, want_z=False)
-            idx, count = oracle.topk(sel, oc.n, w.k)
+            if tau > 0:
+                idx, count, _, _ = oracle.topp(sel, oc.n, np.float32(sm), tau, w.k)
+            else:
+                idx, count = oracle.topk(sel, oc.n, w.k)
             yo, _ = oracle.attend(oc, q16, idx, count, opos[l], oV[l], np.float32(sm), acc=oacc[l])
             assert _rel_err(y[l].cpu().numpy().reshape(-1, 128), yo) <= TOL, f"step {t} layer {l}"
             if due[l]:
