@@ -722,6 +722,47 @@ def scan_only(w, iters):
                       "GBs": by / ms / 1e6, "frac": by / ms / 1e6 / HBM_PEAK_GBS}), flush=True)
 
 
+def gather_only(w, iters):
+    """Value gather alone at the workload's shape: k selected rows of 256 B per (sequence, KV head) read from a
+    pinned host store at random rows (drawn here; the store's contents do not matter), against the host link's
+    rate for one large pinned copy measured in the same process."""
+    import torch
+    from paper_2507_19823_amd import binding as B
+    cap = w.n + 16
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap, w.bits, w.group)
+    R, k = w.batch * w.n_kv_heads, w.k
+    big = torch.empty(1 << 28, dtype=torch.uint8, pin_memory=True)
+    dbig = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    dbig.copy_(big, non_blocking=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(8):
+        dbig.copy_(big, non_blocking=True)
+    torch.cuda.synchronize()
+    link_peak = 8 * (1 << 28) / (time.perf_counter() - t0) / 1e9
+    del big, dbig
+    g = torch.Generator().manual_seed(1000 * w.config + 3)
+    idx = torch.stack([torch.randperm(w.n, generator=g)[:k].sort().values for _ in range(R)]).to(torch.int32)
+    idx = idx.reshape(w.batch, w.n_kv_heads, k).cuda()
+    count = torch.full((w.batch, w.n_kv_heads), k, dtype=torch.int32, device="cuda")
+    pos = torch.arange(cap, dtype=torch.int32).repeat(w.batch, w.n_kv_heads, 1).contiguous().cuda()
+    vh = torch.empty(w.batch, w.n_kv_heads, w.n, 128, dtype=torch.float16, pin_memory=True)
+    vh.view(torch.int16).random_(0, 30000)
+    ws = torch.empty(B.hca_workspace_bytes(shape, k, 1), dtype=torch.uint8, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ts = []
+    for _ in range(iters + 1):
+        e0.record()
+        B.hca_gather_values(shape, idx, count, k, pos, vh, w.n, w.n, None, 0, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        ts.append(e0.elapsed_time(e1))
+    ms = sum(ts[1:]) / iters
+    by = R * k * 256
+    print(json.dumps({"mode": "gather", "workload": w.name, "ms": ms, "bytes_per_launch": by, "GBs": by / ms / 1e6,
+                      "host_link_peak_GBs": link_peak, "frac_of_link_peak": by / ms / 1e6 / link_peak}), flush=True)
+
+
 def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
     """Times the oracle, as it stands, on layer 0 of the same workload: consecutive decode steps
     (append one token, score every resident token, top-k, attend with accumulated-score update)
@@ -798,9 +839,10 @@ def main():
                     help="row splits tried by the pipelined per-layer latency probe")
     ap.add_argument("--stages", type=int, default=4, choices=[3, 4],
                     help="native pipeline: 4 = scan | top-k | gather | attend; 3 = top-k shares the scan stream")
-    ap.add_argument("--mode", default="step", choices=["step", "scan", "vq"],
+    ap.add_argument("--mode", default="step", choices=["step", "scan", "vq", "gather"],
                     help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration; "
-                         "vq: the codebook form of the key path (assignment, table, lookup scan) on one layer")
+                         "vq: the codebook form of the key path (assignment, table, lookup scan) on one layer; "
+                         "gather: only the value gather at the workload's shape, against the host link's copy rate")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported "
@@ -822,6 +864,8 @@ def main():
     L = args.layers or (16 if args.config == 2 else w.layers)
     if args.mode == "scan":
         return scan_only(w, args.steps)
+    if args.mode == "gather":
+        return gather_only(w, args.steps)
     if args.mode == "vq":
         print(json.dumps(dict(mode="vq", **vq_probe(w, args.steps))), flush=True)
         return
