@@ -168,3 +168,101 @@ def test_vq_one_layer_at_full_size(oracle):
     oy, _ = oracle.vq_attend(oc, T, oidx, ocount, opos, v_host.numpy().reshape(R, n, 128), sm, acc=oacc)
     assert _rel_err(y.cpu().numpy().reshape(-1, 128), oy) <= TOL
     assert np.allclose(_rows(acc), oacc, rtol=1e-4, atol=1e-7)
+
+
+def test_step_driver_at_full_size(oracle):
+    """The library's step driver as bench.py runs it - four stages on four streams, a score buffer per layer,
+    in-place eviction - on two layers of workload 4 at full size (1 Mi tokens each), two decode steps, the
+    second with an eviction of layer 1: every layer's selection (through its output), output, resident count
+    and, at the end, accumulated scores and value-row map against the oracle."""
+    import ctypes as C
+    import math
+    from paper_2507_19823_amd import binding as B
+    w = S.CONFIGS[4]
+    Lr, steps = 2, 2
+    R, n0 = w.batch * w.n_kv_heads, w.n
+    cap, vnew = n0 + 32, 8
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    dev = "cuda"
+    kc, acc, pos, vh, vd, ocs, oacc, opos, oV = [], [], [], [], [], [], [], [], []
+    for l in range(Lr):
+        d = S.make_layer(w, l, device=dev)
+        k_t = torch.zeros(B.hca_kcache_bytes(shape), dtype=torch.uint8, device=dev)
+        a_t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
+        p_t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.int32, device=dev)
+        B.hca_quantize_keys(shape, k_t, d["keys"], n0, [0] * w.batch, a_t, p_t, [0] * w.batch)
+        v = torch.empty(w.batch, w.n_kv_heads, n0, 128, dtype=torch.float16, pin_memory=True)
+        v.copy_(d["values"])
+        kc.append(k_t); acc.append(a_t); pos.append(p_t); vh.append(v)
+        vd.append(torch.zeros(w.batch, w.n_kv_heads, vnew, 128, dtype=torch.float16, device=dev))
+        oc = oracle.Cache(R, cap, 128, w.bits, w.group)
+        oracle.quantize(oc, _rows(d["keys"].cpu()))
+        ocs.append(oc)
+        oacc.append(np.zeros((R, cap), np.float32))
+        p = np.zeros((R, cap), np.int32)
+        p[:, :n0] = np.arange(n0)
+        opos.append(p)
+        V = np.zeros((R, n0 + vnew, 128), np.float16)
+        V[:, :n0] = v.numpy().reshape(R, n0, 128)
+        oV.append(V)
+        del d
+    y = torch.zeros(Lr, w.batch, w.n_q_heads, 128, dtype=torch.float32, device=dev)
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    d = B.hca_pipeline_desc()
+    d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
+    keep = []
+    for i in range(3):
+        t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
+        keep.append(t)
+        d.sel[i] = t.data_ptr()
+    d.n_sel = 3
+    wsb = B.hca_workspace_bytes(shape, w.k, n0)
+    for i in range(4):
+        a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
+        b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
+        c = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
+        keep += [a, b, c]
+        d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), c.data_ptr()
+    wt, we = torch.zeros(wsb, dtype=torch.uint8, device=dev), torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
+    pl = B.hca_pipeline_create(shape, Lr, d, 0)
+    layers = (B.hca_layer * Lr)()
+    for l in range(Lr):
+        layers[l].kcache, layers[l].acc, layers[l].pos = kc[l].data_ptr(), acc[l].data_ptr(), pos[l].data_ptr()
+        layers[l].v_host, layers[l].v_hbm, layers[l].y = vh[l].data_ptr(), vd[l].data_ptr(), y[l].data_ptr()
+    nres = (C.c_int64 * (Lr * w.batch))(*([n0] * (Lr * w.batch)))
+    sm = 1.0 / math.sqrt(128.0)
+    for t in range(steps):
+        ins = [S.make_step(w, l, t) for l in range(Lr)]
+        kn = [x[0].cuda() for x in ins]
+        qs = [x[2].cuda() for x in ins]
+        for l in range(Lr):
+            vd[l][:, :, t] = ins[l][1][:, :, 0].cuda()
+            layers[l].k_new, layers[l].q = kn[l].data_ptr(), qs[l].data_ptr()
+        due = [t == 1 and l == 1 for l in range(Lr)]
+        ev = (C.c_int64 * Lr)(*[n0 if x else 0 for x in due])
+        torch.cuda.synchronize()
+        B.hca_pipeline_step(pl, layers, nres, n0 + t, w.k, n0, n0, vnew, sm, ev, 1, -1)
+        torch.cuda.synchronize()
+        for l in range(Lr):
+            oc = ocs[l]
+            n = int(oc.n[0])
+            oV[l][:, n0 + t] = _rows(ins[l][1])[:, 0]
+            opos[l][:, n] = n0 + t
+            oacc[l][:, n] = 0
+            oracle.quantize(oc, _rows(ins[l][0]))
+            q16 = ins[l][2].numpy().reshape(-1, 128)
+            sel, _ = oracle.score(oc, q16, want_z=False)
+            idx, count = oracle.topk(sel, oc.n, w.k)
+            yo, _ = oracle.attend(oc, q16, idx, count, opos[l], oV[l], np.float32(sm), acc=oacc[l])
+            assert _rel_err(y[l].cpu().numpy().reshape(-1, 128), yo) <= TOL, f"step {t} layer {l}"
+            if due[l]:
+                assert int((oacc[l] > 0).sum(1).max()) < n0 - 1          # ties decide: the keep-set is unique
+                oracle.evict(oc, oacc[l], opos[l], n0, 1)
+            assert nres[l * w.batch] == int(oc.n[0]), f"step {t} layer {l}"
+    for l in range(Lr):
+        n = int(ocs[l].n[0])
+        assert np.array_equal(_rows(pos[l])[:, :n], opos[l][:, :n])
+        assert np.array_equal(_rows(acc[l])[:, :n] > 0, oacc[l][:, :n] > 0)
+        assert np.allclose(_rows(acc[l])[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-7)
+    B.hca_pipeline_destroy(pl)
