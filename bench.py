@@ -399,7 +399,10 @@ def per_layer_latency_grouped(cfg, groups, streams, iters=8):
 def vq_probe(w, iters, g=32, c=256):
     """Codebook form of the key path on one layer of the workload: bulk assignment (tokens/s), table build
     + lookup scan (time, bytes of the index matrix streamed + scores written against the HBM peak - the bound now
-    that the table reads are free of bank conflicts - and table bytes read from LDS against the LDS peak)."""
+    that the table reads are free of bank conflicts - and table bytes read from LDS against the LDS peak).
+    c > 256 (the paper's own c = 8192): 16-bit indices, the table is read through L2; the codebook is then c sampled
+    sub-vectors per group without Lloyd rounds (the host trainer would take minutes at that size, and the kernels'
+    time does not depend on where the centroids lie)."""
     import numpy as np
     import torch
     import synth_inputs as S
@@ -412,10 +415,15 @@ def vq_probe(w, iters, g=32, c=256):
     # codebooks from the library's host trainer on the first 8192 tokens of each KV head of sequence 0
     t0 = time.perf_counter()
     cen = []
+    wide = c > 256 or g * c * G > 32768
     for h in range(w.n_kv_heads):
-        kval = d["keys"][0, h, :8192].cpu().numpy()
+        kval = d["keys"][0, h, :(8192 if not wide else 32768)].cpu().numpy()
         init = np.stack([rng.choice(kval.shape[0], c, replace=False) for _ in range(g)]).astype(np.int32)
-        cen.append(B.hca_vq_train(kval, g, c, init, 4)[0])
+        if wide:
+            sub = kval.astype(np.float32).reshape(kval.shape[0], g, 128 // g)
+            cen.append(np.stack([sub[init[i], i] for i in range(g)]))
+        else:
+            cen.append(B.hca_vq_train(kval, g, c, init, 4)[0])
     t_train = time.perf_counter() - t0
     cen = torch.from_numpy(np.stack(cen)).cuda()
     cb = B.make_codebook(g, c, cen)
@@ -442,7 +450,7 @@ def vq_probe(w, iters, g=32, c=256):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / iters
     rows = w.batch * w.n_kv_heads
-    hbm_bytes = rows * w.n * (g + 4)
+    hbm_bytes = rows * w.n * (g * (2 if wide else 1) + 4)
     lds_bytes = rows * w.n * g * G * 4
     # LDS: 256 compute units x 256 B per clock (16-byte reads, measured: 4 clocks per conflict-free wave read)
     # x 2.4 GHz.  Assignment: per centroid and channel one subtract and one fused multiply-add = 3 flop.
@@ -452,7 +460,8 @@ def vq_probe(w, iters, g=32, c=256):
            "assign_ms": assign_ms, "assign_token_heads_per_s": rows * w.n / assign_ms * 1e3,
            "assign_roofline": {"bound": "alu", "achieved": assign_flop / assign_ms / 1e9, "peak": 157.3,
                                "unit": "TFLOP/s", "frac": assign_flop / assign_ms / 1e9 / 157.3},
-           "score_ms": ms, "index_bytes_per_token_head": g,
+           "score_ms": ms, "index_bytes_per_token_head": g * (2 if wide else 1),
+           "table": "global memory, read through L2" if wide else "LDS",
            "context_tokens_scored_per_s": w.batch * w.n / ms * 1e3,
            "score_roofline": {"bound": "hbm", "achieved": hbm_bytes / ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": hbm_bytes / ms / 1e6 / HBM_PEAK_GBS,
@@ -834,6 +843,7 @@ def main():
     ap.add_argument("--pipeline", default="native", choices=["native", "staged", "gather", "none"],
                     help="native: the library's four-stage step driver; staged: the same pipeline enqueued from Python; "
                          "gather: only the gather overlaps; none: serial")
+    ap.add_argument("--vq-codewords", type=int, default=256, help="--mode vq: centroids per group (up to 8192)")
     ap.add_argument("--no-latency", action="store_true", help="skip the per-layer latency probes at 128K / 1M / 4M")
     ap.add_argument("--latency-parts", type=int, nargs="*", default=[],
                     help="row splits tried by the pipelined per-layer latency probe")
@@ -867,7 +877,7 @@ def main():
     if args.mode == "gather":
         return gather_only(w, args.steps)
     if args.mode == "vq":
-        print(json.dumps(dict(mode="vq", **vq_probe(w, args.steps))), flush=True)
+        print(json.dumps(dict(mode="vq", **vq_probe(w, args.steps, c=args.vq_codewords))), flush=True)
         return
     # host link: peak (one large pinned copy) and the gather as the path issues it
     # The boxes expose 4 hardware queues per process and HIP deals streams onto them round-robin, so

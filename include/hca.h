@@ -334,10 +334,11 @@ int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* vrow, const
  * (hca_gather_values) and eviction decisions are those of the uniform-code path and are called
  * with the same hca_shape; its bits / group fields are not used by the hca_vq_* calls.
  *
- * Supported: head_dim 128, g in {32, 64}, 1 <= c <= 256 and g * c * n_q_heads/n_kv_heads <= 32768,
- * so that indices are bytes and the whole table of a KV head (<= 128 KiB) sits in the LDS of the
- * compute unit that scans it; a larger table would have to be gathered from L2 at about sixteen
- * times the cost of streaming P from HBM.
+ * Supported: head_dim 128, g in {32, 64}, 1 <= c <= 8192, in two storage forms chosen by the codebook's
+ * shape.  Narrow (c <= 256 and g * c * n_q_heads/n_kv_heads <= 32768): indices are bytes and the whole
+ * table of a KV head (<= 128 KiB) sits in the LDS of the compute unit that scans it.  Wide (anything
+ * else, up to the paper's own c = 8192 of Fig. 4 / Table 4a): 16-bit indices, the table (up to 4 MiB per
+ * KV head) is read through the L2 of the die that scans the row - several times the cost of streaming P.
  *
  * Arithmetic (the same on the oracle's side, so that indices, tables and scores match bit for bit):
  *   distance  d = 0; channels of the group ascending: e = x - c; d = fmaf(e, e, d); nearest = smallest d,
@@ -348,8 +349,9 @@ int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* vrow, const
  *             max over the KV head's query heads.  A table with a NaN or an infinity is an input error
  *             (not detected).
  * Layouts: centroids fp32 [n_kv_heads, g, c, dbar] (row (b, h) uses the codebook of KV head h);
- * pcache uint8 [batch, n_kv_heads, capacity, g], the g index bytes of a slot in a slot-dependent order:
- * byte p of slot j holds the index of group 16 * (p / 16) + (p + j) % 16 (hca_vq_export_pcache undoes it);
+ * pcache, narrow: uint8 [batch, n_kv_heads, capacity, g], the g index bytes of a slot in a slot-dependent
+ * order: byte p of slot j holds the index of group 16 * (p / 16) + (p + j) % 16 (hca_vq_export_pcache undoes
+ * it); wide: uint16 [batch, n_kv_heads, capacity, g] in group order;
  * lut: fp32 T [batch, n_kv_heads, c, g, n_q_heads/n_kv_heads], then fp32 [batch, n_kv_heads, g, 4], the
  * largest |T| per group and query head, then int32 [batch, n_kv_heads, 4], the exponents s of the row's
  * query heads. */
@@ -361,6 +363,9 @@ typedef struct {
 
 size_t hca_vq_pcache_bytes(const hca_shape* shape, const hca_vq_codebook* cb);
 size_t hca_vq_lut_bytes(const hca_shape* shape, const hca_vq_codebook* cb);
+/* Size of the `workspace` argument of the hca_vq_* calls (and of hca_topk, hca_topp, hca_gather_values used with
+ * them): hca_workspace_bytes of the same shape with bits = 4, group = 32, whatever those fields hold. */
+size_t hca_vq_workspace_bytes(const hca_shape* shape, const hca_vq_codebook* cb, int64_t k_max, int64_t m_max);
 
 /* Offline codebook training on the host (Sec. 3.1): Lloyd's k-means per group over the sub-vectors
  * of a validation set.  Host pointers only, no device work, blocks until done.
@@ -385,10 +390,10 @@ int32_t hca_vq_assign(const hca_shape* shape, const hca_vq_codebook* cb, void* p
                       const int64_t* value_row0, void* stream);
 
 /* Test / debug: the index rows in canonical order.
- *   indices  device, uint8 [batch, n_kv_heads, capacity, g]: indices[.., j, i] = index of group i of slot j,
- *            slots >= n_resident untouched */
+ *   indices  device, [batch, n_kv_heads, capacity, g], uint8 for the narrow form and uint16 for the wide one:
+ *            indices[.., j, i] = index of group i of slot j, slots >= n_resident untouched */
 int32_t hca_vq_export_pcache(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache,
-                             const int64_t* n_resident, uint8_t* indices, void* stream);
+                             const int64_t* n_resident, void* indices, void* stream);
 
 /* Builds the table of every query head into `lut` (device, hca_vq_lut_bytes; kept for
  * hca_vq_attend_gathered), then scores every resident token (Eq. 3).
@@ -409,7 +414,7 @@ int32_t hca_vq_attend_gathered(const hca_shape* shape, const hca_vq_codebook* cb
  * highest accumulated scores, ties to the lower slot) and the same stable compaction, applied to the
  * index rows of pcache together with acc and pos.  In place (all three *_dst NULL) or into a second
  * buffer set (all three given, distinct from the sources; rows with n_resident <= M are carried over
- * unchanged).  workspace: hca_workspace_bytes(shape, k, M).  Afterwards n_resident = min(n_resident, M).
+ * unchanged).  workspace: hca_vq_workspace_bytes(shape, cb, k, M).  Afterwards n_resident = min(n_resident, M).
  * Errors: HCA_ERR_CAPACITY if M < 1, M > capacity or n_protect > M. */
 int32_t hca_vq_evict(const hca_shape* shape, const hca_vq_codebook* cb, void* pcache, float* acc, int32_t* pos,
                      const int64_t* n_resident, int64_t M, int64_t n_protect, int32_t* kept_opt, void* workspace,

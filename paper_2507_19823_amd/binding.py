@@ -114,6 +114,8 @@ def lib():
         cbp = C.POINTER(hca_vq_codebook)
         L.hca_vq_pcache_bytes.restype = C.c_size_t
         L.hca_vq_pcache_bytes.argtypes = [sp, cbp]
+        L.hca_vq_workspace_bytes.restype = C.c_size_t
+        L.hca_vq_workspace_bytes.argtypes = [sp, cbp, i64, i64]
         L.hca_vq_lut_bytes.restype = C.c_size_t
         L.hca_vq_lut_bytes.argtypes = [sp, cbp]
         L.hca_vq_train.restype = i32
@@ -276,6 +278,10 @@ def make_codebook(groups, codewords, centroids=None):
 
 def hca_vq_pcache_bytes(shape, cb):
     return int(lib().hca_vq_pcache_bytes(C.byref(shape), C.byref(cb)))
+
+
+def hca_vq_workspace_bytes(shape, cb, k_max, m_max=1):
+    return int(lib().hca_vq_workspace_bytes(C.byref(shape), C.byref(cb), int(k_max), int(m_max)))
 
 
 def hca_vq_lut_bytes(shape, cb):

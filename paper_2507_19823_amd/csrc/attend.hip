@@ -266,7 +266,7 @@ __device__ __forceinline__ void load_entry(const float* p, float (&e)[G]) {
 // Codebook form: the logit of a selected token is the sum over the groups of the table entries
 // its indices select (Eq. 3), added exactly on the table's power-of-two grid (the exponents that the
 // scan left behind the table in `lut`).  Thread i of the chunk owns selected token i0 + i.
-template <int G>
+template <int G, bool WIDE>
 __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t cap, const uint8_t* __restrict__ pcache,
                                                          const float* __restrict__ lut, const int32_t* __restrict__ idx,
                                                          const int32_t* __restrict__ count, int32_t k, float sm_scale,
@@ -285,21 +285,29 @@ __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t c
   {
     const int i = threadIdx.x;
     const int64_t slot = idx[(int64_t)row * k + i0 + (i < nvalid ? i : nvalid - 1)];
-    const uint8_t* pr = pcache + ((int64_t)row * cap + slot) * g;
+    const uint8_t* pr = pcache + ((int64_t)row * cap + slot) * g * (WIDE ? 2 : 1);
     const float* T = lut + (int64_t)row * g * c * G;
     const int32_t* sexp = reinterpret_cast<const int32_t*>(lut + (int64_t)gridDim.y * g * (c * G + 4)) + row * 4;
     int s[G], zi[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) { s[h] = sexp[h]; zi[h] = 0; }
     for (int i16 = 0; i16 < g; i16 += 16) {
-      const uint4 pw = *reinterpret_cast<const uint4*>(pr + i16);
-      const uint32_t wd[4] = {pw.x, pw.y, pw.z, pw.w};
+      int code[16], grp[16];
+      if constexpr (WIDE) {                     // 16-bit indices in group order
+        const uint4 pa = *reinterpret_cast<const uint4*>(pr + 2 * i16), pb = *reinterpret_cast<const uint4*>(pr + 2 * i16 + 16);
+        const uint32_t wd[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
+#pragma unroll
+        for (int b = 0; b < 16; ++b) { code[b] = (int)((wd[b >> 1] >> (16 * (b & 1))) & 0xffffu); grp[b] = i16 + b; }
+      } else {                                  // byte indices, rotated by the slot number
+        const uint4 pw = *reinterpret_cast<const uint4*>(pr + i16);
+        const uint32_t wd[4] = {pw.x, pw.y, pw.z, pw.w};
+#pragma unroll
+        for (int b = 0; b < 16; ++b) { code[b] = (int)((wd[b >> 2] >> (8 * (b & 3))) & 255u); grp[b] = vq_group_at(i16 + b, slot); }
+      }
       float e[16][G];
 #pragma unroll
-      for (int b = 0; b < 16; ++b) {            // 16 independent table reads in flight
-        const int code = (int)((wd[b >> 2] >> (8 * (b & 3))) & 255u);
-        load_entry<G>(T + ((int64_t)code * g + vq_group_at(i16 + b, slot)) * G, e[b]);
-      }
+      for (int b = 0; b < 16; ++b)              // 16 independent table reads in flight
+        load_entry<G>(T + ((int64_t)code[b] * g + grp[b]) * G, e[b]);
 #pragma unroll
       for (int b = 0; b < 16; ++b)
 #pragma unroll
@@ -446,9 +454,15 @@ int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* 
   const int ns = nsplit_of(k);
   if (ns > 64) return HCA_ERR_CAPACITY;
   dim3 gp((unsigned)ns, (unsigned)L.rows);
-  if (L.gqa == 4) vq_attend_partial<4><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
-  else if (L.gqa == 2) vq_attend_partial<2><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
-  else vq_attend_partial<1><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);
+#define HCA_VQ_PARTIAL(GQ)                                                                                               \
+  do {                                                                                                                   \
+    if (vq_is_wide(L, g, c)) vq_attend_partial<GQ, true><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns); \
+    else vq_attend_partial<GQ, false><<<gp, 256, 0, st>>>(g, c, L.cap, pcache, lut, idx, count, k, sm_scale, a, ns);               \
+  } while (0)
+  if (L.gqa == 4) HCA_VQ_PARTIAL(4);
+  else if (L.gqa == 2) HCA_VQ_PARTIAL(2);
+  else HCA_VQ_PARTIAL(1);
+#undef HCA_VQ_PARTIAL
   dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
   attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, nullptr);
   HCA_HIP(hipGetLastError());

@@ -307,9 +307,14 @@ __device__ __forceinline__ uint4 rotate_bytes(uint4 x, int r) {
   return o;
 }
 
-// ---- codebook caches: the rows that move are index rows of g bytes (g = 32 or 64) ------------
-// kept[d] -> destination slot d; one thread per 16-byte piece of a row.
-__global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const uint8_t* __restrict__ pcache,
+// ---- codebook caches: the rows that move are index rows of g bytes (or 2 g with 16-bit indices) ----
+// A call moves a window of `pieces` 16-byte pieces of every row: source rows of sb bytes, window at piece
+// sp0; destination rows of db bytes, window at piece dp0.  acc and pos travel with the call whose source
+// window starts at piece 0.
+// kept[d] -> destination slot d; one thread per 16-byte piece.  rot: byte indices stored rotated by the slot
+// number, re-rotated for the slot they move to.
+__global__ __launch_bounds__(256) void vq_evict_gather(int sb, int sp0, int db, int dp0, int pieces, bool rot, int64_t cap,
+                                                       const uint8_t* __restrict__ pcache,
                                                        const float* __restrict__ acc, const int32_t* __restrict__ pos,
                                                        int n_kv_heads, SelRows sr, int64_t M,
                                                        const int32_t* __restrict__ kept, uint8_t* __restrict__ pdst,
@@ -317,25 +322,26 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int g, int64_t cap, const
                                                        int64_t dst_row, const uint32_t* __restrict__ first_hole) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
-  const int pieces = g / 16;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t d = gid / pieces;
   const int j = (int)(gid % pieces);
   if (d >= M) return;
   if (first_hole != nullptr && d < (int64_t)first_hole[4 * row + 2]) return;   // in place: this slot keeps its row
   const int64_t s = kept[(int64_t)row * M + d];
-  // the record's rotation follows its slot: byte p of slot d is byte (p + d - s) % 16 of slot s
-  reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * g)[j] =
-      rotate_bytes(reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * g)[j], (int)((d - s) & 15));
-  if (j == 0) adst[(int64_t)row * dst_row + d] = acc[(int64_t)row * cap + s];
-  if (j == 1) odst[(int64_t)row * dst_row + d] = pos[(int64_t)row * cap + s];
+  // a rotated record's rotation follows its slot: byte p of slot d is byte (p + d - s) % 16 of slot s
+  const uint4 v = reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * sb)[sp0 + j];
+  reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = rot ? rotate_bytes(v, (int)((d - s) & 15)) : v;
+  if (sp0 == 0 && j == 0) adst[(int64_t)row * dst_row + d] = acc[(int64_t)row * cap + s];
+  if (sp0 == 0 && (j == 1 || pieces == 1)) odst[(int64_t)row * dst_row + d] = pos[(int64_t)row * cap + s];
 }
 
-// Copies the first cnt[b] slots of every row that `which` selects from (src, row stride ssrc) to (dst, sdst):
-// the copy-back of an in-place eviction (compacted rows, cnt = M) and the carry-over of untouched rows
-// of an out-of-place one (cnt = n).
+// Copies a window of the first cnt[b] slots of every row that `which` selects from (src, row stride ssrc
+// slots) to (dst, sdst): the copy-back of an in-place eviction (compacted rows, cnt = M) and the carry-over
+// of untouched rows of an out-of-place one (cnt = n).  acc and pos go with the call whose destination
+// window starts at piece 0.
 // first_hole (in-place copy-back only): slots below the row's lowest dropped slot are left alone.
-__global__ __launch_bounds__(256) void vq_evict_copy_rows(int g, int n_kv_heads, SelRows sr, bool compacted, NRes cnt,
+__global__ __launch_bounds__(256) void vq_evict_copy_rows(int sb, int sp0, int db, int dp0, int pieces, int n_kv_heads,
+                                                          SelRows sr, bool compacted, NRes cnt,
                                                           const uint32_t* __restrict__ first_hole,
                                                           const uint8_t* __restrict__ psrc, const float* __restrict__ asrc,
                                                           const int32_t* __restrict__ osrc, int64_t ssrc,
@@ -345,21 +351,22 @@ __global__ __launch_bounds__(256) void vq_evict_copy_rows(int g, int n_kv_heads,
   const int b = row / n_kv_heads;
   if ((sr.want[b] >= 0) != compacted) return;
   const int64_t m = cnt.n[b];
-  const int pieces = g / 16;
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t d = gid / pieces;
+  const int j = (int)(gid % pieces);
   const int64_t lo = first_hole != nullptr ? (int64_t)first_hole[4 * row + 2] : 0;
-  if (gid >= lo * pieces && gid < m * pieces)
-    reinterpret_cast<uint4*>(pdst + (int64_t)row * sdst * g)[gid] =
-        reinterpret_cast<const uint4*>(psrc + (int64_t)row * ssrc * g)[gid];
-  if (gid >= lo && gid < m) {
-    adst[(int64_t)row * sdst + gid] = asrc[(int64_t)row * ssrc + gid];
-    odst[(int64_t)row * sdst + gid] = osrc[(int64_t)row * ssrc + gid];
+  if (d < lo || d >= m) return;
+  reinterpret_cast<uint4*>(pdst + ((int64_t)row * sdst + d) * db)[dp0 + j] =
+      reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
+  if (dp0 == 0 && j == 0) {
+    adst[(int64_t)row * sdst + d] = asrc[(int64_t)row * ssrc + d];
+    odst[(int64_t)row * sdst + d] = osrc[(int64_t)row * ssrc + d];
   }
 }
 
-int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
-                        int64_t M, int64_t n_protect, int32_t* kept, void* ws, uint8_t* pcache_dst, float* acc_dst,
-                        int32_t* pos_dst, hipStream_t st) {
+int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* acc, int32_t* pos, const NRes& nr,
+                        int64_t nmax, int64_t M, int64_t n_protect, int32_t* kept, void* ws, uint8_t* pcache_dst,
+                        float* acc_dst, int32_t* pos_dst, hipStream_t st) {
   SelRows sr;
   bool any = false, carry = false;
   for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
@@ -373,13 +380,15 @@ int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int
     }
   }
   const bool oop = pcache_dst != nullptr;
-  EvictWs e;                                // the staging for 64 B of uniform codes per slot holds g <= 64 index bytes
+  const bool wide = vq_is_wide(L, g, c);
+  const int rb = g * (wide ? 2 : 1);        // bytes of an index row: 32 .. 128
+  const int pieces = rb / 16;
+  EvictWs e;                                // the staging holds 64 bytes per slot (sized for uniform codes)
   carve(&e, ws, L, M);
-  const int pieces = g / 16;
   if (oop && carry && nmax > 0) {
     dim3 gr((unsigned)((nmax * pieces + 255) / 256), (unsigned)L.rows);
-    vq_evict_copy_rows<<<gr, 256, 0, st>>>(g, L.n_kv_heads, sr, false, nr, nullptr, pcache, acc, pos, L.cap, pcache_dst, acc_dst,
-                                           pos_dst, L.cap);
+    vq_evict_copy_rows<<<gr, 256, 0, st>>>(rb, 0, rb, 0, pieces, L.n_kv_heads, sr, false, nr, nullptr, pcache, acc, pos, L.cap,
+                                           pcache_dst, acc_dst, pos_dst, L.cap);
   }
   if (!any) {
     if (oop) HCA_HIP(hipGetLastError());
@@ -392,17 +401,22 @@ int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int
   if (rc != HCA_OK) return rc;
   dim3 g1((unsigned)p.nchunks, (unsigned)L.rows);
   evict_positions<<<g1, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kp);
-  dim3 gg((unsigned)((M * pieces + 255) / 256), (unsigned)L.rows);
   if (oop) {
-    vq_evict_gather<<<gg, 256, 0, st>>>(g, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, pcache_dst, acc_dst, pos_dst,
-                                        L.cap, nullptr);
+    dim3 gg((unsigned)((M * pieces + 255) / 256), (unsigned)L.rows);
+    vq_evict_gather<<<gg, 256, 0, st>>>(rb, 0, rb, 0, pieces, !wide, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp,
+                                        pcache_dst, acc_dst, pos_dst, L.cap, nullptr);
   } else {
-    vq_evict_gather<<<gg, 256, 0, st>>>(g, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, e.codes, e.acc, e.pos, M,
-                                        p.state);
+    // through the staging area, 64 bytes of every row at a time (one pass, or two for 128-byte rows)
     NRes cnt;
     for (int b = 0; b < kMaxBatch; ++b) cnt.n[b] = M;
-    vq_evict_copy_rows<<<gg, 256, 0, st>>>(g, L.n_kv_heads, sr, true, cnt, p.state, e.codes, e.acc, e.pos, M, pcache, acc,
-                                           pos, L.cap);
+    for (int p0 = 0; p0 < pieces; p0 += 4) {
+      const int wp = pieces - p0 < 4 ? pieces - p0 : 4;
+      dim3 gg((unsigned)((M * wp + 255) / 256), (unsigned)L.rows);
+      vq_evict_gather<<<gg, 256, 0, st>>>(rb, p0, 64, 0, wp, !wide, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, e.codes,
+                                          e.acc, e.pos, M, p.state);
+      vq_evict_copy_rows<<<gg, 256, 0, st>>>(64, 0, rb, p0, wp, L.n_kv_heads, sr, true, cnt, p.state, e.codes, e.acc, e.pos, M,
+                                             pcache, acc, pos, L.cap);
+    }
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;

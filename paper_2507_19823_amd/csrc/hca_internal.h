@@ -89,12 +89,14 @@ int32_t launch_attend_weights(const Layout& L, const void* kcache, const void* q
 int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* pcache, const float* lut,
                                   const int32_t* idx, const int32_t* count, int32_t k, float sm_scale, float* y,
                                   float* acc_opt, void* ws, hipStream_t st);
-// codebook form of the key path (vq.hip)
+// codebook form of the key path (vq.hip).  Narrow: byte indices, table of a KV head in LDS (<= 128 KiB);
+// wide: 16-bit indices, table read through L2.
+inline bool vq_is_wide(const Layout& L, int g, int c) { return c > 256 || (int64_t)g * c * L.gqa > 32768; }
 int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, uint8_t* pcache, const void* k_new,
                          int64_t T, const NRes& nr, float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st);
 int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, const uint8_t* pcache, const void* q,
                         const NRes& nr, int64_t nmax, float* lut, float* sel, float* z_opt, hipStream_t st);
-int32_t launch_vq_evict(const Layout& L, int g, uint8_t* pcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
+int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* acc, int32_t* pos, const NRes& nr, int64_t nmax,
                         int64_t M, int64_t n_protect, int32_t* kept, void* ws, uint8_t* pcache_dst, float* acc_dst,
                         int32_t* pos_dst, hipStream_t st);
 size_t evict_workspace_bytes(const Layout& L, int64_t M);

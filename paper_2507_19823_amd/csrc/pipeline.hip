@@ -44,8 +44,7 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   if (desc->ws_topk == nullptr) return nullptr;
   if (desc->vq_groups != 0) {                // codebook form: same limits as the hca_vq_* calls; eviction in place
     if (desc->vq_groups != 32 && desc->vq_groups != 64) return nullptr;
-    if (desc->vq_codewords < 1 || desc->vq_codewords > 256) return nullptr;
-    if ((int64_t)desc->vq_groups * desc->vq_codewords * L.gqa > 32768) return nullptr;
+    if (desc->vq_codewords < 1 || desc->vq_codewords > 8192) return nullptr;
     if (desc->spare_kcache != nullptr || desc->spare_acc != nullptr || desc->spare_pos != nullptr) return nullptr;
   }
   if (!(desc->topp_tau >= 0.0)) return nullptr;
@@ -203,7 +202,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
         // no spare buffers: compact in place behind this attend.  Rows below the first dropped slot keep
         // their place, so when the dropped tokens sit near the end (the usual case: ties go against the
         // higher slot) only the select passes and a short tail move are paid
-        rc = vq ? launch_vq_evict(L, vg, (uint8_t*)ly.kcache, ly.acc, ly.pos, nr, nmax, M, n_protect, nullptr,
+        rc = vq ? launch_vq_evict(L, vg, vc, (uint8_t*)ly.kcache, ly.acc, ly.pos, nr, nmax, M, n_protect, nullptr,
                                   p->d.ws_evict, nullptr, nullptr, nullptr, sc)
                 : launch_evict(L, ly.kcache, ly.acc, ly.pos, nr, nmax, M, n_protect, nullptr, p->d.ws_evict, nullptr,
                                nullptr, nullptr, sc);

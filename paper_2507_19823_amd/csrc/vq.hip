@@ -3,7 +3,12 @@
 // becomes a table T[centroid][group][query head of the KV head] that sits in LDS while a workgroup
 // scans its share of the index matrix.  The host-side trainer is at the end of the file.
 //
-// Index rows are stored rotated: byte p of the record of slot j holds the index of group
+// Two storage forms.  Narrow (c <= 256 and the table of a KV head within 128 KiB): byte indices, table in
+// LDS - everything said above.  Wide (up to c = 8192, the paper's own size, Fig. 4 / Table 4a): 16-bit
+// indices in plain group order and the table read from global memory, i.e. from the L2 of the die that
+// scans the row (vq_scan_wide_kernel).
+//
+// Narrow index rows are stored rotated: byte p of the record of slot j holds the index of group
 // 16 * (p / 16) + (p + j) % 16  (vq_byte_of / vq_group_at in hca_device.h).  A thread of the scan reads
 // its token's bytes in storage order, so at any moment the 16 lanes that share one pass of a 16-byte
 // LDS read are on 16 different groups, and because a group's entries sit 16 bytes apart within a
@@ -23,7 +28,7 @@ namespace hca {
 // One wave = 64 tokens x one quad of 4 consecutive groups.  Every centroid read is wave-uniform
 // (scalar loads), the running minimum is per lane.  distance: e = x - c; d = fmaf(e, e, d) over the
 // group's channels in ascending order from d = 0; the first smallest wins.
-template <int DBAR>
+template <int DBAR, bool WIDE>
 __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_heads, int64_t cap,
                                                         const float* __restrict__ centroids,
                                                         uint8_t* __restrict__ pcache, const uint16_t* __restrict__ k_new,
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
     }
   }
   const float* cb = centroids + ((int64_t)(row % n_kv_heads) * g + quad * 4) * c * DBAR;
-  uint32_t packed = 0;
+  int win[4];
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const float* cg = cb + (int64_t)u * c * DBAR;
@@ -74,14 +79,20 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
       }
       if (d < bd || cc == 0) { bd = d; best = cc; }
     }
-    packed |= (uint32_t)best << (8 * u);
+    win[u] = best;
   }
   if (!live) return;
   const int b = row / n_kv_heads;
   const int64_t slot = nr.n[b] + tt;
-  uint8_t* rec = pcache + ((int64_t)row * cap + slot) * g;
+  if constexpr (WIDE) {
+    uint16_t* rec = reinterpret_cast<uint16_t*>(pcache) + ((int64_t)row * cap + slot) * g + quad * 4;
+    *reinterpret_cast<uint2*>(rec) = uint2{(uint32_t)win[0] | ((uint32_t)win[1] << 16),
+                                           (uint32_t)win[2] | ((uint32_t)win[3] << 16)};
+  } else {
+    uint8_t* rec = pcache + ((int64_t)row * cap + slot) * g;
 #pragma unroll
-  for (int u = 0; u < 4; ++u) rec[vq_byte_of(quad * 4 + u, slot)] = (uint8_t)(packed >> (8 * u));
+    for (int u = 0; u < 4; ++u) rec[vq_byte_of(quad * 4 + u, slot)] = (uint8_t)win[u];
+  }
   if (quad == 0) {
     if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
     if (pos != nullptr) pos[(int64_t)row * cap + slot] = (int32_t)(vrow0.n[b] + tt);
@@ -92,7 +103,7 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
 // and spreads the group's centroids over its lanes (lane, lane + 64, ...), then the lanes' candidates are
 // reduced by (distance, index): the smaller distance wins, equal distances go to the lower index - the
 // same winner as the ascending scan with a strict comparison.
-template <int DBAR>
+template <int DBAR, bool WIDE>
 __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int n_kv_heads, int64_t cap,
                                                               const float* __restrict__ centroids,
                                                               uint8_t* __restrict__ pcache,
@@ -128,7 +139,10 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
       const int ob = __shfl_xor(best, o);
       if (ob != 0x7fffffff && (best == 0x7fffffff || od < bd || (od == bd && ob < best))) { bd = od; best = ob; }
     }
-    if (lane == 0) pcache[((int64_t)row * cap + slot) * g + vq_byte_of(i, slot)] = (uint8_t)best;
+    if (lane == 0) {
+      if constexpr (WIDE) reinterpret_cast<uint16_t*>(pcache)[((int64_t)row * cap + slot) * g + i] = (uint16_t)best;
+      else pcache[((int64_t)row * cap + slot) * g + vq_byte_of(i, slot)] = (uint8_t)best;
+    }
   }
   if (threadIdx.x == 0) {
     if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
@@ -138,7 +152,7 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
 
 // -------------------------------------------------------------------------------- table ---
 // T[row][cc][i][h] = qbar_i . C[i][cc] for the G query heads of the row: t = 0; t = fmaf(q, c, t) over
-// the group's channels in ascending order.  grid (g, rows), one thread per centroid.  The workgroup also
+// the group's channels in ascending order.  grid (g, rows), centroids spread over the threads.  The workgroup also
 // leaves the largest magnitude of its group's entries, per head, in amax[row][i][4] for the scan.
 template <int G, int DBAR>
 __global__ __launch_bounds__(256) void vq_lut_kernel(int g, int c, int n_kv_heads, const float* __restrict__ centroids,
@@ -146,21 +160,24 @@ __global__ __launch_bounds__(256) void vq_lut_kernel(int g, int c, int n_kv_head
                                                      float* __restrict__ amax) {
   __shared__ float wmax[4][4];
   const int i = blockIdx.x, row = blockIdx.y;
-  const int cc = threadIdx.x;
   float m[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) m[h] = 0.f;
-  if (cc < c) {
+  float qv[G][DBAR];
+#pragma unroll
+  for (int h = 0; h < G; ++h)
+#pragma unroll
+    for (int dd = 0; dd < DBAR; ++dd) qv[h][dd] = h2f(q[((int64_t)row * G + h) * kHeadDim + i * DBAR + dd]);
+  for (int cc = threadIdx.x; cc < c; cc += 256) {
     const float* cv = centroids + (((int64_t)(row % n_kv_heads) * g + i) * c + cc) * DBAR;
     float* out = lut + (((int64_t)row * c + cc) * g + i) * G;
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-      const uint16_t* qh = q + ((int64_t)row * G + h) * kHeadDim + i * DBAR;
       float t = 0.f;
 #pragma unroll
-      for (int dd = 0; dd < DBAR; ++dd) t = fmaf(h2f(qh[dd]), cv[dd], t);
+      for (int dd = 0; dd < DBAR; ++dd) t = fmaf(qv[h][dd], cv[dd], t);
       out[h] = t;
-      m[h] = fabsf(t);
+      m[h] = fmaxf(m[h], fabsf(t));
     }
   }
 #pragma unroll
@@ -328,6 +345,84 @@ __global__ __launch_bounds__(1024) void vq_scan_kernel(int c, int64_t cap, const
   }
 }
 
+// Eq. 3 for the wide form (16-bit indices, more centroids than LDS can hold): the table stays in global
+// memory as fp32 and each entry is put on its head's grid as it is read.  Workgroups are dealt to rows
+// round-robin (workgroup x serves row x % rows): the hardware deals consecutive workgroups to the eight
+// dies in turn, so with eight rows every row is scanned by one die and its table (4 MiB at c = 8192, four
+// query heads) stays in that die's L2.  One token per thread at a time: NG * 2 index bytes, NG table reads
+// of 4 * G bytes from L2, exact integer sums.
+template <int G, int NG>
+__global__ __launch_bounds__(256) void vq_scan_wide_kernel(int c, int64_t cap, const uint16_t* __restrict__ pcache,
+                                                            float* __restrict__ lut, NRes nr, int n_kv_heads, int rows,
+                                                            int64_t per_wg, float* __restrict__ sel,
+                                                            float* __restrict__ z_out) {
+  using E = typename EntryT<G>::type;
+  __shared__ int sexp[4];
+  const int row = blockIdx.x % rows;
+  const int64_t chunk = blockIdx.x / rows;
+  const int64_t n = nr.n[row / n_kv_heads];
+  const int64_t j0 = chunk * per_wg;
+  if (j0 >= n) return;
+  int64_t j1 = j0 + per_wg;
+  if (j1 > n) j1 = n;
+  float* tail = lut + (int64_t)rows * NG * c * G;
+  if (threadIdx.x < 64) {                                 // exponents from the per-group maxima, as in the LDS form
+    const float* am = tail + (int64_t)row * NG * 4;
+    const int h = threadIdx.x & 3, part = threadIdx.x >> 2;
+    float m = 0.f;
+    if (h < G)
+      for (int i = part; i < NG; i += 16) m = fmaxf(m, am[i * 4 + h]);
+#pragma unroll
+    for (int o = 32; o >= 4; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (threadIdx.x < G) {
+      const int s = vq_grid_exponent(m);
+      sexp[threadIdx.x] = s;
+      if (chunk == 0) reinterpret_cast<int32_t*>(tail + (int64_t)rows * NG * 4)[row * 4 + threadIdx.x] = s;
+    }
+  }
+  __syncthreads();
+  int s[G];
+#pragma unroll
+  for (int h = 0; h < G; ++h) s[h] = sexp[h];
+  const E* tab = reinterpret_cast<const E*>(lut) + (int64_t)row * NG * c;
+  const uint16_t* prow = pcache + (int64_t)row * cap * NG;
+  for (int64_t j = j0 + threadIdx.x; j < j1; j += 256) {
+    uint4 pw[NG / 8];
+#pragma unroll
+    for (int v = 0; v < NG / 8; ++v)
+    {
+      const v4i t4 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(prow + j * NG) + v);
+      pw[v] = uint4{(uint32_t)t4.x, (uint32_t)t4.y, (uint32_t)t4.z, (uint32_t)t4.w};
+    }
+    int zi[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) zi[h] = 0;
+#pragma unroll
+    for (int v = 0; v < NG / 8; v += 2) {
+      const uint32_t wd[8] = {pw[v].x, pw[v].y, pw[v].z, pw[v].w, pw[v + 1].x, pw[v + 1].y, pw[v + 1].z, pw[v + 1].w};
+      E e[16];                                            // sixteen table reads in flight
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {
+        const uint32_t code = (wd[b >> 1] >> (16 * (b & 1))) & 0xffffu;
+        e[b] = tab[(int64_t)code * NG + 8 * v + b];
+      }
+#pragma unroll
+      for (int b = 0; b < 16; b += 2) entry_add2<G>(zi, entry_fix<G>(e[b], s), entry_fix<G>(e[b + 1], s));
+    }
+    float z[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) z[h] = ldexpf((float)zi[h], -s[h]);
+    float best = z[0];
+#pragma unroll
+    for (int h = 1; h < G; ++h) best = fmaxf(best, z[h]);
+    sel[(int64_t)row * cap + j] = best;
+    if (z_out != nullptr) {
+#pragma unroll
+      for (int h = 0; h < G; ++h) z_out[((int64_t)row * G + h) * cap + j] = z[h];
+    }
+  }
+}
+
 // Canonical export of the index rows for tests: out[row][slot][group], slots < n_resident.
 __global__ __launch_bounds__(256) void vq_export_kernel(int g, int64_t cap, const uint8_t* __restrict__ pcache, NRes nr,
                                                         int n_kv_heads, uint8_t* __restrict__ out) {
@@ -340,24 +435,49 @@ __global__ __launch_bounds__(256) void vq_export_kernel(int g, int64_t cap, cons
   out[((int64_t)row * cap + slot) * g + i] = pcache[((int64_t)row * cap + slot) * g + vq_byte_of(i, slot)];
 }
 
+__global__ __launch_bounds__(256) void vq_export_wide_kernel(int g, int64_t cap, const uint16_t* __restrict__ pcache,
+                                                             NRes nr, int n_kv_heads, uint16_t* __restrict__ out) {
+  const int row = blockIdx.y;
+  const int64_t n = nr.n[row / n_kv_heads];
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= n * g) return;
+  out[(int64_t)row * cap * g + gid] = pcache[(int64_t)row * cap * g + gid];
+}
+
 int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, uint8_t* pcache, const void* k_new,
                          int64_t T, const NRes& nr, float* acc_opt, int32_t* pos_opt, const NRes& vrow0, hipStream_t st) {
   if (T == 0) return HCA_OK;
   const uint16_t* kn = (const uint16_t*)k_new;
+  const bool wide = vq_is_wide(L, g, c);
+#define HCA_ASSIGN(KERNEL, GRID)                                                                                      \
+  do {                                                                                                                \
+    if (g == 32 && wide) KERNEL<4, true><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0); \
+    else if (g == 32) KERNEL<4, false><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);   \
+    else if (wide) KERNEL<2, true><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);      \
+    else KERNEL<2, false><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);               \
+  } while (0)
   if (T <= 8) {                                     // decode appends: parallel over centroids, not over tokens
     dim3 gs((unsigned)T, (unsigned)L.rows);
-    if (g == 32)
-      vq_assign_small_kernel<4><<<gs, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
-    else
-      vq_assign_small_kernel<2><<<gs, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
-    HCA_HIP(hipGetLastError());
-    return HCA_OK;
+    HCA_ASSIGN(vq_assign_small_kernel, gs);
+  } else {
+    dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 16));
+    HCA_ASSIGN(vq_assign_kernel, grid);
   }
-  dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 16));
-  if (g == 32)
-    vq_assign_kernel<4><<<grid, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
-  else
-    vq_assign_kernel<2><<<grid, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+#undef HCA_ASSIGN
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+template <int G, int NG>
+static int32_t scan_wide_launch(const Layout& L, int c, const uint8_t* pcache, float* lut, const NRes& nr, int64_t nmax,
+                                float* sel, float* z_opt, hipStream_t st) {
+  // about eight workgroups of 256 threads per compute unit, shares a multiple of 256 slots
+  int64_t per_row = 2048 / L.rows;
+  if (per_row < 1) per_row = 1;
+  const int64_t per_wg = align_up((nmax + per_row - 1) / per_row, 256);
+  const int64_t chunks = (nmax + per_wg - 1) / per_wg;
+  vq_scan_wide_kernel<G, NG><<<(unsigned)(chunks * L.rows), 256, 0, st>>>(c, L.cap, (const uint16_t*)pcache, lut, nr,
+                                                                          L.n_kv_heads, L.rows, per_wg, sel, z_opt);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -394,6 +514,16 @@ int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, c
 #undef HCA_LUT
   HCA_HIP(hipGetLastError());
   if (nmax == 0) return HCA_OK;
+  if (vq_is_wide(L, g, c)) {
+    if (g == 32) {
+      if (L.gqa == 4) return scan_wide_launch<4, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+      if (L.gqa == 2) return scan_wide_launch<2, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+      return scan_wide_launch<1, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    }
+    if (L.gqa == 4) return scan_wide_launch<4, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    if (L.gqa == 2) return scan_wide_launch<2, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    return scan_wide_launch<1, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+  }
   if (g == 32) {
     if (L.gqa == 4) return scan_launch<4, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
     if (L.gqa == 2) return scan_launch<2, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
@@ -414,8 +544,7 @@ static int32_t vq_layout(const hca_shape* shape, const hca_vq_codebook* cb, Layo
   if (rc != HCA_OK) return rc;
   if (cb->groups != 32 && cb->groups != 64) return HCA_ERR_UNSUPPORTED;
   if (cb->codewords < 1) return HCA_ERR_BAD_ARG;
-  if (cb->codewords > 256) return HCA_ERR_UNSUPPORTED;
-  if ((int64_t)cb->groups * cb->codewords * L->gqa > 32768) return HCA_ERR_UNSUPPORTED;   // table beyond 128 KiB of LDS
+  if (cb->codewords > 8192) return HCA_ERR_UNSUPPORTED;
   if (need_centroids && cb->centroids == nullptr) return HCA_ERR_BAD_ARG;
   return HCA_OK;
 }
@@ -483,7 +612,16 @@ extern "C" {
 size_t hca_vq_pcache_bytes(const hca_shape* shape, const hca_vq_codebook* cb) {
   Layout L;
   if (vq_layout(shape, cb, &L, false) != HCA_OK) return 0;
-  return (size_t)L.rows * (size_t)L.cap * (size_t)cb->groups;
+  return (size_t)L.rows * (size_t)L.cap * (size_t)cb->groups * (vq_is_wide(L, cb->groups, cb->codewords) ? 2 : 1);
+}
+
+size_t hca_vq_workspace_bytes(const hca_shape* shape, const hca_vq_codebook* cb, int64_t k_max, int64_t m_max) {
+  Layout L;
+  if (vq_layout(shape, cb, &L, false) != HCA_OK) return 0;
+  hca_shape s = *shape;      // the hca_vq_* calls lay the workspace out as the 4-bit uniform path does
+  s.bits = 4;
+  s.group = 32;
+  return hca_workspace_bytes(&s, k_max, m_max);
 }
 
 size_t hca_vq_lut_bytes(const hca_shape* shape, const hca_vq_codebook* cb) {
@@ -562,7 +700,7 @@ int32_t hca_vq_score(const hca_shape* shape, const hca_vq_codebook* cb, const vo
 }
 
 int32_t hca_vq_export_pcache(const hca_shape* shape, const hca_vq_codebook* cb, const void* pcache,
-                             const int64_t* n_resident, uint8_t* indices, void* stream) {
+                             const int64_t* n_resident, void* indices, void* stream) {
   Layout L;
   int32_t rc = vq_layout(shape, cb, &L, false);
   if (rc != HCA_OK) return rc;
@@ -573,8 +711,12 @@ int32_t hca_vq_export_pcache(const hca_shape* shape, const hca_vq_codebook* cb, 
   if (rc != HCA_OK) return rc;
   if (nmax == 0) return HCA_OK;
   dim3 grid((unsigned)((nmax * cb->groups + 255) / 256), (unsigned)L.rows);
-  vq_export_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(cb->groups, L.cap, (const uint8_t*)pcache, nr, L.n_kv_heads,
-                                                          indices);
+  if (vq_is_wide(L, cb->groups, cb->codewords))
+    vq_export_wide_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(cb->groups, L.cap, (const uint16_t*)pcache, nr,
+                                                                 L.n_kv_heads, (uint16_t*)indices);
+  else
+    vq_export_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(cb->groups, L.cap, (const uint8_t*)pcache, nr, L.n_kv_heads,
+                                                            (uint8_t*)indices);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -608,8 +750,8 @@ int32_t hca_vq_evict(const hca_shape* shape, const hca_vq_codebook* cb, void* pc
   int64_t nmax;
   rc = load_nres(L, n_resident, &nr, &nmax);
   if (rc != HCA_OK) return rc;
-  return launch_vq_evict(L, cb->groups, (uint8_t*)pcache, acc, pos, nr, nmax, M, n_protect, kept_opt, workspace,
-                         (uint8_t*)pcache_dst, acc_dst, pos_dst, (hipStream_t)stream);
+  return launch_vq_evict(L, cb->groups, cb->codewords, (uint8_t*)pcache, acc, pos, nr, nmax, M, n_protect, kept_opt,
+                         workspace, (uint8_t*)pcache_dst, acc_dst, pos_dst, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -84,10 +84,18 @@ def test_vq_sizes_and_unsupported_shapes(B):
     assert B.hca_vq_pcache_bytes(s, cb) == 2 * 8 * 1000 * 32
     assert B.hca_vq_lut_bytes(s, cb) == 2 * 8 * 32 * 256 * 4 * 4 + 2 * 8 * (32 + 1) * 4 * 4   # tables + per-group maxima + grid exponents
     assert B.hca_vq_pcache_bytes(s, B.make_codebook(64, 128)) == 2 * 8 * 1000 * 64
-    for g, c in ((16, 256), (32, 257), (64, 256), (32, 0)):     # 64 x 256 x 4 heads is beyond 128 KiB of LDS
+    for g, c in ((16, 256), (32, 8193), (48, 64), (32, 0)):
         assert B.hca_vq_pcache_bytes(s, B.make_codebook(g, c)) == 0
-    s1 = B.make_shape(1, 8, 8, 1000)                            # one query head per KV head: 64 x 256 fits
+    # wide form (16-bit indices): more than 256 centroids, or a table beyond 128 KiB of LDS (64 x 256 x 4 heads)
+    assert B.hca_vq_pcache_bytes(s, B.make_codebook(32, 257)) == 2 * 8 * 1000 * 32 * 2
+    assert B.hca_vq_pcache_bytes(s, B.make_codebook(32, 8192)) == 2 * 8 * 1000 * 32 * 2
+    assert B.hca_vq_pcache_bytes(s, B.make_codebook(64, 256)) == 2 * 8 * 1000 * 64 * 2
+    assert B.hca_vq_lut_bytes(s, B.make_codebook(32, 8192)) == 2 * 8 * 32 * 8192 * 4 * 4 + 2 * 8 * (32 + 1) * 4 * 4
+    s1 = B.make_shape(1, 8, 8, 1000)                            # one query head per KV head: 64 x 256 fits in LDS
     assert B.hca_vq_pcache_bytes(s1, B.make_codebook(64, 256)) == 8 * 1000 * 64
+    # workspace of the hca_vq_* calls: that of the 4-bit uniform path, whatever the shape's bits / group say
+    s4 = B.make_shape(2, 32, 8, 1000)
+    assert B.hca_vq_workspace_bytes(s, cb, 64, 500) == B.hca_workspace_bytes(s4, 64, 500) > 0
 
 
 def test_vq_bad_arguments_are_rejected_on_the_host(B):

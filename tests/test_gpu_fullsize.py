@@ -98,46 +98,57 @@ def test_one_layer_at_full_size(oracle, cfg):
         assert _rel_err(st.y.cpu().numpy().reshape(-1, 128), y) <= TOL
 
 
-def test_vq_one_layer_at_full_size(oracle):
-    """Codebook form at the shape bench.py --mode vq times (config 4 layer: 1 Mi tokens x 8 KV heads, g = 32,
-    c = 256).  The assignment is checked on a sample of tokens (the oracle's brute-force nearest-centroid
-    search over all 8 Mi token-heads would take minutes); scores, top-k and the attention output are
-    checked in full on an index matrix drawn by the test and handed to both sides."""
+@pytest.mark.parametrize("c", [256, 8192])
+def test_vq_one_layer_at_full_size(oracle, c):
+    """Codebook form at the shapes bench.py --mode vq times (config 4 layer: 1 Mi tokens x 8 KV heads, g = 32;
+    c = 256: byte indices, table in LDS; c = 8192, the paper's size: 16-bit indices, table read through L2).
+    The assignment is checked on a sample of tokens (the oracle's brute-force nearest-centroid search over all
+    8 Mi token-heads would take minutes); scores, top-k and the attention output are checked in full on an
+    index matrix drawn by the test and handed to both sides."""
     from paper_2507_19823_amd import binding as B
     w = S.CONFIGS[4]
-    R, n, G, g, c, k = w.batch * w.n_kv_heads, w.n, w.gqa, 32, 256, w.k
+    R, n, G, g, k = w.batch * w.n_kv_heads, w.n, w.gqa, 32, w.k
+    wide = c > 256
+    it, ib = (np.uint16, 2) if wide else (np.uint8, 1)
     cap = n + 32
     rng = np.random.default_rng(4004)
     d = S.make_layer(w, 0, device="cuda")
     keys = d["keys"]
-    cen = np.stack([oracle.vq_train(keys[0, h, :4096].cpu().numpy(), g, c,
-                                    np.stack([rng.choice(4096, c, replace=False) for _ in range(g)]).astype(np.int32), 2)[0]
-                    for h in range(w.n_kv_heads)])
+    if wide:                                          # drawn: training 8192 centroids in the plain oracle takes minutes
+        cen = rng.standard_normal((w.n_kv_heads, g, c, 128 // g)).astype(np.float32)
+    else:
+        cen = np.stack([oracle.vq_train(keys[0, h, :4096].cpu().numpy(), g, c,
+                                        np.stack([rng.choice(4096, c, replace=False) for _ in range(g)]).astype(np.int32), 2)[0]
+                        for h in range(w.n_kv_heads)])
     shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
     cend = torch.from_numpy(cen).cuda()
     cb = B.make_codebook(g, c, cend)
     P = torch.zeros(B.hca_vq_pcache_bytes(shape, cb), dtype=torch.uint8, device="cuda")
     B.hca_vq_assign(shape, cb, P, keys, n, [0])
     torch.cuda.synchronize()
-    Pg = torch.zeros(R, cap, g, dtype=torch.uint8, device="cuda")          # canonical order, by the library's export
+    Pg = torch.zeros(R, cap, g * ib, dtype=torch.uint8, device="cuda")     # canonical order, by the library's export
     B.hca_vq_export_pcache(shape, cb, P, [n], Pg)
     torch.cuda.synchronize()
-    # sample: the first and last 1100 tokens and 6000 random ones per row
-    pick = np.unique(np.concatenate([np.arange(1100), np.arange(n - 1100, n), rng.integers(0, n, 6000)]))
+    # sample: the first and last tokens and random ones per row (fewer against 8192 centroids)
+    e_, r_ = (1100, 6000) if not wide else (70, 160)
+    pick = np.unique(np.concatenate([np.arange(e_), np.arange(n - e_, n), rng.integers(0, n, r_)]))
     oc = oracle.VQCache(R, len(pick), cen)
     oracle.vq_assign(oc, keys.view(R, n, 128)[:, torch.from_numpy(pick).cuda()].cpu().numpy())
-    assert np.array_equal(Pg[:, torch.from_numpy(pick).cuda()].cpu().numpy(), oc.P.astype(np.uint8)), "indices differ"
-    assert int(P.view(R, cap, g)[:, n:].max()) == 0
+    got = Pg[:, torch.from_numpy(pick).cuda()].cpu().numpy()
+    assert np.array_equal(got.view(it) if wide else got, oc.P.astype(it)), "indices differ"
+    assert int(P.view(R, cap, g * ib)[:, n:].max()) == 0
     del oc, Pg
 
     # scores / top-k / attend on a drawn index matrix (zipf-like code popularity, as trained codebooks show)
     pop = rng.permutation(c)
-    Pr = pop[np.minimum((rng.pareto(1.2, (R, n, g)) * 8).astype(np.int64), c - 1)].astype(np.uint8)
-    # stored order (documented in include/hca.h): byte p of slot j holds the index of group 16*(p//16) + (p+j)%16
-    pp, jj = np.arange(g)[None, :], np.arange(n)[:, None]
-    where = (pp & ~15) | ((pp + jj) & 15)
-    P.view(R, cap, g)[:, :n] = torch.from_numpy(np.take_along_axis(Pr, np.broadcast_to(where[None], Pr.shape), axis=2)).cuda()
-    del where
+    Pr = pop[np.minimum((rng.pareto(1.2, (R, n, g)) * (8 if not wide else 200)).astype(np.int64), c - 1)].astype(it)
+    if wide:                                          # stored order: 16-bit indices in group order
+        P.view(torch.int16).view(R, cap, g)[:, :n] = torch.from_numpy(Pr.view(np.int16)).cuda()
+    else:   # stored order (include/hca.h): byte p of slot j holds the index of group 16*(p//16) + (p+j)%16
+        pp, jj = np.arange(g)[None, :], np.arange(n)[:, None]
+        where = (pp & ~15) | ((pp + jj) & 15)
+        P.view(R, cap, g)[:, :n] = torch.from_numpy(np.take_along_axis(Pr, np.broadcast_to(where[None], Pr.shape), axis=2)).cuda()
+        del where
     oc = oracle.VQCache(R, cap, cen)
     oc.P[:, :n] = Pr
     oc.n[:] = n
@@ -146,7 +157,7 @@ def test_vq_one_layer_at_full_size(oracle):
     sel = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
     idx = torch.zeros(w.batch, w.n_kv_heads, k, dtype=torch.int32, device="cuda")
     count = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.hca_workspace_bytes(shape, k, 1), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.hca_vq_workspace_bytes(shape, cb, k, 1), dtype=torch.uint8, device="cuda")
     pos = torch.arange(cap, dtype=torch.int32, device="cuda").repeat(w.batch, w.n_kv_heads, 1).contiguous()
     acc = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device="cuda")
     y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")

@@ -22,7 +22,11 @@ def _rel_err(y, ref):
 
 
 def _codebook(oracle, rng, keys, n_kv, g, c, iters=3):
-    """One trained codebook per KV head (oracle-side trainer; the GPU path only consumes the result)."""
+    """One trained codebook per KV head (oracle-side trainer; the GPU path only consumes the result).  Beyond 256
+    centroids the codebook is drawn instead (training that many centroids in the plain oracle takes minutes and
+    adds nothing to a parity check)."""
+    if c > 256:
+        return (rng.standard_normal((n_kv, g, c, D // g)) * 1.5).astype(np.float32)
     out = []
     for h in range(n_kv):
         kval = keys[0, h, :min(keys.shape[2], 2000)]
@@ -37,7 +41,9 @@ class _State:
         self.shape = B.make_shape(batch, hq, hkv, cap)
         self.cen = torch.from_numpy(cen).cuda()
         self.cb = B.make_codebook(g, c, self.cen)
+        self.wide = c > 256 or g * c * (hq // hkv) > 32768          # 16-bit indices, table read through L2
         self.P = torch.full((B.hca_vq_pcache_bytes(self.shape, self.cb),), 0xEE, dtype=torch.uint8, device="cuda")
+        assert self.P.numel() == batch * hkv * cap * g * (2 if self.wide else 1)
         self.lut = torch.zeros(B.hca_vq_lut_bytes(self.shape, self.cb) // 4, dtype=torch.float32, device="cuda")
         self.sel = torch.full((batch, hkv, cap), -7.0, dtype=torch.float32, device="cuda")
         self.z = torch.full((batch, hq, cap), -7.0, dtype=torch.float32, device="cuda")
@@ -45,7 +51,7 @@ class _State:
         self.pos = torch.full((batch, hkv, cap), -1, dtype=torch.int32, device="cuda")
         self.idx = torch.full((batch, hkv, k), -9, dtype=torch.int32, device="cuda")
         self.count = torch.zeros(batch, hkv, dtype=torch.int32, device="cuda")
-        self.ws = torch.empty(B.hca_workspace_bytes(self.shape, k, 1), dtype=torch.uint8, device="cuda")
+        self.ws = torch.empty(B.hca_vq_workspace_bytes(self.shape, self.cb, k, 1), dtype=torch.uint8, device="cuda")
         self.y = torch.zeros(batch, hq, D, dtype=torch.float32, device="cuda")
         self.n = [0] * batch
 
@@ -56,11 +62,19 @@ class _State:
         self.n = [x + T for x in self.n]
 
     def P_rows(self, P=None, n=None):
-        """Index rows in canonical order [R, cap, g] (the library stores a slot's bytes rotated by its slot number);
-        slots at or beyond n read 0xEE."""
-        out = torch.full((self.batch * self.hkv, self.cap, self.g), 0xEE, dtype=torch.uint8, device="cuda")
+        """Index rows in canonical order [R, cap, g] (the library stores a slot's byte indices rotated by its slot
+        number); slots at or beyond n read 0xEE (0xEEEE in the wide form)."""
+        out = torch.full((self.batch * self.hkv, self.cap, self.g * (2 if self.wide else 1)), 0xEE, dtype=torch.uint8,
+                         device="cuda")
         self.B.hca_vq_export_pcache(self.shape, self.cb, self.P if P is None else P, self.n if n is None else n, out)
-        return out.cpu().numpy()
+        a = out.cpu().numpy()
+        return a.view(np.uint16) if self.wide else a
+
+    def fill(self):
+        return 0xEEEE if self.wide else 0xEE
+
+    def idx_dtype(self):
+        return np.uint16 if self.wide else np.uint8
 
     def table(self):
         """(T fp32 [R*G, g, c], exponents int32 [R*G]) from the library's lut buffer."""
@@ -72,7 +86,8 @@ class _State:
 
 
 @pytest.mark.parametrize("g,c,G,hkv,batch", [(32, 256, 4, 2, 2), (64, 128, 4, 2, 1), (32, 17, 2, 3, 1), (64, 256, 1, 2, 2),
-                                             (32, 1, 4, 1, 1)])
+                                             (32, 1, 4, 1, 1), (32, 1024, 4, 2, 1), (32, 8192, 4, 1, 1), (64, 256, 4, 2, 1),
+                                             (64, 2048, 2, 1, 2), (32, 300, 1, 2, 1)])
 def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
     rng = np.random.default_rng(g * 7 + c + G)
     n, cap = 2500, 2600
@@ -92,9 +107,9 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
     oc = oracle.VQCache(R, cap, cen)
     oracle.vq_assign(oc, keys.reshape(R, n, D)[:, :n_used])
     Pg = st.P_rows()
-    assert np.array_equal(Pg[:, :n_used], oc.P[:, :n_used].astype(np.uint8))
-    assert np.all(Pg[:, n_used:] == 0xEE)
-    assert np.all(st.P.cpu().numpy().reshape(R, cap, g)[:, n_used:] == 0xEE)  # nothing written past n
+    assert np.array_equal(Pg[:, :n_used], oc.P[:, :n_used].astype(st.idx_dtype()))
+    assert np.all(Pg[:, n_used:] == st.fill())
+    assert np.all(st.P.cpu().numpy().reshape(R, cap, -1)[:, n_used:] == 0xEE)  # nothing written past n
     assert np.array_equal(st.pos.cpu().numpy().reshape(R, cap)[:, :n_used], np.tile(np.arange(n_used), (R, 1)))
     assert np.all(st.acc.cpu().numpy().reshape(R, cap)[:, :n_used] == 0) and np.all(st.acc.cpu().numpy().reshape(R, cap)[:, n_used:] == 9)
 
@@ -114,7 +129,7 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
 
 
 @pytest.mark.parametrize("g,c,G,n,k", [(32, 256, 4, 9000, 512), (64, 128, 4, 3001, 100), (32, 64, 2, 5000, 5000),
-                                       (32, 256, 1, 700, 1)])
+                                       (32, 256, 1, 700, 1), (32, 1024, 4, 6000, 300), (64, 512, 2, 2500, 2500)])
 def test_vq_decode_path_matches_oracle(B, oracle, g, c, G, n, k):
     """assign -> table + scores -> top-k -> gather (host + HBM rows) -> attend with accumulated scores."""
     rng = np.random.default_rng(n + k)
@@ -189,12 +204,14 @@ def test_vq_ragged_lengths_and_empty_rows(B, oracle):
 
 
 @pytest.mark.parametrize("mode", ["inplace", "spare"])
-@pytest.mark.parametrize("g,n,M,Rp", [(32, 5000, 3000, 16), (64, 1200, 700, 0), (32, 900, 900, 4), (32, 3000, 1, 1)])
-def test_vq_evict_matches_oracle(B, oracle, mode, g, n, M, Rp):
+@pytest.mark.parametrize("g,c,n,M,Rp", [(32, 64, 5000, 3000, 16), (64, 64, 1200, 700, 0), (32, 64, 900, 900, 4),
+                                        (32, 64, 3000, 1, 1), (32, 300, 4000, 2500, 8), (64, 300, 2600, 1700, 3)])
+def test_vq_evict_matches_oracle(B, oracle, mode, g, c, n, M, Rp):
     """Keep-set, compacted index rows, acc and pos against the oracle; one sequence is short enough to be
-    left alone (n <= M) and must come through unchanged, also into the spare buffers."""
+    left alone (n <= M) and must come through unchanged, also into the spare buffers.  c = 300: 16-bit indices,
+    rows of 64 and 128 bytes (the latter pass through the staging area in two halves)."""
     rng = np.random.default_rng(n + M + Rp + g)
-    batch, hkv, G, c = 2, 2, 4, 64
+    batch, hkv, G = 2, 2, 4
     R, cap = batch * hkv, n + 5
     lens = [n, min(n, M) - (1 if M > 1 else 0)]
     keys = rng.standard_normal((batch, hkv, n, D)).astype(np.float16)
@@ -211,7 +228,7 @@ def test_vq_evict_matches_oracle(B, oracle, mode, g, n, M, Rp):
     accd = torch.from_numpy(acc.reshape(batch, hkv, cap)).cuda()
     posd = torch.from_numpy(pos.reshape(batch, hkv, cap)).cuda()
     kept = torch.full((batch, hkv, M), -5, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.hca_workspace_bytes(st.shape, 8, M), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.hca_vq_workspace_bytes(st.shape, st.cb, 8, M), dtype=torch.uint8, device="cuda")
     if mode == "spare":
         P2 = torch.full_like(st.P, 0xAB)
         acc2, pos2 = torch.full_like(accd, -1.0), torch.full_like(posd, -1)
@@ -232,7 +249,7 @@ def test_vq_evict_matches_oracle(B, oracle, mode, g, n, M, Rp):
             assert np.array_equal(kg[r], okept[r])
         else:
             assert np.all(kg[r] == -5)                       # rows left alone report nothing
-        assert np.array_equal(Pg[r, :m], oc.P[r, :m].astype(np.uint8))
+        assert np.array_equal(Pg[r, :m], oc.P[r, :m].astype(st.idx_dtype()))
         assert np.array_equal(ag[r, :m], acc[r, :m]) and np.array_equal(pg[r, :m], pos[r, :m])
 
 
@@ -259,7 +276,7 @@ def test_vq_decode_loop_with_appends_topp_and_eviction(B, oracle):
     pos[:, :n0] = np.arange(n0)
     acc = np.zeros((R, cap), np.float32)
     sm = 1.0 / np.sqrt(D)
-    ws_e = torch.empty(B.hca_workspace_bytes(st.shape, k_max, w.evict_keep), dtype=torch.uint8, device="cuda")
+    ws_e = torch.empty(B.hca_vq_workspace_bytes(st.shape, st.cb, k_max, w.evict_keep), dtype=torch.uint8, device="cuda")
     counts_seen = set()
     for step in range(w.steps):
         k_new, v_new, q = S.make_step(w, 0, step)
@@ -296,14 +313,14 @@ def test_vq_decode_loop_with_appends_topp_and_eviction(B, oracle):
             oracle.vq_evict(oc, acc, pos, w.evict_keep, w.evict_every)
             m = w.evict_keep
             assert st.n[0] == m == oc.n[0]
-            assert np.array_equal(st.P_rows()[:, :m], oc.P[:, :m].astype(np.uint8))
+            assert np.array_equal(st.P_rows()[:, :m], oc.P[:, :m].astype(st.idx_dtype()))
             assert np.array_equal(st.pos.cpu().numpy().reshape(R, cap)[:, :m], pos[:, :m])
             assert np.array_equal(st.acc.cpu().numpy().reshape(R, cap)[:, :m], acc[:, :m])
     assert len(counts_seen) > 1
 
 
-@pytest.mark.parametrize("tau,Lr,n_sel", [(0.0, 3, 3), (0.9, 3, 3), (0.9, 5, 3), (0.97, 4, 4)])
-def test_native_step_driver_in_the_papers_form(B, oracle, tau, Lr, n_sel):
+@pytest.mark.parametrize("tau,Lr,n_sel,c", [(0.0, 3, 3, 64), (0.9, 3, 3, 64), (0.9, 5, 3, 64), (0.97, 4, 4, 64), (0.9, 3, 3, 512)])
+def test_native_step_driver_in_the_papers_form(B, oracle, tau, Lr, n_sel, c):
     """hca_pipeline_step with a codebook cache per layer (and Eq. 4 selection when tau > 0) over 3 to 5 layers,
     12 decode steps, staggered in-place eviction every 4 steps: every layer's output, resident count and final
     index rows / pos / acc against the oracle run layer by layer."""
@@ -312,7 +329,8 @@ def test_native_step_driver_in_the_papers_form(B, oracle, tau, Lr, n_sel):
     import synth_inputs as S
     steps, E = 12, 4
     w = S.Workload("vqdrv", 9, 2, 8, 2, 1500, 4, 32, 96)
-    batch, hkv, G, g, c = w.batch, w.n_kv_heads, w.gqa, 32, 64
+    batch, hkv, G, g = w.batch, w.n_kv_heads, w.gqa, 32
+    wide = c > 256
     R, n0 = batch * hkv, w.n
     cap, vnew = n0 + E + 16, steps + 4
     shape = B.make_shape(batch, w.n_q_heads, hkv, cap)
@@ -344,7 +362,7 @@ def test_native_step_driver_in_the_papers_form(B, oracle, tau, Lr, n_sel):
     streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
     d = B.hca_pipeline_desc()
     d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
-    wsb = B.hca_workspace_bytes(shape, w.k, n0)
+    wsb = B.hca_vq_workspace_bytes(shape, cbs[0], w.k, n0)
     keep = []
     for i in range(n_sel):
         t = torch.zeros(batch, hkv, cap, dtype=torch.float32, device="cuda")
@@ -405,10 +423,11 @@ def test_native_step_driver_in_the_papers_form(B, oracle, tau, Lr, n_sel):
         assert len(counts_seen) > 1
     for l in range(Lr):
         n = int(ocs[l].n[0])
-        out = torch.zeros(R, cap, g, dtype=torch.uint8, device="cuda")
+        out = torch.zeros(R, cap, g * (2 if wide else 1), dtype=torch.uint8, device="cuda")
         B.hca_vq_export_pcache(shape, cbs[l], P[l], [n] * batch, out)
         torch.cuda.synchronize()
-        assert np.array_equal(out.cpu().numpy()[:, :n], ocs[l].P[:, :n].astype(np.uint8))
+        og = out.cpu().numpy().view(np.uint16) if wide else out.cpu().numpy()
+        assert np.array_equal(og[:, :n], ocs[l].P[:, :n].astype(og.dtype))
         assert np.array_equal(pos[l].cpu().numpy().reshape(R, cap)[:, :n], opos[l][:, :n])
         assert np.allclose(acc[l].cpu().numpy().reshape(R, cap)[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-6)
     B.hca_pipeline_destroy(pl)
