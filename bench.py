@@ -461,7 +461,7 @@ def vq_probe(w, iters, g=32, c=256):
            "assign_roofline": {"bound": "alu", "achieved": assign_flop / assign_ms / 1e9, "peak": 157.3,
                                "unit": "TFLOP/s", "frac": assign_flop / assign_ms / 1e9 / 157.3},
            "score_ms": ms, "index_bytes_per_token_head": g * (2 if wide else 1),
-           "table": "global memory, read through L2" if wide else "LDS",
+           "table": "through LDS, a slice of groups at a time" if wide else "LDS",
            "context_tokens_scored_per_s": w.batch * w.n / ms * 1e3,
            "score_roofline": {"bound": "hbm", "achieved": hbm_bytes / ms / 1e6, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": hbm_bytes / ms / 1e6 / HBM_PEAK_GBS,

@@ -338,7 +338,7 @@ int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* vrow, const
  * shape.  Narrow (c <= 256 and g * c * n_q_heads/n_kv_heads <= 32768): indices are bytes and the whole
  * table of a KV head (<= 128 KiB) sits in the LDS of the compute unit that scans it.  Wide (anything
  * else, up to the paper's own c = 8192 of Fig. 4 / Table 4a): 16-bit indices, the table (up to 4 MiB per
- * KV head) is read through the L2 of the die that scans the row - several times the cost of streaming P.
+ * KV head) passes through LDS a slice of groups at a time, once per tile of 16 Ki tokens.
  *
  * Arithmetic (the same on the oracle's side, so that indices, tables and scores match bit for bit):
  *   distance  d = 0; channels of the group ascending: e = x - c; d = fmaf(e, e, d); nearest = smallest d,
@@ -351,8 +351,10 @@ int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* vrow, const
  * Layouts: centroids fp32 [n_kv_heads, g, c, dbar] (row (b, h) uses the codebook of KV head h);
  * pcache, narrow: uint8 [batch, n_kv_heads, capacity, g], the g index bytes of a slot in a slot-dependent
  * order: byte p of slot j holds the index of group 16 * (p / 16) + (p + j) % 16 (hca_vq_export_pcache undoes
- * it); wide: uint16 [batch, n_kv_heads, capacity, g] in group order;
- * lut: fp32 T [batch, n_kv_heads, c, g, n_q_heads/n_kv_heads], then fp32 [batch, n_kv_heads, g, 4], the
+ * it); wide: uint16 [batch, n_kv_heads, ceil(capacity / 16384), g, 16384] - tiles of 16 Ki slots, inside a
+ * tile the indices of one group side by side (the scan takes the groups a few at a time);
+ * lut: fp32 T [batch, n_kv_heads, c, g, n_q_heads/n_kv_heads] (wide form: [batch, n_kv_heads, g, c, ...]),
+ * then fp32 [batch, n_kv_heads, g, 4], the
  * largest |T| per group and query head, then int32 [batch, n_kv_heads, 4], the exponents s of the row's
  * query heads. */
 typedef struct {

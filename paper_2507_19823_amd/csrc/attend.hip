@@ -285,29 +285,33 @@ __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t c
   {
     const int i = threadIdx.x;
     const int64_t slot = idx[(int64_t)row * k + i0 + (i < nvalid ? i : nvalid - 1)];
-    const uint8_t* pr = pcache + ((int64_t)row * cap + slot) * g * (WIDE ? 2 : 1);
+    const uint8_t* pr = pcache + ((int64_t)row * cap + slot) * g;                  // narrow form: the slot's record
+    const uint16_t* pw = reinterpret_cast<const uint16_t*>(pcache);
+    const int64_t tiles = vq_tiles(cap);
     const float* T = lut + (int64_t)row * g * c * G;
     const int32_t* sexp = reinterpret_cast<const int32_t*>(lut + (int64_t)gridDim.y * g * (c * G + 4)) + row * 4;
     int s[G], zi[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) { s[h] = sexp[h]; zi[h] = 0; }
     for (int i16 = 0; i16 < g; i16 += 16) {
-      int code[16], grp[16];
-      if constexpr (WIDE) {                     // 16-bit indices in group order
-        const uint4 pa = *reinterpret_cast<const uint4*>(pr + 2 * i16), pb = *reinterpret_cast<const uint4*>(pr + 2 * i16 + 16);
-        const uint32_t wd[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
+      int64_t ent[16];                          // entry number in the table of this row
+      if constexpr (WIDE) {                     // 16-bit indices, group-major tiles; table [group][centroid]
 #pragma unroll
-        for (int b = 0; b < 16; ++b) { code[b] = (int)((wd[b >> 1] >> (16 * (b & 1))) & 0xffffu); grp[b] = i16 + b; }
-      } else {                                  // byte indices, rotated by the slot number
-        const uint4 pw = *reinterpret_cast<const uint4*>(pr + i16);
-        const uint32_t wd[4] = {pw.x, pw.y, pw.z, pw.w};
+        for (int b = 0; b < 16; ++b) {
+          const int code = (int)pw[vq_wide_at(g, tiles, row, slot, i16 + b)];
+          ent[b] = (int64_t)(i16 + b) * c + code;
+        }
+      } else {                                  // byte indices, rotated by the slot number; table [centroid][group]
+        const uint4 pv = *reinterpret_cast<const uint4*>(pr + i16);
+        const uint32_t wd[4] = {pv.x, pv.y, pv.z, pv.w};
 #pragma unroll
-        for (int b = 0; b < 16; ++b) { code[b] = (int)((wd[b >> 2] >> (8 * (b & 3))) & 255u); grp[b] = vq_group_at(i16 + b, slot); }
+        for (int b = 0; b < 16; ++b)
+          ent[b] = (int64_t)((wd[b >> 2] >> (8 * (b & 3))) & 255u) * g + vq_group_at(i16 + b, slot);
       }
       float e[16][G];
 #pragma unroll
       for (int b = 0; b < 16; ++b)              // 16 independent table reads in flight
-        load_entry<G>(T + ((int64_t)code[b] * g + grp[b]) * G, e[b]);
+        load_entry<G>(T + ent[b] * G, e[b]);
 #pragma unroll
       for (int b = 0; b < 16; ++b)
 #pragma unroll

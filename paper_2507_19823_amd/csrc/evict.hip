@@ -313,8 +313,29 @@ __device__ __forceinline__ uint4 rotate_bytes(uint4 x, int r) {
 // window starts at piece 0.
 // kept[d] -> destination slot d; one thread per 16-byte piece.  rot: byte indices stored rotated by the slot
 // number, re-rotated for the slot they move to.
-__global__ __launch_bounds__(256) void vq_evict_gather(int sb, int sp0, int db, int dp0, int pieces, bool rot, int64_t cap,
-                                                       const uint8_t* __restrict__ pcache,
+// Wide form (tiled 16-bit indices): one 16-byte piece = the indices of 8 consecutive groups of a slot, picked
+// out of / put back into the group-major tiles; between the two they travel as token-major rows.
+__device__ __forceinline__ uint4 vq_wide_read8(const uint16_t* pw, int g, int64_t tiles, int64_t row, int64_t slot, int g0) {
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] = (uint32_t)pw[vq_wide_at(g, tiles, row, slot, g0 + 2 * i)] |
+           ((uint32_t)pw[vq_wide_at(g, tiles, row, slot, g0 + 2 * i + 1)] << 16);
+  return uint4{w[0], w[1], w[2], w[3]};
+}
+__device__ __forceinline__ void vq_wide_write8(uint16_t* pw, int g, int64_t tiles, int64_t row, int64_t slot, int g0, uint4 v) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    pw[vq_wide_at(g, tiles, row, slot, g0 + 2 * i)] = (uint16_t)(w[i] & 0xffffu);
+    pw[vq_wide_at(g, tiles, row, slot, g0 + 2 * i + 1)] = (uint16_t)(w[i] >> 16);
+  }
+}
+
+// form: 0 = narrow (byte indices, rotated records), 1 = wide source and destination caches, 2 = wide source cache
+// and token-major destination (the staging area)
+__global__ __launch_bounds__(256) void vq_evict_gather(int sb, int sp0, int db, int dp0, int pieces, int form, int g,
+                                                       int64_t cap, int64_t dcap, const uint8_t* __restrict__ pcache,
                                                        const float* __restrict__ acc, const int32_t* __restrict__ pos,
                                                        int n_kv_heads, SelRows sr, int64_t M,
                                                        const int32_t* __restrict__ kept, uint8_t* __restrict__ pdst,
@@ -328,9 +349,15 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int sb, int sp0, int db, 
   if (d >= M) return;
   if (first_hole != nullptr && d < (int64_t)first_hole[4 * row + 2]) return;   // in place: this slot keeps its row
   const int64_t s = kept[(int64_t)row * M + d];
-  // a rotated record's rotation follows its slot: byte p of slot d is byte (p + d - s) % 16 of slot s
-  const uint4 v = reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * sb)[sp0 + j];
-  reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = rot ? rotate_bytes(v, (int)((d - s) & 15)) : v;
+  if (form == 0) {
+    // a rotated record's rotation follows its slot: byte p of slot d is byte (p + d - s) % 16 of slot s
+    const uint4 v = reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * sb)[sp0 + j];
+    reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = rotate_bytes(v, (int)((d - s) & 15));
+  } else {
+    const uint4 v = vq_wide_read8(reinterpret_cast<const uint16_t*>(pcache), g, vq_tiles(cap), row, s, 8 * (sp0 + j));
+    if (form == 1) vq_wide_write8(reinterpret_cast<uint16_t*>(pdst), g, vq_tiles(dcap), row, d, 8 * (dp0 + j), v);
+    else reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = v;
+  }
   if (sp0 == 0 && j == 0) adst[(int64_t)row * dst_row + d] = acc[(int64_t)row * cap + s];
   if (sp0 == 0 && (j == 1 || pieces == 1)) odst[(int64_t)row * dst_row + d] = pos[(int64_t)row * cap + s];
 }
@@ -340,7 +367,10 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int sb, int sp0, int db, 
 // of untouched rows of an out-of-place one (cnt = n).  acc and pos go with the call whose destination
 // window starts at piece 0.
 // first_hole (in-place copy-back only): slots below the row's lowest dropped slot are left alone.
-__global__ __launch_bounds__(256) void vq_evict_copy_rows(int sb, int sp0, int db, int dp0, int pieces, int n_kv_heads,
+// form: 0 = plain rows on both sides, 1 = wide caches on both sides (carry-over), 2 = token-major source (the
+// staging area) into a wide cache (copy-back)
+__global__ __launch_bounds__(256) void vq_evict_copy_rows(int sb, int sp0, int db, int dp0, int pieces, int form, int g,
+                                                          int64_t scap, int64_t dcap, int n_kv_heads,
                                                           SelRows sr, bool compacted, NRes cnt,
                                                           const uint32_t* __restrict__ first_hole,
                                                           const uint8_t* __restrict__ psrc, const float* __restrict__ asrc,
@@ -356,8 +386,14 @@ __global__ __launch_bounds__(256) void vq_evict_copy_rows(int sb, int sp0, int d
   const int j = (int)(gid % pieces);
   const int64_t lo = first_hole != nullptr ? (int64_t)first_hole[4 * row + 2] : 0;
   if (d < lo || d >= m) return;
-  reinterpret_cast<uint4*>(pdst + ((int64_t)row * sdst + d) * db)[dp0 + j] =
-      reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
+  if (form == 0) {
+    reinterpret_cast<uint4*>(pdst + ((int64_t)row * sdst + d) * db)[dp0 + j] =
+        reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
+  } else {
+    const uint4 v = form == 1 ? vq_wide_read8(reinterpret_cast<const uint16_t*>(psrc), g, vq_tiles(scap), row, d, 8 * (sp0 + j))
+                              : reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
+    vq_wide_write8(reinterpret_cast<uint16_t*>(pdst), g, vq_tiles(dcap), row, d, 8 * (dp0 + j), v);
+  }
   if (dp0 == 0 && j == 0) {
     adst[(int64_t)row * sdst + d] = asrc[(int64_t)row * ssrc + d];
     odst[(int64_t)row * sdst + d] = osrc[(int64_t)row * ssrc + d];
@@ -387,8 +423,8 @@ int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* a
   carve(&e, ws, L, M);
   if (oop && carry && nmax > 0) {
     dim3 gr((unsigned)((nmax * pieces + 255) / 256), (unsigned)L.rows);
-    vq_evict_copy_rows<<<gr, 256, 0, st>>>(rb, 0, rb, 0, pieces, L.n_kv_heads, sr, false, nr, nullptr, pcache, acc, pos, L.cap,
-                                           pcache_dst, acc_dst, pos_dst, L.cap);
+    vq_evict_copy_rows<<<gr, 256, 0, st>>>(rb, 0, rb, 0, pieces, wide ? 1 : 0, g, L.cap, L.cap, L.n_kv_heads, sr, false, nr,
+                                           nullptr, pcache, acc, pos, L.cap, pcache_dst, acc_dst, pos_dst, L.cap);
   }
   if (!any) {
     if (oop) HCA_HIP(hipGetLastError());
@@ -403,8 +439,8 @@ int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* a
   evict_positions<<<g1, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kp);
   if (oop) {
     dim3 gg((unsigned)((M * pieces + 255) / 256), (unsigned)L.rows);
-    vq_evict_gather<<<gg, 256, 0, st>>>(rb, 0, rb, 0, pieces, !wide, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp,
-                                        pcache_dst, acc_dst, pos_dst, L.cap, nullptr);
+    vq_evict_gather<<<gg, 256, 0, st>>>(rb, 0, rb, 0, pieces, wide ? 1 : 0, g, L.cap, L.cap, pcache, acc, pos, L.n_kv_heads,
+                                        sr, M, kp, pcache_dst, acc_dst, pos_dst, L.cap, nullptr);
   } else {
     // through the staging area, 64 bytes of every row at a time (one pass, or two for 128-byte rows)
     NRes cnt;
@@ -412,10 +448,10 @@ int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* a
     for (int p0 = 0; p0 < pieces; p0 += 4) {
       const int wp = pieces - p0 < 4 ? pieces - p0 : 4;
       dim3 gg((unsigned)((M * wp + 255) / 256), (unsigned)L.rows);
-      vq_evict_gather<<<gg, 256, 0, st>>>(rb, p0, 64, 0, wp, !wide, L.cap, pcache, acc, pos, L.n_kv_heads, sr, M, kp, e.codes,
-                                          e.acc, e.pos, M, p.state);
-      vq_evict_copy_rows<<<gg, 256, 0, st>>>(64, 0, rb, p0, wp, L.n_kv_heads, sr, true, cnt, p.state, e.codes, e.acc, e.pos, M,
-                                             pcache, acc, pos, L.cap);
+      vq_evict_gather<<<gg, 256, 0, st>>>(rb, p0, 64, 0, wp, wide ? 2 : 0, g, L.cap, L.cap, pcache, acc, pos, L.n_kv_heads, sr,
+                                          M, kp, e.codes, e.acc, e.pos, M, p.state);
+      vq_evict_copy_rows<<<gg, 256, 0, st>>>(64, 0, rb, p0, wp, wide ? 2 : 0, g, M, L.cap, L.n_kv_heads, sr, true, cnt,
+                                             p.state, e.codes, e.acc, e.pos, M, pcache, acc, pos, L.cap);
     }
   }
   HCA_HIP(hipGetLastError());

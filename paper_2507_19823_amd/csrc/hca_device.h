@@ -56,6 +56,14 @@ __device__ __forceinline__ int vq_byte_of(int grp, int64_t slot) {
 __device__ __forceinline__ int vq_group_at(int byte, int64_t slot) {
   return (byte & ~15) | ((byte + (int)slot) & 15);
 }
+// Wide codebook form: 16-bit indices, stored in tiles of kVqTile slots, group-major inside a tile
+// (uint16 [row][tile][group][kVqTile]), so that the scan, which handles one group (or a few) at a time, reads
+// each group's indices of its tile in one piece.  Position of (row, slot, group) in uint16 units:
+constexpr int kVqTile = 16384;
+__host__ __device__ __forceinline__ int64_t vq_tiles(int64_t cap) { return (cap + kVqTile - 1) / kVqTile; }
+__host__ __device__ __forceinline__ int64_t vq_wide_at(int g, int64_t tiles, int64_t row, int64_t slot, int grp) {
+  return ((row * tiles + slot / kVqTile) * g + grp) * kVqTile + slot % kVqTile;
+}
 // Power-of-two grid of one query head's table: s = 23 - floor(log2(largest magnitude)) (0 for an all-zero
 // table), entry -> rint(entry * 2^s), at most 2^24 in magnitude, so that 64 of them add up exactly in 32 bits.
 __device__ __forceinline__ int vq_grid_exponent(float amax) {

@@ -5,8 +5,9 @@
 //
 // Two storage forms.  Narrow (c <= 256 and the table of a KV head within 128 KiB): byte indices, table in
 // LDS - everything said above.  Wide (up to c = 8192, the paper's own size, Fig. 4 / Table 4a): 16-bit
-// indices in plain group order and the table read from global memory, i.e. from the L2 of the die that
-// scans the row (vq_scan_wide_kernel).
+// indices stored group-major in tiles of 16 Ki slots (vq_wide_at in hca_device.h) and a table kept
+// group-major too; a workgroup scans one tile and brings the table through LDS one slice of groups at a
+// time (vq_scan_wide_kernel).
 //
 // Narrow index rows are stored rotated: byte p of the record of slot j holds the index of group
 // 16 * (p / 16) + (p + j) % 16  (vq_byte_of / vq_group_at in hca_device.h).  A thread of the scan reads
@@ -85,9 +86,10 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
   const int b = row / n_kv_heads;
   const int64_t slot = nr.n[b] + tt;
   if constexpr (WIDE) {
-    uint16_t* rec = reinterpret_cast<uint16_t*>(pcache) + ((int64_t)row * cap + slot) * g + quad * 4;
-    *reinterpret_cast<uint2*>(rec) = uint2{(uint32_t)win[0] | ((uint32_t)win[1] << 16),
-                                           (uint32_t)win[2] | ((uint32_t)win[3] << 16)};
+    uint16_t* pw = reinterpret_cast<uint16_t*>(pcache);
+    const int64_t tiles = vq_tiles(cap);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) pw[vq_wide_at(g, tiles, row, slot, quad * 4 + u)] = (uint16_t)win[u];
   } else {
     uint8_t* rec = pcache + ((int64_t)row * cap + slot) * g;
 #pragma unroll
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
       if (ob != 0x7fffffff && (best == 0x7fffffff || od < bd || (od == bd && ob < best))) { bd = od; best = ob; }
     }
     if (lane == 0) {
-      if constexpr (WIDE) reinterpret_cast<uint16_t*>(pcache)[((int64_t)row * cap + slot) * g + i] = (uint16_t)best;
+      if constexpr (WIDE) reinterpret_cast<uint16_t*>(pcache)[vq_wide_at(g, vq_tiles(cap), row, slot, i)] = (uint16_t)best;
       else pcache[((int64_t)row * cap + slot) * g + vq_byte_of(i, slot)] = (uint8_t)best;
     }
   }
@@ -151,11 +153,12 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
 }
 
 // -------------------------------------------------------------------------------- table ---
-// T[row][cc][i][h] = qbar_i . C[i][cc] for the G query heads of the row: t = 0; t = fmaf(q, c, t) over
+// T[row][cc][i][h] (narrow form; T[row][i][cc][h] in the wide form) = qbar_i . C[i][cc] for the G query heads of the row: t = 0; t = fmaf(q, c, t) over
 // the group's channels in ascending order.  grid (g, rows), centroids spread over the threads.  The workgroup also
 // leaves the largest magnitude of its group's entries, per head, in amax[row][i][4] for the scan.
 template <int G, int DBAR>
-__global__ __launch_bounds__(256) void vq_lut_kernel(int g, int c, int n_kv_heads, const float* __restrict__ centroids,
+__global__ __launch_bounds__(256) void vq_lut_kernel(int g, int c, int n_kv_heads, bool wide,
+                                                     const float* __restrict__ centroids,
                                                      const uint16_t* __restrict__ q, float* __restrict__ lut,
                                                      float* __restrict__ amax) {
   __shared__ float wmax[4][4];
@@ -170,7 +173,7 @@ __global__ __launch_bounds__(256) void vq_lut_kernel(int g, int c, int n_kv_head
     for (int dd = 0; dd < DBAR; ++dd) qv[h][dd] = h2f(q[((int64_t)row * G + h) * kHeadDim + i * DBAR + dd]);
   for (int cc = threadIdx.x; cc < c; cc += 256) {
     const float* cv = centroids + (((int64_t)(row % n_kv_heads) * g + i) * c + cc) * DBAR;
-    float* out = lut + (((int64_t)row * c + cc) * g + i) * G;
+    float* out = lut + (wide ? ((int64_t)row * g + i) * c + cc : ((int64_t)row * c + cc) * g + i) * G;
 #pragma unroll
     for (int h = 0; h < G; ++h) {
       float t = 0.f;
@@ -345,73 +348,99 @@ __global__ __launch_bounds__(1024) void vq_scan_kernel(int c, int64_t cap, const
   }
 }
 
-// Eq. 3 for the wide form (16-bit indices, more centroids than LDS can hold): the table stays in global
-// memory as fp32 and each entry is put on its head's grid as it is read.  Workgroups are dealt to rows
-// round-robin (workgroup x serves row x % rows): the hardware deals consecutive workgroups to the eight
-// dies in turn, so with eight rows every row is scanned by one die and its table (4 MiB at c = 8192, four
-// query heads) stays in that die's L2.  One token per thread at a time: NG * 2 index bytes, NG table reads
-// of 4 * G bytes from L2, exact integer sums.
-template <int G, int NG>
-__global__ __launch_bounds__(256) void vq_scan_wide_kernel(int c, int64_t cap, const uint16_t* __restrict__ pcache,
-                                                            float* __restrict__ lut, NRes nr, int n_kv_heads, int rows,
-                                                            int64_t per_wg, float* __restrict__ sel,
-                                                            float* __restrict__ z_out) {
+// Eq. 3 for the wide form (16-bit indices, a table larger than LDS).  One workgroup of 1024 threads scans
+// one tile of 16 Ki slots, 16 consecutive slots per thread with their running integer sums in registers,
+// and walks through the groups a slice at a time: gps groups whose entries (gps * c * G * 4 bytes <= 128 KiB)
+// are copied from the group-major table into LDS on their heads' grids, then looked up with the tile's
+// indices of those groups (32 contiguous bytes per thread and group).  The table is re-read once per tile:
+// 4 MiB of full lines from L2 per 16 Ki tokens, instead of one L2 request per token and group.
+template <int G>
+__global__ __launch_bounds__(1024) void vq_scan_wide_kernel(int g, int c, int gps, int64_t cap,
+                                                             const uint16_t* __restrict__ pcache,
+                                                             float* __restrict__ lut, NRes nr, int n_kv_heads, int rows,
+                                                             float* __restrict__ sel, float* __restrict__ z_out) {
   using E = typename EntryT<G>::type;
+  using F = typename EntryT<G>::fix;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
   __shared__ int sexp[4];
+  // workgroup x serves row x % rows: consecutive workgroups go to the eight dies in turn, so with eight rows
+  // every row is scanned by one die and its table (4 MiB at c = 8192, four query heads) stays in that die's L2
   const int row = blockIdx.x % rows;
-  const int64_t chunk = blockIdx.x / rows;
+  const int64_t tile = blockIdx.x / rows;
   const int64_t n = nr.n[row / n_kv_heads];
-  const int64_t j0 = chunk * per_wg;
-  if (j0 >= n) return;
-  int64_t j1 = j0 + per_wg;
-  if (j1 > n) j1 = n;
-  float* tail = lut + (int64_t)rows * NG * c * G;
+  const int64_t t0 = tile * kVqTile;
+  if (t0 >= n) return;
+  float* tail = lut + (int64_t)rows * g * c * G;
   if (threadIdx.x < 64) {                                 // exponents from the per-group maxima, as in the LDS form
-    const float* am = tail + (int64_t)row * NG * 4;
+    const float* am = tail + (int64_t)row * g * 4;
     const int h = threadIdx.x & 3, part = threadIdx.x >> 2;
     float m = 0.f;
     if (h < G)
-      for (int i = part; i < NG; i += 16) m = fmaxf(m, am[i * 4 + h]);
+      for (int i = part; i < g; i += 16) m = fmaxf(m, am[i * 4 + h]);
 #pragma unroll
     for (int o = 32; o >= 4; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
     if (threadIdx.x < G) {
       const int s = vq_grid_exponent(m);
       sexp[threadIdx.x] = s;
-      if (chunk == 0) reinterpret_cast<int32_t*>(tail + (int64_t)rows * NG * 4)[row * 4 + threadIdx.x] = s;
+      if (tile == 0) reinterpret_cast<int32_t*>(tail + (int64_t)rows * g * 4)[row * 4 + threadIdx.x] = s;
     }
   }
   __syncthreads();
   int s[G];
 #pragma unroll
   for (int h = 0; h < G; ++h) s[h] = sexp[h];
-  const E* tab = reinterpret_cast<const E*>(lut) + (int64_t)row * NG * c;
-  const uint16_t* prow = pcache + (int64_t)row * cap * NG;
-  for (int64_t j = j0 + threadIdx.x; j < j1; j += 256) {
-    uint4 pw[NG / 8];
+  F* tab = reinterpret_cast<F*>(lds_raw);
+  const E* trow = reinterpret_cast<const E*>(lut) + (int64_t)row * g * c;
+  const int64_t tiles = vq_tiles(cap);
+  const uint16_t* ptile = pcache + (row * tiles + tile) * g * (int64_t)kVqTile + threadIdx.x * 16;
+  int zi[16][G];
 #pragma unroll
-    for (int v = 0; v < NG / 8; ++v)
-    {
-      const v4i t4 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(prow + j * NG) + v);
-      pw[v] = uint4{(uint32_t)t4.x, (uint32_t)t4.y, (uint32_t)t4.z, (uint32_t)t4.w};
-    }
-    int zi[G];
+  for (int tt = 0; tt < 16; ++tt)
 #pragma unroll
-    for (int h = 0; h < G; ++h) zi[h] = 0;
+    for (int h = 0; h < G; ++h) zi[tt][h] = 0;
+  // the indices of the next group are fetched while the current group is looked up (and while the next slice
+  // of the table is brought in), so no slice waits for HBM
+  auto load_idx = [](const uint16_t* p, int i) {          // read once: keep it out of the way of the table in L2
+    const v4i t4 = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(p) + i);
+    return uint4{(uint32_t)t4.x, (uint32_t)t4.y, (uint32_t)t4.z, (uint32_t)t4.w};
+  };
+  uint4 na = load_idx(ptile, 0), nb = load_idx(ptile, 1);
+  for (int g0 = 0; g0 < g; g0 += gps) {
+    __syncthreads();                                      // the previous slice's lookups are done
+    const E* src = trow + (int64_t)g0 * c;
+    for (int i = threadIdx.x; i < gps * c; i += 1024) tab[i] = entry_fix<G>(src[i], s);
+    __syncthreads();
+    for (int gl = 0; gl < gps; ++gl) {
+      const uint4 pa = na, pb = nb;
+      if (g0 + gl + 1 < g) {
+        const uint16_t* ip = ptile + (int64_t)(g0 + gl + 1) * kVqTile;
+        na = load_idx(ip, 0);
+        nb = load_idx(ip, 1);
+      }
+      const uint32_t wd[8] = {pa.x, pa.y, pa.z, pa.w, pb.x, pb.y, pb.z, pb.w};
+      F e[16];                                            // sixteen table reads in flight
 #pragma unroll
-    for (int v = 0; v < NG / 8; v += 2) {
-      const uint32_t wd[8] = {pw[v].x, pw[v].y, pw[v].z, pw[v].w, pw[v + 1].x, pw[v + 1].y, pw[v + 1].z, pw[v + 1].w};
-      E e[16];                                            // sixteen table reads in flight
-#pragma unroll
-      for (int b = 0; b < 16; ++b) {
-        const uint32_t code = (wd[b >> 1] >> (16 * (b & 1))) & 0xffffu;
-        e[b] = tab[(int64_t)code * NG + 8 * v + b];
+      for (int tt = 0; tt < 16; ++tt) {
+        uint32_t code = (wd[tt >> 1] >> (16 * (tt & 1))) & 0xffffu;
+        if (code >= (uint32_t)c) code = 0;                // slots past n hold whatever memory held
+        e[tt] = tab[gl * c + code];
       }
 #pragma unroll
-      for (int b = 0; b < 16; b += 2) entry_add2<G>(zi, entry_fix<G>(e[b], s), entry_fix<G>(e[b + 1], s));
+      for (int tt = 0; tt < 16; ++tt) {
+        if constexpr (G == 4) { zi[tt][0] += e[tt].x; zi[tt][1] += e[tt].y; zi[tt][2] += e[tt].z; zi[tt][3] += e[tt].w; }
+        else if constexpr (G == 2) { zi[tt][0] += e[tt].x; zi[tt][1] += e[tt].y; }
+        else { zi[tt][0] += e[tt]; }
+      }
     }
+  }
+  const int64_t j0 = t0 + threadIdx.x * 16;
+#pragma unroll
+  for (int tt = 0; tt < 16; ++tt) {
+    const int64_t j = j0 + tt;
+    if (j >= n) break;
     float z[G];
 #pragma unroll
-    for (int h = 0; h < G; ++h) z[h] = ldexpf((float)zi[h], -s[h]);
+    for (int h = 0; h < G; ++h) z[h] = ldexpf((float)zi[tt][h], -s[h]);
     float best = z[0];
 #pragma unroll
     for (int h = 1; h < G; ++h) best = fmaxf(best, z[h]);
@@ -441,7 +470,9 @@ __global__ __launch_bounds__(256) void vq_export_wide_kernel(int g, int64_t cap,
   const int64_t n = nr.n[row / n_kv_heads];
   const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (gid >= n * g) return;
-  out[(int64_t)row * cap * g + gid] = pcache[(int64_t)row * cap * g + gid];
+  const int64_t slot = gid / g;
+  const int i = (int)(gid % g);
+  out[(int64_t)row * cap * g + gid] = pcache[vq_wide_at(g, vq_tiles(cap), row, slot, i)];
 }
 
 int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, uint8_t* pcache, const void* k_new,
@@ -468,16 +499,17 @@ int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, 
   return HCA_OK;
 }
 
-template <int G, int NG>
-static int32_t scan_wide_launch(const Layout& L, int c, const uint8_t* pcache, float* lut, const NRes& nr, int64_t nmax,
-                                float* sel, float* z_opt, hipStream_t st) {
-  // about eight workgroups of 256 threads per compute unit, shares a multiple of 256 slots
-  int64_t per_row = 2048 / L.rows;
-  if (per_row < 1) per_row = 1;
-  const int64_t per_wg = align_up((nmax + per_row - 1) / per_row, 256);
-  const int64_t chunks = (nmax + per_wg - 1) / per_wg;
-  vq_scan_wide_kernel<G, NG><<<(unsigned)(chunks * L.rows), 256, 0, st>>>(c, L.cap, (const uint16_t*)pcache, lut, nr,
-                                                                          L.n_kv_heads, L.rows, per_wg, sel, z_opt);
+template <int G>
+static int32_t scan_wide_launch(const Layout& L, int g, int c, const uint8_t* pcache, float* lut, const NRes& nr,
+                                int64_t nmax, float* sel, float* z_opt, hipStream_t st) {
+  int gps = 1;                                      // groups per LDS slice: the most that fit 128 KiB
+  while (gps * 2 <= g && (int64_t)gps * 2 * c * G * 4 <= 128 * 1024) gps *= 2;
+  const size_t lds = (size_t)gps * c * G * 4;
+  if (lds > 64 * 1024)
+    HCA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vq_scan_wide_kernel<G>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));   // + 16 B static
+  vq_scan_wide_kernel<G><<<(unsigned)(vq_tiles(nmax) * L.rows), 1024, lds, st>>>(g, c, gps, L.cap, (const uint16_t*)pcache,
+                                                                                 lut, nr, L.n_kv_heads, L.rows, sel, z_opt);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -505,7 +537,7 @@ int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, c
   const uint16_t* qq = (const uint16_t*)q;
   dim3 gl((unsigned)g, (unsigned)L.rows);
   float* amax = lut + (int64_t)L.rows * g * c * L.gqa;   // [rows][g][4], then the exponents [rows][4]
-#define HCA_LUT(G, D) vq_lut_kernel<G, D><<<gl, 256, 0, st>>>(g, c, L.n_kv_heads, centroids, qq, lut, amax)
+#define HCA_LUT(G, D) vq_lut_kernel<G, D><<<gl, 256, 0, st>>>(g, c, L.n_kv_heads, vq_is_wide(L, g, c), centroids, qq, lut, amax)
   if (g == 32) {
     if (L.gqa == 4) HCA_LUT(4, 4); else if (L.gqa == 2) HCA_LUT(2, 4); else HCA_LUT(1, 4);
   } else {
@@ -515,14 +547,9 @@ int32_t launch_vq_score(const Layout& L, int g, int c, const float* centroids, c
   HCA_HIP(hipGetLastError());
   if (nmax == 0) return HCA_OK;
   if (vq_is_wide(L, g, c)) {
-    if (g == 32) {
-      if (L.gqa == 4) return scan_wide_launch<4, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
-      if (L.gqa == 2) return scan_wide_launch<2, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
-      return scan_wide_launch<1, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
-    }
-    if (L.gqa == 4) return scan_wide_launch<4, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
-    if (L.gqa == 2) return scan_wide_launch<2, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
-    return scan_wide_launch<1, 64>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    if (L.gqa == 4) return scan_wide_launch<4>(L, g, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    if (L.gqa == 2) return scan_wide_launch<2>(L, g, c, pcache, lut, nr, nmax, sel, z_opt, st);
+    return scan_wide_launch<1>(L, g, c, pcache, lut, nr, nmax, sel, z_opt, st);
   }
   if (g == 32) {
     if (L.gqa == 4) return scan_launch<4, 32>(L, c, pcache, lut, nr, nmax, sel, z_opt, st);
@@ -612,7 +639,9 @@ extern "C" {
 size_t hca_vq_pcache_bytes(const hca_shape* shape, const hca_vq_codebook* cb) {
   Layout L;
   if (vq_layout(shape, cb, &L, false) != HCA_OK) return 0;
-  return (size_t)L.rows * (size_t)L.cap * (size_t)cb->groups * (vq_is_wide(L, cb->groups, cb->codewords) ? 2 : 1);
+  if (vq_is_wide(L, cb->groups, cb->codewords))      // whole tiles of 16 Ki slots
+    return (size_t)L.rows * (size_t)vq_tiles(L.cap) * kVqTile * (size_t)cb->groups * 2;
+  return (size_t)L.rows * (size_t)L.cap * (size_t)cb->groups;
 }
 
 size_t hca_vq_workspace_bytes(const hca_shape* shape, const hca_vq_codebook* cb, int64_t k_max, int64_t m_max) {

@@ -87,9 +87,11 @@ def test_vq_sizes_and_unsupported_shapes(B):
     for g, c in ((16, 256), (32, 8193), (48, 64), (32, 0)):
         assert B.hca_vq_pcache_bytes(s, B.make_codebook(g, c)) == 0
     # wide form (16-bit indices): more than 256 centroids, or a table beyond 128 KiB of LDS (64 x 256 x 4 heads)
-    assert B.hca_vq_pcache_bytes(s, B.make_codebook(32, 257)) == 2 * 8 * 1000 * 32 * 2
-    assert B.hca_vq_pcache_bytes(s, B.make_codebook(32, 8192)) == 2 * 8 * 1000 * 32 * 2
-    assert B.hca_vq_pcache_bytes(s, B.make_codebook(64, 256)) == 2 * 8 * 1000 * 64 * 2
+    # stored in whole tiles of 16 Ki slots
+    assert B.hca_vq_pcache_bytes(s, B.make_codebook(32, 257)) == 2 * 8 * 16384 * 32 * 2
+    assert B.hca_vq_pcache_bytes(s, B.make_codebook(32, 8192)) == 2 * 8 * 16384 * 32 * 2
+    assert B.hca_vq_pcache_bytes(s, B.make_codebook(64, 256)) == 2 * 8 * 16384 * 64 * 2
+    assert B.hca_vq_pcache_bytes(B.make_shape(1, 32, 8, 16385), B.make_codebook(32, 1024)) == 8 * 2 * 16384 * 32 * 2
     assert B.hca_vq_lut_bytes(s, B.make_codebook(32, 8192)) == 2 * 8 * 32 * 8192 * 4 * 4 + 2 * 8 * (32 + 1) * 4 * 4
     s1 = B.make_shape(1, 8, 8, 1000)                            # one query head per KV head: 64 x 256 fits in LDS
     assert B.hca_vq_pcache_bytes(s1, B.make_codebook(64, 256)) == 8 * 1000 * 64

@@ -136,14 +136,20 @@ def test_vq_one_layer_at_full_size(oracle, c):
     oracle.vq_assign(oc, keys.view(R, n, 128)[:, torch.from_numpy(pick).cuda()].cpu().numpy())
     got = Pg[:, torch.from_numpy(pick).cuda()].cpu().numpy()
     assert np.array_equal(got.view(it) if wide else got, oc.P.astype(it)), "indices differ"
-    assert int(P.view(R, cap, g * ib)[:, n:].max()) == 0
+    if wide:                                          # [R, tiles, g, 16384] uint16: nothing written past n
+        assert int(P.view(torch.int16).view(R, -1, g, 16384)[:, -1, :, n % 16384:].abs().max()) == 0
+    else:
+        assert int(P.view(R, cap, g)[:, n:].max()) == 0
     del oc, Pg
 
     # scores / top-k / attend on a drawn index matrix (zipf-like code popularity, as trained codebooks show)
     pop = rng.permutation(c)
     Pr = pop[np.minimum((rng.pareto(1.2, (R, n, g)) * (8 if not wide else 200)).astype(np.int64), c - 1)].astype(it)
-    if wide:                                          # stored order: 16-bit indices in group order
-        P.view(torch.int16).view(R, cap, g)[:, :n] = torch.from_numpy(Pr.view(np.int16)).cuda()
+    if wide:   # stored order (include/hca.h): uint16 [row][tile][group][16384], slot = tile * 16384 + position in the tile
+        assert n % 16384 == 0
+        Pt = torch.from_numpy(Pr.view(np.int16)).cuda().view(R, n // 16384, 16384, g).transpose(2, 3)
+        P.view(torch.int16).view(R, -1, g, 16384)[:, :n // 16384] = Pt
+        del Pt
     else:   # stored order (include/hca.h): byte p of slot j holds the index of group 16*(p//16) + (p+j)%16
         pp, jj = np.arange(g)[None, :], np.arange(n)[:, None]
         where = (pp & ~15) | ((pp + jj) & 15)

@@ -43,7 +43,8 @@ class _State:
         self.cb = B.make_codebook(g, c, self.cen)
         self.wide = c > 256 or g * c * (hq // hkv) > 32768          # 16-bit indices, table read through L2
         self.P = torch.full((B.hca_vq_pcache_bytes(self.shape, self.cb),), 0xEE, dtype=torch.uint8, device="cuda")
-        assert self.P.numel() == batch * hkv * cap * g * (2 if self.wide else 1)
+        tiled = -(-cap // 16384) * 16384                              # the wide form stores whole tiles of 16 Ki slots
+        assert self.P.numel() == batch * hkv * (tiled * g * 2 if self.wide else cap * g)
         self.lut = torch.zeros(B.hca_vq_lut_bytes(self.shape, self.cb) // 4, dtype=torch.float32, device="cuda")
         self.sel = torch.full((batch, hkv, cap), -7.0, dtype=torch.float32, device="cuda")
         self.z = torch.full((batch, hq, cap), -7.0, dtype=torch.float32, device="cuda")
@@ -80,7 +81,10 @@ class _State:
         """(T fp32 [R*G, g, c], exponents int32 [R*G]) from the library's lut buffer."""
         R, G = self.batch * self.hkv, self.hq // self.hkv
         flat = self.lut.cpu().numpy()
-        T = flat[:R * self.c * self.g * G].reshape(R, self.c, self.g, G).transpose(0, 3, 2, 1).reshape(R * G, self.g, self.c)
+        if self.wide:                                                 # [R, g, c, G]
+            T = flat[:R * self.c * self.g * G].reshape(R, self.g, self.c, G).transpose(0, 3, 1, 2).reshape(R * G, self.g, self.c)
+        else:                                                         # [R, c, g, G]
+            T = flat[:R * self.c * self.g * G].reshape(R, self.c, self.g, G).transpose(0, 3, 2, 1).reshape(R * G, self.g, self.c)
         sexp = flat[R * self.g * (self.c * G + 4):].view(np.int32).reshape(R, 4)[:, :G].reshape(R * G)
         return np.ascontiguousarray(T), sexp
 
@@ -109,7 +113,11 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
     Pg = st.P_rows()
     assert np.array_equal(Pg[:, :n_used], oc.P[:, :n_used].astype(st.idx_dtype()))
     assert np.all(Pg[:, n_used:] == st.fill())
-    assert np.all(st.P.cpu().numpy().reshape(R, cap, -1)[:, n_used:] == 0xEE)  # nothing written past n
+    if st.wide:                                                           # [R, tiles, g, 16384] uint16
+        raw = st.P.cpu().numpy().view(np.uint16).reshape(R, -1, g, 16384).transpose(0, 1, 3, 2).reshape(R, -1, g)
+        assert np.all(raw[:, n_used:] == 0xEEEE)
+    else:
+        assert np.all(st.P.cpu().numpy().reshape(R, cap, -1)[:, n_used:] == 0xEE)  # nothing written past n
     assert np.array_equal(st.pos.cpu().numpy().reshape(R, cap)[:, :n_used], np.tile(np.arange(n_used), (R, 1)))
     assert np.all(st.acc.cpu().numpy().reshape(R, cap)[:, :n_used] == 0) and np.all(st.acc.cpu().numpy().reshape(R, cap)[:, n_used:] == 9)
 
