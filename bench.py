@@ -537,9 +537,13 @@ def paper_form_probe(w, streams, layers=8, steps=6, g=32, c=256, tau=0.9):
         d = S.make_layer(w, l, device="cuda", want_values=True)
         cen = []
         for h in range(w.n_kv_heads):
-            kval = d["keys"][0, h, :4096].cpu().numpy()
+            kval = d["keys"][0, h, :(4096 if c <= 256 else 32768)].cpu().numpy()
             init = np.stack([rng.choice(kval.shape[0], c, replace=False) for _ in range(g)]).astype(np.int32)
-            cen.append(B.hca_vq_train(kval, g, c, init, 2)[0])
+            if c <= 256:
+                cen.append(B.hca_vq_train(kval, g, c, init, 2)[0])
+            else:      # sampled sub-vectors as centroids: the host trainer would take minutes at this size
+                sub = kval.astype(np.float32).reshape(kval.shape[0], g, 128 // g)
+                cen.append(np.stack([sub[init[i], i] for i in range(g)]))
         cens.append(torch.from_numpy(np.stack(cen)).cuda())
         cbs.append(B.make_codebook(g, c, cens[-1]))
         P.append(torch.empty(B.hca_vq_pcache_bytes(shape, cbs[-1]), dtype=torch.uint8, device="cuda"))
@@ -559,7 +563,7 @@ def paper_form_probe(w, streams, layers=8, steps=6, g=32, c=256, tau=0.9):
     count = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
     y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device="cuda")
     vnew = torch.zeros(w.batch, w.n_kv_heads, 2 * steps, 128, dtype=torch.float16, device="cuda")
-    ws = torch.empty(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.hca_vq_workspace_bytes(shape, cbs[0], w.k, 1), dtype=torch.uint8, device="cuda")
     sm = 1.0 / (128.0 ** 0.5)
     kept = []
 
@@ -600,10 +604,10 @@ def paper_form_probe(w, streams, layers=8, steps=6, g=32, c=256, tau=0.9):
     for i in range(4):
         a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device="cuda")
         b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device="cuda")
-        cws = torch.empty(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+        cws = torch.empty(B.hca_vq_workspace_bytes(shape, cbs[0], w.k, 1), dtype=torch.uint8, device="cuda")
         keep += [a, b, cws]
         d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), cws.data_ptr()
-    wt = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device="cuda")
+    wt = torch.zeros(B.hca_vq_workspace_bytes(shape, cbs[0], w.k, 1), dtype=torch.uint8, device="cuda")
     d.ws_topk = wt.data_ptr()
     d.vq_groups, d.vq_codewords, d.topp_tau = g, c, tau
     pl = B.hca_pipeline_create(shape, layers, d, 0)
@@ -919,6 +923,10 @@ def main():
         paper_form = paper_form_probe(S.CONFIGS[4], (main_s[0], extra[0], gath_s[0], extra[1]))
         log(f"paper-form decode step at 1M: {paper_form['ms_per_layer']:.3f} ms per layer on one stream, "
             f"{paper_form['pipelined_ms_per_layer']:.3f} ms through the step driver")
+        # the same with the paper's own codebook size (g = 32, c = 8192: 16-bit indices, table through LDS in slices)
+        paper_form["c8192"] = paper_form_probe(S.CONFIGS[4], (main_s[0], extra[0], gath_s[0], extra[1]), layers=4, c=8192)
+        log(f"paper-form decode step at 1M, c = 8192: {paper_form['c8192']['ms_per_layer']:.3f} ms per layer on one "
+            f"stream, {paper_form['c8192']['pipelined_ms_per_layer']:.3f} ms through the step driver")
         cpu_split = cpu_split_probe(S.CONFIGS[4])
         log(f"value side at 1M, k 4096: gather + attend {cpu_split['gather_plus_attend_ms']:.3f} ms; paper's split "
             f"{cpu_split['split_gpu_weights_ms']:.3f} ms on the GPU + {cpu_split['split_host_sum_ms']:.3f} ms on the host")

@@ -101,10 +101,10 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
   }
 }
 
-// Few tokens per call (decode appends): one workgroup per (token, row); a wave takes every fourth group
-// and spreads the group's centroids over its lanes (lane, lane + 64, ...), then the lanes' candidates are
-// reduced by (distance, index): the smaller distance wins, equal distances go to the lower index - the
-// same winner as the ascending scan with a strict comparison.
+// Few tokens per call (decode appends): one workgroup per (token, row, four groups); a wave takes one group
+// and spreads the group's centroids over its lanes (lane, lane + 64, ...; four distances in flight per lane),
+// then the lanes' candidates are reduced by (distance, index): the smaller distance wins, equal distances go
+// to the lower index - the same winner as the ascending scan with a strict comparison.
 template <int DBAR, bool WIDE>
 __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int n_kv_heads, int64_t cap,
                                                               const float* __restrict__ centroids,
@@ -119,21 +119,35 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
   const int64_t slot = nr.n[b] + tt;
   const uint16_t* src = k_new + ((int64_t)row * T + tt) * kHeadDim;
   const float* cb = centroids + (int64_t)(row % n_kv_heads) * g * c * DBAR;
-  for (int i = w; i < g; i += 4) {
+  const int i = blockIdx.z * 4 + w;
+  if (i < g) {
     float x[DBAR];
 #pragma unroll
     for (int dd = 0; dd < DBAR; ++dd) x[dd] = h2f(src[i * DBAR + dd]);
     float bd = INFINITY;
     int best = 0x7fffffff;
-    for (int cc = lane; cc < c; cc += 64) {
-      const float* cv = cb + ((int64_t)i * c + cc) * DBAR;
-      float d = 0.f;
+    for (int c0 = lane; c0 < c; c0 += 256) {
+      float cv[4][DBAR];
 #pragma unroll
-      for (int dd = 0; dd < DBAR; ++dd) {
-        const float e = x[dd] - cv[dd];
-        d = fmaf(e, e, d);
+      for (int u = 0; u < 4; ++u) {
+        const int cc = c0 + 64 * u < c ? c0 + 64 * u : c0;
+        const float* p = cb + ((int64_t)i * c + cc) * DBAR;
+#pragma unroll
+        for (int dd = 0; dd < DBAR; ++dd) cv[u][dd] = p[dd];
       }
-      if (d < bd || best == 0x7fffffff) { bd = d; best = cc; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int cc = c0 + 64 * u;
+        if (cc < c) {
+          float d = 0.f;
+#pragma unroll
+          for (int dd = 0; dd < DBAR; ++dd) {
+            const float e = x[dd] - cv[u][dd];
+            d = fmaf(e, e, d);
+          }
+          if (d < bd || best == 0x7fffffff) { bd = d; best = cc; }
+        }
+      }
     }
 #pragma unroll
     for (int o = 32; o >= 1; o >>= 1) {
@@ -146,7 +160,7 @@ __global__ __launch_bounds__(256) void vq_assign_small_kernel(int g, int c, int 
       else pcache[((int64_t)row * cap + slot) * g + vq_byte_of(i, slot)] = (uint8_t)best;
     }
   }
-  if (threadIdx.x == 0) {
+  if (threadIdx.x == 0 && blockIdx.z == 0) {
     if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
     if (pos != nullptr) pos[(int64_t)row * cap + slot] = (int32_t)(vrow0.n[b] + tt);
   }
@@ -488,7 +502,7 @@ int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, 
     else KERNEL<2, false><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);               \
   } while (0)
   if (T <= 8) {                                     // decode appends: parallel over centroids, not over tokens
-    dim3 gs((unsigned)T, (unsigned)L.rows);
+    dim3 gs((unsigned)T, (unsigned)L.rows, (unsigned)(g / 4));
     HCA_ASSIGN(vq_assign_small_kernel, gs);
   } else {
     dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 16));
