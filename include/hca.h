@@ -224,7 +224,8 @@ typedef struct {
   /* The paper's own form of the step (Sec. 3.1, 3.2).  vq_groups > 0: the key side is the codebook form -
      hca_vq_assign, hca_vq_score, hca_vq_attend_gathered, hca_vq_evict (in place: the spare_* fields must be
      NULL) instead of their uniform-code counterparts, with the codebook shape given here and each layer's
-     centroids and table in its hca_layer.  topp_tau > 0: the selection is Eq. 4 (hca_topp with this tau and the
+     centroids and table in its hca_layer; the workspaces above are then sized with hca_vq_workspace_bytes.
+     topp_tau > 0: the selection is Eq. 4 (hca_topp with this tau and the
      step's k as the cut-off) instead of top-k.  The two are independent. */
   int32_t vq_groups, vq_codewords;
   double topp_tau;
