@@ -123,17 +123,21 @@ __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __r
                                                     const uint32_t* __restrict__ first_hole) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t d = d0 + (gid >> 2);
-  const int j = (int)(gid & 3);
-  if (d >= d1) return;
-  // in place: slots below the block of the first dropped slot already hold their own data
-  if (first_hole != nullptr && d < (int64_t)(first_hole[4 * row + 2] & ~(uint32_t)(L.tpb - 1))) return;
-  const int64_t s = kept[(int64_t)row * M + d];
+  // in place: slots below the block of the first dropped slot already hold their own data, so the walk starts
+  // there (the grid is modest and strides: when the dropped slots sit near the end, as they do when ties go
+  // against the higher slot, almost nothing is launched in vain)
+  if (first_hole != nullptr) {
+    const int64_t lo = (int64_t)(first_hole[4 * row + 2] & ~(uint32_t)(L.tpb - 1));
+    if (lo > d0) d0 = lo;
+  }
   const uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
   const uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
   uint8_t* cdst = e.codes + (int64_t)row * e.codes_row;
   uint8_t* mdst = e.meta + (int64_t)row * e.meta_row;
+  for (int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x; gid < (d1 - d0) * 4; gid += (int64_t)gridDim.x * 256) {
+  const int64_t d = d0 + (gid >> 2);
+  const int j = (int)(gid & 3);
+  const int64_t s = kept[(int64_t)row * M + d];
   if (BITS == 4) {
     const uint4 w = *reinterpret_cast<const uint4*>(crow + (s >> 4) * kBlockBytes + ((s & 15) + 16 * j) * 16);
     *reinterpret_cast<uint4*>(cdst + (d >> 4) * kBlockBytes + ((d & 15) + 16 * j) * 16) = w;
@@ -150,6 +154,7 @@ __global__ __launch_bounds__(256) void evict_gather(Layout L, const uint8_t* __r
   }
   if (j == 1) e.acc[(int64_t)row * e.ap_row + d] = acc[(int64_t)row * L.cap + s];
   if (j == 2) e.pos[(int64_t)row * e.ap_row + d] = pos[(int64_t)row * L.cap + s];
+  }
 }
 
 // staging -> front of the cache (whole blocks; slots past M in the last block are dead).
@@ -159,18 +164,18 @@ __global__ __launch_bounds__(256) void evict_copyback(Layout L, uint8_t* __restr
                                                       const uint32_t* __restrict__ first_hole) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const int64_t d_start = (int64_t)(first_hole[4 * row + 2] & ~(uint32_t)(L.tpb - 1));   // block-aligned
   const int64_t b_start = d_start / L.tpb;
   uint4* cdst = reinterpret_cast<uint4*>(kcache + (int64_t)row * L.codes_row_bytes());
   uint4* mdst = reinterpret_cast<uint4*>(kcache + L.meta_off + (int64_t)row * L.meta_row_bytes());
   const uint4* csrc = reinterpret_cast<const uint4*>(e.codes + (int64_t)row * mblk * kBlockBytes);
   const uint4* msrc = reinterpret_cast<const uint4*>(e.meta + (int64_t)row * mblk * kMetaBytes);
-  if (gid >= b_start * (kBlockBytes / 16) && gid < mblk * (kBlockBytes / 16)) cdst[gid] = csrc[gid];
-  if (gid >= b_start * (kMetaBytes / 16) && gid < mblk * (kMetaBytes / 16)) mdst[gid] = msrc[gid];
-  if (gid >= d_start && gid < M) {
-    acc[(int64_t)row * L.cap + gid] = e.acc[(int64_t)row * M + gid];
-    pos[(int64_t)row * L.cap + gid] = e.pos[(int64_t)row * M + gid];
+  const int64_t stride = (int64_t)gridDim.x * 256, t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  for (int64_t i = b_start * (kBlockBytes / 16) + t; i < mblk * (kBlockBytes / 16); i += stride) cdst[i] = csrc[i];
+  for (int64_t i = b_start * (kMetaBytes / 16) + t; i < mblk * (kMetaBytes / 16); i += stride) mdst[i] = msrc[i];
+  for (int64_t i = d_start + t; i < M; i += stride) {
+    acc[(int64_t)row * L.cap + i] = e.acc[(int64_t)row * M + i];
+    pos[(int64_t)row * L.cap + i] = e.pos[(int64_t)row * M + i];
   }
 }
 
@@ -264,7 +269,11 @@ static int32_t evict_prepare(const Layout& L, void* kcache, float* acc, int32_t*
 static int32_t evict_move(const Layout& L, void* kcache, float* acc, int32_t* pos, const EvictPlan& pl, int64_t d0,
                           int64_t d1, hipStream_t st) {
   if (!pl.any || d1 <= d0) return HCA_OK;
-  dim3 gg((unsigned)(((d1 - d0) * 4 + 255) / 256), (unsigned)L.rows);
+  // at most 2048 workgroups in all: the kernels stride over what there is to move
+  const int64_t cap_wg = L.rows >= 2048 ? 1 : 2048 / L.rows;
+  int64_t wg = ((d1 - d0) * 4 + 255) / 256;
+  if (wg > cap_wg) wg = cap_wg;
+  dim3 gg((unsigned)wg, (unsigned)L.rows);
   if (L.bits == 4)
     evict_gather<4><<<gg, 256, 0, st>>>(L, (const uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, d0, d1, pl.kept, pl.d,
                                         pl.oop ? nullptr : pl.state);
@@ -274,7 +283,9 @@ static int32_t evict_move(const Layout& L, void* kcache, float* acc, int32_t* po
   if (!pl.oop && d1 == pl.M) {
     int64_t items = pl.mblk * (kBlockBytes / 16);
     if (items < pl.M) items = pl.M;
-    dim3 gc((unsigned)((items + 255) / 256), (unsigned)L.rows);
+    int64_t wc = (items + 255) / 256;
+    if (wc > cap_wg) wc = cap_wg;
+    dim3 gc((unsigned)wc, (unsigned)L.rows);
     evict_copyback<<<gc, 256, 0, st>>>(L, (uint8_t*)kcache, acc, pos, L.n_kv_heads, pl.sr, pl.M, pl.mblk, pl.e, pl.state);
   }
   HCA_HIP(hipGetLastError());
@@ -343,23 +354,24 @@ __global__ __launch_bounds__(256) void vq_evict_gather(int sb, int sp0, int db, 
                                                        int64_t dst_row, const uint32_t* __restrict__ first_hole) {
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t d = gid / pieces;
-  const int j = (int)(gid % pieces);
-  if (d >= M) return;
-  if (first_hole != nullptr && d < (int64_t)first_hole[4 * row + 2]) return;   // in place: this slot keeps its row
-  const int64_t s = kept[(int64_t)row * M + d];
-  if (form == 0) {
-    // a rotated record's rotation follows its slot: byte p of slot d is byte (p + d - s) % 16 of slot s
-    const uint4 v = reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * sb)[sp0 + j];
-    reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = rotate_bytes(v, (int)((d - s) & 15));
-  } else {
-    const uint4 v = vq_wide_read8(reinterpret_cast<const uint16_t*>(pcache), g, vq_tiles(cap), row, s, 8 * (sp0 + j));
-    if (form == 1) vq_wide_write8(reinterpret_cast<uint16_t*>(pdst), g, vq_tiles(dcap), row, d, 8 * (dp0 + j), v);
-    else reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = v;
+  // in place: slots below the first dropped one keep their rows, the walk (a modest grid that strides) starts there
+  const int64_t lo = first_hole != nullptr ? (int64_t)first_hole[4 * row + 2] : 0;
+  for (int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x; gid < (M - lo) * pieces; gid += (int64_t)gridDim.x * 256) {
+    const int64_t d = lo + gid / pieces;
+    const int j = (int)(gid % pieces);
+    const int64_t s = kept[(int64_t)row * M + d];
+    if (form == 0) {
+      // a rotated record's rotation follows its slot: byte p of slot d is byte (p + d - s) % 16 of slot s
+      const uint4 v = reinterpret_cast<const uint4*>(pcache + ((int64_t)row * cap + s) * sb)[sp0 + j];
+      reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = rotate_bytes(v, (int)((d - s) & 15));
+    } else {
+      const uint4 v = vq_wide_read8(reinterpret_cast<const uint16_t*>(pcache), g, vq_tiles(cap), row, s, 8 * (sp0 + j));
+      if (form == 1) vq_wide_write8(reinterpret_cast<uint16_t*>(pdst), g, vq_tiles(dcap), row, d, 8 * (dp0 + j), v);
+      else reinterpret_cast<uint4*>(pdst + ((int64_t)row * dst_row + d) * db)[dp0 + j] = v;
+    }
+    if (sp0 == 0 && j == 0) adst[(int64_t)row * dst_row + d] = acc[(int64_t)row * cap + s];
+    if (sp0 == 0 && (j == 1 || pieces == 1)) odst[(int64_t)row * dst_row + d] = pos[(int64_t)row * cap + s];
   }
-  if (sp0 == 0 && j == 0) adst[(int64_t)row * dst_row + d] = acc[(int64_t)row * cap + s];
-  if (sp0 == 0 && (j == 1 || pieces == 1)) odst[(int64_t)row * dst_row + d] = pos[(int64_t)row * cap + s];
 }
 
 // Copies a window of the first cnt[b] slots of every row that `which` selects from (src, row stride ssrc
@@ -381,22 +393,22 @@ __global__ __launch_bounds__(256) void vq_evict_copy_rows(int sb, int sp0, int d
   const int b = row / n_kv_heads;
   if ((sr.want[b] >= 0) != compacted) return;
   const int64_t m = cnt.n[b];
-  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t d = gid / pieces;
-  const int j = (int)(gid % pieces);
   const int64_t lo = first_hole != nullptr ? (int64_t)first_hole[4 * row + 2] : 0;
-  if (d < lo || d >= m) return;
-  if (form == 0) {
-    reinterpret_cast<uint4*>(pdst + ((int64_t)row * sdst + d) * db)[dp0 + j] =
-        reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
-  } else {
-    const uint4 v = form == 1 ? vq_wide_read8(reinterpret_cast<const uint16_t*>(psrc), g, vq_tiles(scap), row, d, 8 * (sp0 + j))
-                              : reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
-    vq_wide_write8(reinterpret_cast<uint16_t*>(pdst), g, vq_tiles(dcap), row, d, 8 * (dp0 + j), v);
-  }
-  if (dp0 == 0 && j == 0) {
-    adst[(int64_t)row * sdst + d] = asrc[(int64_t)row * ssrc + d];
-    odst[(int64_t)row * sdst + d] = osrc[(int64_t)row * ssrc + d];
+  for (int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x; gid < (m - lo) * pieces; gid += (int64_t)gridDim.x * 256) {
+    const int64_t d = lo + gid / pieces;
+    const int j = (int)(gid % pieces);
+    if (form == 0) {
+      reinterpret_cast<uint4*>(pdst + ((int64_t)row * sdst + d) * db)[dp0 + j] =
+          reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
+    } else {
+      const uint4 v = form == 1 ? vq_wide_read8(reinterpret_cast<const uint16_t*>(psrc), g, vq_tiles(scap), row, d, 8 * (sp0 + j))
+                                : reinterpret_cast<const uint4*>(psrc + ((int64_t)row * ssrc + d) * sb)[sp0 + j];
+      vq_wide_write8(reinterpret_cast<uint16_t*>(pdst), g, vq_tiles(dcap), row, d, 8 * (dp0 + j), v);
+    }
+    if (dp0 == 0 && j == 0) {
+      adst[(int64_t)row * sdst + d] = asrc[(int64_t)row * ssrc + d];
+      odst[(int64_t)row * sdst + d] = osrc[(int64_t)row * ssrc + d];
+    }
   }
 }
 
@@ -421,8 +433,10 @@ int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* a
   const int pieces = rb / 16;
   EvictWs e;                                // the staging holds 64 bytes per slot (sized for uniform codes)
   carve(&e, ws, L, M);
+  const int64_t cap_wg = L.rows >= 2048 ? 1 : 2048 / L.rows;   // at most 2048 workgroups in all: the kernels stride
+  auto wgs = [&](int64_t items) { const int64_t w = (items + 255) / 256; return (unsigned)(w > cap_wg ? cap_wg : (w < 1 ? 1 : w)); };
   if (oop && carry && nmax > 0) {
-    dim3 gr((unsigned)((nmax * pieces + 255) / 256), (unsigned)L.rows);
+    dim3 gr(wgs(nmax * pieces), (unsigned)L.rows);
     vq_evict_copy_rows<<<gr, 256, 0, st>>>(rb, 0, rb, 0, pieces, wide ? 1 : 0, g, L.cap, L.cap, L.n_kv_heads, sr, false, nr,
                                            nullptr, pcache, acc, pos, L.cap, pcache_dst, acc_dst, pos_dst, L.cap);
   }
@@ -438,7 +452,7 @@ int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* a
   dim3 g1((unsigned)p.nchunks, (unsigned)L.rows);
   evict_positions<<<g1, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kp);
   if (oop) {
-    dim3 gg((unsigned)((M * pieces + 255) / 256), (unsigned)L.rows);
+    dim3 gg(wgs(M * pieces), (unsigned)L.rows);
     vq_evict_gather<<<gg, 256, 0, st>>>(rb, 0, rb, 0, pieces, wide ? 1 : 0, g, L.cap, L.cap, pcache, acc, pos, L.n_kv_heads,
                                         sr, M, kp, pcache_dst, acc_dst, pos_dst, L.cap, nullptr);
   } else {
@@ -447,7 +461,7 @@ int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* a
     for (int b = 0; b < kMaxBatch; ++b) cnt.n[b] = M;
     for (int p0 = 0; p0 < pieces; p0 += 4) {
       const int wp = pieces - p0 < 4 ? pieces - p0 : 4;
-      dim3 gg((unsigned)((M * wp + 255) / 256), (unsigned)L.rows);
+      dim3 gg(wgs(M * wp), (unsigned)L.rows);
       vq_evict_gather<<<gg, 256, 0, st>>>(rb, p0, 64, 0, wp, wide ? 2 : 0, g, L.cap, L.cap, pcache, acc, pos, L.n_kv_heads, sr,
                                           M, kp, e.codes, e.acc, e.pos, M, p.state);
       vq_evict_copy_rows<<<gg, 256, 0, st>>>(64, 0, rb, p0, wp, wide ? 2 : 0, g, M, L.cap, L.n_kv_heads, sr, true, cnt,
