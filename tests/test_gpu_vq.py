@@ -137,7 +137,8 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
 
 
 @pytest.mark.parametrize("g,c,G,n,k", [(32, 256, 4, 9000, 512), (64, 128, 4, 3001, 100), (32, 64, 2, 5000, 5000),
-                                       (32, 256, 1, 700, 1), (32, 1024, 4, 6000, 300), (64, 512, 2, 2500, 2500)])
+                                       (32, 256, 1, 700, 1), (32, 1024, 4, 6000, 300), (64, 512, 2, 2500, 2500),
+                                       (32, 512, 4, 20000, 700)])     # the last: two index tiles, the second ragged
 def test_vq_decode_path_matches_oracle(B, oracle, g, c, G, n, k):
     """assign -> table + scores -> top-k -> gather (host + HBM rows) -> attend with accumulated scores."""
     rng = np.random.default_rng(n + k)
