@@ -29,7 +29,7 @@ def log(*a):
 class Model:
     """All layers of one workload: per-layer key cache / acc / pos / host values, shared scratch."""
 
-    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3, evict_spare=False):
+    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3, evict_spare=False, fused=False):
         import torch
         from paper_2507_19823_amd import binding as B
         self.torch, self.B, self.w = torch, B, w
@@ -55,8 +55,12 @@ class Model:
         self.v_host = [None] * layers
         self.v_hbm = [torch.zeros(w.batch, w.n_kv_heads, self.vnew, 128, dtype=torch.float16, device=dev)
                       for _ in range(layers)]
+        # score buffers of the pipeline slots; with the fused scan + top-k a selection workspace per slot instead
+        self.fused = fused
         self.sels = [torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev)
-                     for _ in range(max(3, n_sel))]
+                     for _ in range(1 if fused else max(3, n_sel))]
+        self.ws_sel = [torch.empty(B.hca_workspace_bytes(self.shape, w.k, 1), dtype=torch.uint8, device=dev)
+                       for _ in range(max(3, n_sel) if fused else 0)]
         self.sel = self.sels[0]
         self.sel_ev = [dict(score_done=torch.cuda.Event(), sel_free=torch.cuda.Event()) for _ in range(3)]
         self.ws_main = torch.empty(B.hca_workspace_bytes(self.shape, w.k, self.n0), dtype=torch.uint8, device=dev)
@@ -129,6 +133,18 @@ class Model:
 
     def scan_select(self, l, t, st, pipe, ev=None):
         """a1 + a2 + a3 of layer l, decode step t, on stream st."""
+        if self.fused:
+            B, w, n = self.B, self.w, self.n[l]
+            B.hca_quantize_keys(self.shape, self.kcache[l], self.k_new[t][l], 1, n, self.acc[l], self.pos[l],
+                                [self.n0 + t] * w.batch, st)
+            self.n[l] = n = [x + 1 for x in n]
+            if ev is not None:
+                ev[0].record(st)
+            B.hca_score_topk(self.shape, self.kcache[l], self.q[t][l], n, w.k, pipe["idx"], pipe["count"],
+                             self.ws_main, st)
+            if ev is not None:
+                ev[1].record(st)
+            return
         self.scan(l, t, st, self.sel, ev)
         self.B.hca_topk(self.shape, self.sel, self.n[l], self.w.k, pipe["idx"], pipe["count"], self.ws_main, st)
 
@@ -172,9 +188,15 @@ class Model:
         d = B.hca_pipeline_desc()
         d.stream_scan, d.stream_topk = sa.cuda_stream, sb.cuda_stream
         d.stream_gather, d.stream_attend = sg.cuda_stream, sc.cuda_stream
-        for i, sbuf in enumerate(self.sels):
-            d.sel[i] = sbuf.data_ptr()
-        d.n_sel = len(self.sels)
+        if self.fused:
+            d.fused_select = 1
+            for i, wbuf in enumerate(self.ws_sel):
+                d.ws_select[i] = wbuf.data_ptr()
+            d.n_sel = len(self.ws_sel)
+        else:
+            for i, sbuf in enumerate(self.sels):
+                d.sel[i] = sbuf.data_ptr()
+            d.n_sel = len(self.sels)
         d.timing_layer_stride = timing_stride
         for i in range(4):
             d.idx[i] = self.pipe[i]["idx"].data_ptr()
@@ -269,7 +291,7 @@ class Model:
             self.attend_evict(prev, t, main, pp)
 
 
-def per_layer_latency(cfg, main, side, link_peak, iters=8):
+def per_layer_latency(cfg, main, side, link_peak, iters=8, fused=False, streams=None):
     """One layer of workload `cfg` (synth_inputs.CONFIGS), decode steps issued back to back on one stream with no
     overlap between layers: time from query ready to y ready (quantise-append, scan, top-k, gather,
     attend).  For config 5 the cache is first evicted to its 50% cap, as the config says."""
@@ -278,9 +300,9 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8):
     from paper_2507_19823_amd import binding as B
     w = S.CONFIGS[cfg]
     warm = 3
-    m = Model(w, 1, 0, iters + warm)
+    m = Model(w, 1, 0, 2 * iters + warm, fused=fused)
     m.build(1)
-    m.make_steps(iters + warm)
+    m.make_steps(2 * iters + warm)
     t = 0
     for _ in range(2):
         m.decode_step(t, main, side, overlap=False)
@@ -305,6 +327,7 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8):
     scan = sorted(x[0][0].elapsed_time(x[0][1]) for x in sc)[iters // 2]
     code_bytes = 128 * w.bits // 8 + (128 // w.group) * 4
     scan_bytes = w.batch * w.n_kv_heads * (resident + iters // 2) * (code_bytes + 4)
+    score_topk_ms = scan if fused else None          # fused: the bracket holds the whole hca_score_topk call
     # the gather alone, as the path issues it
     pipe = m.pipe[0]
     g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -315,7 +338,18 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8):
     torch.cuda.synchronize()
     gms = g0.elapsed_time(g1) / iters
     gbytes = w.batch * w.n_kv_heads * w.k * 256
-    out = {"workload": w.name, "resident_tokens": resident, "ms_per_layer": lat,
+    if fused and streams is not None:
+        # the selecting scan alone: the same layer through the step driver (one layer: nothing overlaps), timed
+        # by the driver's HIP events around the launch
+        m.native_pipeline(*streams, iters)
+        for i in range(iters):
+            m.decode_step_native(t + iters + i, i)
+            torch.cuda.synchronize()
+        per = sorted(B.hca_pipeline_scan_ms(m.pl, i, 1)[0] for i in range(iters))
+        scan = per[iters // 2]                       # HIP events around the launch
+        scan_bytes = w.batch * w.n_kv_heads * (resident + iters + iters // 2) * code_bytes
+        B.hca_pipeline_destroy(m.pl)
+    out = {"workload": w.name, "resident_tokens": resident, "ms_per_layer": lat, "score_topk_ms": score_topk_ms,
            "key_scan_ms": scan, "key_scan_GBs": scan_bytes / scan / 1e6, "key_scan_frac_of_hbm_peak": scan_bytes / scan / 1e6 / HBM_PEAK_GBS,
            "gather_ms": gms, "gather_GBs": gbytes / gms / 1e6, "gather_frac_of_link_peak": gbytes / gms / 1e6 / link_peak}
     del m
@@ -735,6 +769,38 @@ def scan_only(w, iters):
                       "GBs": by / ms / 1e6, "frac": by / ms / 1e6 / HBM_PEAK_GBS}), flush=True)
 
 
+def select_only(w, iters):
+    """hca_score_topk alone on one layer (two cache copies alternate): the selecting scan and the small kernels
+    around it, preceded by the same 1 GiB calibration copy as --mode scan."""
+    import torch
+    from paper_2507_19823_amd import binding as B
+    m = Model(w, 2, 0, 1, fused=True)
+    m.build(0)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)                                    # calibration dispatch: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    q = m.layer0["q"].cuda()
+    pipe = m.pipe[0]
+
+    def call(i):
+        B.hca_score_topk(m.shape, m.kcache[i & 1], q, m.n[0], w.k, pipe["idx"], pipe["count"], m.ws_main)
+
+    for i in range(3):
+        call(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        call(i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    code_bytes = 128 * w.bits // 8 + (128 // w.group) * 4
+    print(json.dumps({"mode": "select", "workload": w.name, "score_topk_ms": ms,
+                      "scan_algorithmic_bytes_per_launch": w.batch * w.n_kv_heads * w.n * code_bytes}), flush=True)
+
+
 def gather_only(w, iters):
     """Value gather alone at the workload's shape: k selected rows of 256 B per (sequence, KV head) read from a
     pinned host store at random rows (drawn here; the store's contents do not matter), against the host link's
@@ -840,6 +906,9 @@ def main():
                     help="native pipeline: evict out of place into a spare buffer set, in slices behind the attends "
                          "(default: in place, which moves only the slots from the first dropped one on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-fused-select", action="store_true",
+                    help="scan and top-k as two calls with a score buffer between them (hca_score_qkeys, hca_topk) "
+                         "instead of hca_score_topk; always so with --pipeline staged / gather / none")
     ap.add_argument("--sel-buffers", type=int, default=32,
                     help="score buffers of the native step driver (one per layer: the scan never waits for one)")
     ap.add_argument("--bracket-stride", type=int, default=4,
@@ -853,8 +922,9 @@ def main():
                     help="row splits tried by the pipelined per-layer latency probe")
     ap.add_argument("--stages", type=int, default=4, choices=[3, 4],
                     help="native pipeline: 4 = scan | top-k | gather | attend; 3 = top-k shares the scan stream")
-    ap.add_argument("--mode", default="step", choices=["step", "scan", "vq", "gather"],
+    ap.add_argument("--mode", default="step", choices=["step", "scan", "select", "vq", "gather"],
                     help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration; "
+                         "select: the same for hca_score_topk (selecting scan, sampling, selection); "
                          "vq: the codebook form of the key path (assignment, table, lookup scan) on one layer; "
                          "gather: only the value gather at the workload's shape, against the host link's copy rate")
     args = ap.parse_args()
@@ -878,6 +948,8 @@ def main():
     L = args.layers or (16 if args.config == 2 else w.layers)
     if args.mode == "scan":
         return scan_only(w, args.steps)
+    if args.mode == "select":
+        return select_only(w, args.steps)
     if args.mode == "gather":
         return gather_only(w, args.steps)
     if args.mode == "vq":
@@ -907,6 +979,14 @@ def main():
             latency[name] = per_layer_latency(c, main_s[0], gath_s[0], link_peak)
             latency[name]["ms_per_layer_serial"] = latency[name]["ms_per_layer"]
             log(f"latency probe {name}: {latency[name]['ms_per_layer']:.3f} ms per layer, stages one after another")
+            # the same with scan and top-k as one call (hca_score_topk); key_scan_ms is then the whole call
+            f = per_layer_latency(c, main_s[0], gath_s[0], link_peak, fused=True,
+                                  streams=(main_s[0], extra[0], gath_s[0], extra[1]))
+            latency[name]["fused_select"] = {"ms_per_layer": f["ms_per_layer"], "score_topk_ms": f["score_topk_ms"],
+                                             "select_scan_ms": f["key_scan_ms"], "select_scan_GBs": f["key_scan_GBs"],
+                                             "select_scan_frac_of_hbm_peak": f["key_scan_frac_of_hbm_peak"]}
+            log(f"latency probe {name}: {f['ms_per_layer']:.3f} ms per layer with scan and top-k fused "
+                f"({f['score_topk_ms']:.3f} ms for the two; the selecting scan alone {f['key_scan_ms']:.3f} ms)")
             for parts in args.latency_parts:
                 g = per_layer_latency_grouped(c, parts, (main_s[0], extra[0], gath_s[0], extra[1]))
                 log(f"latency probe {name}: {g['ms_per_layer']:.3f} ms per layer as {parts} pipelined parts "
@@ -934,7 +1014,9 @@ def main():
         log(f"selection at 1M: top-k {selection['topk_ms']:.3f} ms, Eq. 4 at tau 0.9 {selection['topp_tau0.9']['ms']:.3f} ms")
 
     total_steps = args.steps + args.warmup
-    model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers), evict_spare=args.evict_spare)
+    fused = args.pipeline == "native" and not args.no_fused_select
+    model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers), evict_spare=args.evict_spare,
+                  fused=fused)
     layer_v_gib = w.batch * w.n_kv_heads * w.n * 256 / 2 ** 30
     phys = max(1, min(L, int(args.host_gib / layer_v_gib)))
     t0 = time.perf_counter()
@@ -998,11 +1080,11 @@ def main():
     else:
         events = [e for step_events in events for e in step_events]
         scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
-    scan_bytes = w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + 4)
+    scan_bytes = w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + (0 if fused else 4))
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
 
     traffic = None
-    pmc = os.path.join(ROOT, "profiles", "score_kernel_cfg4_1m_pmc.md")
+    pmc = os.path.join(ROOT, "profiles", "select_scan_cfg4_1m_pmc.md" if fused else "score_kernel_cfg4_1m_pmc.md")
     if args.config == 4 and os.path.exists(pmc):     # measured with rocprofv3 --pmc, see that file
         for line in open(pmc):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -1016,7 +1098,8 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "context": w.n, "layers": L, "q_heads": w.n_q_heads,
                    "kv_heads": w.n_kv_heads, "key_bits": w.bits, "group": w.group, "top_k": w.k,
                    "evict_every": args.evict_every, "values": "context rows in pinned host fp16, appended rows in an HBM slice",
-                   "physical_value_layers": phys, "pipeline": args.pipeline},
+                   "physical_value_layers": phys, "pipeline": args.pipeline,
+                   "selection": "hca_score_topk (scan + top-k fused)" if fused else "hca_score_qkeys + hca_topk"},
         "pipelined_ms_per_layer": ms_per_step / L,
         "per_layer_decode_latency": latency,
         "codebook_key_path": codebook,
@@ -1026,12 +1109,13 @@ def main():
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,
-        "roofline": {"bound": "hbm", "kernel": "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "score_kernel (selecting scan)" if fused else "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes,
                      "avg_event_bracket_ms": bracket_ms,
                      # the same kernel at the same shape with no other kernel beside it (latency probe above)
-                     "frac_alone": latency.get("1M", {}).get("key_scan_frac_of_hbm_peak") if args.config == 4 else None},
+                     "frac_alone": (latency.get("1M", {}).get("fused_select", {}).get("select_scan_frac_of_hbm_peak") if fused
+                                    else latency.get("1M", {}).get("key_scan_frac_of_hbm_peak")) if args.config == 4 else None},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = run_cpu_baseline(model, w)

@@ -120,6 +120,18 @@ int32_t hca_score_qkeys(const hca_shape* shape, const void* kcache, const void* 
 int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resident,
                  int32_t k, int32_t* idx, int32_t* count, void* workspace, void* stream);
 
+/* Steps 2 and 3a in one call (Eq. 2, then the sorted prefix Pi_k of Sec. 3.2): idx and count exactly as
+ * hca_score_qkeys followed by hca_topk would leave them, without the score of every slot ever reaching
+ * memory.  A strided sample of each row (8192 slots) is scored first and gives a threshold that at least k
+ * slots of the row pass with overwhelming probability; the scan then keeps only the (score, slot) pairs
+ * at or above it, and the selection runs on those few thousand pairs.  A row whose sample misled (fewer
+ * than k pairs) is scanned a second time with no threshold inside the same call, so the result never
+ * depends on the sample; only the time does.
+ *   workspace  device, hca_workspace_bytes(shape, k, 1) bytes
+ * Errors: HCA_ERR_CAPACITY if k < 1, k > capacity, or a row holds more than 8 Mi resident slots. */
+int32_t hca_score_topk(const hca_shape* shape, const void* kcache, const void* q_f16, const int64_t* n_resident,
+                       int32_t k, int32_t* idx, int32_t* count, void* workspace, void* stream);
+
 /* Step 3b, Eq. 5 with the softmax taken over the selected set: for each query
  * head, l_i = z~[idx_i] * sm_scale (z~ recomputed from the codes),
  * a = softmax(l), y = sum_i a_i * V[pos[idx_i]].
@@ -229,6 +241,12 @@ typedef struct {
      step's k as the cut-off) instead of top-k.  The two are independent. */
   int32_t vq_groups, vq_codewords;
   double topp_tau;
+  /* fused_select != 0: scan and top-k as in hca_score_topk (uniform codes and top-k only): the scan stage
+     estimates the threshold and leaves the candidate lists, the top-k stage selects from them.  No score
+     buffer is written: sel[] is ignored, and the first n_sel entries of ws_select are the per-slot
+     workspaces instead (device, hca_workspace_bytes(shape, k, 1) each). */
+  int32_t fused_select;
+  void* ws_select[HCA_PIPELINE_MAX_SEL];
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;

@@ -46,7 +46,8 @@ class hca_pipeline_desc(C.Structure):
                 ("ws_evict", C.c_void_p), ("spare_kcache", C.c_void_p), ("spare_acc", C.c_void_p),
                 ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64),
                 ("timing_layer_stride", C.c_int32), ("vq_groups", C.c_int32), ("vq_codewords", C.c_int32),
-                ("topp_tau", C.c_double)]
+                ("topp_tau", C.c_double), ("fused_select", C.c_int32),
+                ("ws_select", C.c_void_p * PIPELINE_MAX_SEL)]
 
 
 class hca_vq_codebook(C.Structure):
@@ -78,6 +79,8 @@ def lib():
         L.hca_score_qkeys.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.hca_topk.restype = i32
         L.hca_topk.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp]
+        L.hca_score_topk.restype = i32
+        L.hca_score_topk.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.hca_score_qkeys_lse.restype = i32
         L.hca_score_qkeys_lse.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, vp]
         L.hca_attend_gathered_global.restype = i32
@@ -190,6 +193,12 @@ def hca_score_qkeys(shape, kcache, q_f16, n_resident, sel, z_opt=None, workspace
     nr = _nres(n_resident, shape.batch)
     _check(lib().hca_score_qkeys(C.byref(shape), _ptr(kcache), _ptr(q_f16), nr, _ptr(sel), _ptr(z_opt),
                                  _ptr(workspace), _stream(stream)), "hca_score_qkeys")
+
+
+def hca_score_topk(shape, kcache, q_f16, n_resident, k, idx, count, workspace, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_score_topk(C.byref(shape), _ptr(kcache), _ptr(q_f16), nr, int(k), _ptr(idx), _ptr(count),
+                                _ptr(workspace), _stream(stream)), "hca_score_topk")
 
 
 def hca_topk(shape, sel, n_resident, k, idx, count, workspace, stream=None):

@@ -151,6 +151,21 @@ int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resi
   return launch_topk(L, sel, nr, nmax, k, idx, count, workspace, (hipStream_t)stream);
 }
 
+int32_t hca_score_topk(const hca_shape* shape, const void* kcache, const void* q_f16, const int64_t* n_resident,
+                       int32_t k, int32_t* idx, int32_t* count, void* workspace, void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (kcache == nullptr || q_f16 == nullptr || idx == nullptr || count == nullptr || workspace == nullptr)
+    return HCA_ERR_BAD_ARG;
+  if (k < 1 || k > L.cap) return HCA_ERR_CAPACITY;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  return launch_score_topk(L, kcache, q_f16, nr, nmax, k, idx, count, workspace, (hipStream_t)stream);
+}
+
 int32_t hca_score_qkeys_lse(const hca_shape* shape, const void* kcache, const void* q_f16,
                             const int64_t* n_resident, float sm_scale, float* sel, float* lse, void* workspace,
                             void* stream) {

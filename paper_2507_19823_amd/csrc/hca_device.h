@@ -109,8 +109,8 @@ __device__ __forceinline__ int operand_channel(int m, int j, int x) {
   }
 }
 
-// Computes the fixed-point query of row `row` into LDS.  Called by all 256 threads of the
-// block; wave w handles query head w of the row.  Ends with a barrier.
+// Computes the fixed-point query of row `row` into LDS.  Called by all threads of the block
+// (at least 256); wave w < 4 handles query head w of the row.  Ends with a barrier.
 __device__ __forceinline__ void load_query(const uint16_t* __restrict__ q, int row, int gqa, int group,
                                            QShared* sh) {
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
@@ -125,9 +125,11 @@ __device__ __forceinline__ void load_query(const uint16_t* __restrict__ q, int r
   for (int o = 32; o >= 1; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
   int s = 0;
   if (amax != 0.f) s = 13 - ilogbf(amax);
-  sh->qfx[w][2 * lane] = (int16_t)(int)rintf(ldexpf(x0, s));
-  sh->qfx[w][2 * lane + 1] = (int16_t)(int)rintf(ldexpf(x1, s));
-  if (lane == 0) sh->sexp[w] = s;
+  if (w < 4) {                       // workgroups larger than four waves: the extra waves only take the barriers
+    sh->qfx[w][2 * lane] = (int16_t)(int)rintf(ldexpf(x0, s));
+    sh->qfx[w][2 * lane + 1] = (int16_t)(int)rintf(ldexpf(x1, s));
+    if (lane == 0) sh->sexp[w] = s;
+  }
   __syncthreads();
   if (tid < 16) {
     const int h = tid >> 2, g = tid & 3;

@@ -3,7 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/hca.h"
+
 #include "hca_device.h"
 
 namespace hca {
@@ -31,6 +34,17 @@ struct Tuning {
 Tuning& tuning();
 
 inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// Raises a kernel's dynamic-LDS limit, once per device and call site (`done`: one bit per device).  Repeating
+// the call on every launch is correct but stalls a host thread that is enqueueing ahead of the GPU.
+inline int32_t lds_opt_in(const void* kernel, int bytes, std::atomic<uint64_t>* done) {
+  int dev = 0;
+  HCA_HIP(hipGetDevice(&dev));
+  if (dev >= 0 && dev < 64 && ((done->load(std::memory_order_acquire) >> dev) & 1)) return HCA_OK;
+  HCA_HIP(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+  if (dev >= 0 && dev < 64) done->fetch_or(1ull << dev, std::memory_order_release);
+  return HCA_OK;
+}
 
 // Radix-select engine (select.hip): per row, finds the `want[r]`-th largest key among
 // slots [0, nsel[r]) and per-chunk counts, so that a following ordered pass can emit the
@@ -70,6 +84,46 @@ int32_t launch_score_lse(const Layout& L, const void* kcache, const void* q, con
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
                     int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean = false);
 size_t topk_hist_bytes(int rows);
+// Scan and selection in one: the scan keeps only the (order key, slot) pairs of the slots whose key reaches a
+// per-row threshold estimated from a strided sample of the row, in per-chunk lists (chunk = the slots of one
+// scan workgroup, at most kSelectMaxChunks of them per row).
+constexpr int kSelectMaxChunks = 1024;
+struct SelectOut {
+  uint32_t* spec;       // [rows][4]: threshold key t0, 1 = the row has to be scanned again with t0 = 0, -, -
+  uint32_t* ncand;      // [rows][kSelectMaxChunks] pairs in each chunk's list
+  uint2* lists;         // [rows][row_entries]: chunk c owns entries [c * chunk, (c + 1) * chunk)
+  uint32_t* samples;    // [rows][8192] keys of the sampled slots (0: no such slot)
+  int64_t row_entries;
+};
+// blocks per wave of the selecting scan over nmax slots (chunks per row <= kSelectMaxChunks); 0: too long a row
+int select_scan_bpw(const Layout& L, int64_t nmax);
+int32_t launch_select_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int32_t k,
+                             const SelectOut& so, hipStream_t st);
+int32_t launch_select_scan(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                           const SelectOut& so, bool only_failed, hipStream_t st, uint64_t* stamps = nullptr);
+int32_t launch_select_sample_scores(const Layout& L, const void* kcache, const void* q, const NRes& nr,
+                                    const SelectOut& so, hipStream_t st);
+int32_t launch_select_rank_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before, float* acc,
+                                  int32_t* pos, const NRes& vrow0, int32_t k, const SelectOut& so, hipStream_t st);
+int32_t launch_select_scan_and_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                      const SelectOut& so, hipStream_t st, uint64_t* stamps, const void* next_kcache,
+                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples);
+int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, void* ws,
+                              hipStream_t st);
+int32_t launch_select_threshold_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before,
+                                       float* acc, int32_t* pos, const NRes& vrow0, int32_t k, void* ws,
+                                       hipStream_t st);
+int32_t launch_select_scan_next(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const void* next_kcache,
+                                const void* next_q, const NRes& next_nr, void* next_ws);
+int32_t launch_select_threshold(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                int32_t k, void* ws, hipStream_t st);
+int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
+                            void* ws, hipStream_t st, uint64_t* stamps = nullptr);
+int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
+                             int32_t* idx, int32_t* count, void* ws, hipStream_t st);
+int32_t launch_score_topk(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
+                          int32_t* idx, int32_t* count, void* ws, hipStream_t st);
 int32_t launch_topp(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, float sm_scale, double tau,
                     int32_t k_max, int32_t* idx, int32_t* count, uint64_t* mass_opt, void* ws, hipStream_t st);
 size_t attend_workspace_bytes(const Layout& L, int64_t k);

@@ -38,7 +38,9 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   Layout L;
   if (make_layout(shape, &L) != HCA_OK || desc == nullptr || n_layers < 1 || timing_slots < 0) return nullptr;
   if (desc->n_sel < 3 || desc->n_sel > HCA_PIPELINE_MAX_SEL) return nullptr;
-  for (int i = 0; i < desc->n_sel; ++i) if (desc->sel[i] == nullptr) return nullptr;
+  const bool fused = desc->fused_select != 0;
+  for (int i = 0; i < desc->n_sel; ++i) if ((fused ? desc->ws_select[i] : (void*)desc->sel[i]) == nullptr) return nullptr;
+  if (fused && (desc->vq_groups != 0 || desc->topp_tau > 0.0)) return nullptr;   // uniform codes and top-k only
   for (int i = 0; i < 4; ++i)
     if (desc->idx[i] == nullptr || desc->count[i] == nullptr || desc->ws_attend[i] == nullptr) return nullptr;
   if (desc->ws_topk == nullptr) return nullptr;
@@ -132,6 +134,26 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     }
     return HCA_OK;
   };
+  const bool fused = p->d.fused_select != 0;
+  // Fused selection: the scan stream carries two launches per layer, as without it: (threshold from the
+  // layer's samples + append of its key), then (selecting scan + sampling of the next layer's cache).  The
+  // first layer's samples come from a launch of their own.
+  auto lengths = [&](int l2, NRes* out, int64_t* nmax2) -> int32_t {
+    const hca_layer& y2 = layers[l2];
+    if (y2.kcache == nullptr || y2.acc == nullptr || y2.pos == nullptr || y2.k_new == nullptr || y2.q == nullptr)
+      return HCA_ERR_BAD_ARG;
+    return load_nres(L, n_resident + (int64_t)l2 * L.batch, out, nmax2);
+  };
+  if (fused) {
+    NRes n0;
+    int64_t m0;
+    int32_t rc = lengths(0, &n0, &m0);
+    if (rc != HCA_OK) return rc;
+    if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[0], 0));
+    HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[0], 0));
+    rc = launch_select_samples(L, layers[0].kcache, layers[0].q, n0, p->d.ws_select[0], sa);
+    if (rc != HCA_OK) return rc;
+  }
   for (int l = 0; l < p->n_layers; ++l) {
     hca_layer& ly = layers[l];
     int64_t* nl = n_resident + (int64_t)l * L.batch;
@@ -150,29 +172,51 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     // stage 1: append + key scan
     // top-k of the previous user of this score buffer (with a buffer per layer that is this layer's own
     // previous step, which layer_done covers)
-    if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[s3], 0));
-    HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l], 0));    // this layer's attend / evict of the previous step
-    rc = vq ? launch_vq_assign(L, vg, vc, ly.vq_centroids, (uint8_t*)ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa)
-            : launch_quantize(L, ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa);
-    if (rc != HCA_OK) return rc;
-    for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
-    nmax += 1;
+    if (fused) {
+      // (the waits for this layer's buffers went out before its sampling, one layer earlier)
+      rc = launch_select_threshold_append(L, ly.kcache, ly.k_new, nr, ly.acc, ly.pos, vrow0, k, p->d.ws_select[s3], sa);
+      if (rc != HCA_OK) return rc;
+      for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
+      nmax += 1;
+    } else {
+      if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[s3], 0));
+      HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l], 0));    // this layer's attend / evict of the previous step
+      rc = vq ? launch_vq_assign(L, vg, vc, ly.vq_centroids, (uint8_t*)ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa)
+              : launch_quantize(L, ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa);
+      if (rc != HCA_OK) return rc;
+      for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
+      nmax += 1;
+    }
     if (timed) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
     uint64_t* stamps = nullptr;
     if (!vq && timing_slot >= 0 && p->d.scan_stamps != nullptr) {
       if (p->d.scan_stamp_pairs < score_stamp_pairs(L, nmax)) return HCA_ERR_CAPACITY;
       stamps = (uint64_t*)p->d.scan_stamps + ((int64_t)timing_slot * p->n_layers + l) * p->d.scan_stamp_pairs * 2;
     }
+    auto fused_scan = [&]() -> int32_t {
+      if (l + 1 == p->n_layers) return launch_select_begin(L, ly.kcache, ly.q, nr, nmax, k, p->d.ws_select[s3], sa, stamps);
+      NRes n2;
+      int64_t m2;
+      const int32_t r2 = lengths(l + 1, &n2, &m2);
+      if (r2 != HCA_OK) return r2;
+      const int t3 = (l + 1) % p->n_sel;
+      if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[t3], 0));
+      HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l + 1], 0));
+      return launch_select_scan_next(L, ly.kcache, ly.q, nr, nmax, k, p->d.ws_select[s3], sa, stamps, layers[l + 1].kcache,
+                                     layers[l + 1].q, n2, p->d.ws_select[t3]);
+    };
     rc = vq ? launch_vq_score(L, vg, vc, ly.vq_centroids, (const uint8_t*)ly.kcache, ly.q, nr, nmax, ly.vq_lut,
                               p->d.sel[s3], nullptr, sa)
-            : launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps);
+         : fused ? fused_scan()
+                 : launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps);
     if (rc != HCA_OK) return rc;
     if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
     HCA_HIP(hipEventRecord(p->score_done[s3], sa));
     // stage 2: top-k
     HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
     HCA_HIP(hipStreamWaitEvent(sb, p->pipe_free[s4], 0));    // attend of the previous user of idx / staging
-    rc = p->d.topp_tau > 0.0
+    rc = fused ? launch_select_finish(L, ly.kcache, ly.q, nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_select[s3], sb)
+         : p->d.topp_tau > 0.0
              ? launch_topp(L, p->d.sel[s3], nr, nmax, sm_scale, p->d.topp_tau, k, p->d.idx[s4], p->d.count[s4], nullptr,
                            p->d.ws_topk, sb)
              : launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb, true);

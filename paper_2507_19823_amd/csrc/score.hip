@@ -1,6 +1,7 @@
 // Step 2: the key scan.  z~ = q . Q(K)^T (Eq. 2 / Eq. 3) for every resident token, streamed
 // once from HBM as packed codes and contracted on the matrix cores in exact integer arithmetic.
 #include "hca_internal.h"
+#include "quantize_device.h"
 
 namespace hca {
 
@@ -45,24 +46,38 @@ __device__ __forceinline__ uint4 allgather_rows(uint32_t v) {
 // LSE: every wave also leaves, per query head, the (max, sum of exp) pair of its logits z~ * sm_scale
 // in `part` ([row][4][waves of the row] float2), from which lse_merge forms the softmax denominator
 // over all resident tokens.
-template <int BITS, bool WRITE_Z, int U, bool LSE = false>
-__global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __restrict__ kcache,
-                                                    const uint16_t* __restrict__ q, NRes nr, int bpw,
-                                                    float* __restrict__ sel, float* __restrict__ z,
-                                                    uint64_t* __restrict__ stamps, float sm_scale = 0.f,
-                                                    float2* __restrict__ part = nullptr) {
+// SELECT: instead of the score of every token, only the (order key, slot) pairs of the tokens whose key reaches the
+// row's threshold t0 leave the kernel, in slot order, as the list of the workgroup's chunk (chunk = the slots of
+// one workgroup; chunk c of a row owns entries [c * chunk, (c + 1) * chunk) of the row's list area, so no two
+// workgroups ever contend for a position and no workgroup waits for an atomic).  With a threshold a little below the k-th largest
+// score of the row the 4 bytes per token of score traffic - written here and read twice by the top-k passes -
+// shrink to a few thousand pairs per row.
+// bx = the workgroup's chunk of the row, gx = chunks per row (blockIdx.x and gridDim.x in the plain launch)
+template <int BITS, bool WRITE_Z, int U, bool LSE, bool SELECT>
+__device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __restrict__ kcache,
+                                           const uint16_t* __restrict__ q, const NRes& nr, int bpw,
+                                           float* __restrict__ sel, float* __restrict__ z,
+                                           uint64_t* __restrict__ stamps, float sm_scale, float2* __restrict__ part,
+                                           const SelectOut& so, const int bx, const int gx) {
   static_assert(U % 4 == 0, "stores are batched four tiles at a time");
   __shared__ QShared sh;
+  // SELECT: every wave collects its qualifying pairs in slot order in its quarter of the dynamic LDS (room for
+  // all the wave's slots), then the workgroup strings the four lists together
+  extern __shared__ uint2 wlist_all[];
+  __shared__ uint32_t wcount[4];
   const int row = blockIdx.y;
   const int64_t n = nr.n[row / L.n_kv_heads];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nblocks = (int)((n + L.tpb - 1) / L.tpb);
-  if ((int64_t)blockIdx.x * 4 * bpw >= nblocks) return;  // whole workgroup past the end
+  if ((int64_t)bx * 4 * bpw >= nblocks) {        // whole workgroup past the end
+    if (SELECT && threadIdx.x == 0) so.ncand[(int64_t)row * kSelectMaxChunks + bx] = 0;
+    return;
+  }
   // optional profiling: every wave leaves its start and end time (constant-rate wall clock)
-  uint64_t* stamp = stamps ? stamps + (((int64_t)row * gridDim.x + blockIdx.x) * 4 + w) * 2 : nullptr;
+  uint64_t* stamp = stamps ? stamps + (((int64_t)row * gx + bx) * 4 + w) * 2 : nullptr;
   if (stamp && lane == 0) stamp[0] = wall_clock64();
-  const int wave_first = (blockIdx.x * 4 + w) * bpw;
+  const int wave_first = (bx * 4 + w) * bpw;
   int wave_end = wave_first + bpw;
   if (wave_end > nblocks) wave_end = nblocks;
   if (wave_end < wave_first) wave_end = wave_first;
@@ -115,10 +130,24 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
     }
   };
   // the lane in row hd stores tile hd of four consecutive tiles starting at token tok0
+  const uint32_t t0key = SELECT ? so.spec[4 * row] : 0u;
+  uint2* wlist = SELECT ? wlist_all + (int64_t)w * bpw * L.tpb : nullptr;
+  uint32_t nlist = 0;                                     // SELECT: pairs in this wave's list so far (wave-uniform)
+  // SELECT: appends the lanes' pairs that qualify, in lane order (the caller's lanes are in slot order)
+  auto emit_pairs = [&](float v, int tok, bool live) {
+    const uint32_t key = order_key(v);
+    const bool hit = live && key >= t0key;
+    const uint64_t m = __ballot(hit);
+    if (m != 0) {
+      if (hit) wlist[nlist + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = uint2{key, (uint32_t)tok};
+      nlist += (uint32_t)__popcll(m);
+    }
+  };
   auto store4 = [&](int tok0, float v0, float v1, float v2, float v3) {
     const float v = hd == 0 ? v0 : (hd == 1 ? v1 : (hd == 2 ? v2 : v3));
     const int tok = tok0 + lane;                          // 16*hd + t == lane
-    if (tok < ntok) selrow[tok] = v;
+    if constexpr (SELECT) emit_pairs(v, tok, tok < ntok);
+    else if (tok < ntok) selrow[tok] = v;
   };
 
   // Software pipeline over groups of U blocks: the loads of group g+1 are issued before group g is
@@ -172,12 +201,28 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
     float lo, hi;
     score_one(b0, wv, mw, lo, hi);
     if constexpr (LSE) lse_fold();
-    if constexpr (BITS == 4) {
+    if constexpr (SELECT) {
+      // lanes 0..15 carry tile 0; with 2-bit codes lanes 16..31 carry tile 1: lane order is slot order
+      if constexpr (BITS == 4) emit_pairs(lo, b0 * 16 + t, hd == 0 && b0 * 16 + t < ntok);
+      else emit_pairs(hd == 0 ? lo : hi, b0 * 32 + 16 * hd + t, hd < 2 && b0 * 32 + 16 * hd + t < ntok);
+    } else if constexpr (BITS == 4) {
       if (hd == 0 && b0 * 16 + t < ntok) selrow[b0 * 16 + t] = lo;
     } else {
       if (hd == 0 && b0 * 32 + t < ntok) selrow[b0 * 32 + t] = lo;
       if (hd == 1 && b0 * 32 + 16 + t < ntok) selrow[b0 * 32 + 16 + t] = hi;
     }
+  }
+  if constexpr (SELECT) {
+    // the four waves' lists, in wave order (= slot order), become the chunk's list
+    if (lane == 0) wcount[w] = nlist;
+    __syncthreads();
+    uint32_t base = 0, total = 0;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) { if (x < w) base += wcount[x]; total += wcount[x]; }
+    const int64_t chunk_slots = (int64_t)4 * bpw * L.tpb;
+    uint2* dst = so.lists + (int64_t)row * so.row_entries + (int64_t)bx * chunk_slots + base;
+    for (uint32_t i = lane; i < nlist; i += 64) dst[i] = wlist[i];
+    if (threadIdx.x == 0) so.ncand[(int64_t)row * kSelectMaxChunks + bx] = total;
   }
   if constexpr (LSE) {
     // merge over the 16 lanes of a head row, then one lane per head stores the wave's pair
@@ -190,9 +235,33 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
       lm = mm;
     }
     if (t == 0)   // back to natural-log units: max in logit units, the sum is unit-free
-      part[((int64_t)row * 4 + hd) * (gridDim.x * 4) + blockIdx.x * 4 + w] = float2{lm * 0.693147181f, ls};
+      part[((int64_t)row * 4 + hd) * (gx * 4) + bx * 4 + w] = float2{lm * 0.693147181f, ls};
   }
   if (stamp && lane == 0) stamp[1] = wall_clock64();
+}
+
+template <int BITS, bool WRITE_Z, int U, bool LSE = false, bool SELECT = false>
+__global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __restrict__ kcache,
+                                                    const uint16_t* __restrict__ q, NRes nr, int bpw,
+                                                    float* __restrict__ sel, float* __restrict__ z,
+                                                    uint64_t* __restrict__ stamps, float sm_scale = 0.f,
+                                                    float2* __restrict__ part = nullptr, SelectOut so = SelectOut{}) {
+  score_body<BITS, WRITE_Z, U, LSE, SELECT>(L, kcache, q, nr, bpw, sel, z, stamps, sm_scale, part, so, (int)blockIdx.x,
+                                            (int)gridDim.x);
+}
+
+// The selecting scan once more for the rows whose sampled threshold left too few pairs (spec[row][1] != 0, with
+// the threshold already reset to 0).  Almost always there is no such row, so the launch is kept small - a few
+// workgroups per row that walk over the row's chunks - and costs next to nothing when it has nothing to do.
+template <int BITS, int U>
+__global__ __launch_bounds__(256) void score_failed_rows_kernel(Layout L, const uint8_t* __restrict__ kcache,
+                                                                const uint16_t* __restrict__ q, NRes nr, int bpw,
+                                                                int nchunks, SelectOut so) {
+  if (so.spec[4 * blockIdx.y + 1] == 0) return;
+  for (int bx = blockIdx.x; bx < nchunks; bx += gridDim.x) {
+    score_body<BITS, false, U, false, true>(L, kcache, q, nr, bpw, nullptr, nullptr, nullptr, 0.f, nullptr, so, bx, nchunks);
+    __syncthreads();                                        // the shared query image and counters are reused
+  }
 }
 
 // lse[row * G + h] = log sum exp over the first `live` wave pairs of the row (waves of workgroups that
@@ -230,6 +299,300 @@ __global__ __launch_bounds__(256) void lse_merge(Layout L, NRes nr, int bpw, int
     for (int x = 0; x < 4; ++x) if (sm[x] != -INFINITY) S += ss[x] * expf(sm[x] - M);
     lse[blockIdx.x] = (M == -INFINITY) ? -INFINITY : M + logf(S);
   }
+}
+
+// Threshold estimate for the selecting scan.  kSampleTokens slots of every row (whole code blocks, evenly spaced:
+// sampled block s is block floor(s * nblocks / S) of the row) are scored by select_sample_score; select_sample_rank
+// then leaves in spec[row] a key t0 such that, if the sample behaves like a random one, at least `want` slots of
+// the row have keys >= t0 with overwhelming probability:
+//   m = sampled slots, kappa = want * m / n, r = ceil((3 + sqrt(9 + kappa))^2)  (the count of slots above the
+//   r-th largest of m samples has mean n r / m and deviation n sqrt(r) / m: this r puts `want` six deviations
+//   below the mean), t0 = the r-th largest sampled key with its low 10 bits cleared; t0 = 0 when r >= m.
+// The selection stays exact whatever the sample does: a row whose list comes out short is scanned again with
+// t0 = 0 (spec[row][1]).
+constexpr int kSampleTokens = 8192;
+constexpr int kSampleWgs = 16;
+
+// bx = which of the kSampleWgs workgroups of the row this is; called by all 256 threads
+template <int BITS>
+__device__ __forceinline__ void sample_score_body(const Layout& L, const uint8_t* __restrict__ kcache,
+                                                  const uint16_t* __restrict__ q, const NRes& nr,
+                                                  uint32_t* __restrict__ samples, const int bx, const int row) {
+  constexpr int kTpb = BITS == 4 ? 16 : 32;
+  constexpr int kPerWave = kSampleTokens / kTpb / (4 * kSampleWgs);   // sampled blocks per wave: 8 (4-bit) or 4
+  __shared__ QShared sh;
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t n = nr.n[row / L.n_kv_heads];
+  if (n <= 0) {                                             // nothing to sample: this workgroup's share reads "no slot"
+    for (int i = threadIdx.x; i < kSampleTokens / kSampleWgs; i += 256)
+      samples[(int64_t)row * kSampleTokens + bx * (kSampleTokens / kSampleWgs) + i] = 0;
+    return;
+  }
+  const int nblocks = (int)((n + kTpb - 1) / kTpb);
+  const int S = nblocks < kSampleTokens / kTpb ? nblocks : kSampleTokens / kTpb;
+  const int t = lane & 15, hd = lane >> 4;
+  const uint4* cptr = reinterpret_cast<const uint4*>(kcache + (int64_t)row * L.codes_row_bytes()) + lane;
+  const uint32_t* mptr = reinterpret_cast<const uint32_t*>(kcache + L.meta_off + (int64_t)row * L.meta_row_bytes()) +
+                         (BITS == 4 ? 4 * t + hd : 2 * (16 * (hd >> 1) + t) + (hd & 1));
+  uint32_t* out = samples + (int64_t)row * kSampleTokens;
+  const int s0 = (bx * 4 + w) * kPerWave;
+  uint4 wv[kPerWave];
+  uint32_t mw[kPerWave];
+  int blk[kPerWave];
+#pragma unroll
+  for (int u = 0; u < kPerWave; ++u) {
+    const int s = s0 + u;
+    blk[u] = s < S ? (int)((int64_t)s * nblocks / S) : 0;
+    wv[u] = load_stream16(&cptr[(int64_t)blk[u] * 64]);
+    mw[u] = __builtin_nontemporal_load(&mptr[(int64_t)blk[u] * 64]);
+  }
+  QOperand<BITS> op;
+  load_query(q, row, L.gqa, L.group, &sh);
+  build_operand<BITS>(&sh, &op);
+  const bool head_live = hd < L.gqa;
+#pragma unroll
+  for (int u = 0; u < kPerWave; ++u) {
+    const int s = s0 + u;
+    const uint4 mv = allgather_rows(mw[u]);
+    if constexpr (BITS == 4) {
+      const float zv = score_block4(op, wv[u], mv);
+      const float best = max_over_heads(head_live ? zv : -INFINITY);
+      const bool live = s < S && (int64_t)blk[u] * 16 + t < n;
+      if (hd == 0) out[s * 16 + t] = live ? order_key(best) : 0u;      // no finite score has key 0
+    } else {
+      const float z0 = score_tile2(op, wv[u].x, wv[u].y, uint2{mv.x, mv.y});
+      const float z1 = score_tile2(op, wv[u].z, wv[u].w, uint2{mv.z, mv.w});
+      const float b0 = max_over_heads(head_live ? z0 : -INFINITY);
+      const float b1 = max_over_heads(head_live ? z1 : -INFINITY);
+      if (hd < 2) {
+        const int tok = 16 * hd + t;
+        const bool live = s < S && (int64_t)blk[u] * 32 + tok < n;
+        out[s * 32 + tok] = live ? order_key(hd == 0 ? b0 : b1) : 0u;
+      }
+    }
+  }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void select_sample_score(Layout L, const uint8_t* __restrict__ kcache,
+                                                           const uint16_t* __restrict__ q, NRes nr, SelectOut so) {
+  sample_score_body<BITS>(L, kcache, q, nr, so.samples, (int)blockIdx.x, (int)blockIdx.y);
+}
+
+// 256 threads per row: small enough to find room on a chip that another stream's scan keeps full
+__device__ __forceinline__ void sample_rank_body(const Layout& L, const NRes& nr, int32_t k, const SelectOut& so,
+                                                 const int row) {
+  constexpr int kPer = kSampleTokens / 256;
+  __shared__ uint32_t hist[4096];
+  __shared__ uint32_t wsum[4];
+  __shared__ uint32_t s_bin, s_rem;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t n = nr.n[row / L.n_kv_heads];
+  const int64_t want = n < k ? n : k;
+  uint32_t* sp = so.spec + 4 * row;
+  if (want <= 0) {
+    if (tid == 0) { sp[0] = 0xffffffffu; sp[1] = 0; }
+    return;
+  }
+  uint32_t key[kPer];
+  const uint32_t* in = so.samples + (int64_t)row * kSampleTokens;
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) key[i] = in[i * 256 + tid];
+  for (int i = tid; i < 4096; i += 256) hist[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kPer; ++i)
+    if (key[i] != 0) atomicAdd(&hist[key[i] >> 20], 1u);
+  __syncthreads();
+  // exclusive prefix over the threads of `sum`, and the total
+  auto scan256 = [&](uint32_t sum, uint32_t* total) {
+    uint32_t inc = sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const uint32_t a = __shfl_up(inc, o);
+      if (lane >= o) inc += a;
+    }
+    __syncthreads();                                        // earlier readers of wsum are done
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    uint32_t running = inc - sum, tot = 0;
+    for (int x = 0; x < 4; ++x) { if (x < w) running += wsum[x]; tot += wsum[x]; }
+    *total = tot;
+    return running;
+  };
+  // bins from the top: thread tid owns bins 4095 - 16 tid - i
+  uint32_t h[16], sum = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { h[i] = hist[4095 - (16 * tid + i)]; sum += h[i]; }
+  uint32_t m;                                               // sampled slots that exist
+  uint32_t running = scan256(sum, &m);
+  const float kappa = (float)want * (float)m / (float)n;
+  const float root = 3.0f + sqrtf(9.0f + kappa);
+  const uint32_t r = (uint32_t)ceilf(root * root);
+  if (r >= m) {                                             // short rows: everything is a candidate
+    if (tid == 0) { sp[0] = 0; sp[1] = 0; }
+    return;
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    if (running < r && r <= running + h[i]) { s_bin = 4095 - (16 * tid + i); s_rem = r - running; }
+    running += h[i];
+  }
+  __syncthreads();
+  const uint32_t bin = s_bin, rem = s_rem;
+  for (int i = tid; i < 1024; i += 256) hist[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kPer; ++i)
+    if (key[i] != 0 && (key[i] >> 20) == bin) atomicAdd(&hist[(key[i] >> 10) & 1023u], 1u);
+  __syncthreads();
+  uint32_t g[4];
+  sum = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { g[i] = hist[1023 - (4 * tid + i)]; sum += g[i]; }
+  uint32_t unused;
+  running = scan256(sum, &unused);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (running < rem && rem <= running + g[i]) {
+      sp[0] = (bin << 20) | ((uint32_t)(1023 - (4 * tid + i)) << 10);
+      sp[1] = 0;
+    }
+    running += g[i];
+  }
+}
+
+__global__ __launch_bounds__(256) void select_sample_rank(Layout L, NRes nr, int32_t k, SelectOut so) {
+  sample_rank_body(L, nr, k, so, (int)blockIdx.x);
+}
+
+// The two small jobs of a layer that precede its selecting scan in a decode step, as one launch: workgroup
+// (0, row) turns the row's samples into its threshold (lengths `nr_after`, the new token included), workgroup
+// (1, row) quantises and appends the step's key (lengths `nr_before`).
+template <int BITS>
+__global__ __launch_bounds__(256) void select_rank_append(Layout L, NRes nr_before, NRes nr_after, int32_t k,
+                                                          SelectOut so, uint8_t* __restrict__ kcache,
+                                                          const uint16_t* __restrict__ k_new,
+                                                          float* __restrict__ acc, int32_t* __restrict__ pos,
+                                                          NRes vrow0) {
+  if (blockIdx.x == 0) sample_rank_body(L, nr_after, k, so, (int)blockIdx.y);
+  else quantize_body<BITS>(L, kcache, k_new, 1, nr_before, acc, pos, vrow0, 0, (int)blockIdx.y);
+}
+
+// The selecting scan of one layer with, as its first kSampleWgs workgroups per row, the sampling for another
+// cache (the next layer of the step): the sampling then costs no launch of its own.
+struct SampleJob {
+  const uint8_t* kcache;
+  const uint16_t* q;
+  uint32_t* samples;
+  NRes nr;
+};
+template <int BITS, int U>
+__global__ __launch_bounds__(256) void score_select_sample_kernel(Layout L, const uint8_t* __restrict__ kcache,
+                                                                  const uint16_t* __restrict__ q, NRes nr, int bpw,
+                                                                  uint64_t* __restrict__ stamps, SelectOut so,
+                                                                  SampleJob sj) {
+  if (blockIdx.x < kSampleWgs) {
+    sample_score_body<BITS>(L, sj.kcache, sj.q, sj.nr, sj.samples, (int)blockIdx.x, (int)blockIdx.y);
+    return;
+  }
+  score_body<BITS, false, U, false, true>(L, kcache, q, nr, bpw, nullptr, nullptr, stamps, 0.f, nullptr, so,
+                                          (int)blockIdx.x - kSampleWgs, (int)gridDim.x - kSampleWgs);
+}
+
+int select_scan_bpw(const Layout& L, int64_t nmax) {
+  const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
+  const int64_t total = nblocks * L.rows;
+  int64_t bpw = total / (256 * 4 * 16);
+  if (bpw < 4) bpw = 4;
+  const int64_t bpw_max = L.bits == 4 ? 16 : 32;
+  if (bpw > bpw_max) bpw = bpw_max;
+  const int64_t need = (nblocks + 4 * kSelectMaxChunks - 1) / (4 * kSelectMaxChunks);   // chunks per row <= 1024
+  if (bpw < need) bpw = (need + 7) / 8 * 8;
+  if (4 * bpw * L.tpb * (int64_t)sizeof(uint2) > 64 * 1024) return 0;                     // wave lists no longer fit
+  return (int)bpw;
+}
+
+int32_t launch_select_sample_scores(const Layout& L, const void* kcache, const void* q, const NRes& nr,
+                                    const SelectOut& so, hipStream_t st) {
+  const uint8_t* kc = (const uint8_t*)kcache;
+  const uint16_t* qq = (const uint16_t*)q;
+  dim3 grid(kSampleWgs, (unsigned)L.rows);
+  if (L.bits == 4) select_sample_score<4><<<grid, 256, 0, st>>>(L, kc, qq, nr, so);
+  else select_sample_score<2><<<grid, 256, 0, st>>>(L, kc, qq, nr, so);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_select_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int32_t k,
+                             const SelectOut& so, hipStream_t st) {
+  const int32_t rc = launch_select_sample_scores(L, kcache, q, nr, so, st);
+  if (rc != HCA_OK) return rc;
+  select_sample_rank<<<L.rows, 256, 0, st>>>(L, nr, k, so);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_select_rank_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before, float* acc,
+                                  int32_t* pos, const NRes& vrow0, int32_t k, const SelectOut& so, hipStream_t st) {
+  NRes after = nr_before;
+  for (int b = 0; b < L.batch; ++b) after.n[b] += 1;
+  dim3 grid(2, (unsigned)L.rows);
+  if (L.bits == 4)
+    select_rank_append<4><<<grid, 256, 0, st>>>(L, nr_before, after, k, so, (uint8_t*)kcache, (const uint16_t*)k_new, acc,
+                                                pos, vrow0);
+  else
+    select_rank_append<2><<<grid, 256, 0, st>>>(L, nr_before, after, k, so, (uint8_t*)kcache, (const uint16_t*)k_new, acc,
+                                                pos, vrow0);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+// The selecting scan plus the sampling of another cache (next_* as in launch_select_sample's arguments).
+int32_t launch_select_scan_and_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                      const SelectOut& so, hipStream_t st, uint64_t* stamps, const void* next_kcache,
+                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples) {
+  if (nmax == 0) return HCA_ERR_BAD_ARG;
+  const int bpw = select_scan_bpw(L, nmax);
+  if (bpw == 0) return HCA_ERR_CAPACITY;
+  const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
+  dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)) + kSampleWgs, (unsigned)L.rows);
+  const size_t lds = (size_t)4 * bpw * L.tpb * sizeof(uint2);
+  SampleJob sj{(const uint8_t*)next_kcache, (const uint16_t*)next_q, next_samples, next_nr};
+  if (L.bits == 4)
+    score_select_sample_kernel<4, 8><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
+                                                             so, sj);
+  else
+    score_select_sample_kernel<2, 4><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
+                                                             so, sj);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_select_scan(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                           const SelectOut& so, bool only_failed, hipStream_t st, uint64_t* stamps) {
+  if (nmax == 0) return HCA_OK;
+  const int bpw = select_scan_bpw(L, nmax);
+  if (bpw == 0) return HCA_ERR_CAPACITY;
+  const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
+  dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
+  const size_t lds = (size_t)4 * bpw * L.tpb * sizeof(uint2);
+  const uint8_t* kc = (const uint8_t*)kcache;
+  const uint16_t* qq = (const uint16_t*)q;
+  if (only_failed) {
+    dim3 small(grid.x < 16 ? grid.x : 16, (unsigned)L.rows);
+    if (L.bits == 4) score_failed_rows_kernel<4, 8><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
+    else score_failed_rows_kernel<2, 4><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
+  } else if (L.bits == 4) {
+    score_kernel<4, false, 8, false, true><<<grid, 256, lds, st>>>(L, kc, qq, nr, bpw, nullptr, nullptr, stamps, 0.f,
+                                                                   nullptr, so);
+  } else {
+    score_kernel<2, false, 4, false, true><<<grid, 256, lds, st>>>(L, kc, qq, nr, bpw, nullptr, nullptr, stamps, 0.f,
+                                                                   nullptr, so);
+  }
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
 }
 
 // number of (start, end) stamp pairs a scan launch over nmax tokens writes at most

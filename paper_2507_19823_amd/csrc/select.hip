@@ -748,6 +748,337 @@ __global__ __launch_bounds__(256) void tk_emit_lists(int64_t chunk, int nchunks,
 
 
 // ---------------------------------------------------------------------------------------
+// Top-k straight from the scan (Sec. 3.2): the selecting scan has left, per chunk and in slot order, the
+// (key, slot) pairs at or above the row's sampled threshold.  One workgroup per row strings the chunks' lists
+// together (in LDS when they fit) - the result is the row's candidates in ascending slot order -, runs the whole
+// radix select (12 + 10 + 10 bits) over it and writes the selected slots in ascending order:
+//   selected(j) = key_j > T  or  (key_j == T and #{i < j : key_i == T} < r_eq)
+//   position(j) = #{i < j : key_i > T} + min(#{i < j : key_i == T}, r_eq)
+// A row with fewer pairs than it has to select is marked for a second scan without threshold; `only_failed`
+// launches handle exactly those rows.
+constexpr int kFullLds = 16384;     // pairs held in LDS (128 KiB, dynamic)
+
+// counter updates when the lanes of a wave share a handful of bins (the leading bits of keys that all lie
+// just above one threshold): one atomic per distinct bin for the first few, single updates for the rest
+__device__ __forceinline__ void lds_count_few(uint32_t* h, uint32_t bin, bool hit) {
+  uint64_t todo = __ballot(hit);
+  const int lane = threadIdx.x & 63;
+#pragma unroll 1
+  for (int it = 0; it < 4 && todo != 0; ++it) {
+    const int leader = __ffsll((unsigned long long)todo) - 1;
+    const uint32_t b0 = __shfl(bin, leader);
+    const uint64_t same = __ballot(hit && bin == b0) & todo;
+    if (lane == leader) atomicAdd(&h[b0], (uint32_t)__popcll(same));
+    todo &= ~same;
+  }
+  if ((todo >> lane) & 1) atomicAdd(&h[bin], 1u);
+}
+
+__global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr,
+                                                        SelectOut so, int32_t k, int32_t* __restrict__ idx,
+                                                        int32_t* __restrict__ count, bool only_failed) {
+  extern __shared__ uint2 lc[];
+  __shared__ uint32_t h[kBins12], off[1025], wsum[16];
+  __shared__ uint32_t s_prefix, s_rem, s_cb;
+  const int row = blockIdx.x;
+  const int64_t want = sr.want[row / n_kv_heads];
+  const int tid = threadIdx.x;
+  uint32_t* spec = so.spec + 4 * row;
+  if (want <= 0) {
+    if (tid == 0 && !only_failed) count[row] = 0;
+    return;
+  }
+  if (only_failed && spec[1] == 0) return;
+  // off[c] = pairs in the chunks before c; off[1024] = all of them
+  const uint32_t mine_cnt = tid < nchunks ? so.ncand[(int64_t)row * kSelectMaxChunks + tid] : 0;
+  const uint32_t before = block_scan_excl_1024(mine_cnt, wsum);
+  off[tid] = before;
+  if (tid == 1023) off[1024] = before + mine_cnt;
+  __syncthreads();
+  const uint32_t total = off[1024];
+  if (total < (uint32_t)want) {            // the sampled threshold was too high: scan the row again without one
+    if (tid == 0) { spec[0] = 0; spec[1] = 1; }
+    return;
+  }
+  const uint2* gl = so.lists + (int64_t)row * so.row_entries;
+  // pair p of the row in slot order: the chunk c with off[c] <= p < off[c + 1], entry p - off[c] of its list
+  auto fetch = [&](uint32_t p) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int s = 512; s >= 1; s >>= 1)
+      if (off[c + s] <= p) c += s;
+    return gl[(int64_t)c * chunk + (p - off[c])];
+  };
+  const bool staged = total <= (uint32_t)kFullLds;
+  const int lane = tid & 63, wv = tid >> 6;
+  uint32_t kmax = 0;                                        // largest key this thread has seen
+  if (staged) {
+    // 16 lanes per chunk: the first 32 pairs of 64 chunks per wave in 32 loads, all in flight together (nearly
+    // all lists are shorter than that); longer lists follow
+    const int sub = lane >> 4, i = lane & 15;
+    uint2 x[16], y[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int c = wv * 64 + j * 4 + sub;
+      const uint32_t m = off[c + 1] - off[c];
+      x[j] = (uint32_t)i < m ? gl[(int64_t)c * chunk + i] : uint2{0, 0};
+      y[j] = (uint32_t)i + 16 < m ? gl[(int64_t)c * chunk + i + 16] : uint2{0, 0};
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int c = wv * 64 + j * 4 + sub;
+      const uint32_t o = off[c], m = off[c + 1] - o;
+      if ((uint32_t)i < m) { lc[o + i] = x[j]; kmax = x[j].x > kmax ? x[j].x : kmax; }
+      if ((uint32_t)i + 16 < m) { lc[o + i + 16] = y[j]; kmax = y[j].x > kmax ? y[j].x : kmax; }
+    }
+#pragma unroll 1
+    for (int j = 0; j < 16; ++j) {
+      const int c = wv * 64 + j * 4 + sub;
+      const uint32_t o = off[c], m = off[c + 1] - o;
+      for (uint32_t e = 32 + i; e < m; e += 16) {
+        const uint2 z = gl[(int64_t)c * chunk + e];
+        lc[o + e] = z;
+        kmax = z.x > kmax ? z.x : kmax;
+      }
+    }
+  }
+  __syncthreads();
+  auto at = [&](uint32_t p) { return staged ? lc[p] : fetch(p); };
+  // strided visit (any order will do for the histograms)
+  auto visit = [&](auto&& f) {
+    for (uint32_t i0 = 0; i0 < total; i0 += 1024) {
+      const bool hit = i0 + tid < total;
+      const uint2 x = at(hit ? i0 + tid : 0);
+      f(x.x, x.y, hit);
+    }
+  };
+  if (!staged) visit([&](uint32_t key, uint32_t, bool hit) { if (hit && key > kmax) kmax = key; });
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) { const uint32_t v = __shfl_xor(kmax, o); kmax = v > kmax ? v : kmax; }
+  if (lane == 0) wsum[wv] = kmax;
+  __syncthreads();
+  for (int x = 0; x < 16; ++x) kmax = wsum[x] > kmax ? wsum[x] : kmax;
+  __syncthreads();
+  // Radix select on d = key - base (every key of the list is >= base, the scan's threshold): pd = the leading
+  // digits of d found so far, s = the number of bits of d below them; rem = how many are still to take among the
+  // pairs whose d starts with pd, cb = how many such pairs there are.  The first level spreads the occupied
+  // range of d over 4096 bins, so the counters are not fought over although the keys share their leading bits.
+  const uint32_t base = spec[0];
+  const uint32_t maxd = kmax - base;
+  int sbits = 32 - __clz((int)(maxd | 1)) - 12;             // bits of maxd beyond the 12 of the first level
+  if (sbits < 0) sbits = 0;
+  uint32_t pd = 0, rem = (uint32_t)want, cb = total;
+  {
+    for (int i = tid; i < kBins12; i += 1024) h[i] = 0;
+    __syncthreads();
+    visit([&](uint32_t key, uint32_t, bool hit) { lds_count(h, (key - base) >> sbits, hit, !staged); });
+    __syncthreads();
+      uint32_t hb[4], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { hb[i] = h[kBins12 - 1 - (4 * tid + i)]; sum += hb[i]; }
+    uint32_t running = block_scan_excl_1024(sum, wsum);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (running < rem && rem <= running + hb[i]) {
+        s_prefix = (uint32_t)(kBins12 - 1 - (4 * tid + i));
+        s_rem = rem - running;
+        s_cb = hb[i];
+      }
+      running += hb[i];
+    }
+    __syncthreads();
+    pd = s_prefix;
+    rem = s_rem;
+    cb = s_cb;
+    __syncthreads();
+  }
+  uint32_t T = 0, req = 0;
+  while (true) {                                            // every condition below is uniform over the workgroup
+    if (sbits == 0) {                                       // d is fully known: the pairs left all hold one key
+      T = base + pd;
+      req = rem;
+      break;
+    }
+    if (cb <= 1024) {
+      // few pairs left: rank them against each other.  sl = their keys; T is the key with fewer than rem keys
+      // above it that, together with its equals, reaches rem.
+      uint32_t* sl = h;
+      if (tid == 0) s_cb = 0;
+      __syncthreads();
+      visit([&](uint32_t key, uint32_t, bool hit) {
+        if (hit && ((key - base) >> sbits) == pd) sl[atomicAdd(&s_cb, 1u)] = key;
+      });
+      __syncthreads();
+      if ((uint32_t)tid < cb) {
+        const uint32_t ki = sl[tid];
+        uint32_t gt = 0, eq = 0;
+        for (uint32_t j = 0; j < cb; ++j) {
+          const uint32_t kj = sl[j];
+          gt += kj > ki;
+          eq += kj == ki;
+        }
+        if (gt < rem && rem <= gt + eq) { s_prefix = ki; s_rem = rem - gt; }   // equal keys write equal values
+      }
+      __syncthreads();
+      T = s_prefix;
+      req = s_rem;
+      break;
+    }
+    const int ns = sbits > 10 ? sbits - 10 : 0, width = sbits - ns;
+    h[tid] = 0;
+    __syncthreads();
+    visit([&](uint32_t key, uint32_t, bool hit) {
+      const uint32_t d = key - base;
+      lds_count(h, (d >> ns) & ((1u << width) - 1), hit && (d >> sbits) == pd, !staged);
+    });
+    __syncthreads();
+    const uint32_t mine = h[1023 - tid];
+    const uint32_t running = block_scan_excl_1024(mine, wsum);
+    if (running < rem && rem <= running + mine) {
+      s_prefix = (pd << width) | (uint32_t)(1023 - tid);
+      s_rem = rem - running;
+      s_cb = mine;
+    }
+    __syncthreads();
+    pd = s_prefix;
+    rem = s_rem;
+    cb = s_cb;
+    sbits = ns;
+    __syncthreads();
+  }
+  // ordered part: thread tid owns the run [tid * E, tid * E + E) of the list
+  const uint32_t E = (total + 1023) / 1024;
+  const uint32_t p0 = (uint32_t)tid * E;
+  const uint32_t p1 = p0 + E < total ? p0 + E : total;
+  uint32_t ng = 0, ne = 0;
+  for (uint32_t p = p0; p < p1; ++p) {
+    const uint32_t key = at(p).x;
+    ng += key > T;
+    ne += key == T;
+  }
+  uint32_t rg = block_scan_excl_1024(ng, wsum);             // pairs above T on lower slots
+  uint32_t re = block_scan_excl_1024(ne, wsum);             // pairs equal to T on lower slots
+  int32_t* out = idx + (int64_t)row * k;
+  for (uint32_t p = p0; p < p1; ++p) {
+    const uint2 x = at(p);
+    if (x.x > T) { out[rg + (re < req ? re : req)] = (int32_t)x.y; ++rg; }
+    else if (x.x == T) { if (re < req) out[rg + re] = (int32_t)x.y; ++re; }
+  }
+  if (tid == 0) count[row] = (int32_t)want;
+}
+
+namespace {
+struct FusedPlan {
+  SelRows sr;
+  SelectOut so;
+  TopkWs t;
+  int64_t chunk;
+  int nchunks;
+};
+int32_t fused_plan(const Layout& L, const NRes& nr, int64_t nmax, int32_t k, void* ws, FusedPlan* f) {
+  for (int b = 0; b < kMaxBatch; ++b) { f->sr.nsel[b] = 0; f->sr.want[b] = -1; }
+  for (int b = 0; b < L.batch; ++b) {
+    f->sr.nsel[b] = nr.n[b];
+    f->sr.want[b] = nr.n[b] < k ? nr.n[b] : k;
+    if (f->sr.want[b] == 0) f->sr.want[b] = -1;
+  }
+  topk_carve(&f->t, ws, L.rows, L.cap);
+  const int bpw = select_scan_bpw(L, nmax > 0 ? nmax : 1);
+  if (bpw == 0) return HCA_ERR_CAPACITY;
+  f->chunk = (int64_t)4 * bpw * L.tpb;
+  const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
+  f->nchunks = (int)((nblocks + 4 * bpw - 1) / (4 * bpw));
+  if (f->nchunks < 1) f->nchunks = 1;
+  if (f->nchunks > kSelectMaxChunks || (int64_t)f->nchunks * f->chunk > f->t.row_entries) return HCA_ERR_CAPACITY;
+  f->so = SelectOut{f->t.prow, f->t.ncand, f->t.cand, reinterpret_cast<uint32_t*>(f->t.pmass), f->t.row_entries};
+  return HCA_OK;
+}
+}  // namespace
+
+// The fused selection in three parts, each on any stream ordered after the one before.
+// 1. threshold from the sample.  The row lengths may be those before the step's token is appended: slots past
+//    them are not sampled, and the estimate does not need the one more slot.
+int32_t launch_select_threshold(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                int32_t k, void* ws, hipStream_t st) {
+  FusedPlan f;
+  int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
+  if (rc != HCA_OK || nmax == 0) return rc;
+  return launch_select_sample(L, kcache, q, nr, k, f.so, st);
+}
+
+// The parts of the fused selection as a decode step strings them together on one stream, two launches per
+// layer: (a) the sampling alone, for the step's first layer; (b) threshold from the samples + append of the
+// step's key; (c) the selecting scan together with the sampling of the next layer's cache (lengths before that
+// layer's own append: the one more slot does not matter to the estimate and is not read).
+int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, void* ws,
+                              hipStream_t st) {
+  TopkWs t;
+  topk_carve(&t, ws, L.rows, L.cap);
+  SelectOut so{t.prow, t.ncand, t.cand, reinterpret_cast<uint32_t*>(t.pmass), t.row_entries};
+  return launch_select_sample_scores(L, kcache, q, nr, so, st);
+}
+
+int32_t launch_select_threshold_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before,
+                                       float* acc, int32_t* pos, const NRes& vrow0, int32_t k, void* ws,
+                                       hipStream_t st) {
+  TopkWs t;
+  topk_carve(&t, ws, L.rows, L.cap);
+  SelectOut so{t.prow, t.ncand, t.cand, reinterpret_cast<uint32_t*>(t.pmass), t.row_entries};
+  return launch_select_rank_append(L, kcache, k_new, nr_before, acc, pos, vrow0, k, so, st);
+}
+
+int32_t launch_select_scan_next(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const void* next_kcache,
+                                const void* next_q, const NRes& next_nr, void* next_ws) {
+  FusedPlan f;
+  int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
+  if (rc != HCA_OK) return rc;
+  TopkWs t2;
+  topk_carve(&t2, next_ws, L.rows, L.cap);
+  return launch_select_scan_and_sample(L, kcache, q, nr, nmax, f.so, st, stamps, next_kcache, next_q, next_nr,
+                                       reinterpret_cast<uint32_t*>(t2.pmass));
+}
+
+// 2. the selecting scan
+int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
+                            void* ws, hipStream_t st, uint64_t* stamps) {
+  FusedPlan f;
+  int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
+  if (rc != HCA_OK || nmax == 0) return rc;
+  return launch_select_scan(L, kcache, q, nr, nmax, f.so, false, st, stamps);
+}
+
+// 3. the selection over the lists, then,
+// for rows whose sampled threshold left too few pairs, a scan with every slot a candidate and the selection
+// again (both launches return at once for every other row).
+int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
+                             int32_t* idx, int32_t* count, void* ws, hipStream_t st) {
+  FusedPlan f;
+  int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
+  if (rc != HCA_OK) return rc;
+  static std::atomic<uint64_t> opted{0};
+  rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit), kFullLds * 8, &opted);
+  if (rc != HCA_OK) return rc;
+  tk_resolve_emit<<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false);
+  if (nmax > 0) {
+    rc = launch_select_scan(L, kcache, q, nr, nmax, f.so, true, st);
+    if (rc != HCA_OK) return rc;
+    tk_resolve_emit<<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true);
+  }
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_score_topk(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
+                          int32_t* idx, int32_t* count, void* ws, hipStream_t st) {
+  int32_t rc = launch_select_threshold(L, kcache, q, nr, nmax, k, ws, st);
+  if (rc != HCA_OK) return rc;
+  rc = launch_select_begin(L, kcache, q, nr, nmax, k, ws, st, nullptr);
+  if (rc != HCA_OK) return rc;
+  return launch_select_finish(L, kcache, q, nr, nmax, k, idx, count, ws, st);
+}
+
+// ---------------------------------------------------------------------------------------
 // Cumulative-weight selection (Sec. 3.2, Eq. 4): the shortest prefix of the descending order whose
 // softmax weight reaches tau.  Weights are integers (fixed-order fp32 arithmetic, see tp_weight), so
 // the histogram sums below are exact and independent of the order in which atomics land.  The

@@ -519,9 +519,11 @@ static int32_t scan_wide_launch(const Layout& L, int g, int c, const uint8_t* pc
   int gps = 1;                                      // groups per LDS slice: the most that fit 128 KiB
   while (gps * 2 <= g && (int64_t)gps * 2 * c * G * 4 <= 128 * 1024) gps *= 2;
   const size_t lds = (size_t)gps * c * G * 4;
-  if (lds > 64 * 1024)
-    HCA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vq_scan_wide_kernel<G>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));   // + 16 B static
+  if (lds > 64 * 1024) {
+    static std::atomic<uint64_t> opted{0};                  // one per instantiation
+    const int32_t rc = lds_opt_in(reinterpret_cast<const void*>(&vq_scan_wide_kernel<G>), 128 * 1024, &opted);   // + 16 B static
+    if (rc != HCA_OK) return rc;
+  }
   vq_scan_wide_kernel<G><<<(unsigned)(vq_tiles(nmax) * L.rows), 1024, lds, st>>>(g, c, gps, L.cap, (const uint16_t*)pcache,
                                                                                  lut, nr, L.n_kv_heads, L.rows, sel, z_opt);
   HCA_HIP(hipGetLastError());
@@ -532,9 +534,11 @@ template <int G, int NG>
 static int32_t scan_launch(const Layout& L, int c, const uint8_t* pcache, float* lut, const NRes& nr,
                            int64_t nmax, float* sel, float* z_opt, hipStream_t st) {
   const size_t lds = (size_t)NG * c * G * 4;
-  if (lds > 64 * 1024)                              // tables beyond 64 KiB need the opt-in (per device; the call is cheap)
-    HCA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&vq_scan_kernel<G, NG>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024));   // + 272 B static
+  if (lds > 64 * 1024) {                            // tables beyond 64 KiB need the opt-in, once per device
+    static std::atomic<uint64_t> opted{0};          // one per instantiation
+    const int32_t rc = lds_opt_in(reinterpret_cast<const void*>(&vq_scan_kernel<G, NG>), 128 * 1024, &opted);   // + 272 B static
+    if (rc != HCA_OK) return rc;
+  }
   // about one workgroup per compute unit, each with at least 1024 tokens, shares a multiple of 1024
   int64_t per_row = 256 / L.rows;
   if (per_row < 1) per_row = 1;

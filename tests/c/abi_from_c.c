@@ -31,6 +31,7 @@ int main(void) {
   CHECK(hca_quantize_keys(&s, NULL, p, 1, n, NULL, NULL, NULL, NULL) == HCA_ERR_BAD_ARG);
   CHECK(hca_score_qkeys(&s, p, p, NULL, (float*)p, NULL, NULL, NULL) == HCA_ERR_BAD_ARG);
   CHECK(hca_topk(&s, (const float*)p, n, 0, (int32_t*)p, (int32_t*)p, p, NULL) == HCA_ERR_CAPACITY);
+  CHECK(hca_score_topk(&s, p, p, n, 0, (int32_t*)p, (int32_t*)p, p, NULL) == HCA_ERR_CAPACITY);
   CHECK(hca_topp(&s, (const float*)p, n, 0.1f, 0.0, 8, (int32_t*)p, (int32_t*)p, NULL, p, NULL) == HCA_ERR_BAD_ARG);
   CHECK(hca_evict(&s, p, (float*)p, (int32_t*)p, n, 0, 0, NULL, p, NULL, NULL, NULL, NULL) == HCA_ERR_CAPACITY);
   s.bits = 3;

@@ -61,6 +61,13 @@ def test_bad_arguments_are_rejected_on_the_host(B):
     assert L.hca_topk(C.byref(s), one, n, 0, one, one, one, None) == -3
     assert L.hca_topk(C.byref(s), one, n, 1025, one, one, one, None) == -3
     assert L.hca_topk(C.byref(s), one, n, 8, one, one, None, None) == -1
+    assert L.hca_score_topk(C.byref(s), one, one, n, 0, one, one, one, None) == -3
+    assert L.hca_score_topk(C.byref(s), one, one, n, 1025, one, one, one, None) == -3
+    assert L.hca_score_topk(C.byref(s), one, None, n, 8, one, one, one, None) == -1
+    assert L.hca_score_topk(C.byref(s), one, one, n, 8, one, one, None, None) == -1
+    big = B.make_shape(1, 32, 8, 9 << 20)                    # more than 8 Mi resident slots in a row: refused
+    nb = (C.c_int64 * 1)(9 << 20)
+    assert L.hca_score_topk(C.byref(big), one, one, nb, 8, one, one, one, None) == -3
     assert L.hca_evict(C.byref(s), one, one, one, n, 0, 0, None, one, None, None, None, None) == -3
     assert L.hca_evict(C.byref(s), one, one, one, n, 10, 11, None, one, None, None, None, None) == -3
     assert L.hca_evict(C.byref(s), one, one, one, n, 200, 0, None, one, None, None, None, None) == 0   # n <= M: nothing to do

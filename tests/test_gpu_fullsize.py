@@ -68,6 +68,13 @@ def test_one_layer_at_full_size(oracle, cfg):
     idx, count = oracle.topk(sel, oc.n, w.k)
     assert np.array_equal(_rows(st.idx), idx), "top-k index sets differ"
     assert np.array_equal(st.count.cpu().numpy().reshape(-1), count)
+    # scan and top-k in one call, in the launch shape bench.py times
+    fidx = torch.full_like(st.idx, -1)
+    fcount = torch.full_like(st.count, -1)
+    B.hca_score_topk(st.shape, st.kcache, q, st.n, w.k, fidx, fcount, st.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(_rows(fidx), idx), "fused scan + top-k: index sets differ"
+    assert np.array_equal(fcount.cpu().numpy().reshape(-1), count)
     pos = np.tile(np.arange(cap, dtype=np.int32), (R, 1))
     acc = np.zeros((R, cap), np.float32)
     V = v_host.numpy().reshape(R, n, 128)
@@ -94,6 +101,9 @@ def test_one_layer_at_full_size(oracle, cfg):
         assert np.array_equal(_rows(st.sel)[:, :M], sel[:, :M])
         idx, count = oracle.topk(sel, oc.n, w.k)
         assert np.array_equal(_rows(st.idx), idx)
+        B.hca_score_topk(st.shape, st.kcache, q2.cuda(), st.n, w.k, fidx, fcount, st.ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(_rows(fidx), idx), "fused scan + top-k on the compacted cache: index sets differ"
         y, _ = oracle.attend(oc, q16, idx, count, pos, V, st.sm_scale)
         assert _rel_err(st.y.cpu().numpy().reshape(-1, 128), y) <= TOL
 
@@ -187,9 +197,10 @@ def test_vq_one_layer_at_full_size(oracle, c):
     assert np.allclose(_rows(acc), oacc, rtol=1e-4, atol=1e-7)
 
 
-def test_step_driver_at_full_size(oracle):
-    """The library's step driver as bench.py runs it - four stages on four streams, a score buffer per layer,
-    in-place eviction - on two layers of workload 4 at full size (1 Mi tokens each), two decode steps, the
+@pytest.mark.parametrize("fused", [False, True])
+def test_step_driver_at_full_size(oracle, fused):
+    """The library's step driver as bench.py runs it - four stages on four streams, a score buffer (or, with
+    the fused scan + top-k, a selection workspace) per slot, in-place eviction - on two layers of workload 4 at full size (1 Mi tokens each), two decode steps, the
     second with an eviction of layer 1: every layer's selection (through its output), output, resident count
     and, at the end, accumulated scores and value-row map against the oracle."""
     import ctypes as C
@@ -229,10 +240,15 @@ def test_step_driver_at_full_size(oracle):
     d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
     keep = []
     for i in range(3):
-        t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
+        if fused:
+            t = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
+            d.ws_select[i] = t.data_ptr()
+        else:
+            t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
+            d.sel[i] = t.data_ptr()
         keep.append(t)
-        d.sel[i] = t.data_ptr()
     d.n_sel = 3
+    d.fused_select = int(fused)
     wsb = B.hca_workspace_bytes(shape, w.k, n0)
     for i in range(4):
         a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)

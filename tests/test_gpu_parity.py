@@ -366,13 +366,15 @@ def test_kernels_are_deterministic(H):
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("Lr,n_sel,spare,tau", [(3, 3, True, 0.0), (5, 3, True, 0.0), (5, 5, True, 0.0), (5, 5, False, 0.0),
-                                                 (3, 3, False, 0.0), (4, 4, False, 0.9), (3, 3, True, 0.95)])
-def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau):
-    """hca_pipeline_step over 3 to 5 layers (score buffers shared between layers or one each), 12 decode
-    steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k or the
-    cumulative-weight selection of Eq. 4 (tau > 0): every layer's output, resident count and final cache state
-    against the oracle run layer by layer."""
+@pytest.mark.parametrize("Lr,n_sel,spare,tau,fused", [
+    (3, 3, True, 0.0, False), (5, 3, True, 0.0, False), (5, 5, True, 0.0, False), (5, 5, False, 0.0, False),
+    (3, 3, False, 0.0, False), (4, 4, False, 0.9, False), (3, 3, True, 0.95, False),
+    (5, 3, True, 0.0, True), (5, 5, False, 0.0, True), (1, 3, False, 0.0, True)])
+def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fused):
+    """hca_pipeline_step over 1 to 5 layers (score buffers shared between layers or one each), 12 decode
+    steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k (as scan +
+    top-k or fused as in hca_score_topk) or the cumulative-weight selection of Eq. 4 (tau > 0): every layer's
+    output, resident count and final cache state against the oracle run layer by layer."""
     import ctypes as C
     from paper_2507_19823_amd import binding as B
     steps, E = 12, 4
@@ -409,8 +411,15 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau):
     wsb = B.hca_workspace_bytes(shape, w.k, n0)
     keep = []
     for i in range(n_sel):
-        t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev); keep.append(t); d.sel[i] = t.data_ptr()
+        if fused:
+            t = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
+            d.ws_select[i] = t.data_ptr()
+        else:
+            t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
+            d.sel[i] = t.data_ptr()
+        keep.append(t)
     d.n_sel = n_sel
+    d.fused_select = int(fused)
     for i in range(4):
         a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
         b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)

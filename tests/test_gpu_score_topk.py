@@ -1,0 +1,88 @@
+"""GPU parity of hca_score_topk (scan and top-k in one call, Sec. 3.2) against the oracle's score + top-k."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as S
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import paper_2507_19823_amd as H
+    assert torch.cuda.is_available(), "GPU tests need the MI355X"
+    H.lib()
+    return H
+
+
+def _rows(t):
+    a = t.detach().cpu().numpy()
+    return a.reshape(a.shape[0] * a.shape[1], *a.shape[2:])
+
+
+def _run(H, oracle, w, keys, q, lens, k):
+    """Quantises `keys` on both sides, cuts the sequences to `lens`, selects k per row; compares index sets."""
+    from paper_2507_19823_amd import binding as B
+    from paper_2507_19823_amd.session import LayerState
+    st = LayerState(w.batch, w.n_q_heads, w.n_kv_heads, w.n, w.bits, w.group, k_max=k, want_z=False)
+    oc = oracle.Cache(w.batch * w.n_kv_heads, w.n, 128, w.bits, w.group)
+    st.quantize(keys.cuda())
+    oracle.quantize(oc, _rows(keys))
+    st.n = list(lens)
+    oc.n[...] = np.repeat(lens, w.n_kv_heads)
+    R = w.batch * w.n_kv_heads
+    idx = torch.full((R, k), -9, dtype=torch.int32, device="cuda")
+    count = torch.full((R,), -9, dtype=torch.int32, device="cuda")
+    B.hca_score_topk(st.shape, st.kcache, q.cuda(), st.n, k, idx, count, st.ws)
+    torch.cuda.synchronize()
+    sel, _ = oracle.score(oc, q.numpy().reshape(-1, 128), want_z=False)
+    ridx, rcount = oracle.topk(sel, oc.n, k)
+    gi, gc = idx.cpu().numpy(), count.cpu().numpy()
+    for r in range(R):
+        c = min(k, lens[r // w.n_kv_heads])
+        assert gc[r] == c == rcount[r], f"row {r}: count {gc[r]} / {rcount[r]} / {c}"
+        assert np.array_equal(gi[r, :c], ridx[r, :c]), f"row {r}: index sets differ"
+        assert np.all(gi[r, c:] == -9)
+    return st
+
+
+@pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
+@pytest.mark.parametrize("n,k,lens", [
+    (300, 64, [300, 17]), (5000, 256, [5000, 0]), (5000, 5000, [4999, 5000]), (70001, 2048, [70001, 33000]),
+    (300000, 1024, [300000, 150001]),
+])
+def test_score_topk_matches_the_oracle(H, oracle, bits, gs, n, k, lens):
+    w = S.Workload("st", 90 + bits, 2, 8, 2, n, bits, gs, k)
+    d = S.make_layer(w, want_values=False)
+    _run(H, oracle, w, d["keys"], d["q"], lens, k)
+
+
+def test_ties_and_a_list_too_long_for_lds(H, oracle):
+    """Every key the same: every slot passes any threshold (50 000 pairs, more than are staged in LDS) and the
+    k lowest slots win."""
+    w = S.Workload("tie", 95, 1, 4, 1, 50000, 4, 32, 777)
+    d = S.make_layer(w, want_values=False)
+    keys = d["keys"][:, :, :1].expand(-1, -1, w.n, -1).contiguous()
+    _run(H, oracle, w, keys, d["q"], [w.n], w.k)
+
+
+@pytest.mark.parametrize("bits,gs,tpb", [(4, 32, 16), (2, 64, 32)])
+def test_a_sample_that_misleads_still_gives_the_exact_set(H, oracle, bits, gs, tpb):
+    """The sample reads block floor(s * nblocks / S), s < S = 8192 / (slots per block).  Those blocks get keys along
+    the query (large scores), all others keys against it: the sampled threshold then admits far fewer than k
+    slots and the row has to go through the second, unthresholded scan."""
+    n, k = 200000, 1024
+    w = S.Workload("mis", 96 + bits, 1, 4, 1, n, bits, gs, k)
+    d = S.make_layer(w, want_values=False)
+    q = d["q"].clone()
+    q[0, 1:] = q[0, :1]                                       # four equal query heads
+    g = torch.Generator().manual_seed(5)
+    noise = 0.05 * torch.randn(n, 128, generator=g)
+    nblocks = (n + tpb - 1) // tpb
+    Sn = min(nblocks, 8192 // tpb)
+    sampled = torch.zeros(nblocks, dtype=torch.bool)
+    sampled[(torch.arange(Sn, dtype=torch.int64) * nblocks) // Sn] = True
+    sign = torch.where(sampled.repeat_interleave(tpb)[:n], 1.0, -1.0)[:, None]
+    keys = (sign * q[0, 0].float()[None, :] * (0.5 + torch.rand(n, 1, generator=g)) + noise).to(torch.float16)
+    _run(H, oracle, w, keys[None, None], q, [n], k)
