@@ -9,7 +9,8 @@ template <int BITS>
 __global__ __launch_bounds__(256) void quantize_kernel(Layout L, uint8_t* __restrict__ kcache,
                                                        const uint16_t* __restrict__ k_new, int64_t T, NRes nr,
                                                        float* __restrict__ acc, int32_t* __restrict__ pos, NRes vrow0) {
-  quantize_body<BITS>(L, kcache, k_new, T, nr, acc, pos, vrow0, (int)blockIdx.x, (int)blockIdx.y);
+  const int seq = blockIdx.y / L.n_kv_heads;
+  quantize_body<BITS>(L, kcache, k_new, T, nr.n[seq], acc, pos, vrow0.n[seq], (int)blockIdx.x, (int)blockIdx.y);
 }
 
 // Canonical export: one thread per (slot, j) piece.

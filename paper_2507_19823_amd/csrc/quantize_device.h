@@ -8,11 +8,12 @@ namespace hca {
 // One wave quantises 16 tokens.  Lane (t = lane%16, j = lane/16) owns the two 16-channel
 // pieces of token t that it will later feed to the matrix core (see Layout), i.e. input bytes
 // [32j, 32j+32) and [128+32j, 128+32j+32) of the token's 256-byte fp16 row.
-// bx = index of the workgroup's 64 tokens; called by all 256 threads of a workgroup.
+// bx = index of the workgroup's 64 tokens, n_before = the row's resident slots, vrow0 = value row of the first new
+// token; called by all 256 threads of a workgroup.
 template <int BITS>
 __device__ __forceinline__ void quantize_body(const Layout& L, uint8_t* __restrict__ kcache,
-                                              const uint16_t* __restrict__ k_new, int64_t T, const NRes& nr,
-                                              float* __restrict__ acc, int32_t* __restrict__ pos, const NRes& vrow0,
+                                              const uint16_t* __restrict__ k_new, int64_t T, const int64_t n_before,
+                                              float* __restrict__ acc, int32_t* __restrict__ pos, const int64_t vrow0,
                                               const int bx, const int row) {
   constexpr int QMAX = (1 << BITS) - 1;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -76,11 +77,11 @@ __device__ __forceinline__ void quantize_body(const Layout& L, uint8_t* __restri
     meta[m] = (uint32_t)sh | ((uint32_t)f2h_bits(mn) << 16);
   }
 
-  const int64_t slot = nr.n[row / L.n_kv_heads] + tc;
+  const int64_t slot = n_before + tc;
   uint8_t* crow = kcache + (int64_t)row * L.codes_row_bytes();
   uint8_t* mrow = kcache + L.meta_off + (int64_t)row * L.meta_row_bytes();
   if (live && j == 1 && acc != nullptr) acc[(int64_t)row * L.cap + slot] = 0.0f;
-  if (live && j == 2 && pos != nullptr) pos[(int64_t)row * L.cap + slot] = (int32_t)(vrow0.n[row / L.n_kv_heads] + tt);
+  if (live && j == 2 && pos != nullptr) pos[(int64_t)row * L.cap + slot] = (int32_t)(vrow0 + tt);
   if (BITS == 4) {
     const uint32_t o0 = __shfl_xor(meta[0], 32), o1 = __shfl_xor(meta[1], 32);
     if (live) {

@@ -381,22 +381,21 @@ __global__ __launch_bounds__(256) void select_sample_score(Layout L, const uint8
 }
 
 // 256 threads per row: small enough to find room on a chip that another stream's scan keeps full
-__device__ __forceinline__ void sample_rank_body(const Layout& L, const NRes& nr, int32_t k, const SelectOut& so,
-                                                 const int row) {
+__device__ __forceinline__ void sample_rank_body(const int64_t n, int32_t k, const uint32_t* __restrict__ samples,
+                                                 uint32_t* __restrict__ spec, const int row) {
   constexpr int kPer = kSampleTokens / 256;
   __shared__ uint32_t hist[4096];
   __shared__ uint32_t wsum[4];
   __shared__ uint32_t s_bin, s_rem;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int64_t n = nr.n[row / L.n_kv_heads];
   const int64_t want = n < k ? n : k;
-  uint32_t* sp = so.spec + 4 * row;
+  uint32_t* sp = spec + 4 * row;
   if (want <= 0) {
     if (tid == 0) { sp[0] = 0xffffffffu; sp[1] = 0; }
     return;
   }
   uint32_t key[kPer];
-  const uint32_t* in = so.samples + (int64_t)row * kSampleTokens;
+  const uint32_t* in = samples + (int64_t)row * kSampleTokens;
 #pragma unroll
   for (int i = 0; i < kPer; ++i) key[i] = in[i * 256 + tid];
   for (int i = tid; i < 4096; i += 256) hist[i] = 0;
@@ -464,7 +463,7 @@ __device__ __forceinline__ void sample_rank_body(const Layout& L, const NRes& nr
 }
 
 __global__ __launch_bounds__(256) void select_sample_rank(Layout L, NRes nr, int32_t k, SelectOut so) {
-  sample_rank_body(L, nr, k, so, (int)blockIdx.x);
+  sample_rank_body(nr.n[blockIdx.x / L.n_kv_heads], k, so.samples, so.spec, (int)blockIdx.x);
 }
 
 // The two small jobs of a layer that precede its selecting scan in a decode step, as one launch: workgroup
@@ -476,8 +475,9 @@ __global__ __launch_bounds__(256) void select_rank_append(Layout L, NRes nr_befo
                                                           const uint16_t* __restrict__ k_new,
                                                           float* __restrict__ acc, int32_t* __restrict__ pos,
                                                           NRes vrow0) {
-  if (blockIdx.x == 0) sample_rank_body(L, nr_after, k, so, (int)blockIdx.y);
-  else quantize_body<BITS>(L, kcache, k_new, 1, nr_before, acc, pos, vrow0, 0, (int)blockIdx.y);
+  const int seq = blockIdx.y / L.n_kv_heads;
+  if (blockIdx.x == 0) sample_rank_body(nr_after.n[seq], k, so.samples, so.spec, (int)blockIdx.y);
+  else quantize_body<BITS>(L, kcache, k_new, 1, nr_before.n[seq], acc, pos, vrow0.n[seq], 0, (int)blockIdx.y);
 }
 
 // The selecting scan of one layer with, as its first kSampleWgs workgroups per row, the sampling for another

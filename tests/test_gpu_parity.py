@@ -369,7 +369,7 @@ def test_kernels_are_deterministic(H):
 @pytest.mark.parametrize("Lr,n_sel,spare,tau,fused", [
     (3, 3, True, 0.0, False), (5, 3, True, 0.0, False), (5, 5, True, 0.0, False), (5, 5, False, 0.0, False),
     (3, 3, False, 0.0, False), (4, 4, False, 0.9, False), (3, 3, True, 0.95, False),
-    (5, 3, True, 0.0, True), (5, 5, False, 0.0, True), (1, 3, False, 0.0, True)])
+    (5, 3, True, 0.0, True), (5, 5, False, 0.0, True), (1, 3, False, 0.0, True), (4, 4, True, 0.0, True)])
 def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fused):
     """hca_pipeline_step over 1 to 5 layers (score buffers shared between layers or one each), 12 decode
     steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k (as scan +
