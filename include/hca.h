@@ -122,7 +122,7 @@ int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resi
 
 /* Steps 2 and 3a in one call (Eq. 2, then the sorted prefix Pi_k of Sec. 3.2): idx and count exactly as
  * hca_score_qkeys followed by hca_topk would leave them, without the score of every slot ever reaching
- * memory.  A strided sample of each row (8192 slots) is scored first and gives a threshold that at least k
+ * memory.  A strided sample of each row (8192 to 65536 slots) is scored first and gives a threshold that at least k
  * slots of the row pass with overwhelming probability; the scan then keeps only the (score, slot) pairs
  * at or above it, and the selection runs on those few thousand pairs.  A row whose sample misled (fewer
  * than k pairs) is scanned a second time with no threshold inside the same call, so the result never
@@ -131,6 +131,15 @@ int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resi
  * Errors: HCA_ERR_CAPACITY if k < 1, k > capacity, or a row holds more than 8 Mi resident slots. */
 int32_t hca_score_topk(const hca_shape* shape, const void* kcache, const void* q_f16, const int64_t* n_resident,
                        int32_t k, int32_t* idx, int32_t* count, void* workspace, void* stream);
+
+/* What the last hca_score_topk on `workspace` did (same shape and n_resident; to be called before the workspace
+ * is used for anything else): per row the number of (score, slot) pairs that passed the threshold of the scan
+ * that produced the result - all resident slots if that was the second scan - and whether the row needed that
+ * second scan.  A monitor for the sampling step with which the top-k of Sec. 3.2 is found here, not part of the
+ * method.
+ *   candidates, rescanned  device, int32 [batch, n_kv_heads] each */
+int32_t hca_score_topk_report(const hca_shape* shape, const int64_t* n_resident, void* workspace,
+                              int32_t* candidates, int32_t* rescanned, void* stream);
 
 /* Step 3b, Eq. 5 with the softmax taken over the selected set: for each query
  * head, l_i = z~[idx_i] * sm_scale (z~ recomputed from the codes),

@@ -81,6 +81,8 @@ def lib():
         L.hca_topk.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp]
         L.hca_score_topk.restype = i32
         L.hca_score_topk.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp, vp]
+        L.hca_score_topk_report.restype = i32
+        L.hca_score_topk_report.argtypes = [sp, vp, vp, vp, vp, vp]
         L.hca_score_qkeys_lse.restype = i32
         L.hca_score_qkeys_lse.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, vp]
         L.hca_attend_gathered_global.restype = i32
@@ -199,6 +201,12 @@ def hca_score_topk(shape, kcache, q_f16, n_resident, k, idx, count, workspace, s
     nr = _nres(n_resident, shape.batch)
     _check(lib().hca_score_topk(C.byref(shape), _ptr(kcache), _ptr(q_f16), nr, int(k), _ptr(idx), _ptr(count),
                                 _ptr(workspace), _stream(stream)), "hca_score_topk")
+
+
+def hca_score_topk_report(shape, n_resident, workspace, candidates, rescanned, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_score_topk_report(C.byref(shape), nr, _ptr(workspace), _ptr(candidates), _ptr(rescanned),
+                                       _stream(stream)), "hca_score_topk_report")
 
 
 def hca_topk(shape, sel, n_resident, k, idx, count, workspace, stream=None):

@@ -166,6 +166,19 @@ int32_t hca_score_topk(const hca_shape* shape, const void* kcache, const void* q
   return launch_score_topk(L, kcache, q_f16, nr, nmax, k, idx, count, workspace, (hipStream_t)stream);
 }
 
+int32_t hca_score_topk_report(const hca_shape* shape, const int64_t* n_resident, void* workspace, int32_t* candidates,
+                              int32_t* rescanned, void* stream) {
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (workspace == nullptr || candidates == nullptr || rescanned == nullptr) return HCA_ERR_BAD_ARG;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  return launch_select_report(L, nr, nmax, workspace, candidates, rescanned, (hipStream_t)stream);
+}
+
 int32_t hca_score_qkeys_lse(const hca_shape* shape, const void* kcache, const void* q_f16,
                             const int64_t* n_resident, float sm_scale, float* sel, float* lse, void* workspace,
                             void* stream) {

@@ -92,9 +92,12 @@ struct SelectOut {
   uint32_t* spec;       // [rows][4]: threshold key t0, 1 = the row has to be scanned again with t0 = 0, -, -
   uint32_t* ncand;      // [rows][kSelectMaxChunks] pairs in each chunk's list
   uint2* lists;         // [rows][row_entries]: chunk c owns entries [c * chunk, (c + 1) * chunk)
-  uint32_t* samples;    // [rows][8192] keys of the sampled slots (0: no such slot)
+  uint32_t* samples;    // [rows][m_samples] keys of the sampled slots (0: no such slot)
   int64_t row_entries;
+  int m_samples;        // slots sampled per row (select_sample_count)
 };
+constexpr int kSampleMax = 65536;
+int select_sample_count(int64_t nmax, int32_t k);
 // blocks per wave of the selecting scan over nmax slots (chunks per row <= kSelectMaxChunks); 0: too long a row
 int select_scan_bpw(const Layout& L, int64_t nmax);
 int32_t launch_select_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int32_t k,
@@ -107,21 +110,23 @@ int32_t launch_select_rank_append(const Layout& L, void* kcache, const void* k_n
                                   int32_t* pos, const NRes& vrow0, int32_t k, const SelectOut& so, hipStream_t st);
 int32_t launch_select_scan_and_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                                       const SelectOut& so, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples);
-int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, void* ws,
-                              hipStream_t st);
+                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples, int next_m);
+int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                              int32_t k, void* ws, hipStream_t st);
 int32_t launch_select_threshold_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before,
-                                       float* acc, int32_t* pos, const NRes& vrow0, int32_t k, void* ws,
-                                       hipStream_t st);
+                                       int64_t nmax_before, float* acc, int32_t* pos, const NRes& vrow0, int32_t k,
+                                       void* ws, hipStream_t st);
 int32_t launch_select_scan_next(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                                 int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                const void* next_q, const NRes& next_nr, void* next_ws);
+                                const void* next_q, const NRes& next_nr, int64_t next_nmax, void* next_ws);
 int32_t launch_select_threshold(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                                 int32_t k, void* ws, hipStream_t st);
 int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
                             void* ws, hipStream_t st, uint64_t* stamps = nullptr);
 int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
                              int32_t* idx, int32_t* count, void* ws, hipStream_t st);
+int32_t launch_select_report(const Layout& L, const NRes& nr, int64_t nmax, void* ws, int32_t* candidates,
+                             int32_t* rescanned, hipStream_t st);
 int32_t launch_score_topk(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
                           int32_t* idx, int32_t* count, void* ws, hipStream_t st);
 int32_t launch_topp(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, float sm_scale, double tau,

@@ -151,7 +151,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (rc != HCA_OK) return rc;
     if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[0], 0));
     HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[0], 0));
-    rc = launch_select_samples(L, layers[0].kcache, layers[0].q, n0, p->d.ws_select[0], sa);
+    rc = launch_select_samples(L, layers[0].kcache, layers[0].q, n0, m0, k, p->d.ws_select[0], sa);
     if (rc != HCA_OK) return rc;
   }
   for (int l = 0; l < p->n_layers; ++l) {
@@ -174,7 +174,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     // previous step, which layer_done covers)
     if (fused) {
       // (the waits for this layer's buffers went out before its sampling, one layer earlier)
-      rc = launch_select_threshold_append(L, ly.kcache, ly.k_new, nr, ly.acc, ly.pos, vrow0, k, p->d.ws_select[s3], sa);
+      rc = launch_select_threshold_append(L, ly.kcache, ly.k_new, nr, nmax, ly.acc, ly.pos, vrow0, k, p->d.ws_select[s3], sa);
       if (rc != HCA_OK) return rc;
       for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
       nmax += 1;
@@ -203,7 +203,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[t3], 0));
       HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l + 1], 0));
       return launch_select_scan_next(L, ly.kcache, ly.q, nr, nmax, k, p->d.ws_select[s3], sa, stamps, layers[l + 1].kcache,
-                                     layers[l + 1].q, n2, p->d.ws_select[t3]);
+                                     layers[l + 1].q, n2, m2, p->d.ws_select[t3]);
     };
     rc = vq ? launch_vq_score(L, vg, vc, ly.vq_centroids, (const uint8_t*)ly.kcache, ly.q, nr, nmax, ly.vq_lut,
                               p->d.sel[s3], nullptr, sa)

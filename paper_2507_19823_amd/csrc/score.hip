@@ -1,5 +1,7 @@
 // Step 2: the key scan.  z~ = q . Q(K)^T (Eq. 2 / Eq. 3) for every resident token, streamed
 // once from HBM as packed codes and contracted on the matrix cores in exact integer arithmetic.
+#include <math.h>
+
 #include "hca_internal.h"
 #include "quantize_device.h"
 
@@ -251,7 +253,7 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
 }
 
 // The selecting scan once more for the rows whose sampled threshold left too few pairs (spec[row][1] != 0, with
-// the threshold already reset to 0).  Almost always there is no such row, so the launch is kept small - a few
+// the threshold already reset to 0).  Almost always there is no such row, so the launch is kept small - up to 64
 // workgroups per row that walk over the row's chunks - and costs next to nothing when it has nothing to do.
 template <int BITS, int U>
 __global__ __launch_bounds__(256) void score_failed_rows_kernel(Layout L, const uint8_t* __restrict__ kcache,
@@ -301,8 +303,9 @@ __global__ __launch_bounds__(256) void lse_merge(Layout L, NRes nr, int bpw, int
   }
 }
 
-// Threshold estimate for the selecting scan.  kSampleTokens slots of every row (whole code blocks, evenly spaced:
-// sampled block s is block floor(s * nblocks / S) of the row) are scored by select_sample_score; select_sample_rank
+// Threshold estimate for the selecting scan.  m slots of every row (whole code blocks, evenly spaced: sampled
+// block s is block floor(s * nblocks / S) of the row, S = min(nblocks, m / slots per block); m = 8192 .. 65536, a
+// power of two chosen by select_sample_count) are scored by select_sample_score; select_sample_rank
 // then leaves in spec[row] a key t0 such that, if the sample behaves like a random one, at least `want` slots of
 // the row have keys >= t0 with overwhelming probability:
 //   m = sampled slots, kappa = want * m / n, r = ceil((3 + sqrt(9 + kappa))^2)  (the count of slots above the
@@ -310,32 +313,32 @@ __global__ __launch_bounds__(256) void lse_merge(Layout L, NRes nr, int bpw, int
 //   below the mean), t0 = the r-th largest sampled key with its low 10 bits cleared; t0 = 0 when r >= m.
 // The selection stays exact whatever the sample does: a row whose list comes out short is scanned again with
 // t0 = 0 (spec[row][1]).
-constexpr int kSampleTokens = 8192;
-constexpr int kSampleWgs = 16;
+constexpr int kSamplePerWg = 512;       // sampled slots per workgroup: m / 512 workgroups per row
 
-// bx = which of the kSampleWgs workgroups of the row this is; called by all 256 threads
+// bx = which of the m / kSamplePerWg workgroups of the row this is; called by all 256 threads
 template <int BITS>
 __device__ __forceinline__ void sample_score_body(const Layout& L, const uint8_t* __restrict__ kcache,
                                                   const uint16_t* __restrict__ q, const NRes& nr,
-                                                  uint32_t* __restrict__ samples, const int bx, const int row) {
+                                                  uint32_t* __restrict__ samples, const int m, const int bx,
+                                                  const int row) {
   constexpr int kTpb = BITS == 4 ? 16 : 32;
-  constexpr int kPerWave = kSampleTokens / kTpb / (4 * kSampleWgs);   // sampled blocks per wave: 8 (4-bit) or 4
+  constexpr int kPerWave = kSamplePerWg / kTpb / 4;        // sampled blocks per wave: 8 (4-bit) or 4
   __shared__ QShared sh;
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t n = nr.n[row / L.n_kv_heads];
   if (n <= 0) {                                             // nothing to sample: this workgroup's share reads "no slot"
-    for (int i = threadIdx.x; i < kSampleTokens / kSampleWgs; i += 256)
-      samples[(int64_t)row * kSampleTokens + bx * (kSampleTokens / kSampleWgs) + i] = 0;
+    for (int i = threadIdx.x; i < kSamplePerWg; i += 256)
+      samples[(int64_t)row * m + bx * kSamplePerWg + i] = 0;
     return;
   }
   const int nblocks = (int)((n + kTpb - 1) / kTpb);
-  const int S = nblocks < kSampleTokens / kTpb ? nblocks : kSampleTokens / kTpb;
+  const int S = nblocks < m / kTpb ? nblocks : m / kTpb;
   const int t = lane & 15, hd = lane >> 4;
   const uint4* cptr = reinterpret_cast<const uint4*>(kcache + (int64_t)row * L.codes_row_bytes()) + lane;
   const uint32_t* mptr = reinterpret_cast<const uint32_t*>(kcache + L.meta_off + (int64_t)row * L.meta_row_bytes()) +
                          (BITS == 4 ? 4 * t + hd : 2 * (16 * (hd >> 1) + t) + (hd & 1));
-  uint32_t* out = samples + (int64_t)row * kSampleTokens;
+  uint32_t* out = samples + (int64_t)row * m;
   const int s0 = (bx * 4 + w) * kPerWave;
   uint4 wv[kPerWave];
   uint32_t mw[kPerWave];
@@ -377,13 +380,12 @@ __device__ __forceinline__ void sample_score_body(const Layout& L, const uint8_t
 template <int BITS>
 __global__ __launch_bounds__(256) void select_sample_score(Layout L, const uint8_t* __restrict__ kcache,
                                                            const uint16_t* __restrict__ q, NRes nr, SelectOut so) {
-  sample_score_body<BITS>(L, kcache, q, nr, so.samples, (int)blockIdx.x, (int)blockIdx.y);
+  sample_score_body<BITS>(L, kcache, q, nr, so.samples, so.m_samples, (int)blockIdx.x, (int)blockIdx.y);
 }
 
 // 256 threads per row: small enough to find room on a chip that another stream's scan keeps full
 __device__ __forceinline__ void sample_rank_body(const int64_t n, int32_t k, const uint32_t* __restrict__ samples,
-                                                 uint32_t* __restrict__ spec, const int row) {
-  constexpr int kPer = kSampleTokens / 256;
+                                                 const int m_samples, uint32_t* __restrict__ spec, const int row) {
   __shared__ uint32_t hist[4096];
   __shared__ uint32_t wsum[4];
   __shared__ uint32_t s_bin, s_rem;
@@ -394,15 +396,17 @@ __device__ __forceinline__ void sample_rank_body(const int64_t n, int32_t k, con
     if (tid == 0) { sp[0] = 0xffffffffu; sp[1] = 0; }
     return;
   }
-  uint32_t key[kPer];
-  const uint32_t* in = samples + (int64_t)row * kSampleTokens;
-#pragma unroll
-  for (int i = 0; i < kPer; ++i) key[i] = in[i * 256 + tid];
+  const uint32_t* in = samples + (int64_t)row * m_samples;
   for (int i = tid; i < 4096; i += 256) hist[i] = 0;
   __syncthreads();
+  for (int i0 = 0; i0 < m_samples; i0 += 8 * 256) {        // 8 loads in flight per thread
+    uint32_t key[8];
 #pragma unroll
-  for (int i = 0; i < kPer; ++i)
-    if (key[i] != 0) atomicAdd(&hist[key[i] >> 20], 1u);
+    for (int i = 0; i < 8; ++i) key[i] = in[i0 + i * 256 + tid];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (key[i] != 0) atomicAdd(&hist[key[i] >> 20], 1u);
+  }
   __syncthreads();
   // exclusive prefix over the threads of `sum`, and the total
   auto scan256 = [&](uint32_t sum, uint32_t* total) {
@@ -442,9 +446,14 @@ __device__ __forceinline__ void sample_rank_body(const int64_t n, int32_t k, con
   const uint32_t bin = s_bin, rem = s_rem;
   for (int i = tid; i < 1024; i += 256) hist[i] = 0;
   __syncthreads();
+  for (int i0 = 0; i0 < m_samples; i0 += 8 * 256) {
+    uint32_t key[8];
 #pragma unroll
-  for (int i = 0; i < kPer; ++i)
-    if (key[i] != 0 && (key[i] >> 20) == bin) atomicAdd(&hist[(key[i] >> 10) & 1023u], 1u);
+    for (int i = 0; i < 8; ++i) key[i] = in[i0 + i * 256 + tid];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (key[i] != 0 && (key[i] >> 20) == bin) atomicAdd(&hist[(key[i] >> 10) & 1023u], 1u);
+  }
   __syncthreads();
   uint32_t g[4];
   sum = 0;
@@ -463,7 +472,7 @@ __device__ __forceinline__ void sample_rank_body(const int64_t n, int32_t k, con
 }
 
 __global__ __launch_bounds__(256) void select_sample_rank(Layout L, NRes nr, int32_t k, SelectOut so) {
-  sample_rank_body(nr.n[blockIdx.x / L.n_kv_heads], k, so.samples, so.spec, (int)blockIdx.x);
+  sample_rank_body(nr.n[blockIdx.x / L.n_kv_heads], k, so.samples, so.m_samples, so.spec, (int)blockIdx.x);
 }
 
 // The two small jobs of a layer that precede its selecting scan in a decode step, as one launch: workgroup
@@ -476,16 +485,17 @@ __global__ __launch_bounds__(256) void select_rank_append(Layout L, NRes nr_befo
                                                           float* __restrict__ acc, int32_t* __restrict__ pos,
                                                           NRes vrow0) {
   const int seq = blockIdx.y / L.n_kv_heads;
-  if (blockIdx.x == 0) sample_rank_body(nr_after.n[seq], k, so.samples, so.spec, (int)blockIdx.y);
+  if (blockIdx.x == 0) sample_rank_body(nr_after.n[seq], k, so.samples, so.m_samples, so.spec, (int)blockIdx.y);
   else quantize_body<BITS>(L, kcache, k_new, 1, nr_before.n[seq], acc, pos, vrow0.n[seq], 0, (int)blockIdx.y);
 }
 
-// The selecting scan of one layer with, as its first kSampleWgs workgroups per row, the sampling for another
+// The selecting scan of one layer with, as its first m / 512 workgroups per row, the sampling for another
 // cache (the next layer of the step): the sampling then costs no launch of its own.
 struct SampleJob {
   const uint8_t* kcache;
   const uint16_t* q;
   uint32_t* samples;
+  int m;                      // slots to sample per row; the launch has m / kSamplePerWg more workgroups per row
   NRes nr;
 };
 template <int BITS, int U>
@@ -493,12 +503,28 @@ __global__ __launch_bounds__(256) void score_select_sample_kernel(Layout L, cons
                                                                   const uint16_t* __restrict__ q, NRes nr, int bpw,
                                                                   uint64_t* __restrict__ stamps, SelectOut so,
                                                                   SampleJob sj) {
-  if (blockIdx.x < kSampleWgs) {
-    sample_score_body<BITS>(L, sj.kcache, sj.q, sj.nr, sj.samples, (int)blockIdx.x, (int)blockIdx.y);
+  const int extra = sj.m / kSamplePerWg;
+  if ((int)blockIdx.x < extra) {
+    sample_score_body<BITS>(L, sj.kcache, sj.q, sj.nr, sj.samples, sj.m, (int)blockIdx.x, (int)blockIdx.y);
     return;
   }
   score_body<BITS, false, U, false, true>(L, kcache, q, nr, bpw, nullptr, nullptr, stamps, 0.f, nullptr, so,
-                                          (int)blockIdx.x - kSampleWgs, (int)gridDim.x - kSampleWgs);
+                                          (int)blockIdx.x - extra, (int)gridDim.x - extra);
+}
+
+// Slots to sample per row.  More samples give a tighter threshold: with m samples the scan lets through about
+// n r / m pairs per row, r as in the comment above.  The smallest of 8192 .. 65536 that keeps that estimate within
+// what the selection holds in LDS (16384 pairs, less a margin for the spread of the count).
+int select_sample_count(int64_t nmax, int32_t k) {
+  int m = 8192;
+  for (; m < 65536; m *= 2) {
+    const double want = (double)(k < nmax ? k : nmax);
+    const double kappa = want * m / (double)(nmax > 0 ? nmax : 1);
+    const double root = 3.0 + sqrt(9.0 + kappa);
+    const double r = root * root;
+    if (r >= m || (double)nmax * r / m <= 14336.0) break;
+  }
+  return m;
 }
 
 int select_scan_bpw(const Layout& L, int64_t nmax) {
@@ -518,7 +544,7 @@ int32_t launch_select_sample_scores(const Layout& L, const void* kcache, const v
                                     const SelectOut& so, hipStream_t st) {
   const uint8_t* kc = (const uint8_t*)kcache;
   const uint16_t* qq = (const uint16_t*)q;
-  dim3 grid(kSampleWgs, (unsigned)L.rows);
+  dim3 grid((unsigned)(so.m_samples / kSamplePerWg), (unsigned)L.rows);
   if (L.bits == 4) select_sample_score<4><<<grid, 256, 0, st>>>(L, kc, qq, nr, so);
   else select_sample_score<2><<<grid, 256, 0, st>>>(L, kc, qq, nr, so);
   HCA_HIP(hipGetLastError());
@@ -552,14 +578,14 @@ int32_t launch_select_rank_append(const Layout& L, void* kcache, const void* k_n
 // The selecting scan plus the sampling of another cache (next_* as in launch_select_sample's arguments).
 int32_t launch_select_scan_and_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                                       const SelectOut& so, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples) {
+                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples, int next_m) {
   if (nmax == 0) return HCA_ERR_BAD_ARG;
   const int bpw = select_scan_bpw(L, nmax);
   if (bpw == 0) return HCA_ERR_CAPACITY;
   const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
-  dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)) + kSampleWgs, (unsigned)L.rows);
+  dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)) + (unsigned)(next_m / kSamplePerWg), (unsigned)L.rows);
   const size_t lds = (size_t)4 * bpw * L.tpb * sizeof(uint2);
-  SampleJob sj{(const uint8_t*)next_kcache, (const uint16_t*)next_q, next_samples, next_nr};
+  SampleJob sj{(const uint8_t*)next_kcache, (const uint16_t*)next_q, next_samples, next_m, next_nr};
   if (L.bits == 4)
     score_select_sample_kernel<4, 8><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
                                                              so, sj);
@@ -581,7 +607,7 @@ int32_t launch_select_scan(const Layout& L, const void* kcache, const void* q, c
   const uint8_t* kc = (const uint8_t*)kcache;
   const uint16_t* qq = (const uint16_t*)q;
   if (only_failed) {
-    dim3 small(grid.x < 16 ? grid.x : 16, (unsigned)L.rows);
+    dim3 small(grid.x < 64 ? grid.x : 64, (unsigned)L.rows);
     if (L.bits == 4) score_failed_rows_kernel<4, 8><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
     else score_failed_rows_kernel<2, 4><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
   } else if (L.bits == 4) {

@@ -239,6 +239,9 @@ struct TopkWs {
   uint64_t* pmass;     // [rows][4096] integer weight per bin
   uint64_t* pstate;    // [rows][4]: target still to reach, Theta, Z, (unused)
   uint32_t* prow;      // [rows][4]: key of the row maximum, slots still allowed, selected count, (unused)
+  // scan + top-k in one call only
+  uint32_t* samples;   // [rows][kSampleMax] keys of the sampled slots
+  uint32_t* spec;      // [rows][4]: threshold key, 1 = row scanned a second time, unused, unused
 };
 
 // chunk geometry for a row of n slots: at most 1024 chunks, each a multiple of 1024 slots, >= 4096
@@ -269,6 +272,8 @@ size_t topk_workspace_bytes(int rows, int64_t cap) {
   b += align_up((int64_t)rows * kBins12 * 8, 256);
   b += align_up((int64_t)rows * 4 * 8, 256);
   b += align_up((int64_t)rows * 4 * 4, 256);
+  b += align_up((int64_t)rows * kSampleMax * 4, 256);
+  b += align_up((int64_t)rows * 4 * 4, 256);
   return b;
 }
 
@@ -285,7 +290,9 @@ static void topk_carve(TopkWs* t, void* ws, int rows, int64_t cap) {
   t->pcount = (uint32_t*)w; w += align_up((int64_t)rows * kBins12 * 4, 256);
   t->pmass = (uint64_t*)w;  w += align_up((int64_t)rows * kBins12 * 8, 256);
   t->pstate = (uint64_t*)w; w += align_up((int64_t)rows * 4 * 8, 256);
-  t->prow = (uint32_t*)w;
+  t->prow = (uint32_t*)w;   w += align_up((int64_t)rows * 4 * 4, 256);
+  t->samples = (uint32_t*)w; w += align_up((int64_t)rows * kSampleMax * 4, 256);
+  t->spec = (uint32_t*)w;
 }
 
 __global__ void tk_zero(uint32_t* p, int64_t n) {
@@ -990,7 +997,7 @@ int32_t fused_plan(const Layout& L, const NRes& nr, int64_t nmax, int32_t k, voi
   f->nchunks = (int)((nblocks + 4 * bpw - 1) / (4 * bpw));
   if (f->nchunks < 1) f->nchunks = 1;
   if (f->nchunks > kSelectMaxChunks || (int64_t)f->nchunks * f->chunk > f->t.row_entries) return HCA_ERR_CAPACITY;
-  f->so = SelectOut{f->t.prow, f->t.ncand, f->t.cand, reinterpret_cast<uint32_t*>(f->t.pmass), f->t.row_entries};
+  f->so = SelectOut{f->t.spec, f->t.ncand, f->t.cand, f->t.samples, f->t.row_entries, select_sample_count(nmax, k)};
   return HCA_OK;
 }
 }  // namespace
@@ -1010,33 +1017,35 @@ int32_t launch_select_threshold(const Layout& L, const void* kcache, const void*
 // layer: (a) the sampling alone, for the step's first layer; (b) threshold from the samples + append of the
 // step's key; (c) the selecting scan together with the sampling of the next layer's cache (lengths before that
 // layer's own append: the one more slot does not matter to the estimate and is not read).
-int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, void* ws,
-                              hipStream_t st) {
+// (nmax, nmax_before, next_nmax: the longest row at the lengths before the step's append - the sampling of a layer
+// and its threshold must agree on the sample count, which depends on it.)
+int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                              int32_t k, void* ws, hipStream_t st) {
   TopkWs t;
   topk_carve(&t, ws, L.rows, L.cap);
-  SelectOut so{t.prow, t.ncand, t.cand, reinterpret_cast<uint32_t*>(t.pmass), t.row_entries};
+  SelectOut so{t.spec, t.ncand, t.cand, t.samples, t.row_entries, select_sample_count(nmax, k)};
   return launch_select_sample_scores(L, kcache, q, nr, so, st);
 }
 
 int32_t launch_select_threshold_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before,
-                                       float* acc, int32_t* pos, const NRes& vrow0, int32_t k, void* ws,
-                                       hipStream_t st) {
+                                       int64_t nmax_before, float* acc, int32_t* pos, const NRes& vrow0, int32_t k,
+                                       void* ws, hipStream_t st) {
   TopkWs t;
   topk_carve(&t, ws, L.rows, L.cap);
-  SelectOut so{t.prow, t.ncand, t.cand, reinterpret_cast<uint32_t*>(t.pmass), t.row_entries};
+  SelectOut so{t.spec, t.ncand, t.cand, t.samples, t.row_entries, select_sample_count(nmax_before, k)};
   return launch_select_rank_append(L, kcache, k_new, nr_before, acc, pos, vrow0, k, so, st);
 }
 
 int32_t launch_select_scan_next(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                                 int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                const void* next_q, const NRes& next_nr, void* next_ws) {
+                                const void* next_q, const NRes& next_nr, int64_t next_nmax, void* next_ws) {
   FusedPlan f;
   int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
   if (rc != HCA_OK) return rc;
   TopkWs t2;
   topk_carve(&t2, next_ws, L.rows, L.cap);
   return launch_select_scan_and_sample(L, kcache, q, nr, nmax, f.so, st, stamps, next_kcache, next_q, next_nr,
-                                       reinterpret_cast<uint32_t*>(t2.pmass));
+                                       t2.samples, select_sample_count(next_nmax, k));
 }
 
 // 2. the selecting scan
@@ -1076,6 +1085,34 @@ int32_t launch_score_topk(const Layout& L, const void* kcache, const void* q, co
   rc = launch_select_begin(L, kcache, q, nr, nmax, k, ws, st, nullptr);
   if (rc != HCA_OK) return rc;
   return launch_select_finish(L, kcache, q, nr, nmax, k, idx, count, ws, st);
+}
+
+// What the last fused selection on this workspace did, per row: pairs that passed the threshold of the scan that
+// produced the result, and whether that scan was the second, unthresholded one.
+__global__ __launch_bounds__(256) void tk_select_report(TopkWs t, int nchunks, int32_t* __restrict__ candidates,
+                                                        int32_t* __restrict__ rescanned) {
+  __shared__ uint32_t wsum[4];
+  const int row = blockIdx.x;
+  uint32_t v = 0;
+  for (int c = threadIdx.x; c < nchunks; c += 256) v += t.ncand[(int64_t)row * kMaxChunks + c];
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o);
+  if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = v;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    candidates[row] = (int32_t)(wsum[0] + wsum[1] + wsum[2] + wsum[3]);
+    rescanned[row] = (int32_t)t.spec[4 * row + 1];
+  }
+}
+
+int32_t launch_select_report(const Layout& L, const NRes& nr, int64_t nmax, void* ws, int32_t* candidates,
+                             int32_t* rescanned, hipStream_t st) {
+  FusedPlan f;
+  const int32_t rc = fused_plan(L, nr, nmax, 1, ws, &f);
+  if (rc != HCA_OK) return rc;
+  tk_select_report<<<L.rows, 256, 0, st>>>(f.t, nmax > 0 ? f.nchunks : 0, candidates, rescanned);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
 }
 
 // ---------------------------------------------------------------------------------------

@@ -58,6 +58,13 @@ class LayerState:
         self.idx = self.idx_buf[: self.rows * k].view(self.batch, self.hkv, k)   # row stride k
         B.hca_topk(self.shape, self.sel, self.n, k, self.idx, self.count, self.ws, stream)
 
+    def score_topk(self, q, k, stream=None):
+        """score + topk as one call that never writes the per-token scores (self.sel is left untouched)."""
+        assert k <= self.k_max
+        self.k = k
+        self.idx = self.idx_buf[: self.rows * k].view(self.batch, self.hkv, k)
+        B.hca_score_topk(self.shape, self.kcache, q, self.n, k, self.idx, self.count, self.ws, stream)
+
     def attend(self, q, v_host, n_host_rows, v_hbm, use_acc=True, gather_stream=None, stream=None):
         hs = 0 if v_host is None else v_host.shape[2]
         ds = 0 if v_hbm is None else v_hbm.shape[2]

@@ -75,6 +75,12 @@ def test_one_layer_at_full_size(oracle, cfg):
     torch.cuda.synchronize()
     assert np.array_equal(_rows(fidx), idx), "fused scan + top-k: index sets differ"
     assert np.array_equal(fcount.cpu().numpy().reshape(-1), count)
+    cand = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    resc = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    B.hca_score_topk_report(st.shape, st.n, st.ws, cand, resc)
+    torch.cuda.synchronize()
+    assert int(resc.max()) == 0, "a row needed the second scan: the timed path is not the fast one"
+    assert w.k <= int(cand.min()) and int(cand.max()) <= 16384, "candidate lists outside the LDS stage"
     pos = np.tile(np.arange(cap, dtype=np.int32), (R, 1))
     acc = np.zeros((R, cap), np.float32)
     V = v_host.numpy().reshape(R, n, 128)

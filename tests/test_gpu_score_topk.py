@@ -44,7 +44,11 @@ def _run(H, oracle, w, keys, q, lens, k):
         assert gc[r] == c == rcount[r], f"row {r}: count {gc[r]} / {rcount[r]} / {c}"
         assert np.array_equal(gi[r, :c], ridx[r, :c]), f"row {r}: index sets differ"
         assert np.all(gi[r, c:] == -9)
-    return st
+    cand = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    resc = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    B.hca_score_topk_report(st.shape, st.n, st.ws, cand, resc)
+    torch.cuda.synchronize()
+    return cand.cpu().numpy(), resc.cpu().numpy()
 
 
 @pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
@@ -55,7 +59,14 @@ def _run(H, oracle, w, keys, q, lens, k):
 def test_score_topk_matches_the_oracle(H, oracle, bits, gs, n, k, lens):
     w = S.Workload("st", 90 + bits, 2, 8, 2, n, bits, gs, k)
     d = S.make_layer(w, want_values=False)
-    _run(H, oracle, w, d["keys"], d["q"], lens, k)
+    cand, resc = _run(H, oracle, w, d["keys"], d["q"], lens, k)
+    for r in range(w.batch * w.n_kv_heads):
+        nr_ = lens[r // w.n_kv_heads]
+        if nr_ > 0:
+            assert min(k, nr_) <= cand[r] <= nr_
+            assert resc[r] == 0, "seeded random keys: the sampled threshold must hold"
+    if n >= 70001:      # long rows: the threshold discards almost everything
+        assert cand[0] < n // 8
 
 
 def test_ties_and_a_list_too_long_for_lds(H, oracle):
@@ -64,7 +75,8 @@ def test_ties_and_a_list_too_long_for_lds(H, oracle):
     w = S.Workload("tie", 95, 1, 4, 1, 50000, 4, 32, 777)
     d = S.make_layer(w, want_values=False)
     keys = d["keys"][:, :, :1].expand(-1, -1, w.n, -1).contiguous()
-    _run(H, oracle, w, keys, d["q"], [w.n], w.k)
+    cand, resc = _run(H, oracle, w, keys, d["q"], [w.n], w.k)
+    assert cand[0] == w.n and resc[0] == 0        # one key value: every slot passes the threshold
 
 
 @pytest.mark.parametrize("bits,gs,tpb", [(4, 32, 16), (2, 64, 32)])
@@ -85,4 +97,5 @@ def test_a_sample_that_misleads_still_gives_the_exact_set(H, oracle, bits, gs, t
     sampled[(torch.arange(Sn, dtype=torch.int64) * nblocks) // Sn] = True
     sign = torch.where(sampled.repeat_interleave(tpb)[:n], 1.0, -1.0)[:, None]
     keys = (sign * q[0, 0].float()[None, :] * (0.5 + torch.rand(n, 1, generator=g)) + noise).to(torch.float16)
-    _run(H, oracle, w, keys[None, None], q, [n], k)
+    cand, resc = _run(H, oracle, w, keys[None, None], q, [n], k)
+    assert resc[0] == 1 and cand[0] == n          # the row went through the second scan
