@@ -69,6 +69,14 @@ def test_score_topk_matches_the_oracle(H, oracle, bits, gs, n, k, lens):
         assert cand[0] < n // 8
 
 
+@pytest.mark.parametrize("hq,hkv", [(4, 2), (2, 2), (6, 3)])
+def test_fewer_query_heads_per_kv_head(H, oracle, hq, hkv):
+    """Groups of two query heads and of one: the selection score is the maximum over the heads that exist."""
+    w = S.Workload("gqa", 97 + hq, 2, hq, hkv, 40000, 4, 32, 512)
+    d = S.make_layer(w, want_values=False)
+    _run(H, oracle, w, d["keys"], d["q"], [40000, 12345], 512)
+
+
 def test_ties_and_a_list_too_long_for_lds(H, oracle):
     """Every key the same: every slot passes any threshold (50 000 pairs, more than are staged in LDS) and the
     k lowest slots win."""
