@@ -1077,6 +1077,10 @@ def main():
         gaps = (flat_s[1:] - flat_e[:-1]) / khz * 1e3
         log("key scan launches: mean %.1f us; idle between consecutive ones: mean %.1f us, median %.1f us" % (
             scan_ms * 1e3, float(gaps.mean()), float(gaps.median())))
+        if os.environ.get("HCA_BENCH_GAPS"):
+            top = torch.topk(gaps, 24)
+            log("largest gaps (us @ step.layer): " + " ".join(
+                "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(top.values, top.indices)))
     else:
         events = [e for step_events in events for e in step_events]
         scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)

@@ -108,17 +108,32 @@ int32_t launch_select_sample_scores(const Layout& L, const void* kcache, const v
                                     const SelectOut& so, hipStream_t st);
 int32_t launch_select_rank_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before, float* acc,
                                   int32_t* pos, const NRes& vrow0, int32_t k, const SelectOut& so, hipStream_t st);
-int32_t launch_select_scan_and_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                                      const SelectOut& so, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples, int next_m);
+// what a step's selecting scan of layer l carries for the layers behind it (null kcache: nothing)
+struct SelectStepNext {
+  void* a_kcache = nullptr;          // layer l + 1: threshold from its samples + append of its key
+  const void* a_k_new = nullptr;
+  float* a_acc = nullptr;
+  int32_t* a_pos = nullptr;
+  int64_t a_vrow0 = 0;
+  int32_t k = 0;
+  SelectOut a_so{};
+  NRes a_nr{};                       // lengths before the layer's append
+  const void* b_kcache = nullptr;    // layer l + 2: sampling
+  const void* b_q = nullptr;
+  SelectOut b_so{};
+  NRes b_nr{};
+};
+int32_t launch_select_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                           const SelectOut& so, hipStream_t st, uint64_t* stamps, const SelectStepNext& nx);
+// the SelectOut view of a selection workspace for rows of at most nmax_before slots (before the step's append)
+SelectOut select_view(const Layout& L, void* ws, int64_t nmax_before, int32_t k);
+int32_t launch_select_scan_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const SelectStepNext& nx);
 int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                               int32_t k, void* ws, hipStream_t st);
 int32_t launch_select_threshold_append(const Layout& L, void* kcache, const void* k_new, const NRes& nr_before,
                                        int64_t nmax_before, float* acc, int32_t* pos, const NRes& vrow0, int32_t k,
                                        void* ws, hipStream_t st);
-int32_t launch_select_scan_next(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                                int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                const void* next_q, const NRes& next_nr, int64_t next_nmax, void* next_ws);
 int32_t launch_select_threshold(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                                 int32_t k, void* ws, hipStream_t st);
 int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,

@@ -135,24 +135,37 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     return HCA_OK;
   };
   const bool fused = p->d.fused_select != 0;
-  // Fused selection: the scan stream carries two launches per layer, as without it: (threshold from the
-  // layer's samples + append of its key), then (selecting scan + sampling of the next layer's cache).  The
-  // first layer's samples come from a launch of their own.
+  // Fused selection: the scan stream carries one launch per layer.  The launch of layer l is its selecting scan
+  // plus a few workgroups for the layers behind it: the threshold of layer l + 1 (from samples the previous launch
+  // took) with the append of its key, and the sampling of layer l + 2.  The first two layers' samples and the first
+  // layer's threshold + append come from launches of their own at the start of the step.
   auto lengths = [&](int l2, NRes* out, int64_t* nmax2) -> int32_t {
     const hca_layer& y2 = layers[l2];
     if (y2.kcache == nullptr || y2.acc == nullptr || y2.pos == nullptr || y2.k_new == nullptr || y2.q == nullptr)
       return HCA_ERR_BAD_ARG;
-    return load_nres(L, n_resident + (int64_t)l2 * L.batch, out, nmax2);
+    const int32_t rc = load_nres(L, n_resident + (int64_t)l2 * L.batch, out, nmax2);
+    if (rc != HCA_OK) return rc;
+    for (int b = 0; b < L.batch; ++b)
+      if (out->n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;
+    return HCA_OK;
+  };
+  // before anything of this step touches layer l2's cache or its selection workspace
+  auto wait_layer = [&](int l2) -> int32_t {
+    if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[l2 % p->n_sel], 0));
+    HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l2], 0));
+    return HCA_OK;
   };
   if (fused) {
-    NRes n0;
-    int64_t m0;
-    int32_t rc = lengths(0, &n0, &m0);
-    if (rc != HCA_OK) return rc;
-    if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[0], 0));
-    HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[0], 0));
-    rc = launch_select_samples(L, layers[0].kcache, layers[0].q, n0, m0, k, p->d.ws_select[0], sa);
-    if (rc != HCA_OK) return rc;
+    for (int l2 = 0; l2 < 2 && l2 < p->n_layers; ++l2) {
+      NRes n2;
+      int64_t m2;
+      int32_t rc = lengths(l2, &n2, &m2);
+      if (rc != HCA_OK) return rc;
+      rc = wait_layer(l2);
+      if (rc != HCA_OK) return rc;
+      rc = launch_select_samples(L, layers[l2].kcache, layers[l2].q, n2, m2, k, p->d.ws_select[l2 % p->n_sel], sa);
+      if (rc != HCA_OK) return rc;
+    }
   }
   for (int l = 0; l < p->n_layers; ++l) {
     hca_layer& ly = layers[l];
@@ -166,16 +179,19 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     int32_t rc = load_nres(L, nl, &nr, &nmax);
     if (rc != HCA_OK) return rc;
     for (int b = 0; b < L.batch; ++b)
-      if (nr.n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;
+      if (!fused && nr.n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;   // fused: checked when the append was enqueued
     const int s3 = l % p->n_sel, s4 = l % 4;
     const bool timed = timing_slot >= 0 && l % p->timing_stride == 0;
     // stage 1: append + key scan
     // top-k of the previous user of this score buffer (with a buffer per layer that is this layer's own
     // previous step, which layer_done covers)
     if (fused) {
-      // (the waits for this layer's buffers went out before its sampling, one layer earlier)
-      rc = launch_select_threshold_append(L, ly.kcache, ly.k_new, nr, nmax, ly.acc, ly.pos, vrow0, k, p->d.ws_select[s3], sa);
-      if (rc != HCA_OK) return rc;
+      // (the waits for this layer's buffers went out before its sampling; its threshold and append rode on the
+      // previous layer's launch, except for the step's first layer)
+      if (l == 0) {
+        rc = launch_select_threshold_append(L, ly.kcache, ly.k_new, nr, nmax, ly.acc, ly.pos, vrow0, k, p->d.ws_select[s3], sa);
+        if (rc != HCA_OK) return rc;
+      }
       for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
       nmax += 1;
     } else {
@@ -194,16 +210,31 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       stamps = (uint64_t*)p->d.scan_stamps + ((int64_t)timing_slot * p->n_layers + l) * p->d.scan_stamp_pairs * 2;
     }
     auto fused_scan = [&]() -> int32_t {
-      if (l + 1 == p->n_layers) return launch_select_begin(L, ly.kcache, ly.q, nr, nmax, k, p->d.ws_select[s3], sa, stamps);
-      NRes n2;
-      int64_t m2;
-      const int32_t r2 = lengths(l + 1, &n2, &m2);
-      if (r2 != HCA_OK) return r2;
-      const int t3 = (l + 1) % p->n_sel;
-      if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[t3], 0));
-      HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l + 1], 0));
-      return launch_select_scan_next(L, ly.kcache, ly.q, nr, nmax, k, p->d.ws_select[s3], sa, stamps, layers[l + 1].kcache,
-                                     layers[l + 1].q, n2, m2, p->d.ws_select[t3]);
+      SelectStepNext nx;
+      nx.k = k;
+      if (l + 1 < p->n_layers) {
+        hca_layer& ya = layers[l + 1];
+        int64_t ma;
+        const int32_t ra = lengths(l + 1, &nx.a_nr, &ma);
+        if (ra != HCA_OK) return ra;
+        nx.a_kcache = ya.kcache;
+        nx.a_k_new = ya.k_new;
+        nx.a_acc = ya.acc;
+        nx.a_pos = ya.pos;
+        nx.a_vrow0 = value_row0;
+        nx.a_so = select_view(L, p->d.ws_select[(l + 1) % p->n_sel], ma, k);
+      }
+      if (l + 2 < p->n_layers) {
+        int64_t mb;
+        int32_t rb = lengths(l + 2, &nx.b_nr, &mb);
+        if (rb != HCA_OK) return rb;
+        rb = wait_layer(l + 2);
+        if (rb != HCA_OK) return rb;
+        nx.b_kcache = layers[l + 2].kcache;
+        nx.b_q = layers[l + 2].q;
+        nx.b_so = select_view(L, p->d.ws_select[(l + 2) % p->n_sel], mb, k);
+      }
+      return launch_select_scan_step(L, ly.kcache, ly.q, nr, nmax, k, p->d.ws_select[s3], sa, stamps, nx);
     };
     rc = vq ? launch_vq_score(L, vg, vc, ly.vq_centroids, (const uint8_t*)ly.kcache, ly.q, nr, nmax, ly.vq_lut,
                               p->d.sel[s3], nullptr, sa)

@@ -489,27 +489,46 @@ __global__ __launch_bounds__(256) void select_rank_append(Layout L, NRes nr_befo
   else quantize_body<BITS>(L, kcache, k_new, 1, nr_before.n[seq], acc, pos, vrow0.n[seq], 0, (int)blockIdx.y);
 }
 
-// The selecting scan of one layer with, as its first m / 512 workgroups per row, the sampling for another
-// cache (the next layer of the step): the sampling then costs no launch of its own.
-struct SampleJob {
-  const uint8_t* kcache;
-  const uint16_t* q;
-  uint32_t* samples;
-  int m;                      // slots to sample per row; the launch has m / kSamplePerWg more workgroups per row
-  NRes nr;
+// One launch per layer for a decode step: the selecting scan of layer l with, as extra workgroups in front of its
+// own, the sampling of layer l + 2 (m / 512 workgroups per row), the threshold of layer l + 1 from the samples that
+// the previous launch took (one workgroup per row) and the append of layer l + 1's key (one workgroup per row).
+// The roles touch different layers and do not depend on each other; what one launch writes the next one reads.
+struct StepJob {
+  // layer l + 1: threshold + append (a_on = 0: none)
+  uint8_t* a_kcache;
+  const uint16_t* a_k_new;
+  float* a_acc;
+  int32_t* a_pos;
+  const uint32_t* a_samples;
+  uint32_t* a_spec;
+  int64_t a_vrow0;
+  int32_t a_k, a_m, a_on;
+  // layer l + 2: sampling (b_m = 0: none)
+  const uint8_t* b_kcache;
+  const uint16_t* b_q;
+  uint32_t* b_samples;
+  int32_t b_m;
+  NRes a_nr, b_nr;            // lengths before the layers' own appends
 };
 template <int BITS, int U>
-__global__ __launch_bounds__(256) void score_select_sample_kernel(Layout L, const uint8_t* __restrict__ kcache,
-                                                                  const uint16_t* __restrict__ q, NRes nr, int bpw,
-                                                                  uint64_t* __restrict__ stamps, SelectOut so,
-                                                                  SampleJob sj) {
-  const int extra = sj.m / kSamplePerWg;
-  if ((int)blockIdx.x < extra) {
-    sample_score_body<BITS>(L, sj.kcache, sj.q, sj.nr, sj.samples, sj.m, (int)blockIdx.x, (int)blockIdx.y);
+__global__ __launch_bounds__(256) void score_select_step_kernel(Layout L, const uint8_t* __restrict__ kcache,
+                                                                const uint16_t* __restrict__ q, NRes nr, int bpw,
+                                                                uint64_t* __restrict__ stamps, SelectOut so, StepJob j) {
+  const int nsb = j.b_m / kSamplePerWg;
+  const int extra = nsb + (j.a_on ? 2 : 0);
+  const int bx = blockIdx.x, row = blockIdx.y;
+  if (bx < nsb) {
+    sample_score_body<BITS>(L, j.b_kcache, j.b_q, j.b_nr, j.b_samples, j.b_m, bx, row);
     return;
   }
-  score_body<BITS, false, U, false, true>(L, kcache, q, nr, bpw, nullptr, nullptr, stamps, 0.f, nullptr, so,
-                                          (int)blockIdx.x - extra, (int)gridDim.x - extra);
+  if (bx < extra) {
+    const int64_t n_before = j.a_nr.n[row / L.n_kv_heads];
+    if (bx == nsb) sample_rank_body(n_before + 1, j.a_k, j.a_samples, j.a_m, j.a_spec, row);
+    else quantize_body<BITS>(L, j.a_kcache, j.a_k_new, 1, n_before, j.a_acc, j.a_pos, j.a_vrow0, 0, row);
+    return;
+  }
+  score_body<BITS, false, U, false, true>(L, kcache, q, nr, bpw, nullptr, nullptr, stamps, 0.f, nullptr, so, bx - extra,
+                                          (int)gridDim.x - extra);
 }
 
 // Slots to sample per row.  More samples give a tighter threshold: with m samples the scan lets through about
@@ -575,23 +594,38 @@ int32_t launch_select_rank_append(const Layout& L, void* kcache, const void* k_n
   return HCA_OK;
 }
 
-// The selecting scan plus the sampling of another cache (next_* as in launch_select_sample's arguments).
-int32_t launch_select_scan_and_sample(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                                      const SelectOut& so, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                      const void* next_q, const NRes& next_nr, uint32_t* next_samples, int next_m) {
+int32_t launch_select_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                           const SelectOut& so, hipStream_t st, uint64_t* stamps, const SelectStepNext& nx) {
   if (nmax == 0) return HCA_ERR_BAD_ARG;
   const int bpw = select_scan_bpw(L, nmax);
   if (bpw == 0) return HCA_ERR_CAPACITY;
   const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
-  dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)) + (unsigned)(next_m / kSamplePerWg), (unsigned)L.rows);
+  StepJob j;
+  j.a_kcache = (uint8_t*)nx.a_kcache;
+  j.a_k_new = (const uint16_t*)nx.a_k_new;
+  j.a_acc = nx.a_acc;
+  j.a_pos = nx.a_pos;
+  j.a_samples = nx.a_so.samples;
+  j.a_spec = nx.a_so.spec;
+  j.a_vrow0 = nx.a_vrow0;
+  j.a_k = nx.k;
+  j.a_m = nx.a_so.m_samples;
+  j.a_on = nx.a_kcache != nullptr;
+  j.b_kcache = (const uint8_t*)nx.b_kcache;
+  j.b_q = (const uint16_t*)nx.b_q;
+  j.b_samples = nx.b_so.samples;
+  j.b_m = nx.b_kcache != nullptr ? nx.b_so.m_samples : 0;
+  j.a_nr = nx.a_nr;
+  j.b_nr = nx.b_nr;
+  const unsigned extra = (unsigned)(j.b_m / kSamplePerWg) + (j.a_on ? 2u : 0u);
+  dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)) + extra, (unsigned)L.rows);
   const size_t lds = (size_t)4 * bpw * L.tpb * sizeof(uint2);
-  SampleJob sj{(const uint8_t*)next_kcache, (const uint16_t*)next_q, next_samples, next_m, next_nr};
   if (L.bits == 4)
-    score_select_sample_kernel<4, 8><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
-                                                             so, sj);
+    score_select_step_kernel<4, 8><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
+                                                           so, j);
   else
-    score_select_sample_kernel<2, 4><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
-                                                             so, sj);
+    score_select_step_kernel<2, 4><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
+                                                           so, j);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

@@ -1013,10 +1013,10 @@ int32_t launch_select_threshold(const Layout& L, const void* kcache, const void*
   return launch_select_sample(L, kcache, q, nr, k, f.so, st);
 }
 
-// The parts of the fused selection as a decode step strings them together on one stream, two launches per
-// layer: (a) the sampling alone, for the step's first layer; (b) threshold from the samples + append of the
-// step's key; (c) the selecting scan together with the sampling of the next layer's cache (lengths before that
-// layer's own append: the one more slot does not matter to the estimate and is not read).
+// The parts of the fused selection as a decode step strings them together on one stream: (a) the sampling alone
+// and (b) threshold from the samples + append of the step's key, as launches of their own for the step's first
+// layers; (c) the selecting scan of a layer carrying (b) for the next layer and (a) for the one after it (lengths
+// before those layers' own appends: the one more slot does not matter to the estimate and is not read).
 // (nmax, nmax_before, next_nmax: the longest row at the lengths before the step's append - the sampling of a layer
 // and its threshold must agree on the sample count, which depends on it.)
 int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
@@ -1036,16 +1036,18 @@ int32_t launch_select_threshold_append(const Layout& L, void* kcache, const void
   return launch_select_rank_append(L, kcache, k_new, nr_before, acc, pos, vrow0, k, so, st);
 }
 
-int32_t launch_select_scan_next(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                                int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const void* next_kcache,
-                                const void* next_q, const NRes& next_nr, int64_t next_nmax, void* next_ws) {
+SelectOut select_view(const Layout& L, void* ws, int64_t nmax_before, int32_t k) {
+  TopkWs t;
+  topk_carve(&t, ws, L.rows, L.cap);
+  return SelectOut{t.spec, t.ncand, t.cand, t.samples, t.row_entries, select_sample_count(nmax_before, k)};
+}
+
+int32_t launch_select_scan_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                                int32_t k, void* ws, hipStream_t st, uint64_t* stamps, const SelectStepNext& nx) {
   FusedPlan f;
-  int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
+  const int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
   if (rc != HCA_OK) return rc;
-  TopkWs t2;
-  topk_carve(&t2, next_ws, L.rows, L.cap);
-  return launch_select_scan_and_sample(L, kcache, q, nr, nmax, f.so, st, stamps, next_kcache, next_q, next_nr,
-                                       t2.samples, select_sample_count(next_nmax, k));
+  return launch_select_step(L, kcache, q, nr, nmax, f.so, st, stamps, nx);
 }
 
 // 2. the selecting scan
