@@ -906,6 +906,8 @@ def main():
                     help="native pipeline: evict out of place into a spare buffer set, in slices behind the attends "
                          "(default: in place, which moves only the slots from the first dropped one on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gap-report", action="store_true",
+                    help="log the largest idle times between consecutive scan launches with their step.layer")
     ap.add_argument("--no-fused-select", action="store_true",
                     help="scan and top-k as two calls with a score buffer between them (hca_score_qkeys, hca_topk) "
                          "instead of hca_score_topk; always so with --pipeline staged / gather / none")
@@ -1077,7 +1079,7 @@ def main():
         gaps = (flat_s[1:] - flat_e[:-1]) / khz * 1e3
         log("key scan launches: mean %.1f us; idle between consecutive ones: mean %.1f us, median %.1f us" % (
             scan_ms * 1e3, float(gaps.mean()), float(gaps.median())))
-        if os.environ.get("HCA_BENCH_GAPS"):
+        if args.gap_report:
             top = torch.topk(gaps, 24)
             log("largest gaps (us @ step.layer): " + " ".join(
                 "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(top.values, top.indices)))
