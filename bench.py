@@ -359,7 +359,7 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8, fused=False, streams=
     return out
 
 
-def per_layer_latency_grouped(cfg, groups, streams, iters=8):
+def per_layer_latency_grouped(cfg, groups, streams, iters=8, fused=True):
     """One layer of workload `cfg` (synth_inputs.CONFIGS) with its rows (sequences x KV heads) cut into `groups` parts that
     go through the four stages as a pipeline: the gather of one part overlaps the scan of the next.  Unlike
     the overlap across layers this is legal in a real model, where the next layer's query does not exist yet:
@@ -378,7 +378,7 @@ def per_layer_latency_grouped(cfg, groups, streams, iters=8):
     wg = dataclasses.replace(w, name=f"{w.name}/{groups}parts", batch=w.batch // gb,
                              n_q_heads=w.n_q_heads // gh, n_kv_heads=w.n_kv_heads // gh)
     warm = 3
-    m = Model(wg, groups, 0, iters + warm, n_sel=groups)
+    m = Model(wg, groups, 0, iters + warm, n_sel=groups, fused=fused)
     m.build(groups)
     m.make_steps(iters + warm)
     sa, sb, sg, sc = streams
