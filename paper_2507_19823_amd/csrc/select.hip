@@ -764,6 +764,7 @@ __global__ __launch_bounds__(256) void tk_emit_lists(int64_t chunk, int nchunks,
 // A row with fewer pairs than it has to select is marked for a second scan without threshold; `only_failed`
 // launches handle exactly those rows.
 constexpr int kFullLds = 16384;     // pairs held in LDS (128 KiB, dynamic)
+constexpr int kSearchMax = 65536;   // pairs still addressed by position when they do not fit LDS
 
 // counter updates when the lanes of a wave share a handful of bins (the leading bits of keys that all lie
 // just above one threshold): one atomic per distinct bin for the first few, single updates for the rest
@@ -808,6 +809,10 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
     return;
   }
   const uint2* gl = so.lists + (int64_t)row * so.row_entries;
+  const bool staged = total <= (uint32_t)kFullLds;
+  // beyond the LDS stage: up to kSearchMax pairs are still addressed by their position in slot order (short lists:
+  // walking them chunk by chunk would cost a memory round trip per chunk), more than that are walked chunk by chunk
+  const bool by_position = total <= (uint32_t)kSearchMax;
   // pair p of the row in slot order: the chunk c with off[c] <= p < off[c + 1], entry p - off[c] of its list
   auto fetch = [&](uint32_t p) {
     uint32_t c = 0;
@@ -816,7 +821,7 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
       if (off[c + s] <= p) c += s;
     return gl[(int64_t)c * chunk + (p - off[c])];
   };
-  const bool staged = total <= (uint32_t)kFullLds;
+  auto at = [&](uint32_t p) { return staged ? lc[p] : fetch(p); };
   const int lane = tid & 63, wv = tid >> 6;
   uint32_t kmax = 0;                                        // largest key this thread has seen
   if (staged) {
@@ -850,13 +855,29 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
     }
   }
   __syncthreads();
-  auto at = [&](uint32_t p) { return staged ? lc[p] : fetch(p); };
-  // strided visit (any order will do for the histograms)
+  // visit(f): f(key, slot, exists) over every pair of the row, in any order, called by all lanes of a wave
+  // together.  By position: strided over the LDS copy (or, unstaged, through fetch).  Otherwise the lists where
+  // they are: wave w takes chunks w, w + 16, ... and reads each list 1024 pairs at a time (sixteen loads in flight
+  // per lane).
   auto visit = [&](auto&& f) {
-    for (uint32_t i0 = 0; i0 < total; i0 += 1024) {
-      const bool hit = i0 + tid < total;
-      const uint2 x = at(hit ? i0 + tid : 0);
-      f(x.x, x.y, hit);
+    if (by_position) {
+      for (uint32_t i0 = 0; i0 < total; i0 += 1024) {
+        const bool hit = i0 + tid < total;
+        const uint2 x = at(hit ? i0 + tid : 0);
+        f(x.x, x.y, hit);
+      }
+    } else {
+      for (int c = wv; c < nchunks; c += 16) {
+        const uint32_t m = off[c + 1] - off[c];
+        const uint2* src = gl + (int64_t)c * chunk;
+        for (uint32_t i0 = 0; i0 < m; i0 += 1024) {
+          uint2 x[16];
+#pragma unroll
+          for (int v = 0; v < 16; ++v) x[v] = i0 + v * 64 + lane < m ? src[i0 + v * 64 + lane] : uint2{0, 0};
+#pragma unroll
+          for (int v = 0; v < 16; ++v) f(x[v].x, x[v].y, i0 + v * 64 + lane < m);
+        }
+      }
     }
   };
   if (!staged) visit([&](uint32_t key, uint32_t, bool hit) { if (hit && key > kmax) kmax = key; });
@@ -953,25 +974,84 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
     sbits = ns;
     __syncthreads();
   }
-  // ordered part: thread tid owns the run [tid * E, tid * E + E) of the list
-  const uint32_t E = (total + 1023) / 1024;
-  const uint32_t p0 = (uint32_t)tid * E;
-  const uint32_t p1 = p0 + E < total ? p0 + E : total;
-  uint32_t ng = 0, ne = 0;
-  for (uint32_t p = p0; p < p1; ++p) {
-    const uint32_t key = at(p).x;
-    ng += key > T;
-    ne += key == T;
-  }
-  uint32_t rg = block_scan_excl_1024(ng, wsum);             // pairs above T on lower slots
-  uint32_t re = block_scan_excl_1024(ne, wsum);             // pairs equal to T on lower slots
   int32_t* out = idx + (int64_t)row * k;
-  for (uint32_t p = p0; p < p1; ++p) {
-    const uint2 x = at(p);
-    if (x.x > T) { out[rg + (re < req ? re : req)] = (int32_t)x.y; ++rg; }
-    else if (x.x == T) { if (re < req) out[rg + re] = (int32_t)x.y; ++re; }
-  }
   if (tid == 0) count[row] = (int32_t)want;
+  if (by_position) {
+    // ordered part by position (slot order): thread tid owns the run [tid * E, tid * E + E)
+    const uint32_t E = (total + 1023) / 1024;
+    const uint32_t p0 = (uint32_t)tid * E;
+    const uint32_t p1 = p0 + E < total ? p0 + E : total;
+    uint32_t ng = 0, ne = 0;
+    for (uint32_t p = p0; p < p1; ++p) {
+      const uint32_t key = at(p).x;
+      ng += key > T;
+      ne += key == T;
+    }
+    uint32_t rg = block_scan_excl_1024(ng, wsum);           // pairs above T on lower slots
+    uint32_t re = block_scan_excl_1024(ne, wsum);           // pairs equal to T on lower slots
+    for (uint32_t p = p0; p < p1; ++p) {
+      const uint2 x = at(p);
+      if (x.x > T) { out[rg + (re < req ? re : req)] = (int32_t)x.y; ++rg; }
+      else if (x.x == T) { if (re < req) out[rg + re] = (int32_t)x.y; ++re; }
+    }
+    return;
+  }
+  // ordered part on the lists where they are: per chunk the pairs above / equal to T, a prefix over the chunks,
+  // then every wave walks its chunks again, 64 pairs at a time, positions by ballot
+  uint32_t* cg = h;            // [1024] pairs above T per chunk -> pairs above T in the chunks before
+  uint32_t* ce = h + 1024;     // the same for pairs equal to T
+  __syncthreads();
+  for (int c = wv; c < 1024; c += 16) {
+    uint32_t g = 0, e = 0;
+    if (c < nchunks) {
+      const uint32_t m = off[c + 1] - off[c];
+      const uint2* src = gl + (int64_t)c * chunk;
+      for (uint32_t i0 = 0; i0 < m; i0 += 1024) {
+        uint32_t key[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) key[v] = i0 + v * 64 + lane < m ? src[i0 + v * 64 + lane].x : 0u;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const bool live = i0 + v * 64 + lane < m;
+          g += (uint32_t)__popcll(__ballot(live && key[v] > T));
+          e += (uint32_t)__popcll(__ballot(live && key[v] == T));
+        }
+      }
+    }
+    if (lane == 0) { cg[c] = g; ce[c] = e; }
+  }
+  __syncthreads();
+  {
+    const uint32_t g = cg[tid], e = ce[tid];
+    const uint32_t og = block_scan_excl_1024(g, wsum);
+    const uint32_t oe = block_scan_excl_1024(e, wsum);
+    cg[tid] = og;
+    ce[tid] = oe;
+  }
+  __syncthreads();
+  const uint64_t lt = (1ull << lane) - 1;
+  for (int c = wv; c < nchunks; c += 16) {
+    const uint32_t m = off[c + 1] - off[c];
+    const uint2* src = gl + (int64_t)c * chunk;
+    uint32_t pg = cg[c], pe = ce[c];
+    for (uint32_t i0 = 0; i0 < m; i0 += 512) {
+      uint2 xs[8];
+#pragma unroll
+      for (int v = 0; v < 8; ++v) xs[v] = i0 + v * 64 + lane < m ? src[i0 + v * 64 + lane] : uint2{0, 0};
+#pragma unroll
+      for (int v = 0; v < 8; ++v) {
+        const bool live = i0 + v * 64 + lane < m;
+        const uint2 x = xs[v];
+        const bool fg = live && x.x > T, fe = live && x.x == T;
+        const uint64_t mg = __ballot(fg), me = __ballot(fe);
+        const uint32_t gb = pg + (uint32_t)__popcll(mg & lt), eb = pe + (uint32_t)__popcll(me & lt);
+        if (fg) out[gb + (eb < req ? eb : req)] = (int32_t)x.y;
+        else if (fe && eb < req) out[gb + eb] = (int32_t)x.y;
+        pg += (uint32_t)__popcll(mg);
+        pe += (uint32_t)__popcll(me);
+      }
+    }
+  }
 }
 
 namespace {
