@@ -125,8 +125,9 @@ int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resi
  * memory.  A strided sample of each row (8192 to 65536 slots) is scored first and gives a threshold that at least k
  * slots of the row pass with overwhelming probability; the scan then keeps only the (score, slot) pairs
  * at or above it, and the selection runs on those few thousand pairs.  A row whose sample misled (fewer
- * than k pairs) is scanned a second time with no threshold inside the same call, so the result never
- * depends on the sample; only the time does.
+ * than k pairs) is scanned a second time inside the same call - with a lower threshold that a count taken
+ * during the first scan proves sufficient, else with none -, so the result never depends on the sample;
+ * only the time does.
  *   workspace  device, hca_workspace_bytes(shape, k, 1) bytes
  * Errors: HCA_ERR_CAPACITY if k < 1, k > capacity, or a row holds more than 8 Mi resident slots. */
 int32_t hca_score_topk(const hca_shape* shape, const void* kcache, const void* q_f16, const int64_t* n_resident,

@@ -89,8 +89,10 @@ size_t topk_hist_bytes(int rows);
 // scan workgroup, at most kSelectMaxChunks of them per row).
 constexpr int kSelectMaxChunks = 1024;
 struct SelectOut {
-  uint32_t* spec;       // [rows][4]: threshold key t0, 1 = the row has to be scanned again with t0 = 0, -, -
+  uint32_t* spec;       // [rows][4]: threshold key t0, 1 = the row has to be scanned again (with the threshold then
+                        // in word 0), second threshold t1 <= t0 (only counted against), -
   uint32_t* ncand;      // [rows][kSelectMaxChunks] pairs in each chunk's list
+  uint32_t* n1;         // [rows][kSelectMaxChunks] slots of each chunk with key >= t1
   uint2* lists;         // [rows][row_entries]: chunk c owns entries [c * chunk, (c + 1) * chunk)
   uint32_t* samples;    // [rows][m_samples] keys of the sampled slots (0: no such slot)
   int64_t row_entries;

@@ -66,14 +66,17 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
   // SELECT: every wave collects its qualifying pairs in slot order in its quarter of the dynamic LDS (room for
   // all the wave's slots), then the workgroup strings the four lists together
   extern __shared__ uint2 wlist_all[];
-  __shared__ uint32_t wcount[4];
+  __shared__ uint32_t wcount[8];
   const int row = blockIdx.y;
   const int64_t n = nr.n[row / L.n_kv_heads];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nblocks = (int)((n + L.tpb - 1) / L.tpb);
   if ((int64_t)bx * 4 * bpw >= nblocks) {        // whole workgroup past the end
-    if (SELECT && threadIdx.x == 0) so.ncand[(int64_t)row * kSelectMaxChunks + bx] = 0;
+    if (SELECT && threadIdx.x == 0) {
+      so.ncand[(int64_t)row * kSelectMaxChunks + bx] = 0;
+      so.n1[(int64_t)row * kSelectMaxChunks + bx] = 0;
+    }
     return;
   }
   // optional profiling: every wave leaves its start and end time (constant-rate wall clock)
@@ -133,12 +136,15 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
   };
   // the lane in row hd stores tile hd of four consecutive tiles starting at token tok0
   const uint32_t t0key = SELECT ? so.spec[4 * row] : 0u;
+  const uint32_t t1key = SELECT ? so.spec[4 * row + 2] : 0u;   // the deeper threshold: only counted against
+  uint32_t n1 = 0;                                         // slots of this wave with key >= t1key (wave-uniform)
   uint2* wlist = SELECT ? wlist_all + (int64_t)w * bpw * L.tpb : nullptr;
   uint32_t nlist = 0;                                     // SELECT: pairs in this wave's list so far (wave-uniform)
   // SELECT: appends the lanes' pairs that qualify, in lane order (the caller's lanes are in slot order)
   auto emit_pairs = [&](float v, int tok, bool live) {
     const uint32_t key = order_key(v);
     const bool hit = live && key >= t0key;
+    n1 += (uint32_t)__popcll(__ballot(live && key >= t1key));
     const uint64_t m = __ballot(hit);
     if (m != 0) {
       if (hit) wlist[nlist + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = uint2{key, (uint32_t)tok};
@@ -216,7 +222,7 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
   }
   if constexpr (SELECT) {
     // the four waves' lists, in wave order (= slot order), become the chunk's list
-    if (lane == 0) wcount[w] = nlist;
+    if (lane == 0) { wcount[w] = nlist; wcount[4 + w] = n1; }
     __syncthreads();
     uint32_t base = 0, total = 0;
 #pragma unroll
@@ -224,7 +230,10 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
     const int64_t chunk_slots = (int64_t)4 * bpw * L.tpb;
     uint2* dst = so.lists + (int64_t)row * so.row_entries + (int64_t)bx * chunk_slots + base;
     for (uint32_t i = lane; i < nlist; i += 64) dst[i] = wlist[i];
-    if (threadIdx.x == 0) so.ncand[(int64_t)row * kSelectMaxChunks + bx] = total;
+    if (threadIdx.x == 0) {
+      so.ncand[(int64_t)row * kSelectMaxChunks + bx] = total;
+      so.n1[(int64_t)row * kSelectMaxChunks + bx] = wcount[4] + wcount[5] + wcount[6] + wcount[7];
+    }
   }
   if constexpr (LSE) {
     // merge over the 16 lanes of a head row, then one lane per head stores the wave's pair
@@ -388,12 +397,12 @@ __device__ __forceinline__ void sample_rank_body(const int64_t n, int32_t k, con
                                                  const int m_samples, uint32_t* __restrict__ spec, const int row) {
   __shared__ uint32_t hist[4096];
   __shared__ uint32_t wsum[4];
-  __shared__ uint32_t s_bin, s_rem;
+  __shared__ uint32_t s_bin, s_rem, s_bin1;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t want = n < k ? n : k;
   uint32_t* sp = spec + 4 * row;
   if (want <= 0) {
-    if (tid == 0) { sp[0] = 0xffffffffu; sp[1] = 0; }
+    if (tid == 0) { sp[0] = 0xffffffffu; sp[1] = 0; sp[2] = 0xffffffffu; }
     return;
   }
   const uint32_t* in = samples + (int64_t)row * m_samples;
@@ -434,15 +443,22 @@ __device__ __forceinline__ void sample_rank_body(const int64_t n, int32_t k, con
   const float root = 3.0f + sqrtf(9.0f + kappa);
   const uint32_t r = (uint32_t)ceilf(root * root);
   if (r >= m) {                                             // short rows: everything is a candidate
-    if (tid == 0) { sp[0] = 0; sp[1] = 0; }
+    if (tid == 0) { sp[0] = 0; sp[1] = 0; sp[2] = 0; }
     return;
   }
+  // a second, deeper threshold for the case that the first one turns out too high: the lower bound of the 12-bit
+  // bin that holds the 8r-th largest sample (0 if there is no such sample).  The scan counts the slots at or
+  // above it, so that the selection knows whether a second scan with it is enough.
+  const uint32_t r1 = 8 * r;
+  if (tid == 0) sp[2] = 0;
 #pragma unroll
   for (int i = 0; i < 16; ++i) {
     if (running < r && r <= running + h[i]) { s_bin = 4095 - (16 * tid + i); s_rem = r - running; }
+    if (running < r1 && r1 <= running + h[i]) s_bin1 = 4095 - (16 * tid + i);
     running += h[i];
   }
   __syncthreads();
+  if (tid == 0 && r1 < m) sp[2] = s_bin1 << 20;
   const uint32_t bin = s_bin, rem = s_rem;
   for (int i = tid; i < 1024; i += 256) hist[i] = 0;
   __syncthreads();

@@ -804,8 +804,16 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
   if (tid == 1023) off[1024] = before + mine_cnt;
   __syncthreads();
   const uint32_t total = off[1024];
-  if (total < (uint32_t)want) {            // the sampled threshold was too high: scan the row again without one
-    if (tid == 0) { spec[0] = 0; spec[1] = 1; }
+  if (total < (uint32_t)want) {
+    // the sampled threshold was too high: scan the row again, with the second threshold if the first scan counted
+    // enough slots at or above it, else without one
+    const uint32_t mine_n1 = tid < nchunks ? so.n1[(int64_t)row * kSelectMaxChunks + tid] : 0;
+    const uint32_t before1 = block_scan_excl_1024(mine_n1, wsum);
+    if (tid == 1023) {
+      const uint32_t enough = before1 + mine_n1 >= (uint32_t)want;
+      spec[0] = enough && spec[1] == 0 ? spec[2] : 0;       // (a second failure cannot happen: the count is exact)
+      spec[1] = 1;
+    }
     return;
   }
   const uint2* gl = so.lists + (int64_t)row * so.row_entries;
@@ -1077,7 +1085,7 @@ int32_t fused_plan(const Layout& L, const NRes& nr, int64_t nmax, int32_t k, voi
   f->nchunks = (int)((nblocks + 4 * bpw - 1) / (4 * bpw));
   if (f->nchunks < 1) f->nchunks = 1;
   if (f->nchunks > kSelectMaxChunks || (int64_t)f->nchunks * f->chunk > f->t.row_entries) return HCA_ERR_CAPACITY;
-  f->so = SelectOut{f->t.spec, f->t.ncand, f->t.cand, f->t.samples, f->t.row_entries, select_sample_count(nmax, k)};
+  f->so = SelectOut{f->t.spec, f->t.ncand, f->t.above, f->t.cand, f->t.samples, f->t.row_entries, select_sample_count(nmax, k)};
   return HCA_OK;
 }
 }  // namespace
@@ -1103,7 +1111,7 @@ int32_t launch_select_samples(const Layout& L, const void* kcache, const void* q
                               int32_t k, void* ws, hipStream_t st) {
   TopkWs t;
   topk_carve(&t, ws, L.rows, L.cap);
-  SelectOut so{t.spec, t.ncand, t.cand, t.samples, t.row_entries, select_sample_count(nmax, k)};
+  SelectOut so{t.spec, t.ncand, t.above, t.cand, t.samples, t.row_entries, select_sample_count(nmax, k)};
   return launch_select_sample_scores(L, kcache, q, nr, so, st);
 }
 
@@ -1112,14 +1120,14 @@ int32_t launch_select_threshold_append(const Layout& L, void* kcache, const void
                                        void* ws, hipStream_t st) {
   TopkWs t;
   topk_carve(&t, ws, L.rows, L.cap);
-  SelectOut so{t.spec, t.ncand, t.cand, t.samples, t.row_entries, select_sample_count(nmax_before, k)};
+  SelectOut so{t.spec, t.ncand, t.above, t.cand, t.samples, t.row_entries, select_sample_count(nmax_before, k)};
   return launch_select_rank_append(L, kcache, k_new, nr_before, acc, pos, vrow0, k, so, st);
 }
 
 SelectOut select_view(const Layout& L, void* ws, int64_t nmax_before, int32_t k) {
   TopkWs t;
   topk_carve(&t, ws, L.rows, L.cap);
-  return SelectOut{t.spec, t.ncand, t.cand, t.samples, t.row_entries, select_sample_count(nmax_before, k)};
+  return SelectOut{t.spec, t.ncand, t.above, t.cand, t.samples, t.row_entries, select_sample_count(nmax_before, k)};
 }
 
 int32_t launch_select_scan_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
