@@ -262,7 +262,7 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
 }
 
 // The selecting scan once more for the rows whose sampled threshold left too few pairs (spec[row][1] != 0, with
-// the threshold already reset to 0).  Almost always there is no such row, so the launch is kept small - up to 64
+// the threshold already reset to 0).  Almost always there is no such row, so the launch is kept small - up to 256
 // workgroups per row that walk over the row's chunks - and costs next to nothing when it has nothing to do.
 template <int BITS, int U>
 __global__ __launch_bounds__(256) void score_failed_rows_kernel(Layout L, const uint8_t* __restrict__ kcache,
@@ -657,7 +657,7 @@ int32_t launch_select_scan(const Layout& L, const void* kcache, const void* q, c
   const uint8_t* kc = (const uint8_t*)kcache;
   const uint16_t* qq = (const uint16_t*)q;
   if (only_failed) {
-    dim3 small(grid.x < 64 ? grid.x : 64, (unsigned)L.rows);
+    dim3 small(grid.x < 256 ? grid.x : 256, (unsigned)L.rows);
     if (L.bits == 4) score_failed_rows_kernel<4, 8><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
     else score_failed_rows_kernel<2, 4><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
   } else if (L.bits == 4) {
