@@ -89,10 +89,18 @@ int main() {
   HCA_OK_(hca_score_qkeys(&s, kc, dq, nres, sel, nullptr, nullptr, st));
   HCA_OK_(hca_topk(&s, sel, nres, k, idx, count, ws, st));
   HCA_OK_(hca_sparse_attend(&s, kc, dq, idx, count, k, pos, vh, n, n, nullptr, 0, sm, y, acc, ws, gst, st));
+  // the same selection as one call that writes no per-token scores
+  int32_t *fidx, *fcount;
+  HIP_OK(hipMalloc(&fidx, (size_t)R * k * 4));
+  HIP_OK(hipMalloc(&fcount, (size_t)R * 4));
+  HCA_OK_(hca_score_topk(&s, kc, dq, nres, k, fidx, fcount, ws, st));
   HIP_OK(hipStreamSynchronize(st));
 
   std::vector<int32_t> gidx((size_t)R * k), gcount(R);
   std::vector<float> gy((size_t)R * G * D), gacc((size_t)R * cap);
+  std::vector<int32_t> fgidx((size_t)R * k), fgcount(R);
+  HIP_OK(hipMemcpy(fgidx.data(), fidx, fgidx.size() * 4, hipMemcpyDeviceToHost));
+  HIP_OK(hipMemcpy(fgcount.data(), fcount, fgcount.size() * 4, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(gidx.data(), idx, gidx.size() * 4, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(gcount.data(), count, gcount.size() * 4, hipMemcpyDeviceToHost));
   HIP_OK(hipMemcpy(gy.data(), y, gy.size() * 4, hipMemcpyDeviceToHost));
@@ -116,6 +124,9 @@ int main() {
     if (gcount[r] != ocount[r] || gcount[r] != k) { printf("count differs in row %ld\n", (long)r); return 5; }
     for (int i = 0; i < k; ++i)
       if (gidx[(size_t)r * k + i] != oidx[(size_t)r * k + i]) { printf("top-k differs in row %ld\n", (long)r); return 5; }
+    if (fgcount[r] != ocount[r]) { printf("fused count differs in row %ld\n", (long)r); return 5; }
+    for (int i = 0; i < k; ++i)
+      if (fgidx[(size_t)r * k + i] != oidx[(size_t)r * k + i]) { printf("fused top-k differs in row %ld\n", (long)r); return 5; }
   }
   double worst = 0.0;
   for (int64_t hq = 0; hq < R * G; ++hq) {
