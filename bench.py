@@ -57,6 +57,7 @@ class Model:
                       for _ in range(layers)]
         # score buffers of the pipeline slots; with the fused scan + top-k a selection workspace per slot instead
         self.fused = fused
+        self.gap_report = False
         self.sels = [torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev)
                      for _ in range(1 if fused else max(3, n_sel))]
         self.ws_sel = [torch.empty(B.hca_workspace_bytes(self.shape, w.k, 1), dtype=torch.uint8, device=dev)
@@ -207,6 +208,9 @@ class Model:
             pairs = B.hca_scan_stamp_pairs(self.shape, self.cap)
             self.stamps = self.torch.zeros(timing_slots, self.L, pairs, 2, dtype=self.torch.int64, device="cuda")
             d.scan_stamps, d.scan_stamp_pairs = self.stamps.data_ptr(), pairs
+            if self.gap_report:
+                self.gstamps = self.torch.zeros(timing_slots, self.L, 1024, 2, dtype=self.torch.int64, device="cuda")
+                d.gather_stamps = self.gstamps.data_ptr()
         if self.evict_spare:
             d.spare_kcache, d.spare_acc, d.spare_pos = (x.data_ptr() for x in self.spare)
         self.pl = B.hca_pipeline_create(self.shape, self.L, d, timing_slots)
@@ -1032,6 +1036,7 @@ def main():
 
     main, side = main_s[0], gath_s[0]
 
+    model.gap_report = args.gap_report
     if args.pipeline == "native":
         model.native_pipeline(main, main if args.stages == 3 else extra[0], side, extra[1], args.steps,
                               args.bracket_stride)
@@ -1080,6 +1085,16 @@ def main():
         log("key scan launches: mean %.1f us; idle between consecutive ones: mean %.1f us, median %.1f us" % (
             scan_ms * 1e3, float(gaps.mean()), float(gaps.median())))
         if args.gap_report:
+            gs = model.gstamps
+            g_start = torch.where(gs[..., 0] > 0, gs[..., 0], torch.full_like(gs[..., 0], 1 << 62)).amin(-1).reshape(-1).double()
+            g_end = gs[..., 1].amax(-1).reshape(-1).double()
+            ggaps = (g_start[1:] - g_end[:-1]) / khz * 1e3
+            gdur = (g_end - g_start) / khz * 1e3
+            log("gathers: mean %.1f us; idle between consecutive ones: mean %.1f us, median %.1f us" % (
+                float(gdur.mean()), float(ggaps.mean()), float(ggaps.median())))
+            gtop = torch.topk(ggaps, 24)
+            log("largest gather gaps (us @ step.layer): " + " ".join(
+                "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(gtop.values, gtop.indices)))
             top = torch.topk(gaps, 24)
             log("largest gaps (us @ step.layer): " + " ".join(
                 "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(top.values, top.indices)))

@@ -257,6 +257,10 @@ typedef struct {
      workspaces instead (device, hca_workspace_bytes(shape, k, 1) each). */
   int32_t fused_select;
   void* ws_select[HCA_PIPELINE_MAX_SEL];
+  /* optional profiling of the value gather, like scan_stamps: device, uint64 [timing_slots][n_layers][1024][2],
+     zero-filled by the caller; every workgroup of a timed gather launch (at most 1024) stores its start and end
+     wall-clock tick.  NULL: off. */
+  void* gather_stamps;
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;

@@ -47,7 +47,7 @@ class hca_pipeline_desc(C.Structure):
                 ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64),
                 ("timing_layer_stride", C.c_int32), ("vq_groups", C.c_int32), ("vq_codewords", C.c_int32),
                 ("topp_tau", C.c_double), ("fused_select", C.c_int32),
-                ("ws_select", C.c_void_p * PIPELINE_MAX_SEL)]
+                ("ws_select", C.c_void_p * PIPELINE_MAX_SEL), ("gather_stamps", C.c_void_p)]
 
 
 class hca_vq_codebook(C.Structure):

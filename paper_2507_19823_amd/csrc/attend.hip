@@ -45,8 +45,11 @@ __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__
                                                      const uint4* __restrict__ v_host, int64_t host_stride,
                                                      int64_t n_host_rows, const uint4* __restrict__ v_hbm,
                                                      int64_t hbm_stride, uint4* __restrict__ vstage,
-                                                     int wgs) {
+                                                     int wgs, uint64_t* __restrict__ stamps) {
   const int row = blockIdx.y, wg = blockIdx.x;
+  // optional profiling: every workgroup leaves its start and end time (constant-rate wall clock)
+  uint64_t* stamp = stamps ? stamps + ((int64_t)row * wgs + wg) * 2 : nullptr;
+  if (stamp && threadIdx.x == 0) stamp[0] = wall_clock64();
   const int cnt = count[row];
   const int part = threadIdx.x & 15;
   const int64_t step = (int64_t)wgs * 16;                 // value rows per sweep of the row's workgroups
@@ -74,6 +77,10 @@ __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__
         __builtin_nontemporal_store(t4, reinterpret_cast<v4i*>(vstage + ((int64_t)row * k + i) * 16 + part));
       }
     }
+  }
+  if (stamp) {
+    __syncthreads();
+    if (threadIdx.x == 0) stamp[1] = wall_clock64();
   }
 }
 
@@ -410,7 +417,7 @@ static hipEvent_t next_event(hipError_t* err) {
 
 int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
                       const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
-                      int64_t hbm_stride, void* ws, hipStream_t st) {
+                      int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps) {
   AttendWs a;
   carve(&a, ws, L, k);
   const Tuning& tn = tuning();
@@ -419,11 +426,12 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
   // link; more only take queue entries in the memory system away from the HBM-bound kernels beside it.
   int64_t lim = tn.gather_wgs > 0 ? tn.gather_wgs : (L.rows >= 64 ? 1 : 64 / L.rows);
   if (wgs > lim) wgs = lim;
+  if (wgs * L.rows > kGatherStampPairs) stamps = nullptr;      // more workgroups than the stamp buffer holds
   dim3 g((unsigned)wgs, (unsigned)L.rows);
   const uint4 *vh = (const uint4*)v_host, *vd = (const uint4*)v_hbm;
 #define HCA_GATHER(U)                                                                                              \
   gather_values<U><<<g, 256, 0, st>>>(idx, count, k, pos, L.cap, vh, host_stride, n_host_rows, vd, hbm_stride, \
-                                      (uint4*)a.vstage, (int)wgs)
+                                      (uint4*)a.vstage, (int)wgs, stamps)
   if (tn.gather_unroll >= 4) HCA_GATHER(4);
   else if (tn.gather_unroll >= 2) HCA_GATHER(2);
   else HCA_GATHER(1);

@@ -155,7 +155,9 @@ int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const 
                       float sm_scale, float* y, float* acc_opt, void* ws, hipStream_t gst, hipStream_t st);
 int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
                       const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
-                      int64_t hbm_stride, void* ws, hipStream_t st);
+                      int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps = nullptr);
+// (start, end) pairs a gather launch writes into `stamps` at most
+constexpr int kGatherStampPairs = 1024;
 int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
                                void* ws, hipStream_t st, const float* lse = nullptr);

@@ -256,8 +256,11 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     HCA_HIP(hipEventRecord(p->topk_done[s4], sb));
     // stage 3: host-link gather
     HCA_HIP(hipStreamWaitEvent(sg, p->topk_done[s4], 0));
+    uint64_t* gstamps = nullptr;
+    if (timing_slot >= 0 && p->d.gather_stamps != nullptr)
+      gstamps = (uint64_t*)p->d.gather_stamps + ((int64_t)timing_slot * p->n_layers + l) * kGatherStampPairs * 2;
     rc = launch_gather(L, p->d.idx[s4], p->d.count[s4], k, ly.pos, ly.v_host, host_stride, n_host_rows, ly.v_hbm,
-                       hbm_stride, p->d.ws_attend[s4], sg);
+                       hbm_stride, p->d.ws_attend[s4], sg, gstamps);
     if (rc != HCA_OK) return rc;
     HCA_HIP(hipEventRecord(p->gather_done[s4], sg));
     // stage 4: attend (+ eviction into the spare buffers, which then swap with the layer's)
