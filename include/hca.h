@@ -64,7 +64,9 @@ typedef struct {
 const char* hca_version(void);
 
 /* Overrides a launch-shape knob (process-wide; for tuning and profiling, not needed for
- * correct results).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth".
+ * correct results).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth",
+ * "host_spin_us" (how long the worker threads of hca_host_weighted_sum poll for the next
+ * call before they sleep; default 100, 0 = sleep at once).
  * Returns HCA_ERR_BAD_ARG for an unknown name. */
 int32_t hca_tune(const char* name, int32_t value);
 
@@ -349,7 +351,10 @@ int32_t hca_attend_gathered_global(const hca_shape* shape, const void* kcache, c
  *   vrow, count, w_f16  host-readable copies of the outputs above (count: int32 [batch, n_kv_heads])
  *   v_host   host, fp16 [batch, n_kv_heads, host_stride, head_dim]
  *   y        host, fp32 [batch, n_q_heads, head_dim]
- *   n_threads  host threads to use (1 .. 64)
+ *   n_threads  host threads to use (1 .. 64), the calling thread among them.  The others are worker
+ *            threads the library starts on first use and keeps until the process ends (they sleep
+ *            between calls, after polling for "host_spin_us" microseconds, see hca_tune); calls from
+ *            several threads at once are served one after another.
  * Errors: HCA_ERR_CAPACITY if a value row lies outside host_stride. */
 int32_t hca_attend_weights(const hca_shape* shape, const void* kcache, const void* q_f16, const int32_t* idx,
                            const int32_t* count, int32_t k, const int32_t* pos, float sm_scale, const float* lse_opt,

@@ -70,6 +70,7 @@ int32_t hca_tune(const char* name, int32_t value) {
   else if (!strcmp(name, "gather_unroll")) t.gather_unroll = value;
   else if (!strcmp(name, "score_bpw")) t.score_bpw = value;
   else if (!strcmp(name, "score_depth")) t.score_depth = value;
+  else if (!strcmp(name, "host_spin_us")) t.host_spin_us = value < 0 ? 0 : value;
   else return HCA_ERR_BAD_ARG;
   return HCA_OK;
 }

@@ -30,6 +30,7 @@ struct Tuning {
   int gather_unroll = 4;   // rows in flight per thread
   int score_bpw = 0;       // 1 KiB code blocks per wave (0 = automatic)
   int score_depth = 0;     // blocks fetched ahead per wave (4 or 8; 0 = 8 for 4-bit codes, 4 for 2-bit)
+  int host_spin_us = 100;  // how long the host-sum workers poll for the next call before they sleep
 };
 Tuning& tuning();
 

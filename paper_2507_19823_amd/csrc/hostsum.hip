@@ -1,7 +1,14 @@
 // The host half of the paper's CPU-GPU split (Sec. 3.2 "CPU part", Eq. 5): the GPU hands over, per selected
 // token, its value-row number and one 2-byte weight per query head (hca_attend_weights); the host forms
 // y = sum_i w_i V_i from the value store that never leaves host memory.  Host code only.
+#include <immintrin.h>
+
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
 #include <cstring>
+#include <functional>
+#include <mutex>
 #include <thread>
 #include <vector>
 
@@ -16,8 +23,8 @@ static inline float half_to_float(uint16_t h) {
 }
 
 // y_part[G][128] += sum over selected tokens [i0, i1) of one row
-static void sum_range(int G, int32_t k, const int32_t* vrow, const uint16_t* w /*[G][k]*/, const uint16_t* v_row0,
-                      int64_t i0, int64_t i1, float* y_part) {
+[[maybe_unused]] static void sum_range_plain(int G, int32_t k, const int32_t* vrow, const uint16_t* w /*[G][k]*/, const uint16_t* v_row0,
+                            int64_t i0, int64_t i1, float* y_part) {
   for (int64_t i = i0; i < i1; ++i) {
     const int32_t r = vrow[i];
     if (r < 0) continue;
@@ -33,6 +40,109 @@ static void sum_range(int G, int32_t k, const int32_t* vrow, const uint16_t* w /
     }
   }
 }
+
+#if defined(__AVX2__) && defined(__FMA__) && defined(__F16C__)
+// The same with 8-wide fp16 -> fp32 conversion and fused multiply-adds (the host pass of this library is built
+// with these instruction sets switched on).  Per output element the terms are added in the same order as above.
+static void sum_range_avx2(int G, int32_t k, const int32_t* vrow,
+                                                                    const uint16_t* w, const uint16_t* v_row0,
+                                                                    int64_t i0, int64_t i1, float* y_part) {
+  constexpr int kAhead = 8;                        // rows asked for ahead of use (each row is four cache lines)
+  for (int64_t i = i0; i < i1; ++i) {
+    const int32_t r = vrow[i];
+    if (r < 0) continue;
+    if (i + kAhead < i1 && vrow[i + kAhead] >= 0) {
+      const char* nx = reinterpret_cast<const char*>(v_row0 + (int64_t)vrow[i + kAhead] * kHeadDim);
+      _mm_prefetch(nx, _MM_HINT_T0);
+      _mm_prefetch(nx + 64, _MM_HINT_T0);
+      _mm_prefetch(nx + 128, _MM_HINT_T0);
+      _mm_prefetch(nx + 192, _MM_HINT_T0);
+    }
+    const __m128i* v = reinterpret_cast<const __m128i*>(v_row0 + (int64_t)r * kHeadDim);
+    __m256 vf[kHeadDim / 8];
+    for (int c = 0; c < kHeadDim / 8; ++c) vf[c] = _mm256_cvtph_ps(_mm_loadu_si128(v + c));
+    for (int h = 0; h < G; ++h) {
+      const __m256 wh = _mm256_set1_ps(half_to_float(w[(int64_t)h * k + i]));
+      float* y = y_part + h * kHeadDim;
+      for (int c = 0; c < kHeadDim / 8; ++c)
+        _mm256_storeu_ps(y + 8 * c, _mm256_fmadd_ps(wh, vf[c], _mm256_loadu_ps(y + 8 * c)));
+    }
+  }
+}
+
+constexpr auto sum_range = sum_range_avx2;
+#else
+constexpr auto sum_range = sum_range_plain;
+#endif
+
+// Worker threads that outlive the call: starting sixteen threads costs more than the sum they are started for.
+// One job at a time (callers are serialised); the calling thread works along.  The threads are never joined:
+// they sleep on the condition variable until the process ends.
+class HostPool {
+ public:
+  static HostPool& get() {
+    static HostPool* p = new HostPool();            // never destroyed: the workers may outlive static destructors
+    return *p;
+  }
+  template <class F>
+  void run(int n_threads, int ntask, F&& task) {
+    std::lock_guard<std::mutex> serial(call_);
+    grow(n_threads - 1);
+    {
+      std::lock_guard<std::mutex> g(m_);
+      fn_ = [&](int t) { task(t); };
+      next_.store(0);
+      ntask_ = ntask;
+      helpers_ = n_threads - 1;
+      busy_ = n_threads - 1;
+      generation_.store(generation_.load(std::memory_order_relaxed) + 1, std::memory_order_release);
+    }
+    cv_.notify_all();
+    drain();
+    std::unique_lock<std::mutex> g(m_);
+    done_.wait(g, [&] { return busy_ == 0; });
+    fn_ = nullptr;
+  }
+
+ private:
+  void drain() {
+    for (int t = next_.fetch_add(1); t < ntask_; t = next_.fetch_add(1)) fn_(t);
+  }
+  void grow(int want) {
+    while ((int)workers_.size() < want) {
+      const int id = (int)workers_.size();
+      workers_.emplace_back([this, id] { loop(id); });
+      workers_.back().detach();
+    }
+  }
+  void loop(int id) {
+    uint64_t seen = 0;
+    for (;;) {
+      // a decode loop calls again within a fraction of a millisecond: poll for that long before sleeping
+      const auto t0 = std::chrono::steady_clock::now();
+      while (generation_.load(std::memory_order_acquire) == seen) {
+        for (int i = 0; i < 64; ++i) _mm_pause();
+        if (std::chrono::steady_clock::now() - t0 >= std::chrono::microseconds(tuning().host_spin_us)) break;
+      }
+      {
+        std::unique_lock<std::mutex> g(m_);
+        cv_.wait(g, [&] { return generation_.load(std::memory_order_relaxed) != seen; });
+        seen = generation_.load(std::memory_order_relaxed);
+        if (id >= helpers_) continue;               // this job asked for fewer threads
+      }
+      drain();
+      std::lock_guard<std::mutex> g(m_);
+      if (--busy_ == 0) done_.notify_one();
+    }
+  }
+  std::mutex call_, m_;
+  std::condition_variable cv_, done_;
+  std::vector<std::thread> workers_;
+  std::function<void(int)> fn_;
+  std::atomic<int> next_{0};
+  int ntask_ = 0, helpers_ = 0, busy_ = 0;
+  std::atomic<uint64_t> generation_{0};
+};
 
 }  // namespace hca
 
@@ -58,30 +168,32 @@ extern "C" int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* 
   int parts = (n_threads + L.rows - 1) / L.rows;
   if (parts < 1) parts = 1;
   const int ntask = L.rows * parts;
-  std::vector<float> partial((size_t)ntask * G * kHeadDim, 0.0f);
-  auto work = [&](int t0) {
-    for (int t = t0; t < ntask; t += n_threads) {
-      const int row = t / parts, part = t % parts;
-      int64_t cnt = count[row];
-      if (cnt > k) cnt = k;
-      const int64_t per = (cnt + parts - 1) / parts;
-      int64_t i0 = per * part, i1 = i0 + per;
-      if (i1 > cnt) i1 = cnt;
-      if (i0 < i1)
-        sum_range(G, k, vrow + (int64_t)row * k, (const uint16_t*)w_f16 + (int64_t)row * G * k,
-                  (const uint16_t*)v_host + (int64_t)row * host_stride * kHeadDim, i0, i1,
-                  &partial[(size_t)t * G * kHeadDim]);
-    }
-  };
   for (int row = 0; row < L.rows; ++row) {
     int64_t cnt = count[row] < k ? count[row] : k;
     for (int64_t i = 0; i < cnt; ++i)
       if (vrow[(int64_t)row * k + i] >= host_stride) return HCA_ERR_CAPACITY;
   }
-  std::vector<std::thread> pool;
-  for (int t = 1; t < n_threads; ++t) pool.emplace_back(work, t);
-  work(0);
-  for (auto& th : pool) th.join();
+  std::vector<float> partial((size_t)ntask * G * kHeadDim, 0.0f);
+  auto task = [&](int t) {
+    const int row = t / parts, part = t % parts;
+    int64_t cnt = count[row];
+    if (cnt > k) cnt = k;
+    const int64_t per = (cnt + parts - 1) / parts;
+    int64_t i0 = per * part, i1 = i0 + per;
+    if (i1 > cnt) i1 = cnt;
+    if (i0 >= i1) return;
+    // the running sums live on the stack of the thread that forms them and are handed over once at the end
+    alignas(64) float acc[4 * kHeadDim];             // at most four query heads share a KV head
+    std::memset(acc, 0, sizeof(float) * G * kHeadDim);
+    sum_range(G, k, vrow + (int64_t)row * k, (const uint16_t*)w_f16 + (int64_t)row * G * k,
+              (const uint16_t*)v_host + (int64_t)row * host_stride * kHeadDim, i0, i1, acc);
+    std::memcpy(&partial[(size_t)t * G * kHeadDim], acc, sizeof(float) * G * kHeadDim);
+  };
+  if (n_threads == 1) {
+    for (int t = 0; t < ntask; ++t) task(t);
+  } else {
+    HostPool::get().run(n_threads, ntask, task);
+  }
   for (int row = 0; row < L.rows; ++row)
     for (int e = 0; e < G * kHeadDim; ++e) {
       float acc = 0.0f;

@@ -196,6 +196,25 @@ def test_host_weighted_sum_matches_numpy(B):
         B.hca_host_weighted_sum(shape, torch.from_numpy(vrow), torch.from_numpy(count), k, torch.from_numpy(w16),
                                 torch.from_numpy(V), vrows, y, nt)
         assert np.allclose(y.numpy(), ref, rtol=1e-4, atol=1e-5)
+    # the worker threads are kept between calls and serve one call at a time: callers on two threads,
+    # with different thread counts, both get the full sum every time
+    import threading
+    wrong = []
+
+    def caller(nt):
+        yy = torch.zeros(R * G, 128)
+        for _ in range(25):
+            yy.zero_()
+            B.hca_host_weighted_sum(shape, torch.from_numpy(vrow), torch.from_numpy(count), k,
+                                    torch.from_numpy(w16), torch.from_numpy(V), vrows, yy, nt)
+            if not np.allclose(yy.numpy(), ref, rtol=1e-4, atol=1e-5):
+                wrong.append(nt)
+    th = [threading.Thread(target=caller, args=(nt,)) for nt in (3, 8)]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    assert not wrong
     bad = vrow.copy()
     bad[1, 0] = vrows
     with pytest.raises(B.HcaError):
