@@ -60,17 +60,22 @@ __device__ __forceinline__ void quantize_body(const Layout& L, uint8_t* __restri
     if ((sh & 0x7fffu) == 0) sh = 0x3c00u;
     const float sc = h2f(sh);
     const float inv = 1.0f / sc;
-    uint32_t lo = 0, hi = 0;
+    // x >= mn, so the quotient is never negative: one upper clamp, then the saturating float -> byte
+    // conversion, which rounds to nearest even and drops the code into its byte of a dword (4 codes each).
+    uint32_t b[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-      float v = rintf((x[m][i] - mn) * inv);
-      v = fminf(fmaxf(v, 0.0f), (float)QMAX);
-      const uint32_t c = (uint32_t)(int)v;
-      if (BITS == 4) {
-        if (i < 8) lo |= c << (4 * i); else hi |= c << (4 * (i - 8));
-      } else {
-        lo |= c << (2 * i);
-      }
+      const float v = fminf((x[m][i] - mn) * inv, (float)QMAX);
+      b[i >> 2] = __builtin_amdgcn_cvt_pk_u8_f32(v, (uint32_t)(i & 3), b[i >> 2]);
+    }
+    // bytes -> packed codes: even- and odd-numbered codes of two dwords gathered bytewise, the odd ones
+    // shifted up by one code width; once for 4-bit codes, twice for 2-bit codes
+    constexpr uint32_t kEven = 0x06040200u, kOdd = 0x07050301u;
+    uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], kEven) | (__builtin_amdgcn_perm(b[1], b[0], kOdd) << BITS);
+    uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], kEven) | (__builtin_amdgcn_perm(b[3], b[2], kOdd) << BITS);
+    if (BITS == 2) {
+      lo = __builtin_amdgcn_perm(hi, lo, kEven) | (__builtin_amdgcn_perm(hi, lo, kOdd) << 4);
+      hi = 0;
     }
     packed[m][0] = lo;
     packed[m][1] = hi;
