@@ -69,6 +69,18 @@ def test_score_topk_matches_the_oracle(H, oracle, bits, gs, n, k, lens):
         assert cand[0] < n // 8
 
 
+@pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
+def test_the_largest_k(H, oracle, bits, gs):
+    """k = 16384, the most the step driver accepts: more candidates than the LDS stage holds, one row barely
+    longer than k."""
+    n, k = 120000, 16384
+    lens = [n, k + 5]
+    w = S.Workload("stmax", 95 + bits, 2, 8, 2, n, bits, gs, k)
+    d = S.make_layer(w, want_values=False)
+    cand, resc = _run(H, oracle, w, d["keys"], d["q"], lens, k)
+    assert int(cand.min()) >= k
+
+
 @pytest.mark.parametrize("hq,hkv", [(4, 2), (2, 2), (6, 3)])
 def test_fewer_query_heads_per_kv_head(H, oracle, hq, hkv):
     """Groups of two query heads and of one: the selection score is the maximum over the heads that exist."""
