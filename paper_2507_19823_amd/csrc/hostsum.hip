@@ -2,6 +2,7 @@
 // token, its value-row number and one 2-byte weight per query head (hca_attend_weights); the host forms
 // y = sum_i w_i V_i from the value store that never leaves host memory.  Host code only.
 #include <immintrin.h>
+#include <unistd.h>
 
 #include <atomic>
 #include <chrono>
@@ -81,7 +82,17 @@ constexpr auto sum_range = sum_range_plain;
 class HostPool {
  public:
   static HostPool& get() {
-    static HostPool* p = new HostPool();            // never destroyed: the workers may outlive static destructors
+    // never destroyed: the workers may outlive static destructors.  A forked child inherits the object but none
+    // of its threads, so it starts a pool of its own.
+    static std::mutex mu;
+    static HostPool* p = nullptr;
+    static pid_t owner = 0;
+    std::lock_guard<std::mutex> g(mu);
+    const pid_t me = getpid();
+    if (p == nullptr || owner != me) {
+      p = new HostPool();
+      owner = me;
+    }
     return *p;
   }
   template <class F>

@@ -215,6 +215,31 @@ def test_host_weighted_sum_matches_numpy(B):
     for t in th:
         t.join()
     assert not wrong
+    # a forked child has none of the parent's worker threads and must start its own
+    pid = os.fork()
+    if pid == 0:
+        code = 1
+        try:
+            yy = torch.zeros(R * G, 128)
+            B.hca_host_weighted_sum(shape, torch.from_numpy(vrow), torch.from_numpy(count), k,
+                                    torch.from_numpy(w16), torch.from_numpy(V), vrows, yy, 4)
+            code = 0 if np.allclose(yy.numpy(), ref, rtol=1e-4, atol=1e-5) else 2
+        finally:
+            os._exit(code)
+    import time
+    t_end = time.time() + 30
+    status = None
+    while time.time() < t_end:
+        done, st = os.waitpid(pid, os.WNOHANG)
+        if done == pid:
+            status = st
+            break
+        time.sleep(0.02)
+    if status is None:
+        os.kill(pid, 9)
+        os.waitpid(pid, 0)
+        pytest.fail("the forked child did not finish its host sum")
+    assert os.WIFEXITED(status) and os.WEXITSTATUS(status) == 0
     bad = vrow.copy()
     bad[1, 0] = vrows
     with pytest.raises(B.HcaError):
