@@ -1130,7 +1130,7 @@ def main():
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,
-        "roofline": {"bound": "hbm", "kernel": "score_kernel (selecting scan)" if fused else "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "score_select_step_kernel (the selecting scan; one launch per layer)" if fused else "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes,
                      "avg_event_bracket_ms": bracket_ms,
