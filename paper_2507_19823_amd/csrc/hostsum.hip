@@ -9,6 +9,7 @@
 #include <condition_variable>
 #include <cstring>
 #include <functional>
+#include <memory>
 #include <mutex>
 #include <thread>
 #include <vector>
@@ -77,8 +78,9 @@ constexpr auto sum_range = sum_range_plain;
 #endif
 
 // Worker threads that outlive the call: starting sixteen threads costs more than the sum they are started for.
-// One job at a time (callers are serialised); the calling thread works along.  The threads are never joined:
-// they sleep on the condition variable until the process ends.
+// One job at a time (callers are serialised); the calling thread works along and the call ends when the last
+// task has ended, whoever ran it: a worker that wakes late finds its job drained and goes back to waiting,
+// nobody waits for it.  The threads are never joined: they sleep on the condition variable until the process ends.
 class HostPool {
  public:
   static HostPool& get() {
@@ -99,25 +101,34 @@ class HostPool {
   void run(int n_threads, int ntask, F&& task) {
     std::lock_guard<std::mutex> serial(call_);
     grow(n_threads - 1);
+    auto job = std::make_shared<Job>();
+    job->fn = [&](int t) { task(t); };
+    job->ntask = ntask;
+    job->helpers = n_threads - 1;
     {
       std::lock_guard<std::mutex> g(m_);
-      fn_ = [&](int t) { task(t); };
-      next_.store(0);
-      ntask_ = ntask;
-      helpers_ = n_threads - 1;
-      busy_ = n_threads - 1;
+      job_ = job;
       generation_.store(generation_.load(std::memory_order_relaxed) + 1, std::memory_order_release);
     }
     cv_.notify_all();
-    drain();
-    std::unique_lock<std::mutex> g(m_);
-    done_.wait(g, [&] { return busy_ == 0; });
-    fn_ = nullptr;
+    drain(*job);
+    // the tasks still running on other threads: short ones, so poll
+    while (job->finished.load(std::memory_order_acquire) < ntask) _mm_pause();
   }
 
  private:
-  void drain() {
-    for (int t = next_.fetch_add(1); t < ntask_; t = next_.fetch_add(1)) fn_(t);
+  // One call's work.  Workers hold it by shared pointer, so one that is still looking at it when the call
+  // has returned touches memory that is still there - and, every task having been claimed, nothing else.
+  struct Job {
+    std::function<void(int)> fn;
+    int ntask = 0, helpers = 0;
+    std::atomic<int> next{0}, finished{0};
+  };
+  static void drain(Job& j) {
+    for (int t = j.next.fetch_add(1); t < j.ntask; t = j.next.fetch_add(1)) {
+      j.fn(t);
+      j.finished.fetch_add(1, std::memory_order_release);
+    }
   }
   void grow(int want) {
     while ((int)workers_.size() < want) {
@@ -135,23 +146,20 @@ class HostPool {
         for (int i = 0; i < 64; ++i) _mm_pause();
         if (std::chrono::steady_clock::now() - t0 >= std::chrono::microseconds(tuning().host_spin_us)) break;
       }
+      std::shared_ptr<Job> job;
       {
         std::unique_lock<std::mutex> g(m_);
         cv_.wait(g, [&] { return generation_.load(std::memory_order_relaxed) != seen; });
         seen = generation_.load(std::memory_order_relaxed);
-        if (id >= helpers_) continue;               // this job asked for fewer threads
+        job = job_;
       }
-      drain();
-      std::lock_guard<std::mutex> g(m_);
-      if (--busy_ == 0) done_.notify_one();
+      if (id < job->helpers) drain(*job);           // else this job asked for fewer threads
     }
   }
   std::mutex call_, m_;
-  std::condition_variable cv_, done_;
+  std::condition_variable cv_;
   std::vector<std::thread> workers_;
-  std::function<void(int)> fn_;
-  std::atomic<int> next_{0};
-  int ntask_ = 0, helpers_ = 0, busy_ = 0;
+  std::shared_ptr<Job> job_;
   std::atomic<uint64_t> generation_{0};
 };
 
@@ -176,7 +184,8 @@ extern "C" int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* 
   if (n_threads > 64) n_threads = 64;
   const int G = L.gqa;
   // tasks: every row cut into `parts` ranges of its selected tokens, partial sums added up afterwards
-  int parts = (n_threads + L.rows - 1) / L.rows;
+  // (four tasks per thread when there are several threads: the threads do not all start at the same moment)
+  int parts = ((n_threads > 1 ? 4 * n_threads : 1) + L.rows - 1) / L.rows;
   if (parts < 1) parts = 1;
   const int ntask = L.rows * parts;
   for (int row = 0; row < L.rows; ++row) {
