@@ -216,14 +216,17 @@ def test_host_weighted_sum_matches_numpy(B):
         t.join()
     assert not wrong
     # a forked child has none of the parent's worker threads and must start its own
+    # (every tensor is made before the fork: the child only calls the library and compares)
+    yy = torch.zeros(R * G, 128)
+    yy_np = yy.numpy()
+    args = (shape, torch.from_numpy(vrow), torch.from_numpy(count), k, torch.from_numpy(w16), torch.from_numpy(V),
+            vrows, yy, 4)
     pid = os.fork()
     if pid == 0:
         code = 1
         try:
-            yy = torch.zeros(R * G, 128)
-            B.hca_host_weighted_sum(shape, torch.from_numpy(vrow), torch.from_numpy(count), k,
-                                    torch.from_numpy(w16), torch.from_numpy(V), vrows, yy, 4)
-            code = 0 if np.allclose(yy.numpy(), ref, rtol=1e-4, atol=1e-5) else 2
+            B.hca_host_weighted_sum(*args)
+            code = 0 if np.allclose(yy_np, ref, rtol=1e-4, atol=1e-5) else 2
         finally:
             os._exit(code)
     import time
