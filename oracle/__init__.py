@@ -22,7 +22,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build(force=False)
+        # HCO_ORACLE_LIB: an already built variant of the same sources (the sanitizer test's)
+        path = os.environ.get("HCO_ORACLE_LIB") or _build.build(force=False)
         L = C.CDLL(path)
         L.hco_h2f.restype = C.c_float
         L.hco_h2f.argtypes = [C.c_uint16]
@@ -330,6 +331,44 @@ def topp(sel, n, sm_scale, tau, k_max):
     _check(lib().hco_topp(_p(sel), C.c_int64(R), C.c_int64(cap), _p(n), C.c_float(sm_scale), C.c_double(tau),
                           C.c_int64(k_max), _p(idx), _p(count), _p(kstar), _p(mass)), "topp")
     return idx, count, kstar, mass
+
+
+# ---- plain fp64 definitions (hca_plain_oracle.c): what the bit-reproducible forms above stand for ----------
+
+def score_plain(cache, q):
+    """Eq. 2's z~ = q . Q(K)^T with the query as it is, every term in fp64.  q [R*G, D] fp16 -> z [R*G, cap] fp64."""
+    q = _u16(q)
+    G = q.shape[0] // cache.R
+    z = np.zeros((cache.R * G, cache.cap), np.float64)
+    _check(lib().hco_score_plain(_p(q), _p(cache.codes), _p(cache.scale), _p(cache.zero), C.c_int64(cache.R),
+                                 C.c_int(G), C.c_int(cache.D), C.c_int(cache.bits), C.c_int(cache.gs),
+                                 C.c_int64(cache.cap), _p(cache.n), _p(z)), "score_plain")
+    return z
+
+
+def vq_score_plain(cache, T):
+    """Eq. 3 as written: z[hq, j] = sum_i T[hq, i, P[j, i]] in fp64.  T [R*G, g, c] fp32 -> z [R*G, cap] fp64."""
+    T = np.ascontiguousarray(T, np.float32)
+    G = T.shape[0] // cache.R
+    z = np.zeros((cache.R * G, cache.cap), np.float64)
+    _check(lib().hco_vq_score_plain(_p(T), _p(cache.P), C.c_int64(cache.R), C.c_int(G), C.c_int(cache.g),
+                                    C.c_int(cache.c), C.c_int64(cache.cap), _p(cache.n), _p(z)), "vq_score_plain")
+    return z
+
+
+def topp_plain(sel, n, sm_scale, tau, want_cum=True):
+    """Eq. 4 as written, fp64 softmax over each row.  Returns (kstar int64 [R], order int32 [R,cap] or None,
+    cum fp64 [R,cap] or None): order[r, t] is the slot at sorted position t (score descending, slot
+    ascending), cum[r, t] the attention mass of the first t + 1 sorted slots."""
+    sel = np.ascontiguousarray(sel, np.float32)
+    R, cap = sel.shape
+    n = _i64(n)
+    kstar = np.zeros(R, np.int64)
+    order = np.zeros((R, cap), np.int32) if want_cum else None
+    cum = np.zeros((R, cap), np.float64) if want_cum else None
+    _check(lib().hco_topp_plain(_p(sel), C.c_int64(R), C.c_int64(cap), _p(n), C.c_double(sm_scale),
+                                C.c_double(tau), _p(kstar), _p(order), _p(cum)), "topp_plain")
+    return kstar, order, cum
 
 
 # ---- the paper's CPU-side weighted sum (Sec. 3.2 "CPU part", Sec. 3.3: 2 bytes per weight) ----------

@@ -1,4 +1,5 @@
-"""Compile the CPU oracle (plain C, gcc: hca_oracle.c, hca_vq_oracle.c, hca_topp_oracle.c) into oracle/libhca_oracle.so.
+"""Compile the CPU oracle (plain C, gcc: hca_oracle.c, hca_vq_oracle.c, hca_topp_oracle.c, hca_plain_oracle.c)
+into oracle/libhca_oracle.so.
 
 Flags matter: -ffp-contract=off keeps every fp32 operation a single rounded IEEE
 operation (the oracle's bit-level definition depends on it); no fast-math.
@@ -9,7 +10,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRCS = [os.path.join(HERE, "hca_oracle.c"), os.path.join(HERE, "hca_vq_oracle.c"),
-        os.path.join(HERE, "hca_topp_oracle.c")]
+        os.path.join(HERE, "hca_topp_oracle.c"), os.path.join(HERE, "hca_plain_oracle.c")]
 LIB = os.path.join(HERE, "libhca_oracle.so")
 
 
@@ -20,6 +21,16 @@ def build(force: bool = True) -> str:
            "-fPIC", "-shared", "-Wall", "-Wextra", "-o", LIB] + SRCS + ["-lm"]
     subprocess.run(cmd, check=True)
     return LIB
+
+
+def build_sanitized(out: str) -> str:
+    """The same sources with gcc's address and undefined-behaviour sanitizers, into `out` (host code only; a test
+    loads it in a child process that preloads the sanitizer runtime)."""
+    cmd = ["gcc", "-std=c11", "-O1", "-g", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+           "-fPIC", "-shared", "-o", out] + SRCS + ["-lm"]
+    subprocess.run(cmd, check=True)
+    return out
 
 
 if __name__ == "__main__":

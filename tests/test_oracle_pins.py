@@ -140,6 +140,110 @@ def test_quantize_exhaustive_two_level_group(oracle):
     assert reach.mean() > 0.95 and ok.all()
 
 
+def _one_group_codes(oracle, vals, bits=4, gs=32):
+    """Quantise one token whose first group holds `vals` (padded with the group's minimum) and return that
+    group's codes, scale and zero."""
+    x = np.full((1, 1, 128), np.float16(0.0))
+    v = np.asarray(vals, np.float16)
+    x[0, 0, :gs] = v.min()
+    x[0, 0, :len(v)] = v
+    c = oracle.Cache(1, 1, 128, bits, gs)
+    oracle.quantize(c, x)
+    code = _unpack(c.codes[:, :1], bits)[0, 0, :len(v)]
+    return list(code), float(c.scale.view(np.float16)[0, 0, 0]), float(c.zero.view(np.float16)[0, 0, 0])
+
+
+def test_quantize_rounds_halves_to_even(oracle):
+    """Hand-worked: a 4-bit group with minimum 0 and maximum 15 has scale fp16(15 / 15) = 1 and reciprocal 1, so a
+    channel's code is rint(x) itself.  2.5 and 3.5 lie exactly between two codes: ties go to the even one, 2 and 4
+    (adding one half and truncating would give 3 and 4); likewise 0.5 -> 0, 1.5 -> 2, 13.5 -> 14, 14.5 -> 14."""
+    code, scale, zero = _one_group_codes(oracle, [0.0, 15.0, 2.5, 3.5, 0.5, 1.5, 13.5, 14.5, 7.0, 7.25, 7.75])
+    assert scale == 1.0 and zero == 0.0
+    assert code == [0, 15, 2, 4, 0, 2, 14, 14, 7, 7, 8]
+    # 2-bit, group of 64: minimum 0, maximum 3 -> scale 1: 0.5 -> 0, 1.5 -> 2, 2.5 -> 2
+    code, scale, _ = _one_group_codes(oracle, [0.0, 3.0, 0.5, 1.5, 2.5], bits=2, gs=64)
+    assert scale == 1.0 and code == [0, 3, 0, 2, 2]
+
+
+def test_quantize_multiplies_by_the_reciprocal_of_the_scale(oracle):
+    """Hand-worked case in which code = rint((x - min) * (1 / scale)), the form this build fixes, differs from
+    rint((x - min) / scale).  Group minimum 0, maximum 105/256: scale = fp16(105/256 / 15) = 7/256 exactly.
+    x = 91/512: x / scale = 6.5 exactly, a tie, which division would round to the even code 6.  The reciprocal
+    1 / scale = 256/7 = 36.5714285714... is not representable; its fp32 rounding is 9586981 * 2^-18 =
+    36.57143020629883 (0.43 ulp above).  x times that is 6.50000029057..., which lies above the midpoint
+    6.5 + 2^-22 of the two neighbouring fp32 numbers 6.5 and 6.5 + 2^-21, so the product rounds to 6.5 + 2^-21
+    and rint gives 7."""
+    from fractions import Fraction as F
+    inv = F(9586981, 2 ** 18)
+    assert abs(inv - F(256, 7)) < F(1, 2 ** 19) and float(np.float32(1) / np.float32(7 / 256)) == float(inv)
+    prod = F(91, 512) * inv
+    assert prod > F(13, 2) + F(1, 2 ** 22)                       # beyond the fp32 midpoint above 6.5
+    code, scale, zero = _one_group_codes(oracle, [0.0, 105 / 256, 91 / 512])
+    assert scale == 7 / 256 and zero == 0.0
+    assert code == [0, 15, 7]
+
+
+def test_score_adds_the_four_group_terms_pairwise(oracle):
+    """Hand-built cache (codes / scale / zero written directly) whose four group terms are 2^24, 0, 1, 1 before the
+    2^-s factor: (t0 + t1) + (t2 + t3) = 2^24 + 2, exactly representable, while adding left to right loses both
+    ones (2^24 + 1 rounds back to 2^24 twice).  Query: 1.0 in the first channel of every group, so s = 13,
+    qfx = 8192 there, Q_g = 8192 and D_g = 8192 * (first code of the group).
+      group 0: code 0, zero 2048           -> fma(scale, 0, 2048 * 8192) = 2^24
+      group 1: code 0, zero 0              -> 0
+      groups 2, 3: code 1, scale 2^-13, zero 0 -> 2^-13 * 8192 = 1
+    z~ = (2^24 + 2) * 2^-13 = 2048 + 2^-12."""
+    c = oracle.Cache(1, 1, 128, 4, 32)
+    c.n[:] = 1
+    h = lambda v: np.array([v], np.float16).view(np.uint16)[0]
+    c.scale[0, 0] = [h(1.0), h(1.0), h(2.0 ** -13), h(2.0 ** -13)]
+    c.zero[0, 0] = [h(2048.0), h(0.0), h(0.0), h(0.0)]
+    c.codes[0, 0, 32] = 1                                        # channel 64 (group 2): low nibble of byte 32
+    c.codes[0, 0, 48] = 1                                        # channel 96 (group 3)
+    q = np.zeros((1, 128), np.float16)
+    q[0, ::32] = 1.0
+    qfx, s = oracle.query_fixed(q[0])
+    assert s == 13 and list(qfx[::32]) == [8192] * 4 and np.count_nonzero(qfx) == 4
+    sel, z = oracle.score(c, q)
+    assert float(z[0, 0]) == 2048.0 + 2.0 ** -12
+    assert float(sel[0, 0]) == 2048.0 + 2.0 ** -12
+    # two groups (2-bit, group 64): t0 + t1 only; 2^24 and 1 -> 2^24 (the one is lost to rounding, once)
+    c2 = oracle.Cache(1, 1, 128, 2, 64)
+    c2.n[:] = 1
+    c2.scale[0, 0] = [h(1.0), h(2.0 ** -13)]
+    c2.zero[0, 0] = [h(2048.0), h(0.0)]
+    c2.codes[0, 0, 16] = 1                                       # channel 64 (group 1): low crumb of byte 16
+    q2 = np.zeros((1, 128), np.float16)
+    q2[0, ::64] = 1.0
+    _, z2 = oracle.score(c2, q2)
+    assert float(z2[0, 0]) == 2048.0
+
+
+@pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64), (8, 32)])
+def test_fixed_point_score_against_the_plain_fp64_definition(oracle, bits, gs):
+    """The plain form of Eq. 2's z~ = q . Q(K)^T (query untouched, fp64) is (a) numpy's matrix product over the
+    dequantised keys, and (b) within 2^-14 max|q| sum_c |k^_c| of the fixed-point form: the query's 15-bit
+    image is off by at most half a step of 2^-s per channel, and 2^(13-s) <= max|q|."""
+    rng = np.random.default_rng(40 + bits)
+    R, G, T, D = 2, 4, 257, 128
+    k = _keys(rng, R, T)
+    q = (rng.standard_normal((R * G, D)) * 0.7).astype(np.float16)
+    c = oracle.Cache(R, T + 3, D, bits, gs)
+    oracle.quantize(c, k)
+    zp = oracle.score_plain(c, q)
+    _, z = oracle.score(c, q)
+    code = _unpack(c.codes[:, :T], bits).astype(np.float64)
+    sc = np.repeat(c.scale[:, :T].view(np.float16).astype(np.float64), gs, axis=-1)
+    zr = np.repeat(c.zero[:, :T].view(np.float16).astype(np.float64), gs, axis=-1)
+    khat = sc * code + zr                                                     # [R,T,D], independent decode
+    for hq in range(R * G):
+        r = hq // G
+        ref = khat[r] @ q[hq].astype(np.float64)
+        assert np.allclose(zp[hq, :T], ref, rtol=1e-12, atol=1e-12)
+        assert np.all(zp[hq, T:] == 0)
+        mag = np.abs(khat[r]).sum(-1) * np.abs(q[hq].astype(np.float64)).max()
+        assert np.all(np.abs(z[hq, :T] - zp[hq, :T]) <= 2.0 ** -14 * mag + 1e-5 * np.abs(zp[hq, :T]) + 1e-6)
+
+
 def test_budget_closed_forms(oracle):
     """Table 1a: a g-entry 16-bit index row against a d-entry 16-bit key row is g/d of the
     key budget; the 4-bit and 2-bit code rows of this build occupy the same bytes."""

@@ -109,3 +109,51 @@ def test_clip_gives_the_top_k_set_and_ragged_rows(oracle):
     for r in (0, 3):
         assert kstar[r] > 30 and np.array_equal(idx[r], ridx[r])
     assert np.array_equal(idx[2, :count[2]], np.sort(np.argsort(-sel[2, :17], kind="stable")[:count[2]]))
+
+
+def topp_margin(n, Z):
+    """How far the attention mass of the integer form's prefix may lie from the fp64 one (derivation: every integer
+    weight is exp(u) 2^31 (1 + d) with |d| <= 3e-5 - polynomial 2e-5, fp32 logit and product roundings the rest -
+    minus a truncation below one unit; a prefix sum over Z therefore moves by at most 2 * 3e-5 relative plus n
+    units out of Z >= 2^31)."""
+    return 6e-5 + n / float(Z)
+
+
+@pytest.mark.parametrize("tau", [0.3, 0.9, 0.999])
+def test_plain_eq4_against_numpy_and_the_integer_form_against_it(oracle, tau):
+    """hco_topp_plain is Eq. 4 as written (fp64 softmax, sort, shortest prefix reaching tau): checked against numpy.
+    The integer form's k* is then valid for the plain one up to the stated margin: its prefix holds at least
+    tau - eps of the plain mass and one slot less holds less than tau + eps."""
+    rng = np.random.default_rng(int(tau * 1000))
+    R, n, cap = 4, 3000, 3010
+    sm = 0.0884
+    sel = np.zeros((R, cap), np.float32)
+    sel[:, :n] = rng.standard_normal((R, n)).astype(np.float32) * 30
+    sel[1, :n] = np.round(sel[1, :n] / 4) * 4                              # heavy ties
+    sel[2, :n] *= 0.05                                                     # nearly flat: long prefix
+    sel[3, 7] = 900.0                                                      # one dominant token
+    ns = [n, n, n, n - 100]
+    kp, order, cum = oracle.topp_plain(sel, ns, sm, tau)
+    _, _, ks, mass = oracle.topp(sel, ns, sm, tau, n)
+    for r in range(R):
+        nr = ns[r]
+        l = sel[r, :nr].astype(np.float64) * sm
+        a = np.exp(l - l.max())
+        a /= a.sum()
+        o = np.lexsort((np.arange(nr), -sel[r, :nr].astype(np.float64)))
+        ref = np.cumsum(a[o])
+        assert np.array_equal(order[r, :nr], o)
+        assert np.allclose(cum[r, :nr], ref, rtol=1e-12, atol=1e-15)
+        want = int(np.argmax(ref >= tau)) + 1 if ref[-1] >= tau else nr
+        assert kp[r] == want
+        eps = topp_margin(nr, int(mass[r, 1]))
+        k = int(ks[r])
+        assert cum[r, k - 1] >= tau - eps
+        assert k == 1 or cum[r, k - 2] < tau + eps
+        # and wherever the plain prefix clears tau by more than the margin on both sides, the two agree
+        if cum[r, kp[r] - 1] >= tau + eps and (kp[r] == 1 or cum[r, kp[r] - 2] < tau - eps):
+            assert k == kp[r]
+    # equal scores: the mass of a prefix is its length over n (closed form)
+    flat = np.full((1, 100), 2.0, np.float32)
+    kp, _, cum = oracle.topp_plain(flat, [100], 0.3, 0.25)
+    assert kp[0] == 25 and np.allclose(cum[0], np.arange(1, 101) / 100, rtol=1e-12)

@@ -164,6 +164,32 @@ def test_eq3_sum_is_exact_on_the_tables_grid(oracle):
             oracle.vq_score(vc, Tb)
 
 
+def test_plain_eq3_against_numpy_and_the_grid_form_against_it(oracle):
+    """hco_vq_score_plain is Eq. 3 as written (fp64 sum of the fp32 table entries a token's indices select):
+    checked against numpy indexing.  The grid form (hco_vq_score) stays within g half steps of the grid plus one
+    final fp32 rounding of it, for Gaussian tables and for tables spread over many binades."""
+    rng = np.random.default_rng(17)
+    R, G, g, c, n = 3, 2, 32, 300, 200
+    vc = oracle.VQCache(R, n + 4, np.zeros((1, g, c, D // g), np.float32))
+    vc.P[:, :n] = rng.integers(0, c, size=(R, n, g)).astype(np.uint16)
+    vc.n[:] = [n, n - 7, 0]
+    for spread in (0, 10):
+        T = (rng.standard_normal((R * G, g, c)) * np.exp2(rng.integers(-spread, 1, size=(R * G, g, c)))).astype(np.float32)
+        zp = oracle.vq_score_plain(vc, T)
+        _, z = oracle.vq_score(vc, T)
+        _, sexp = oracle.vq_lut_fx(T)
+        for hq in range(R * G):
+            nr = int(vc.n[hq // G])
+            ref = T[hq].astype(np.float64)[np.arange(g)[None, :], vc.P[hq // G, :nr].astype(np.int64)].sum(1)
+            assert np.allclose(zp[hq, :nr], ref, rtol=1e-13, atol=1e-13)
+            assert np.all(zp[hq, nr:] == 0)
+            bound = g * 0.5 * 2.0 ** -int(sexp[hq]) + np.abs(ref) * 2.0 ** -23
+            assert np.all(np.abs(z[hq, :nr].astype(np.float64) - zp[hq, :nr]) <= bound)
+    with pytest.raises(Exception):                                   # an index beyond the codebook is refused
+        vc.P[0, 0, 0] = c
+        oracle.vq_score_plain(vc, T)
+
+
 def test_codebook_holding_every_subvector_reproduces_eq1(oracle):
     """With one centroid per distinct sub-vector the compressor is the identity, so the scores are the
     exact q . K and selecting every token gives standard attention (Eq. 1)."""
