@@ -273,7 +273,12 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
                                   int32_t timing_slots);
 void hca_pipeline_destroy(hca_pipeline* p);
 
-/* Enqueues one decode step.  layers: host array [n_layers], updated when buffers swap on eviction.
+/* Enqueues one decode step.  Every argument, length and capacity of every layer is checked before the first
+ * enqueue: an HCA_ERR_BAD_ARG / HCA_ERR_CAPACITY return has launched nothing and has changed neither n_resident
+ * nor layers.  HCA_ERR_HIP (a HIP call failed while enqueueing) can come from the middle of a step: part of it
+ * is then enqueued and n_resident / layers updated for the layers reached; the caller synchronises the device
+ * and abandons the pipeline.
+ * layers: host array [n_layers], updated when buffers swap on eviction.
  * n_resident: host, int64 [n_layers][batch], updated (+1 for the appended token, then min(., evict_M)).
  * value_row0: value-store row of the appended token (all sequences).  evict_M: host, int64 [n_layers]
  * or NULL; layer l with evict_M[l] != 0 and n_resident > evict_M[l] is evicted to evict_M[l] after its

@@ -66,12 +66,24 @@ const char* hca_version(void) { return "hca 0.1 (gfx950)"; }
 int32_t hca_tune(const char* name, int32_t value) {
   if (name == nullptr) return HCA_ERR_BAD_ARG;
   Tuning& t = tuning();
-  if (!strcmp(name, "gather_wgs")) t.gather_wgs = value;
-  else if (!strcmp(name, "gather_unroll")) t.gather_unroll = value;
-  else if (!strcmp(name, "score_bpw")) t.score_bpw = value;
-  else if (!strcmp(name, "score_depth")) t.score_depth = value;
-  else if (!strcmp(name, "host_spin_us")) t.host_spin_us = value < 0 ? 0 : value;
-  else return HCA_ERR_BAD_ARG;
+  // every knob has a closed range: the kernels' buffers (wave stamps, partial sums) are sized for it
+  if (!strcmp(name, "gather_wgs")) {
+    if (value < 0 || value > 1024) return HCA_ERR_BAD_ARG;
+    t.gather_wgs = value;
+  } else if (!strcmp(name, "gather_unroll")) {
+    if (value < 0 || value > 4) return HCA_ERR_BAD_ARG;
+    t.gather_unroll = value;
+  } else if (!strcmp(name, "score_bpw")) {
+    if (value != 0 && (value < kScoreBpwMin || value > kScoreBpwMax)) return HCA_ERR_BAD_ARG;
+    t.score_bpw = value;
+  } else if (!strcmp(name, "score_depth")) {
+    if (!(value == 0 || value == 4 || value == 8)) return HCA_ERR_BAD_ARG;
+    t.score_depth = value;
+  } else if (!strcmp(name, "host_spin_us")) {
+    t.host_spin_us = value < 0 ? 0 : value;
+  } else {
+    return HCA_ERR_BAD_ARG;
+  }
   return HCA_OK;
 }
 

@@ -28,11 +28,14 @@ int32_t load_nres(const Layout& L, const int64_t* n_resident, NRes* out, int64_t
 struct Tuning {
   int gather_wgs = 0;      // workgroups of the value gather per row (0 = default)
   int gather_unroll = 4;   // rows in flight per thread
-  int score_bpw = 0;       // 1 KiB code blocks per wave (0 = automatic)
+  int score_bpw = 0;       // 1 KiB code blocks per wave (0 = automatic; else kScoreBpwMin .. kScoreBpwMax)
   int score_depth = 0;     // blocks fetched ahead per wave (4 or 8; 0 = 8 for 4-bit codes, 4 for 2-bit)
   int host_spin_us = 100;  // how long the host-sum workers poll for the next call before they sleep
 };
 Tuning& tuning();
+// Blocks per wave of the key scan.  The lower bound sizes the per-wave buffers of a launch (wall-clock stamps,
+// partial softmax sums): a row of nblocks blocks never has more than nblocks / kScoreBpwMin + 4 waves.
+constexpr int kScoreBpwMin = 4, kScoreBpwMax = 32;
 
 inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 

@@ -113,6 +113,28 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
   if (timing_slot >= p->timing_slots) return HCA_ERR_BAD_ARG;
   const int vg = p->d.vq_groups, vc = p->d.vq_codewords;
   const bool vq = vg > 0;
+  // Every argument, length and capacity check of every layer comes before the first enqueue, so that an error
+  // found here leaves the streams, n_resident and layers[] untouched.  Past this loop only a failing HIP call can
+  // end the step early.
+  if (n_host_rows < 0 || host_stride < 0 || hbm_stride < 0) return HCA_ERR_BAD_ARG;
+  for (int l = 0; l < p->n_layers; ++l) {
+    const hca_layer& ly = layers[l];
+    if (ly.kcache == nullptr || ly.acc == nullptr || ly.pos == nullptr || ly.k_new == nullptr || ly.q == nullptr ||
+        ly.y == nullptr)
+      return HCA_ERR_BAD_ARG;
+    if (vq && (ly.vq_centroids == nullptr || ly.vq_lut == nullptr)) return HCA_ERR_BAD_ARG;
+    if (n_host_rows > 0 && (ly.v_host == nullptr || host_stride < n_host_rows)) return HCA_ERR_BAD_ARG;
+    if (ly.v_host == nullptr && ly.v_hbm == nullptr) return HCA_ERR_BAD_ARG;
+    NRes nr;
+    int64_t nmax;
+    const int32_t rc = load_nres(L, n_resident + (int64_t)l * L.batch, &nr, &nmax);
+    if (rc != HCA_OK) return rc;
+    for (int b = 0; b < L.batch; ++b)
+      if (nr.n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;             // the step appends one token per sequence
+    if (!vq && timing_slot >= 0 && p->d.scan_stamps != nullptr && p->d.scan_stamp_pairs < score_stamp_pairs(L, nmax + 1))
+      return HCA_ERR_CAPACITY;
+    if (p->d.fused_select != 0 && select_scan_bpw(L, nmax + 1) == 0) return HCA_ERR_CAPACITY;   // row too long for the lists
+  }
   hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk;
   hipStream_t sg = (hipStream_t)p->d.stream_gather, sc = (hipStream_t)p->d.stream_attend;
   NRes vrow0;

@@ -674,7 +674,7 @@ int32_t launch_select_scan(const Layout& L, const void* kcache, const void* q, c
 // number of (start, end) stamp pairs a scan launch over nmax tokens writes at most
 int64_t score_stamp_pairs(const Layout& L, int64_t nmax) {
   const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
-  return (nblocks / 4 + 1) * 4 * L.rows;      // >= grid.x * 4 waves * rows for any blocks-per-wave >= 4
+  return (nblocks / kScoreBpwMin + 4) * L.rows;   // >= grid.x * 4 waves * rows for any blocks-per-wave >= kScoreBpwMin
 }
 
 // float2 pairs a scan launch with LSE leaves per row: 4 heads x (waves of the row), for any blocks-per-wave >= 4
@@ -696,8 +696,12 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
   const int64_t bpw_max = L.bits == 4 ? 16 : 32;
   if (bpw > bpw_max) bpw = bpw_max;
   if (tn.score_bpw > 0) bpw = tn.score_bpw;
+  if (bpw < kScoreBpwMin) bpw = kScoreBpwMin;
+  if (bpw > kScoreBpwMax) bpw = kScoreBpwMax;
   const int depth = tn.score_depth > 0 ? tn.score_depth : (L.bits == 4 ? 8 : 4);
   dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
+  // every wave of the launch owns one stamp pair: the caller's buffer holds score_stamp_pairs() of them
+  if (stamps != nullptr && (int64_t)grid.x * 4 * L.rows > score_stamp_pairs(L, nmax)) return HCA_ERR_CAPACITY;
   const uint8_t* kc = (const uint8_t*)kcache;
   const uint16_t* qq = (const uint16_t*)q;
 #define HCA_SCORE(B, Z, U) score_kernel<B, Z, U><<<grid, 256, 0, st>>>(L, kc, qq, nr, (int)bpw, sel, z_opt, stamps)
@@ -732,7 +736,7 @@ int32_t launch_score_lse(const Layout& L, const void* kcache, const void* q, con
   if (bpw < 4) bpw = 4;
   const int64_t bpw_max = L.bits == 4 ? 16 : 32;
   if (bpw > bpw_max) bpw = bpw_max;
-  if (tn.score_bpw >= 4) bpw = tn.score_bpw;
+  if (tn.score_bpw >= kScoreBpwMin) bpw = tn.score_bpw;
   dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
   if ((size_t)L.rows * 4 * grid.x * 4 * sizeof(float2) > score_workspace_bytes(L)) return HCA_ERR_CAPACITY;
   const uint8_t* kc = (const uint8_t*)kcache;

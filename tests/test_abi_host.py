@@ -154,6 +154,33 @@ def test_tune_accepts_known_knobs_only(B):
     assert B.lib().hca_tune(None, 1) == -1
 
 
+def test_tune_refuses_values_the_kernels_buffers_are_not_sized_for(B):
+    """Fewer than 4 code blocks per wave would give a scan launch more waves than the per-wave stamp and
+    partial-sum buffers hold; every knob has a closed range."""
+    L = B.lib()
+    for name, bad in ((b"score_bpw", (1, 2, 3, 33, -1)), (b"score_depth", (1, 2, 3, 16, -4)),
+                      (b"gather_wgs", (-1, 1025)), (b"gather_unroll", (-1, 5))):
+        for v in bad:
+            assert L.hca_tune(name, v) == -1, (name, v)
+    for name, good in ((b"score_bpw", (4, 16, 32, 0)), (b"score_depth", (4, 8, 0)), (b"gather_wgs", (1, 1024, 0)),
+                       (b"gather_unroll", (1, 2, 4))):
+        for v in good:
+            assert L.hca_tune(name, v) == 0, (name, v)
+
+
+@pytest.mark.parametrize("bits,group,tpb", [(4, 32, 16), (2, 64, 32)])
+def test_scan_stamp_pairs_cover_every_accepted_launch_shape(B, bits, group, tpb):
+    """One (start, end) pair per wave: 4 waves per workgroup, ceil(blocks / (4 * blocks per wave)) workgroups per
+    row, for every blocks-per-wave value hca_tune accepts."""
+    for batch, n in ((1, 1), (1, 4097), (4, 131072 + 64), (1, (1 << 20) + 1), (2, 12345)):
+        s = B.make_shape(batch, 32, 8, n, bits, group)
+        pairs = B.lib().hca_scan_stamp_pairs(C.byref(s), n)
+        nblocks = -(-n // tpb)
+        for bpw in range(4, 33):
+            waves = -(-nblocks // (4 * bpw)) * 4 * batch * 8
+            assert waves <= pairs, (batch, n, bpw)
+
+
 def test_topp_and_global_weight_arguments(B):
     L = B.lib()
     s = B.make_shape(1, 32, 8, 1024)

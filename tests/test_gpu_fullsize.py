@@ -305,3 +305,197 @@ def test_step_driver_at_full_size(oracle, fused):
         assert np.array_equal(_rows(acc[l])[:, :n] > 0, oacc[l][:, :n] > 0)
         assert np.allclose(_rows(acc[l])[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-7)
     B.hca_pipeline_destroy(pl)
+
+
+# ---- config 3 at its full shape: 4 sequences x 128 Ki tokens, k = 2048, 64 decode steps with an append each,
+# eviction every 16 steps back to M = 128 Ki with the newest 16 slots protected -------------------------------
+
+_CFG3 = {}
+
+
+def _cfg3_reference(oracle):
+    """The oracle's own run of the 64 steps (nothing from the GPU enters it): per step the top-k sets and the
+    outputs, per eviction the keep lists, at the end the cache.  Computed once for the three GPU paths."""
+    if _CFG3:
+        return _CFG3
+    w = S.CONFIGS[3]
+    R, n0, steps, E, M = w.batch * w.n_kv_heads, w.n, w.steps, w.evict_every, w.evict_keep
+    cap = n0 + E + 16
+    d = S.make_layer(w, 0)
+    oc = oracle.Cache(R, cap, 128, w.bits, w.group)
+    oracle.quantize(oc, _rows(d["keys"]))
+    V = np.zeros((R, n0 + steps, 128), np.float16)
+    V[:, :n0] = _rows(d["values"])
+    pos = np.tile(np.arange(cap, dtype=np.int32), (R, 1))
+    acc = np.zeros((R, cap), np.float32)
+    sm = np.float32(1.0 / np.sqrt(128.0))
+    ref = {"idx": [], "y": [], "kept": {}, "ins": [], "ever_selected_max": []}
+    for t in range(steps):
+        k_new, v_new, q = S.make_step(w, 0, t)
+        ref["ins"].append((k_new, v_new, q))
+        n = int(oc.n[0])
+        V[:, n0 + t] = _rows(v_new)[:, 0]
+        pos[:, n] = n0 + t
+        acc[:, n] = 0
+        oracle.quantize(oc, _rows(k_new))
+        q16 = q.numpy().reshape(-1, 128)
+        sel, _ = oracle.score(oc, q16, want_z=False)
+        idx, count = oracle.topk(sel, oc.n, w.k)
+        assert np.all(count == w.k)
+        y, _ = oracle.attend(oc, q16, idx, count, pos, V, sm, acc=acc)
+        ref["idx"].append(idx)
+        ref["y"].append(y)
+        if (t + 1) % E == 0:
+            nn = int(oc.n[0])
+            # the keep-set is decided by which slots were ever selected (exact on both sides) as long as fewer
+            # than M - R unprotected slots carry a non-zero accumulated score; the rest are ties, lowest slots first
+            ref["ever_selected_max"].append(int((acc[:, :nn - E] > 0).sum(1).max()))
+            ref["kept"][t] = oracle.evict(oc, acc, pos, M, E)
+            assert int(oc.n[0]) == M
+        print(f"cfg3 oracle step {t} done", flush=True)
+    ref.update(oc=oc, V=V, pos=pos, acc=acc, values=d["values"], keys=d["keys"], cap=cap, sm=float(sm))
+    _CFG3.update(ref)
+    return _CFG3
+
+
+def _cfg3_check_final(B, shape, ref, kc, acc_t, pos_t, M):
+    w = S.CONFIGS[3]
+    cap = ref["cap"]
+    cb = torch.zeros(w.batch, w.n_kv_heads, cap, 64, dtype=torch.uint8, device="cuda")
+    sc = torch.zeros(w.batch, w.n_kv_heads, cap, 4, dtype=torch.float16, device="cuda")
+    zr = torch.zeros_like(sc)
+    B.hca_export_kcache(shape, kc, [M] * w.batch, cb, sc, zr)
+    torch.cuda.synchronize()
+    oc = ref["oc"]
+    assert np.array_equal(_rows(cb)[:, :M], oc.codes[:, :M])
+    assert np.array_equal(_rows(sc).view(np.uint16)[:, :M], oc.scale[:, :M])
+    assert np.array_equal(_rows(zr).view(np.uint16)[:, :M], oc.zero[:, :M])
+    assert np.array_equal(_rows(pos_t)[:, :M], ref["pos"][:, :M])
+    ga, oa = _rows(acc_t)[:, :M], ref["acc"][:, :M]
+    assert np.array_equal(ga > 0, oa > 0)
+    assert np.allclose(ga, oa, rtol=1e-3, atol=1e-6)
+
+
+def _cfg3_pinned_values(ref):
+    w = S.CONFIGS[3]
+    vh = torch.empty(w.batch, w.n_kv_heads, w.n + w.steps, 128, dtype=torch.float16, pin_memory=True)
+    vh.copy_(torch.from_numpy(ref["V"]).view(w.batch, w.n_kv_heads, w.n + w.steps, 128))
+    return vh
+
+
+def test_config3_full_shape_per_call_path(oracle):
+    """quantize / score / top-k (and the fused hca_score_topk) / attend / evict called one by one, 64 steps; the
+    GPU keeps its own accumulated scores throughout (they are never resynchronised with the oracle's)."""
+    from paper_2507_19823_amd import binding as B
+    from paper_2507_19823_amd.session import LayerState
+    ref = _cfg3_reference(oracle)
+    w = S.CONFIGS[3]
+    R, n0, E, M, cap = w.batch * w.n_kv_heads, w.n, w.evict_every, w.evict_keep, ref["cap"]
+    assert max(ref["ever_selected_max"]) < M - E, "keep-sets would depend on float order: compare stage-wise instead"
+    st = LayerState(w.batch, w.n_q_heads, w.n_kv_heads, cap, w.bits, w.group, k_max=w.k, m_max=M)
+    st.quantize(ref["keys"].cuda())
+    vh = _cfg3_pinned_values(ref)
+    side = torch.cuda.Stream()
+    fidx = torch.full_like(st.idx_buf[: R * w.k].view(w.batch, w.n_kv_heads, w.k), -1)
+    fcount = torch.full_like(st.count, -1)
+    worst = 0.0
+    for t in range(w.steps):
+        k_new, _, q = ref["ins"][t]
+        print(f"cfg3 per-call step {t}", flush=True)
+        st.quantize(k_new.cuda(), value_row0=[n0 + t] * w.batch)
+        qd = q.cuda()
+        _decode_step(B, st, qd, vh, n0 + w.steps, None, side)
+        B.hca_score_topk(st.shape, st.kcache, qd, st.n, w.k, fidx, fcount, st.ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(_rows(st.idx), ref["idx"][t]), f"step {t}: top-k sets differ"
+        assert np.array_equal(_rows(fidx), ref["idx"][t]), f"step {t}: fused scan + top-k sets differ"
+        err = _rel_err(st.y.cpu().numpy().reshape(-1, 128), ref["y"][t])
+        worst = max(worst, err)
+        assert err <= TOL, f"step {t}: {err}"
+        if (t + 1) % E == 0:
+            kept = torch.full((w.batch, w.n_kv_heads, M), -1, dtype=torch.int32, device="cuda")
+            st.evict(M, E, kept)
+            torch.cuda.synchronize()
+            assert np.array_equal(_rows(kept), ref["kept"][t]), f"step {t}: eviction keep-sets differ"
+            assert st.n[0] == M
+    _cfg3_check_final(B, st.shape, ref, st.kcache, st.acc, st.pos, M)
+    print(f"cfg3 per-call path: worst output error {worst:.2e}; ever-selected slots per row at the evictions "
+          f"{ref['ever_selected_max']} of {M - E}", flush=True)
+
+
+@pytest.mark.parametrize("fused,spare", [(True, False), (False, True)])
+def test_config3_full_shape_step_driver(oracle, fused, spare):
+    """The same 64 steps through hca_pipeline_step (one layer): scan + top-k fused with in-place eviction, and
+    the two-call form with eviction into a spare buffer set."""
+    import ctypes as C
+    from paper_2507_19823_amd import binding as B
+    ref = _cfg3_reference(oracle)
+    w = S.CONFIGS[3]
+    R, n0, E, M, cap = w.batch * w.n_kv_heads, w.n, w.evict_every, w.evict_keep, ref["cap"]
+    assert max(ref["ever_selected_max"]) < M - E
+    dev = "cuda"
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    nset = 2 if spare else 1
+    kc = [torch.zeros(B.hca_kcache_bytes(shape), dtype=torch.uint8, device=dev) for _ in range(nset)]
+    acc = [torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev) for _ in range(nset)]
+    pos = [torch.arange(cap, dtype=torch.int32, device=dev).repeat(w.batch, w.n_kv_heads, 1).contiguous()
+           for _ in range(nset)]
+    B.hca_quantize_keys(shape, kc[0], ref["keys"].cuda(), n0, [0] * w.batch)
+    vh = _cfg3_pinned_values(ref)
+    y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device=dev)
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    d = B.hca_pipeline_desc()
+    d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
+    wsb = B.hca_workspace_bytes(shape, w.k, M)
+    keep = []
+    for i in range(3):
+        t_ = (torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev) if fused else
+              torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev))
+        if fused:
+            d.ws_select[i] = t_.data_ptr()
+        else:
+            d.sel[i] = t_.data_ptr()
+        keep.append(t_)
+    d.n_sel = 3
+    d.fused_select = int(fused)
+    idxs = []
+    for i in range(4):
+        a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
+        b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
+        c = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
+        keep += [a, b, c]
+        idxs.append(a)
+        d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), c.data_ptr()
+    wt = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
+    we = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
+    if spare:
+        d.spare_kcache, d.spare_acc, d.spare_pos = kc[1].data_ptr(), acc[1].data_ptr(), pos[1].data_ptr()
+    pl = B.hca_pipeline_create(shape, 1, d, 0)
+    layers = (B.hca_layer * 1)()
+    layers[0].kcache, layers[0].acc, layers[0].pos = kc[0].data_ptr(), acc[0].data_ptr(), pos[0].data_ptr()
+    layers[0].v_host, layers[0].v_hbm, layers[0].y = vh.data_ptr(), None, y.data_ptr()
+    nres = (C.c_int64 * w.batch)(*([n0] * w.batch))
+    vrows = n0 + w.steps
+    worst = 0.0
+    for t in range(w.steps):
+        k_new, _, q = ref["ins"][t]
+        kn, qd = k_new.cuda(), q.cuda()
+        layers[0].k_new, layers[0].q = kn.data_ptr(), qd.data_ptr()
+        ev = (C.c_int64 * 1)(M if (t + 1) % E == 0 else 0)
+        torch.cuda.synchronize()
+        print(f"cfg3 step driver fused={fused} spare={spare} step {t}", flush=True)
+        B.hca_pipeline_step(pl, layers, nres, n0 + t, w.k, vrows, vrows, 0, ref["sm"], ev, E, -1)
+        torch.cuda.synchronize()
+        assert np.array_equal(_rows(idxs[0]), ref["idx"][t]), f"step {t}: top-k sets differ"
+        err = _rel_err(y.cpu().numpy().reshape(-1, 128), ref["y"][t])
+        worst = max(worst, err)
+        assert err <= TOL, f"step {t}: {err}"
+        want_n = M if (t + 1) % E == 0 else n0 + (t % E) + 1
+        assert [int(x) for x in nres] == [want_n] * w.batch
+    bufs = {kc[i].data_ptr(): (kc[i], acc[i], pos[i]) for i in range(nset)}
+    k_t, a_t, p_t = bufs[layers[0].kcache]
+    assert layers[0].acc == a_t.data_ptr() and layers[0].pos == p_t.data_ptr()
+    _cfg3_check_final(B, shape, ref, k_t, a_t, p_t, M)
+    B.hca_pipeline_destroy(pl)
+    print(f"cfg3 step driver fused={fused} spare={spare}: worst output error {worst:.2e}", flush=True)

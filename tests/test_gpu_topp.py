@@ -38,6 +38,19 @@ def _check(oracle, v, lens, hkv, sm, tau, k_max, got):
     assert np.array_equal(count, ocount)
     for r in range(v.shape[0]):
         assert np.array_equal(idx[r, :count[r]], oidx[r, :count[r]])
+    # validity against Eq. 4 as written (fp64 softmax, sort, shortest prefix with mass >= tau): the GPU's prefix
+    # holds at least tau - eps of the plain mass and one slot less holds less than tau + eps, eps being the margin
+    # derived for the integer weights (6e-5 relative plus n units out of Z); rows cut at k_max are top-k_max sets
+    _, order, cum = oracle.topp_plain(v, n, sm, tau)
+    for r in range(v.shape[0]):
+        nr, c = int(n[r]), int(count[r])
+        if nr == 0 or okstar[r] > k_max:
+            continue
+        eps = 6e-5 + nr / float(mass[r, 1])
+        assert c == okstar[r]
+        assert cum[r, c - 1] >= min(tau, 1.0) - eps, (r, c, cum[r, c - 1])
+        assert c == 1 or cum[r, c - 2] < tau + eps, (r, c, cum[r, c - 2])
+        assert np.array_equal(np.sort(order[r, :c]), idx[r, :c])      # the same sorted prefix, as a set
     return okstar
 
 

@@ -134,6 +134,12 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
     assert np.array_equal(zg[:, :n_used].view(np.uint32), z[:, :n_used].view(np.uint32))
     assert np.array_equal(sg[:, :n_used].view(np.uint32), sel[:, :n_used].view(np.uint32))
     assert np.all(sg[:, n_used:] == -7.0) and np.all(zg[:, n_used:] == -7.0)
+    # validity against Eq. 3 as written (fp64 sum of the table entries the indices select): the GPU's scores lie
+    # within g half steps of the head's grid plus one fp32 rounding of it
+    zp = oracle.vq_score_plain(oc, Tg)
+    for hq in range(R * G):
+        bound = g * 0.5 * 2.0 ** -int(sg_exp[hq]) + np.abs(zp[hq, :n_used]) * 2.0 ** -23
+        assert np.all(np.abs(zg[hq, :n_used].astype(np.float64) - zp[hq, :n_used]) <= bound)
 
 
 @pytest.mark.parametrize("g,c,G,n,k", [(32, 256, 4, 9000, 512), (64, 128, 4, 3001, 100), (32, 64, 2, 5000, 5000),
