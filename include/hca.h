@@ -122,6 +122,18 @@ int32_t hca_score_qkeys(const hca_shape* shape, const void* kcache, const void* 
 int32_t hca_topk(const hca_shape* shape, const float* sel, const int64_t* n_resident,
                  int32_t k, int32_t* idx, int32_t* count, void* workspace, void* stream);
 
+/* hca_topk for callers that cannot allocate or pass device scratch memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same result as hca_topk, bit for bit; the scratch memory of
+ * its kernels is a 16 MiB array inside the library's device image (one copy per GPU, held until the process
+ * ends) instead of a workspace.  The call allocates nothing and frees nothing.
+ * Limit: rows * (32 KiB + 8 B * (roundup(n_max, 1024) + 2 * max(4096, roundup(ceil(n_max / 1024), 1024)))) must
+ * not exceed 16 MiB, n_max being the largest n_resident and rows = batch * n_kv_heads - e.g. 8 rows of 131 136
+ * slots, 32 rows of 32 Ki; beyond it: HCA_ERR_CAPACITY (nothing launched).  capacity may be larger than n_max.
+ * All calls on one GPU share that GPU's array: calls that may overlap there (different streams, different
+ * threads) race; calls on one stream are ordered and safe.  Other arguments and errors as hca_topk. */
+int32_t hca_topk_noalloc(const hca_shape* shape, const float* sel, const int64_t* n_resident, int32_t k,
+                         int32_t* idx, int32_t* count, void* stream);
+
 /* Steps 2 and 3a in one call (Eq. 2, then the sorted prefix Pi_k of Sec. 3.2): idx and count exactly as
  * hca_score_qkeys followed by hca_topk would leave them, without the score of every slot ever reaching
  * memory.  A strided sample of each row (8192 to 65536 slots) is scored first and gives a threshold that at least k

@@ -79,6 +79,8 @@ def lib():
         L.hca_score_qkeys.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp]
         L.hca_topk.restype = i32
         L.hca_topk.argtypes = [sp, vp, vp, i32, vp, vp, vp, vp]
+        L.hca_topk_noalloc.restype = i32
+        L.hca_topk_noalloc.argtypes = [sp, vp, vp, i32, vp, vp, vp]
         L.hca_score_topk.restype = i32
         L.hca_score_topk.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.hca_score_topk_report.restype = i32
@@ -213,6 +215,12 @@ def hca_topk(shape, sel, n_resident, k, idx, count, workspace, stream=None):
     nr = _nres(n_resident, shape.batch)
     _check(lib().hca_topk(C.byref(shape), _ptr(sel), nr, int(k), _ptr(idx), _ptr(count), _ptr(workspace),
                           _stream(stream)), "hca_topk")
+
+
+def hca_topk_noalloc(shape, sel, n_resident, k, idx, count, stream=None):
+    nr = _nres(n_resident, shape.batch)
+    _check(lib().hca_topk_noalloc(C.byref(shape), _ptr(sel), nr, int(k), _ptr(idx), _ptr(count), _stream(stream)),
+           "hca_topk_noalloc")
 
 
 def hca_sparse_attend(shape, kcache, q_f16, idx, count, k, pos, v_host, host_stride, n_host_rows, v_hbm,

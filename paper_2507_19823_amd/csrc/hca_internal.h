@@ -86,7 +86,8 @@ size_t score_workspace_bytes(const Layout& L);
 int32_t launch_score_lse(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                          float sm_scale, float* sel, float* lse_out, void* lse_ws, hipStream_t st);
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
-                    int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean = false);
+                    int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean = false,
+                    int64_t list_cap = 0);   // list_cap > 0: candidate lists carved for rows of that many slots
 size_t topk_hist_bytes(int rows);
 // Scan and selection in one: the scan keeps only the (order key, slot) pairs of the slots whose key reaches a
 // per-row threshold estimated from a strided sample of the row, in per-chunk lists (chunk = the slots of one

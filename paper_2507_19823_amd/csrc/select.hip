@@ -1546,7 +1546,7 @@ int32_t launch_topp(const Layout& L, const float* sel, const NRes& nr, int64_t n
 size_t topk_hist_bytes(int rows) { return (size_t)rows * kBins12 * 4; }
 
 int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t nmax, int32_t k,
-                    int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean) {
+                    int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool hist_clean, int64_t list_cap) {
   SelRows sr;
   for (int b = 0; b < kMaxBatch; ++b) { sr.nsel[b] = 0; sr.want[b] = -1; }
   for (int b = 0; b < L.batch; ++b) {
@@ -1555,7 +1555,7 @@ int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t n
     if (sr.want[b] == 0) sr.want[b] = -1;
   }
   TopkWs t;
-  topk_carve(&t, ws, L.rows, L.cap);
+  topk_carve(&t, ws, L.rows, list_cap > 0 ? list_cap : L.cap);
   int64_t chunk;
   int32_t nchunks;
   chunk_geometry(nmax, &chunk, &nchunks);
@@ -1578,4 +1578,68 @@ int32_t launch_topk(const Layout& L, const float* sel, const NRes& nr, int64_t n
   return HCA_OK;
 }
 
+// What hca_topk itself touches of its workspace when the candidate lists are sized for rows of at most
+// `list_cap` slots: everything of topk_carve up to and including the lists.
+static size_t topk_only_bytes(int rows, int64_t list_cap) {
+  size_t b = 0;
+  b += align_up((int64_t)rows * kBins12 * 4, 256);
+  b += align_up((int64_t)rows * kMaxChunks * 4, 256);
+  b += align_up((int64_t)rows * 4 * 4, 256);
+  b += align_up((int64_t)rows * 1024 * 4, 256);
+  b += align_up((int64_t)rows * 1024 * 2 * 4, 256);
+  b += align_up((int64_t)rows * list_entries_per_row(list_cap) * 8, 256);
+  return b;
+}
+
 }  // namespace hca
+
+// ---- hca_topk without a workspace argument --------------------------------------------------------------
+// The scratch memory of the top-k kernels (histogram, per-chunk counts and offsets, candidate lists) as a
+// file-scope device array instead of a caller's workspace, for callers that may not allocate.  Every device the
+// library runs on holds its own copy of the array at its own address; in host code the array's name is only a
+// handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kTopkScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kTopkScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];     // device address of `scratch` on each device, once known
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+int32_t scratch_address(void** out) {
+  int dev = 0;
+  HCA_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return HCA_ERR_UNSUPPORTED;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    HCA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return hca::hip_fail(hipErrorInvalidSymbol);
+    g_scratch_ptr[dev].store(p, std::memory_order_release);      // racing first calls store the same address
+  }
+  *out = p;
+  return HCA_OK;
+}
+}  // namespace
+
+extern "C" int32_t hca_topk_noalloc(const hca_shape* shape, const float* sel, const int64_t* n_resident, int32_t k,
+                                    int32_t* idx, int32_t* count, void* stream) {
+  using namespace hca;
+  Layout L;
+  int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (sel == nullptr || idx == nullptr || count == nullptr) return HCA_ERR_BAD_ARG;
+  if (k < 1 || k > L.cap) return HCA_ERR_CAPACITY;
+  NRes nr;
+  int64_t nmax;
+  rc = load_nres(L, n_resident, &nr, &nmax);
+  if (rc != HCA_OK) return rc;
+  // the lists are sized for the longest resident row, not for the capacity: the limit is on what is scanned
+  const int64_t list_cap = nmax > 0 ? nmax : 1;
+  if (topk_only_bytes(L.rows, list_cap) > kTopkScratchBytes) return HCA_ERR_CAPACITY;
+  void* ws = nullptr;
+  rc = scratch_address(&ws);
+  if (rc != HCA_OK) return rc;
+  // the array keeps the previous call's contents: launch_topk clears the histogram with a fill kernel
+  // (hist_clean = false) and every other region is written before it is read
+  return launch_topk(L, sel, nr, nmax, k, idx, count, ws, (hipStream_t)stream, false, list_cap);
+}
