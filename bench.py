@@ -29,7 +29,8 @@ def log(*a):
 class Model:
     """All layers of one workload: per-layer key cache / acc / pos / host values, shared scratch."""
 
-    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3, evict_spare=False, fused=False):
+    def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3, evict_spare=False, fused=False,
+                 host_chunks=0, host_threads=12, tune=None):
         import torch
         from paper_2507_19823_amd import binding as B
         self.torch, self.B, self.w = torch, B, w
@@ -57,6 +58,7 @@ class Model:
                       for _ in range(layers)]
         # score buffers of the pipeline slots; with the fused scan + top-k a selection workspace per slot instead
         self.fused = fused
+        self.host_chunks, self.host_threads, self.tune = host_chunks, host_threads, dict(tune or {})
         self.gap_report = False
         self.sels = [torch.empty(w.batch, w.n_kv_heads, self.cap, dtype=torch.float32, device=dev)
                      for _ in range(1 if fused else max(3, n_sel))]
@@ -108,6 +110,11 @@ class Model:
             if vh is not None:
                 vh.copy_(d["values"])
                 self.v_host[l] = vh
+                if self.host_chunks:                  # the host threads will read this store at random rows
+                    t0 = time.perf_counter()
+                    torch.cuda.synchronize()
+                    B.hca_host_prefault(vh, 16)
+                    self.prefault_s = getattr(self, "prefault_s", 0.0) + time.perf_counter() - t0
             elif phys_value_layers > 0:
                 self.v_host[l] = self.v_host[l % phys_value_layers]   # logical layer shares a physical store
             if l == 0:
@@ -213,6 +220,9 @@ class Model:
                 d.gather_stamps = self.gstamps.data_ptr()
         if self.evict_spare:
             d.spare_kcache, d.spare_acc, d.spare_pos = (x.data_ptr() for x in self.spare)
+        d.host_chunks, d.host_threads = self.host_chunks, self.host_threads
+        for name, val in self.tune.items():           # this pipeline's own launch-shape knobs
+            setattr(d, name, val)
         self.pl = B.hca_pipeline_create(self.shape, self.L, d, timing_slots)
         self.pl_layers = (B.hca_layer * self.L)()
         for l in range(self.L):
@@ -909,6 +919,10 @@ def main():
     ap.add_argument("--evict-spare", action="store_true",
                     help="native pipeline: evict out of place into a spare buffer set, in slices behind the attends "
                          "(default: in place, which moves only the slots from the first dropped one on)")
+    ap.add_argument("--host-chunks", type=int, default=0,
+                    help="hybrid value side of the native step driver: of every row's selected tokens the first N "
+                         "chunks of 256 are summed by host threads from the value store, the rest gathered (0: all gathered)")
+    ap.add_argument("--host-threads", type=int, default=12, help="worker threads of the hybrid value side")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gap-report", action="store_true",
                     help="log the largest idle times between consecutive scan launches with their step.layer")
@@ -944,9 +958,13 @@ def main():
     from paper_2507_19823_amd import binding as B
     B.lib()
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    tune = {}
     for kv in args.tune:
         name, val = kv.split("=")
-        B.hca_tune(name, int(val))
+        if args.pipeline == "native" and args.mode == "step" and name != "host_spin_us":
+            tune[name] = int(val)                     # the step driver takes its knobs from its own descriptor
+        else:
+            B.hca_tune(name, int(val))
 
     w = S.CONFIGS[args.config]
     # a 32 Ki-token layer (20 MiB of codes) would sit in the last-level cache if it were scanned over and over:
@@ -1022,7 +1040,8 @@ def main():
     total_steps = args.steps + args.warmup
     fused = args.pipeline == "native" and not args.no_fused_select
     model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers), evict_spare=args.evict_spare,
-                  fused=fused)
+                  fused=fused, host_chunks=args.host_chunks if args.pipeline == "native" else 0,
+                  host_threads=args.host_threads, tune=tune)
     layer_v_gib = w.batch * w.n_kv_heads * w.n * 256 / 2 ** 30
     phys = max(1, min(L, int(args.host_gib / layer_v_gib)))
     t0 = time.perf_counter()
@@ -1067,6 +1086,12 @@ def main():
     log(f"timed region done: {dt:.3f}s for {args.steps} steps (host enqueue {host_dt:.3f}s; per step ms: "
         + " ".join(f"{x:.2f}" for x in host_steps) + ")")
     ms_per_step = dt * 1e3 / args.steps
+    host_side = None
+    if args.pipeline == "native" and model.host_chunks:
+        to, bad = B.hca_pipeline_host_status(model.pl)
+        ju, tu = B.hca_pipeline_host_times(model.pl)
+        host_side = {"wait_timeouts": to, "bad_rows": bad, "host_us_per_layer": ju, "host_us_per_chunk": tu}
+        log(f"hybrid value side: host threads {ju:.1f} us per layer, {tu:.1f} us per chunk; timeouts {to}, bad rows {bad}")
     tokens_per_step = w.batch * w.n * L
     value = tokens_per_step / (dt / args.steps)
     bracket_ms = None
@@ -1120,6 +1145,9 @@ def main():
                    "kv_heads": w.n_kv_heads, "key_bits": w.bits, "group": w.group, "top_k": w.k,
                    "evict_every": args.evict_every, "values": "context rows in pinned host fp16, appended rows in an HBM slice",
                    "physical_value_layers": phys, "pipeline": args.pipeline,
+                   "value_side": (f"hybrid: {model.host_chunks} of {-(-w.k // 256)} chunks of 256 selected tokens per row "
+                                  f"summed by {model.host_threads} host threads from the value store, the rest gathered"
+                                  if model.host_chunks else "all selected rows gathered over the host link"),
                    "selection": "hca_score_topk (scan + top-k fused)" if fused else "hca_score_qkeys + hca_topk"},
         "pipelined_ms_per_layer": ms_per_step / L,
         "per_layer_decode_latency": latency,

@@ -63,8 +63,9 @@ typedef struct {
 /* Library version string (static storage). */
 const char* hca_version(void);
 
-/* Overrides a launch-shape knob (process-wide; for tuning and profiling, not needed for
- * correct results).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth",
+/* Overrides a launch-shape knob for the per-call entry points (process-wide state, meant for tuning and
+ * profiling sessions, not needed for correct results; a step driver takes its knobs from its own
+ * hca_pipeline_desc instead and only starts from these).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth",
  * "host_spin_us" (how long the worker threads of hca_host_weighted_sum poll for the next
  * call before they sleep; default 100, 0 = sleep at once).
  * Returns HCA_ERR_BAD_ARG for an unknown name. */
@@ -275,6 +276,22 @@ typedef struct {
      zero-filled by the caller; every workgroup of a timed gather launch (at most 1024) stores its start and end
      wall-clock tick.  NULL: off. */
   void* gather_stamps;
+  /* Hybrid value side (Sec. 3.2 "CPU part", Eq. 5 for a share of the selection; uniform codes only).
+     host_chunks > 0: of every row's selected tokens (ascending slot order, chunks of 256) the first host_chunks
+     chunks are not gathered over the host link; the GPU sends, per token, its value-row number and one fp32
+     weight per query head (relative to the chunk's maximum) to pinned memory, host threads of the driver form
+     the chunk's partial sums from the value store where it lives, and the GPU merges them with the partial sums
+     of the gathered chunks under the one softmax normaliser.  Selection, accumulated scores and eviction are
+     unaffected; y differs from the all-gather form by fp32 summation order only.  Tokens of those chunks whose
+     value row is not in the host store (rows >= n_host_rows) are summed on the GPU.
+     host_threads: worker threads (1 .. 64; they poll while steps are in flight and sleep when idle; 0 starts
+     none - then every merge times out, for tests of that path).  host_spin_limit: polls of the host's flag
+     before a merge gives up and records a timeout (0: about a second); see hca_pipeline_host_status.
+     The driver owns the pinned exchange buffers (about 1.3 KiB per selected token of the host share, four
+     sets) and the threads from hca_pipeline_create to hca_pipeline_destroy. */
+  int32_t host_chunks, host_threads, host_spin_limit;
+  /* Launch-shape knobs of this pipeline's kernels (0: the library's default; ranges as in hca_tune). */
+  int32_t gather_wgs, gather_unroll, score_bpw, score_depth;
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;
@@ -299,6 +316,19 @@ void hca_pipeline_destroy(hca_pipeline* p);
 int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_resident, int64_t value_row0, int32_t k,
                           int64_t host_stride, int64_t n_host_rows, int64_t hbm_stride, float sm_scale,
                           const int64_t* evict_M, int64_t n_protect, int32_t timing_slot);
+
+/* Hybrid value side: *wait_timeouts != 0 if a merge ever gave up waiting for the host threads (its y is then
+ * wrong), *bad_rows = value-row numbers outside the host store that the host threads were handed (skipped).
+ * Both stay 0 in a correct run.  *mean_job_us: mean time the host threads took per layer, from the GPU's signal
+ * to the last chunk's partial sum; *mean_chunk_us: mean time per chunk of 256 tokens.  Any pointer may be NULL. */
+int32_t hca_pipeline_host_status(hca_pipeline* p, uint32_t* wait_timeouts, uint32_t* bad_rows, double* mean_job_us,
+                                 double* mean_chunk_us);
+
+/* Host code, blocks until done: reads one byte of every 4 KiB page of [ptr, ptr + bytes) with n_threads threads
+ * (1 .. 64).  For a pinned value store that the hybrid value side's host threads (or hca_host_weighted_sum) will
+ * read: the first CPU access to a page of a pinned allocation is a page fault of several microseconds, which
+ * would otherwise be paid inside the first decode steps, once per selected row. */
+int32_t hca_host_prefault(const void* ptr, size_t bytes, int32_t n_threads);
 
 /* (start, end) pairs a key-scan launch over n_tokens resident tokens may write into scan_stamps. */
 int64_t hca_scan_stamp_pairs(const hca_shape* shape, int64_t n_tokens);

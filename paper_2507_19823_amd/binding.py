@@ -47,7 +47,10 @@ class hca_pipeline_desc(C.Structure):
                 ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64),
                 ("timing_layer_stride", C.c_int32), ("vq_groups", C.c_int32), ("vq_codewords", C.c_int32),
                 ("topp_tau", C.c_double), ("fused_select", C.c_int32),
-                ("ws_select", C.c_void_p * PIPELINE_MAX_SEL), ("gather_stamps", C.c_void_p)]
+                ("ws_select", C.c_void_p * PIPELINE_MAX_SEL), ("gather_stamps", C.c_void_p),
+                ("host_chunks", C.c_int32), ("host_threads", C.c_int32), ("host_spin_limit", C.c_int32),
+                ("gather_wgs", C.c_int32), ("gather_unroll", C.c_int32), ("score_bpw", C.c_int32),
+                ("score_depth", C.c_int32)]
 
 
 class hca_vq_codebook(C.Structure):
@@ -111,6 +114,11 @@ def lib():
         L.hca_pipeline_step.restype = i32
         L.hca_pipeline_step.argtypes = [vp, C.POINTER(hca_layer), C.POINTER(i64), i64, i32, i64, i64, i64, f32,
                                         C.POINTER(i64), i64, i32]
+        L.hca_pipeline_host_status.restype = i32
+        L.hca_pipeline_host_status.argtypes = [vp, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
+                                               C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.hca_host_prefault.restype = i32
+        L.hca_host_prefault.argtypes = [vp, C.c_size_t, i32]
         L.hca_scan_stamp_pairs.restype = i64
         L.hca_scan_stamp_pairs.argtypes = [sp, i64]
         L.hca_wall_clock_khz.restype = i32
@@ -284,6 +292,25 @@ def hca_pipeline_scan_ms(handle, timing_slot, n_layers):
     out = (C.c_float * n_layers)()
     _check(lib().hca_pipeline_scan_ms(handle, int(timing_slot), out), "hca_pipeline_scan_ms")
     return list(out)
+
+
+def hca_pipeline_host_status(handle):
+    """(wait_timeouts, bad_rows) of the hybrid value side; both 0 in a correct run."""
+    a, b = C.c_uint32(0), C.c_uint32(0)
+    _check(lib().hca_pipeline_host_status(handle, C.byref(a), C.byref(b), None, None), "hca_pipeline_host_status")
+    return int(a.value), int(b.value)
+
+
+def hca_pipeline_host_times(handle):
+    """(mean microseconds per layer, mean microseconds per chunk) of the hybrid value side's host threads."""
+    ju, tu = C.c_double(0), C.c_double(0)
+    _check(lib().hca_pipeline_host_status(handle, None, None, C.byref(ju), C.byref(tu)), "hca_pipeline_host_status")
+    return float(ju.value), float(tu.value)
+
+
+def hca_host_prefault(t, n_threads=16):
+    """Walks a pinned tensor once on the CPU so that later random reads of it do not page-fault."""
+    _check(lib().hca_host_prefault(_ptr(t), t.numel() * t.element_size(), int(n_threads)), "hca_host_prefault")
 
 
 def hca_scan_stamp_pairs(shape, n_tokens):

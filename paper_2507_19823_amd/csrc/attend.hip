@@ -4,7 +4,7 @@
 
 namespace hca {
 
-constexpr int kChunk = 256;  // selected tokens per workgroup of the partial kernel
+constexpr int kChunk = kAttendChunk;  // selected tokens per workgroup of the partial kernel
 
 struct AttendWs {
   uint16_t* vstage;  // [rows][k][128] fp16
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__
                                                      const uint4* __restrict__ v_host, int64_t host_stride,
                                                      int64_t n_host_rows, const uint4* __restrict__ v_hbm,
                                                      int64_t hbm_stride, uint4* __restrict__ vstage,
-                                                     int wgs, uint64_t* __restrict__ stamps) {
+                                                     int wgs, uint64_t* __restrict__ stamps, int first) {
   const int row = blockIdx.y, wg = blockIdx.x;
   // optional profiling: every workgroup leaves its start and end time (constant-rate wall clock)
   uint64_t* stamp = stamps ? stamps + ((int64_t)row * wgs + wg) * 2 : nullptr;
@@ -53,7 +53,8 @@ __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__
   const int cnt = count[row];
   const int part = threadIdx.x & 15;
   const int64_t step = (int64_t)wgs * 16;                 // value rows per sweep of the row's workgroups
-  for (int64_t i0 = (int64_t)wg * 16 + (threadIdx.x >> 4); i0 < cnt; i0 += step * UNROLL) {
+  // entries below `first` are not fetched (their values are summed where they live, on the host)
+  for (int64_t i0 = (int64_t)first + (int64_t)wg * 16 + (threadIdx.x >> 4); i0 < cnt; i0 += step * UNROLL) {
     uint4 v[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
@@ -189,14 +190,13 @@ __device__ __forceinline__ void partial_softmax_sum(PartialShared& ps, const Att
 }
 
 template <int BITS, bool VALUES = true>
-__global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* __restrict__ kcache,
-                                                      const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
-                                                      const int32_t* __restrict__ count, int32_t k, float sm_scale,
-                                                      AttendWs a, int nsplit) {
-  __shared__ QShared sh;
-  __shared__ PartialShared ps;
+__device__ __forceinline__ bool attend_partial_body(PartialShared& ps, QShared& sh, const Layout& L,
+                                                    const uint8_t* __restrict__ kcache, const uint16_t* __restrict__ q,
+                                                    const int32_t* __restrict__ idx, const int32_t* __restrict__ count,
+                                                    int32_t k, float sm_scale, const AttendWs& a, int nsplit,
+                                                    const int split) {
   auto& lg = ps.lg;
-  const int row = blockIdx.y, split = blockIdx.x;
+  const int row = blockIdx.y;
   const int cnt = count[row];
   const int i0 = split * kChunk;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -205,7 +205,7 @@ __global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* _
   float* py = a.py + (((int64_t)row * nsplit + split) * 4) * kHeadDim;
   if (i0 >= cnt) {  // empty chunk: neutral partial
     partial_empty(pmz, py);
-    return;
+    return false;
   }
   const int nvalid = (cnt - i0 < kChunk) ? cnt - i0 : kChunk;
   load_query(q, row, L.gqa, L.group, &sh);
@@ -254,6 +254,86 @@ __global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* _
   __syncthreads();
 
   partial_softmax_sum<VALUES>(ps, a, row, i0, nvalid, k, pmz, py);
+  return true;
+}
+
+// split0: the first chunk of the launch (chunks below it belong to the host share)
+template <int BITS, bool VALUES = true>
+__global__ __launch_bounds__(256) void attend_partial(Layout L, const uint8_t* __restrict__ kcache,
+                                                      const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
+                                                      const int32_t* __restrict__ count, int32_t k, float sm_scale,
+                                                      AttendWs a, int nsplit, int split0) {
+  __shared__ QShared sh;
+  __shared__ PartialShared ps;
+  attend_partial_body<BITS, VALUES>(ps, sh, L, kcache, q, idx, count, k, sm_scale, a, nsplit, (int)blockIdx.x + split0);
+}
+
+// The chunks of the host share: logits, chunk (max, sum) and stored logits as for any chunk (the merge and the
+// accumulated scores need them), no value rows; instead every entry's exp(logit - chunk max) per head and its
+// value-row number go to pinned host memory.  An entry whose value row is not in the host store (rows >=
+// n_host_rows live in the HBM slice: the newest tokens) is summed here, into the chunk's device-side partial,
+// and is handed to the host as "nothing to add".
+template <int BITS>
+__global__ __launch_bounds__(256) void attend_host_chunks(Layout L, const uint8_t* __restrict__ kcache,
+                                                          const uint16_t* __restrict__ q, const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ count, int32_t k,
+                                                          const int32_t* __restrict__ pos, int64_t n_host_rows,
+                                                          const uint16_t* __restrict__ v_hbm, int64_t hbm_stride,
+                                                          float sm_scale, AttendWs a, int nsplit, HostShare hs) {
+  __shared__ QShared sh;
+  __shared__ PartialShared ps;
+  __shared__ int32_t vr[kChunk];
+  __shared__ int n_dev;
+  const int row = blockIdx.y, split = blockIdx.x;
+  const int tid = threadIdx.x;
+  float* out_p = hs.p + ((int64_t)row * hs.chunks + split) * 4 * kChunk;
+  int32_t* out_v = hs.vrow + ((int64_t)row * hs.chunks + split) * kChunk;
+  float* py = a.py + (((int64_t)row * nsplit + split) * 4) * kHeadDim;
+  if (tid == 0) n_dev = 0;
+  const bool live_chunk = attend_partial_body<BITS, false>(ps, sh, L, kcache, q, idx, count, k, sm_scale, a, nsplit, split);
+  if (!live_chunk) {                  // nothing selected here: partial_empty has written the neutral partial
+    out_v[tid] = -1;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) out_p[h * kChunk + tid] = 0.f;
+    return;
+  }
+  // ps.lg now holds exp(logit - chunk max) of the chunk's live entries
+  const int cnt = count[row];
+  const int i0 = split * kChunk;
+  const int nvalid = (cnt - i0 < kChunk) ? cnt - i0 : kChunk;
+  int32_t r = -1;
+  bool on_dev = false;
+  if (tid < nvalid) {
+    const int32_t slot = idx[(int64_t)row * k + i0 + tid];
+    const int32_t v = pos[(int64_t)row * L.cap + slot];
+    on_dev = v >= n_host_rows;
+    r = on_dev ? -1 : v;
+    vr[tid] = on_dev ? (int32_t)(v - n_host_rows) : -1;
+    if (on_dev) atomicAdd(&n_dev, 1);
+  } else {
+    vr[tid] = -1;
+  }
+  out_v[tid] = r;
+#pragma unroll
+  for (int h = 0; h < 4; ++h) out_p[h * kChunk + tid] = (tid < nvalid && h < L.gqa) ? ps.lg[h][tid] : 0.f;
+  __syncthreads();
+  // device-side partial of the chunk: the entries that the host cannot reach (usually none)
+  for (int c = tid; c < 4 * kHeadDim; c += 256) {
+    const int h = c >> 7, d = c & 127;
+    float s = 0.f;
+    if (n_dev > 0 && h < L.gqa) {
+      for (int i = 0; i < nvalid; ++i) {
+        const int32_t x = vr[i];
+        if (x >= 0) s = fmaf(ps.lg[h][i], h2f(v_hbm[((int64_t)row * hbm_stride + x) * kHeadDim + d]), s);
+      }
+    }
+    py[c] = s;
+  }
+}
+
+// Tells the host that everything enqueued before it on the stream is in place.
+__global__ void host_signal(uint32_t* gpu_seq, uint32_t seq) {
+  if (threadIdx.x == 0) __hip_atomic_store(gpu_seq, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
 // Table entry of one (group, centroid): the G query heads of the KV head, adjacent in memory.
@@ -341,7 +421,7 @@ __global__ __launch_bounds__(256) void vq_attend_partial(int g, int c, int64_t c
 __global__ __launch_bounds__(256) void attend_merge(Layout L, const int32_t* __restrict__ idx,
                                                     const int32_t* __restrict__ count, int32_t k, AttendWs a,
                                                     int nsplit, float* __restrict__ y, float* __restrict__ acc,
-                                                    const float* __restrict__ lse) {
+                                                    const float* __restrict__ lse, HostShare hs) {
   __shared__ float fm[4], fz[4];
   __shared__ float wgt[4][64];  // nsplit <= 64
   __shared__ float pm[64][4], pz[64][4];
@@ -372,11 +452,36 @@ __global__ __launch_bounds__(256) void attend_merge(Layout L, const int32_t* __r
   }
   __syncthreads();
   if (blockIdx.x == 0) {
+    if (hs.chunks > 0) {
+      // the host's partial sums of this row: wait, a bounded number of polls, until the host has stored this
+      // step's sequence number (it never stores an older one afterwards)
+      if (threadIdx.x == 0) {
+        int polls = 0;
+        while ((int32_t)(__hip_atomic_load(hs.host_seq + row, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) - hs.seq) < 0) {
+          if (++polls >= hs.spin_limit) {
+            __hip_atomic_store(hs.err, hs.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            break;
+          }
+          __builtin_amdgcn_s_sleep(20);
+        }
+      }
+      __syncthreads();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "");       // nothing read below may come from before the flag
+    }
     for (int c = threadIdx.x; c < L.gqa * kHeadDim; c += 256) {
       const int h = c >> 7, d = c & 127;
       float s = 0.f;
+      // chunks of the host share: device-side partial (entries the host cannot reach) + the host's partial
+      for (int sp = 0; sp < hs.chunks && sp < nsplit; ++sp) {
+        const float e = wgt[h][sp];
+        if (e != 0.f) {
+          const float v = a.py[((int64_t)row * nsplit * 4 + sp * 4 + h) * kHeadDim + d] +
+                          __builtin_nontemporal_load(&hs.py[(((int64_t)row * hs.chunks + sp) * 4 + h) * kHeadDim + d]);
+          s = fmaf(e, v, s);
+        }
+      }
       const float* src = a.py + ((int64_t)row * nsplit * 4 + h) * kHeadDim + d;
-      for (int s0 = 0; s0 < nsplit; s0 += 16) {      // 16 independent loads per batch
+      for (int s0 = hs.chunks; s0 < nsplit; s0 += 16) {      // 16 independent loads per batch
         float v[16];
 #pragma unroll
         for (int x = 0; x < 16; ++x) v[x] = (s0 + x < nsplit) ? src[(int64_t)(s0 + x) * 4 * kHeadDim] : 0.f;
@@ -417,10 +522,11 @@ static hipEvent_t next_event(hipError_t* err) {
 
 int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
                       const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
-                      int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps) {
+                      int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps, int first_entry,
+                      const Tuning* tune) {
   AttendWs a;
   carve(&a, ws, L, k);
-  const Tuning& tn = tuning();
+  const Tuning& tn = tune != nullptr ? *tune : tuning();
   int64_t wgs = ((int64_t)k + 15) / 16;                  // one workgroup per 16 rows at most
   // per (sequence, KV head).  About 64 workgroups in total keep enough reads in flight to fill the host
   // link; more only take queue entries in the memory system away from the HBM-bound kernels beside it.
@@ -431,7 +537,7 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
   const uint4 *vh = (const uint4*)v_host, *vd = (const uint4*)v_hbm;
 #define HCA_GATHER(U)                                                                                              \
   gather_values<U><<<g, 256, 0, st>>>(idx, count, k, pos, L.cap, vh, host_stride, n_host_rows, vd, hbm_stride, \
-                                      (uint4*)a.vstage, (int)wgs, stamps)
+                                      (uint4*)a.vstage, (int)wgs, stamps, first_entry)
   if (tn.gather_unroll >= 4) HCA_GATHER(4);
   else if (tn.gather_unroll >= 2) HCA_GATHER(2);
   else HCA_GATHER(1);
@@ -442,18 +548,53 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
 
 int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
-                               void* ws, hipStream_t st, const float* lse) {
+                               void* ws, hipStream_t st, const float* lse, const HostShare* hs) {
   AttendWs a;
   carve(&a, ws, L, k);
   const int ns = nsplit_of(k);
   if (ns > 64) return HCA_ERR_CAPACITY;
-  dim3 gp((unsigned)ns, (unsigned)L.rows);
-  if (L.bits == 4)
-    attend_partial<4><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
-  else
-    attend_partial<2><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
+  HostShare h0;
+  if (hs != nullptr) h0 = *hs;
+  if (h0.chunks > ns) h0.chunks = ns;
+  if (ns - h0.chunks > 0) {            // the chunks whose value rows the gather has staged
+    dim3 gp((unsigned)(ns - h0.chunks), (unsigned)L.rows);
+    if (L.bits == 4)
+      attend_partial<4><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns,
+                                            h0.chunks);
+    else
+      attend_partial<2><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns,
+                                            h0.chunks);
+  }
   dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
-  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, lse);
+  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, lse, h0);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int host_share_chunks(int32_t k, int want) {
+  const int ns = nsplit_of(k);
+  return want < 0 ? 0 : (want > ns ? ns : want);
+}
+size_t host_share_p_bytes(const Layout& L, int chunks) { return (size_t)L.rows * chunks * 4 * kChunk * sizeof(float); }
+size_t host_share_vrow_bytes(const Layout& L, int chunks) { return (size_t)L.rows * chunks * kChunk * sizeof(int32_t); }
+size_t host_share_py_bytes(const Layout& L, int chunks) { return (size_t)L.rows * chunks * 4 * kHeadDim * sizeof(float); }
+
+int32_t launch_attend_host_chunks(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                                  const int32_t* count, int32_t k, const int32_t* pos, int64_t n_host_rows,
+                                  const void* v_hbm, int64_t hbm_stride, float sm_scale, void* ws, const HostShare& hs,
+                                  hipStream_t st) {
+  AttendWs a;
+  carve(&a, ws, L, k);
+  const int ns = nsplit_of(k);
+  if (ns > 64 || hs.chunks < 1 || hs.chunks > ns) return HCA_ERR_CAPACITY;
+  dim3 gp((unsigned)hs.chunks, (unsigned)L.rows);
+  if (L.bits == 4)
+    attend_host_chunks<4><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, pos,
+                                              n_host_rows, (const uint16_t*)v_hbm, hbm_stride, sm_scale, a, ns, hs);
+  else
+    attend_host_chunks<2><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, pos,
+                                              n_host_rows, (const uint16_t*)v_hbm, hbm_stride, sm_scale, a, ns, hs);
+  host_signal<<<1, 64, 0, st>>>(hs.gpu_seq, hs.seq);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -476,7 +617,7 @@ int32_t launch_vq_attend_gathered(const Layout& L, int g, int c, const uint8_t* 
   else HCA_VQ_PARTIAL(1);
 #undef HCA_VQ_PARTIAL
   dim3 gm((unsigned)(1 + (acc_opt ? ns : 0)), (unsigned)L.rows);
-  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, nullptr);
+  attend_merge<<<gm, 256, 0, st>>>(L, idx, count, k, a, ns, y, acc_opt, nullptr, HostShare{});
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -537,9 +678,9 @@ int32_t launch_attend_weights(const Layout& L, const void* kcache, const void* q
   if (ns > 64) return HCA_ERR_CAPACITY;
   dim3 gp((unsigned)ns, (unsigned)L.rows);
   if (L.bits == 4)
-    attend_partial<4, false><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
+    attend_partial<4, false><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns, 0);
   else
-    attend_partial<2, false><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns);
+    attend_partial<2, false><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, sm_scale, a, ns, 0);
   weights_finalize<<<gp, 256, 0, st>>>(L, idx, count, k, pos, a, ns, lse, (uint16_t*)w_out, vrow_out, acc_opt);
   HCA_HIP(hipGetLastError());
   return HCA_OK;

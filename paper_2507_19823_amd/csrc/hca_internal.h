@@ -80,7 +80,7 @@ int32_t launch_quantize(const Layout& L, void* kcache, const void* k_new, int64_
 int32_t launch_export(const Layout& L, const void* kcache, const NRes& nr, uint8_t* codes, void* scale,
                       void* zero, hipStream_t st);
 int32_t launch_score(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                     float* sel, float* z_opt, hipStream_t st, uint64_t* stamps = nullptr);
+                     float* sel, float* z_opt, hipStream_t st, uint64_t* stamps = nullptr, const Tuning* tn = nullptr);
 int64_t score_stamp_pairs(const Layout& L, int64_t nmax);
 size_t score_workspace_bytes(const Layout& L);
 int32_t launch_score_lse(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
@@ -158,14 +158,45 @@ int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const 
                       const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,
                       int64_t host_stride, int64_t n_host_rows, const void* v_hbm, int64_t hbm_stride,
                       float sm_scale, float* y, float* acc_opt, void* ws, hipStream_t gst, hipStream_t st);
+// first_entry: selected entries below it are left out (the host share of the value side sums them in place)
 int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
                       const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
-                      int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps = nullptr);
+                      int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps = nullptr, int first_entry = 0,
+                      const Tuning* tn = nullptr);     // tn: launch-shape knobs (null: the process-wide ones)
 // (start, end) pairs a gather launch writes into `stamps` at most
 constexpr int kGatherStampPairs = 1024;
+constexpr int kAttendChunk = 256;   // selected tokens per chunk of the attend kernels
+// Host share of the value side (Sec. 3.2 "CPU part", Eq. 5): the first `chunks` chunks of every row's selected
+// tokens are summed on the host, where their value rows live; per token only exp(logit - chunk max) for each
+// query head and the value-row number cross the link, and one partial sum per chunk and head comes back.
+// All pointers are pinned host memory that the kernels read and write in place.
+struct HostShare {
+  int chunks = 0;                   // 0: off
+  float* p = nullptr;               // [rows][chunks][4][kAttendChunk] weights relative to the chunk's maximum
+  int32_t* vrow = nullptr;          // [rows][chunks][kAttendChunk] value row, -1: nothing to add for this entry
+  const float* py = nullptr;        // [rows][chunks][4][kHeadDim] the host's partial sums
+  const uint32_t* host_seq = nullptr;  // [rows]: the host stores `seq` here once the row's sums are in place
+  uint32_t* gpu_seq = nullptr;      // [1]: `seq` once p / vrow are in place
+  uint32_t* err = nullptr;          // [1]: set when a wait for the host ran out
+  uint32_t seq = 0;
+  int spin_limit = 0;               // polls of host_seq before the merge gives up
+};
+
+int host_share_chunks(int32_t k, int want);          // `want` clipped to the chunks k selected tokens make
+size_t host_share_p_bytes(const Layout& L, int chunks);
+size_t host_share_vrow_bytes(const Layout& L, int chunks);
+size_t host_share_py_bytes(const Layout& L, int chunks);
+// logits, chunk partials and the host's inputs of the first hs.chunks chunks of every row, then the signal
+int32_t launch_attend_host_chunks(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
+                                  const int32_t* count, int32_t k, const int32_t* pos, int64_t n_host_rows,
+                                  const void* v_hbm, int64_t hbm_stride, float sm_scale, void* ws, const HostShare& hs,
+                                  hipStream_t st);
+// host code (hostsum.hip): py[h][c] = sum over the chunk's entries with vrow >= 0 of p[h][i] * V[vrow[i]][c],
+// h < G; entries with vrow >= n_rows are skipped and counted in the return value
+int host_chunk_sum(int G, const float* p, const int32_t* vrow, const uint16_t* v_row0, int64_t n_rows, float* py);
 int32_t launch_attend_gathered(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                const int32_t* count, int32_t k, float sm_scale, float* y, float* acc_opt,
-                               void* ws, hipStream_t st, const float* lse = nullptr);
+                               void* ws, hipStream_t st, const float* lse = nullptr, const HostShare* hs = nullptr);
 int32_t launch_attend_weights(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                               const int32_t* count, int32_t k, const int32_t* pos, float sm_scale, const float* lse,
                               void* w_out, int32_t* vrow_out, float* acc_opt, void* ws, hipStream_t st);

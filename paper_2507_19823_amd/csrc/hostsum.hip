@@ -6,6 +6,7 @@
 
 #include <atomic>
 #include <chrono>
+#include <cmath>
 #include <condition_variable>
 #include <cstring>
 #include <functional>
@@ -76,6 +77,54 @@ constexpr auto sum_range = sum_range_avx2;
 #else
 constexpr auto sum_range = sum_range_plain;
 #endif
+
+// One chunk of the host share of a decode step (the step driver's worker threads call this): fp32 weights
+// p[h][i] (relative to the chunk's maximum; the GPU merges the chunks), value rows read where they live.
+int host_chunk_sum(int G, const float* p, const int32_t* vrow, const uint16_t* v_row0, int64_t n_rows, float* py) {
+  alignas(64) float acc[4 * kHeadDim];
+  std::memset(acc, 0, sizeof(acc));
+  int bad = 0;
+#if defined(__AVX2__) && defined(__FMA__) && defined(__F16C__)
+  constexpr int kAhead = 8;
+  for (int i = 0; i < kAttendChunk; ++i) {
+    const int32_t r = vrow[i];
+    if (i + kAhead < kAttendChunk) {
+      const int32_t rn = vrow[i + kAhead];
+      if (rn >= 0 && rn < n_rows) {
+        const char* nx = reinterpret_cast<const char*>(v_row0 + (int64_t)rn * kHeadDim);
+        _mm_prefetch(nx, _MM_HINT_T0);
+        _mm_prefetch(nx + 64, _MM_HINT_T0);
+        _mm_prefetch(nx + 128, _MM_HINT_T0);
+        _mm_prefetch(nx + 192, _MM_HINT_T0);
+      }
+    }
+    if (r < 0) continue;
+    if (r >= n_rows) { ++bad; continue; }
+    const __m128i* v = reinterpret_cast<const __m128i*>(v_row0 + (int64_t)r * kHeadDim);
+    __m256 vf[kHeadDim / 8];
+    for (int c = 0; c < kHeadDim / 8; ++c) vf[c] = _mm256_cvtph_ps(_mm_loadu_si128(v + c));
+    for (int h = 0; h < G; ++h) {
+      const __m256 wh = _mm256_set1_ps(p[h * kAttendChunk + i]);
+      float* y = acc + h * kHeadDim;
+      for (int c = 0; c < kHeadDim / 8; ++c)
+        _mm256_store_ps(y + 8 * c, _mm256_fmadd_ps(wh, vf[c], _mm256_load_ps(y + 8 * c)));
+    }
+  }
+#else
+  for (int i = 0; i < kAttendChunk; ++i) {
+    const int32_t r = vrow[i];
+    if (r < 0) continue;
+    if (r >= n_rows) { ++bad; continue; }
+    const _Float16* v = reinterpret_cast<const _Float16*>(v_row0) + (int64_t)r * kHeadDim;
+    for (int h = 0; h < G; ++h) {
+      const float wh = p[h * kAttendChunk + i];
+      for (int c = 0; c < kHeadDim; ++c) acc[h * kHeadDim + c] = fmaf(wh, (float)v[c], acc[h * kHeadDim + c]);
+    }
+  }
+#endif
+  std::memcpy(py, acc, sizeof(float) * 4 * kHeadDim);
+  return bad;
+}
 
 // Worker threads that outlive the call: starting sixteen threads costs more than the sum they are started for.
 // One job at a time (callers are serialised); the calling thread works along and the call ends when the last
@@ -222,3 +271,31 @@ extern "C" int32_t hca_host_weighted_sum(const hca_shape* shape, const int32_t* 
     }
   return HCA_OK;
 }
+
+// The first CPU access to each 4 KiB page of a pinned allocation is a page fault (the pages exist and are
+// pinned, but the CPU's own mapping of them is made on demand; microseconds each, and the handlers of several
+// threads serialise).  A value store that host threads will read at random rows is therefore walked once,
+// one byte per page, before the first decode step.
+extern "C" int32_t hca_host_prefault(const void* ptr, size_t bytes, int32_t n_threads) {
+  if (ptr == nullptr && bytes != 0) return HCA_ERR_BAD_ARG;
+  if (n_threads < 1) n_threads = 1;
+  if (n_threads > 64) n_threads = 64;
+  constexpr size_t kPage = 4096;
+  const size_t pages = (bytes + kPage - 1) / kPage;
+  const unsigned char* base = (const unsigned char*)ptr;
+  auto walk = [&](size_t p0, size_t p1) {
+    unsigned sum = 0;
+    for (size_t p = p0; p < p1; ++p) sum += *(const volatile unsigned char*)(base + p * kPage);
+    (void)sum;
+  };
+  std::vector<std::thread> th;
+  const size_t per = (pages + n_threads - 1) / n_threads;
+  for (int t = 1; t < n_threads; ++t) {
+    const size_t p0 = per * t, p1 = p0 + per < pages ? p0 + per : pages;
+    if (p0 < p1) th.emplace_back(walk, p0, p1);
+  }
+  walk(0, per < pages ? per : pages);
+  for (auto& t : th) t.join();
+  return HCA_OK;
+}
+

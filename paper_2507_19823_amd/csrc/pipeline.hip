@@ -2,9 +2,227 @@
 // (append + key scan | top-k | host-link gather | attend + eviction), one HIP stream per stage,
 // stages of a layer chained by events.  Pure enqueue logic around the launchers of the other
 // translation units; nothing here touches data.
+#include <immintrin.h>
+
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <cstring>
+#include <memory>
+#include <mutex>
+#include <thread>
 #include <vector>
 
 #include "hca_internal.h"
+
+namespace hca {
+
+// Host half of the hybrid value side (Sec. 3.2 "CPU part", Eq. 5): worker threads that, layer after layer, wait
+// for the GPU's signal that a layer's weights and value-row numbers are in pinned memory, sum the host share's
+// chunks from the value store where it lives, and store the step's sequence number per row for the GPU's merge
+// to see.  Jobs are taken strictly in the order the step driver publishes them; every worker walks through
+// every job (claiming whatever chunks are still unclaimed), so no queue is ever reordered.
+class HostSide {
+ public:
+  static constexpr int kSlots = 4, kRing = 1024;
+  struct Job {
+    uint32_t seq = 0;
+    int slot = 0, chunks = 0;         // chunks per row of this job (<= the pipeline's host_chunks: k may be small)
+    const uint16_t* v_host = nullptr;
+    int64_t host_stride = 0, n_host_rows = 0;
+    std::atomic<int> next_task{0};
+    std::atomic<int> tasks_left{0};
+    std::atomic<int64_t> t_first{0};  // when the first worker saw the GPU's signal (ns, steady clock)
+    std::atomic<int> row_left[kMaxBatch * 8];
+  };
+
+  HostSide(const Layout& L, int chunks, int threads) : L_(L), chunks_(chunks), nthreads_(threads) {}
+  ~HostSide() { stop(); release(); }
+
+  // pinned control and exchange buffers (one set per pipeline slot), then the threads
+  int32_t start() {
+    if (L_.rows > kMaxBatch * 8) return HCA_ERR_UNSUPPORTED;
+    const size_t pb = host_share_p_bytes(L_, chunks_), vb = host_share_vrow_bytes(L_, chunks_),
+                 yb = host_share_py_bytes(L_, chunks_);
+    for (int s = 0; s < kSlots; ++s) {
+      HCA_HIP(hipHostMalloc((void**)&p_[s], pb, hipHostMallocCoherent));
+      HCA_HIP(hipHostMalloc((void**)&vrow_[s], vb, hipHostMallocCoherent));
+      HCA_HIP(hipHostMalloc((void**)&py_[s], yb, hipHostMallocCoherent));
+      std::memset(py_[s], 0, yb);
+    }
+    // flags: one cache line each, so that the GPU's store to one never touches a line the host is writing
+    HCA_HIP(hipHostMalloc((void**)&flags_, kFlagBytes, hipHostMallocCoherent));
+    std::memset(flags_, 0, kFlagBytes);
+    jobs_.reset(new Job[kRing]);
+    progress_.reset(new std::atomic<uint32_t>[nthreads_ > 0 ? nthreads_ : 1]);
+    for (int t = 0; t < nthreads_; ++t) progress_[t].store(1, std::memory_order_relaxed);
+    for (int t = 0; t < nthreads_; ++t) threads_.emplace_back([this, t] { loop(t); });
+    return HCA_OK;
+  }
+
+  // What the kernels of the job with number `seq` in slot `slot` get
+  HostShare share(int slot, uint32_t seq, int spin_limit) const {
+    HostShare h;
+    h.chunks = chunks_;
+    h.p = p_[slot];
+    h.vrow = vrow_[slot];
+    h.py = py_[slot];
+    h.host_seq = host_seq(slot);
+    h.gpu_seq = gpu_seq(slot);
+    h.err = err_word();
+    h.seq = seq;
+    h.spin_limit = spin_limit;
+    return h;
+  }
+
+  uint32_t next_seq() const { return published_.load(std::memory_order_relaxed) + 1; }
+
+  // Called by the enqueueing thread after the layer's host-chunk kernels are enqueued.
+  void publish(uint32_t seq, int slot, int chunks, const void* v_host, int64_t host_stride, int64_t n_host_rows) {
+    // the ring entry is free once every worker has gone past the job that used it last
+    if (seq > (uint32_t)kRing) {
+      const uint32_t old = seq - kRing;
+      for (int t = 0; t < nthreads_; ++t)
+        while ((int32_t)(progress_[t].load(std::memory_order_acquire) - old) <= 0) _mm_pause();
+    }
+    Job& j = jobs_[seq % kRing];
+    j.seq = seq;
+    j.slot = slot;
+    j.chunks = chunks;
+    j.v_host = (const uint16_t*)v_host;
+    j.host_stride = host_stride;
+    j.n_host_rows = n_host_rows;
+    j.next_task.store(0, std::memory_order_relaxed);
+    j.tasks_left.store(L_.rows * chunks, std::memory_order_relaxed);
+    j.t_first.store(0, std::memory_order_relaxed);
+    for (int r = 0; r < L_.rows; ++r) j.row_left[r].store(chunks, std::memory_order_relaxed);
+    published_.store(seq, std::memory_order_release);
+    if (sleepers_.load(std::memory_order_acquire) > 0) {
+      std::lock_guard<std::mutex> g(m_);
+      cv_.notify_all();
+    }
+  }
+
+  uint32_t errors() const { return __atomic_load_n(err_word(), __ATOMIC_RELAXED) != 0 ? 1u : 0u; }
+  uint32_t bad_rows() const { return bad_rows_.load(std::memory_order_relaxed); }
+  // mean time from the GPU's signal (as first seen by a worker) to the job's last chunk, and mean time per chunk
+  void times(double* job_us, double* task_us) const {
+    const int64_t nj = jobs_done_.load(std::memory_order_relaxed), nt = tasks_done_.load(std::memory_order_relaxed);
+    *job_us = nj > 0 ? job_ns_.load(std::memory_order_relaxed) * 1e-3 / (double)nj : 0.0;
+    *task_us = nt > 0 ? task_ns_.load(std::memory_order_relaxed) * 1e-3 / (double)nt : 0.0;
+  }
+
+  void stop() {
+    if (stopped_) return;
+    stopped_ = true;
+    stop_.store(true, std::memory_order_release);
+    {
+      std::lock_guard<std::mutex> g(m_);
+      cv_.notify_all();
+    }
+    for (auto& t : threads_) t.join();
+    threads_.clear();
+  }
+
+ private:
+  static constexpr size_t kLine = 64;
+  // flags_: [kSlots] gpu_seq lines, then [kSlots][rows] host_seq (a line per slot and 16 rows), then the error word
+  static constexpr size_t kFlagBytes = kLine * (kSlots + kSlots * (kMaxBatch * 8 / 16) + 1);
+  uint32_t* gpu_seq(int slot) const { return (uint32_t*)(flags_ + kLine * slot); }
+  uint32_t* host_seq(int slot) const { return (uint32_t*)(flags_ + kLine * (kSlots + slot * (kMaxBatch * 8 / 16))); }
+  uint32_t* err_word() const { return (uint32_t*)(flags_ + kLine * (kSlots + kSlots * (kMaxBatch * 8 / 16))); }
+
+  void release() {
+    for (int s = 0; s < kSlots; ++s) {
+      if (p_[s]) (void)hipHostFree(p_[s]);
+      if (vrow_[s]) (void)hipHostFree(vrow_[s]);
+      if (py_[s]) (void)hipHostFree(py_[s]);
+      p_[s] = nullptr; vrow_[s] = nullptr; py_[s] = nullptr;
+    }
+    if (flags_) (void)hipHostFree(flags_);
+    flags_ = nullptr;
+  }
+
+  void loop(int me) {
+    // Weights far below the chunk's maximum are subnormal floats; x86 cores take a microcode assist for every
+    // operation on one (a hundred times the cost of a normal multiply-add).  Flush them to zero in this thread:
+    // what is lost is below 2^-126 of the chunk's largest weight.
+    _mm_setcsr(_mm_getcsr() | 0x8040u);               // FTZ | DAZ
+    uint32_t next = 1;
+    for (;;) {
+      // 1. the job's description
+      int idle = 0;
+      while ((int32_t)(published_.load(std::memory_order_acquire) - next) < 0) {
+        if (stop_.load(std::memory_order_acquire)) return;
+        if (++idle < 20000) { _mm_pause(); continue; }
+        std::unique_lock<std::mutex> g(m_);               // nothing for a while: sleep until the next publish
+        sleepers_.fetch_add(1, std::memory_order_acq_rel);
+        cv_.wait_for(g, std::chrono::milliseconds(50), [&] {
+          return stop_.load(std::memory_order_acquire) ||
+                 (int32_t)(published_.load(std::memory_order_acquire) - next) >= 0;
+        });
+        sleepers_.fetch_sub(1, std::memory_order_acq_rel);
+        idle = 0;
+      }
+      Job& j = jobs_[next % kRing];
+      // 2. the GPU's signal that the job's inputs are in pinned memory
+      const uint32_t* gs = gpu_seq(j.slot);
+      while ((int32_t)(__atomic_load_n(gs, __ATOMIC_ACQUIRE) - j.seq) < 0) {
+        if (stop_.load(std::memory_order_acquire)) return;
+        _mm_pause();
+      }
+      // 3. chunks, one at a time, whoever comes first
+      const int nch = j.chunks, ntask = L_.rows * nch;
+      int64_t t_seen = now_ns(), zero = 0;
+      j.t_first.compare_exchange_strong(zero, t_seen, std::memory_order_acq_rel);
+      for (int t = j.next_task.fetch_add(1, std::memory_order_acq_rel); t < ntask;
+           t = j.next_task.fetch_add(1, std::memory_order_acq_rel)) {
+        const int64_t t_a = now_ns();
+        const int row = t / nch, ch = t % nch;
+        const int64_t e = (int64_t)row * nch + ch;
+        const int bad = host_chunk_sum(L_.gqa, p_[j.slot] + e * 4 * kAttendChunk, vrow_[j.slot] + e * kAttendChunk,
+                                       j.v_host + (int64_t)row * j.host_stride * kHeadDim,
+                                       j.n_host_rows < j.host_stride ? j.n_host_rows : j.host_stride,
+                                       py_[j.slot] + e * 4 * kHeadDim);
+        if (bad) bad_rows_.fetch_add((uint32_t)bad, std::memory_order_relaxed);
+        if (j.row_left[row].fetch_sub(1, std::memory_order_acq_rel) == 1)      // the row's last chunk: tell the GPU
+          __atomic_store_n(host_seq(j.slot) + row, j.seq, __ATOMIC_RELEASE);
+        const int64_t t_b = now_ns();
+        task_ns_.fetch_add(t_b - t_a, std::memory_order_relaxed);
+        tasks_done_.fetch_add(1, std::memory_order_relaxed);
+        if (j.tasks_left.fetch_sub(1, std::memory_order_acq_rel) == 1) {
+          job_ns_.fetch_add(t_b - j.t_first.load(std::memory_order_acquire), std::memory_order_relaxed);
+          jobs_done_.fetch_add(1, std::memory_order_relaxed);
+        }
+      }
+      ++next;
+      progress_[me].store(next, std::memory_order_release);
+    }
+  }
+
+  static int64_t now_ns() {
+    return std::chrono::duration_cast<std::chrono::nanoseconds>(std::chrono::steady_clock::now().time_since_epoch()).count();
+  }
+  std::atomic<int64_t> job_ns_{0}, task_ns_{0}, jobs_done_{0}, tasks_done_{0};
+  Layout L_;
+  int chunks_, nthreads_;
+  float* p_[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+  int32_t* vrow_[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+  float* py_[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+  unsigned char* flags_ = nullptr;
+  std::unique_ptr<Job[]> jobs_;
+  std::unique_ptr<std::atomic<uint32_t>[]> progress_;
+  std::atomic<uint32_t> published_{0};
+  std::atomic<uint32_t> bad_rows_{0};
+  std::atomic<int> sleepers_{0};
+  std::atomic<bool> stop_{false};
+  bool stopped_ = false;
+  std::mutex m_;
+  std::condition_variable cv_;
+  std::vector<std::thread> threads_;
+};
+
+}  // namespace hca
 
 struct hca_pipeline {
   hca::Layout L;
@@ -18,6 +236,9 @@ struct hca_pipeline {
   std::vector<hipEvent_t> layer_done;
   std::vector<hipEvent_t> t0, t1;   // timing events around the scan launches: [slots][layers]
   int timing_slots;
+  std::unique_ptr<hca::HostSide> host;   // hybrid value side (desc.host_chunks > 0), else null
+  int host_chunks = 0, host_spin_limit = 0;
+  hca::Tuning tune;                 // this pipeline's launch-shape knobs
 };
 
 // an eviction in progress: its slices go out one at a time behind the attends of the following layers
@@ -50,6 +271,13 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
     if (desc->spare_kcache != nullptr || desc->spare_acc != nullptr || desc->spare_pos != nullptr) return nullptr;
   }
   if (!(desc->topp_tau >= 0.0)) return nullptr;
+  if (desc->host_chunks < 0 || desc->host_chunks > 64 || desc->host_threads < 0 || desc->host_threads > 64 ||
+      desc->host_spin_limit < 0)
+    return nullptr;
+  if (desc->host_chunks > 0 && desc->vq_groups != 0) return nullptr;          // uniform codes only
+  if (desc->gather_wgs < 0 || desc->gather_wgs > 1024 || desc->gather_unroll < 0 || desc->gather_unroll > 4) return nullptr;
+  if (desc->score_bpw != 0 && (desc->score_bpw < kScoreBpwMin || desc->score_bpw > kScoreBpwMax)) return nullptr;
+  if (!(desc->score_depth == 0 || desc->score_depth == 4 || desc->score_depth == 8)) return nullptr;
   hca_pipeline* p = new hca_pipeline();
   p->L = L;
   p->n_layers = n_layers;
@@ -58,6 +286,14 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   p->n_sel = desc->n_sel < n_layers ? desc->n_sel : n_layers;
   p->sel_waits = desc->n_sel < n_layers;
   p->timing_stride = desc->timing_layer_stride > 1 ? desc->timing_layer_stride : 1;
+  p->tune = tuning();                        // the process-wide defaults, then this pipeline's own values
+  if (desc->gather_wgs > 0) p->tune.gather_wgs = desc->gather_wgs;
+  if (desc->gather_unroll > 0) p->tune.gather_unroll = desc->gather_unroll;
+  if (desc->score_bpw > 0) p->tune.score_bpw = desc->score_bpw;
+  if (desc->score_depth > 0) p->tune.score_depth = desc->score_depth;
+  p->host_chunks = desc->host_chunks;
+  // ~2 us per poll over the host link: about a second before a merge gives up on the host
+  p->host_spin_limit = desc->host_spin_limit > 0 ? desc->host_spin_limit : (1 << 19);
   p->score_done.resize(p->n_sel);
   p->sel_free.resize(p->n_sel);
   bool ok = true;
@@ -74,6 +310,10 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   p->t1.resize((size_t)timing_slots * n_layers);
   for (size_t i = 0; i < p->t0.size(); ++i) { mk(&p->t0[i], hipEventDefault); mk(&p->t1[i], hipEventDefault); }
   if (!ok) { delete p; return nullptr; }   // events already made are left to process teardown
+  if (p->host_chunks > 0) {
+    p->host.reset(new HostSide(L, p->host_chunks, desc->host_threads));
+    if (p->host->start() != HCA_OK) { delete p; return nullptr; }
+  }
   // the top-k histogram at the head of ws_topk starts clean and is kept clean by every selection
   if (hipMemsetAsync(desc->ws_topk, 0, topk_hist_bytes(L.rows), (hipStream_t)desc->stream_topk) != hipSuccess) {
     delete p;
@@ -84,6 +324,10 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
 
 void hca_pipeline_destroy(hca_pipeline* p) {
   if (p == nullptr) return;
+  if (p->host) {                       // the workers read pinned buffers that die with the object
+    (void)hipDeviceSynchronize();      // no merge may still be polling a flag of theirs
+    p->host->stop();
+  }
   for (auto e : p->score_done) (void)hipEventDestroy(e);
   for (auto e : p->sel_free) (void)hipEventDestroy(e);
   for (int i = 0; i < 4; ++i) {
@@ -134,7 +378,9 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (!vq && timing_slot >= 0 && p->d.scan_stamps != nullptr && p->d.scan_stamp_pairs < score_stamp_pairs(L, nmax + 1))
       return HCA_ERR_CAPACITY;
     if (p->d.fused_select != 0 && select_scan_bpw(L, nmax + 1) == 0) return HCA_ERR_CAPACITY;   // row too long for the lists
+    if (p->host_chunks > 0 && (ly.v_host == nullptr || n_host_rows < 1)) return HCA_ERR_BAD_ARG;  // the host sums from v_host
   }
+  const int hchunks = p->host ? host_share_chunks(k, p->host_chunks) : 0;
   hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk;
   hipStream_t sg = (hipStream_t)p->d.stream_gather, sc = (hipStream_t)p->d.stream_attend;
   NRes vrow0;
@@ -261,7 +507,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     rc = vq ? launch_vq_score(L, vg, vc, ly.vq_centroids, (const uint8_t*)ly.kcache, ly.q, nr, nmax, ly.vq_lut,
                               p->d.sel[s3], nullptr, sa)
          : fused ? fused_scan()
-                 : launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps);
+                 : launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps, &p->tune);
     if (rc != HCA_OK) return rc;
     if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
     HCA_HIP(hipEventRecord(p->score_done[s3], sa));
@@ -281,8 +527,21 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     uint64_t* gstamps = nullptr;
     if (timing_slot >= 0 && p->d.gather_stamps != nullptr)
       gstamps = (uint64_t*)p->d.gather_stamps + ((int64_t)timing_slot * p->n_layers + l) * kGatherStampPairs * 2;
+    HostShare hs;
+    if (hchunks > 0) {
+      // hybrid value side: the first chunks of every row's selection are summed by the host threads from the
+      // value store itself; what they need (weights relative to each chunk's maximum, value-row numbers)
+      // goes out first on this stream, then the signal, then the gather of the remaining entries
+      const uint32_t seq = p->host->next_seq();
+      hs = p->host->share(s4, seq, p->host_spin_limit);
+      hs.chunks = hchunks;
+      rc = launch_attend_host_chunks(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, ly.pos, n_host_rows, ly.v_hbm,
+                                     hbm_stride, sm_scale, p->d.ws_attend[s4], hs, sg);
+      if (rc != HCA_OK) return rc;
+      p->host->publish(seq, s4, hchunks, ly.v_host, host_stride, n_host_rows);
+    }
     rc = launch_gather(L, p->d.idx[s4], p->d.count[s4], k, ly.pos, ly.v_host, host_stride, n_host_rows, ly.v_hbm,
-                       hbm_stride, p->d.ws_attend[s4], sg, gstamps);
+                       hbm_stride, p->d.ws_attend[s4], sg, gstamps, hchunks * kAttendChunk, &p->tune);
     if (rc != HCA_OK) return rc;
     HCA_HIP(hipEventRecord(p->gather_done[s4], sg));
     // stage 4: attend (+ eviction into the spare buffers, which then swap with the layer's)
@@ -290,7 +549,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     rc = vq ? launch_vq_attend_gathered(L, vg, vc, (const uint8_t*)ly.kcache, ly.vq_lut, p->d.idx[s4], p->d.count[s4], k,
                                         sm_scale, ly.y, ly.acc, p->d.ws_attend[s4], sc)
             : launch_attend_gathered(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, sm_scale, ly.y, ly.acc,
-                                     p->d.ws_attend[s4], sc);
+                                     p->d.ws_attend[s4], sc, nullptr, hchunks > 0 ? &hs : nullptr);
     if (rc != HCA_OK) return rc;
     const int64_t M = evict_M != nullptr ? evict_M[l] : 0;
     HCA_HIP(hipEventRecord(p->pipe_free[s4], sc));
@@ -329,6 +588,18 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     int32_t rc = advance(job);
     if (rc != HCA_OK) return rc;
   }
+  return HCA_OK;
+}
+
+int32_t hca_pipeline_host_status(hca_pipeline* p, uint32_t* wait_timeouts, uint32_t* bad_rows, double* mean_job_us,
+                                 double* mean_chunk_us) {
+  if (p == nullptr) return HCA_ERR_BAD_ARG;
+  if (wait_timeouts != nullptr) *wait_timeouts = p->host ? p->host->errors() : 0u;
+  if (bad_rows != nullptr) *bad_rows = p->host ? p->host->bad_rows() : 0u;
+  double ju = 0.0, tu = 0.0;
+  if (p->host) p->host->times(&ju, &tu);
+  if (mean_job_us != nullptr) *mean_job_us = ju;
+  if (mean_chunk_us != nullptr) *mean_chunk_us = tu;
   return HCA_OK;
 }
 

@@ -683,12 +683,12 @@ size_t score_workspace_bytes(const Layout& L) {
 }
 
 int32_t launch_score(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
-                     float* sel, float* z_opt, hipStream_t st, uint64_t* stamps) {
+                     float* sel, float* z_opt, hipStream_t st, uint64_t* stamps, const Tuning* tune) {
   if (nmax == 0) return HCA_OK;
   const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
   // aim at ~16 waves per SIMD over the whole chip when the cache is large, >= 4 blocks per wave
   const int64_t total = nblocks * L.rows;
-  const Tuning& tn = tuning();
+  const Tuning& tn = tune != nullptr ? *tune : tuning();
   int64_t bpw = total / (256 * 4 * 16);
   if (bpw < 4) bpw = 4;
   // measured best on MI355X: 4-bit codes 8 blocks ahead, 16 per wave; 2-bit codes (two tiles per block,

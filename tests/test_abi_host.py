@@ -295,3 +295,13 @@ def test_header_and_library_from_plain_c(B):
     r = subprocess.run([_c_program("abi_from_c")], capture_output=True, text=True)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "abi ok" in r.stdout
+
+
+def test_host_prefault_walks_any_range(B):
+    import numpy as np
+    L = B.lib()
+    a = np.ones(3 * 4096 + 17, np.uint8)
+    for threads in (1, 3, 64, 1000):
+        assert L.hca_host_prefault(C.c_void_p(a.ctypes.data), a.nbytes, threads) == 0
+    assert L.hca_host_prefault(None, 0, 4) == 0
+    assert L.hca_host_prefault(None, 10, 4) == -1

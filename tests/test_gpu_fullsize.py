@@ -423,8 +423,8 @@ def test_config3_full_shape_per_call_path(oracle):
           f"{ref['ever_selected_max']} of {M - E}", flush=True)
 
 
-@pytest.mark.parametrize("fused,spare", [(True, False), (False, True)])
-def test_config3_full_shape_step_driver(oracle, fused, spare):
+@pytest.mark.parametrize("fused,spare,host", [(True, False, 0), (False, True, 0), (True, False, 3)])
+def test_config3_full_shape_step_driver(oracle, fused, spare, host):
     """The same 64 steps through hca_pipeline_step (one layer): scan + top-k fused with in-place eviction, and
     the two-call form with eviction into a spare buffer set."""
     import ctypes as C
@@ -471,6 +471,7 @@ def test_config3_full_shape_step_driver(oracle, fused, spare):
     d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
     if spare:
         d.spare_kcache, d.spare_acc, d.spare_pos = kc[1].data_ptr(), acc[1].data_ptr(), pos[1].data_ptr()
+    d.host_chunks, d.host_threads = host, 12      # hybrid value side: 3 of the 8 chunks of 256 summed on the host
     pl = B.hca_pipeline_create(shape, 1, d, 0)
     layers = (B.hca_layer * 1)()
     layers[0].kcache, layers[0].acc, layers[0].pos = kc[0].data_ptr(), acc[0].data_ptr(), pos[0].data_ptr()
@@ -484,7 +485,7 @@ def test_config3_full_shape_step_driver(oracle, fused, spare):
         layers[0].k_new, layers[0].q = kn.data_ptr(), qd.data_ptr()
         ev = (C.c_int64 * 1)(M if (t + 1) % E == 0 else 0)
         torch.cuda.synchronize()
-        print(f"cfg3 step driver fused={fused} spare={spare} step {t}", flush=True)
+        print(f"cfg3 step driver fused={fused} spare={spare} host={host} step {t}", flush=True)
         B.hca_pipeline_step(pl, layers, nres, n0 + t, w.k, vrows, vrows, 0, ref["sm"], ev, E, -1)
         torch.cuda.synchronize()
         assert np.array_equal(_rows(idxs[0]), ref["idx"][t]), f"step {t}: top-k sets differ"
@@ -497,5 +498,6 @@ def test_config3_full_shape_step_driver(oracle, fused, spare):
     k_t, a_t, p_t = bufs[layers[0].kcache]
     assert layers[0].acc == a_t.data_ptr() and layers[0].pos == p_t.data_ptr()
     _cfg3_check_final(B, shape, ref, k_t, a_t, p_t, M)
+    assert B.hca_pipeline_host_status(pl) == (0, 0)
     B.hca_pipeline_destroy(pl)
-    print(f"cfg3 step driver fused={fused} spare={spare}: worst output error {worst:.2e}", flush=True)
+    print(f"cfg3 step driver fused={fused} spare={spare} host_chunks={host}: worst output error {worst:.2e}", flush=True)

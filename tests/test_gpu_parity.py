@@ -366,11 +366,13 @@ def test_kernels_are_deterministic(H):
         assert torch.equal(a, b)
 
 
-@pytest.mark.parametrize("Lr,n_sel,spare,tau,fused", [
-    (3, 3, True, 0.0, False), (5, 3, True, 0.0, False), (5, 5, True, 0.0, False), (5, 5, False, 0.0, False),
-    (3, 3, False, 0.0, False), (4, 4, False, 0.9, False), (3, 3, True, 0.95, False),
-    (5, 3, True, 0.0, True), (5, 5, False, 0.0, True), (1, 3, False, 0.0, True), (4, 4, True, 0.0, True)])
-def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fused):
+@pytest.mark.parametrize("Lr,n_sel,spare,tau,fused,host", [
+    (3, 3, True, 0.0, False, 0), (5, 3, True, 0.0, False, 0), (5, 5, True, 0.0, False, 0), (5, 5, False, 0.0, False, 0),
+    (3, 3, False, 0.0, False, 0), (4, 4, False, 0.9, False, 0), (3, 3, True, 0.95, False, 0),
+    (5, 3, True, 0.0, True, 0), (5, 5, False, 0.0, True, 0), (1, 3, False, 0.0, True, 0), (4, 4, True, 0.0, True, 0),
+    # hybrid value side: the first `host` chunks of 256 selected tokens are summed by the driver's host threads
+    (5, 5, False, 0.0, True, 1), (3, 3, True, 0.0, False, 2), (5, 3, False, 0.9, False, 1), (6, 6, False, 0.0, True, 3)])
+def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fused, host):
     """hca_pipeline_step over 1 to 5 layers (score buffers shared between layers or one each), 12 decode
     steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k (as scan +
     top-k or fused as in hca_score_topk) or the cumulative-weight selection of Eq. 4 (tau > 0): every layer's
@@ -378,7 +380,9 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
     import ctypes as C
     from paper_2507_19823_amd import binding as B
     steps, E = 12, 4
-    w = S.Workload("drv", 7, 2, 8, 2, 1500, 4, 32, 96)
+    # with a host share the selection spans several chunks (k = 600: three chunks, the last ragged), and the
+    # appended tokens' value rows (HBM slice) fall into the host's chunks whenever they rank early
+    w = S.Workload("drv", 7, 2, 8, 2, 1500, 4, 32, 600 if host else 96)
     R, n0 = w.batch * w.n_kv_heads, w.n
     cap, vnew = n0 + E + 16, steps + 4
     shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
@@ -431,6 +435,7 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
     if spare:
         d.spare_kcache, d.spare_acc, d.spare_pos = kc[Lr].data_ptr(), acc[Lr].data_ptr(), pos[Lr].data_ptr()
     d.topp_tau = tau
+    d.host_chunks, d.host_threads = host, 3
     pl = B.hca_pipeline_create(shape, Lr, d, 0)
     layers = (B.hca_layer * Lr)()
     for l in range(Lr):
@@ -484,6 +489,59 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
         assert np.array_equal(_rows(sc).view(np.uint16)[:, :n], ocs[l].scale[:, :n])
         assert np.array_equal(_rows(p_t)[:, :n], opos[l][:, :n])
         assert np.allclose(_rows(a_t)[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-6)
+    assert B.hca_pipeline_host_status(pl) == (0, 0)
+    B.hca_pipeline_destroy(pl)
+
+
+def test_step_driver_merge_gives_up_on_a_silent_host(H):
+    """Hybrid value side with no host threads started and a tiny poll limit: every merge's bounded wait runs out,
+    the kernels end normally, and the driver reports the timeout."""
+    import ctypes as C
+    from paper_2507_19823_amd import binding as B
+    w = S.Workload("drv", 8, 1, 8, 2, 900, 4, 32, 300)
+    n0, cap = w.n, w.n + 8
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    dev = "cuda"
+    data = S.make_layer(w, 0)
+    kc = torch.zeros(B.hca_kcache_bytes(shape), dtype=torch.uint8, device=dev)
+    acc = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
+    pos = torch.arange(cap, dtype=torch.int32, device=dev).repeat(w.batch, w.n_kv_heads, 1).contiguous()
+    B.hca_quantize_keys(shape, kc, data["keys"].cuda(), n0, [0] * w.batch)
+    vh = data["values"].contiguous().pin_memory()
+    vd = torch.zeros(w.batch, w.n_kv_heads, 4, 128, dtype=torch.float16, device=dev)
+    y = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.float32, device=dev)
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    d = B.hca_pipeline_desc()
+    d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
+    wsb = B.hca_workspace_bytes(shape, w.k, 1)
+    keep = []
+    for i in range(3):
+        t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
+        d.sel[i] = t.data_ptr()
+        keep.append(t)
+    d.n_sel = 3
+    for i in range(4):
+        a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
+        b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
+        c = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+        keep += [a, b, c]
+        d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), c.data_ptr()
+    wt = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    d.ws_topk = wt.data_ptr()
+    d.host_chunks, d.host_threads, d.host_spin_limit = 1, 0, 20
+    pl = B.hca_pipeline_create(shape, 1, d, 0)
+    layers = (B.hca_layer * 1)()
+    layers[0].kcache, layers[0].acc, layers[0].pos = kc.data_ptr(), acc.data_ptr(), pos.data_ptr()
+    layers[0].v_host, layers[0].v_hbm, layers[0].y = vh.data_ptr(), vd.data_ptr(), y.data_ptr()
+    k_new, _, q = S.make_step(w, 0, 0)
+    kn, qd = k_new.cuda(), q.cuda()
+    layers[0].k_new, layers[0].q = kn.data_ptr(), qd.data_ptr()
+    nres = (C.c_int64 * 1)(n0)
+    assert B.hca_pipeline_host_status(pl) == (0, 0)
+    B.hca_pipeline_step(pl, layers, nres, n0, w.k, n0, n0, 4, 1.0 / math.sqrt(128.0), None, 0, -1)
+    torch.cuda.synchronize()
+    assert B.hca_pipeline_host_status(pl)[0] != 0
+    assert nres[0] == n0 + 1
     B.hca_pipeline_destroy(pl)
 
 
