@@ -30,7 +30,7 @@ class Model:
     """All layers of one workload: per-layer key cache / acc / pos / host values, shared scratch."""
 
     def __init__(self, w, layers, evict_every, total_steps, n_pipe=2, n_sel=3, evict_spare=False, fused=False,
-                 host_chunks=0, host_threads=12, tune=None):
+                 host_chunks=0, host_threads=12, tune=None, n_pipe_sets=4, dual_scan="single"):
         import torch
         from paper_2507_19823_amd import binding as B
         self.torch, self.B, self.w = torch, B, w
@@ -70,7 +70,9 @@ class Model:
         self.ws_topk = torch.empty(B.hca_workspace_bytes(self.shape, w.k, 1), dtype=torch.uint8, device=dev)
         wsa = B.hca_workspace_bytes(self.shape, w.k, 1)
         self.pipe = []
-        for _ in range(4):
+        self.n_pipe_sets = n_pipe_sets
+        self.dual_scan = dual_scan
+        for _ in range(n_pipe_sets):
             self.pipe.append(dict(
                 idx=torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev),
                 count=torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev),
@@ -206,7 +208,9 @@ class Model:
                 d.sel[i] = sbuf.data_ptr()
             d.n_sel = len(self.sels)
         d.timing_layer_stride = timing_stride
-        for i in range(4):
+        d.n_pipe = self.n_pipe_sets
+        d.dual_scan = {"single": 0, "dual": 1, "pair": 2}[self.dual_scan] if self.fused else 0
+        for i in range(self.n_pipe_sets):
             d.idx[i] = self.pipe[i]["idx"].data_ptr()
             d.count[i] = self.pipe[i]["count"].data_ptr()
             d.ws_attend[i] = self.pipe[i]["ws"].data_ptr()
@@ -923,6 +927,12 @@ def main():
                     help="hybrid value side of the native step driver: of every row's selected tokens the first N "
                          "chunks of 256 are summed by host threads from the value store, the rest gathered (0: all gathered)")
     ap.add_argument("--host-threads", type=int, default=12, help="worker threads of the hybrid value side")
+    ap.add_argument("--scan-mode", default="single", choices=["single", "dual", "pair"],
+                    help="native step driver with the fused selection: single = one scan launch per layer on one stream; "
+                         "dual = even layers scan + select on one stream, odd layers on a second one, so that two scans "
+                         "overlap; pair = one scan launch per two layers")
+    ap.add_argument("--pipe-sets", type=int, default=4, choices=[4, 5, 6, 7, 8],
+                    help="native step driver: sets of selection / staging buffers, i.e. layers in flight between top-k and attend")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gap-report", action="store_true",
                     help="log the largest idle times between consecutive scan launches with their step.layer")
@@ -1041,7 +1051,7 @@ def main():
     fused = args.pipeline == "native" and not args.no_fused_select
     model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers), evict_spare=args.evict_spare,
                   fused=fused, host_chunks=args.host_chunks if args.pipeline == "native" else 0,
-                  host_threads=args.host_threads, tune=tune)
+                  host_threads=args.host_threads, tune=tune, n_pipe_sets=args.pipe_sets, dual_scan=args.scan_mode)
     layer_v_gib = w.batch * w.n_kv_heads * w.n * 256 / 2 ** 30
     phys = max(1, min(L, int(args.host_gib / layer_v_gib)))
     t0 = time.perf_counter()
@@ -1074,17 +1084,26 @@ def main():
     log("warmup done")
     events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
               for _ in range(args.steps)]
+    step_end = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    host_done = []
+    step_end[0].record(extra[1])                      # the attend stream: a step's last kernels run there
     t0 = time.perf_counter()
     host_steps = []
     for t in range(args.warmup, total_steps):
         h0 = time.perf_counter()
         run_step(t, events[t - args.warmup])
+        step_end[t - args.warmup + 1].record(extra[1] if args.pipeline in ("native", "staged") else main)
         host_steps.append((time.perf_counter() - h0) * 1e3)
+        host_done.append((time.perf_counter() - t0) * 1e3)
     host_dt = time.perf_counter() - t0
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     log(f"timed region done: {dt:.3f}s for {args.steps} steps (host enqueue {host_dt:.3f}s; per step ms: "
         + " ".join(f"{x:.2f}" for x in host_steps) + ")")
+    if args.pipeline == "native":
+        gpu_done = [step_end[0].elapsed_time(step_end[i + 1]) for i in range(args.steps)]
+        log("host lead per step (GPU end of step - host end of its enqueue, ms): "
+            + " ".join(f"{g - h:.2f}" for g, h in zip(gpu_done, host_done)))
     ms_per_step = dt * 1e3 / args.steps
     host_side = None
     if args.pipeline == "native" and model.host_chunks:
@@ -1103,6 +1122,12 @@ def main():
         st_ = model.stamps
         starts = torch.where(st_[..., 0] > 0, st_[..., 0], torch.full_like(st_[..., 0], 1 << 62)).amin(-1)
         ends = st_[..., 1].amax(-1)
+        layers_per_launch = 1
+        if fused and args.scan_mode == "pair" and L % 2 == 0:
+            # one launch scans two layers: its duration runs from the first wave of either to the last wave of either
+            layers_per_launch = 2
+            starts = starts.reshape(args.steps, L // 2, 2).amin(-1)
+            ends = ends.reshape(args.steps, L // 2, 2).amax(-1)
         khz = B.hca_wall_clock_khz()
         scan_ms = float((ends - starts).double().mean()) / khz
         flat_s, flat_e = starts.reshape(-1).double(), ends.reshape(-1).double()
@@ -1110,6 +1135,12 @@ def main():
         log("key scan launches: mean %.1f us; idle between consecutive ones: mean %.1f us, median %.1f us" % (
             scan_ms * 1e3, float(gaps.mean()), float(gaps.median())))
         if args.gap_report:
+            edges = [0, 10, 20, 30, 50, 80, 120, 200, 400, 100000]
+            hist = []
+            for a, b in zip(edges[:-1], edges[1:]):
+                m = (gaps >= a) & (gaps < b)
+                hist.append(f"[{a},{b}): {int(m.sum())} gaps, {float(gaps[m].sum()) / args.steps:.0f} us/step")
+            log("scan gap histogram: " + "; ".join(hist))
             gs = model.gstamps
             g_start = torch.where(gs[..., 0] > 0, gs[..., 0], torch.full_like(gs[..., 0], 1 << 62)).amin(-1).reshape(-1).double()
             g_end = gs[..., 1].amax(-1).reshape(-1).double()
@@ -1117,6 +1148,22 @@ def main():
             gdur = (g_end - g_start) / khz * 1e3
             log("gathers: mean %.1f us; idle between consecutive ones: mean %.1f us, median %.1f us" % (
                 float(gdur.mean()), float(ggaps.mean()), float(ggaps.median())))
+            # merged timeline of scan launches and gathers around one step boundary (wall-clock stamps, us)
+            try:
+                sb_, ge_ = starts.reshape(-1).double() / khz * 1e3, ends.reshape(-1).double() / khz * 1e3
+                per = sb_.numel() // args.steps
+                mid = (args.steps // 2) * per
+                base = float(sb_[mid])
+                ev_ = [(float(sb_[i]) - base, float(ge_[i]) - base, f"scan  launch {i % per} step {i // per}")
+                       for i in range(mid - per // 2, mid + per // 2)]
+                gi0 = (args.steps // 2) * L
+                ev_ += [(float(g_start[i]) / khz * 1e3 - base, float(g_end[i]) / khz * 1e3 - base, f"gather layer {i % L} step {i // L}")
+                        for i in range(gi0 - L // 2, gi0 + L // 2)]
+                with open(os.path.join(ROOT, "gpurun_out", "timeline_stamps.txt"), "w") as f:
+                    for a_, b_, n_ in sorted(ev_):
+                        f.write(f"{a_:10.1f} {b_:10.1f} {n_}\n")
+            except Exception as e:                    # a diagnostic only
+                log(f"timeline dump failed: {e}")
             gtop = torch.topk(ggaps, 24)
             log("largest gather gaps (us @ step.layer): " + " ".join(
                 "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(gtop.values, gtop.indices)))
@@ -1124,9 +1171,10 @@ def main():
             log("largest gaps (us @ step.layer): " + " ".join(
                 "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(top.values, top.indices)))
     else:
+        layers_per_launch = 1
         events = [e for step_events in events for e in step_events]
         scan_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
-    scan_bytes = w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + (0 if fused else 4))
+    scan_bytes = layers_per_launch * w.batch * w.n_kv_heads * (w.n + 1) * (code_bytes + (0 if fused else 4))
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
 
     traffic = None

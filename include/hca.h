@@ -65,8 +65,11 @@ const char* hca_version(void);
 
 /* Overrides a launch-shape knob for the per-call entry points (process-wide state, meant for tuning and
  * profiling sessions, not needed for correct results; a step driver takes its knobs from its own
- * hca_pipeline_desc instead and only starts from these).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth",
- * "host_spin_us" (how long the worker threads of hca_host_weighted_sum poll for the next
+ * hca_pipeline_desc instead and only starts from these).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth", "select_wg" (threads per workgroup of the
+ * selection over the candidate lists of hca_score_topk: 1024 - pairs staged in LDS, needs a whole compute unit -
+ * or 256 - pairs read from L2, finds room beside a running scan, slower where measured; 0: 1024),
+ * "host_isa" (2: the hybrid value side's host threads use their AVX2 form even where the CPU has AVX-512; 0: the
+ * widest form), "host_spin_us" (how long the worker threads of hca_host_weighted_sum poll for the next
  * call before they sleep; default 100, 0 = sleep at once).
  * Returns HCA_ERR_BAD_ARG for an unknown name. */
 int32_t hca_tune(const char* name, int32_t value);
@@ -238,14 +241,15 @@ typedef struct {
 } hca_layer;
 
 #define HCA_PIPELINE_MAX_SEL 64
+#define HCA_PIPELINE_MAX_PIPE 8
 typedef struct {
   void *stream_scan, *stream_topk, *stream_gather, *stream_attend;   /* four distinct hipStream_t */
   float* sel[HCA_PIPELINE_MAX_SEL]; /* device, fp32 [batch, n_kv_heads, capacity] each; the first n_sel are used */
   int32_t n_sel;                 /* 3 .. HCA_PIPELINE_MAX_SEL score buffers.  With one per layer the key scan of a
                                     layer never waits for the top-k of an earlier layer to release its buffer */
-  int32_t* idx[4];               /* device, int32 [batch, n_kv_heads, k] each */
-  int32_t* count[4];             /* device, int32 [batch, n_kv_heads] each */
-  void* ws_attend[4];            /* device, hca_workspace_bytes(shape, k, 1) each */
+  int32_t* idx[HCA_PIPELINE_MAX_PIPE];    /* device, int32 [batch, n_kv_heads, k] each; the first n_pipe are used */
+  int32_t* count[HCA_PIPELINE_MAX_PIPE];  /* device, int32 [batch, n_kv_heads] each */
+  void* ws_attend[HCA_PIPELINE_MAX_PIPE]; /* device, hca_workspace_bytes(shape, k, 1) each */
   void* ws_topk;                 /* device, hca_workspace_bytes(shape, k, 1); owned by the driver from
                                     hca_pipeline_create on (it keeps a histogram there between steps) */
   void* ws_evict;                /* device, hca_workspace_bytes(shape, k, M); NULL if eviction is never asked for */
@@ -287,11 +291,22 @@ typedef struct {
      host_threads: worker threads (1 .. 64; they poll while steps are in flight and sleep when idle; 0 starts
      none - then every merge times out, for tests of that path).  host_spin_limit: polls of the host's flag
      before a merge gives up and records a timeout (0: about a second); see hca_pipeline_host_status.
-     The driver owns the pinned exchange buffers (about 1.3 KiB per selected token of the host share, four
-     sets) and the threads from hca_pipeline_create to hca_pipeline_destroy. */
+     The driver owns the pinned exchange buffers (about 1.3 KiB per selected token of the host share, one set per
+     idx / count / ws_attend set) and the threads from hca_pipeline_create to hca_pipeline_destroy. */
   int32_t host_chunks, host_threads, host_spin_limit;
   /* Launch-shape knobs of this pipeline's kernels (0: the library's default; ranges as in hca_tune). */
-  int32_t gather_wgs, gather_unroll, score_bpw, score_depth;
+  int32_t gather_wgs, gather_unroll, score_bpw, score_depth, select_wg;
+  /* Sets of idx / count / ws_attend in use: 0 or 4 .. HCA_PIPELINE_MAX_PIPE.  A set is held by a layer from its
+     top-k to the end of its attend; with the hybrid value side that span holds the host threads' turn too, and
+     more than four layers have to be in flight to keep every stage busy. */
+  int32_t n_pipe;
+  /* fused_select only, n_sel >= 6 or one workspace per layer.
+     dual_scan == 1: two scan streams.  Even layers run append + scan + selection on stream_scan, odd layers on
+     stream_topk; the scans of the two overlap, so the key stream from HBM does not pause between launches.
+     dual_scan == 2: paired launches.  Layers l and l + 1 (l even) are scanned by one launch on stream_scan, their
+     selections follow on stream_topk: half as many pauses between scan launches, one launch tail per two
+     layers.  hca_pipeline_scan_ms then reports the shared launch under the even layer and -1 for the odd one. */
+  int32_t dual_scan;
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;
@@ -329,6 +344,15 @@ int32_t hca_pipeline_host_status(hca_pipeline* p, uint32_t* wait_timeouts, uint3
  * read: the first CPU access to a page of a pinned allocation is a page fault of several microseconds, which
  * would otherwise be paid inside the first decode steps, once per selected row. */
 int32_t hca_host_prefault(const void* ptr, size_t bytes, int32_t n_threads);
+
+/* Test / debug, host code: the work of one host thread of the hybrid value side on one chunk of 256 selected
+ * tokens: py[h][c] = sum_i p[h][i] * V[vrow[i]][c] over the entries with vrow[i] >= 0, for h < gqa (rows of the
+ * other heads are zero).
+ *   p      host, fp32 [4][256]         vrow  host, int32 [256]
+ *   v_rows host, fp16 [n_rows][128]    py    host, fp32 [4][128]
+ * Returns the number of entries with vrow >= n_rows (skipped), or HCA_ERR_BAD_ARG. */
+int32_t hca_debug_host_chunk_sum(int32_t gqa, const float* p, const int32_t* vrow, const void* v_rows, int64_t n_rows,
+                                 float* py);
 
 /* (start, end) pairs a key-scan launch over n_tokens resident tokens may write into scan_stamps. */
 int64_t hca_scan_stamp_pairs(const hca_shape* shape, int64_t n_tokens);

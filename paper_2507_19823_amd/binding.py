@@ -36,13 +36,14 @@ class hca_layer(C.Structure):
 
 
 PIPELINE_MAX_SEL = 64
+PIPELINE_MAX_PIPE = 8
 
 
 class hca_pipeline_desc(C.Structure):
     _fields_ = [("stream_scan", C.c_void_p), ("stream_topk", C.c_void_p), ("stream_gather", C.c_void_p),
                 ("stream_attend", C.c_void_p), ("sel", C.c_void_p * PIPELINE_MAX_SEL), ("n_sel", C.c_int32),
-                ("idx", C.c_void_p * 4),
-                ("count", C.c_void_p * 4), ("ws_attend", C.c_void_p * 4), ("ws_topk", C.c_void_p),
+                ("idx", C.c_void_p * PIPELINE_MAX_PIPE),
+                ("count", C.c_void_p * PIPELINE_MAX_PIPE), ("ws_attend", C.c_void_p * PIPELINE_MAX_PIPE), ("ws_topk", C.c_void_p),
                 ("ws_evict", C.c_void_p), ("spare_kcache", C.c_void_p), ("spare_acc", C.c_void_p),
                 ("spare_pos", C.c_void_p), ("scan_stamps", C.c_void_p), ("scan_stamp_pairs", C.c_int64),
                 ("timing_layer_stride", C.c_int32), ("vq_groups", C.c_int32), ("vq_codewords", C.c_int32),
@@ -50,7 +51,7 @@ class hca_pipeline_desc(C.Structure):
                 ("ws_select", C.c_void_p * PIPELINE_MAX_SEL), ("gather_stamps", C.c_void_p),
                 ("host_chunks", C.c_int32), ("host_threads", C.c_int32), ("host_spin_limit", C.c_int32),
                 ("gather_wgs", C.c_int32), ("gather_unroll", C.c_int32), ("score_bpw", C.c_int32),
-                ("score_depth", C.c_int32)]
+                ("score_depth", C.c_int32), ("select_wg", C.c_int32), ("n_pipe", C.c_int32), ("dual_scan", C.c_int32)]
 
 
 class hca_vq_codebook(C.Structure):
@@ -117,6 +118,8 @@ def lib():
         L.hca_pipeline_host_status.restype = i32
         L.hca_pipeline_host_status.argtypes = [vp, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32),
                                                C.POINTER(C.c_double), C.POINTER(C.c_double)]
+        L.hca_debug_host_chunk_sum.restype = i32
+        L.hca_debug_host_chunk_sum.argtypes = [i32, vp, vp, vp, i64, vp]
         L.hca_host_prefault.restype = i32
         L.hca_host_prefault.argtypes = [vp, C.c_size_t, i32]
         L.hca_scan_stamp_pairs.restype = i64

@@ -79,6 +79,12 @@ int32_t hca_tune(const char* name, int32_t value) {
   } else if (!strcmp(name, "score_depth")) {
     if (!(value == 0 || value == 4 || value == 8)) return HCA_ERR_BAD_ARG;
     t.score_depth = value;
+  } else if (!strcmp(name, "select_wg")) {
+    if (!(value == 0 || value == 256 || value == 1024)) return HCA_ERR_BAD_ARG;
+    t.select_wg = value;
+  } else if (!strcmp(name, "host_isa")) {
+    if (!(value == 0 || value == 2)) return HCA_ERR_BAD_ARG;
+    t.host_isa = value;
   } else if (!strcmp(name, "host_spin_us")) {
     t.host_spin_us = value < 0 ? 0 : value;
   } else {

@@ -45,8 +45,13 @@ __global__ __launch_bounds__(256) void gather_values(const int32_t* __restrict__
                                                      const uint4* __restrict__ v_host, int64_t host_stride,
                                                      int64_t n_host_rows, const uint4* __restrict__ v_hbm,
                                                      int64_t hbm_stride, uint4* __restrict__ vstage,
-                                                     int wgs, uint64_t* __restrict__ stamps, int first) {
+                                                     int wgs, uint64_t* __restrict__ stamps, int first,
+                                                     uint32_t* __restrict__ gpu_seq, uint32_t seq) {
   const int row = blockIdx.y, wg = blockIdx.x;
+  // hybrid value side: the kernel before this one on the stream left the host's inputs in pinned memory; a
+  // kernel starts only when its predecessor's stores are visible, so the first thing this one does is tell the host
+  if (gpu_seq != nullptr && row == 0 && wg == 0 && threadIdx.x == 0)
+    __hip_atomic_store(gpu_seq, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   // optional profiling: every workgroup leaves its start and end time (constant-rate wall clock)
   uint64_t* stamp = stamps ? stamps + ((int64_t)row * wgs + wg) * 2 : nullptr;
   if (stamp && threadIdx.x == 0) stamp[0] = wall_clock64();
@@ -331,11 +336,6 @@ __global__ __launch_bounds__(256) void attend_host_chunks(Layout L, const uint8_
   }
 }
 
-// Tells the host that everything enqueued before it on the stream is in place.
-__global__ void host_signal(uint32_t* gpu_seq, uint32_t seq) {
-  if (threadIdx.x == 0) __hip_atomic_store(gpu_seq, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-}
-
 // Table entry of one (group, centroid): the G query heads of the KV head, adjacent in memory.
 template <int G>
 __device__ __forceinline__ void load_entry(const float* p, float (&e)[G]) {
@@ -523,9 +523,11 @@ static hipEvent_t next_event(hipError_t* err) {
 int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
                       const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
                       int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps, int first_entry,
-                      const Tuning* tune) {
+                      const Tuning* tune, const HostShare* hs) {
   AttendWs a;
   carve(&a, ws, L, k);
+  uint32_t* gpu_seq = hs != nullptr ? hs->gpu_seq : nullptr;
+  const uint32_t seq = hs != nullptr ? hs->seq : 0u;
   const Tuning& tn = tune != nullptr ? *tune : tuning();
   int64_t wgs = ((int64_t)k + 15) / 16;                  // one workgroup per 16 rows at most
   // per (sequence, KV head).  About 64 workgroups in total keep enough reads in flight to fill the host
@@ -537,7 +539,7 @@ int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count,
   const uint4 *vh = (const uint4*)v_host, *vd = (const uint4*)v_hbm;
 #define HCA_GATHER(U)                                                                                              \
   gather_values<U><<<g, 256, 0, st>>>(idx, count, k, pos, L.cap, vh, host_stride, n_host_rows, vd, hbm_stride, \
-                                      (uint4*)a.vstage, (int)wgs, stamps, first_entry)
+                                      (uint4*)a.vstage, (int)wgs, stamps, first_entry, gpu_seq, seq)
   if (tn.gather_unroll >= 4) HCA_GATHER(4);
   else if (tn.gather_unroll >= 2) HCA_GATHER(2);
   else HCA_GATHER(1);
@@ -594,7 +596,6 @@ int32_t launch_attend_host_chunks(const Layout& L, const void* kcache, const voi
   else
     attend_host_chunks<2><<<gp, 256, 0, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, idx, count, k, pos,
                                               n_host_rows, (const uint16_t*)v_hbm, hbm_stride, sm_scale, a, ns, hs);
-  host_signal<<<1, 64, 0, st>>>(hs.gpu_seq, hs.seq);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

@@ -31,6 +31,11 @@ struct Tuning {
   int score_bpw = 0;       // 1 KiB code blocks per wave (0 = automatic; else kScoreBpwMin .. kScoreBpwMax)
   int score_depth = 0;     // blocks fetched ahead per wave (4 or 8; 0 = 8 for 4-bit codes, 4 for 2-bit)
   int host_spin_us = 100;  // how long the host-sum workers poll for the next call before they sleep
+  int host_isa = 0;        // host_chunk_sum: 0 = the widest vector form the CPU has, 2 = the AVX2 form
+  int select_wg = 0;       // threads per workgroup of the selection over the candidate lists: 1024 (pairs staged in
+                           // LDS, needs a whole compute unit) or 256 (pairs read from L2, fits beside a running
+                           // scan, but measured slower inside a decode step: its dependent passes crawl when a
+                           // scan keeps the memory system busy); 0 = 1024
 };
 Tuning& tuning();
 // Blocks per wave of the key scan.  The lower bound sizes the per-wave buffers of a launch (wall-clock stamps,
@@ -132,6 +137,24 @@ struct SelectStepNext {
 };
 int32_t launch_select_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
                            const SelectOut& so, hipStream_t st, uint64_t* stamps, const SelectStepNext& nx);
+int32_t launch_select_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
+                                const int64_t nmax[2], const SelectOut so[2], uint64_t* const stamps[2],
+                                const SelectStepNext nx[2], hipStream_t st);
+// the two layers of a pair launch, each with its selection workspace
+int32_t launch_select_scan_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2],
+                                     const NRes nr[2], const int64_t nmax[2], int32_t k, void* const ws[2], hipStream_t st,
+                                     uint64_t* const stamps[2], const SelectStepNext nx[2]);
+// the start of a step as two launches: sampling of up to four layers, threshold + append of up to two
+int32_t launch_select_begin_samples(const Layout& L, int n, const void* const kcache[], const void* const q[],
+                                    const NRes nr[], const SelectOut so[], hipStream_t st);
+int32_t launch_select_begin_rank_append(const Layout& L, int n, void* const kcache[], const void* const k_new[],
+                                        const NRes nr_before[], float* const acc[], int32_t* const pos[],
+                                        int64_t vrow0, int32_t k, const SelectOut so[], hipStream_t st);
+int32_t launch_select_rescan_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
+                                  const int64_t nmax[2], const SelectOut so[2], hipStream_t st);
+int32_t launch_select_finish_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
+                                  const int64_t nmax[2], int32_t k, int32_t* const idx[2], int32_t* const count[2],
+                                  void* const ws[2], hipStream_t st);
 // the SelectOut view of a selection workspace for rows of at most nmax_before slots (before the step's append)
 SelectOut select_view(const Layout& L, void* ws, int64_t nmax_before, int32_t k);
 int32_t launch_select_scan_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
@@ -146,7 +169,7 @@ int32_t launch_select_threshold(const Layout& L, const void* kcache, const void*
 int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
                             void* ws, hipStream_t st, uint64_t* stamps = nullptr);
 int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
-                             int32_t* idx, int32_t* count, void* ws, hipStream_t st);
+                             int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool small_wg = false);
 int32_t launch_select_report(const Layout& L, const NRes& nr, int64_t nmax, void* ws, int32_t* candidates,
                              int32_t* rescanned, hipStream_t st);
 int32_t launch_score_topk(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
@@ -158,11 +181,13 @@ int32_t launch_attend(const Layout& L, const void* kcache, const void* q, const 
                       const int32_t* count, int32_t k, const int32_t* pos, const void* v_host,
                       int64_t host_stride, int64_t n_host_rows, const void* v_hbm, int64_t hbm_stride,
                       float sm_scale, float* y, float* acc_opt, void* ws, hipStream_t gst, hipStream_t st);
+struct HostShare;
 // first_entry: selected entries below it are left out (the host share of the value side sums them in place)
 int32_t launch_gather(const Layout& L, const int32_t* idx, const int32_t* count, int32_t k, const int32_t* pos,
                       const void* v_host, int64_t host_stride, int64_t n_host_rows, const void* v_hbm,
                       int64_t hbm_stride, void* ws, hipStream_t st, uint64_t* stamps = nullptr, int first_entry = 0,
-                      const Tuning* tn = nullptr);     // tn: launch-shape knobs (null: the process-wide ones)
+                      const Tuning* tn = nullptr,      // tn: launch-shape knobs (null: the process-wide ones)
+                      const HostShare* hs = nullptr);  // hs: the launch also signals the host (hs->gpu_seq = hs->seq)
 // (start, end) pairs a gather launch writes into `stamps` at most
 constexpr int kGatherStampPairs = 1024;
 constexpr int kAttendChunk = 256;   // selected tokens per chunk of the attend kernels
@@ -186,7 +211,8 @@ int host_share_chunks(int32_t k, int want);          // `want` clipped to the ch
 size_t host_share_p_bytes(const Layout& L, int chunks);
 size_t host_share_vrow_bytes(const Layout& L, int chunks);
 size_t host_share_py_bytes(const Layout& L, int chunks);
-// logits, chunk partials and the host's inputs of the first hs.chunks chunks of every row, then the signal
+// logits, chunk partials and the host's inputs of the first hs.chunks chunks of every row; the signal to the
+// host comes from the next kernel on the stream (launch_gather with the same hs)
 int32_t launch_attend_host_chunks(const Layout& L, const void* kcache, const void* q, const int32_t* idx,
                                   const int32_t* count, int32_t k, const int32_t* pos, int64_t n_host_rows,
                                   const void* v_hbm, int64_t hbm_stride, float sm_scale, void* ws, const HostShare& hs,

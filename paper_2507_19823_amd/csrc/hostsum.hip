@@ -78,9 +78,56 @@ constexpr auto sum_range = sum_range_avx2;
 constexpr auto sum_range = sum_range_plain;
 #endif
 
+#if defined(__x86_64__)
+// AVX-512 form of host_chunk_sum (chosen at run time when the CPU has it; this translation unit is built for
+// AVX2).  Two passes over the chunk's rows, one per 128-byte half of a value row (64 channels): the partial sums
+// of the four query heads for those 64 channels stay in 16 registers for the whole pass, so a token costs one
+// conversion and four multiply-adds per 16 channels and no traffic to the accumulators.  The halves are
+// different cache lines, so nothing is fetched twice; rows are asked for well ahead of use.
+__attribute__((target("avx512f,avx512vl,avx512bw,f16c,fma"))) static int chunk_sum_avx512(
+    int G, const float* p, const int32_t* vrow, const uint16_t* v_row0, int64_t n_rows, float* py) {
+  constexpr int kAhead = 24;
+  int bad = 0;
+  for (int half = 0; half < 2; ++half) {
+    __m512 acc[4][4];
+    for (int h = 0; h < 4; ++h)
+      for (int c = 0; c < 4; ++c) acc[h][c] = _mm512_setzero_ps();
+    const uint16_t* base = v_row0 + half * 64;
+    for (int i = 0; i < kAttendChunk; ++i) {
+      if (i + kAhead < kAttendChunk) {
+        const int32_t rn = vrow[i + kAhead];
+        if (rn >= 0 && rn < n_rows) {
+          const char* nx = reinterpret_cast<const char*>(base + (int64_t)rn * kHeadDim);
+          _mm_prefetch(nx, _MM_HINT_T0);
+          _mm_prefetch(nx + 64, _MM_HINT_T0);
+        }
+      }
+      const int32_t r = vrow[i];
+      if (r < 0) continue;
+      if (r >= n_rows) { bad += half == 0; continue; }
+      const __m256i* v = reinterpret_cast<const __m256i*>(base + (int64_t)r * kHeadDim);
+      __m512 vf[4];
+      for (int c = 0; c < 4; ++c) vf[c] = _mm512_cvtph_ps(_mm256_loadu_si256(v + c));
+      for (int h = 0; h < G; ++h) {
+        const __m512 wh = _mm512_set1_ps(p[h * kAttendChunk + i]);
+        for (int c = 0; c < 4; ++c) acc[h][c] = _mm512_fmadd_ps(wh, vf[c], acc[h][c]);
+      }
+    }
+    for (int h = 0; h < 4; ++h)
+      for (int c = 0; c < 4; ++c) _mm512_storeu_ps(py + h * kHeadDim + half * 64 + 16 * c, acc[h][c]);
+  }
+  return bad;
+}
+#endif
+
 // One chunk of the host share of a decode step (the step driver's worker threads call this): fp32 weights
 // p[h][i] (relative to the chunk's maximum; the GPU merges the chunks), value rows read where they live.
 int host_chunk_sum(int G, const float* p, const int32_t* vrow, const uint16_t* v_row0, int64_t n_rows, float* py) {
+#if defined(__x86_64__)
+  static const bool has512 = __builtin_cpu_supports("avx512f") && __builtin_cpu_supports("avx512vl") &&
+                             __builtin_cpu_supports("avx512bw");
+  if (has512 && tuning().host_isa != 2) return chunk_sum_avx512(G, p, vrow, v_row0, n_rows, py);
+#endif
   alignas(64) float acc[4 * kHeadDim];
   std::memset(acc, 0, sizeof(acc));
   int bad = 0;
@@ -297,5 +344,13 @@ extern "C" int32_t hca_host_prefault(const void* ptr, size_t bytes, int32_t n_th
   walk(0, per < pages ? per : pages);
   for (auto& t : th) t.join();
   return HCA_OK;
+}
+
+// Test / debug: one chunk of the hybrid value side's host work (what a worker thread of the step driver does).
+extern "C" int32_t hca_debug_host_chunk_sum(int32_t gqa, const float* p, const int32_t* vrow, const void* v_rows,
+                                            int64_t n_rows, float* py) {
+  if (gqa < 1 || gqa > 4 || p == nullptr || vrow == nullptr || v_rows == nullptr || py == nullptr || n_rows < 0)
+    return HCA_ERR_BAD_ARG;
+  return host_chunk_sum(gqa, p, vrow, (const uint16_t*)v_rows, n_rows, py);
 }
 

@@ -24,7 +24,7 @@ namespace hca {
 // every job (claiming whatever chunks are still unclaimed), so no queue is ever reordered.
 class HostSide {
  public:
-  static constexpr int kSlots = 4, kRing = 1024;
+  static constexpr int kSlots = HCA_PIPELINE_MAX_PIPE, kRing = 1024;
   struct Job {
     uint32_t seq = 0;
     int slot = 0, chunks = 0;         // chunks per row of this job (<= the pipeline's host_chunks: k may be small)
@@ -206,9 +206,9 @@ class HostSide {
   std::atomic<int64_t> job_ns_{0}, task_ns_{0}, jobs_done_{0}, tasks_done_{0};
   Layout L_;
   int chunks_, nthreads_;
-  float* p_[kSlots] = {nullptr, nullptr, nullptr, nullptr};
-  int32_t* vrow_[kSlots] = {nullptr, nullptr, nullptr, nullptr};
-  float* py_[kSlots] = {nullptr, nullptr, nullptr, nullptr};
+  float* p_[kSlots] = {};
+  int32_t* vrow_[kSlots] = {};
+  float* py_[kSlots] = {};
   unsigned char* flags_ = nullptr;
   std::unique_ptr<Job[]> jobs_;
   std::unique_ptr<std::atomic<uint32_t>[]> progress_;
@@ -232,7 +232,13 @@ struct hca_pipeline {
   bool sel_waits;                   // fewer score buffers than layers: the scan waits for the buffer's last top-k
   std::vector<hipEvent_t> score_done, sel_free;
   int timing_stride;
-  hipEvent_t topk_done[4], gather_done[4], pipe_free[4];
+  hipEvent_t topk_done[HCA_PIPELINE_MAX_PIPE], gather_done[HCA_PIPELINE_MAX_PIPE], pipe_free[HCA_PIPELINE_MAX_PIPE];
+  int n_pipe;                       // sets of selection / staging buffers in use
+  hipEvent_t slot_free[HCA_PIPELINE_MAX_PIPE];   // what frees each set: the layer_done of the layer that used it last,
+                                    // or the set's pipe_free when that layer's layer_done comes later (sliced
+                                    // eviction); null: never used
+  bool dual;                        // fused selection on two streams: even layers on stream_scan, odd on stream_topk
+  bool pair;                        // fused selection, one scan launch per two layers
   std::vector<hipEvent_t> layer_done;
   std::vector<hipEvent_t> t0, t1;   // timing events around the scan launches: [slots][layers]
   int timing_slots;
@@ -262,7 +268,13 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   const bool fused = desc->fused_select != 0;
   for (int i = 0; i < desc->n_sel; ++i) if ((fused ? desc->ws_select[i] : (void*)desc->sel[i]) == nullptr) return nullptr;
   if (fused && (desc->vq_groups != 0 || desc->topp_tau > 0.0)) return nullptr;   // uniform codes and top-k only
-  for (int i = 0; i < 4; ++i)
+  // two scan streams: only with the fused selection, and with enough selection workspaces that the three layers a
+  // launch touches on either stream never share one
+  if (desc->dual_scan < 0 || desc->dual_scan > 2) return nullptr;
+  if (desc->dual_scan != 0 && (!fused || (desc->n_sel < 6 && desc->n_sel < n_layers))) return nullptr;
+  const int n_pipe = desc->n_pipe == 0 ? 4 : desc->n_pipe;
+  if (n_pipe < 4 || n_pipe > HCA_PIPELINE_MAX_PIPE) return nullptr;
+  for (int i = 0; i < n_pipe; ++i)
     if (desc->idx[i] == nullptr || desc->count[i] == nullptr || desc->ws_attend[i] == nullptr) return nullptr;
   if (desc->ws_topk == nullptr) return nullptr;
   if (desc->vq_groups != 0) {                // codebook form: same limits as the hca_vq_* calls; eviction in place
@@ -278,11 +290,16 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   if (desc->gather_wgs < 0 || desc->gather_wgs > 1024 || desc->gather_unroll < 0 || desc->gather_unroll > 4) return nullptr;
   if (desc->score_bpw != 0 && (desc->score_bpw < kScoreBpwMin || desc->score_bpw > kScoreBpwMax)) return nullptr;
   if (!(desc->score_depth == 0 || desc->score_depth == 4 || desc->score_depth == 8)) return nullptr;
+  if (!(desc->select_wg == 0 || desc->select_wg == 256 || desc->select_wg == 1024)) return nullptr;
   hca_pipeline* p = new hca_pipeline();
   p->L = L;
   p->n_layers = n_layers;
   p->d = *desc;
   p->timing_slots = timing_slots;
+  p->n_pipe = n_pipe;
+  for (int i = 0; i < HCA_PIPELINE_MAX_PIPE; ++i) p->slot_free[i] = nullptr;
+  p->dual = desc->dual_scan == 1;
+  p->pair = desc->dual_scan == 2;
   p->n_sel = desc->n_sel < n_layers ? desc->n_sel : n_layers;
   p->sel_waits = desc->n_sel < n_layers;
   p->timing_stride = desc->timing_layer_stride > 1 ? desc->timing_layer_stride : 1;
@@ -291,6 +308,7 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   if (desc->gather_unroll > 0) p->tune.gather_unroll = desc->gather_unroll;
   if (desc->score_bpw > 0) p->tune.score_bpw = desc->score_bpw;
   if (desc->score_depth > 0) p->tune.score_depth = desc->score_depth;
+  if (desc->select_wg > 0) p->tune.select_wg = desc->select_wg;
   p->host_chunks = desc->host_chunks;
   // ~2 us per poll over the host link: about a second before a merge gives up on the host
   p->host_spin_limit = desc->host_spin_limit > 0 ? desc->host_spin_limit : (1 << 19);
@@ -299,7 +317,7 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   bool ok = true;
   auto mk = [&](hipEvent_t* e, unsigned flags) { ok = ok && hipEventCreateWithFlags(e, flags) == hipSuccess; };
   for (int i = 0; i < p->n_sel; ++i) { mk(&p->score_done[i], hipEventDisableTiming); mk(&p->sel_free[i], hipEventDisableTiming); }
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < HCA_PIPELINE_MAX_PIPE; ++i) {
     mk(&p->topk_done[i], hipEventDisableTiming);
     mk(&p->gather_done[i], hipEventDisableTiming);
     mk(&p->pipe_free[i], hipEventDisableTiming);
@@ -330,7 +348,7 @@ void hca_pipeline_destroy(hca_pipeline* p) {
   }
   for (auto e : p->score_done) (void)hipEventDestroy(e);
   for (auto e : p->sel_free) (void)hipEventDestroy(e);
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < HCA_PIPELINE_MAX_PIPE; ++i) {
     (void)hipEventDestroy(p->topk_done[i]);
     (void)hipEventDestroy(p->gather_done[i]);
     (void)hipEventDestroy(p->pipe_free[i]);
@@ -381,7 +399,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (p->host_chunks > 0 && (ly.v_host == nullptr || n_host_rows < 1)) return HCA_ERR_BAD_ARG;  // the host sums from v_host
   }
   const int hchunks = p->host ? host_share_chunks(k, p->host_chunks) : 0;
-  hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk;
+  const hipStream_t sa = (hipStream_t)p->d.stream_scan, sb = (hipStream_t)p->d.stream_topk, sb_topk = sb;
   hipStream_t sg = (hipStream_t)p->d.stream_gather, sc = (hipStream_t)p->d.stream_attend;
   NRes vrow0;
   for (int b = 0; b < kMaxBatch; ++b) vrow0.n[b] = value_row0;
@@ -418,23 +436,118 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     return HCA_OK;
   };
   // before anything of this step touches layer l2's cache or its selection workspace
+  // Two scan streams (desc.dual_scan): even layers run append + scan + selection on stream_scan, odd layers on
+  // stream_topk, each stream a chain of its own (a launch carries the threshold + append of the layer two on and
+  // the sampling of the layer four on), so that one stream's scan fills the time the other spends between two
+  // of its scans (launch gap, selection) and the key stream from HBM does not pause.
+  // Paired launches (desc.dual_scan == 2): the same two chains, but layers l and l + 1 (l even) share one launch
+  // on stream_scan, and their selections follow each other on stream_topk.
+  const int S = (p->dual || p->pair) ? 2 : 1;
+  auto scan_stream = [&](int l2) -> hipStream_t { return (p->dual && (l2 & 1)) ? sb : sa; };
   auto wait_layer = [&](int l2) -> int32_t {
-    if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[l2 % p->n_sel], 0));
-    HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l2], 0));
+    if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(scan_stream(l2), p->sel_free[l2 % p->n_sel], 0));
+    HCA_HIP(hipStreamWaitEvent(scan_stream(l2), p->layer_done[l2], 0));
     return HCA_OK;
   };
-  if (fused) {
-    for (int l2 = 0; l2 < 2 && l2 < p->n_layers; ++l2) {
+  bool begun = false;                      // the chains' first layers already have their threshold + append
+  if (fused && !p->dual) {
+    // one stream carries every chain: the step starts with two launches, the sampling of the first layers of
+    // every chain and the threshold + append of the chains' first layers
+    const int ns = 2 * S < p->n_layers ? 2 * S : p->n_layers, nt = S < p->n_layers ? S : p->n_layers;
+    const void* kc[4];
+    const void* qq[4];
+    NRes nrs[4];
+    SelectOut sos[4];
+    for (int l2 = 0; l2 < ns; ++l2) {
+      int64_t m2;
+      int32_t rc = lengths(l2, &nrs[l2], &m2);
+      if (rc != HCA_OK) return rc;
+      rc = wait_layer(l2);
+      if (rc != HCA_OK) return rc;
+      kc[l2] = layers[l2].kcache;
+      qq[l2] = layers[l2].q;
+      sos[l2] = select_view(L, p->d.ws_select[l2 % p->n_sel], m2, k);
+    }
+    int32_t rc = launch_select_begin_samples(L, ns, kc, qq, nrs, sos, sa);
+    if (rc != HCA_OK) return rc;
+    void* kcw[2];
+    const void* kn[2];
+    float* accs[2];
+    int32_t* poss[2];
+    for (int l2 = 0; l2 < nt; ++l2) {
+      kcw[l2] = layers[l2].kcache;
+      kn[l2] = layers[l2].k_new;
+      accs[l2] = layers[l2].acc;
+      poss[l2] = layers[l2].pos;
+    }
+    rc = launch_select_begin_rank_append(L, nt, kcw, kn, nrs, accs, poss, value_row0, k, sos, sa);
+    if (rc != HCA_OK) return rc;
+    begun = true;
+  } else if (fused) {
+    for (int l2 = 0; l2 < 2 * S && l2 < p->n_layers; ++l2) {
       NRes n2;
       int64_t m2;
       int32_t rc = lengths(l2, &n2, &m2);
       if (rc != HCA_OK) return rc;
       rc = wait_layer(l2);
       if (rc != HCA_OK) return rc;
-      rc = launch_select_samples(L, layers[l2].kcache, layers[l2].q, n2, m2, k, p->d.ws_select[l2 % p->n_sel], sa);
+      rc = launch_select_samples(L, layers[l2].kcache, layers[l2].q, n2, m2, k, p->d.ws_select[l2 % p->n_sel],
+                                 scan_stream(l2));
       if (rc != HCA_OK) return rc;
     }
   }
+  // What the fused scan launch of a layer needs: its lengths after the append, its stamp area, and the jobs it
+  // carries for the layers behind it on its chain.  Enqueues what has to precede the launch (the first layers'
+  // own threshold + append, the waits for the layer whose sampling rides along) and moves the host's lengths on.
+  struct FusedCtx { NRes nr; int64_t nmax = 0; uint64_t* stamps = nullptr; SelectStepNext nx; };
+  auto fused_prepare = [&](int l, FusedCtx* c) -> int32_t {
+    hca_layer& ly = layers[l];
+    int64_t* nl = n_resident + (int64_t)l * L.batch;
+    const hipStream_t st = scan_stream(l);
+    int32_t rc = load_nres(L, nl, &c->nr, &c->nmax);
+    if (rc != HCA_OK) return rc;
+    // (the waits for this layer's buffers went out before its sampling; its threshold and append rode on an
+    // earlier launch of its chain, except for the chain's first layer)
+    if (l < S && !begun) {
+      rc = launch_select_threshold_append(L, ly.kcache, ly.k_new, c->nr, c->nmax, ly.acc, ly.pos, vrow0, k,
+                                          p->d.ws_select[l % p->n_sel], st);
+      if (rc != HCA_OK) return rc;
+    }
+    for (int b = 0; b < L.batch; ++b) { c->nr.n[b] += 1; nl[b] += 1; }
+    c->nmax += 1;
+    if (timing_slot >= 0 && p->d.scan_stamps != nullptr)
+      c->stamps = (uint64_t*)p->d.scan_stamps + ((int64_t)timing_slot * p->n_layers + l) * p->d.scan_stamp_pairs * 2;
+    SelectStepNext& nx = c->nx;
+    nx.k = k;
+    if (l + S < p->n_layers) {
+      hca_layer& ya = layers[l + S];
+      int64_t ma;
+      rc = lengths(l + S, &nx.a_nr, &ma);
+      if (rc != HCA_OK) return rc;
+      nx.a_kcache = ya.kcache;
+      nx.a_k_new = ya.k_new;
+      nx.a_acc = ya.acc;
+      nx.a_pos = ya.pos;
+      nx.a_vrow0 = value_row0;
+      nx.a_so = select_view(L, p->d.ws_select[(l + S) % p->n_sel], ma, k);
+    }
+    if (l + 2 * S < p->n_layers) {
+      int64_t mb;
+      rc = lengths(l + 2 * S, &nx.b_nr, &mb);
+      if (rc != HCA_OK) return rc;
+      rc = wait_layer(l + 2 * S);
+      if (rc != HCA_OK) return rc;
+      nx.b_kcache = layers[l + 2 * S].kcache;
+      nx.b_q = layers[l + 2 * S].q;
+      nx.b_so = select_view(L, p->d.ws_select[(l + 2 * S) % p->n_sel], mb, k);
+    }
+    return HCA_OK;
+  };
+  FusedCtx second;                         // the pair's second layer, until its own turn in the loop
+  int second_layer = -1;
+  bool have_second = false;
+  bool pair_selected = false;              // the pair's second layer already has its selection enqueued
+  int pair_selected_layer = -1;
   for (int l = 0; l < p->n_layers; ++l) {
     hca_layer& ly = layers[l];
     int64_t* nl = n_resident + (int64_t)l * L.batch;
@@ -442,27 +555,59 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
         ly.y == nullptr)
       return HCA_ERR_BAD_ARG;
     if (vq && (ly.vq_centroids == nullptr || ly.vq_lut == nullptr)) return HCA_ERR_BAD_ARG;
+    const int s3 = l % p->n_sel, s4 = l % p->n_pipe;
+    const hipStream_t sa = scan_stream(l);           // this layer's scan stream ...
+    const hipStream_t sb = p->dual ? sa : sb_topk;   // ... and the stream of its selection
     NRes nr;
     int64_t nmax;
-    int32_t rc = load_nres(L, nl, &nr, &nmax);
-    if (rc != HCA_OK) return rc;
-    for (int b = 0; b < L.batch; ++b)
-      if (!fused && nr.n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;   // fused: checked when the append was enqueued
-    const int s3 = l % p->n_sel, s4 = l % 4;
-    const bool timed = timing_slot >= 0 && l % p->timing_stride == 0;
+    int32_t rc = HCA_OK;
     // stage 1: append + key scan
-    // top-k of the previous user of this score buffer (with a buffer per layer that is this layer's own
-    // previous step, which layer_done covers)
     if (fused) {
-      // (the waits for this layer's buffers went out before its sampling; its threshold and append rode on the
-      // previous layer's launch, except for the step's first layer)
-      if (l == 0) {
-        rc = launch_select_threshold_append(L, ly.kcache, ly.k_new, nr, nmax, ly.acc, ly.pos, vrow0, k, p->d.ws_select[s3], sa);
+      if (have_second && second_layer == l) {
+        // second layer of a pair: its scan went out with the first layer's, and the top-k stream already waits for it
+        nr = second.nr;
+        nmax = second.nmax;
+        have_second = false;
+      } else {
+        FusedCtx c0, c1;
+        rc = fused_prepare(l, &c0);
         if (rc != HCA_OK) return rc;
+        const bool timed = timing_slot >= 0 && l % p->timing_stride == 0;
+        if (timed) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
+        if (p->pair && l + 1 < p->n_layers) {
+          rc = fused_prepare(l + 1, &c1);
+          if (rc != HCA_OK) return rc;
+          const void* const kc2[2] = {layers[l].kcache, layers[l + 1].kcache};
+          const void* const q2[2] = {layers[l].q, layers[l + 1].q};
+          const NRes nr2[2] = {c0.nr, c1.nr};
+          const int64_t nm2[2] = {c0.nmax, c1.nmax};
+          void* const ws2[2] = {p->d.ws_select[s3], p->d.ws_select[(l + 1) % p->n_sel]};
+          uint64_t* const st2[2] = {c0.stamps, c1.stamps};
+          const SelectStepNext nx2[2] = {c0.nx, c1.nx};
+          rc = launch_select_scan_step_pair(L, kc2, q2, nr2, nm2, k, ws2, sa, st2, nx2);
+          second = c1;
+          second_layer = l + 1;
+          have_second = true;
+        } else {
+          rc = launch_select_scan_step(L, ly.kcache, ly.q, c0.nr, c0.nmax, k, p->d.ws_select[s3], sa, c0.stamps, c0.nx);
+        }
+        if (rc != HCA_OK) return rc;
+        if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
+        if (sb != sa) {
+          HCA_HIP(hipEventRecord(p->score_done[s3], sa));
+          HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
+        }
+        nr = c0.nr;
+        nmax = c0.nmax;
       }
-      for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
-      nmax += 1;
     } else {
+      rc = load_nres(L, nl, &nr, &nmax);
+      if (rc != HCA_OK) return rc;
+      for (int b = 0; b < L.batch; ++b)
+        if (nr.n[b] + 1 > L.cap) return HCA_ERR_CAPACITY;
+      const bool timed = timing_slot >= 0 && l % p->timing_stride == 0;
+      // top-k of the previous user of this score buffer (with a buffer per layer that is this layer's own
+      // previous step, which layer_done covers)
       if (p->sel_waits) HCA_HIP(hipStreamWaitEvent(sa, p->sel_free[s3], 0));
       HCA_HIP(hipStreamWaitEvent(sa, p->layer_done[l], 0));    // this layer's attend / evict of the previous step
       rc = vq ? launch_vq_assign(L, vg, vc, ly.vq_centroids, (uint8_t*)ly.kcache, ly.k_new, 1, nr, ly.acc, ly.pos, vrow0, sa)
@@ -470,51 +615,48 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       if (rc != HCA_OK) return rc;
       for (int b = 0; b < L.batch; ++b) { nr.n[b] += 1; nl[b] += 1; }
       nmax += 1;
+      if (timed) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
+      uint64_t* stamps = nullptr;
+      if (!vq && timing_slot >= 0 && p->d.scan_stamps != nullptr)
+        stamps = (uint64_t*)p->d.scan_stamps + ((int64_t)timing_slot * p->n_layers + l) * p->d.scan_stamp_pairs * 2;
+      rc = vq ? launch_vq_score(L, vg, vc, ly.vq_centroids, (const uint8_t*)ly.kcache, ly.q, nr, nmax, ly.vq_lut,
+                                p->d.sel[s3], nullptr, sa)
+              : launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps, &p->tune);
+      if (rc != HCA_OK) return rc;
+      if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
+      HCA_HIP(hipEventRecord(p->score_done[s3], sa));
+      HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
     }
-    if (timed) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
-    uint64_t* stamps = nullptr;
-    if (!vq && timing_slot >= 0 && p->d.scan_stamps != nullptr) {
-      if (p->d.scan_stamp_pairs < score_stamp_pairs(L, nmax)) return HCA_ERR_CAPACITY;
-      stamps = (uint64_t*)p->d.scan_stamps + ((int64_t)timing_slot * p->n_layers + l) * p->d.scan_stamp_pairs * 2;
-    }
-    auto fused_scan = [&]() -> int32_t {
-      SelectStepNext nx;
-      nx.k = k;
-      if (l + 1 < p->n_layers) {
-        hca_layer& ya = layers[l + 1];
-        int64_t ma;
-        const int32_t ra = lengths(l + 1, &nx.a_nr, &ma);
-        if (ra != HCA_OK) return ra;
-        nx.a_kcache = ya.kcache;
-        nx.a_k_new = ya.k_new;
-        nx.a_acc = ya.acc;
-        nx.a_pos = ya.pos;
-        nx.a_vrow0 = value_row0;
-        nx.a_so = select_view(L, p->d.ws_select[(l + 1) % p->n_sel], ma, k);
+    // stage 2: top-k.  The set of idx / count / staging buffers is free when the layer that used it last is done
+    // (its attend, and its eviction if it had one)
+    if (pair_selected && pair_selected_layer == l) {
+      pair_selected = false;                 // second layer of a pair: selected together with the first
+    } else if (fused && have_second && second_layer == l + 1) {
+      // first layer of a pair: one selection launch (and one pair of fall-back launches) for both layers
+      const int s3b = (l + 1) % p->n_sel, s4b = (l + 1) % p->n_pipe;
+      if (p->slot_free[s4] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4], 0));
+      if (p->slot_free[s4b] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4b], 0));
+      const void* const kc2[2] = {layers[l].kcache, layers[l + 1].kcache};
+      const void* const q2[2] = {layers[l].q, layers[l + 1].q};
+      const NRes nr2[2] = {nr, second.nr};
+      const int64_t nm2[2] = {nmax, second.nmax};
+      int32_t* const idx2[2] = {p->d.idx[s4], p->d.idx[s4b]};
+      int32_t* const cnt2[2] = {p->d.count[s4], p->d.count[s4b]};
+      void* const ws2[2] = {p->d.ws_select[s3], p->d.ws_select[s3b]};
+      rc = launch_select_finish_pair(L, kc2, q2, nr2, nm2, k, idx2, cnt2, ws2, sb);
+      if (rc != HCA_OK) return rc;
+      if (p->sel_waits) {
+        HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
+        HCA_HIP(hipEventRecord(p->sel_free[s3b], sb));
       }
-      if (l + 2 < p->n_layers) {
-        int64_t mb;
-        int32_t rb = lengths(l + 2, &nx.b_nr, &mb);
-        if (rb != HCA_OK) return rb;
-        rb = wait_layer(l + 2);
-        if (rb != HCA_OK) return rb;
-        nx.b_kcache = layers[l + 2].kcache;
-        nx.b_q = layers[l + 2].q;
-        nx.b_so = select_view(L, p->d.ws_select[(l + 2) % p->n_sel], mb, k);
-      }
-      return launch_select_scan_step(L, ly.kcache, ly.q, nr, nmax, k, p->d.ws_select[s3], sa, stamps, nx);
-    };
-    rc = vq ? launch_vq_score(L, vg, vc, ly.vq_centroids, (const uint8_t*)ly.kcache, ly.q, nr, nmax, ly.vq_lut,
-                              p->d.sel[s3], nullptr, sa)
-         : fused ? fused_scan()
-                 : launch_score(L, ly.kcache, ly.q, nr, nmax, p->d.sel[s3], nullptr, sa, stamps, &p->tune);
-    if (rc != HCA_OK) return rc;
-    if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
-    HCA_HIP(hipEventRecord(p->score_done[s3], sa));
-    // stage 2: top-k
-    HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
-    HCA_HIP(hipStreamWaitEvent(sb, p->pipe_free[s4], 0));    // attend of the previous user of idx / staging
-    rc = fused ? launch_select_finish(L, ly.kcache, ly.q, nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_select[s3], sb)
+      HCA_HIP(hipEventRecord(p->topk_done[s4], sb));
+      HCA_HIP(hipEventRecord(p->topk_done[s4b], sb));
+      pair_selected = true;
+      pair_selected_layer = l + 1;
+    } else {
+    if (p->slot_free[s4] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4], 0));
+    rc = fused ? launch_select_finish(L, ly.kcache, ly.q, nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_select[s3], sb,
+                                      p->tune.select_wg == 256)
          : p->d.topp_tau > 0.0
              ? launch_topp(L, p->d.sel[s3], nr, nmax, sm_scale, p->d.topp_tau, k, p->d.idx[s4], p->d.count[s4], nullptr,
                            p->d.ws_topk, sb)
@@ -522,6 +664,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     if (rc != HCA_OK) return rc;
     if (p->sel_waits) HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
     HCA_HIP(hipEventRecord(p->topk_done[s4], sb));
+    }
     // stage 3: host-link gather
     HCA_HIP(hipStreamWaitEvent(sg, p->topk_done[s4], 0));
     uint64_t* gstamps = nullptr;
@@ -541,7 +684,8 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       p->host->publish(seq, s4, hchunks, ly.v_host, host_stride, n_host_rows);
     }
     rc = launch_gather(L, p->d.idx[s4], p->d.count[s4], k, ly.pos, ly.v_host, host_stride, n_host_rows, ly.v_hbm,
-                       hbm_stride, p->d.ws_attend[s4], sg, gstamps, hchunks * kAttendChunk, &p->tune);
+                       hbm_stride, p->d.ws_attend[s4], sg, gstamps, hchunks * kAttendChunk, &p->tune,
+                       hchunks > 0 ? &hs : nullptr);
     if (rc != HCA_OK) return rc;
     HCA_HIP(hipEventRecord(p->gather_done[s4], sg));
     // stage 4: attend (+ eviction into the spare buffers, which then swap with the layer's)
@@ -552,7 +696,6 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
                                      p->d.ws_attend[s4], sc, nullptr, hchunks > 0 ? &hs : nullptr);
     if (rc != HCA_OK) return rc;
     const int64_t M = evict_M != nullptr ? evict_M[l] : 0;
-    HCA_HIP(hipEventRecord(p->pipe_free[s4], sc));
     bool starts_job = false;
     if (M != 0) {
       bool any = false;
@@ -575,6 +718,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
         }
         job.active = true; job.layer = l; job.next_slice = 0; job.nr = nr; job.nmax = nmax; job.M = M;
         starts_job = true;
+        HCA_HIP(hipEventRecord(p->pipe_free[s4], sc));     // the set is free now; layer_done comes with the last slice
         for (int b = 0; b < L.batch; ++b) if (nl[b] > M) nl[b] = M;
       }
     }
@@ -582,7 +726,12 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       rc = advance(job);
       if (rc != HCA_OK) return rc;
     }
-    if (!starts_job) HCA_HIP(hipEventRecord(p->layer_done[l], sc));   // else the job's last slice records it
+    if (!starts_job) {
+      HCA_HIP(hipEventRecord(p->layer_done[l], sc));
+      p->slot_free[s4] = p->layer_done[l];
+    } else {                               // the job's last slice records layer_done
+      p->slot_free[s4] = p->pipe_free[s4];
+    }
   }
   while (job.active) {                     // the step ends with every started eviction fully enqueued
     int32_t rc = advance(job);
@@ -621,7 +770,8 @@ int32_t hca_pipeline_scan_ms(hca_pipeline* p, int32_t timing_slot, float* ms) {
   for (int l = 0; l < p->n_layers; ++l) {
     const size_t i = (size_t)timing_slot * p->n_layers + l;
     ms[l] = -1.0f;                                    // layers without a bracket
-    if (l % p->timing_stride == 0) HCA_HIP(hipEventElapsedTime(&ms[l], p->t0[i], p->t1[i]));
+    // (paired launches: the bracket of an even layer holds the launch it shares with the next layer)
+    if (l % p->timing_stride == 0 && !(p->pair && (l & 1))) HCA_HIP(hipEventElapsedTime(&ms[l], p->t0[i], p->t1[i]));
   }
   return HCA_OK;
 }

@@ -7,6 +7,8 @@
 
 namespace hca {
 
+struct NRes32 { int32_t n[kMaxBatch]; };   // row lengths as kernel arguments of the paired launches
+
 // max of two finite floats (plain v_max_f32: the inputs are never NaN, so no canonicalisation)
 __device__ __forceinline__ float fmax_raw(float a, float b) {
   float r;
@@ -57,18 +59,16 @@ __device__ __forceinline__ uint4 allgather_rows(uint32_t v) {
 // bx = the workgroup's chunk of the row, gx = chunks per row (blockIdx.x and gridDim.x in the plain launch)
 template <int BITS, bool WRITE_Z, int U, bool LSE, bool SELECT>
 __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __restrict__ kcache,
-                                           const uint16_t* __restrict__ q, const NRes& nr, int bpw,
+                                           const uint16_t* __restrict__ q, const int64_t n, int bpw,
                                            float* __restrict__ sel, float* __restrict__ z,
                                            uint64_t* __restrict__ stamps, float sm_scale, float2* __restrict__ part,
-                                           const SelectOut& so, const int bx, const int gx) {
+                                           const SelectOut& so, const int bx, const int gx, const int row) {
   static_assert(U % 4 == 0, "stores are batched four tiles at a time");
   __shared__ QShared sh;
   // SELECT: every wave collects its qualifying pairs in slot order in its quarter of the dynamic LDS (room for
   // all the wave's slots), then the workgroup strings the four lists together
   extern __shared__ uint2 wlist_all[];
   __shared__ uint32_t wcount[8];
-  const int row = blockIdx.y;
-  const int64_t n = nr.n[row / L.n_kv_heads];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nblocks = (int)((n + L.tpb - 1) / L.tpb);
@@ -257,8 +257,8 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
                                                     float* __restrict__ sel, float* __restrict__ z,
                                                     uint64_t* __restrict__ stamps, float sm_scale = 0.f,
                                                     float2* __restrict__ part = nullptr, SelectOut so = SelectOut{}) {
-  score_body<BITS, WRITE_Z, U, LSE, SELECT>(L, kcache, q, nr, bpw, sel, z, stamps, sm_scale, part, so, (int)blockIdx.x,
-                                            (int)gridDim.x);
+  score_body<BITS, WRITE_Z, U, LSE, SELECT>(L, kcache, q, nr.n[blockIdx.y / L.n_kv_heads], bpw, sel, z, stamps, sm_scale,
+                                            part, so, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y);
 }
 
 // The selecting scan once more for the rows whose sampled threshold left too few pairs (spec[row][1] != 0, with
@@ -270,9 +270,33 @@ __global__ __launch_bounds__(256) void score_failed_rows_kernel(Layout L, const 
                                                                 int nchunks, SelectOut so) {
   if (so.spec[4 * blockIdx.y + 1] == 0) return;
   for (int bx = blockIdx.x; bx < nchunks; bx += gridDim.x) {
-    score_body<BITS, false, U, false, true>(L, kcache, q, nr, bpw, nullptr, nullptr, nullptr, 0.f, nullptr, so, bx, nchunks);
+    score_body<BITS, false, U, false, true>(L, kcache, q, nr.n[blockIdx.y / L.n_kv_heads], bpw, nullptr, nullptr, nullptr,
+                                            0.f, nullptr, so, bx, nchunks, (int)blockIdx.y);
     __syncthreads();                                        // the shared query image and counters are reused
   }
+}
+
+// The same for the two layers of a paired launch: grid.y = 2 x rows.
+struct RescanSide {
+  const uint8_t* kcache;
+  const uint16_t* q;
+  SelectOut so;
+  int32_t bpw, nchunks;
+  NRes32 nr;
+};
+template <int BITS, int U>
+__device__ __forceinline__ void rescan_side(const Layout& L, const RescanSide& s, const int row) {
+  if (s.so.spec[4 * row + 1] == 0) return;
+  for (int bx = blockIdx.x; bx < s.nchunks; bx += gridDim.x) {
+    score_body<BITS, false, U, false, true>(L, s.kcache, s.q, s.nr.n[row / L.n_kv_heads], s.bpw, nullptr, nullptr, nullptr,
+                                            0.f, nullptr, s.so, bx, s.nchunks, row);
+    __syncthreads();
+  }
+}
+template <int BITS, int U>
+__global__ __launch_bounds__(256) void score_failed_rows_pair_kernel(Layout L, RescanSide a, RescanSide b) {
+  if ((int)blockIdx.y < L.rows) rescan_side<BITS, U>(L, a, (int)blockIdx.y);
+  else rescan_side<BITS, U>(L, b, (int)blockIdx.y - L.rows);
 }
 
 // lse[row * G + h] = log sum exp over the first `live` wave pairs of the row (waves of workgroups that
@@ -327,7 +351,7 @@ constexpr int kSamplePerWg = 512;       // sampled slots per workgroup: m / 512 
 // bx = which of the m / kSamplePerWg workgroups of the row this is; called by all 256 threads
 template <int BITS>
 __device__ __forceinline__ void sample_score_body(const Layout& L, const uint8_t* __restrict__ kcache,
-                                                  const uint16_t* __restrict__ q, const NRes& nr,
+                                                  const uint16_t* __restrict__ q, const int64_t n,
                                                   uint32_t* __restrict__ samples, const int m, const int bx,
                                                   const int row) {
   constexpr int kTpb = BITS == 4 ? 16 : 32;
@@ -335,7 +359,6 @@ __device__ __forceinline__ void sample_score_body(const Layout& L, const uint8_t
   __shared__ QShared sh;
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int64_t n = nr.n[row / L.n_kv_heads];
   if (n <= 0) {                                             // nothing to sample: this workgroup's share reads "no slot"
     for (int i = threadIdx.x; i < kSamplePerWg; i += 256)
       samples[(int64_t)row * m + bx * kSamplePerWg + i] = 0;
@@ -389,7 +412,8 @@ __device__ __forceinline__ void sample_score_body(const Layout& L, const uint8_t
 template <int BITS>
 __global__ __launch_bounds__(256) void select_sample_score(Layout L, const uint8_t* __restrict__ kcache,
                                                            const uint16_t* __restrict__ q, NRes nr, SelectOut so) {
-  sample_score_body<BITS>(L, kcache, q, nr, so.samples, so.m_samples, (int)blockIdx.x, (int)blockIdx.y);
+  sample_score_body<BITS>(L, kcache, q, nr.n[blockIdx.y / L.n_kv_heads], so.samples, so.m_samples, (int)blockIdx.x,
+                          (int)blockIdx.y);
 }
 
 // 256 threads per row: small enough to find room on a chip that another stream's scan keeps full
@@ -534,7 +558,7 @@ __global__ __launch_bounds__(256) void score_select_step_kernel(Layout L, const 
   const int extra = nsb + (j.a_on ? 2 : 0);
   const int bx = blockIdx.x, row = blockIdx.y;
   if (bx < nsb) {
-    sample_score_body<BITS>(L, j.b_kcache, j.b_q, j.b_nr, j.b_samples, j.b_m, bx, row);
+    sample_score_body<BITS>(L, j.b_kcache, j.b_q, j.b_nr.n[row / L.n_kv_heads], j.b_samples, j.b_m, bx, row);
     return;
   }
   if (bx < extra) {
@@ -543,8 +567,149 @@ __global__ __launch_bounds__(256) void score_select_step_kernel(Layout L, const 
     else quantize_body<BITS>(L, j.a_kcache, j.a_k_new, 1, n_before, j.a_acc, j.a_pos, j.a_vrow0, 0, row);
     return;
   }
-  score_body<BITS, false, U, false, true>(L, kcache, q, nr, bpw, nullptr, nullptr, stamps, 0.f, nullptr, so, bx - extra,
-                                          (int)gridDim.x - extra);
+  score_body<BITS, false, U, false, true>(L, kcache, q, nr.n[row / L.n_kv_heads], bpw, nullptr, nullptr, stamps, 0.f,
+                                          nullptr, so, bx - extra, (int)gridDim.x - extra, row);
+}
+
+// Two layers in one launch (the step driver's paired form): grid.y = 2 x rows, the upper half belongs to the
+// second layer.  Each side is a complete score_select_step_kernel job with its own lengths, chunk count and
+// extra workgroups; a workgroup beyond its side's needs returns at once.  One launch instead of two halves
+// the pauses of the key stream between launches and the launch's tail is paid once for two layers.
+struct StepSide {
+  const uint8_t* kcache;          // the layer whose cache is scanned
+  const uint16_t* q;
+  uint64_t* stamps;
+  SelectOut so;
+  int32_t bpw, chunks;            // blocks per wave and chunks per row of this side's scan
+  NRes32 nr;
+  // threshold + append of the layer two on (a_on = 0: none)
+  uint8_t* a_kcache;
+  const uint16_t* a_k_new;
+  float* a_acc;
+  int32_t* a_pos;
+  const uint32_t* a_samples;
+  uint32_t* a_spec;
+  int64_t a_vrow0;
+  int32_t a_k, a_m, a_on;
+  // sampling of the layer four on (b_m = 0: none)
+  const uint8_t* b_kcache;
+  const uint16_t* b_q;
+  uint32_t* b_samples;
+  int32_t b_m;
+  NRes32 a_nr, b_nr;              // lengths before those layers' own appends
+};
+
+template <int BITS, int U>
+__device__ __forceinline__ void step_side(const Layout& L, const StepSide& s, const int row) {
+  const int nsb = s.b_m / kSamplePerWg;
+  const int extra = nsb + (s.a_on ? 2 : 0);
+  const int bx = blockIdx.x;
+  const int seq = row / L.n_kv_heads;
+  if (bx < nsb) {
+    sample_score_body<BITS>(L, s.b_kcache, s.b_q, s.b_nr.n[seq], s.b_samples, s.b_m, bx, row);
+    return;
+  }
+  if (bx < extra) {
+    const int64_t n_before = s.a_nr.n[seq];
+    if (bx == nsb) sample_rank_body(n_before + 1, s.a_k, s.a_samples, s.a_m, s.a_spec, row);
+    else quantize_body<BITS>(L, s.a_kcache, s.a_k_new, 1, n_before, s.a_acc, s.a_pos, s.a_vrow0, 0, row);
+    return;
+  }
+  if (bx - extra >= s.chunks) return;
+  score_body<BITS, false, U, false, true>(L, s.kcache, s.q, s.nr.n[seq], s.bpw, nullptr, nullptr, s.stamps, 0.f, nullptr,
+                                          s.so, bx - extra, s.chunks, row);
+}
+
+template <int BITS, int U>
+__global__ __launch_bounds__(256) void score_select_pair_kernel(Layout L, StepSide s0, StepSide s1) {
+  if ((int)blockIdx.y < L.rows) step_side<BITS, U>(L, s0, (int)blockIdx.y);
+  else step_side<BITS, U>(L, s1, (int)blockIdx.y - L.rows);
+}
+
+// The start of a decode step in two launches instead of one per layer and job: the sampling of the first layers
+// of every chain (up to four layers), then the threshold + append of the chains' first layers (up to two).
+struct BeginSample {
+  const uint8_t* kcache;
+  const uint16_t* q;
+  uint32_t* samples;
+  int32_t m;
+  NRes32 nr;
+};
+struct BeginSampleArgs { BeginSample s[4]; int32_t n; };
+template <int BITS>
+__global__ __launch_bounds__(256) void select_begin_samples(Layout L, BeginSampleArgs a) {
+  const int side = (int)blockIdx.y / L.rows, row = (int)blockIdx.y % L.rows;
+  const BeginSample& s = a.s[side];
+  if ((int)blockIdx.x >= s.m / kSamplePerWg) return;
+  sample_score_body<BITS>(L, s.kcache, s.q, s.nr.n[row / L.n_kv_heads], s.samples, s.m, (int)blockIdx.x, row);
+}
+struct BeginRank {
+  uint8_t* kcache;
+  const uint16_t* k_new;
+  float* acc;
+  int32_t* pos;
+  const uint32_t* samples;
+  uint32_t* spec;
+  int64_t vrow0;
+  int32_t k, m;
+  NRes32 nr_before;
+};
+struct BeginRankArgs { BeginRank s[2]; int32_t n; };
+template <int BITS>
+__global__ __launch_bounds__(256) void select_begin_rank_append(Layout L, BeginRankArgs a) {
+  const int side = (int)blockIdx.y / L.rows, row = (int)blockIdx.y % L.rows;
+  const BeginRank& s = a.s[side];
+  const int64_t n_before = s.nr_before.n[row / L.n_kv_heads];
+  if (blockIdx.x == 0) sample_rank_body(n_before + 1, s.k, s.samples, s.m, s.spec, row);
+  else quantize_body<BITS>(L, s.kcache, s.k_new, 1, n_before, s.acc, s.pos, s.vrow0, 0, row);
+}
+
+int32_t launch_select_begin_samples(const Layout& L, int n, const void* const kcache[], const void* const q[],
+                                    const NRes nr[], const SelectOut so[], hipStream_t st) {
+  if (n < 1 || n > 4) return HCA_ERR_BAD_ARG;
+  BeginSampleArgs a;
+  a.n = n;
+  unsigned gx = 1;
+  for (int i = 0; i < n; ++i) {
+    a.s[i].kcache = (const uint8_t*)kcache[i];
+    a.s[i].q = (const uint16_t*)q[i];
+    a.s[i].samples = so[i].samples;
+    a.s[i].m = so[i].m_samples;
+    for (int b = 0; b < kMaxBatch; ++b) a.s[i].nr.n[b] = (int32_t)nr[i].n[b];
+    if ((unsigned)(a.s[i].m / kSamplePerWg) > gx) gx = (unsigned)(a.s[i].m / kSamplePerWg);
+  }
+  for (int i = n; i < 4; ++i) a.s[i] = a.s[0];
+  dim3 grid(gx, (unsigned)(n * L.rows));
+  if (L.bits == 4) select_begin_samples<4><<<grid, 256, 0, st>>>(L, a);
+  else select_begin_samples<2><<<grid, 256, 0, st>>>(L, a);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_select_begin_rank_append(const Layout& L, int n, void* const kcache[], const void* const k_new[],
+                                        const NRes nr_before[], float* const acc[], int32_t* const pos[],
+                                        int64_t vrow0, int32_t k, const SelectOut so[], hipStream_t st) {
+  if (n < 1 || n > 2) return HCA_ERR_BAD_ARG;
+  BeginRankArgs a;
+  a.n = n;
+  for (int i = 0; i < n; ++i) {
+    a.s[i].kcache = (uint8_t*)kcache[i];
+    a.s[i].k_new = (const uint16_t*)k_new[i];
+    a.s[i].acc = acc[i];
+    a.s[i].pos = pos[i];
+    a.s[i].samples = so[i].samples;
+    a.s[i].spec = so[i].spec;
+    a.s[i].vrow0 = vrow0;
+    a.s[i].k = k;
+    a.s[i].m = so[i].m_samples;
+    for (int b = 0; b < kMaxBatch; ++b) a.s[i].nr_before.n[b] = (int32_t)nr_before[i].n[b];
+  }
+  for (int i = n; i < 2; ++i) a.s[i] = a.s[0];
+  dim3 grid(2, (unsigned)(n * L.rows));
+  if (L.bits == 4) select_begin_rank_append<4><<<grid, 256, 0, st>>>(L, a);
+  else select_begin_rank_append<2><<<grid, 256, 0, st>>>(L, a);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
 }
 
 // Slots to sample per row.  More samples give a tighter threshold: with m samples the scan lets through about
@@ -642,6 +807,89 @@ int32_t launch_select_step(const Layout& L, const void* kcache, const void* q, c
   else
     score_select_step_kernel<2, 4><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
                                                            so, j);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+static int32_t fill_side(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,
+                         const SelectOut& so, uint64_t* stamps, const SelectStepNext& nx, StepSide* s, unsigned* gx,
+                         size_t* lds) {
+  if (nmax == 0) return HCA_ERR_BAD_ARG;
+  const int bpw = select_scan_bpw(L, nmax);
+  if (bpw == 0) return HCA_ERR_CAPACITY;
+  const int64_t nblocks = (nmax + L.tpb - 1) / L.tpb;
+  s->kcache = (const uint8_t*)kcache;
+  s->q = (const uint16_t*)q;
+  s->stamps = stamps;
+  s->so = so;
+  s->bpw = bpw;
+  s->chunks = (int32_t)((nblocks + 4 * bpw - 1) / (4 * bpw));
+  for (int b = 0; b < kMaxBatch; ++b) {
+    s->nr.n[b] = (int32_t)nr.n[b];
+    s->a_nr.n[b] = (int32_t)nx.a_nr.n[b];
+    s->b_nr.n[b] = (int32_t)nx.b_nr.n[b];
+  }
+  s->a_kcache = (uint8_t*)nx.a_kcache;
+  s->a_k_new = (const uint16_t*)nx.a_k_new;
+  s->a_acc = nx.a_acc;
+  s->a_pos = nx.a_pos;
+  s->a_samples = nx.a_so.samples;
+  s->a_spec = nx.a_so.spec;
+  s->a_vrow0 = nx.a_vrow0;
+  s->a_k = nx.k;
+  s->a_m = nx.a_so.m_samples;
+  s->a_on = nx.a_kcache != nullptr;
+  s->b_kcache = (const uint8_t*)nx.b_kcache;
+  s->b_q = (const uint16_t*)nx.b_q;
+  s->b_samples = nx.b_so.samples;
+  s->b_m = nx.b_kcache != nullptr ? nx.b_so.m_samples : 0;
+  const unsigned g = (unsigned)s->chunks + (unsigned)(s->b_m / kSamplePerWg) + (s->a_on ? 2u : 0u);
+  if (g > *gx) *gx = g;
+  const size_t l = (size_t)4 * bpw * L.tpb * sizeof(uint2);
+  if (l > *lds) *lds = l;
+  return HCA_OK;
+}
+
+// The selecting scans of two layers (and what each carries for the layers behind it) as one launch.
+int32_t launch_select_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
+                                const int64_t nmax[2], const SelectOut so[2], uint64_t* const stamps[2],
+                                const SelectStepNext nx[2], hipStream_t st) {
+  StepSide s0, s1;
+  unsigned gx = 0;
+  size_t lds = 0;
+  int32_t rc = fill_side(L, kcache[0], q[0], nr[0], nmax[0], so[0], stamps[0], nx[0], &s0, &gx, &lds);
+  if (rc != HCA_OK) return rc;
+  rc = fill_side(L, kcache[1], q[1], nr[1], nmax[1], so[1], stamps[1], nx[1], &s1, &gx, &lds);
+  if (rc != HCA_OK) return rc;
+  dim3 grid(gx, (unsigned)(2 * L.rows));
+  if (L.bits == 4) score_select_pair_kernel<4, 8><<<grid, 256, lds, st>>>(L, s0, s1);
+  else score_select_pair_kernel<2, 4><<<grid, 256, lds, st>>>(L, s0, s1);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+int32_t launch_select_rescan_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
+                                  const int64_t nmax[2], const SelectOut so[2], hipStream_t st) {
+  RescanSide rs[2];
+  unsigned gx = 1;
+  size_t lds = 0;
+  for (int i = 0; i < 2; ++i) {
+    const int bpw = select_scan_bpw(L, nmax[i]);
+    if (bpw == 0) return HCA_ERR_CAPACITY;
+    const int64_t nblocks = (nmax[i] + L.tpb - 1) / L.tpb;
+    rs[i].kcache = (const uint8_t*)kcache[i];
+    rs[i].q = (const uint16_t*)q[i];
+    rs[i].so = so[i];
+    rs[i].bpw = bpw;
+    rs[i].nchunks = (int32_t)((nblocks + 4 * bpw - 1) / (4 * bpw));
+    for (int b = 0; b < kMaxBatch; ++b) rs[i].nr.n[b] = (int32_t)nr[i].n[b];
+    if ((unsigned)rs[i].nchunks > gx) gx = (unsigned)rs[i].nchunks;
+    const size_t l = (size_t)4 * bpw * L.tpb * sizeof(uint2);
+    if (l > lds) lds = l;
+  }
+  dim3 grid(gx < 256 ? gx : 256, (unsigned)(2 * L.rows));
+  if (L.bits == 4) score_failed_rows_pair_kernel<4, 8><<<grid, 256, lds, st>>>(L, rs[0], rs[1]);
+  else score_failed_rows_pair_kernel<2, 4><<<grid, 256, lds, st>>>(L, rs[0], rs[1]);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

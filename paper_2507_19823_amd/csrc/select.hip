@@ -782,14 +782,38 @@ __device__ __forceinline__ void lds_count_few(uint32_t* h, uint32_t bin, bool hi
   if ((todo >> lane) & 1) atomicAdd(&h[bin], 1u);
 }
 
-__global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr,
-                                                        SelectOut so, int32_t k, int32_t* __restrict__ idx,
-                                                        int32_t* __restrict__ count, bool only_failed) {
+// exclusive prefix sum of one value per thread over a workgroup of NT threads
+template <int NT>
+__device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum /*[NT / 64]*/) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t a = __shfl_up(inc, o);
+    if (lane >= o) inc += a;
+  }
+  if (lane == 63) wsum[w] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int x = 0; x < w; ++x) base += wsum[x];
+  __syncthreads();
+  return base + inc - v;
+}
+
+// NT = 1024: one large workgroup per row with the row's pairs staged in 128 KiB of LDS - the quickest form when
+// the chip has a compute unit to spare.  NT = 256: four waves and 20 KiB of LDS, the pairs read where they lie
+// (they sit in L2); this one finds room beside the workgroups of a key scan that fills every compute unit,
+// where the large form has to wait for a scan to drain.  Same result.
+template <int NT>
+__device__ __forceinline__ void tk_resolve_emit_body(const int64_t chunk, const int nchunks, const int64_t want,
+                                                     const SelectOut& so, const int32_t k, int32_t* __restrict__ idx,
+                                                     int32_t* __restrict__ count, const bool only_failed, const int row) {
+  constexpr int NW = NT / 64;              // waves
+  constexpr int PER = 1024 / NT;           // chunks (and 10-bit bins) per thread
+  constexpr bool kStage = NT == 1024;
   extern __shared__ uint2 lc[];
   __shared__ uint32_t h[kBins12], off[1025], wsum[16];
   __shared__ uint32_t s_prefix, s_rem, s_cb;
-  const int row = blockIdx.x;
-  const int64_t want = sr.want[row / n_kv_heads];
   const int tid = threadIdx.x;
   uint32_t* spec = so.spec + 4 * row;
   if (want <= 0) {
@@ -797,27 +821,41 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
     return;
   }
   if (only_failed && spec[1] == 0) return;
-  // off[c] = pairs in the chunks before c; off[1024] = all of them
-  const uint32_t mine_cnt = tid < nchunks ? so.ncand[(int64_t)row * kSelectMaxChunks + tid] : 0;
-  const uint32_t before = block_scan_excl_1024(mine_cnt, wsum);
-  off[tid] = before;
-  if (tid == 1023) off[1024] = before + mine_cnt;
+  // off[c] = pairs in the chunks before c; off[1024] = all of them.  Thread tid owns chunks [PER tid, PER tid + PER)
+  {
+    uint32_t mine[PER], sum = 0;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+      const int c = tid * PER + x;
+      mine[x] = c < nchunks ? so.ncand[(int64_t)row * kSelectMaxChunks + c] : 0;
+      sum += mine[x];
+    }
+    uint32_t before = block_scan_excl<NT>(sum, wsum);
+#pragma unroll
+    for (int x = 0; x < PER; ++x) { off[tid * PER + x] = before; before += mine[x]; }
+    if (tid == NT - 1) off[1024] = before;
+  }
   __syncthreads();
   const uint32_t total = off[1024];
   if (total < (uint32_t)want) {
     // the sampled threshold was too high: scan the row again, with the second threshold if the first scan counted
     // enough slots at or above it, else without one
-    const uint32_t mine_n1 = tid < nchunks ? so.n1[(int64_t)row * kSelectMaxChunks + tid] : 0;
-    const uint32_t before1 = block_scan_excl_1024(mine_n1, wsum);
-    if (tid == 1023) {
-      const uint32_t enough = before1 + mine_n1 >= (uint32_t)want;
+    uint32_t sum1 = 0;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+      const int c = tid * PER + x;
+      sum1 += c < nchunks ? so.n1[(int64_t)row * kSelectMaxChunks + c] : 0;
+    }
+    const uint32_t before1 = block_scan_excl<NT>(sum1, wsum);
+    if (tid == NT - 1) {
+      const uint32_t enough = before1 + sum1 >= (uint32_t)want;
       spec[0] = enough && spec[1] == 0 ? spec[2] : 0;       // (a second failure cannot happen: the count is exact)
       spec[1] = 1;
     }
     return;
   }
   const uint2* gl = so.lists + (int64_t)row * so.row_entries;
-  const bool staged = total <= (uint32_t)kFullLds;
+  const bool staged = kStage && total <= (uint32_t)kFullLds;
   // beyond the LDS stage: up to kSearchMax pairs are still addressed by their position in slot order (short lists:
   // walking them chunk by chunk would cost a memory round trip per chunk), more than that are walked chunk by chunk
   const bool by_position = total <= (uint32_t)kSearchMax;
@@ -829,53 +867,64 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
       if (off[c + s] <= p) c += s;
     return gl[(int64_t)c * chunk + (p - off[c])];
   };
-  auto at = [&](uint32_t p) { return staged ? lc[p] : fetch(p); };
   const int lane = tid & 63, wv = tid >> 6;
   uint32_t kmax = 0;                                        // largest key this thread has seen
-  if (staged) {
-    // 16 lanes per chunk: the first 32 pairs of 64 chunks per wave in 32 loads, all in flight together (nearly
-    // all lists are shorter than that); longer lists follow
-    const int sub = lane >> 4, i = lane & 15;
-    uint2 x[16], y[16];
+  if constexpr (kStage) {
+    if (staged) {
+      // 16 lanes per chunk: the first 32 pairs of 64 chunks per wave in 32 loads, all in flight together (nearly
+      // all lists are shorter than that); longer lists follow
+      const int sub = lane >> 4, i = lane & 15;
+      uint2 x[16], y[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int c = wv * 64 + j * 4 + sub;
-      const uint32_t m = off[c + 1] - off[c];
-      x[j] = (uint32_t)i < m ? gl[(int64_t)c * chunk + i] : uint2{0, 0};
-      y[j] = (uint32_t)i + 16 < m ? gl[(int64_t)c * chunk + i + 16] : uint2{0, 0};
-    }
+      for (int j = 0; j < 16; ++j) {
+        const int c = wv * 64 + j * 4 + sub;
+        const uint32_t m = off[c + 1] - off[c];
+        x[j] = (uint32_t)i < m ? gl[(int64_t)c * chunk + i] : uint2{0, 0};
+        y[j] = (uint32_t)i + 16 < m ? gl[(int64_t)c * chunk + i + 16] : uint2{0, 0};
+      }
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int c = wv * 64 + j * 4 + sub;
-      const uint32_t o = off[c], m = off[c + 1] - o;
-      if ((uint32_t)i < m) { lc[o + i] = x[j]; kmax = x[j].x > kmax ? x[j].x : kmax; }
-      if ((uint32_t)i + 16 < m) { lc[o + i + 16] = y[j]; kmax = y[j].x > kmax ? y[j].x : kmax; }
-    }
+      for (int j = 0; j < 16; ++j) {
+        const int c = wv * 64 + j * 4 + sub;
+        const uint32_t o = off[c], m = off[c + 1] - o;
+        if ((uint32_t)i < m) { lc[o + i] = x[j]; kmax = x[j].x > kmax ? x[j].x : kmax; }
+        if ((uint32_t)i + 16 < m) { lc[o + i + 16] = y[j]; kmax = y[j].x > kmax ? y[j].x : kmax; }
+      }
 #pragma unroll 1
-    for (int j = 0; j < 16; ++j) {
-      const int c = wv * 64 + j * 4 + sub;
-      const uint32_t o = off[c], m = off[c + 1] - o;
-      for (uint32_t e = 32 + i; e < m; e += 16) {
-        const uint2 z = gl[(int64_t)c * chunk + e];
-        lc[o + e] = z;
-        kmax = z.x > kmax ? z.x : kmax;
+      for (int j = 0; j < 16; ++j) {
+        const int c = wv * 64 + j * 4 + sub;
+        const uint32_t o = off[c], m = off[c + 1] - o;
+        for (uint32_t e = 32 + i; e < m; e += 16) {
+          const uint2 z = gl[(int64_t)c * chunk + e];
+          lc[o + e] = z;
+          kmax = z.x > kmax ? z.x : kmax;
+        }
       }
     }
   }
   __syncthreads();
   // visit(f): f(key, slot, exists) over every pair of the row, in any order, called by all lanes of a wave
-  // together.  By position: strided over the LDS copy (or, unstaged, through fetch).  Otherwise the lists where
-  // they are: wave w takes chunks w, w + 16, ... and reads each list 1024 pairs at a time (sixteen loads in flight
-  // per lane).
+  // together.  By position: strided over the LDS copy (or, unstaged, through fetch, four pairs in flight per
+  // thread).  Otherwise the lists where they are: wave w takes chunks w, w + NW, ... and reads each list 1024
+  // pairs at a time (sixteen loads in flight per lane).
   auto visit = [&](auto&& f) {
     if (by_position) {
-      for (uint32_t i0 = 0; i0 < total; i0 += 1024) {
-        const bool hit = i0 + tid < total;
-        const uint2 x = at(hit ? i0 + tid : 0);
-        f(x.x, x.y, hit);
+      if (staged) {
+        for (uint32_t i0 = 0; i0 < total; i0 += NT) {
+          const bool hit = i0 + tid < total;
+          const uint2 x = lc[hit ? i0 + tid : 0];
+          f(x.x, x.y, hit);
+        }
+      } else {
+        for (uint32_t i0 = 0; i0 < total; i0 += 4 * NT) {
+          uint2 x[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) x[v] = fetch(i0 + v * NT + tid < total ? i0 + v * NT + tid : 0);
+#pragma unroll
+          for (int v = 0; v < 4; ++v) f(x[v].x, x[v].y, i0 + v * NT + tid < total);
+        }
       }
     } else {
-      for (int c = wv; c < nchunks; c += 16) {
+      for (int c = wv; c < nchunks; c += NW) {
         const uint32_t m = off[c + 1] - off[c];
         const uint2* src = gl + (int64_t)c * chunk;
         for (uint32_t i0 = 0; i0 < m; i0 += 1024) {
@@ -893,7 +942,7 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
   for (int o = 32; o >= 1; o >>= 1) { const uint32_t v = __shfl_xor(kmax, o); kmax = v > kmax ? v : kmax; }
   if (lane == 0) wsum[wv] = kmax;
   __syncthreads();
-  for (int x = 0; x < 16; ++x) kmax = wsum[x] > kmax ? wsum[x] : kmax;
+  for (int x = 0; x < NW; ++x) kmax = wsum[x] > kmax ? wsum[x] : kmax;
   __syncthreads();
   // Radix select on d = key - base (every key of the list is >= base, the scan's threshold): pd = the leading
   // digits of d found so far, s = the number of bits of d below them; rem = how many are still to take among the
@@ -905,18 +954,19 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
   if (sbits < 0) sbits = 0;
   uint32_t pd = 0, rem = (uint32_t)want, cb = total;
   {
-    for (int i = tid; i < kBins12; i += 1024) h[i] = 0;
+    for (int i = tid; i < kBins12; i += NT) h[i] = 0;
     __syncthreads();
     visit([&](uint32_t key, uint32_t, bool hit) { lds_count(h, (key - base) >> sbits, hit, !staged); });
     __syncthreads();
-      uint32_t hb[4], sum = 0;
+    constexpr int BPT = kBins12 / NT;                       // bins per thread, from the top
+    uint32_t hb[BPT], sum = 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { hb[i] = h[kBins12 - 1 - (4 * tid + i)]; sum += hb[i]; }
-    uint32_t running = block_scan_excl_1024(sum, wsum);
+    for (int i = 0; i < BPT; ++i) { hb[i] = h[kBins12 - 1 - (BPT * tid + i)]; sum += hb[i]; }
+    uint32_t running = block_scan_excl<NT>(sum, wsum);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < BPT; ++i) {
       if (running < rem && rem <= running + hb[i]) {
-        s_prefix = (uint32_t)(kBins12 - 1 - (4 * tid + i));
+        s_prefix = (uint32_t)(kBins12 - 1 - (BPT * tid + i));
         s_rem = rem - running;
         s_cb = hb[i];
       }
@@ -945,8 +995,8 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
         if (hit && ((key - base) >> sbits) == pd) sl[atomicAdd(&s_cb, 1u)] = key;
       });
       __syncthreads();
-      if ((uint32_t)tid < cb) {
-        const uint32_t ki = sl[tid];
+      for (uint32_t me = (uint32_t)tid; me < cb; me += NT) {
+        const uint32_t ki = sl[me];
         uint32_t gt = 0, eq = 0;
         for (uint32_t j = 0; j < cb; ++j) {
           const uint32_t kj = sl[j];
@@ -961,19 +1011,25 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
       break;
     }
     const int ns = sbits > 10 ? sbits - 10 : 0, width = sbits - ns;
-    h[tid] = 0;
+    for (int i = tid; i < 1024; i += NT) h[i] = 0;
     __syncthreads();
     visit([&](uint32_t key, uint32_t, bool hit) {
       const uint32_t d = key - base;
       lds_count(h, (d >> ns) & ((1u << width) - 1), hit && (d >> sbits) == pd, !staged);
     });
     __syncthreads();
-    const uint32_t mine = h[1023 - tid];
-    const uint32_t running = block_scan_excl_1024(mine, wsum);
-    if (running < rem && rem <= running + mine) {
-      s_prefix = (pd << width) | (uint32_t)(1023 - tid);
-      s_rem = rem - running;
-      s_cb = mine;
+    uint32_t mine[PER], msum = 0;                           // thread tid owns bins 1023 - (PER tid + x)
+#pragma unroll
+    for (int x = 0; x < PER; ++x) { mine[x] = h[1023 - (PER * tid + x)]; msum += mine[x]; }
+    uint32_t running = block_scan_excl<NT>(msum, wsum);
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+      if (running < rem && rem <= running + mine[x]) {
+        s_prefix = (pd << width) | (uint32_t)(1023 - (PER * tid + x));
+        s_rem = rem - running;
+        s_cb = mine[x];
+      }
+      running += mine[x];
     }
     __syncthreads();
     pd = s_prefix;
@@ -986,21 +1042,52 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
   if (tid == 0) count[row] = (int32_t)want;
   if (by_position) {
     // ordered part by position (slot order): thread tid owns the run [tid * E, tid * E + E)
-    const uint32_t E = (total + 1023) / 1024;
+    const uint32_t E = (total + NT - 1) / NT;
     const uint32_t p0 = (uint32_t)tid * E;
     const uint32_t p1 = p0 + E < total ? p0 + E : total;
     uint32_t ng = 0, ne = 0;
-    for (uint32_t p = p0; p < p1; ++p) {
-      const uint32_t key = at(p).x;
-      ng += key > T;
-      ne += key == T;
+    if (staged) {
+      for (uint32_t p = p0; p < p1; ++p) {
+        const uint32_t key = lc[p].x;
+        ng += key > T;
+        ne += key == T;
+      }
+    } else if (p0 < p1) {
+      // the run lies in consecutive entries of consecutive chunks' lists: one search for its start, then a walk
+      uint32_t c = 0;
+#pragma unroll
+      for (int s = 512; s >= 1; s >>= 1)
+        if (off[c + s] <= p0) c += s;
+      uint32_t e = p0 - off[c];
+      for (uint32_t p = p0; p < p1; ++p) {
+        while (e >= off[c + 1] - off[c]) { ++c; e = 0; }
+        const uint32_t key = gl[(int64_t)c * chunk + e].x;
+        ng += key > T;
+        ne += key == T;
+        ++e;
+      }
     }
-    uint32_t rg = block_scan_excl_1024(ng, wsum);           // pairs above T on lower slots
-    uint32_t re = block_scan_excl_1024(ne, wsum);           // pairs equal to T on lower slots
-    for (uint32_t p = p0; p < p1; ++p) {
-      const uint2 x = at(p);
-      if (x.x > T) { out[rg + (re < req ? re : req)] = (int32_t)x.y; ++rg; }
-      else if (x.x == T) { if (re < req) out[rg + re] = (int32_t)x.y; ++re; }
+    uint32_t rg = block_scan_excl<NT>(ng, wsum);            // pairs above T on lower slots
+    uint32_t re = block_scan_excl<NT>(ne, wsum);            // pairs equal to T on lower slots
+    if (staged) {
+      for (uint32_t p = p0; p < p1; ++p) {
+        const uint2 x = lc[p];
+        if (x.x > T) { out[rg + (re < req ? re : req)] = (int32_t)x.y; ++rg; }
+        else if (x.x == T) { if (re < req) out[rg + re] = (int32_t)x.y; ++re; }
+      }
+    } else if (p0 < p1) {
+      uint32_t c = 0;
+#pragma unroll
+      for (int s = 512; s >= 1; s >>= 1)
+        if (off[c + s] <= p0) c += s;
+      uint32_t e = p0 - off[c];
+      for (uint32_t p = p0; p < p1; ++p) {
+        while (e >= off[c + 1] - off[c]) { ++c; e = 0; }
+        const uint2 x = gl[(int64_t)c * chunk + e];
+        if (x.x > T) { out[rg + (re < req ? re : req)] = (int32_t)x.y; ++rg; }
+        else if (x.x == T) { if (re < req) out[rg + re] = (int32_t)x.y; ++re; }
+        ++e;
+      }
     }
     return;
   }
@@ -1009,7 +1096,7 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
   uint32_t* cg = h;            // [1024] pairs above T per chunk -> pairs above T in the chunks before
   uint32_t* ce = h + 1024;     // the same for pairs equal to T
   __syncthreads();
-  for (int c = wv; c < 1024; c += 16) {
+  for (int c = wv; c < 1024; c += NW) {
     uint32_t g = 0, e = 0;
     if (c < nchunks) {
       const uint32_t m = off[c + 1] - off[c];
@@ -1030,15 +1117,22 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
   }
   __syncthreads();
   {
-    const uint32_t g = cg[tid], e = ce[tid];
-    const uint32_t og = block_scan_excl_1024(g, wsum);
-    const uint32_t oe = block_scan_excl_1024(e, wsum);
-    cg[tid] = og;
-    ce[tid] = oe;
+    uint32_t g[PER], e[PER], gs = 0, es = 0;
+#pragma unroll
+    for (int x = 0; x < PER; ++x) { g[x] = cg[PER * tid + x]; e[x] = ce[PER * tid + x]; gs += g[x]; es += e[x]; }
+    uint32_t og = block_scan_excl<NT>(gs, wsum);
+    uint32_t oe = block_scan_excl<NT>(es, wsum);
+#pragma unroll
+    for (int x = 0; x < PER; ++x) {
+      cg[PER * tid + x] = og;
+      ce[PER * tid + x] = oe;
+      og += g[x];
+      oe += e[x];
+    }
   }
   __syncthreads();
   const uint64_t lt = (1ull << lane) - 1;
-  for (int c = wv; c < nchunks; c += 16) {
+  for (int c = wv; c < nchunks; c += NW) {
     const uint32_t m = off[c + 1] - off[c];
     const uint2* src = gl + (int64_t)c * chunk;
     uint32_t pg = cg[c], pe = ce[c];
@@ -1059,6 +1153,36 @@ __global__ __launch_bounds__(1024) void tk_resolve_emit(int64_t chunk, int nchun
         pe += (uint32_t)__popcll(me);
       }
     }
+  }
+}
+
+template <int NT>
+__global__ __launch_bounds__(NT) void tk_resolve_emit(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr,
+                                                      SelectOut so, int32_t k, int32_t* __restrict__ idx,
+                                                      int32_t* __restrict__ count, bool only_failed) {
+  tk_resolve_emit_body<NT>(chunk, nchunks, sr.want[blockIdx.x / n_kv_heads], so, k, idx, count, only_failed,
+                           (int)blockIdx.x);
+}
+
+// The selections of two layers in one launch (the step driver's paired form): workgroups [0, rows) take the
+// first layer, [rows, 2 rows) the second.
+struct ResolveSide {
+  int64_t chunk;
+  int32_t nchunks;
+  int64_t want[kMaxBatch];
+  SelectOut so;
+  int32_t* idx;
+  int32_t* count;
+};
+template <int NT>
+__global__ __launch_bounds__(NT) void tk_resolve_emit_pair(ResolveSide a, ResolveSide b, int rows, int n_kv_heads,
+                                                           int32_t k, bool only_failed) {
+  if ((int)blockIdx.x < rows) {
+    tk_resolve_emit_body<NT>(a.chunk, a.nchunks, a.want[blockIdx.x / n_kv_heads], a.so, k, a.idx, a.count, only_failed,
+                             (int)blockIdx.x);
+  } else {
+    const int row = (int)blockIdx.x - rows;
+    tk_resolve_emit_body<NT>(b.chunk, b.nchunks, b.want[row / n_kv_heads], b.so, k, b.idx, b.count, only_failed, row);
   }
 }
 
@@ -1138,6 +1262,19 @@ int32_t launch_select_scan_step(const Layout& L, const void* kcache, const void*
   return launch_select_step(L, kcache, q, nr, nmax, f.so, st, stamps, nx);
 }
 
+int32_t launch_select_scan_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2],
+                                     const NRes nr[2], const int64_t nmax[2], int32_t k, void* const ws[2], hipStream_t st,
+                                     uint64_t* const stamps[2], const SelectStepNext nx[2]) {
+  SelectOut so[2];
+  for (int i = 0; i < 2; ++i) {
+    FusedPlan f;
+    const int32_t rc = fused_plan(L, nr[i], nmax[i], k, ws[i], &f);
+    if (rc != HCA_OK) return rc;
+    so[i] = f.so;
+  }
+  return launch_select_step_pair(L, kcache, q, nr, nmax, so, stamps, nx, st);
+}
+
 // 2. the selecting scan
 int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
                             void* ws, hipStream_t st, uint64_t* stamps) {
@@ -1151,18 +1288,58 @@ int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, 
 // for rows whose sampled threshold left too few pairs, a scan with every slot a candidate and the selection
 // again (both launches return at once for every other row).
 int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
-                             int32_t* idx, int32_t* count, void* ws, hipStream_t st) {
+                             int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool small_wg) {
   FusedPlan f;
   int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
   if (rc != HCA_OK) return rc;
+  if (small_wg) {
+    tk_resolve_emit<256><<<L.rows, 256, 0, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false);
+    if (nmax > 0) {
+      rc = launch_select_scan(L, kcache, q, nr, nmax, f.so, true, st);
+      if (rc != HCA_OK) return rc;
+      tk_resolve_emit<256><<<L.rows, 256, 0, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true);
+    }
+    HCA_HIP(hipGetLastError());
+    return HCA_OK;
+  }
   static std::atomic<uint64_t> opted{0};
-  rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit), kFullLds * 8, &opted);
+  rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit<1024>), kFullLds * 8, &opted);
   if (rc != HCA_OK) return rc;
-  tk_resolve_emit<<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false);
+  tk_resolve_emit<1024><<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false);
   if (nmax > 0) {
     rc = launch_select_scan(L, kcache, q, nr, nmax, f.so, true, st);
     if (rc != HCA_OK) return rc;
-    tk_resolve_emit<<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true);
+    tk_resolve_emit<1024><<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true);
+  }
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+// The same for the two layers of a paired scan launch: three launches for the two of them.
+int32_t launch_select_finish_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
+                                  const int64_t nmax[2], int32_t k, int32_t* const idx[2], int32_t* const count[2],
+                                  void* const ws[2], hipStream_t st) {
+  FusedPlan f[2];
+  ResolveSide rs[2];
+  for (int i = 0; i < 2; ++i) {
+    const int32_t rc = fused_plan(L, nr[i], nmax[i], k, ws[i], &f[i]);
+    if (rc != HCA_OK) return rc;
+    rs[i].chunk = f[i].chunk;
+    rs[i].nchunks = f[i].nchunks;
+    for (int b = 0; b < kMaxBatch; ++b) rs[i].want[b] = f[i].sr.want[b];
+    rs[i].so = f[i].so;
+    rs[i].idx = idx[i];
+    rs[i].count = count[i];
+  }
+  static std::atomic<uint64_t> opted{0};
+  int32_t rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit_pair<1024>), kFullLds * 8, &opted);
+  if (rc != HCA_OK) return rc;
+  tk_resolve_emit_pair<1024><<<2 * L.rows, 1024, kFullLds * 8, st>>>(rs[0], rs[1], L.rows, L.n_kv_heads, k, false);
+  if (nmax[0] > 0 && nmax[1] > 0) {
+    const SelectOut so2[2] = {f[0].so, f[1].so};
+    rc = launch_select_rescan_pair(L, kcache, q, nr, nmax, so2, st);
+    if (rc != HCA_OK) return rc;
+    tk_resolve_emit_pair<1024><<<2 * L.rows, 1024, kFullLds * 8, st>>>(rs[0], rs[1], L.rows, L.n_kv_heads, k, true);
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
@@ -1174,7 +1351,7 @@ int32_t launch_score_topk(const Layout& L, const void* kcache, const void* q, co
   if (rc != HCA_OK) return rc;
   rc = launch_select_begin(L, kcache, q, nr, nmax, k, ws, st, nullptr);
   if (rc != HCA_OK) return rc;
-  return launch_select_finish(L, kcache, q, nr, nmax, k, idx, count, ws, st);
+  return launch_select_finish(L, kcache, q, nr, nmax, k, idx, count, ws, st, tuning().select_wg == 256);
 }
 
 // What the last fused selection on this workspace did, per row: pairs that passed the threshold of the scan that

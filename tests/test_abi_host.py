@@ -305,3 +305,34 @@ def test_host_prefault_walks_any_range(B):
         assert L.hca_host_prefault(C.c_void_p(a.ctypes.data), a.nbytes, threads) == 0
     assert L.hca_host_prefault(None, 0, 4) == 0
     assert L.hca_host_prefault(None, 10, 4) == -1
+
+
+@pytest.mark.parametrize("isa", [0, 2])
+@pytest.mark.parametrize("gqa", [1, 2, 4])
+def test_host_chunk_sum_against_numpy(B, gqa, isa):
+    """One chunk of the hybrid value side's host work against a float64 matrix product; entries marked -1 are left
+    out, rows beyond the store are skipped and counted.  isa 0: the widest vector form this CPU has; 2: AVX2."""
+    import numpy as np
+    L = B.lib()
+    B.hca_tune("host_isa", isa)
+    rng = np.random.default_rng(gqa)
+    n_rows = 5000
+    V = rng.standard_normal((n_rows, 128)).astype(np.float16)
+    p = np.zeros((4, 256), np.float32)
+    p[:gqa] = rng.random((gqa, 256)).astype(np.float32) * np.exp2(rng.integers(-40, 1, (gqa, 256))).astype(np.float32)
+    vrow = rng.integers(0, n_rows, 256).astype(np.int32)
+    vrow[5::17] = -1
+    vrow[200:] = -1                                   # a ragged chunk
+    py = np.full((4, 128), 7.0, np.float32)
+    assert L.hca_debug_host_chunk_sum(gqa, p.ctypes.data, vrow.ctypes.data, V.ctypes.data, n_rows, py.ctypes.data) == 0
+    live = vrow >= 0
+    ref = p[:, live].astype(np.float64) @ V[vrow[live]].astype(np.float64)
+    assert np.allclose(py[:gqa], ref[:gqa], rtol=1e-5, atol=1e-6)
+    assert np.all(py[gqa:] == 0)
+    vrow[3] = n_rows + 5                              # outside the store: skipped, reported
+    assert L.hca_debug_host_chunk_sum(gqa, p.ctypes.data, vrow.ctypes.data, V.ctypes.data, n_rows, py.ctypes.data) == 1
+    live = (vrow >= 0) & (vrow < n_rows)
+    ref = p[:, live].astype(np.float64) @ V[vrow[live]].astype(np.float64)
+    assert np.allclose(py[:gqa], ref[:gqa], rtol=1e-5, atol=1e-6)
+    assert L.hca_debug_host_chunk_sum(5, p.ctypes.data, vrow.ctypes.data, V.ctypes.data, n_rows, py.ctypes.data) == -1
+    B.hca_tune("host_isa", 0)

@@ -459,7 +459,8 @@ def test_config3_full_shape_step_driver(oracle, fused, spare, host):
     d.n_sel = 3
     d.fused_select = int(fused)
     idxs = []
-    for i in range(4):
+    d.n_pipe = 8 if host else 0
+    for i in range(8 if host else 4):
         a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
         b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
         c = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
@@ -472,6 +473,7 @@ def test_config3_full_shape_step_driver(oracle, fused, spare, host):
     if spare:
         d.spare_kcache, d.spare_acc, d.spare_pos = kc[1].data_ptr(), acc[1].data_ptr(), pos[1].data_ptr()
     d.host_chunks, d.host_threads = host, 12      # hybrid value side: 3 of the 8 chunks of 256 summed on the host
+    d.dual_scan = 2 if host else 0                # (one layer: the paired form falls back to single launches)
     pl = B.hca_pipeline_create(shape, 1, d, 0)
     layers = (B.hca_layer * 1)()
     layers[0].kcache, layers[0].acc, layers[0].pos = kc[0].data_ptr(), acc[0].data_ptr(), pos[0].data_ptr()

@@ -424,7 +424,9 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
         keep.append(t)
     d.n_sel = n_sel
     d.fused_select = int(fused)
-    for i in range(4):
+    n_pipe = 4 + Lr % 5 if host else 4          # with the hybrid value side: 4 .. 8 sets of selection buffers
+    d.n_pipe = n_pipe
+    for i in range(n_pipe):
         a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
         b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
         c = torch.zeros(wsb, dtype=torch.uint8, device=dev)
@@ -436,6 +438,8 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
         d.spare_kcache, d.spare_acc, d.spare_pos = kc[Lr].data_ptr(), acc[Lr].data_ptr(), pos[Lr].data_ptr()
     d.topp_tau = tau
     d.host_chunks, d.host_threads = host, 3
+    # two scan streams, or one scan launch per two layers, wherever the mode allows it
+    d.dual_scan = (2 if Lr in (5, 1) else 1) if (fused and n_sel >= Lr and Lr != 4) else 0
     pl = B.hca_pipeline_create(shape, Lr, d, 0)
     layers = (B.hca_layer * Lr)()
     for l in range(Lr):

@@ -16,6 +16,16 @@ def H():
     return H
 
 
+@pytest.fixture(autouse=True, params=[0, 256], ids=["wg1024", "wg256"])
+def select_wg(request, H):
+    """Every case runs with both forms of the selection over the candidate lists: one 1024-thread workgroup per
+    row with the pairs staged in LDS (the per-call default), and the four-wave form that reads them from L2 (what
+    the step driver uses beside a running scan)."""
+    H.hca_tune("select_wg", request.param)
+    yield request.param
+    H.hca_tune("select_wg", 0)
+
+
 def _rows(t):
     a = t.detach().cpu().numpy()
     return a.reshape(a.shape[0] * a.shape[1], *a.shape[2:])
