@@ -72,6 +72,17 @@ class Model:
         self.pipe = []
         self.n_pipe_sets = n_pipe_sets
         self.dual_scan = dual_scan
+        # The layer whose results are checked against the oracle: one whose set of selection buffers is not taken
+        # again later in the step (so its top-k indices are still there when the step ends), and among those the
+        # one whose first eviction comes latest (the check covers the timed steps up to that eviction).
+        self.verify_layer, self.verify_until = 0, total_steps - 1
+        cands = range(max(0, layers - n_pipe_sets), layers)
+        if evict_every:
+            first = {l: (evict_every - 1 - l) % evict_every for l in cands}
+            self.verify_layer = max(cands, key=lambda l: first[l])
+            self.verify_until = first[self.verify_layer]
+        else:
+            self.verify_layer = max(cands)
         for _ in range(n_pipe_sets):
             self.pipe.append(dict(
                 idx=torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev),
@@ -120,7 +131,9 @@ class Model:
             elif phys_value_layers > 0:
                 self.v_host[l] = self.v_host[l % phys_value_layers]   # logical layer shares a physical store
             if l == 0:
-                self.layer0 = {k: (v.cpu() if v is not None and hasattr(v, "cpu") else v) for k, v in d.items()}
+                self.layer0 = {"q": d["q"].cpu()}
+            if l == self.verify_layer:                # the layer the oracle replays (cpu_baseline leg, verification)
+                self.layerv = {k: (v.cpu() if v is not None and hasattr(v, "cpu") else v) for k, v in d.items()}
             del d
         self.phys = phys_value_layers
         return tq
@@ -446,6 +459,43 @@ def per_layer_latency_grouped(cfg, groups, streams, iters=8, fused=True):
     torch.cuda.empty_cache()
     torch._C._host_emptyCache()
     return {"parts": groups, "ms_per_layer": ms, "host_enqueue_ms": host_ms, "gate_ms": gate / cycles_per_ms}
+
+
+def other_config_step(cfg, layers, phys, steps, streams, args, tune):
+    """ms per decode step of another workload through the same step driver and settings as the headline run
+    (a few steps; `layers` logical layers on `phys` physical value stores)."""
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    w = S.CONFIGS[cfg]
+    warm = 2
+    nsplit = -(-w.k // 256)
+    hc = min(nsplit, round(args.host_chunks * nsplit / 16)) if args.host_chunks else 0
+    m = Model(w, layers, args.evict_every, steps + warm, n_sel=layers if layers >= 3 else 3, fused=not args.no_fused_select,
+              host_chunks=hc, host_threads=args.host_threads, tune=tune, n_pipe_sets=args.pipe_sets,
+              dual_scan=args.scan_mode)
+    m.build(phys)
+    m.make_steps(steps + warm)
+    m.native_pipeline(*streams, 0)
+    for t in range(warm):
+        m.decode_step_native(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(warm, warm + steps):
+        m.decode_step_native(t)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    status = B.hca_pipeline_host_status(m.pl) if hc else (0, 0)
+    B.hca_pipeline_destroy(m.pl)
+    out = {"workload": w.name, "layers": layers, "physical_value_layers": m.phys, "batch": w.batch,
+           "resident_tokens_per_layer": w.n + warm + steps, "top_k": w.k, "steps": steps, "ms_per_step": ms,
+           "ms_per_layer": ms / layers, "context_tokens_scored_per_s": w.batch * w.n * layers / ms * 1e3,
+           "host_chunks_of": [hc, nsplit], "host_timeouts_bad_rows": list(status)}
+    del m
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()
+    return out
 
 
 def vq_probe(w, iters, g=32, c=256):
@@ -860,14 +910,15 @@ def gather_only(w, iters):
                       "host_link_peak_GBs": link_peak, "frac_of_link_peak": by / ms / 1e6 / link_peak}), flush=True)
 
 
-def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
+def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32, min_steps=0):
     """Times the oracle, as it stands, on layer 0 of the same workload: consecutive decode steps
     (append one token, score every resident token, top-k, attend with accumulated-score update)
     until about `budget_s` seconds of CPU work are done."""
     import numpy as np
     import oracle
     import synth_inputs as S
-    d = model.layer0
+    d = model.layerv
+    lv = model.verify_layer
     R = w.batch * w.n_kv_heads
     oc = oracle.Cache(R, w.n + max_steps, 128, w.bits, w.group)
     t0 = time.perf_counter()
@@ -879,8 +930,9 @@ def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
     acc = np.zeros((R, w.n + max_steps), np.float32)
     parts = np.zeros(4)
     steps, scored = 0, 0
-    while steps < max_steps and parts.sum() < budget_s:
-        k_new, v_new, q = S.make_step(w, 0, steps)
+    results = []                                      # (top-k index sets, outputs) of every replayed step
+    while steps < max_steps and (parts.sum() < budget_s or steps < min_steps):
+        k_new, v_new, q = S.make_step(w, lv, steps)
         V[:, w.n + steps] = v_new.numpy().reshape(R, 128)
         q16 = q.numpy().reshape(-1, 128)
         t0 = time.perf_counter()
@@ -890,16 +942,20 @@ def run_cpu_baseline(model, w, budget_s=12.0, max_steps=32):
         t2 = time.perf_counter()
         idx, count = oracle.topk(sel, oc.n, w.k)
         t3 = time.perf_counter()
-        oracle.attend(oc, q16, idx, count, pos, V, model.sm_scale, acc=acc)
+        y, _ = oracle.attend(oc, q16, idx, count, pos, V, model.sm_scale, acc=acc)
         t4 = time.perf_counter()
+        results.append((idx, y))
         parts += (t1 - t0, t2 - t1, t3 - t2, t4 - t3)
         steps += 1
         scored += w.batch * int(oc.n[0])
     total = float(parts.sum())
-    return {
+    cores = len(os.sched_getaffinity(0))
+    return results, {
         "value": scored / total, "unit": "context tokens scored/s",
-        "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": f"{steps} consecutive decode steps of ONE layer (layer 0) of {w.name}, every resident token of "
+        # the oracle's only parallel loop runs over the (sequence, KV head) rows: OpenMP threads beyond them idle
+        "cores": min(oracle.num_threads(), R), "cores_available": cores, "omp_threads": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{steps} consecutive decode steps of ONE layer (layer {lv}) of {w.name}, every resident token of "
                   f"all {w.n_kv_heads} KV heads scored per step, no eviction (append {parts[0]:.3f}s, score "
                   f"{parts[1]:.3f}s, top-k {parts[2]:.3f}s, attend {parts[3]:.3f}s); the oracle's own bulk "
                   f"quantise of the context ({t_build:.1f}s) is not in the timed part",
@@ -923,15 +979,15 @@ def main():
     ap.add_argument("--evict-spare", action="store_true",
                     help="native pipeline: evict out of place into a spare buffer set, in slices behind the attends "
                          "(default: in place, which moves only the slots from the first dropped one on)")
-    ap.add_argument("--host-chunks", type=int, default=0,
+    ap.add_argument("--host-chunks", type=int, default=14,
                     help="hybrid value side of the native step driver: of every row's selected tokens the first N "
                          "chunks of 256 are summed by host threads from the value store, the rest gathered (0: all gathered)")
-    ap.add_argument("--host-threads", type=int, default=12, help="worker threads of the hybrid value side")
-    ap.add_argument("--scan-mode", default="single", choices=["single", "dual", "pair"],
+    ap.add_argument("--host-threads", type=int, default=14, help="worker threads of the hybrid value side")
+    ap.add_argument("--scan-mode", default="pair", choices=["single", "dual", "pair"],
                     help="native step driver with the fused selection: single = one scan launch per layer on one stream; "
                          "dual = even layers scan + select on one stream, odd layers on a second one, so that two scans "
                          "overlap; pair = one scan launch per two layers")
-    ap.add_argument("--pipe-sets", type=int, default=4, choices=[4, 5, 6, 7, 8],
+    ap.add_argument("--pipe-sets", type=int, default=8, choices=[4, 5, 6, 7, 8],
                     help="native step driver: sets of selection / staging buffers, i.e. layers in flight between top-k and attend")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gap-report", action="store_true",
@@ -976,6 +1032,8 @@ def main():
         else:
             B.hca_tune(name, int(val))
 
+    if args.pipeline == "native" and args.host_chunks and "gather_wgs" not in tune:
+        tune["gather_wgs"] = 4                        # the gather moves an eighth of the rows: half the workgroups do
     w = S.CONFIGS[args.config]
     # a 32 Ki-token layer (20 MiB of codes) would sit in the last-level cache if it were scanned over and over:
     # the small workload is run as 16 layers, i.e. 16 cache copies in rotation
@@ -1047,6 +1105,17 @@ def main():
         selection = selection_probe(S.CONFIGS[4])
         log(f"selection at 1M: top-k {selection['topk_ms']:.3f} ms, Eq. 4 at tau 0.9 {selection['topp_tau0.9']['ms']:.3f} ms")
 
+    others = None
+    if not args.no_latency and args.pipeline == "native" and args.config == 4:
+        # the same step driver on the other stacks (a few steps each; the headline stays config 4)
+        st4 = (main_s[0], extra[0], gath_s[0], extra[1])
+        others = {"cfg3": other_config_step(3, 1, 1, 16, st4, args, tune)}
+        log(f"config 3 through the step driver: {others['cfg3']['ms_per_step']:.3f} ms per step")
+        others["cfg5"] = other_config_step(5, 8, 2, 6, st4, args, tune)
+        others["cfg5"]["note"] = ("8 of the 32 layers on 2 physical value stores (the full stack needs 256 GiB of pinned "
+                                  "memory), 4 Mi resident tokens per layer; ms_per_layer x 32 extrapolates the stack")
+        log(f"config 5 through the step driver, 8 layers: {others['cfg5']['ms_per_step']:.3f} ms per step "
+            f"({others['cfg5']['ms_per_layer']:.3f} ms per layer)")
     total_steps = args.steps + args.warmup
     fused = args.pipeline == "native" and not args.no_fused_select
     model = Model(w, L, args.evict_every, total_steps, n_sel=min(L, args.sel_buffers), evict_spare=args.evict_spare,
@@ -1078,12 +1147,36 @@ def main():
         else:
             model.decode_step(t, main, side, args.pipeline == "gather", ev)
 
+    cal_src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)                            # calibration dispatch for counter runs: reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
     for t in range(args.warmup):
         run_step(t)
+    if args.pipeline == "native" and fused:
+        torch.cuda.synchronize()                      # the warm-up steps' selections are not counted
+        for wsl in model.ws_sel:
+            B.hca_score_topk_monitor(model.shape, wsl, None, True)
     torch.cuda.synchronize()
     log("warmup done")
     events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)]
               for _ in range(args.steps)]
+    # what the check against the oracle needs: the verification layer's top-k indices and output of the timed steps
+    # up to its first eviction, copied aside behind each of those steps. Each copy rides the stream that writes its
+    # source (indices: the top-k stream; output: the attend stream), so it is ordered before the next step's
+    # writes and no stream waits for another.
+    captured = {}
+    vslot = model.verify_layer % model.n_pipe_sets if args.pipeline == "native" else 0
+    topk_s = main if args.stages == 3 else extra[0]
+
+    def capture(t):
+        with torch.cuda.stream(topk_s):
+            ci = model.pipe[vslot]["idx"].clone()
+        with torch.cuda.stream(extra[1]):
+            cy = model.y[model.verify_layer].clone()
+        captured[t] = (ci, cy)
+
     step_end = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     host_done = []
     step_end[0].record(extra[1])                      # the attend stream: a step's last kernels run there
@@ -1092,6 +1185,8 @@ def main():
     for t in range(args.warmup, total_steps):
         h0 = time.perf_counter()
         run_step(t, events[t - args.warmup])
+        if args.pipeline == "native" and not args.no_cpu_baseline and t <= model.verify_until and len(captured) < 6:
+            capture(t)
         step_end[t - args.warmup + 1].record(extra[1] if args.pipeline in ("native", "staged") else main)
         host_steps.append((time.perf_counter() - h0) * 1e3)
         host_done.append((time.perf_counter() - t0) * 1e3)
@@ -1178,7 +1273,11 @@ def main():
     achieved = scan_bytes / (scan_ms * 1e-3) / 1e9
 
     traffic = None
-    pmc = os.path.join(ROOT, "profiles", "select_scan_cfg4_1m_pmc.md" if fused else "score_kernel_cfg4_1m_pmc.md")
+    pair = fused and layers_per_launch == 2
+    pmc = os.path.join(ROOT, "profiles", ("select_scan_pair_cfg4_1m_pmc.md" if pair else "select_scan_cfg4_1m_pmc.md")
+                       if fused else "score_kernel_cfg4_1m_pmc.md")
+    kernel = ("score_select_pair_kernel (the selecting scan; two layers per launch)" if pair else
+              "score_select_step_kernel (the selecting scan; one launch per layer)" if fused else "score_kernel")
     if args.config == 4 and os.path.exists(pmc):     # measured with rocprofv3 --pmc, see that file
         for line in open(pmc):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -1191,7 +1290,13 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "context": w.n, "layers": L, "q_heads": w.n_q_heads,
                    "kv_heads": w.n_kv_heads, "key_bits": w.bits, "group": w.group, "top_k": w.k,
-                   "evict_every": args.evict_every, "values": "context rows in pinned host fp16, appended rows in an HBM slice",
+                   "evict_every": args.evict_every,
+                   "eviction_case": ("in place; M = the context length, the newest evict_every slots protected: the dropped "
+                                     "slots are the newest never-selected ones just below the protected window (ties go "
+                                     "against the higher slot), so only the selection passes over the accumulated scores "
+                                     "and a short tail move are paid; an eviction whose first dropped slot is early costs "
+                                     "about 0.7 ms per layer instead of 0.1-0.2") if args.evict_every else None,
+                   "values": "context rows in pinned host fp16, appended rows in an HBM slice",
                    "physical_value_layers": phys, "pipeline": args.pipeline,
                    "value_side": (f"hybrid: {model.host_chunks} of {-(-w.k // 256)} chunks of 256 selected tokens per row "
                                   f"summed by {model.host_threads} host threads from the value store, the rest gathered"
@@ -1199,6 +1304,7 @@ def main():
                    "selection": "hca_score_topk (scan + top-k fused)" if fused else "hca_score_qkeys + hca_topk"},
         "pipelined_ms_per_layer": ms_per_step / L,
         "per_layer_decode_latency": latency,
+        "steps_other_configs": others,
         "codebook_key_path": codebook,
         "selection": selection,
         "paper_form_step": paper_form,
@@ -1206,17 +1312,61 @@ def main():
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,
         "bulk_quantize_GBs": bulk_tokens * (256 + code_bytes) / tq / 1e9,
         "host_link_peak_GBs": link_peak,
-        "roofline": {"bound": "hbm", "kernel": "score_select_step_kernel (the selecting scan; one launch per layer)" if fused else "score_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": (f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the same kernel alone, recorded in "
+                                        f"profiles/{os.path.basename(pmc)} (not a counter of this run)") if traffic else None,
+                     "layers_per_launch": layers_per_launch,
                      "avg_launch_ms": scan_ms, "bytes_per_launch": scan_bytes,
                      "avg_event_bracket_ms": bracket_ms,
                      # the same kernel at the same shape with no other kernel beside it (latency probe above)
                      "frac_alone": (latency.get("1M", {}).get("fused_select", {}).get("select_scan_frac_of_hbm_peak") if fused
                                     else latency.get("1M", {}).get("key_scan_frac_of_hbm_peak")) if args.config == 4 else None},
     }
+    if args.pipeline == "native":
+        # per row and set of selection buffers, over every fused selection of the timed steps: the fewest and the most
+        # pairs a first scan let through, and how many selections needed the second scan
+        if fused:
+            mon = torch.zeros(len(model.ws_sel), model.rows, 4, dtype=torch.int32, device="cuda")
+            for i, wsl in enumerate(model.ws_sel):
+                B.hca_score_topk_monitor(model.shape, wsl, mon[i], False)
+            torch.cuda.synchronize()
+            mon = mon.cpu()
+            out["selection_monitor"] = {"scope": "every row of every layer, every timed step",
+                                        "selections": int(mon[..., 0].sum()),
+                                        "expected_selections": args.steps * L * model.rows,
+                                        "candidates_min": int(mon[..., 1].min()), "candidates_max": int(mon[..., 2].max()),
+                                        "rows_rescanned": int(mon[..., 3].sum())}
+        out["hybrid_value_side"] = host_side
+        B.hca_pipeline_destroy(model.pl)              # ends the driver's host threads before the oracle is timed
+    out["verified"] = None
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = run_cpu_baseline(model, w)
+        want = max(captured) + 1 if captured else 0
+        results, out["cpu_baseline"] = run_cpu_baseline(model, w, min_steps=want)
+        if captured:
+            import numpy as np
+            worst, checked, sets_ok = 0.0, [], True
+            for t, (gi, gy) in sorted(captured.items()):
+                oi, oy = results[t]
+                gi = gi.cpu().numpy().reshape(oi.shape)
+                if not np.array_equal(gi, oi):
+                    log(f"VERIFICATION FAILED: step {t}, layer {model.verify_layer}: top-k index sets differ from the oracle's")
+                    out["verified"], sets_ok = False, False
+                    break
+                gy = gy.cpu().numpy().reshape(oy.shape)
+                err = float(np.max(np.abs(gy - oy).max(-1) / np.maximum(np.abs(oy).max(-1), 1e-30)))
+                worst = max(worst, err)
+                checked.append(t)
+            else:
+                out["verified"] = bool(worst <= 2e-3)
+            out["verification"] = {"layer": model.verify_layer, "steps": checked, "of_timed_steps": f"{args.warmup}..{total_steps - 1}",
+                                   "top_k_sets": "bit-exact" if sets_ok else "differ",
+                                   "max_rel_err_y": worst, "tolerance": 2e-3,
+                                   "against": "the oracle's replay of the same layer from step 0 (cpu_baseline leg)"}
     print(json.dumps(out), flush=True)
+    if out["verified"] is False:
+        log("result printed; the timed region's outputs do NOT match the oracle")
+        sys.exit(1)
     log("result printed")
 
 

@@ -160,6 +160,14 @@ int32_t hca_score_topk(const hca_shape* shape, const void* kcache, const void* q
 int32_t hca_score_topk_report(const hca_shape* shape, const int64_t* n_resident, void* workspace,
                               int32_t* candidates, int32_t* rescanned, void* stream);
 
+/* The same monitor kept running over many calls: every fused selection on `workspace` (hca_score_topk, or a layer
+ * of hca_pipeline_step that was given it as ws_select) adds to four figures per row - selections counted, the
+ * fewest and the most pairs a first scan let through, selections that needed the second scan.  This call copies
+ * them to `out` (if not null) and then, if reset != 0, starts them afresh (count 0, fewest 2^31 - 1, most 0,
+ * second scans 0).  A workspace's figures mean nothing before its first reset.  Not part of the method either.
+ *   out  device, int32 [batch, n_kv_heads, 4], or null */
+int32_t hca_score_topk_monitor(const hca_shape* shape, void* workspace, int32_t* out, int32_t reset, void* stream);
+
 /* Step 3b, Eq. 5 with the softmax taken over the selected set: for each query
  * head, l_i = z~[idx_i] * sm_scale (z~ recomputed from the codes),
  * a = softmax(l), y = sum_i a_i * V[pos[idx_i]].

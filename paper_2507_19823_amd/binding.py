@@ -89,6 +89,8 @@ def lib():
         L.hca_score_topk.argtypes = [sp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.hca_score_topk_report.restype = i32
         L.hca_score_topk_report.argtypes = [sp, vp, vp, vp, vp, vp]
+        L.hca_score_topk_monitor.restype = i32
+        L.hca_score_topk_monitor.argtypes = [sp, vp, vp, i32, vp]
         L.hca_score_qkeys_lse.restype = i32
         L.hca_score_qkeys_lse.argtypes = [sp, vp, vp, vp, f32, vp, vp, vp, vp]
         L.hca_attend_gathered_global.restype = i32
@@ -220,6 +222,11 @@ def hca_score_topk_report(shape, n_resident, workspace, candidates, rescanned, s
     nr = _nres(n_resident, shape.batch)
     _check(lib().hca_score_topk_report(C.byref(shape), nr, _ptr(workspace), _ptr(candidates), _ptr(rescanned),
                                        _stream(stream)), "hca_score_topk_report")
+
+
+def hca_score_topk_monitor(shape, workspace, out=None, reset=False, stream=None):
+    _check(lib().hca_score_topk_monitor(C.byref(shape), _ptr(workspace), _ptr(out) if out is not None else None,
+                                        1 if reset else 0, _stream(stream)), "hca_score_topk_monitor")
 
 
 def hca_topk(shape, sel, n_resident, k, idx, count, workspace, stream=None):

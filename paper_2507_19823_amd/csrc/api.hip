@@ -198,6 +198,14 @@ int32_t hca_score_topk_report(const hca_shape* shape, const int64_t* n_resident,
   return launch_select_report(L, nr, nmax, workspace, candidates, rescanned, (hipStream_t)stream);
 }
 
+int32_t hca_score_topk_monitor(const hca_shape* shape, void* workspace, int32_t* out, int32_t reset, void* stream) {
+  Layout L;
+  const int32_t rc = make_layout(shape, &L);
+  if (rc != HCA_OK) return rc;
+  if (workspace == nullptr) return HCA_ERR_BAD_ARG;
+  return launch_select_monitor(L, workspace, out, reset != 0, (hipStream_t)stream);
+}
+
 int32_t hca_score_qkeys_lse(const hca_shape* shape, const void* kcache, const void* q_f16,
                             const int64_t* n_resident, float sm_scale, float* sel, float* lse, void* workspace,
                             void* stream) {

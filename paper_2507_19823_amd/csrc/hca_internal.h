@@ -107,6 +107,7 @@ struct SelectOut {
   uint32_t* samples;    // [rows][m_samples] keys of the sampled slots (0: no such slot)
   int64_t row_entries;
   int m_samples;        // slots sampled per row (select_sample_count)
+  uint32_t* mon;        // [rows][4] running figures of the selections on this workspace, or null (not kept)
 };
 constexpr int kSampleMax = 65536;
 int select_sample_count(int64_t nmax, int32_t k);
@@ -170,6 +171,7 @@ int32_t launch_select_begin(const Layout& L, const void* kcache, const void* q, 
                             void* ws, hipStream_t st, uint64_t* stamps = nullptr);
 int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,
                              int32_t* idx, int32_t* count, void* ws, hipStream_t st, bool small_wg = false);
+int32_t launch_select_monitor(const Layout& L, void* ws, int32_t* out, int reset, hipStream_t st);
 int32_t launch_select_report(const Layout& L, const NRes& nr, int64_t nmax, void* ws, int32_t* candidates,
                              int32_t* rescanned, hipStream_t st);
 int32_t launch_score_topk(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax, int32_t k,

@@ -242,6 +242,8 @@ struct TopkWs {
   // scan + top-k in one call only
   uint32_t* samples;   // [rows][kSampleMax] keys of the sampled slots
   uint32_t* spec;      // [rows][4]: threshold key, 1 = row scanned a second time, unused, unused
+  uint32_t* mon;       // [rows][4] since the last reset: fused selections, fewest and most pairs a first scan let
+                       // through, selections that needed the second scan
 };
 
 // chunk geometry for a row of n slots: at most 1024 chunks, each a multiple of 1024 slots, >= 4096
@@ -274,6 +276,7 @@ size_t topk_workspace_bytes(int rows, int64_t cap) {
   b += align_up((int64_t)rows * 4 * 4, 256);
   b += align_up((int64_t)rows * kSampleMax * 4, 256);
   b += align_up((int64_t)rows * 4 * 4, 256);
+  b += align_up((int64_t)rows * 4 * 4, 256);
   return b;
 }
 
@@ -292,7 +295,8 @@ static void topk_carve(TopkWs* t, void* ws, int rows, int64_t cap) {
   t->pstate = (uint64_t*)w; w += align_up((int64_t)rows * 4 * 8, 256);
   t->prow = (uint32_t*)w;   w += align_up((int64_t)rows * 4 * 4, 256);
   t->samples = (uint32_t*)w; w += align_up((int64_t)rows * kSampleMax * 4, 256);
-  t->spec = (uint32_t*)w;
+  t->spec = (uint32_t*)w;    w += align_up((int64_t)rows * 4 * 4, 256);
+  t->mon = (uint32_t*)w;
 }
 
 __global__ void tk_zero(uint32_t* p, int64_t n) {
@@ -837,6 +841,13 @@ __device__ __forceinline__ void tk_resolve_emit_body(const int64_t chunk, const 
   }
   __syncthreads();
   const uint32_t total = off[1024];
+  if (!only_failed && tid == 0 && so.mon != nullptr) {      // one workgroup per row and launches in stream order: no atomics
+    uint32_t* m = so.mon + 4 * row;
+    m[0] += 1;
+    m[1] = total < m[1] ? total : m[1];
+    m[2] = total > m[2] ? total : m[2];
+    if (total < (uint32_t)want) m[3] += 1;
+  }
   if (total < (uint32_t)want) {
     // the sampled threshold was too high: scan the row again, with the second threshold if the first scan counted
     // enough slots at or above it, else without one
@@ -1209,7 +1220,8 @@ int32_t fused_plan(const Layout& L, const NRes& nr, int64_t nmax, int32_t k, voi
   f->nchunks = (int)((nblocks + 4 * bpw - 1) / (4 * bpw));
   if (f->nchunks < 1) f->nchunks = 1;
   if (f->nchunks > kSelectMaxChunks || (int64_t)f->nchunks * f->chunk > f->t.row_entries) return HCA_ERR_CAPACITY;
-  f->so = SelectOut{f->t.spec, f->t.ncand, f->t.above, f->t.cand, f->t.samples, f->t.row_entries, select_sample_count(nmax, k)};
+  f->so = SelectOut{f->t.spec, f->t.ncand, f->t.above, f->t.cand, f->t.samples, f->t.row_entries, select_sample_count(nmax, k),
+                    f->t.mon};
   return HCA_OK;
 }
 }  // namespace
@@ -1378,6 +1390,22 @@ int32_t launch_select_report(const Layout& L, const NRes& nr, int64_t nmax, void
   const int32_t rc = fused_plan(L, nr, nmax, 1, ws, &f);
   if (rc != HCA_OK) return rc;
   tk_select_report<<<L.rows, 256, 0, st>>>(f.t, nmax > 0 ? f.nchunks : 0, candidates, rescanned);
+  HCA_HIP(hipGetLastError());
+  return HCA_OK;
+}
+
+// The running figures of the fused selections on a workspace (mon above), copied out and / or started afresh.
+__global__ void tk_select_monitor(uint32_t* __restrict__ mon, int rows, int32_t* __restrict__ out, int reset) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= rows * 4) return;
+  if (out != nullptr) out[i] = (int32_t)mon[i];
+  if (reset) mon[i] = (i & 3) == 1 ? 0x7fffffffu : 0u;
+}
+
+int32_t launch_select_monitor(const Layout& L, void* ws, int32_t* out, int reset, hipStream_t st) {
+  TopkWs t;
+  topk_carve(&t, ws, L.rows, L.cap);
+  tk_select_monitor<<<(L.rows * 4 + 255) / 256, 256, 0, st>>>(t.mon, L.rows, out, reset);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

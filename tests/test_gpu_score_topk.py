@@ -157,3 +157,38 @@ def test_second_scan_with_the_deeper_threshold(H, oracle):
             + 0.02 * torch.randn(n, 128, generator=g)).to(torch.float16)
     cand, resc = _run(H, oracle, w, keys[None, None], q, [n], k)
     assert resc[0] == 1 and k <= cand[0] < n // 4
+
+
+def test_running_monitor_over_several_calls(H):
+    """hca_score_topk_monitor: calls counted, fewest / most pairs of a first scan and second scans per row, over
+    three selections at different lengths (compared with the per-call report after each)."""
+    from paper_2507_19823_amd import binding as B
+    from paper_2507_19823_amd.session import LayerState
+    w = S.Workload("mon", 93, 2, 8, 2, 60000, 4, 32, 512)
+    d = S.make_layer(w, want_values=False)
+    st = LayerState(w.batch, w.n_q_heads, w.n_kv_heads, w.n, w.bits, w.group, k_max=w.k, want_z=False)
+    st.quantize(d["keys"].cuda())
+    R = w.batch * w.n_kv_heads
+    idx = torch.zeros(R, w.k, dtype=torch.int32, device="cuda")
+    count = torch.zeros(R, dtype=torch.int32, device="cuda")
+    cand = torch.zeros(R, dtype=torch.int32, device="cuda")
+    resc = torch.zeros(R, dtype=torch.int32, device="cuda")
+    mon = torch.full((R, 4), -7, dtype=torch.int32, device="cuda")
+    B.hca_score_topk_monitor(st.shape, st.ws, None, True)
+    seen = []
+    for lens in ([60000, 700], [31000, 31000], [45000, 60000]):
+        st.n = list(lens)
+        B.hca_score_topk(st.shape, st.kcache, d["q"].cuda(), st.n, w.k, idx, count, st.ws)
+        B.hca_score_topk_report(st.shape, st.n, st.ws, cand, resc)
+        torch.cuda.synchronize()
+        assert int(resc.sum()) == 0
+        seen.append(cand.cpu().numpy().copy())
+    B.hca_score_topk_monitor(st.shape, st.ws, mon, True)
+    torch.cuda.synchronize()
+    m, seen = mon.cpu().numpy(), np.stack(seen)
+    assert np.all(m[:, 0] == 3) and np.all(m[:, 3] == 0)
+    assert np.array_equal(m[:, 1], seen.min(0)) and np.array_equal(m[:, 2], seen.max(0))
+    B.hca_score_topk_monitor(st.shape, st.ws, mon, False)       # after the reset above
+    torch.cuda.synchronize()
+    m = mon.cpu().numpy()
+    assert np.all(m[:, 0] == 0) and np.all(m[:, 1] == 2**31 - 1) and np.all(m[:, 2] == 0) and np.all(m[:, 3] == 0)
