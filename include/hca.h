@@ -33,6 +33,14 @@
  *  - Supported shapes: head_dim 128; (bits, group) = (4, 32) or (2, 64);
  *    n_q_heads / n_kv_heads in {1, 2, 4}.  Anything else: HCA_ERR_UNSUPPORTED.
  *  - Inputs must be finite (no NaN / Inf); the result is unspecified otherwise.
+ *  - State the library keeps between calls (everything else is the caller's):
+ *    the process-wide launch knobs of hca_tune (read by the per-call entry
+ *    points; a step driver copies them once at creation); a per-thread ring of HIP events used inside
+ *    hca_sparse_attend; the worker threads of hca_host_weighted_sum, started by
+ *    its first call with n_threads > 1, asleep between calls and never joined
+ *    before the process ends; the 16 MiB device array of hca_topk_noalloc; and
+ *    whatever an hca_pipeline object holds until hca_pipeline_destroy (events,
+ *    its own worker threads and pinned exchange buffers when host_chunks > 0).
  */
 #ifndef HCA_H_
 #define HCA_H_
@@ -488,6 +496,11 @@ size_t hca_vq_workspace_bytes(const hca_shape* shape, const hca_vq_codebook* cb,
 
 /* Offline codebook training on the host (Sec. 3.1): Lloyd's k-means per group over the sub-vectors
  * of a validation set.  Host pointers only, no device work, blocks until done.
+ * The paper trains with mini-batch k-means (Sec. 4.1, implementation details); this is the full-batch
+ * form - every round assigns all n_val sub-vectors and then moves every centroid to the mean of its
+ * members - with the seeds handed in by the caller, so that a second implementation reproduces the
+ * codebook bit for bit.  Any codebook of the same shape, however trained, can be given to the other
+ * hca_vq_* calls.
  *   kval_f16   host, fp16 [n_val, head_dim]
  *   init       host, int32: shared == 0: [g, c] validation tokens whose sub-vectors seed group i's
  *              centroids; shared != 0: [c] entries of the pool of all g * n_val sub-vectors (entry
