@@ -809,6 +809,53 @@ def cpu_split_probe(w, threads=16, iters=6):
     return out
 
 
+def correlated_selection(w, iters=12):
+    """hca_score_topk on one layer of `w` whose keys resemble their neighbours (synth_inputs.make_correlated_layer,
+    runs of up to 64 and of up to 4096 slots), beside the same call on the independent keys of the main workload:
+    time per call, spread of the candidate counts, rows that needed the second scan.  The results are the same
+    sets as hca_score_qkeys + hca_topk give (checked here on the GPU; against the oracle in the tests)."""
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    from paper_2507_19823_amd.session import LayerState
+    R = w.batch * w.n_kv_heads
+    out = {"workload": w.name, "k": w.k}
+    for name, run_max in (("independent", 0), ("runs_up_to_64", 64), ("runs_up_to_4096", 4096)):
+        d = (S.make_layer(w, 0, device="cuda", want_values=False) if run_max == 0 else
+             S.make_correlated_layer(w, 0, device="cuda", run_max=run_max))
+        st = LayerState(w.batch, w.n_q_heads, w.n_kv_heads, w.n + 32, w.bits, w.group, k_max=w.k, want_z=False)
+        for a in range(0, w.n, 1 << 18):
+            st.quantize(d["keys"][:, :, a:a + (1 << 18)].contiguous())
+        q = d["q"]
+        del d
+        idx = torch.zeros(R, w.k, dtype=torch.int32, device="cuda")
+        count = torch.zeros(R, dtype=torch.int32, device="cuda")
+        st.score(q)
+        st.topk(w.k)
+        for _ in range(3):
+            B.hca_score_topk(st.shape, st.kcache, q, st.n, w.k, idx, count, st.ws)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(idx.view(-1), st.idx.reshape(-1)))
+        ms = []
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(iters):
+            e0.record()
+            B.hca_score_topk(st.shape, st.kcache, q, st.n, w.k, idx, count, st.ws)
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        cand = torch.zeros(R, dtype=torch.int32, device="cuda")
+        resc = torch.zeros(R, dtype=torch.int32, device="cuda")
+        B.hca_score_topk_report(st.shape, st.n, st.ws, cand, resc)
+        torch.cuda.synchronize()
+        out[name] = {"score_topk_ms": sorted(ms)[iters // 2], "candidates_min": int(cand.min()),
+                     "candidates_max": int(cand.max()), "rows_rescanned": int(resc.sum()),
+                     "same_sets_as_scan_plus_topk": same}
+        del st, idx, count
+        torch.cuda.empty_cache()
+    return out
+
+
 def scan_only(w, iters):
     """Key-scan kernel alone on one layer (two cache copies alternate), preceded by a plain 1 GiB
     device copy whose FETCH_SIZE / WRITE_SIZE readings calibrate the counters (profiles/)."""
@@ -1106,6 +1153,12 @@ def main():
         log(f"selection at 1M: top-k {selection['topk_ms']:.3f} ms, Eq. 4 at tau 0.9 {selection['topp_tau0.9']['ms']:.3f} ms")
 
     others = None
+    correlated = None
+    if not args.no_latency and args.config == 4:
+        correlated = correlated_selection(w)
+        log("fused selection at 1M, ms per call (candidates min..max, second scans): " + "; ".join(
+            f"{k_} {v_['score_topk_ms']:.3f} ({v_['candidates_min']}..{v_['candidates_max']}, {v_['rows_rescanned']})"
+            for k_, v_ in correlated.items() if isinstance(v_, dict)))
     if not args.no_latency and args.pipeline == "native" and args.config == 4:
         # the same step driver on the other stacks (a few steps each; the headline stays config 4)
         st4 = (main_s[0], extra[0], gath_s[0], extra[1])
@@ -1307,6 +1360,7 @@ def main():
         "steps_other_configs": others,
         "codebook_key_path": codebook,
         "selection": selection,
+        "fused_selection_on_correlated_keys": correlated,
         "paper_form_step": paper_form,
         "value_side_cpu_split": cpu_split,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,

@@ -11,6 +11,12 @@ Recipe, per (config id, layer):
           the query of that head is fp16(u + 0.3 * N(0,1))
   seed    1000*config + 10*layer + tensor id (0 keys, 1 values, 2 outlier channels,
           3 planted positions, 4 planted vectors, 5 query noise, 6.. appended tokens)
+
+Correlated variant (make_correlated_layer): what a real key cache looks like to a sampler that reads whole
+code blocks - neighbouring tokens resemble each other.  The sequence is cut into runs whose lengths are
+2^e, e uniform in 0..log2(run_max); every run has one direction vector c ~ N(0,1) (outlier channels x 8) and
+its tokens are fp16(c + noise * N(0,1)); the query of every head is fp16(N(0,1)) with the outlier scaling.
+Seeds: tensor ids 7 (run lengths), 8 (run vectors), 9 (noise and queries) of the same scheme.
 """
 from dataclasses import dataclass
 
@@ -111,6 +117,34 @@ def make_layer(w: Workload, layer=0, device="cpu", want_values=True):
         for hq in range(Hq):
             keys[b, hq // G, planted[b, hq].to(device)] = u_dev[b, hq]
     return {"keys": keys, "values": values, "q": q.to(device), "planted": planted}
+
+
+def make_correlated_layer(w: Workload, layer=0, device="cpu", run_max=4096, noise=0.3):
+    """Keys whose scores are strongly correlated inside runs of up to `run_max` neighbouring slots (see the
+    module text).  Returns dict with keys fp16 [B, Hkv, n, D], q fp16 [B, Hq, D], runs int64 [B, Hkv] (count)."""
+    base = 1000 * w.config + 10 * layer
+    B, Hq, Hkv, D, n, G = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.n, w.gqa
+    m = outlier_scale(w, layer, device)
+    gl, gv, gn = _gen("cpu", base + 7), _gen(device, base + 8), _gen(device, base + 9)
+    e_max = max(0, int(run_max).bit_length() - 1)
+    keys = torch.empty(B, Hkv, n, D, dtype=torch.float16, device=device)
+    runs = torch.zeros(B, Hkv, dtype=torch.int64)
+    for b in range(B):
+        for h in range(Hkv):
+            ends = torch.zeros(0, dtype=torch.int64)
+            while ends.numel() == 0 or int(ends[-1]) < n:            # run lengths 2^e until the row is covered
+                more = torch.cumsum(2 ** torch.randint(0, e_max + 1, (4096,), generator=gl), 0)
+                ends = torch.cat([ends, more + (int(ends[-1]) if ends.numel() else 0)])
+            ends = ends[: int(torch.searchsorted(ends, n)) + 1]
+            runs[b, h] = ends.numel()
+            c = torch.randn(ends.numel(), D, generator=gv, device=device) * m[b, h]
+            run_of = torch.searchsorted(ends.to(device), torch.arange(n, device=device), right=True)
+            for r0 in range(0, n, 1 << 18):
+                r1 = min(n, r0 + (1 << 18))
+                e = torch.randn(r1 - r0, D, generator=gn, device=device)
+                keys[b, h, r0:r1] = (c[run_of[r0:r1]] + noise * e).to(torch.float16)
+    q = (torch.randn(B, Hq, D, generator=gn, device=device) * m.repeat_interleave(G, dim=1)).to(torch.float16)
+    return {"keys": keys, "q": q, "runs": runs}
 
 
 def make_step(w: Workload, layer, step, device="cpu"):

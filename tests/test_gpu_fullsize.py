@@ -114,6 +114,38 @@ def test_one_layer_at_full_size(oracle, cfg):
         assert _rel_err(st.y.cpu().numpy().reshape(-1, 128), y) <= TOL
 
 
+@pytest.mark.parametrize("run_max", [64, 4096])
+def test_fused_selection_on_correlated_keys_at_full_size(oracle, run_max):
+    """Config 4's layer shape with keys that resemble their neighbours over runs of up to `run_max` slots
+    (synth_inputs.make_correlated_layer): a sampled code block then behaves like one sample, the candidate counts
+    spread far more than on independent keys, and the index sets must still be the oracle's, whatever path the
+    rows take (the per-row figures are printed, not asserted, except that they are consistent)."""
+    from paper_2507_19823_amd import binding as B
+    from paper_2507_19823_amd.session import LayerState
+    w = S.CONFIGS[4]
+    R, n = w.batch * w.n_kv_heads, w.n
+    d = S.make_correlated_layer(w, 0, device="cuda", run_max=run_max)
+    st = LayerState(w.batch, w.n_q_heads, w.n_kv_heads, n + 32, w.bits, w.group, k_max=w.k, want_z=False)
+    for a in range(0, n, 1 << 18):
+        st.quantize(d["keys"][:, :, a:a + (1 << 18)].contiguous())
+    idx = torch.full((R, w.k), -1, dtype=torch.int32, device="cuda")
+    count = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    B.hca_score_topk(st.shape, st.kcache, d["q"], st.n, w.k, idx, count, st.ws)
+    cand = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    resc = torch.full((R,), -1, dtype=torch.int32, device="cuda")
+    B.hca_score_topk_report(st.shape, st.n, st.ws, cand, resc)
+    torch.cuda.synchronize()
+    oc = oracle.Cache(R, n + 32, 128, w.bits, w.group)
+    oracle.quantize(oc, _rows(d["keys"]))
+    sel, _ = oracle.score(oc, d["q"].cpu().numpy().reshape(-1, 128), want_z=False)
+    oidx, ocount = oracle.topk(sel, oc.n, w.k)
+    assert np.array_equal(count.cpu().numpy(), ocount)
+    assert np.array_equal(idx.cpu().numpy(), oidx), "correlated keys: index sets differ"
+    cand, resc = cand.cpu().numpy(), resc.cpu().numpy()
+    print(f"run_max {run_max}: candidates {cand.tolist()}, second scans {resc.tolist()}")
+    assert np.all(cand >= w.k) and np.all(cand <= n)
+
+
 @pytest.mark.parametrize("c", [256, 8192])
 def test_vq_one_layer_at_full_size(oracle, c):
     """Codebook form at the shapes bench.py --mode vq times (config 4 layer: 1 Mi tokens x 8 KV heads, g = 32;
