@@ -377,10 +377,17 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8, fused=False, streams=
             m.decode_step_native(t + iters + i, i)
             torch.cuda.synchronize()
         per = sorted(B.hca_pipeline_scan_ms(m.pl, i, 1)[0] for i in range(iters))
-        scan = per[iters // 2]                       # HIP events around the launch
+        bracket = per[iters // 2]                    # HIP events around the launch: the kernel plus its dispatch
+        # the kernel's own duration, as rocprofv3 reports it and as the main roofline figure is taken: from the
+        # per-wave wall-clock stamps of the launch, first wave start to last wave end
+        st_ = m.stamps[:, 0]
+        starts = torch.where(st_[..., 0] > 0, st_[..., 0], torch.full_like(st_[..., 0], 1 << 62)).amin(-1)
+        own = sorted(((st_[..., 1].amax(-1) - starts).double() / B.hca_wall_clock_khz()).tolist())
+        scan = own[iters // 2]
         scan_bytes = w.batch * w.n_kv_heads * (resident + iters + iters // 2) * code_bytes
         B.hca_pipeline_destroy(m.pl)
     out = {"workload": w.name, "resident_tokens": resident, "ms_per_layer": lat, "score_topk_ms": score_topk_ms,
+           "scan_event_bracket_ms": bracket if fused and streams is not None else None,
            "key_scan_ms": scan, "key_scan_GBs": scan_bytes / scan / 1e6, "key_scan_frac_of_hbm_peak": scan_bytes / scan / 1e6 / HBM_PEAK_GBS,
            "gather_ms": gms, "gather_GBs": gbytes / gms / 1e6, "gather_frac_of_link_peak": gbytes / gms / 1e6 / link_peak}
     del m
@@ -1036,6 +1043,8 @@ def main():
                          "overlap; pair = one scan launch per two layers")
     ap.add_argument("--pipe-sets", type=int, default=8, choices=[4, 5, 6, 7, 8],
                     help="native step driver: sets of selection / staging buffers, i.e. layers in flight between top-k and attend")
+    ap.add_argument("--resident", type=int, default=0,
+                    help="--mode scan / select: tokens per sequence instead of the workload's context length")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gap-report", action="store_true",
                     help="log the largest idle times between consecutive scan launches with their step.layer")
@@ -1085,6 +1094,9 @@ def main():
     # a 32 Ki-token layer (20 MiB of codes) would sit in the last-level cache if it were scanned over and over:
     # the small workload is run as 16 layers, i.e. 16 cache copies in rotation
     L = args.layers or (16 if args.config == 2 else w.layers)
+    if args.resident and args.mode in ("scan", "select"):
+        import dataclasses
+        w = dataclasses.replace(w, n=args.resident)
     if args.mode == "scan":
         return scan_only(w, args.steps)
     if args.mode == "select":
@@ -1123,7 +1135,10 @@ def main():
                                   streams=(main_s[0], extra[0], gath_s[0], extra[1]))
             latency[name]["fused_select"] = {"ms_per_layer": f["ms_per_layer"], "score_topk_ms": f["score_topk_ms"],
                                              "select_scan_ms": f["key_scan_ms"], "select_scan_GBs": f["key_scan_GBs"],
-                                             "select_scan_frac_of_hbm_peak": f["key_scan_frac_of_hbm_peak"]}
+                                             "select_scan_frac_of_hbm_peak": f["key_scan_frac_of_hbm_peak"],
+                                             "select_scan_timed_by": "per-wave wall-clock stamps of the launch (first wave "
+                                                                     "start to last wave end, the kernel's own duration)",
+                                             "select_scan_event_bracket_ms": f.get("scan_event_bracket_ms")}
             log(f"latency probe {name}: {f['ms_per_layer']:.3f} ms per layer with scan and top-k fused "
                 f"({f['score_topk_ms']:.3f} ms for the two; the selecting scan alone {f['key_scan_ms']:.3f} ms)")
             for parts in args.latency_parts:

@@ -95,7 +95,15 @@ struct QOperand {
   v4i a[2];       // A operand of MFMA m = 0, 1
   float qf[4];    // (float) sum of qfx over group g, for head lane/16
   float unscale;  // 2^-s of head lane/16
+  float nzero;    // -0.0f, opaque to the compiler (see zero_term)
 };
+
+// zero_g * Q_g rounded once, as a fused multiply-add with the addend -0.0f (x * y + (-0) == x * y for all finite
+// x, y, signs of zero included): in this form the fp16 -> fp32 conversion of `zero` rides inside v_fma_mix_f32
+// instead of costing an instruction of its own.  The addend is kept opaque so that it is not folded back.
+__device__ __forceinline__ float zero_term(uint32_t zero_bits16, float qf, float nzero) {
+  return __builtin_fmaf(h2f(zero_bits16), qf, nzero);
+}
 
 // channel held in byte x (0..15) of the B operand of MFMA m by a lane of k-group j
 template <int BITS>
@@ -169,6 +177,48 @@ __device__ __forceinline__ void build_operand(const QShared* sh, QOperand<BITS>*
 #pragma unroll
   for (int g = 0; g < 4; ++g) op->qf[g] = (float)sh->qsum[hd][g];
   op->unscale = ldexpf(1.0f, -sh->sexp[hd]);
+  float nz = -0.0f;
+  asm volatile("" : "+v"(nz));
+  op->nzero = nz;
+}
+
+// The same operand built once per workgroup of four waves instead of once per wave (every wave of a scan
+// workgroup uses the same query): wave w forms two of the eight operand dwords of every lane, the image goes
+// through LDS (img: 64 lanes x 8 dwords).  To be called by all 256 threads; contains a barrier.
+template <int BITS>
+__device__ __forceinline__ void build_operand_shared(const QShared* sh, uint32_t* img, QOperand<BITS>* op) {
+  const int lane = threadIdx.x & 63, w = (threadIdx.x >> 6) & 3;
+  const int r = lane & 15, j = lane >> 4;
+  const int head = r >> 2, sub = r & 3;
+  const int m = w >> 1;
+  const int piece = sub & 1;
+  const bool active = BITS == 4 ? ((sub >> 1) == (j >> 1)) : (sub < 2);
+#pragma unroll
+  for (int dd = 0; dd < 2; ++dd) {
+    const int i = 2 * (w & 1) + dd;
+    int reg = 0;
+    if (active) {
+#pragma unroll
+      for (int y = 0; y < 4; ++y) {
+        const int v = sh->qfx[head][operand_channel<BITS>(m, j, 4 * i + y)];
+        const int lo = ((v + 128) & 255) - 128;
+        const int hi = (v - lo) / 256;
+        reg |= ((piece ? hi : lo) & 255) << (8 * y);
+      }
+    }
+    img[lane * 8 + 4 * m + i] = (uint32_t)reg;
+  }
+  __syncthreads();
+  const v4i* im = reinterpret_cast<const v4i*>(img + lane * 8);
+  op->a[0] = im[0];
+  op->a[1] = im[1];
+  const int hd = lane >> 4;
+#pragma unroll
+  for (int g = 0; g < 4; ++g) op->qf[g] = (float)sh->qsum[hd][g];
+  op->unscale = ldexpf(1.0f, -sh->sexp[hd]);
+  float nz = -0.0f;
+  asm volatile("" : "+v"(nz));
+  op->nzero = nz;
 }
 
 __device__ __forceinline__ v4i mfma_i8(v4i a, v4i b, v4i c) {
@@ -184,10 +234,10 @@ __device__ __forceinline__ float score_block4(const QOperand<4>& op, uint4 w, ui
   v4i b1 = {(int)(w.z & M), (int)((w.z >> 4) & M), (int)(w.w & M), (int)((w.w >> 4) & M)};
   v4i d0 = mfma_i8(op.a[0], b0, zero);   // rows: lo/hi of group 0, lo/hi of group 1
   v4i d1 = mfma_i8(op.a[1], b1, zero);   // rows: lo/hi of group 2, lo/hi of group 3
-  const float t0 = fmaf(h2f(mw.x), (float)(d0.y * 256 + d0.x), h2f(mw.z) * op.qf[0]);
-  const float t1 = fmaf(h2f(mw.x >> 16), (float)(d0.w * 256 + d0.z), h2f(mw.z >> 16) * op.qf[1]);
-  const float t2 = fmaf(h2f(mw.y), (float)(d1.y * 256 + d1.x), h2f(mw.w) * op.qf[2]);
-  const float t3 = fmaf(h2f(mw.y >> 16), (float)(d1.w * 256 + d1.z), h2f(mw.w >> 16) * op.qf[3]);
+  const float t0 = fmaf(h2f(mw.x), (float)(d0.y * 256 + d0.x), zero_term(mw.z, op.qf[0], op.nzero));
+  const float t1 = fmaf(h2f(mw.x >> 16), (float)(d0.w * 256 + d0.z), zero_term(mw.z >> 16, op.qf[1], op.nzero));
+  const float t2 = fmaf(h2f(mw.y), (float)(d1.y * 256 + d1.x), zero_term(mw.w, op.qf[2], op.nzero));
+  const float t3 = fmaf(h2f(mw.y >> 16), (float)(d1.w * 256 + d1.z), zero_term(mw.w >> 16, op.qf[3], op.nzero));
   const float a = t0 + t1, b = t2 + t3;
   return (a + b) * op.unscale;
 }
@@ -201,8 +251,8 @@ __device__ __forceinline__ float score_tile2(const QOperand<2>& op, uint32_t c0,
   v4i b1 = {(int)(c1 & M), (int)((c1 >> 2) & M), (int)((c1 >> 4) & M), (int)((c1 >> 6) & M)};
   v4i d0 = mfma_i8(op.a[0], b0, zero);   // rows: lo, hi of group 0
   v4i d1 = mfma_i8(op.a[1], b1, zero);   // rows: lo, hi of group 1
-  const float t0 = fmaf(h2f(mw.x), (float)(d0.y * 256 + d0.x), h2f(mw.y) * op.qf[0]);
-  const float t1 = fmaf(h2f(mw.x >> 16), (float)(d1.y * 256 + d1.x), h2f(mw.y >> 16) * op.qf[1]);
+  const float t0 = fmaf(h2f(mw.x), (float)(d0.y * 256 + d0.x), zero_term(mw.y, op.qf[0], op.nzero));
+  const float t1 = fmaf(h2f(mw.x >> 16), (float)(d1.y * 256 + d1.x), zero_term(mw.y >> 16, op.qf[1], op.nzero));
   return (t0 + t1) * op.unscale;
 }
 

@@ -1,6 +1,7 @@
 // Step 2: the key scan.  z~ = q . Q(K)^T (Eq. 2 / Eq. 3) for every resident token, streamed
 // once from HBM as packed codes and contracted on the matrix cores in exact integer arithmetic.
 #include <math.h>
+#include <stdlib.h>
 
 #include "hca_internal.h"
 #include "quantize_device.h"
@@ -42,6 +43,40 @@ __device__ __forceinline__ uint4 allgather_rows(uint32_t v) {
   return uint4{b[0], c[0], b[1], c[1]};
 }
 
+// The same all-gather through the LDS crossbar (ds_bpermute_b32: no LDS memory is touched): four reads with the
+// byte addresses of lanes column + 16 r, r = 0..3.  The scan is bound by vector-ALU issue, the LDS pipe is idle.
+struct RowGather {
+  int a0, a1, a2, a3;
+  __device__ __forceinline__ explicit RowGather(int lane) {
+    a0 = 4 * (lane & 15); a1 = a0 + 64; a2 = a0 + 128; a3 = a0 + 192;
+  }
+  __device__ __forceinline__ uint4 operator()(uint32_t v) const {
+    return uint4{(uint32_t)__builtin_amdgcn_ds_bpermute(a0, (int)v), (uint32_t)__builtin_amdgcn_ds_bpermute(a1, (int)v),
+                 (uint32_t)__builtin_amdgcn_ds_bpermute(a2, (int)v), (uint32_t)__builtin_amdgcn_ds_bpermute(a3, (int)v)};
+  }
+};
+
+// Four values per lane, one per 16-token tile (z0..z3: the score of this lane's (token, head) in tiles 0..3): returns,
+// on the lanes of row r, the maximum over the four rows (= the token's four query heads) of tile r's values - the
+// reduction and the hand-over of tile r to row r in three swaps and three maxima.
+__device__ __forceinline__ float max_over_heads_scatter(float z0, float z1, float z2, float z3) {
+  const auto p = __builtin_amdgcn_permlane32_swap(__float_as_uint(z0), __float_as_uint(z2), false, false);
+  const auto q = __builtin_amdgcn_permlane32_swap(__float_as_uint(z1), __float_as_uint(z3), false, false);
+  // p[0] = [z0.r0 z0.r1 z2.r0 z2.r1], p[1] = [z0.r2 z0.r3 z2.r2 z2.r3]: maxima over the row pairs (0,2), (1,3)
+  const float m02 = fmax_raw(__uint_as_float(p[0]), __uint_as_float(p[1]));
+  const float m13 = fmax_raw(__uint_as_float(q[0]), __uint_as_float(q[1]));
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(m02), __float_as_uint(m13), false, false);
+  // r[0] = [m02.r0 m13.r0 m02.r2 m13.r2], r[1] = [m02.r1 m13.r1 m02.r3 m13.r3]
+  return fmax_raw(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// The float whose order key is `key`, or -inf for keys below those of all finite floats (0: "no threshold"):
+// v >= key_floor(key) <=> order_key(v) >= key for every finite v (-0 and +0 share a key and compare equal).
+__device__ __forceinline__ float key_floor(uint32_t key) {
+  if (key <= 0x007fffffu) return -INFINITY;
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
 // Work split: grid.y = row, grid.x = chunk; a workgroup has 4 waves and each wave scans `bpw`
 // consecutive 1 KiB code blocks, U at a time: U code loads (16 B per lane, the lane's own MFMA
 // operand bytes) and U meta loads (4 B per lane, then an all-gather over the four lanes of a
@@ -69,6 +104,7 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
   // all the wave's slots), then the workgroup strings the four lists together
   extern __shared__ uint2 wlist_all[];
   __shared__ uint32_t wcount[8];
+  __shared__ __align__(16) uint32_t opimg[64 * 8];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nblocks = (int)((n + L.tpb - 1) / L.tpb);
@@ -110,20 +146,20 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
     lm = nm;
   };
   auto lse_fold = [&]() {};
-  // scores block b; returns the per-token max over heads of its tile(s) (on every lane)
-  auto score_one = [&](int b, uint4 wv, uint32_t mword, float& best0, float& best1) {
-    const uint4 mv = allgather_rows(mword);
+  const RowGather gather_rows(lane);
+  // scores block b: this lane's (token, head) score of the block's tile (4-bit) or two tiles (2-bit); -inf on the
+  // lanes of query heads that do not exist
+  auto score_one = [&](int b, uint4 wv, uint4 mv, float& zt0, float& zt1) {
     if constexpr (BITS == 4) {
       const float zv = score_block4(op, wv, mv);
-      best0 = max_over_heads(head_live ? zv : -INFINITY);
-      best1 = best0;
+      zt0 = head_live ? zv : -INFINITY;
       if (WRITE_Z && head_live && b * 16 + t < ntok) zrow[b * 16] = zv;
       if constexpr (LSE) lse_add(zv, head_live && b * 16 + t < ntok);
     } else {
       const float z0 = score_tile2(op, wv.x, wv.y, uint2{mv.x, mv.y});
       const float z1 = score_tile2(op, wv.z, wv.w, uint2{mv.z, mv.w});
-      best0 = max_over_heads(head_live ? z0 : -INFINITY);
-      best1 = max_over_heads(head_live ? z1 : -INFINITY);
+      zt0 = head_live ? z0 : -INFINITY;
+      zt1 = head_live ? z1 : -INFINITY;
       if (WRITE_Z && head_live) {
         if (b * 32 + t < ntok) zrow[b * 32] = z0;
         if (b * 32 + 16 + t < ntok) zrow[b * 32 + 16] = z1;
@@ -134,25 +170,26 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
       }
     }
   };
-  // the lane in row hd stores tile hd of four consecutive tiles starting at token tok0
   const uint32_t t0key = SELECT ? so.spec[4 * row] : 0u;
   const uint32_t t1key = SELECT ? so.spec[4 * row + 2] : 0u;   // the deeper threshold: only counted against
+  const float t0f = key_floor(t0key), t1f = key_floor(t1key);  // the same thresholds as floats: one compare each
   uint32_t n1 = 0;                                         // slots of this wave with key >= t1key (wave-uniform)
   uint2* wlist = SELECT ? wlist_all + (int64_t)w * bpw * L.tpb : nullptr;
   uint32_t nlist = 0;                                     // SELECT: pairs in this wave's list so far (wave-uniform)
   // SELECT: appends the lanes' pairs that qualify, in lane order (the caller's lanes are in slot order)
   auto emit_pairs = [&](float v, int tok, bool live) {
-    const uint32_t key = order_key(v);
-    const bool hit = live && key >= t0key;
-    n1 += (uint32_t)__popcll(__ballot(live && key >= t1key));
-    const uint64_t m = __ballot(hit);
+    n1 += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(live && v >= t1f));
+    const bool hit = live && v >= t0f;
+    const uint64_t m = __builtin_amdgcn_ballot_w64(hit);
     if (m != 0) {
-      if (hit) wlist[nlist + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = uint2{key, (uint32_t)tok};
+      if (hit) wlist[nlist + (uint32_t)__popcll(m & ((1ull << lane) - 1))] = uint2{order_key(v), (uint32_t)tok};
       nlist += (uint32_t)__popcll(m);
     }
   };
-  auto store4 = [&](int tok0, float v0, float v1, float v2, float v3) {
-    const float v = hd == 0 ? v0 : (hd == 1 ? v1 : (hd == 2 ? v2 : v3));
+  // four consecutive tiles starting at token tok0, this lane's (token, head) score in each: the lanes of row r end
+  // up with tile r's selection score (maximum over the heads), i.e. lane l with that of token tok0 + l
+  auto store4 = [&](int tok0, float z0, float z1, float z2, float z3) {
+    const float v = max_over_heads_scatter(z0, z1, z2, z3);
     const int tok = tok0 + lane;                          // 16*hd + t == lane
     if constexpr (SELECT) emit_pairs(v, tok, tok < ntok);
     else if (tok < ntok) selrow[tok] = v;
@@ -171,8 +208,17 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
   };
   auto consume = [&](int g0, const uint4 (&wv)[U], const uint32_t (&mw)[U]) {
     float lo[U], hi[U];
+    // the meta all-gather runs two blocks ahead of the scoring (its results come back through the LDS queue); the
+    // scheduling fences keep it there - all U gathers issued at once cost a wave of occupancy in registers
+    uint4 mv0 = gather_rows(mw[0]);
 #pragma unroll
-    for (int u = 0; u < U; ++u) score_one(g0 + u, wv[u], mw[u], lo[u], hi[u]);
+    for (int u = 0; u < U; ++u) {
+      const uint4 mv = mv0;
+      if (u + 1 < U) mv0 = gather_rows(mw[u + 1]);
+      score_one(g0 + u, wv[u], mv, lo[u], hi[u]);
+      if constexpr (BITS == 4) asm volatile("" : "+v"(lo[u]));
+      else asm volatile("" : "+v"(lo[u]), "+v"(hi[u]));
+    }
     if constexpr (BITS == 4) {
 #pragma unroll
       for (int u = 0; u < U; u += 4) store4((g0 + u) * 16, lo[u], lo[u + 1], lo[u + 2], lo[u + 3]);
@@ -188,7 +234,7 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
   uint32_t ma[U], mb[U];
   if (ngroups > 0) fetch(b0, wa, ma);        // first loads go out before the query is prepared
   load_query(q, row, L.gqa, L.group, &sh);
-  build_operand<BITS>(&sh, &op);
+  build_operand_shared<BITS>(&sh, opimg, &op);
   if (ngroups > 0) {
     int g = 0;
     for (; g + 2 <= ngroups; g += 2) {
@@ -207,7 +253,9 @@ __device__ __forceinline__ void score_body(const Layout& L, const uint8_t* __res
     const uint4 wv = load_stream16(&cptr[(int64_t)b0 * 64]);
     const uint32_t mw = __builtin_nontemporal_load(&mptr[(int64_t)b0 * 64]);
     float lo, hi;
-    score_one(b0, wv, mw, lo, hi);
+    score_one(b0, wv, gather_rows(mw), lo, hi);
+    lo = max_over_heads(lo);
+    if constexpr (BITS == 2) hi = max_over_heads(hi);
     if constexpr (LSE) lse_fold();
     if constexpr (SELECT) {
       // lanes 0..15 carry tile 0; with 2-bit codes lanes 16..31 carry tile 1: lane order is slot order
@@ -259,6 +307,15 @@ __global__ __launch_bounds__(256) void score_kernel(Layout L, const uint8_t* __r
                                                     float2* __restrict__ part = nullptr, SelectOut so = SelectOut{}) {
   score_body<BITS, WRITE_Z, U, LSE, SELECT>(L, kcache, q, nr.n[blockIdx.y / L.n_kv_heads], bpw, sel, z, stamps, sm_scale,
                                             part, so, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y);
+}
+
+// The selecting scan as a launch of its own (hca_score_topk): registers capped for four waves per SIMD.
+template <int BITS, int U>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void score_select_kernel(
+    Layout L, const uint8_t* __restrict__ kcache, const uint16_t* __restrict__ q, NRes nr, int bpw,
+    uint64_t* __restrict__ stamps, SelectOut so) {
+  score_body<BITS, false, U, false, true>(L, kcache, q, nr.n[blockIdx.y / L.n_kv_heads], bpw, nullptr, nullptr, stamps,
+                                          0.f, nullptr, so, (int)blockIdx.x, (int)gridDim.x, (int)blockIdx.y);
 }
 
 // The selecting scan once more for the rows whose sampled threshold left too few pairs (spec[row][1] != 0, with
@@ -551,7 +608,7 @@ struct StepJob {
   NRes a_nr, b_nr;            // lengths before the layers' own appends
 };
 template <int BITS, int U>
-__global__ __launch_bounds__(256) void score_select_step_kernel(Layout L, const uint8_t* __restrict__ kcache,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void score_select_step_kernel(Layout L, const uint8_t* __restrict__ kcache,
                                                                 const uint16_t* __restrict__ q, NRes nr, int bpw,
                                                                 uint64_t* __restrict__ stamps, SelectOut so, StepJob j) {
   const int nsb = j.b_m / kSamplePerWg;
@@ -621,7 +678,7 @@ __device__ __forceinline__ void step_side(const Layout& L, const StepSide& s, co
 }
 
 template <int BITS, int U>
-__global__ __launch_bounds__(256) void score_select_pair_kernel(Layout L, StepSide s0, StepSide s1) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void score_select_pair_kernel(Layout L, StepSide s0, StepSide s1) {
   if ((int)blockIdx.y < L.rows) step_side<BITS, U>(L, s0, (int)blockIdx.y);
   else step_side<BITS, U>(L, s1, (int)blockIdx.y - L.rows);
 }
@@ -805,7 +862,7 @@ int32_t launch_select_step(const Layout& L, const void* kcache, const void* q, c
     score_select_step_kernel<4, 8><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
                                                            so, j);
   else
-    score_select_step_kernel<2, 4><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
+    score_select_step_kernel<2, 8><<<grid, 256, lds, st>>>(L, (const uint8_t*)kcache, (const uint16_t*)q, nr, bpw, stamps,
                                                            so, j);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
@@ -863,7 +920,7 @@ int32_t launch_select_step_pair(const Layout& L, const void* const kcache[2], co
   if (rc != HCA_OK) return rc;
   dim3 grid(gx, (unsigned)(2 * L.rows));
   if (L.bits == 4) score_select_pair_kernel<4, 8><<<grid, 256, lds, st>>>(L, s0, s1);
-  else score_select_pair_kernel<2, 4><<<grid, 256, lds, st>>>(L, s0, s1);
+  else score_select_pair_kernel<2, 8><<<grid, 256, lds, st>>>(L, s0, s1);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -889,7 +946,7 @@ int32_t launch_select_rescan_pair(const Layout& L, const void* const kcache[2], 
   }
   dim3 grid(gx < 256 ? gx : 256, (unsigned)(2 * L.rows));
   if (L.bits == 4) score_failed_rows_pair_kernel<4, 8><<<grid, 256, lds, st>>>(L, rs[0], rs[1]);
-  else score_failed_rows_pair_kernel<2, 4><<<grid, 256, lds, st>>>(L, rs[0], rs[1]);
+  else score_failed_rows_pair_kernel<2, 8><<<grid, 256, lds, st>>>(L, rs[0], rs[1]);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -907,13 +964,11 @@ int32_t launch_select_scan(const Layout& L, const void* kcache, const void* q, c
   if (only_failed) {
     dim3 small(grid.x < 256 ? grid.x : 256, (unsigned)L.rows);
     if (L.bits == 4) score_failed_rows_kernel<4, 8><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
-    else score_failed_rows_kernel<2, 4><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
+    else score_failed_rows_kernel<2, 8><<<small, 256, lds, st>>>(L, kc, qq, nr, bpw, (int)grid.x, so);
   } else if (L.bits == 4) {
-    score_kernel<4, false, 8, false, true><<<grid, 256, lds, st>>>(L, kc, qq, nr, bpw, nullptr, nullptr, stamps, 0.f,
-                                                                   nullptr, so);
+    score_select_kernel<4, 8><<<grid, 256, lds, st>>>(L, kc, qq, nr, bpw, stamps, so);
   } else {
-    score_kernel<2, false, 4, false, true><<<grid, 256, lds, st>>>(L, kc, qq, nr, bpw, nullptr, nullptr, stamps, 0.f,
-                                                                   nullptr, so);
+    score_select_kernel<2, 8><<<grid, 256, lds, st>>>(L, kc, qq, nr, bpw, stamps, so);
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
