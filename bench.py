@@ -816,6 +816,76 @@ def cpu_split_probe(w, threads=16, iters=6):
     return out
 
 
+def prefill_blocks(w, sizes=(1024, 4096, 16384, 65536, 262144)):
+    """Key compression as a block-wise prefill hands it over (App. B: the keys of a block are quantised when the
+    block's attention is done): the context arrives in blocks of T tokens per sequence and every block is appended
+    with one call - hca_quantize_keys (uniform codes, 4-bit / group 32 and 2-bit / group 64) or hca_vq_assign
+    (codebook indices, g = 32, c = 256 and the paper's c = 8192).  The paper gives no block size; the sweep covers
+    1 Ki to 256 Ki tokens.  Per block size: time per call (median of HIP-event brackets around each call), tokens
+    per second, and the fraction of the bound - HBM bytes (256 B of fp16 key read + the codes written per token and
+    KV head) for the uniform form, fp32 vector flops (one subtract + one fused multiply-add per centroid and channel)
+    for the assignment.  Uniform and c = 256 run over 1 Mi / 256 Ki tokens per sequence, c = 8192 over 32 Ki (at
+    least two blocks where the size allows)."""
+    import numpy as np
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    rows = w.batch * w.n_kv_heads
+    d = S.make_layer(w, 0, device="cuda", want_values=False)
+    keys = d["keys"]
+    out = {"workload": w.name, "block_sizes": list(sizes)}
+
+    def run(call, total, T):
+        blocks = [keys[:, :, a:a + T].contiguous() for a in range(0, total, T)]
+        n = [0] * w.batch
+        call(blocks[0], T, n)                        # warm-up (the cache is refilled from slot 0 below)
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in blocks]
+        for (e0, e1), blk in zip(ev, blocks):
+            e0.record()
+            call(blk, T, n)
+            e1.record()
+            n = [x + T for x in n]
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in ev)
+        return ms[len(ms) // 2], len(blocks)
+
+    for bits, group in ((4, 32), (2, 64)):
+        shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.n, bits, group)
+        kc = torch.empty(B.hca_kcache_bytes(shape), dtype=torch.uint8, device="cuda")
+        code_bytes = 128 * bits // 8 + (128 // group) * 4
+        res = []
+        for T in sizes:
+            total = max(min(w.n, 1 << 20), T)
+            ms, nb = run(lambda blk, T_, n: B.hca_quantize_keys(shape, kc, blk, T_, n), total, T)
+            gbs = rows * T * (256 + code_bytes) / ms / 1e6
+            res.append({"block_tokens": T, "blocks": nb, "ms_per_block": ms, "tokens_per_s": w.batch * T / ms * 1e3,
+                        "GBs": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS})
+        out[f"uniform_{bits}bit_group{group}"] = res
+        del kc
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, w.n)
+    rng = np.random.default_rng(1000 * w.config + 8)
+    for c, total_cap in ((256, 1 << 18), (8192, 1 << 15)):
+        g = 32
+        sub = keys[0, :, :32768].float().reshape(w.n_kv_heads, 32768, g, 128 // g)
+        pick = torch.from_numpy(np.stack([rng.choice(32768, c, replace=False) for _ in range(g)])).cuda()
+        cen = torch.stack([torch.stack([sub[h, pick[i], i] for i in range(g)]) for h in range(w.n_kv_heads)]).contiguous()
+        cb = B.make_codebook(g, c, cen)
+        P = torch.empty(B.hca_vq_pcache_bytes(shape, cb), dtype=torch.uint8, device="cuda")
+        res = []
+        for T in sizes:
+            total = max(total_cap, T)
+            ms, nb = run(lambda blk, T_, n: B.hca_vq_assign(shape, cb, P, blk, T_, n), total, T)
+            tf = rows * T * g * c * (128 // g) * 3 / ms / 1e9
+            res.append({"block_tokens": T, "blocks": nb, "ms_per_block": ms, "tokens_per_s": w.batch * T / ms * 1e3,
+                        "TFLOPs": tf, "frac_of_fp32_vector_peak": tf / 157.3})
+        out[f"codebook_g{g}_c{c}"] = res
+        del P, cen
+    del d, keys
+    torch.cuda.empty_cache()
+    return out
+
+
 def correlated_selection(w, iters=12):
     """hca_score_topk on one layer of `w` whose keys resemble their neighbours (synth_inputs.make_correlated_layer,
     runs of up to 64 and of up to 4096 slots), beside the same call on the independent keys of the main workload:
@@ -1064,7 +1134,7 @@ def main():
                     help="row splits tried by the pipelined per-layer latency probe")
     ap.add_argument("--stages", type=int, default=4, choices=[3, 4],
                     help="native pipeline: 4 = scan | top-k | gather | attend; 3 = top-k shares the scan stream")
-    ap.add_argument("--mode", default="step", choices=["step", "scan", "select", "vq", "gather"],
+    ap.add_argument("--mode", default="step", choices=["step", "scan", "select", "vq", "gather", "prefill"],
                     help="scan: only the key-scan kernel on one layer plus a 1 GiB copy for counter calibration; "
                          "select: the same for hca_score_topk (selecting scan, sampling, selection); "
                          "vq: the codebook form of the key path (assignment, table, lookup scan) on one layer; "
@@ -1103,6 +1173,9 @@ def main():
         return select_only(w, args.steps)
     if args.mode == "gather":
         return gather_only(w, args.steps)
+    if args.mode == "prefill":
+        print(json.dumps(dict(mode="prefill", **prefill_blocks(w))), flush=True)
+        return
     if args.mode == "vq":
         print(json.dumps(dict(mode="vq", **vq_probe(w, args.steps, c=args.vq_codewords))), flush=True)
         return
@@ -1169,6 +1242,12 @@ def main():
 
     others = None
     correlated = None
+    prefill = None
+    if not args.no_latency and args.config == 4:
+        prefill = prefill_blocks(w)
+        log("block-wise key compression, fraction of the bound by block size "
+            + "; ".join(f"{k_}: " + " ".join(f"{r.get('frac_of_hbm_peak', r.get('frac_of_fp32_vector_peak')):.2f}" for r in v_)
+                        for k_, v_ in prefill.items() if isinstance(v_, list) and v_ and isinstance(v_[0], dict)))
     if not args.no_latency and args.config == 4:
         correlated = correlated_selection(w)
         log("fused selection at 1M, ms per call (candidates min..max, second scans): " + "; ".join(
@@ -1376,6 +1455,7 @@ def main():
         "codebook_key_path": codebook,
         "selection": selection,
         "fused_selection_on_correlated_keys": correlated,
+        "prefill_block_compression": prefill,
         "paper_form_step": paper_form,
         "value_side_cpu_split": cpu_split,
         "bulk_quantize_tokens_per_s": bulk_tokens / tq,

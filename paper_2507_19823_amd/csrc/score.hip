@@ -1001,7 +1001,7 @@ int32_t launch_score(const Layout& L, const void* kcache, const void* q, const N
   if (tn.score_bpw > 0) bpw = tn.score_bpw;
   if (bpw < kScoreBpwMin) bpw = kScoreBpwMin;
   if (bpw > kScoreBpwMax) bpw = kScoreBpwMax;
-  const int depth = tn.score_depth > 0 ? tn.score_depth : (L.bits == 4 ? 8 : 4);
+  const int depth = tn.score_depth > 0 ? tn.score_depth : 8;
   dim3 grid((unsigned)((nblocks + 4 * bpw - 1) / (4 * bpw)), (unsigned)L.rows);
   // every wave of the launch owns one stamp pair: the caller's buffer holds score_stamp_pairs() of them
   if (stamps != nullptr && (int64_t)grid.x * 4 * L.rows > score_stamp_pairs(L, nmax)) return HCA_ERR_CAPACITY;

@@ -142,6 +142,40 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
         assert np.all(np.abs(zg[hq, :n_used].astype(np.float64) - zp[hq, :n_used]) <= bound)
 
 
+@pytest.mark.parametrize("g,c", [(32, 256), (32, 8192), (64, 1024)])
+def test_blockwise_bulk_assign_equals_one_shot(B, oracle, g, c):
+    """Block-wise prefill hands the keys over a block at a time (App. B): appending 40 000 tokens per row in blocks
+    of 16 384 + 16 384 + 7 232 (the wide form's tile size, so the second block ends on a tile edge) and in uneven
+    blocks of 10 001 + 1 + 29 998 leaves the same index cache as one call with all of them, and the indices around
+    every block edge are the oracle's (brute force on those tokens only: the full set would take minutes at
+    c = 8192)."""
+    rng = np.random.default_rng(5 * g + c)
+    batch, hkv, G, n = 1, 2, 4, 40000
+    cap = n + 100
+    keys = rng.standard_normal((batch, hkv, n, D)).astype(np.float16)
+    keys[:, :, :, 9] *= 8
+    cen = _codebook(oracle, rng, keys, hkv, g, c)
+    kt = torch.from_numpy(keys)
+    R = batch * hkv
+    ref = _State(B, batch, hkv * G, hkv, cap, g, c, cen, 64)
+    ref.assign(kt)
+    torch.cuda.synchronize()
+    Pref = ref.P_rows()
+    for cuts in ([16384, 32768], [10001, 10002]):
+        st = _State(B, batch, hkv * G, hkv, cap, g, c, cen, 64)
+        edges = [0] + cuts + [n]
+        for a, b in zip(edges[:-1], edges[1:]):
+            st.assign(kt[:, :, a:b])
+        torch.cuda.synchronize()
+        assert st.n == [n] * batch
+        assert np.array_equal(st.P_rows(), Pref), f"blocks cut at {cuts}: index cache differs from the one-shot one"
+        assert np.array_equal(st.pos.cpu().numpy(), ref.pos.cpu().numpy())
+    sample = np.unique(np.concatenate([np.arange(max(0, e - 40), min(n, e + 40)) for e in (0, 10001, 10002, 16384, 32768, n)]))
+    oc = oracle.VQCache(R, len(sample), cen)
+    oracle.vq_assign(oc, keys.reshape(R, n, D)[:, sample])
+    assert np.array_equal(Pref[:, sample], oc.P[:, :len(sample)].astype(ref.idx_dtype()))
+
+
 @pytest.mark.parametrize("g,c,G,n,k", [(32, 256, 4, 9000, 512), (64, 128, 4, 3001, 100), (32, 64, 2, 5000, 5000),
                                        (32, 256, 1, 700, 1), (32, 1024, 4, 6000, 300), (64, 512, 2, 2500, 2500),
                                        (32, 512, 4, 20000, 700)])     # the last: two index tiles, the second ragged
