@@ -346,6 +346,18 @@ def score_plain(cache, q):
     return z
 
 
+def score_fp32(cache, q):
+    """Eq. 2's z~ in plain fp32 with the query as it is (per-group ascending fused multiply-add chains, the pairwise
+    group sum).  q [R*G, D] fp16 -> z [R*G, cap] fp32."""
+    q = _u16(q)
+    G = q.shape[0] // cache.R
+    z = np.zeros((cache.R * G, cache.cap), np.float32)
+    _check(lib().hco_score_fp32(_p(q), _p(cache.codes), _p(cache.scale), _p(cache.zero), C.c_int64(cache.R),
+                                C.c_int(G), C.c_int(cache.D), C.c_int(cache.bits), C.c_int(cache.gs),
+                                C.c_int64(cache.cap), _p(cache.n), _p(z)), "score_fp32")
+    return z
+
+
 def vq_score_plain(cache, T):
     """Eq. 3 as written: z[hq, j] = sum_i T[hq, i, P[j, i]] in fp64.  T [R*G, g, c] fp32 -> z [R*G, cap] fp64."""
     T = np.ascontiguousarray(T, np.float32)

@@ -14,6 +14,8 @@
  *
  *   hco_score_plain      z~ = q . Q(K)^T of Eq. 2 (Sec. 3.2) with the query as it is:
  *                        z[hq][j] = sum_c q_c * (scale_g * code_c + zero_g), every term fp64
+ *   hco_score_fp32       the same in plain fp32 arithmetic with the unquantised query (ascending fused
+ *                        multiply-add chains per group), for the distance to the fixed-point form
  *   hco_vq_score_plain   Eq. 3: z[hq][j] = sum_i T[hq][i][P[j][i]], fp64 sum of the fp32 table
  *   hco_topp_plain       Eq. 4: a = softmax(sel * sm_scale) over the row in fp64; slots sorted by
  *                        (sel descending, slot ascending); k* = the least k whose sorted prefix
@@ -52,6 +54,47 @@ int hco_score_plain(const uint16_t* q, const uint8_t* codes, const uint16_t* sca
                       + (double)hco_h2f(zero[(r * cap + j) * NG + c / gs]);
         s += (double)hco_h2f(q[hq * D + c]) * khat;
       }
+      z[hq * cap + j] = s;
+    }
+  }
+  return HCO_OK;
+}
+
+/* The same score in plain fp32 with the query as it is (no fixed point), the form one would write first:
+ * per group D_g = fused multiply-add chain over the group's channels in ascending order of q_c * code_c from
+ * 0.0f; Q_g = fp32 sum of q_c in ascending order; t_g = fmaf(scale_g, D_g, zero_g * Q_g);
+ * z = (t0 + t1) + (t2 + t3) (two groups: t0 + t1; otherwise left to right).  Not reproducible bit for bit on
+ * a matrix core (the chain's order is), which is why hco_score uses the fixed-point query; a test bounds the
+ * distance between the two.  z [R*G][cap] fp32, written for j < n[r]. */
+int hco_score_fp32(const uint16_t* q, const uint8_t* codes, const uint16_t* scale, const uint16_t* zero,
+                   int64_t R, int G, int D, int bits, int gs, int64_t cap, const int64_t* n, float* z) {
+  if (D <= 0 || gs <= 0 || D % gs != 0 || (bits != 2 && bits != 4 && bits != 8) || G < 1) return HCO_ERR_BAD_ARG;
+  const int NG = D / gs, CB = D * bits / 8;
+  if (NG > 16) return HCO_ERR_BAD_ARG;
+  for (int64_t hq = 0; hq < R * G; ++hq) {
+    int64_t r = hq / G;
+    float Qg[16];
+    for (int g = 0; g < NG; ++g) {
+      float acc = 0.0f;
+      for (int c = g * gs; c < (g + 1) * gs; ++c) acc = acc + hco_h2f(q[hq * D + c]);
+      Qg[g] = acc;
+    }
+    for (int64_t j = 0; j < n[r]; ++j) {
+      const uint8_t* crow = codes + (r * cap + j) * CB;
+      float t[16];
+      for (int g = 0; g < NG; ++g) {
+        float Dg = 0.0f;
+        for (int c = g * gs; c < (g + 1) * gs; ++c) {
+          int bit = c * bits;
+          int code = (crow[bit >> 3] >> (bit & 7)) & ((1 << bits) - 1);
+          Dg = fmaf(hco_h2f(q[hq * D + c]), (float)code, Dg);
+        }
+        float zq = hco_h2f(zero[(r * cap + j) * NG + g]) * Qg[g];
+        t[g] = fmaf(hco_h2f(scale[(r * cap + j) * NG + g]), Dg, zq);
+      }
+      float s;
+      if (NG == 4) { float a = t[0] + t[1], b = t[2] + t[3]; s = a + b; }
+      else { s = t[0]; for (int g = 1; g < NG; ++g) s = s + t[g]; }
       z[hq * cap + j] = s;
     }
   }

@@ -244,6 +244,36 @@ def test_fixed_point_score_against_the_plain_fp64_definition(oracle, bits, gs):
         assert np.all(np.abs(z[hq, :T] - zp[hq, :T]) <= 2.0 ** -14 * mag + 1e-5 * np.abs(zp[hq, :T]) + 1e-6)
 
 
+@pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64), (8, 32)])
+def test_fixed_point_score_against_the_plain_fp32_form(oracle, bits, gs):
+    """The score as one would write it first - fp32, query untouched, ascending fused multiply-add chains - is
+    (a) within fp32 rounding of the fp64 definition (at most one rounding per term and per sum:
+    (D + 8) 2^-24 sum_c |q_c k^_c| is generous) and (b) within 2^-14 max|q| sum|k^| plus that rounding of the
+    fixed-point form the GPU reproduces: the two forms of the same score differ by the query's fixed-point step
+    and nothing else."""
+    rng = np.random.default_rng(60 + bits)
+    R, G, T, D = 2, 4, 300, 128
+    k = _keys(rng, R, T)
+    q = (rng.standard_normal((R * G, D)) * 1.3).astype(np.float16)
+    c = oracle.Cache(R, T + 2, D, bits, gs)
+    oracle.quantize(c, k)
+    za = oracle.score_fp32(c, q)
+    zp = oracle.score_plain(c, q)
+    _, zb = oracle.score(c, q)
+    code = _unpack(c.codes[:, :T], bits).astype(np.float64)
+    sc = np.repeat(c.scale[:, :T].view(np.float16).astype(np.float64), gs, axis=-1)
+    zr = np.repeat(c.zero[:, :T].view(np.float16).astype(np.float64), gs, axis=-1)
+    absk = np.abs(sc * code) + np.abs(zr)                                    # [R,T,D]: the terms before they cancel
+    for hq in range(R * G):
+        r = hq // G
+        aq = np.abs(q[hq].astype(np.float64))
+        rounding = (D + 8) * 2.0 ** -24 * (absk[r] @ aq)
+        assert np.all(np.abs(za[hq, :T].astype(np.float64) - zp[hq, :T]) <= rounding + 1e-30)
+        step = 2.0 ** -14 * aq.max() * np.abs(sc[r] * code[r] + zr[r]).sum(-1)
+        assert np.all(np.abs(za[hq, :T].astype(np.float64) - zb[hq, :T]) <= step + rounding + 2.0 ** -23 * np.abs(zp[hq, :T]))
+        assert np.all(za[hq, T:] == 0)
+
+
 def test_budget_closed_forms(oracle):
     """Table 1a: a g-entry 16-bit index row against a d-entry 16-bit key row is g/d of the
     key budget; the 4-bit and 2-bit code rows of this build occupy the same bytes."""
