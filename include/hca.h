@@ -74,8 +74,10 @@ const char* hca_version(void);
 /* Overrides a launch-shape knob for the per-call entry points (process-wide state, meant for tuning and
  * profiling sessions, not needed for correct results; a step driver takes its knobs from its own
  * hca_pipeline_desc instead and only starts from these).  Names: "gather_wgs", "gather_unroll", "score_bpw", "score_depth", "select_wg" (threads per workgroup of the
- * selection over the candidate lists of hca_score_topk: 1024 - pairs staged in LDS, needs a whole compute unit -
- * or 256 - pairs read from L2, finds room beside a running scan, slower where measured; 0: 1024),
+ * selection over the candidate lists of hca_score_topk: 1024 - pairs staged in 128 KiB of LDS, needs a whole compute
+ * unit - or 256 - four waves, pairs staged in 96 KiB of LDS when k <= 4096 and read from L2 otherwise, fits into
+ * the room one finished scan workgroup leaves, slower where measured; 0: 1024; the launch for rows that needed a
+ * second scan always takes the 256 form when two layers are selected by one launch),
  * "host_isa" (2: the hybrid value side's host threads use their AVX2 form even where the CPU has AVX-512; 0: the
  * widest form), "host_spin_us" (how long the worker threads of hca_host_weighted_sum poll for the next
  * call before they sleep; default 100, 0 = sleep at once).

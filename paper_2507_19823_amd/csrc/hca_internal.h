@@ -155,7 +155,7 @@ int32_t launch_select_rescan_pair(const Layout& L, const void* const kcache[2], 
                                   const int64_t nmax[2], const SelectOut so[2], hipStream_t st);
 int32_t launch_select_finish_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
                                   const int64_t nmax[2], int32_t k, int32_t* const idx[2], int32_t* const count[2],
-                                  void* const ws[2], hipStream_t st);
+                                  void* const ws[2], hipStream_t st, bool small_wg = false);
 // the SelectOut view of a selection workspace for rows of at most nmax_before slots (before the step's append)
 SelectOut select_view(const Layout& L, void* ws, int64_t nmax_before, int32_t k);
 int32_t launch_select_scan_step(const Layout& L, const void* kcache, const void* q, const NRes& nr, int64_t nmax,

@@ -7,6 +7,8 @@
 #include <atomic>
 #include <chrono>
 #include <condition_variable>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <memory>
 #include <mutex>
@@ -535,8 +537,15 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       int64_t mb;
       rc = lengths(l + 2 * S, &nx.b_nr, &mb);
       if (rc != HCA_OK) return rc;
-      rc = wait_layer(l + 2 * S);
-      if (rc != HCA_OK) return rc;
+      // paired launches: the wait of the pair's second layer covers the first one's too - layer_done events are
+      // recorded in layer order on the attend stream (not so with spare-buffer evictions, whose last slice
+      // records it later)
+      const bool covered = p->pair && !p->sel_waits && p->d.spare_kcache == nullptr && (l & 1) == 0 &&
+                           l + 1 + 2 * S < p->n_layers;
+      if (!covered) {
+        rc = wait_layer(l + 2 * S);
+        if (rc != HCA_OK) return rc;
+      }
       nx.b_kcache = layers[l + 2 * S].kcache;
       nx.b_q = layers[l + 2 * S].q;
       nx.b_so = select_view(L, p->d.ws_select[(l + 2 * S) % p->n_sel], mb, k);
@@ -643,7 +652,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       int32_t* const idx2[2] = {p->d.idx[s4], p->d.idx[s4b]};
       int32_t* const cnt2[2] = {p->d.count[s4], p->d.count[s4b]};
       void* const ws2[2] = {p->d.ws_select[s3], p->d.ws_select[s3b]};
-      rc = launch_select_finish_pair(L, kc2, q2, nr2, nm2, k, idx2, cnt2, ws2, sb);
+      rc = launch_select_finish_pair(L, kc2, q2, nr2, nm2, k, idx2, cnt2, ws2, sb, p->tune.select_wg == 256);
       if (rc != HCA_OK) return rc;
       if (p->sel_waits) {
         HCA_HIP(hipEventRecord(p->sel_free[s3], sb));

@@ -769,6 +769,10 @@ __global__ __launch_bounds__(256) void tk_emit_lists(int64_t chunk, int nchunks,
 // launches handle exactly those rows.
 constexpr int kFullLds = 16384;     // pairs held in LDS (128 KiB, dynamic)
 constexpr int kSearchMax = 65536;   // pairs still addressed by position when they do not fit LDS
+constexpr int kSmallLds = 12288;    // pairs the four-wave form of the selection holds in LDS (96 KiB) ...
+// ... when the expected list fits: k <= 4096 (the scan lets about 2.7 times k pairs per row through); longer lists
+// are read where they lie, and the launch then asks for no dynamic LDS at all
+static uint32_t small_stage_cap(int32_t k) { return k <= 4096 ? (uint32_t)kSmallLds : 0u; }
 
 // counter updates when the lanes of a wave share a handful of bins (the leading bits of keys that all lie
 // just above one threshold): one atomic per distinct bin for the first few, single updates for the rest
@@ -804,17 +808,19 @@ __device__ __forceinline__ uint32_t block_scan_excl(uint32_t v, uint32_t* wsum /
   return base + inc - v;
 }
 
-// NT = 1024: one large workgroup per row with the row's pairs staged in 128 KiB of LDS - the quickest form when
-// the chip has a compute unit to spare.  NT = 256: four waves and 20 KiB of LDS, the pairs read where they lie
-// (they sit in L2); this one finds room beside the workgroups of a key scan that fills every compute unit,
-// where the large form has to wait for a scan to drain.  Same result.
+// NT = 1024: one large workgroup per row with the row's pairs staged in up to 128 KiB of LDS - the quickest form
+// when the chip has a compute unit to spare.  NT = 256: four waves, one per SIMD, with at most 128 registers each
+// and up to 96 KiB of LDS for the pairs (stage_cap of them; longer lists are read where they lie, in L2): this
+// one fits into the room that a single finished workgroup of a key scan leaves on a compute unit, where the large
+// form has to wait until a scan launch has drained from a whole unit - beside back-to-back scans that is one
+// chance per launch.  Same result.
 template <int NT>
 __device__ __forceinline__ void tk_resolve_emit_body(const int64_t chunk, const int nchunks, const int64_t want,
                                                      const SelectOut& so, const int32_t k, int32_t* __restrict__ idx,
-                                                     int32_t* __restrict__ count, const bool only_failed, const int row) {
+                                                     int32_t* __restrict__ count, const bool only_failed, const int row,
+                                                     const uint32_t stage_cap) {
   constexpr int NW = NT / 64;              // waves
   constexpr int PER = 1024 / NT;           // chunks (and 10-bit bins) per thread
-  constexpr bool kStage = NT == 1024;
   extern __shared__ uint2 lc[];
   __shared__ uint32_t h[kBins12], off[1025], wsum[16];
   __shared__ uint32_t s_prefix, s_rem, s_cb;
@@ -866,7 +872,7 @@ __device__ __forceinline__ void tk_resolve_emit_body(const int64_t chunk, const 
     return;
   }
   const uint2* gl = so.lists + (int64_t)row * so.row_entries;
-  const bool staged = kStage && total <= (uint32_t)kFullLds;
+  const bool staged = total <= stage_cap;                   // stage_cap pairs of dynamic LDS came with the launch
   // beyond the LDS stage: up to kSearchMax pairs are still addressed by their position in slot order (short lists:
   // walking them chunk by chunk would cost a memory round trip per chunk), more than that are walked chunk by chunk
   const bool by_position = total <= (uint32_t)kSearchMax;
@@ -880,29 +886,31 @@ __device__ __forceinline__ void tk_resolve_emit_body(const int64_t chunk, const 
   };
   const int lane = tid & 63, wv = tid >> 6;
   uint32_t kmax = 0;                                        // largest key this thread has seen
-  if constexpr (kStage) {
-    if (staged) {
-      // 16 lanes per chunk: the first 32 pairs of 64 chunks per wave in 32 loads, all in flight together (nearly
-      // all lists are shorter than that); longer lists follow
-      const int sub = lane >> 4, i = lane & 15;
+  if (staged) {
+    // 16 lanes per chunk: the first 32 pairs of 64 chunks per wave in 32 loads, all in flight together (nearly
+    // all lists are shorter than that); longer lists follow.  Wave wv takes chunks 64 (wv + NW rep) .. + 63
+    const int sub = lane >> 4, i = lane & 15;
+#pragma unroll 1
+    for (int rep = 0; rep < 16 / NW; ++rep) {
+      const int cb0 = (wv + NW * rep) * 64;
       uint2 x[16], y[16];
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const int c = wv * 64 + j * 4 + sub;
+        const int c = cb0 + j * 4 + sub;
         const uint32_t m = off[c + 1] - off[c];
         x[j] = (uint32_t)i < m ? gl[(int64_t)c * chunk + i] : uint2{0, 0};
         y[j] = (uint32_t)i + 16 < m ? gl[(int64_t)c * chunk + i + 16] : uint2{0, 0};
       }
 #pragma unroll
       for (int j = 0; j < 16; ++j) {
-        const int c = wv * 64 + j * 4 + sub;
+        const int c = cb0 + j * 4 + sub;
         const uint32_t o = off[c], m = off[c + 1] - o;
         if ((uint32_t)i < m) { lc[o + i] = x[j]; kmax = x[j].x > kmax ? x[j].x : kmax; }
         if ((uint32_t)i + 16 < m) { lc[o + i + 16] = y[j]; kmax = y[j].x > kmax ? y[j].x : kmax; }
       }
 #pragma unroll 1
       for (int j = 0; j < 16; ++j) {
-        const int c = wv * 64 + j * 4 + sub;
+        const int c = cb0 + j * 4 + sub;
         const uint32_t o = off[c], m = off[c + 1] - o;
         for (uint32_t e = 32 + i; e < m; e += 16) {
           const uint2 z = gl[(int64_t)c * chunk + e];
@@ -1170,9 +1178,9 @@ __device__ __forceinline__ void tk_resolve_emit_body(const int64_t chunk, const 
 template <int NT>
 __global__ __launch_bounds__(NT) void tk_resolve_emit(int64_t chunk, int nchunks, int n_kv_heads, SelRows sr,
                                                       SelectOut so, int32_t k, int32_t* __restrict__ idx,
-                                                      int32_t* __restrict__ count, bool only_failed) {
+                                                      int32_t* __restrict__ count, bool only_failed, uint32_t stage_cap) {
   tk_resolve_emit_body<NT>(chunk, nchunks, sr.want[blockIdx.x / n_kv_heads], so, k, idx, count, only_failed,
-                           (int)blockIdx.x);
+                           (int)blockIdx.x, stage_cap);
 }
 
 // The selections of two layers in one launch (the step driver's paired form): workgroups [0, rows) take the
@@ -1187,13 +1195,14 @@ struct ResolveSide {
 };
 template <int NT>
 __global__ __launch_bounds__(NT) void tk_resolve_emit_pair(ResolveSide a, ResolveSide b, int rows, int n_kv_heads,
-                                                           int32_t k, bool only_failed) {
+                                                           int32_t k, bool only_failed, uint32_t stage_cap) {
   if ((int)blockIdx.x < rows) {
     tk_resolve_emit_body<NT>(a.chunk, a.nchunks, a.want[blockIdx.x / n_kv_heads], a.so, k, a.idx, a.count, only_failed,
-                             (int)blockIdx.x);
+                             (int)blockIdx.x, stage_cap);
   } else {
     const int row = (int)blockIdx.x - rows;
-    tk_resolve_emit_body<NT>(b.chunk, b.nchunks, b.want[row / n_kv_heads], b.so, k, b.idx, b.count, only_failed, row);
+    tk_resolve_emit_body<NT>(b.chunk, b.nchunks, b.want[row / n_kv_heads], b.so, k, b.idx, b.count, only_failed, row,
+                             stage_cap);
   }
 }
 
@@ -1305,11 +1314,17 @@ int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q,
   int32_t rc = fused_plan(L, nr, nmax, k, ws, &f);
   if (rc != HCA_OK) return rc;
   if (small_wg) {
-    tk_resolve_emit<256><<<L.rows, 256, 0, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false);
+    const uint32_t cap = small_stage_cap(k);
+    static std::atomic<uint64_t> opted_s{0};
+    if (cap * 8 > 64 * 1024) {
+      rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit<256>), kSmallLds * 8, &opted_s);
+      if (rc != HCA_OK) return rc;
+    }
+    tk_resolve_emit<256><<<L.rows, 256, cap * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false, cap);
     if (nmax > 0) {
       rc = launch_select_scan(L, kcache, q, nr, nmax, f.so, true, st);
       if (rc != HCA_OK) return rc;
-      tk_resolve_emit<256><<<L.rows, 256, 0, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true);
+      tk_resolve_emit<256><<<L.rows, 256, 0, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true, 0u);
     }
     HCA_HIP(hipGetLastError());
     return HCA_OK;
@@ -1317,11 +1332,13 @@ int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q,
   static std::atomic<uint64_t> opted{0};
   rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit<1024>), kFullLds * 8, &opted);
   if (rc != HCA_OK) return rc;
-  tk_resolve_emit<1024><<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false);
+  tk_resolve_emit<1024><<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, false,
+                                                            (uint32_t)kFullLds);
   if (nmax > 0) {
     rc = launch_select_scan(L, kcache, q, nr, nmax, f.so, true, st);
     if (rc != HCA_OK) return rc;
-    tk_resolve_emit<1024><<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true);
+    tk_resolve_emit<1024><<<L.rows, 1024, kFullLds * 8, st>>>(f.chunk, f.nchunks, L.n_kv_heads, f.sr, f.so, k, idx, count, true,
+                                                              (uint32_t)kFullLds);
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
@@ -1330,7 +1347,7 @@ int32_t launch_select_finish(const Layout& L, const void* kcache, const void* q,
 // The same for the two layers of a paired scan launch: three launches for the two of them.
 int32_t launch_select_finish_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
                                   const int64_t nmax[2], int32_t k, int32_t* const idx[2], int32_t* const count[2],
-                                  void* const ws[2], hipStream_t st) {
+                                  void* const ws[2], hipStream_t st, bool small_wg) {
   FusedPlan f[2];
   ResolveSide rs[2];
   for (int i = 0; i < 2; ++i) {
@@ -1343,15 +1360,30 @@ int32_t launch_select_finish_pair(const Layout& L, const void* const kcache[2], 
     rs[i].idx = idx[i];
     rs[i].count = count[i];
   }
-  static std::atomic<uint64_t> opted{0};
-  int32_t rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit_pair<1024>), kFullLds * 8, &opted);
-  if (rc != HCA_OK) return rc;
-  tk_resolve_emit_pair<1024><<<2 * L.rows, 1024, kFullLds * 8, st>>>(rs[0], rs[1], L.rows, L.n_kv_heads, k, false);
+  int32_t rc = HCA_OK;
+  if (small_wg) {
+    const uint32_t cap = small_stage_cap(k);
+    static std::atomic<uint64_t> opted_s{0};
+    if (cap * 8 > 64 * 1024) {
+      rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit_pair<256>), kSmallLds * 8, &opted_s);
+      if (rc != HCA_OK) return rc;
+    }
+    tk_resolve_emit_pair<256><<<2 * L.rows, 256, cap * 8, st>>>(rs[0], rs[1], L.rows, L.n_kv_heads, k, false, cap);
+  } else {
+    static std::atomic<uint64_t> opted{0};
+    rc = lds_opt_in(reinterpret_cast<const void*>(&tk_resolve_emit_pair<1024>), kFullLds * 8, &opted);
+    if (rc != HCA_OK) return rc;
+    tk_resolve_emit_pair<1024><<<2 * L.rows, 1024, kFullLds * 8, st>>>(rs[0], rs[1], L.rows, L.n_kv_heads, k, false,
+                                                                       (uint32_t)kFullLds);
+  }
   if (nmax[0] > 0 && nmax[1] > 0) {
     const SelectOut so2[2] = {f[0].so, f[1].so};
     rc = launch_select_rescan_pair(L, kcache, q, nr, nmax, so2, st);
     if (rc != HCA_OK) return rc;
-    tk_resolve_emit_pair<1024><<<2 * L.rows, 1024, kFullLds * 8, st>>>(rs[0], rs[1], L.rows, L.n_kv_heads, k, true);
+    // the selection for rows that had to be scanned again - almost never any - in the four-wave form without an
+    // LDS stage: beside a running scan the 1024-thread form would wait for a compute unit to drain just to find
+    // that it has nothing to do
+    tk_resolve_emit_pair<256><<<2 * L.rows, 256, 0, st>>>(rs[0], rs[1], L.rows, L.n_kv_heads, k, true, 0u);
   }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
