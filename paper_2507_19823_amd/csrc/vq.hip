@@ -26,10 +26,11 @@
 namespace hca {
 
 // ------------------------------------------------------------------------------- assign ---
-// One wave = 64 tokens x one quad of 4 consecutive groups.  Every centroid read is wave-uniform
-// (scalar loads), the running minimum is per lane.  distance: e = x - c; d = fmaf(e, e, d) over the
-// group's channels in ascending order from d = 0; the first smallest wins.
-template <int DBAR, bool WIDE>
+// One wave = 64 tokens x GPW consecutive groups (4 for bulk calls; 1 for blocks of a few thousand tokens, which
+// would otherwise leave most of the chip without a wave).  Every centroid read is wave-uniform (scalar loads),
+// the running minimum is per lane.  distance: e = x - c; d = fmaf(e, e, d) over the group's channels in ascending
+// order from d = 0; the first smallest wins.
+template <int DBAR, bool WIDE, int GPW>
 __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_heads, int64_t cap,
                                                         const float* __restrict__ centroids,
                                                         uint8_t* __restrict__ pcache, const uint16_t* __restrict__ k_new,
@@ -37,37 +38,40 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
                                                         int32_t* __restrict__ pos, NRes vrow0) {
   const int row = blockIdx.y;
   const int lane = threadIdx.x & 63;
-  const int quad = __builtin_amdgcn_readfirstlane((int)(blockIdx.z * 4 + (threadIdx.x >> 6)));
-  if (quad * 4 >= g) return;
+  const int g0 = __builtin_amdgcn_readfirstlane((int)(blockIdx.z * 4 + (threadIdx.x >> 6))) * GPW;   // first group
+  if (g0 >= g) return;
   const int64_t tt = (int64_t)blockIdx.x * 64 + lane;
   const bool live = tt < T;
   const int64_t tc = live ? tt : T - 1;
-  // the quad's 4 * DBAR channels of this lane's token
-  float x[4][DBAR];
+  // the wave's GPW * DBAR channels of this lane's token
+  float x[GPW][DBAR];
   {
-    const uint16_t* src = k_new + ((int64_t)row * T + tc) * kHeadDim + quad * 4 * DBAR;
-    if constexpr (DBAR == 4) {
+    const uint16_t* src = k_new + ((int64_t)row * T + tc) * kHeadDim + g0 * DBAR;
+    constexpr int NW32 = GPW * DBAR / 2;                  // dwords: 8, 4, 2 or 1
+    uint32_t wd[NW32];
+    if constexpr (NW32 == 8) {
       const uint4 a = reinterpret_cast<const uint4*>(src)[0], b = reinterpret_cast<const uint4*>(src)[1];
-      const uint32_t wd[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        x[i >> 1][2 * (i & 1)] = h2f(wd[i] & 0xffffu);
-        x[i >> 1][2 * (i & 1) + 1] = h2f(wd[i] >> 16);
-      }
-    } else {
+      wd[0] = a.x; wd[1] = a.y; wd[2] = a.z; wd[3] = a.w; wd[4] = b.x; wd[5] = b.y; wd[6] = b.z; wd[7] = b.w;
+    } else if constexpr (NW32 == 4) {
       const uint4 a = reinterpret_cast<const uint4*>(src)[0];
-      const uint32_t wd[4] = {a.x, a.y, a.z, a.w};
+      wd[0] = a.x; wd[1] = a.y; wd[2] = a.z; wd[3] = a.w;
+    } else if constexpr (NW32 == 2) {
+      const uint2 a = reinterpret_cast<const uint2*>(src)[0];
+      wd[0] = a.x; wd[1] = a.y;
+    } else {
+      wd[0] = reinterpret_cast<const uint32_t*>(src)[0];
+    }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        x[i][0] = h2f(wd[i] & 0xffffu);
-        x[i][1] = h2f(wd[i] >> 16);
-      }
+    for (int i = 0; i < NW32; ++i) {
+      const int ch = 2 * i;
+      x[ch / DBAR][ch % DBAR] = h2f(wd[i] & 0xffffu);
+      x[(ch + 1) / DBAR][(ch + 1) % DBAR] = h2f(wd[i] >> 16);
     }
   }
-  const float* cb = centroids + ((int64_t)(row % n_kv_heads) * g + quad * 4) * c * DBAR;
-  int win[4];
+  const float* cb = centroids + ((int64_t)(row % n_kv_heads) * g + g0) * c * DBAR;
+  int win[GPW];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
+  for (int u = 0; u < GPW; ++u) {
     const float* cg = cb + (int64_t)u * c * DBAR;
     float bd = INFINITY;
     int best = 0;
@@ -89,13 +93,13 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
     uint16_t* pw = reinterpret_cast<uint16_t*>(pcache);
     const int64_t tiles = vq_tiles(cap);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) pw[vq_wide_at(g, tiles, row, slot, quad * 4 + u)] = (uint16_t)win[u];
+    for (int u = 0; u < GPW; ++u) pw[vq_wide_at(g, tiles, row, slot, g0 + u)] = (uint16_t)win[u];
   } else {
     uint8_t* rec = pcache + ((int64_t)row * cap + slot) * g;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) rec[vq_byte_of(quad * 4 + u, slot)] = (uint8_t)win[u];
+    for (int u = 0; u < GPW; ++u) rec[vq_byte_of(g0 + u, slot)] = (uint8_t)win[u];
   }
-  if (quad == 0) {
+  if (g0 == 0) {
     if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
     if (pos != nullptr) pos[(int64_t)row * cap + slot] = (int32_t)(vrow0.n[b] + tt);
   }
@@ -501,13 +505,26 @@ int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, 
     else if (wide) KERNEL<2, true><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);      \
     else KERNEL<2, false><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);               \
   } while (0)
+#define HCA_ASSIGN_B(GPW, GRID)                                                                                       \
+  do {                                                                                                                \
+    if (g == 32 && wide) vq_assign_kernel<4, true, GPW><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0); \
+    else if (g == 32) vq_assign_kernel<4, false, GPW><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);   \
+    else if (wide) vq_assign_kernel<2, true, GPW><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);      \
+    else vq_assign_kernel<2, false, GPW><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);               \
+  } while (0)
   if (T <= 8) {                                     // decode appends: parallel over centroids, not over tokens
     dim3 gs((unsigned)T, (unsigned)L.rows, (unsigned)(g / 4));
     HCA_ASSIGN(vq_assign_small_kernel, gs);
+  } else if ((T + 63) / 64 * L.rows * (g / 4) < 16 * 1024) {
+    // a block of a few thousand tokens: with four groups per wave the launch would have at most a few waves per
+    // SIMD (the chip has 1024 of them); one group per wave gives four times as many
+    dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 4));
+    HCA_ASSIGN_B(1, grid);
   } else {
     dim3 grid((unsigned)((T + 63) / 64), (unsigned)L.rows, (unsigned)(g / 16));
-    HCA_ASSIGN(vq_assign_kernel, grid);
+    HCA_ASSIGN_B(4, grid);
   }
+#undef HCA_ASSIGN_B
 #undef HCA_ASSIGN
   HCA_HIP(hipGetLastError());
   return HCA_OK;
