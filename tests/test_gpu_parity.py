@@ -373,6 +373,19 @@ def test_kernels_are_deterministic(H):
     # hybrid value side: the first `host` chunks of 256 selected tokens are summed by the driver's host threads
     (5, 5, False, 0.0, True, 1), (3, 3, True, 0.0, False, 2), (5, 3, False, 0.9, False, 1), (6, 6, False, 0.0, True, 3)])
 def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fused, host):
+    _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, 4, 32)
+
+
+@pytest.mark.parametrize("Lr,n_sel,spare,tau,fused,host", [
+    (5, 5, False, 0.0, True, 1), (6, 6, False, 0.0, True, 3), (5, 3, True, 0.0, True, 0), (3, 3, True, 0.0, False, 2),
+    (4, 4, False, 0.9, False, 0)])
+def test_native_step_driver_with_two_bit_codes(H, oracle, Lr, n_sel, spare, tau, fused, host):
+    """The same cases on 2-bit / group-64 codes (32-token blocks, two tiles per block): paired and single scan
+    launches, the hybrid value side, both eviction forms."""
+    _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, 2, 64)
+
+
+def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs):
     """hca_pipeline_step over 1 to 5 layers (score buffers shared between layers or one each), 12 decode
     steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k (as scan +
     top-k or fused as in hca_score_topk) or the cumulative-weight selection of Eq. 4 (tau > 0): every layer's
@@ -382,10 +395,10 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
     steps, E = 12, 4
     # with a host share the selection spans several chunks (k = 600: three chunks, the last ragged), and the
     # appended tokens' value rows (HBM slice) fall into the host's chunks whenever they rank early
-    w = S.Workload("drv", 7, 2, 8, 2, 1500, 4, 32, 600 if host else 96)
+    w = S.Workload("drv", 7, 2, 8, 2, 1500, bits, gs, 600 if host else 96)
     R, n0 = w.batch * w.n_kv_heads, w.n
     cap, vnew = n0 + E + 16, steps + 4
-    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap, bits, gs)
     dev = "cuda"
     kb = B.hca_kcache_bytes(shape)
     data = [S.make_layer(w, l) for l in range(Lr)]
@@ -399,7 +412,7 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
     ocs, oacc, opos, oV = [], [], [], []
     for l in range(Lr):
         B.hca_quantize_keys(shape, kc[l], data[l]["keys"].cuda(), n0, [0] * w.batch)
-        oc = oracle.Cache(R, cap, 128, 4, 32)
+        oc = oracle.Cache(R, cap, 128, bits, gs)
         oracle.quantize(oc, _rows(data[l]["keys"]))
         ocs.append(oc)
         oacc.append(np.zeros((R, cap), np.float32))
@@ -484,8 +497,8 @@ def test_native_step_driver_matches_oracle(H, oracle, Lr, n_sel, spare, tau, fus
         k_t, a_t, p_t = bufs[layers[l].kcache]
         assert layers[l].acc == a_t.data_ptr() and layers[l].pos == p_t.data_ptr()
         n = int(ocs[l].n[0])
-        cb = torch.zeros(w.batch, w.n_kv_heads, cap, 64, dtype=torch.uint8, device=dev)
-        sc = torch.zeros(w.batch, w.n_kv_heads, cap, 4, dtype=torch.float16, device=dev)
+        cb = torch.zeros(w.batch, w.n_kv_heads, cap, 128 * bits // 8, dtype=torch.uint8, device=dev)
+        sc = torch.zeros(w.batch, w.n_kv_heads, cap, 128 // gs, dtype=torch.float16, device=dev)
         zr = torch.zeros_like(sc)
         B.hca_export_kcache(shape, k_t, [n] * w.batch, cb, sc, zr)
         torch.cuda.synchronize()
