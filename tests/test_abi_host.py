@@ -81,6 +81,11 @@ def test_bad_arguments_are_rejected_on_the_host(B):
                                C.c_float(1.0), one, None, one, None, None) == -1
     s2 = B.make_shape(1, 32, 7, 1024)
     assert L.hca_score_qkeys(C.byref(s2), one, one, n, one, None, None, None) == -1   # 32 % 7 != 0
+    assert L.hca_score_topk_monitor(C.byref(s), None, one, 1, None) == -1             # no workspace
+    assert L.hca_score_topk_monitor(C.byref(s2), one, one, 1, None) == -1
+    assert L.hca_score_topk_report(C.byref(s), n, None, one, one, None) == -1
+    assert L.hca_topk_noalloc(C.byref(s), None, n, 8, one, one, None) == -1
+    assert L.hca_topk_noalloc(C.byref(s), one, n, 0, one, one, None) == -3
 
 
 # ---- codebook form of the key path: host-side checks and the host-side trainer -------------------
