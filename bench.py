@@ -72,6 +72,8 @@ class Model:
         self.pipe = []
         self.n_pipe_sets = n_pipe_sets
         self.dual_scan = dual_scan
+        self.layer_idx_on = False
+        self.layer_idx = None
         # The layer whose results are checked against the oracle: one whose set of selection buffers is not taken
         # again later in the step (so its top-k indices are still there when the step ends), and among those the
         # one whose first eviction comes latest (the check covers the timed steps up to that eviction).
@@ -227,6 +229,13 @@ class Model:
             d.idx[i] = self.pipe[i]["idx"].data_ptr()
             d.count[i] = self.pipe[i]["count"].data_ptr()
             d.ws_attend[i] = self.pipe[i]["ws"].data_ptr()
+        if self.layer_idx_on:
+            # one selection result per layer: the selections run in step with the scans, a set of staging buffers is
+            # claimed only by the gather stage
+            self.layer_idx = self.torch.zeros(self.L, w.batch, w.n_kv_heads, w.k, dtype=self.torch.int32, device="cuda")
+            self.layer_count = self.torch.zeros(self.L, w.batch, w.n_kv_heads, dtype=self.torch.int32, device="cuda")
+            d.layer_idx, d.layer_count = self.layer_idx.data_ptr(), self.layer_count.data_ptr()
+            d.layer_idx_stride = w.batch * w.n_kv_heads * w.k
         d.ws_topk, d.ws_evict = self.ws_topk.data_ptr(), self.ws_main.data_ptr()
         if timing_slots > 0:
             pairs = B.hca_scan_stamp_pairs(self.shape, self.cap)
@@ -483,6 +492,7 @@ def other_config_step(cfg, layers, phys, steps, streams, args, tune):
               dual_scan=args.scan_mode)
     m.build(phys)
     m.make_steps(steps + warm)
+    m.layer_idx_on = not args.slot_idx
     m.native_pipeline(*streams, 0)
     for t in range(warm):
         m.decode_step_native(t)
@@ -1115,6 +1125,9 @@ def main():
                     help="native step driver: sets of selection / staging buffers, i.e. layers in flight between top-k and attend")
     ap.add_argument("--resident", type=int, default=0,
                     help="--mode scan / select: tokens per sequence instead of the workload's context length")
+    ap.add_argument("--slot-idx", action="store_true",
+                    help="native pipeline: the selection results share the n_pipe sets of staging buffers (the first "
+                         "form) instead of one result buffer per layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gap-report", action="store_true",
                     help="log the largest idle times between consecutive scan launches with their step.layer")
@@ -1282,6 +1295,7 @@ def main():
     main, side = main_s[0], gath_s[0]
 
     model.gap_report = args.gap_report
+    model.layer_idx_on = args.pipeline == "native" and not args.slot_idx
     if args.pipeline == "native":
         model.native_pipeline(main, main if args.stages == 3 else extra[0], side, extra[1], args.steps,
                               args.bracket_stride)
@@ -1319,7 +1333,7 @@ def main():
 
     def capture(t):
         with torch.cuda.stream(topk_s):
-            ci = model.pipe[vslot]["idx"].clone()
+            ci = (model.layer_idx[model.verify_layer] if model.layer_idx is not None else model.pipe[vslot]["idx"]).clone()
         with torch.cuda.stream(extra[1]):
             cy = model.y[model.verify_layer].clone()
         captured[t] = (ci, cy)

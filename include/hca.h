@@ -325,6 +325,16 @@ typedef struct {
      selections follow on stream_topk: half as many pauses between scan launches, one launch tail per two
      layers.  hca_pipeline_scan_ms then reports the shared launch under the even layer and -1 for the odd one. */
   int32_t dual_scan;
+  /* Optional: one result buffer per layer for the selection instead of the idx / count of the n_pipe sets.
+     layer_idx != NULL: layer l's selected slots go to layer_idx + l * layer_idx_stride (int32 [batch, n_kv_heads, k],
+     layer_idx_stride >= batch * n_kv_heads * k elements) and its counts to layer_count + l * batch * n_kv_heads;
+     idx[] / count[] are ignored.  The selection of a layer then waits for nothing but its own scan - a set of
+     ws_attend (and of the host share's exchange buffers) is claimed only by the gather stage - so selections run
+     in step with the scans, well ahead of the value side, and the stages behind them are fed as soon as a set
+     comes free instead of once per scan launch. */
+  int32_t* layer_idx;
+  int32_t* layer_count;
+  int64_t layer_idx_stride;
 } hca_pipeline_desc;
 
 typedef struct hca_pipeline hca_pipeline;

@@ -51,7 +51,8 @@ class hca_pipeline_desc(C.Structure):
                 ("ws_select", C.c_void_p * PIPELINE_MAX_SEL), ("gather_stamps", C.c_void_p),
                 ("host_chunks", C.c_int32), ("host_threads", C.c_int32), ("host_spin_limit", C.c_int32),
                 ("gather_wgs", C.c_int32), ("gather_unroll", C.c_int32), ("score_bpw", C.c_int32),
-                ("score_depth", C.c_int32), ("select_wg", C.c_int32), ("n_pipe", C.c_int32), ("dual_scan", C.c_int32)]
+                ("score_depth", C.c_int32), ("select_wg", C.c_int32), ("n_pipe", C.c_int32), ("dual_scan", C.c_int32),
+                ("layer_idx", C.c_void_p), ("layer_count", C.c_void_p), ("layer_idx_stride", C.c_int64)]
 
 
 class hca_vq_codebook(C.Structure):

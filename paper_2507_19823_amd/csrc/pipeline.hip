@@ -276,8 +276,10 @@ hca_pipeline* hca_pipeline_create(const hca_shape* shape, int32_t n_layers, cons
   if (desc->dual_scan != 0 && (!fused || (desc->n_sel < 6 && desc->n_sel < n_layers))) return nullptr;
   const int n_pipe = desc->n_pipe == 0 ? 4 : desc->n_pipe;
   if (n_pipe < 4 || n_pipe > HCA_PIPELINE_MAX_PIPE) return nullptr;
+  const bool own_idx = desc->layer_idx != nullptr;
+  if (own_idx && (desc->layer_count == nullptr || desc->layer_idx_stride < 1)) return nullptr;
   for (int i = 0; i < n_pipe; ++i)
-    if (desc->idx[i] == nullptr || desc->count[i] == nullptr || desc->ws_attend[i] == nullptr) return nullptr;
+    if ((!own_idx && (desc->idx[i] == nullptr || desc->count[i] == nullptr)) || desc->ws_attend[i] == nullptr) return nullptr;
   if (desc->ws_topk == nullptr) return nullptr;
   if (desc->vq_groups != 0) {                // codebook form: same limits as the hca_vq_* calls; eviction in place
     if (desc->vq_groups != 32 && desc->vq_groups != 64) return nullptr;
@@ -367,6 +369,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
   if (p == nullptr || layers == nullptr || n_resident == nullptr) return HCA_ERR_BAD_ARG;
   const Layout& L = p->L;
   if (k < 1 || k > L.cap || k > 64 * 256) return HCA_ERR_CAPACITY;
+  if (p->d.layer_idx != nullptr && p->d.layer_idx_stride < (int64_t)L.rows * k) return HCA_ERR_CAPACITY;
   for (int l = 0; evict_M != nullptr && l < p->n_layers; ++l) {
     if (evict_M[l] == 0) continue;
     if (evict_M[l] < 1 || evict_M[l] > L.cap || n_protect < 0 || n_protect > evict_M[l]) return HCA_ERR_CAPACITY;
@@ -565,6 +568,16 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       return HCA_ERR_BAD_ARG;
     if (vq && (ly.vq_centroids == nullptr || ly.vq_lut == nullptr)) return HCA_ERR_BAD_ARG;
     const int s3 = l % p->n_sel, s4 = l % p->n_pipe;
+    // where this layer's selection goes: its own buffer, or the one of its set
+    const bool own_idx = p->d.layer_idx != nullptr;
+    auto idx_of = [&](int l2) -> int32_t* {
+      return own_idx ? p->d.layer_idx + (int64_t)l2 * p->d.layer_idx_stride : p->d.idx[l2 % p->n_pipe];
+    };
+    auto count_of = [&](int l2) -> int32_t* {
+      return own_idx ? p->d.layer_count + (int64_t)l2 * L.rows : p->d.count[l2 % p->n_pipe];
+    };
+    int32_t* const idx_l = idx_of(l);
+    int32_t* const count_l = count_of(l);
     const hipStream_t sa = scan_stream(l);           // this layer's scan stream ...
     const hipStream_t sb = p->dual ? sa : sb_topk;   // ... and the stream of its selection
     NRes nr;
@@ -643,14 +656,14 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     } else if (fused && have_second && second_layer == l + 1) {
       // first layer of a pair: one selection launch (and one pair of fall-back launches) for both layers
       const int s3b = (l + 1) % p->n_sel, s4b = (l + 1) % p->n_pipe;
-      if (p->slot_free[s4] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4], 0));
-      if (p->slot_free[s4b] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4b], 0));
+      if (!own_idx && p->slot_free[s4] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4], 0));
+      if (!own_idx && p->slot_free[s4b] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4b], 0));
       const void* const kc2[2] = {layers[l].kcache, layers[l + 1].kcache};
       const void* const q2[2] = {layers[l].q, layers[l + 1].q};
       const NRes nr2[2] = {nr, second.nr};
       const int64_t nm2[2] = {nmax, second.nmax};
-      int32_t* const idx2[2] = {p->d.idx[s4], p->d.idx[s4b]};
-      int32_t* const cnt2[2] = {p->d.count[s4], p->d.count[s4b]};
+      int32_t* const idx2[2] = {idx_l, idx_of(l + 1)};
+      int32_t* const cnt2[2] = {count_l, count_of(l + 1)};
       void* const ws2[2] = {p->d.ws_select[s3], p->d.ws_select[s3b]};
       rc = launch_select_finish_pair(L, kc2, q2, nr2, nm2, k, idx2, cnt2, ws2, sb, p->tune.select_wg == 256);
       if (rc != HCA_OK) return rc;
@@ -663,18 +676,19 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       pair_selected = true;
       pair_selected_layer = l + 1;
     } else {
-    if (p->slot_free[s4] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4], 0));
-    rc = fused ? launch_select_finish(L, ly.kcache, ly.q, nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_select[s3], sb,
+    if (!own_idx && p->slot_free[s4] != nullptr) HCA_HIP(hipStreamWaitEvent(sb, p->slot_free[s4], 0));
+    rc = fused ? launch_select_finish(L, ly.kcache, ly.q, nr, nmax, k, idx_l, count_l, p->d.ws_select[s3], sb,
                                       p->tune.select_wg == 256)
          : p->d.topp_tau > 0.0
-             ? launch_topp(L, p->d.sel[s3], nr, nmax, sm_scale, p->d.topp_tau, k, p->d.idx[s4], p->d.count[s4], nullptr,
+             ? launch_topp(L, p->d.sel[s3], nr, nmax, sm_scale, p->d.topp_tau, k, idx_l, count_l, nullptr,
                            p->d.ws_topk, sb)
-             : launch_topk(L, p->d.sel[s3], nr, nmax, k, p->d.idx[s4], p->d.count[s4], p->d.ws_topk, sb, true);
+             : launch_topk(L, p->d.sel[s3], nr, nmax, k, idx_l, count_l, p->d.ws_topk, sb, true);
     if (rc != HCA_OK) return rc;
     if (p->sel_waits) HCA_HIP(hipEventRecord(p->sel_free[s3], sb));
     HCA_HIP(hipEventRecord(p->topk_done[s4], sb));
     }
-    // stage 3: host-link gather
+    // stage 3: host-link gather.  With a selection buffer per layer the set of staging buffers is claimed here
+    if (own_idx && p->slot_free[s4] != nullptr) HCA_HIP(hipStreamWaitEvent(sg, p->slot_free[s4], 0));
     HCA_HIP(hipStreamWaitEvent(sg, p->topk_done[s4], 0));
     uint64_t* gstamps = nullptr;
     if (timing_slot >= 0 && p->d.gather_stamps != nullptr)
@@ -687,21 +701,21 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
       const uint32_t seq = p->host->next_seq();
       hs = p->host->share(s4, seq, p->host_spin_limit);
       hs.chunks = hchunks;
-      rc = launch_attend_host_chunks(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, ly.pos, n_host_rows, ly.v_hbm,
+      rc = launch_attend_host_chunks(L, ly.kcache, ly.q, idx_l, count_l, k, ly.pos, n_host_rows, ly.v_hbm,
                                      hbm_stride, sm_scale, p->d.ws_attend[s4], hs, sg);
       if (rc != HCA_OK) return rc;
       p->host->publish(seq, s4, hchunks, ly.v_host, host_stride, n_host_rows);
     }
-    rc = launch_gather(L, p->d.idx[s4], p->d.count[s4], k, ly.pos, ly.v_host, host_stride, n_host_rows, ly.v_hbm,
+    rc = launch_gather(L, idx_l, count_l, k, ly.pos, ly.v_host, host_stride, n_host_rows, ly.v_hbm,
                        hbm_stride, p->d.ws_attend[s4], sg, gstamps, hchunks * kAttendChunk, &p->tune,
                        hchunks > 0 ? &hs : nullptr);
     if (rc != HCA_OK) return rc;
     HCA_HIP(hipEventRecord(p->gather_done[s4], sg));
     // stage 4: attend (+ eviction into the spare buffers, which then swap with the layer's)
     HCA_HIP(hipStreamWaitEvent(sc, p->gather_done[s4], 0));
-    rc = vq ? launch_vq_attend_gathered(L, vg, vc, (const uint8_t*)ly.kcache, ly.vq_lut, p->d.idx[s4], p->d.count[s4], k,
+    rc = vq ? launch_vq_attend_gathered(L, vg, vc, (const uint8_t*)ly.kcache, ly.vq_lut, idx_l, count_l, k,
                                         sm_scale, ly.y, ly.acc, p->d.ws_attend[s4], sc)
-            : launch_attend_gathered(L, ly.kcache, ly.q, p->d.idx[s4], p->d.count[s4], k, sm_scale, ly.y, ly.acc,
+            : launch_attend_gathered(L, ly.kcache, ly.q, idx_l, count_l, k, sm_scale, ly.y, ly.acc,
                                      p->d.ws_attend[s4], sc, nullptr, hchunks > 0 ? &hs : nullptr);
     if (rc != HCA_OK) return rc;
     const int64_t M = evict_M != nullptr ? evict_M[l] : 0;

@@ -447,6 +447,13 @@ def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs):
         d.idx[i], d.count[i], d.ws_attend[i] = a.data_ptr(), b.data_ptr(), c.data_ptr()
     wt, we = torch.zeros(wsb, dtype=torch.uint8, device=dev), torch.zeros(wsb, dtype=torch.uint8, device=dev)
     d.ws_topk, d.ws_evict = wt.data_ptr(), we.data_ptr()
+    if (Lr + host + int(spare) + int(fused) + bits // 2) % 2 == 0:
+        # every other case: one selection result per layer instead of the sets' idx / count (a stride with slack)
+        stride = R * w.k + 24
+        lidx = torch.full((Lr * stride,), -5, dtype=torch.int32, device=dev)
+        lcnt = torch.full((Lr, R), -5, dtype=torch.int32, device=dev)
+        keep += [lidx, lcnt]
+        d.layer_idx, d.layer_count, d.layer_idx_stride = lidx.data_ptr(), lcnt.data_ptr(), stride
     if spare:
         d.spare_kcache, d.spare_acc, d.spare_pos = kc[Lr].data_ptr(), acc[Lr].data_ptr(), pos[Lr].data_ptr()
     d.topp_tau = tau
