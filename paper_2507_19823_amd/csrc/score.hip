@@ -944,7 +944,9 @@ int32_t launch_select_rescan_pair(const Layout& L, const void* const kcache[2], 
     const size_t l = (size_t)4 * bpw * L.tpb * sizeof(uint2);
     if (l > lds) lds = l;
   }
-  dim3 grid(gx < 256 ? gx : 256, (unsigned)(2 * L.rows));
+  // 16 workgroups per row, not the 256 of the per-call path: nearly always no row failed and every workgroup
+  // returns at once, but beside a running scan 4096 of them take a slot each first (0.2 ms per step at config 4)
+  dim3 grid(gx < 16 ? gx : 16, (unsigned)(2 * L.rows));
   if (L.bits == 4) score_failed_rows_pair_kernel<4, 8><<<grid, 256, lds, st>>>(L, rs[0], rs[1]);
   else score_failed_rows_pair_kernel<2, 8><<<grid, 256, lds, st>>>(L, rs[0], rs[1]);
   HCA_HIP(hipGetLastError());

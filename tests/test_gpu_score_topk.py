@@ -192,3 +192,93 @@ def test_running_monitor_over_several_calls(H):
     torch.cuda.synchronize()
     m = mon.cpu().numpy()
     assert np.all(m[:, 0] == 0) and np.all(m[:, 1] == 2**31 - 1) and np.all(m[:, 2] == 0) and np.all(m[:, 3] == 0)
+
+
+@pytest.mark.parametrize("own_idx", [False, True])
+def test_step_driver_pair_with_a_row_that_needs_the_second_scan(H, oracle, own_idx):
+    """Two layers through hca_pipeline_step with paired scan launches: layer 0's keys mislead the sample (as in
+    test_a_sample_that_misleads_still_gives_the_exact_set), layer 1's do not.  The paired fall-back launches
+    (second scan of the failed row, second selection) must leave the oracle's index sets for both layers; the
+    running monitor counts one second scan on layer 0's workspace and none on layer 1's."""
+    import ctypes as C
+    from paper_2507_19823_amd import binding as B
+    n, k, tpb = 200000, 1024, 16
+    w = S.Workload("mispair", 98, 1, 4, 1, n, 4, 32, k)
+    R, cap, Lr = 1, n + 8, 2
+    d = S.make_layer(w, want_values=False)
+    q = d["q"].clone()
+    q[0, 1:] = q[0, :1]
+    g = torch.Generator().manual_seed(5)
+    nblocks = (n + tpb - 1) // tpb
+    Sn = min(nblocks, 8192 // tpb)
+    sampled = torch.zeros(nblocks, dtype=torch.bool)
+    sampled[(torch.arange(Sn, dtype=torch.int64) * nblocks) // Sn] = True
+    sign = torch.where(sampled.repeat_interleave(tpb)[:n], 1.0, -1.0)[:, None]
+    k0 = (sign * q[0, 0].float()[None, :] * (0.5 + torch.rand(n, 1, generator=g))
+          + 0.05 * torch.randn(n, 128, generator=g)).to(torch.float16)[None, None]
+    keys = [k0, d["keys"]]
+    shape = B.make_shape(1, 4, 1, cap)
+    dev = "cuda"
+    kc = [torch.zeros(B.hca_kcache_bytes(shape), dtype=torch.uint8, device=dev) for _ in range(Lr)]
+    acc = [torch.zeros(1, 1, cap, dtype=torch.float32, device=dev) for _ in range(Lr)]
+    pos = [torch.arange(cap, dtype=torch.int32, device=dev).view(1, 1, cap).contiguous() for _ in range(Lr)]
+    vals = torch.zeros(1, 1, 64, 128, dtype=torch.float16).pin_memory()          # every value row reads row < 64
+    vd = torch.zeros(1, 1, 8, 128, dtype=torch.float16, device=dev)
+    y = torch.zeros(Lr, 1, 4, 128, dtype=torch.float32, device=dev)
+    ocs = []
+    for l in range(Lr):
+        B.hca_quantize_keys(shape, kc[l], keys[l].cuda(), n, [0])
+        pos[l].zero_()                                                         # all slots share value row 0
+        oc = oracle.Cache(R, cap, 128, 4, 32)
+        oracle.quantize(oc, keys[l].numpy().reshape(R, n, 128))
+        ocs.append(oc)
+    streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    dsc = B.hca_pipeline_desc()
+    dsc.stream_scan, dsc.stream_topk, dsc.stream_gather, dsc.stream_attend = (s_.cuda_stream for s_ in streams)
+    wsb = B.hca_workspace_bytes(shape, k, 1)
+    keep = []
+    wsel = [torch.zeros(wsb, dtype=torch.uint8, device=dev) for _ in range(3)]
+    for i in range(3):
+        dsc.ws_select[i] = wsel[i].data_ptr()
+    dsc.n_sel, dsc.fused_select, dsc.n_pipe, dsc.dual_scan = 3, 1, 4, 2
+    sets = []
+    for i in range(4):
+        a = torch.full((1, 1, k), -3, dtype=torch.int32, device=dev)
+        b_ = torch.zeros(1, 1, dtype=torch.int32, device=dev)
+        c_ = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+        sets.append((a, b_, c_))
+        dsc.idx[i], dsc.count[i], dsc.ws_attend[i] = a.data_ptr(), b_.data_ptr(), c_.data_ptr()
+    wt = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+    dsc.ws_topk = wt.data_ptr()
+    lidx = torch.full((Lr, k), -3, dtype=torch.int32, device=dev)
+    lcnt = torch.zeros(Lr, 1, dtype=torch.int32, device=dev)
+    if own_idx:
+        dsc.layer_idx, dsc.layer_count, dsc.layer_idx_stride = lidx.data_ptr(), lcnt.data_ptr(), k
+    pl = B.hca_pipeline_create(shape, Lr, dsc, 0)
+    for i in range(2):
+        B.hca_score_topk_monitor(shape, wsel[i], None, True)
+    layers = (B.hca_layer * Lr)()
+    k_new = torch.zeros(1, 1, 1, 128, dtype=torch.float16, device=dev)         # the appended token: a zero key
+    qd = q.cuda()
+    for l in range(Lr):
+        layers[l].kcache, layers[l].acc, layers[l].pos = kc[l].data_ptr(), acc[l].data_ptr(), pos[l].data_ptr()
+        layers[l].v_host, layers[l].v_hbm, layers[l].y = vals.data_ptr(), vd.data_ptr(), y[l].data_ptr()
+        layers[l].k_new, layers[l].q = k_new.data_ptr(), qd.data_ptr()
+    nres = (C.c_int64 * Lr)(n, n)
+    torch.cuda.synchronize()
+    B.hca_pipeline_step(pl, layers, nres, 0, k, 64, 64, 8, 0.0884, None, 0, -1)
+    torch.cuda.synchronize()
+    mon = torch.zeros(2, R, 4, dtype=torch.int32, device=dev)
+    for i in range(2):
+        B.hca_score_topk_monitor(shape, wsel[i], mon[i], False)
+    torch.cuda.synchronize()
+    for l in range(Lr):
+        oracle.quantize(ocs[l], np.zeros((R, 1, 128), np.float16))
+        sel, _ = oracle.score(ocs[l], q.numpy().reshape(-1, 128), want_z=False)
+        oidx, ocount = oracle.topk(sel, ocs[l].n, k)
+        gi = (lidx[l] if own_idx else sets[l][0].view(-1)).cpu().numpy()
+        assert np.array_equal(gi, oidx[0]), f"layer {l}: index sets differ"
+    m = mon.cpu().numpy()
+    assert m[0, 0, 0] == 1 and m[0, 0, 3] == 1, "layer 0 should have needed the second scan"
+    assert m[1, 0, 0] == 1 and m[1, 0, 3] == 0
+    B.hca_pipeline_destroy(pl)
