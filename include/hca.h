@@ -309,7 +309,8 @@ typedef struct {
      host_threads: worker threads (1 .. 64; they poll while steps are in flight and sleep when idle; 0 starts
      none - then every merge times out, for tests of that path).  host_spin_limit: polls of the host's flag
      before a merge gives up and records a timeout (0: about a second); see hca_pipeline_host_status.
-     The driver owns the pinned exchange buffers (about 1.3 KiB per selected token of the host share, one set per
+     The driver owns the pinned exchange buffers (28 bytes per selected token of the host share - four fp32 weights, a
+     row number, and 2 KiB of partial sums per chunk of 256 -, one set per
      idx / count / ws_attend set) and the threads from hca_pipeline_create to hca_pipeline_destroy. */
   int32_t host_chunks, host_threads, host_spin_limit;
   /* Launch-shape knobs of this pipeline's kernels (0: the library's default; ranges as in hca_tune). */
