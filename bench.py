@@ -1131,6 +1131,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gap-report", action="store_true",
                     help="log the largest idle times between consecutive scan launches with their step.layer")
+    ap.add_argument("--timeline-out", default="", metavar="PATH",
+                    help="with --gap-report: write the merged timeline of scan launches and gathers around one step "
+                         "boundary (wall-clock stamps, us) to this file")
     ap.add_argument("--no-fused-select", action="store_true",
                     help="scan and top-k as two calls with a score buffer between them (hca_score_qkeys, hca_topk) "
                          "instead of hca_score_topk; always so with --pipeline staged / gather / none")
@@ -1406,6 +1409,8 @@ def main():
                 float(gdur.mean()), float(ggaps.mean()), float(ggaps.median())))
             # merged timeline of scan launches and gathers around one step boundary (wall-clock stamps, us)
             try:
+                if not args.timeline_out:
+                    raise RuntimeError("no --timeline-out path given")
                 sb_, ge_ = starts.reshape(-1).double() / khz * 1e3, ends.reshape(-1).double() / khz * 1e3
                 per = sb_.numel() // args.steps
                 mid = (args.steps // 2) * per
@@ -1415,11 +1420,11 @@ def main():
                 gi0 = (args.steps // 2) * L
                 ev_ += [(float(g_start[i]) / khz * 1e3 - base, float(g_end[i]) / khz * 1e3 - base, f"gather layer {i % L} step {i // L}")
                         for i in range(gi0 - L // 2, gi0 + L // 2)]
-                with open(os.path.join(ROOT, "gpurun_out", "timeline_stamps.txt"), "w") as f:
+                with open(args.timeline_out, "w") as f:
                     for a_, b_, n_ in sorted(ev_):
                         f.write(f"{a_:10.1f} {b_:10.1f} {n_}\n")
             except Exception as e:                    # a diagnostic only
-                log(f"timeline dump failed: {e}")
+                log(f"no timeline written: {e}")
             gtop = torch.topk(ggaps, 24)
             log("largest gather gaps (us @ step.layer): " + " ".join(
                 "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(gtop.values, gtop.indices)))
