@@ -235,17 +235,22 @@ def test_vq_one_layer_at_full_size(oracle, c):
     assert np.allclose(_rows(acc), oacc, rtol=1e-4, atol=1e-7)
 
 
-@pytest.mark.parametrize("fused", [False, True])
-def test_step_driver_at_full_size(oracle, fused):
-    """The library's step driver as bench.py runs it - four stages on four streams, a score buffer (or, with
-    the fused scan + top-k, a selection workspace) per slot, in-place eviction - on two layers of workload 4 at full size (1 Mi tokens each), two decode steps, the
-    second with an eviction of layer 1: every layer's selection (through its output), output, resident count
-    and, at the end, accumulated scores and value-row map against the oracle."""
+@pytest.mark.parametrize("mode", ["two_calls", "fused", "as_timed"])
+def test_step_driver_at_full_size(oracle, mode):
+    """The library's step driver - four stages on four streams, a score buffer (or, with the fused scan + top-k,
+    a selection workspace) per slot, in-place eviction - on layers of workload 4 at full size (1 Mi tokens each),
+    two decode steps, the second with an eviction of layer 1: every layer's selection (through its output; in the
+    third form the index sets themselves), output, resident count and, at the end, accumulated scores and
+    value-row map against the oracle.  "as_timed" is the launch configuration bench.py times by default: four
+    layers as two paired scan launches, a selection workspace and a selection result per layer, eight sets of
+    staging buffers, 14 of every row's 16 chunks summed by 14 host threads."""
     import ctypes as C
     import math
     from paper_2507_19823_amd import binding as B
     w = S.CONFIGS[4]
-    Lr, steps = 2, 2
+    fused = mode != "two_calls"
+    timed_form = mode == "as_timed"
+    Lr, steps = (4 if timed_form else 2), 2
     R, n0 = w.batch * w.n_kv_heads, w.n
     cap, vnew = n0 + 32, 8
     shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
@@ -259,6 +264,8 @@ def test_step_driver_at_full_size(oracle, fused):
         B.hca_quantize_keys(shape, k_t, d["keys"], n0, [0] * w.batch, a_t, p_t, [0] * w.batch)
         v = torch.empty(w.batch, w.n_kv_heads, n0, 128, dtype=torch.float16, pin_memory=True)
         v.copy_(d["values"])
+        if timed_form:
+            B.hca_host_prefault(v, 16)            # the host threads' first touch of a page would cost a fault each
         kc.append(k_t); acc.append(a_t); pos.append(p_t); vh.append(v)
         vd.append(torch.zeros(w.batch, w.n_kv_heads, vnew, 128, dtype=torch.float16, device=dev))
         oc = oracle.Cache(R, cap, 128, w.bits, w.group)
@@ -277,7 +284,8 @@ def test_step_driver_at_full_size(oracle, fused):
     d = B.hca_pipeline_desc()
     d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
     keep = []
-    for i in range(3):
+    n_sel, n_pipe = (Lr, 8) if timed_form else (3, 4)
+    for i in range(n_sel):
         if fused:
             t = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
             d.ws_select[i] = t.data_ptr()
@@ -285,10 +293,16 @@ def test_step_driver_at_full_size(oracle, fused):
             t = torch.zeros(w.batch, w.n_kv_heads, cap, dtype=torch.float32, device=dev)
             d.sel[i] = t.data_ptr()
         keep.append(t)
-    d.n_sel = 3
+    d.n_sel = n_sel
     d.fused_select = int(fused)
+    lidx = None
+    if timed_form:
+        d.n_pipe, d.dual_scan, d.host_chunks, d.host_threads = n_pipe, 2, 14, 14
+        lidx = torch.full((Lr, R, w.k), -5, dtype=torch.int32, device=dev)
+        lcnt = torch.full((Lr, R), -5, dtype=torch.int32, device=dev)
+        d.layer_idx, d.layer_count, d.layer_idx_stride = lidx.data_ptr(), lcnt.data_ptr(), R * w.k
     wsb = B.hca_workspace_bytes(shape, w.k, n0)
-    for i in range(4):
+    for i in range(n_pipe):
         a = torch.zeros(w.batch, w.n_kv_heads, w.k, dtype=torch.int32, device=dev)
         b = torch.zeros(w.batch, w.n_kv_heads, dtype=torch.int32, device=dev)
         c = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
@@ -327,6 +341,9 @@ def test_step_driver_at_full_size(oracle, fused):
             idx, count = oracle.topk(sel, oc.n, w.k)
             yo, _ = oracle.attend(oc, q16, idx, count, opos[l], oV[l], np.float32(sm), acc=oacc[l])
             assert _rel_err(y[l].cpu().numpy().reshape(-1, 128), yo) <= TOL, f"step {t} layer {l}"
+            if lidx is not None:
+                assert np.array_equal(lidx[l].cpu().numpy(), idx), f"step {t} layer {l}: top-k sets differ"
+                assert np.array_equal(lcnt[l].cpu().numpy(), count), f"step {t} layer {l}"
             if due[l]:
                 assert int((oacc[l] > 0).sum(1).max()) < n0 - 1          # ties decide: the keep-set is unique
                 oracle.evict(oc, oacc[l], opos[l], n0, 1)
@@ -336,6 +353,8 @@ def test_step_driver_at_full_size(oracle, fused):
         assert np.array_equal(_rows(pos[l])[:, :n], opos[l][:, :n])
         assert np.array_equal(_rows(acc[l])[:, :n] > 0, oacc[l][:, :n] > 0)
         assert np.allclose(_rows(acc[l])[:, :n], oacc[l][:, :n], rtol=1e-3, atol=1e-7)
+    if timed_form:
+        assert B.hca_pipeline_host_status(pl) == (0, 0)
     B.hca_pipeline_destroy(pl)
 
 
