@@ -235,11 +235,11 @@ def test_vq_one_layer_at_full_size(oracle, c):
     assert np.allclose(_rows(acc), oacc, rtol=1e-4, atol=1e-7)
 
 
-@pytest.mark.parametrize("mode", ["two_calls", "fused", "as_timed"])
-def test_step_driver_at_full_size(oracle, mode):
+@pytest.mark.parametrize("cfg,mode", [(4, "two_calls"), (4, "fused"), (4, "as_timed"), (5, "as_timed")])
+def test_step_driver_at_full_size(oracle, cfg, mode):
     """The library's step driver - four stages on four streams, a score buffer (or, with the fused scan + top-k,
-    a selection workspace) per slot, in-place eviction - on layers of workload 4 at full size (1 Mi tokens each),
-    two decode steps, the second with an eviction of layer 1: every layer's selection (through its output; in the
+    a selection workspace) per slot, in-place eviction - on layers of workload 4 at full size (1 Mi tokens each;
+    workload 5: 4 Mi tokens of 2-bit codes, k 8192), two decode steps, the second with an eviction of layer 1: every layer's selection (through its output; in the
     third form the index sets themselves), output, resident count and, at the end, accumulated scores and
     value-row map against the oracle.  "as_timed" is the launch configuration bench.py times by default: four
     layers as two paired scan launches, a selection workspace and a selection result per layer, eight sets of
@@ -247,13 +247,13 @@ def test_step_driver_at_full_size(oracle, mode):
     import ctypes as C
     import math
     from paper_2507_19823_amd import binding as B
-    w = S.CONFIGS[4]
+    w = S.CONFIGS[cfg]
     fused = mode != "two_calls"
     timed_form = mode == "as_timed"
-    Lr, steps = (4 if timed_form else 2), 2
+    Lr, steps = (4 if timed_form and cfg == 4 else 2), 2
     R, n0 = w.batch * w.n_kv_heads, w.n
     cap, vnew = n0 + 32, 8
-    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap)
+    shape = B.make_shape(w.batch, w.n_q_heads, w.n_kv_heads, cap, w.bits, w.group)
     dev = "cuda"
     kc, acc, pos, vh, vd, ocs, oacc, opos, oV = [], [], [], [], [], [], [], [], []
     for l in range(Lr):
@@ -284,7 +284,7 @@ def test_step_driver_at_full_size(oracle, mode):
     d = B.hca_pipeline_desc()
     d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
     keep = []
-    n_sel, n_pipe = (Lr, 8) if timed_form else (3, 4)
+    n_sel, n_pipe = (max(Lr, 3), 8) if timed_form else (3, 4)
     for i in range(n_sel):
         if fused:
             t = torch.zeros(B.hca_workspace_bytes(shape, w.k, 1), dtype=torch.uint8, device=dev)
@@ -297,7 +297,7 @@ def test_step_driver_at_full_size(oracle, mode):
     d.fused_select = int(fused)
     lidx = None
     if timed_form:
-        d.n_pipe, d.dual_scan, d.host_chunks, d.host_threads = n_pipe, 2, 14, 14
+        d.n_pipe, d.dual_scan, d.host_chunks, d.host_threads = n_pipe, 2, 14 * (w.k // 256) // 16, 14
         lidx = torch.full((Lr, R, w.k), -5, dtype=torch.int32, device=dev)
         lcnt = torch.full((Lr, R), -5, dtype=torch.int32, device=dev)
         d.layer_idx, d.layer_count, d.layer_idx_stride = lidx.data_ptr(), lcnt.data_ptr(), R * w.k
