@@ -45,11 +45,15 @@ static void carve(EvictWs* e, void* ws, const Layout& L, int64_t M) {
 }
 
 // Ordered pass over all resident slots of a row: writes kept[position] = old slot.
+// skip_identity (in-place compaction into the workspace's own list only): a chunk up to whose end every slot is
+// kept holds kept[d] = d, which nothing reads - the moves start at the block of the first dropped slot -, so its
+// workgroup returns without touching acc or the list.  The chunk prefixes say so: slots kept below the next
+// chunk's start = #(above T) + min(#(equal to T), r_eq) counted below it.
 __global__ __launch_bounds__(256) void evict_positions(const float* __restrict__ acc, int64_t stride, int64_t chunk,
                                                        int nchunks, int n_kv_heads, SelRows sr, NRes nr,
                                                        uint32_t* __restrict__ state,
                                                        const uint32_t* __restrict__ coff, int64_t M,
-                                                       int32_t* __restrict__ kept) {
+                                                       int32_t* __restrict__ kept, int skip_identity) {
   __shared__ uint32_t wsum[2][4];
   const int row = blockIdx.y;
   const int b = row / n_kv_heads;
@@ -61,6 +65,11 @@ __global__ __launch_bounds__(256) void evict_positions(const float* __restrict__
   int64_t c1 = c0 + chunk;
   if (c1 > n) c1 = n;
   const uint32_t T = state[4 * row], req = state[4 * row + 1];
+  if (skip_identity && (int)blockIdx.x + 1 < nchunks && c0 + chunk <= nsel) {
+    const uint32_t ng = coff[((int64_t)row * nchunks + blockIdx.x + 1) * 2];
+    const uint32_t ne = coff[((int64_t)row * nchunks + blockIdx.x + 1) * 2 + 1];
+    if ((int64_t)ng + (int64_t)(ne < req ? ne : req) == c0 + chunk) return;
+  }
   uint32_t base_g = coff[((int64_t)row * nchunks + blockIdx.x) * 2];
   uint32_t base_e = coff[((int64_t)row * nchunks + blockIdx.x) * 2 + 1];
   const float* v = acc + (int64_t)row * stride;
@@ -261,7 +270,8 @@ static int32_t evict_prepare(const Layout& L, void* kcache, float* acc, int32_t*
   if (rc != HCA_OK) return rc;
   dim3 g((unsigned)p.nchunks, (unsigned)L.rows);
   pl->state = p.state;
-  evict_positions<<<g, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, pl->kept);
+  evict_positions<<<g, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, pl->kept,
+                                     (!pl->oop && kept == nullptr) ? 1 : 0);
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }
@@ -450,7 +460,7 @@ int32_t launch_vq_evict(const Layout& L, int g, int c, uint8_t* pcache, float* a
   int32_t rc = select_run(p, acc, L.cap, L.rows, L.n_kv_heads, sr, st);
   if (rc != HCA_OK) return rc;
   dim3 g1((unsigned)p.nchunks, (unsigned)L.rows);
-  evict_positions<<<g1, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kp);
+  evict_positions<<<g1, 256, 0, st>>>(acc, L.cap, p.chunk, p.nchunks, L.n_kv_heads, sr, nr, p.state, p.coff, M, kp, 0);
   if (oop) {
     dim3 gg(wgs(M * pieces), (unsigned)L.rows);
     vq_evict_gather<<<gg, 256, 0, st>>>(rb, 0, rb, 0, pieces, wide ? 1 : 0, g, L.cap, L.cap, pcache, acc, pos, L.n_kv_heads,

@@ -4,7 +4,9 @@
 // selected slots in ascending order with ties resolved towards the lower slot:
 //   selected(j) = key_j > T  or  (key_j == T and #{i < j : key_i == T} < r_eq)
 //   position(j) = #{i < j : key_i > T} + min(#{i < j : key_i == T}, r_eq)
-// This is the sorted prefix Pi_k of Sec. 3.2 without sorting.
+// This is the sorted prefix Pi_k of Sec. 3.2 without sorting.  The engine serves the eviction's keep-set, whose
+// values are accumulated softmax weights: a first counting pass against 0 settles T for every row whose
+// wanted-th largest value is 0 (sel_try_zero), and the radix passes skip those rows.
 #include "hca_internal.h"
 
 namespace hca {
@@ -43,6 +45,7 @@ __global__ void sel_init(uint32_t* hist, uint32_t* state, int rows, int n_kv_hea
     state[4 * i + 0] = (want == 0) ? 0xffffffffu : 0u;
     state[4 * i + 1] = want > 0 ? (uint32_t)want : 0u;
     state[4 * i + 2] = 0xffffffffu;          // lowest slot that is not selected (filled in by the eviction's ordered pass)
+    state[4 * i + 3] = 0u;                   // 1: threshold found by the zero-threshold shortcut, the radix passes skip the row
   }
 }
 
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(256) void sel_hist(const float* __restrict__ vals, 
   __shared__ uint32_t lh[kBins];
   const int row = blockIdx.y;
   const int64_t nsel = sr.nsel[row / n_kv_heads];
-  if (sr.want[row / n_kv_heads] <= 0) return;
+  if (sr.want[row / n_kv_heads] <= 0 || state[4 * row + 3] != 0) return;
   const int64_t c0 = (int64_t)blockIdx.x * chunk;
   if (c0 >= nsel) return;
   int64_t c1 = c0 + chunk;
@@ -106,7 +109,7 @@ __global__ __launch_bounds__(256) void sel_scan(const uint32_t* __restrict__ his
                                                 int n_kv_heads, SelRows sr) {
   __shared__ uint32_t s[256];
   const int row = blockIdx.x;
-  if (sr.want[row / n_kv_heads] <= 0) return;
+  if (sr.want[row / n_kv_heads] <= 0 || state[4 * row + 3] != 0) return;
   const uint32_t remaining = state[4 * row + 1];
   const uint32_t* gh = hist + ((int64_t)row * 3 + PASS) * kBins;
   const int t = threadIdx.x;
@@ -134,17 +137,21 @@ __global__ __launch_bounds__(256) void sel_scan(const uint32_t* __restrict__ his
   }
 }
 
+// AT_ZERO: the counts are taken against the key of +0.0f, before any radix pass (the shortcut below); otherwise
+// against the row's threshold, and rows that the shortcut resolved keep the counts they already have.
+template <bool AT_ZERO>
 __global__ __launch_bounds__(256) void sel_count(const float* __restrict__ vals, int64_t stride, int64_t chunk,
                                                  int n_kv_heads, SelRows sr, const uint32_t* __restrict__ state,
                                                  uint32_t* __restrict__ ccount) {
   __shared__ uint32_t red[2][4];
   const int row = blockIdx.y;
   if (sr.want[row / n_kv_heads] < 0) return;
+  if (!AT_ZERO && state[4 * row + 3] != 0) return;
   const int64_t nsel = sr.nsel[row / n_kv_heads];
   const int64_t c0 = (int64_t)blockIdx.x * chunk;
   int64_t c1 = c0 + chunk;
   if (c1 > nsel) c1 = nsel;
-  const uint32_t T = state[4 * row];
+  const uint32_t T = AT_ZERO ? order_key(0.0f) : state[4 * row];
   const float* v = vals + (int64_t)row * stride;
   uint32_t gt = 0, eq = 0;
   for (int64_t j = c0 + threadIdx.x; j < c1; j += 256) {
@@ -161,6 +168,39 @@ __global__ __launch_bounds__(256) void sel_count(const float* __restrict__ vals,
     uint32_t* o = ccount + ((int64_t)row * gridDim.x + blockIdx.x) * 2;
     o[0] = red[0][0] + red[0][1] + red[0][2] + red[0][3];
     o[1] = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+  }
+}
+
+// The zero-threshold shortcut.  Accumulated scores are sums of softmax weights: never negative, and exactly 0 for
+// every token that was never selected - most of a long context.  When fewer than `want` slots lie above 0 and the
+// zeros make up the rest, the want-th largest key is the key of +0.0f and the number of zeros to take is
+// want - #(above 0): exactly what the three radix passes would find, from one pass whose per-chunk counts are also
+// the ones the ordered pass needs.  One workgroup per row sums the chunk counts and decides.
+__global__ __launch_bounds__(256) void sel_try_zero(const uint32_t* __restrict__ ccount, uint32_t* __restrict__ state,
+                                                    int nchunks, int n_kv_heads, SelRows sr) {
+  __shared__ uint32_t s[2][256];
+  const int row = blockIdx.x;
+  const int64_t want = sr.want[row / n_kv_heads];
+  if (want <= 0) return;
+  const int t = threadIdx.x;
+  uint32_t g = 0, e = 0;
+  for (int c = t; c < nchunks; c += 256) {
+    g += ccount[((int64_t)row * nchunks + c) * 2];
+    e += ccount[((int64_t)row * nchunks + c) * 2 + 1];
+  }
+  s[0][t] = g; s[1][t] = e;
+  __syncthreads();
+  for (int o = 128; o >= 1; o >>= 1) {
+    if (t < o) { s[0][t] += s[0][t + o]; s[1][t] += s[1][t + o]; }
+    __syncthreads();
+  }
+  if (t == 0) {
+    const uint64_t above = s[0][0], zeros = s[1][0];
+    if (above < (uint64_t)want && (uint64_t)want <= above + zeros) {
+      state[4 * row + 0] = order_key(0.0f);
+      state[4 * row + 1] = (uint32_t)((uint64_t)want - above);
+      state[4 * row + 3] = 1u;
+    }
   }
 }
 
@@ -206,13 +246,15 @@ int32_t select_run(const SelectPlan& p, const float* vals, int64_t stride, int r
     sel_init<<<(unsigned)((n + 255) / 256), 256, 0, st>>>(p.hist, p.state, rows, n_kv_heads, sr);
   }
   dim3 g((unsigned)p.nchunks, (unsigned)rows);
+  sel_count<true><<<g, 256, 0, st>>>(vals, stride, p.chunk, n_kv_heads, sr, p.state, p.ccount);
+  sel_try_zero<<<rows, 256, 0, st>>>(p.ccount, p.state, p.nchunks, n_kv_heads, sr);
   sel_hist<0><<<g, 256, 0, st>>>(vals, stride, p.chunk, n_kv_heads, sr, p.hist, p.state);
   sel_scan<0><<<rows, 256, 0, st>>>(p.hist, p.state, n_kv_heads, sr);
   sel_hist<1><<<g, 256, 0, st>>>(vals, stride, p.chunk, n_kv_heads, sr, p.hist, p.state);
   sel_scan<1><<<rows, 256, 0, st>>>(p.hist, p.state, n_kv_heads, sr);
   sel_hist<2><<<g, 256, 0, st>>>(vals, stride, p.chunk, n_kv_heads, sr, p.hist, p.state);
   sel_scan<2><<<rows, 256, 0, st>>>(p.hist, p.state, n_kv_heads, sr);
-  sel_count<<<g, 256, 0, st>>>(vals, stride, p.chunk, n_kv_heads, sr, p.state, p.ccount);
+  sel_count<false><<<g, 256, 0, st>>>(vals, stride, p.chunk, n_kv_heads, sr, p.state, p.ccount);
   sel_offsets<<<rows, 256, 0, st>>>(p.ccount, p.coff, p.nchunks, n_kv_heads, sr);
   HCA_HIP(hipGetLastError());
   return HCA_OK;

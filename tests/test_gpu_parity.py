@@ -271,6 +271,58 @@ def test_evict_bit_exact_stagewise(H, oracle, bits, gs, n, M, Rp, mode):
     assert np.array_equal(_rows(st.pos)[:, :m], pos[:, :m])
 
 
+@pytest.mark.parametrize("with_list", [True, False])
+@pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
+@pytest.mark.parametrize("n,M,Rp", [(13000, 12000, 16), (13000, 12990, 16), (9000, 4100, 0)])
+def test_evict_when_the_threshold_is_zero(H, oracle, bits, gs, n, M, Rp, with_list):
+    """Rows whose accumulated scores are mostly exact zeros, as in a long context, with the number of positive
+    entries just below, at and just above the number of slots to keep from the unprotected part (the cases on
+    both sides of the point where the M-th largest score becomes 0), a row with -0.0 among the zeros and negative
+    entries, a row with too few non-negative entries, and the positive entries either spread out or packed at the
+    front (so that whole chunks keep every slot): keep lists (when asked for) and compacted state against the
+    oracle, in place, with and without a caller's keep list."""
+    w = S.Workload("ez", 90 + bits, 2, 4, 2, n, bits, gs, 16)
+    want = M - Rp
+    nsel = n - Rp
+    for variant in range(2):
+        rng = np.random.default_rng(1000 * variant + n + M)
+        d = S.make_layer(w, want_values=False)
+        cap = n + 5
+        st = _state(H, w, cap=cap, m_max=M)
+        oc = _ocache(oracle, w, cap)
+        st.quantize(d["keys"].cuda())
+        oracle.quantize(oc, _rows(d["keys"]))
+        R = 4
+        acc = np.zeros((R, cap), np.float32)
+        counts = [want - 1, want, want + 1, 7] if variant == 0 else [want - 1, 0, min(want + 300, nsel), want // 2]
+        for r, c in enumerate(counts):
+            c = max(0, min(c, nsel))
+            where = rng.permutation(nsel)[:c] if (r + variant) % 2 == 0 else np.arange(c)
+            acc[r, where] = (rng.integers(1, 4, c) * 0.25).astype(np.float32)
+        if variant == 1:
+            z = rng.permutation(nsel)[:nsel // 3]
+            acc[3, z] = np.where(acc[3, z] == 0, np.float32(-0.0), acc[3, z])      # -0.0 among the zeros
+            neg = rng.permutation(nsel)[:50]
+            acc[3, neg] = -1.5                                                     # below every zero
+            neg = rng.permutation(nsel)[:nsel - want + 40]
+            acc[1, :nsel] = 0.0
+            acc[1, neg] = -rng.random(neg.size).astype(np.float32) - 0.5           # fewer than `want` entries >= 0
+        acc[:, nsel:n] = 0.125
+        pos = np.zeros((R, cap), np.int32)
+        pos[:, :n] = rng.permutation(n).astype(np.int32)[None]
+        st.acc.copy_(torch.from_numpy(acc.reshape(2, 2, cap)))
+        st.pos.copy_(torch.from_numpy(pos.reshape(2, 2, cap)))
+        kept = torch.full((2, 2, M), -5, dtype=torch.int32, device="cuda") if with_list else None
+        st.evict(M, Rp, kept)
+        torch.cuda.synchronize()
+        okept = oracle.evict(oc, acc, pos, M, Rp)
+        if with_list:
+            assert np.array_equal(_rows(kept), okept), f"variant {variant}"
+        _cmp_cache(st, oc)
+        assert np.array_equal(_rows(st.acc)[:, :M].view(np.uint32), acc[:, :M].view(np.uint32)), f"variant {variant}"
+        assert np.array_equal(_rows(st.pos)[:, :M], pos[:, :M]), f"variant {variant}"
+
+
 def test_decode_loop_with_appends_and_eviction(H, oracle):
     """Config-3-like loop at reduced length: append one token per step, attend, evict every 4 steps;
     the GPU state is compared with the oracle after every step (stage-wise on acc)."""
