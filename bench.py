@@ -1459,9 +1459,10 @@ def main():
                    "evict_every": args.evict_every,
                    "eviction_case": ("in place; M = the context length, the newest evict_every slots protected: the dropped "
                                      "slots are the newest never-selected ones just below the protected window (ties go "
-                                     "against the higher slot), so only the selection passes over the accumulated scores "
-                                     "and a short tail move are paid; an eviction whose first dropped slot is early costs "
-                                     "about 0.7 ms per layer instead of 0.1-0.2") if args.evict_every else None,
+                                     "against the higher slot) and the keep-set's threshold is 0, so one counting pass "
+                                     "over the accumulated scores and a short tail move are paid (~0.06 ms per layer); "
+                                     "an eviction whose first dropped slot is early costs about 0.7 ms per layer, one "
+                                     "whose threshold is not 0 four more passes") if args.evict_every else None,
                    "values": "context rows in pinned host fp16, appended rows in an HBM slice",
                    "physical_value_layers": phys, "pipeline": args.pipeline,
                    "value_side": (f"hybrid: {model.host_chunks} of {-(-w.k // 256)} chunks of 256 selected tokens per row "
