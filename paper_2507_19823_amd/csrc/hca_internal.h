@@ -1,6 +1,7 @@
 // Host-side declarations shared by the translation units of libhca.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include <atomic>
@@ -140,11 +141,11 @@ int32_t launch_select_step(const Layout& L, const void* kcache, const void* q, c
                            const SelectOut& so, hipStream_t st, uint64_t* stamps, const SelectStepNext& nx);
 int32_t launch_select_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
                                 const int64_t nmax[2], const SelectOut so[2], uint64_t* const stamps[2],
-                                const SelectStepNext nx[2], hipStream_t st);
+                                const SelectStepNext nx[2], hipStream_t st, hipEvent_t done = nullptr);
 // the two layers of a pair launch, each with its selection workspace
 int32_t launch_select_scan_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2],
                                      const NRes nr[2], const int64_t nmax[2], int32_t k, void* const ws[2], hipStream_t st,
-                                     uint64_t* const stamps[2], const SelectStepNext nx[2]);
+                                     uint64_t* const stamps[2], const SelectStepNext nx[2], hipEvent_t done = nullptr);
 // the start of a step as two launches: sampling of up to four layers, threshold + append of up to two
 int32_t launch_select_begin_samples(const Layout& L, int n, const void* const kcache[], const void* const q[],
                                     const NRes nr[], const SelectOut so[], hipStream_t st);

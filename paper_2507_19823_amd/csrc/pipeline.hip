@@ -596,6 +596,7 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
         if (rc != HCA_OK) return rc;
         const bool timed = timing_slot >= 0 && l % p->timing_stride == 0;
         if (timed) HCA_HIP(hipEventRecord(p->t0[(size_t)timing_slot * p->n_layers + l], sa));
+        hipEvent_t bound = nullptr;
         if (p->pair && l + 1 < p->n_layers) {
           rc = fused_prepare(l + 1, &c1);
           if (rc != HCA_OK) return rc;
@@ -606,7 +607,10 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
           void* const ws2[2] = {p->d.ws_select[s3], p->d.ws_select[(l + 1) % p->n_sel]};
           uint64_t* const st2[2] = {c0.stamps, c1.stamps};
           const SelectStepNext nx2[2] = {c0.nx, c1.nx};
-          rc = launch_select_scan_step_pair(L, kc2, q2, nr2, nm2, k, ws2, sa, st2, nx2);
+          // the launch's completion event rides on the dispatch itself: the end-of-bracket event when the launch
+          // is timed (the selection stream then waits for that one), the layer's score_done otherwise
+          bound = timed ? p->t1[(size_t)timing_slot * p->n_layers + l] : (sb != sa ? p->score_done[s3] : nullptr);
+          rc = launch_select_scan_step_pair(L, kc2, q2, nr2, nm2, k, ws2, sa, st2, nx2, bound);
           second = c1;
           second_layer = l + 1;
           have_second = true;
@@ -614,10 +618,14 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
           rc = launch_select_scan_step(L, ly.kcache, ly.q, c0.nr, c0.nmax, k, p->d.ws_select[s3], sa, c0.stamps, c0.nx);
         }
         if (rc != HCA_OK) return rc;
-        if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
-        if (sb != sa) {
-          HCA_HIP(hipEventRecord(p->score_done[s3], sa));
-          HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
+        if (bound != nullptr) {
+          if (sb != sa) HCA_HIP(hipStreamWaitEvent(sb, bound, 0));
+        } else {
+          if (timed) HCA_HIP(hipEventRecord(p->t1[(size_t)timing_slot * p->n_layers + l], sa));
+          if (sb != sa) {
+            HCA_HIP(hipEventRecord(p->score_done[s3], sa));
+            HCA_HIP(hipStreamWaitEvent(sb, p->score_done[s3], 0));
+          }
         }
         nr = c0.nr;
         nmax = c0.nmax;

@@ -908,9 +908,12 @@ static int32_t fill_side(const Layout& L, const void* kcache, const void* q, con
 }
 
 // The selecting scans of two layers (and what each carries for the layers behind it) as one launch.
+// `done` (optional): an event that completes with this launch.  It is bound to the dispatch itself
+// (hipExtLaunchKernelGGL's stop event) instead of being recorded behind it: a recorded event is a packet of its
+// own on the stream, and the next scan launch waits ~8 us for it.
 int32_t launch_select_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2], const NRes nr[2],
                                 const int64_t nmax[2], const SelectOut so[2], uint64_t* const stamps[2],
-                                const SelectStepNext nx[2], hipStream_t st) {
+                                const SelectStepNext nx[2], hipStream_t st, hipEvent_t done) {
   StepSide s0, s1;
   unsigned gx = 0;
   size_t lds = 0;
@@ -919,8 +922,15 @@ int32_t launch_select_step_pair(const Layout& L, const void* const kcache[2], co
   rc = fill_side(L, kcache[1], q[1], nr[1], nmax[1], so[1], stamps[1], nx[1], &s1, &gx, &lds);
   if (rc != HCA_OK) return rc;
   dim3 grid(gx, (unsigned)(2 * L.rows));
-  if (L.bits == 4) score_select_pair_kernel<4, 8><<<grid, 256, lds, st>>>(L, s0, s1);
-  else score_select_pair_kernel<2, 8><<<grid, 256, lds, st>>>(L, s0, s1);
+  if (done != nullptr) {
+    if (L.bits == 4)
+      hipExtLaunchKernelGGL((score_select_pair_kernel<4, 8>), grid, dim3(256), (uint32_t)lds, st, nullptr, done, 0, L, s0, s1);
+    else
+      hipExtLaunchKernelGGL((score_select_pair_kernel<2, 8>), grid, dim3(256), (uint32_t)lds, st, nullptr, done, 0, L, s0, s1);
+  } else {
+    if (L.bits == 4) score_select_pair_kernel<4, 8><<<grid, 256, lds, st>>>(L, s0, s1);
+    else score_select_pair_kernel<2, 8><<<grid, 256, lds, st>>>(L, s0, s1);
+  }
   HCA_HIP(hipGetLastError());
   return HCA_OK;
 }

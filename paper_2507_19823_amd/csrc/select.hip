@@ -1327,7 +1327,7 @@ int32_t launch_select_scan_step(const Layout& L, const void* kcache, const void*
 
 int32_t launch_select_scan_step_pair(const Layout& L, const void* const kcache[2], const void* const q[2],
                                      const NRes nr[2], const int64_t nmax[2], int32_t k, void* const ws[2], hipStream_t st,
-                                     uint64_t* const stamps[2], const SelectStepNext nx[2]) {
+                                     uint64_t* const stamps[2], const SelectStepNext nx[2], hipEvent_t done) {
   SelectOut so[2];
   for (int i = 0; i < 2; ++i) {
     FusedPlan f;
@@ -1335,7 +1335,7 @@ int32_t launch_select_scan_step_pair(const Layout& L, const void* const kcache[2
     if (rc != HCA_OK) return rc;
     so[i] = f.so;
   }
-  return launch_select_step_pair(L, kcache, q, nr, nmax, so, stamps, nx, st);
+  return launch_select_step_pair(L, kcache, q, nr, nmax, so, stamps, nx, st, done);
 }
 
 // 2. the selecting scan
