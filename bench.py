@@ -406,6 +406,53 @@ def per_layer_latency(cfg, main, side, link_peak, iters=8, fused=False, streams=
     return out
 
 
+def per_layer_latency_hybrid(cfg, stream, host_threads, iters=8):
+    """One layer of workload `cfg`, decode steps one after another, with the hybrid value side: the step driver
+    with one layer and all four stages on one stream (nothing can overlap: the next step's append waits for this
+    step's output), 5/8 of every row's chunks of selected tokens summed by the host threads while the rest is
+    gathered over the link.  Time from the first kernel of a step to its y, mean over `iters` steps enqueued back
+    to back.  For config 5 the cache is first evicted to its 50% cap, as in per_layer_latency."""
+    import torch
+    import synth_inputs as S
+    from paper_2507_19823_amd import binding as B
+    w = S.CONFIGS[cfg]
+    warm = 3
+    nsplit = -(-w.k // 256)
+    hc = max(1, round(nsplit * 5 / 8))
+    m = Model(w, 1, 0, iters + warm + 2, n_sel=3, fused=True, host_chunks=hc, host_threads=host_threads)
+    m.build(1)
+    m.make_steps(iters + warm + 2)
+    resident = w.n + warm
+    if cfg == 5:
+        B.hca_evict(m.shape, m.kcache[0], m.acc[0], m.pos[0], m.n[0], w.evict_keep, 2, None, m.ws_main,
+                    None, None, None, stream)
+        m.n[0] = [w.evict_keep] * w.batch
+        resident = w.evict_keep + warm
+        torch.cuda.synchronize()
+    m.layer_idx_on = True
+    m.native_pipeline(stream, stream, stream, stream, 0)
+    for t in range(warm):
+        m.decode_step_native(t)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for i in range(iters):
+        m.decode_step_native(warm + i)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    status = B.hca_pipeline_host_status(m.pl)
+    B.hca_pipeline_destroy(m.pl)
+    del m
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    torch._C._host_emptyCache()
+    return {"ms_per_layer": ms, "resident_tokens": resident, "host_chunks_of": [hc, nsplit],
+            "host_threads": host_threads, "host_timeouts_bad_rows": list(status),
+            "how": "hca_pipeline_step with one layer and one stream for all four stages, scan and top-k fused; "
+                   "steps enqueued back to back, each waits for the one before"}
+
+
 def per_layer_latency_grouped(cfg, groups, streams, iters=8, fused=True):
     """One layer of workload `cfg` (synth_inputs.CONFIGS) with its rows (sequences x KV heads) cut into `groups` parts that
     go through the four stages as a pipeline: the gather of one part overlaps the scan of the next.  Unlike
@@ -1230,6 +1277,11 @@ def main():
                                              "select_scan_event_bracket_ms": f.get("scan_event_bracket_ms")}
             log(f"latency probe {name}: {f['ms_per_layer']:.3f} ms per layer with scan and top-k fused "
                 f"({f['score_topk_ms']:.3f} ms for the two; the selecting scan alone {f['key_scan_ms']:.3f} ms)")
+            if args.pipeline == "native" and args.host_threads > 0:
+                h = per_layer_latency_hybrid(c, main_s[0], args.host_threads)
+                latency[name]["hybrid_value_side"] = h
+                log(f"latency probe {name}: {h['ms_per_layer']:.3f} ms per layer with scan and top-k fused and "
+                    f"{h['host_chunks_of'][0]} of {h['host_chunks_of'][1]} chunks of the value side on the host")
             for parts in args.latency_parts:
                 g = per_layer_latency_grouped(c, parts, (main_s[0], extra[0], gath_s[0], extra[1]))
                 log(f"latency probe {name}: {g['ms_per_layer']:.3f} ms per layer as {parts} pipelined parts "

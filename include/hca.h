@@ -261,7 +261,11 @@ typedef struct {
 #define HCA_PIPELINE_MAX_SEL 64
 #define HCA_PIPELINE_MAX_PIPE 8
 typedef struct {
-  void *stream_scan, *stream_topk, *stream_gather, *stream_attend;   /* four distinct hipStream_t */
+  /* hipStream_t of the four stages.  Distinct streams let the stages of different layers overlap (the throughput
+     form).  The same stream may be given for several stages, which then run one after another; with one stream
+     for all four a step is the plain sequence of its kernels with no event hop between them - the form with the
+     lowest latency for a single layer. */
+  void *stream_scan, *stream_topk, *stream_gather, *stream_attend;
   float* sel[HCA_PIPELINE_MAX_SEL]; /* device, fp32 [batch, n_kv_heads, capacity] each; the first n_sel are used */
   int32_t n_sel;                 /* 3 .. HCA_PIPELINE_MAX_SEL score buffers.  With one per layer the key scan of a
                                     layer never waits for the top-k of an earlier layer to release its buffer */

@@ -437,7 +437,15 @@ def test_native_step_driver_with_two_bit_codes(H, oracle, Lr, n_sel, spare, tau,
     _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, 2, 64)
 
 
-def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs):
+@pytest.mark.parametrize("Lr,n_sel,spare,fused,host,bits,gs", [
+    (1, 3, False, True, 2, 4, 32), (1, 3, False, True, 1, 2, 64), (3, 3, True, False, 2, 4, 32), (2, 3, False, True, 0, 4, 32)])
+def test_native_step_driver_on_one_stream(H, oracle, Lr, n_sel, spare, fused, host, bits, gs):
+    """All four stages handed the same stream (the form the single-layer latency figures use): nothing
+    overlaps, results as with four streams."""
+    _step_driver_case(oracle, Lr, n_sel, spare, 0.0, fused, host, bits, gs, one_stream=True)
+
+
+def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs, one_stream=False):
     """hca_pipeline_step over 1 to 5 layers (score buffers shared between layers or one each), 12 decode
     steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k (as scan +
     top-k or fused as in hca_score_topk) or the cumulative-weight selection of Eq. 4 (tau > 0): every layer's
@@ -475,6 +483,8 @@ def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs):
         V[:, :n0] = _rows(data[l]["values"])
         oV.append(V)
     streams = [torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()]
+    if one_stream:
+        streams = [streams[0]] * 4
     d = B.hca_pipeline_desc()
     d.stream_scan, d.stream_topk, d.stream_gather, d.stream_attend = (s.cuda_stream for s in streams)
     wsb = B.hca_workspace_bytes(shape, w.k, n0)
