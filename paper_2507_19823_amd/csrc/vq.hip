@@ -105,6 +105,296 @@ __global__ __launch_bounds__(256) void vq_assign_kernel(int g, int c, int n_kv_h
   }
 }
 
+// Bulk calls (a prefill block, a whole context): the matrix cores find, for every token, the few centroids that can
+// be the nearest one, and only those go through the exact distance chain of vq_assign_kernel - the same index, bit
+// for bit.
+//   e(c) = |c|^2 / 2 - x.c  (= (distance - |x|^2) / 2) comes out of v_mfma_f32_32x32x16_f16, 32 centroids x 32 tokens
+//   per instruction, with every factor an fp16 number so that the 16 products are exact in fp32:
+//     k 0..3   A = -hi(c_d)            B = x_d        hi(c) = fp16(c), lo(c) = fp16(c - hi(c))
+//     k 4..7   A = -lo(c_d)            B = x_d        (x is fp16 as it arrives)
+//     k 8..10  A = h1, h2, h3          B = 1          h = fp32 |c|^2 / 2 cut into three fp16 pieces
+//     k 11..13 A = 1                   B = t1, t2, t3 pass 2 only: t = -(threshold) in three fp16 pieces
+//   Errors against the exact e(c), with S = |x|^2 + max_c |c|^2 < 2^15 (so that no piece overflows fp16; fp16
+//   denormals are kept by the instruction): c_d - hi - lo is at most 2^-22 |c_d| + 2^-25, h and t lose at most
+//   2^-33 of themselves + 2^-25, the fp32 |c|^2 chain 4 u |c|^2 (u = 2^-24), and the instruction's 15 additions at
+//   most 2^-23 each of sum |terms| <= 2.01 S whatever their order and rounding: together below 2^-17.9 S + 2^-23.
+//   The exact chain d(c) itself is within 7 u d <= 2^-20.2 S of the truth (in units of e).  With
+//   delta = 2^-16 S + 2^-21 - three times the sum of those - the winner c* of the exact chain (first smallest d)
+//   has e(c*) - (min_c e(c) + 2 delta) < 0 as computed in pass 2.
+//   Pass 1 takes min_c e(c) per token (eight v_min3 per instruction).  Pass 2 runs the same products with the
+//   threshold folded in and collects the sign bits (eight v_or3): a centroid whose result is negative is noted
+//   in the lane's candidate list - one or two per token; a candidate that finds the list full goes through the
+//   exact chain at once and only the best of those is kept.  Then the exact chain runs over the list in ascending
+//   index order.  A token whose S is out of range or not a number takes the exact chain over every centroid
+//   instead (same result, the speed of the vector form).
+// One workgroup of 8 waves = 1024 tokens x one group; a wave holds 128 tokens (four 32-token B operands) against
+// centroids that pass through LDS 512 at a time (A operands only, double-buffered, one barrier per chunk).
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+constexpr int kAmChunk = 512;       // centroids per LDS chunk
+// the matrix-core form is taken from 1024 tokens x 2048 centroids (or 4096 x 512) on: level with the vector forms
+// at 256 centroids, ahead of them from 512 on, and a workgroup wants 1024 tokens
+constexpr int64_t kAssignMfmaMinTokens = 1024;
+constexpr int kAssignMfmaMinCodewords = 512;
+constexpr int64_t kAssignMfmaMinWork = (int64_t)1 << 21;
+constexpr int kAmCand = 3;          // candidate slots per lane (two lanes per token); further ones are judged at once
+
+__device__ __forceinline__ _Float16 am_f16(float v) { return (_Float16)v; }
+
+template <int DBAR, bool WIDE>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void vq_assign_mfma_kernel(
+    int g, int c, int n_kv_heads, int64_t cap, const float* __restrict__ centroids, uint8_t* __restrict__ pcache,
+    const uint16_t* __restrict__ k_new, int64_t T, NRes nr, float* __restrict__ acc, int32_t* __restrict__ pos,
+    NRes vrow0) {
+  // A operands: [buffer][tile of 32 centroids][k block 0 / 1][row] x 8 fp16
+  __shared__ __align__(16) v8h sA[2][kAmChunk / 32][2][32];
+  __shared__ float s_cmax[8];
+  const int row = blockIdx.y, grp = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int col = lane & 31, kb = lane >> 5;
+  const int64_t tok0 = (int64_t)blockIdx.x * 1024 + w * 128;
+  const float* cg = centroids + ((int64_t)(row % n_kv_heads) * g + grp) * c * DBAR;
+
+  // this lane's tokens: |x|^2 and the B operand of its k block (x itself is read again for the exact chain)
+  float x2[4];
+  v8h bop[4];
+#pragma unroll
+  for (int tt = 0; tt < 4; ++tt) {
+    const int64_t t = tok0 + 32 * tt + col;
+    const int64_t tc = t < T ? t : T - 1;
+    const uint16_t* src = k_new + ((int64_t)row * T + tc) * kHeadDim + grp * DBAR;
+    float n2 = 0.f;
+    _Float16 xh[4] = {(_Float16)0.f, (_Float16)0.f, (_Float16)0.f, (_Float16)0.f};
+#pragma unroll
+    for (int d = 0; d < DBAR; ++d) {
+      const uint16_t bits = src[d];
+      const float xf = h2f(bits);
+      xh[d] = __builtin_bit_cast(_Float16, bits);
+      n2 = fmaf(xf, xf, n2);
+    }
+    x2[tt] = n2;
+    const _Float16 one = (_Float16)1.f, zero = (_Float16)0.f;
+    if (kb == 0) bop[tt] = v8h{xh[0], xh[1], xh[2], xh[3], xh[0], xh[1], xh[2], xh[3]};
+    else bop[tt] = v8h{one, one, one, zero, zero, zero, zero, zero};
+  }
+
+  const int nchunk = (c + kAmChunk - 1) / kAmChunk;
+  v8h ra0, ra1;                      // this thread's centroid of the chunk on its way to LDS
+  float rn = 0.f;
+  auto fetch = [&](int ch) {
+    const int cc = ch * kAmChunk + tid;
+    const _Float16 one = (_Float16)1.f, zero = (_Float16)0.f;
+    ra0 = v8h{zero, zero, zero, zero, zero, zero, zero, zero};
+    ra1 = v8h{(_Float16)65504.f, zero, zero, one, one, one, zero, zero};     // past the codebook: never the minimum
+    rn = 0.f;
+    if (cc < c) {
+      float nn = 0.f;
+      _Float16 hi[4] = {zero, zero, zero, zero}, lo[4] = {zero, zero, zero, zero};
+#pragma unroll
+      for (int d = 0; d < DBAR; ++d) {
+        const float v = cg[(int64_t)cc * DBAR + d];
+        nn = fmaf(v, v, nn);
+        hi[d] = am_f16(-v);
+        lo[d] = am_f16(-v - (float)hi[d]);
+      }
+      const float hh = 0.5f * nn;
+      const _Float16 h1 = am_f16(hh);
+      const float r1 = hh - (float)h1;
+      const _Float16 h2 = am_f16(r1);
+      const _Float16 h3 = am_f16(r1 - (float)h2);
+      ra0 = v8h{hi[0], hi[1], hi[2], hi[3], lo[0], lo[1], lo[2], lo[3]};
+      ra1 = v8h{h1, h2, h3, one, one, one, zero, zero};
+      rn = nn;
+    }
+  };
+  auto commit = [&](int buf) {
+    sA[buf][tid >> 5][0][tid & 31] = ra0;
+    sA[buf][tid >> 5][1][tid & 31] = ra1;
+  };
+  auto tiles_of = [&](int ch) { const int left = c - ch * kAmChunk; return left >= kAmChunk ? kAmChunk / 32 : (left + 31) / 32; };
+  const v16f zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // pass 1: min over the centroids of e(c), and the largest |c|^2
+  float m[4] = {INFINITY, INFINITY, INFINITY, INFINITY};
+  float mycmax = 0.f;
+  bool cbad = false;                 // a centroid whose |c|^2 is not a number or not finite
+  fetch(0);
+  commit(0);
+  mycmax = rn;
+  cbad = !(rn < INFINITY);
+  __syncthreads();
+  for (int ch = 0; ch < nchunk; ++ch) {
+    const int buf = ch & 1;
+    if (ch + 1 < nchunk) fetch(ch + 1);
+    const int ntile = tiles_of(ch);
+    for (int t = 0; t < ntile; ++t) {
+      const v8h a = sA[buf][t][kb][col];
+      v16f d[4];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) d[tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bop[tt], zero16, 0, 0, 0);
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        float mm = m[tt];
+#pragma unroll
+        for (int j = 0; j < 16; j += 2) mm = fminf(fminf(mm, d[tt][j]), d[tt][j + 1]);
+        m[tt] = mm;
+      }
+    }
+    if (ch + 1 < nchunk) {
+      commit(buf ^ 1);
+      cbad = cbad || !(rn < INFINITY);
+      if (rn > mycmax) mycmax = rn;
+    }
+    __syncthreads();
+  }
+  if (cbad) mycmax = INFINITY;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) mycmax = fmaxf(mycmax, __shfl_xor(mycmax, o));
+  if (lane == 0) s_cmax[w] = mycmax;
+  __syncthreads();
+  float cmax2 = s_cmax[0];
+#pragma unroll
+  for (int x = 1; x < 8; ++x) cmax2 = fmaxf(cmax2, s_cmax[x]);
+
+  // thresholds into the B operands of k block 1; tokens out of range take the exact chain over everything
+  bool full[4];
+#pragma unroll
+  for (int tt = 0; tt < 4; ++tt) {
+    float mm = fminf(m[tt], __shfl_xor(m[tt], 32));
+    const float S = x2[tt] + cmax2;
+    full[tt] = !(S < 32768.f) || !(mm == mm) || !(fabsf(mm) < 65000.f);
+    const float thr = mm + 2.f * (S * 1.52587890625e-5f + 4.76837158203125e-7f);      // 2^-16 S + 2^-21
+    const float tneg = full[tt] ? 0.f : -thr;
+    const _Float16 t1 = am_f16(tneg);
+    const float r1 = tneg - (float)t1;
+    const _Float16 t2 = am_f16(r1);
+    const _Float16 t3 = am_f16(r1 - (float)t2);
+    if (kb == 1) { bop[tt][3] = t1; bop[tt][4] = t2; bop[tt][5] = t3; }
+  }
+
+  // pass 2: the same products with the threshold folded in; negative results are candidates
+  int cand[4][kAmCand];
+  int ncand[4] = {0, 0, 0, 0};
+  float rest_d[4] = {INFINITY, INFINITY, INFINITY, INFINITY};      // best of the candidates that found the list full
+  int rest_i[4] = {0x7fffffff, 0x7fffffff, 0x7fffffff, 0x7fffffff};
+#pragma unroll
+  for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+    for (int q = 0; q < kAmCand; ++q) cand[tt][q] = 0;
+  fetch(0);
+  commit(0);
+  __syncthreads();
+  for (int ch = 0; ch < nchunk; ++ch) {
+    const int buf = ch & 1;
+    if (ch + 1 < nchunk) fetch(ch + 1);
+    const int ntile = tiles_of(ch);
+    for (int t = 0; t < ntile; ++t) {
+      const v8h a = sA[buf][t][kb][col];
+      v16f d[4];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) d[tt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bop[tt], zero16, 0, 0, 0);
+      uint32_t sg[4];
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        uint32_t o = 0;
+#pragma unroll
+        for (int j = 0; j < 16; j += 2) o = o | __float_as_uint(d[tt][j]) | __float_as_uint(d[tt][j + 1]);
+        sg[tt] = o;
+      }
+      const uint32_t any = sg[0] | sg[1] | sg[2] | sg[3];
+      if (__builtin_amdgcn_ballot_w64((int32_t)any < 0) == 0) continue;     // mostly: no candidate in these 32 x 128
+      const int cbase = ch * kAmChunk + t * 32 + 4 * kb;
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        if (__builtin_amdgcn_ballot_w64((int32_t)sg[tt] < 0) == 0) continue;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+          // rows of the 32x32 result held by this lane: 8 * (j / 4) + 4 * kb + j % 4, ascending in j
+          if ((int32_t)__float_as_uint(d[tt][j]) < 0) {
+            const int cidx = cbase + 8 * (j >> 2) + (j & 3);
+            if (cidx < c) {
+#pragma unroll
+              for (int q = 0; q < kAmCand; ++q)
+                if (ncand[tt] == q) cand[tt][q] = cidx;
+              if (ncand[tt] >= kAmCand) {
+                // the list is full: this one goes through the exact chain now and only the best of these is kept
+                // (they arrive in ascending index order, so a strict comparison keeps the first smallest)
+                const int64_t tk = tok0 + 32 * tt + col;
+                const uint16_t* src = k_new + ((int64_t)row * T + (tk < T ? tk : T - 1)) * kHeadDim + grp * DBAR;
+                float dist = 0.f;
+#pragma unroll
+                for (int dd = 0; dd < DBAR; ++dd) {
+                  const float e = h2f(src[dd]) - cg[(int64_t)cidx * DBAR + dd];
+                  dist = fmaf(e, e, dist);
+                }
+                if (dist < rest_d[tt]) { rest_d[tt] = dist; rest_i[tt] = cidx; }
+              }
+              ncand[tt] += 1;
+            }
+          }
+        }
+      }
+    }
+    if (ch + 1 < nchunk) commit(buf ^ 1);
+    __syncthreads();
+  }
+
+  // the exact chain over the candidates (ascending index per lane), or over every centroid
+  const int b = row / n_kv_heads;
+#pragma unroll
+  for (int tt = 0; tt < 4; ++tt) {
+    float bd = INFINITY;
+    int bi = 0x7fffffff;
+    const int64_t t = tok0 + 32 * tt + col;
+    float xs[DBAR];
+    {
+      const uint16_t* src = k_new + ((int64_t)row * T + (t < T ? t : T - 1)) * kHeadDim + grp * DBAR;
+#pragma unroll
+      for (int dd = 0; dd < DBAR; ++dd) xs[dd] = h2f(src[dd]);
+    }
+    auto exact = [&](int cidx) {
+      float dist = 0.f;
+#pragma unroll
+      for (int dd = 0; dd < DBAR; ++dd) {
+        const float e = xs[dd] - cg[(int64_t)cidx * DBAR + dd];
+        dist = fmaf(e, e, dist);
+      }
+      return dist;
+    };
+    if (full[tt]) {
+      for (int cidx = kb; cidx < c; cidx += 2) {
+        const float dist = exact(cidx);
+        if (dist < bd) { bd = dist; bi = cidx; }
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < kAmCand; ++q) {
+        if (q < ncand[tt]) {
+          const float dist = exact(cand[tt][q]);
+          if (dist < bd) { bd = dist; bi = cand[tt][q]; }
+        }
+      }
+      if (rest_d[tt] < bd) { bd = rest_d[tt]; bi = rest_i[tt]; }       // later indices than the list's
+    }
+    const float od = __shfl_xor(bd, 32);
+    const int ob = __shfl_xor(bi, 32);
+    if (od < bd || (od == bd && ob < bi)) { bd = od; bi = ob; }
+    // the ascending scan starts from centroid 0 whatever its distance: no finite distance at all, or a first
+    // distance that is not a number, leave it the winner
+    const float d0 = exact(0);
+    const int win = (bi == 0x7fffffff || d0 != d0) ? 0 : bi;
+    if (kb == 0 && t < T) {
+      const int64_t slot = nr.n[b] + t;
+      if constexpr (WIDE) reinterpret_cast<uint16_t*>(pcache)[vq_wide_at(g, vq_tiles(cap), row, slot, grp)] = (uint16_t)win;
+      else pcache[((int64_t)row * cap + slot) * g + vq_byte_of(grp, slot)] = (uint8_t)win;
+      if (grp == 0) {
+        if (acc != nullptr) acc[(int64_t)row * cap + slot] = 0.0f;
+        if (pos != nullptr) pos[(int64_t)row * cap + slot] = (int32_t)(vrow0.n[b] + t);
+      }
+    }
+  }
+}
+
 // Few tokens per call (decode appends): one workgroup per (token, row, four groups); a wave takes one group
 // and spreads the group's centroids over its lanes (lane, lane + 64, ...; four distances in flight per lane),
 // then the lanes' candidates are reduced by (distance, index): the smaller distance wins, equal distances go
@@ -512,7 +802,14 @@ int32_t launch_vq_assign(const Layout& L, int g, int c, const float* centroids, 
     else if (wide) vq_assign_kernel<2, true, GPW><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);      \
     else vq_assign_kernel<2, false, GPW><<<GRID, 256, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);               \
   } while (0)
-  if (T <= 8) {                                     // decode appends: parallel over centroids, not over tokens
+  if (T >= kAssignMfmaMinTokens && c >= kAssignMfmaMinCodewords && T * c >= kAssignMfmaMinWork) {
+    // a block or a context: shortlist on the matrix cores, exact chain on the shortlist
+    dim3 gm((unsigned)((T + 1023) / 1024), (unsigned)L.rows, (unsigned)g);
+    if (g == 32 && wide) vq_assign_mfma_kernel<4, true><<<gm, 512, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+    else if (g == 32) vq_assign_mfma_kernel<4, false><<<gm, 512, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+    else if (wide) vq_assign_mfma_kernel<2, true><<<gm, 512, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+    else vq_assign_mfma_kernel<2, false><<<gm, 512, 0, st>>>(g, c, L.n_kv_heads, L.cap, centroids, pcache, kn, T, nr, acc_opt, pos_opt, vrow0);
+  } else if (T <= 8) {                              // decode appends: parallel over centroids, not over tokens
     dim3 gs((unsigned)T, (unsigned)L.rows, (unsigned)(g / 4));
     HCA_ASSIGN(vq_assign_small_kernel, gs);
   } else if ((T + 63) / 64 * L.rows * (g / 4) < 16 * 1024) {

@@ -142,6 +142,50 @@ def test_assign_table_scores_bit_exact(B, oracle, g, c, G, hkv, batch):
         assert np.all(np.abs(zg[hq, :n_used].astype(np.float64) - zp[hq, :n_used]) <= bound)
 
 
+@pytest.mark.parametrize("g,c,big", [(32, 600, False), (64, 1030, False), (32, 520, True)])
+def test_bulk_assign_with_awkward_keys_and_centroids(B, oracle, g, c, big):
+    """The bulk form of the assignment (matrix-core shortlist, exact chain on the shortlist) on what could trip
+    it: a codebook size that is no multiple of the tile, duplicate centroids and centroids one fp32 step apart
+    (ties and near-ties: the lowest index, the exact chain's verdict), centroids of very different norms, keys that
+    are zero, fp16-subnormal, infinite or so large that the shortlist bound does not apply, keys that sit exactly
+    on a centroid; with `big` some centroids are large enough that no token can use the shortlist."""
+    rng = np.random.default_rng(3 * g + c)
+    batch, hkv, G, n = 1, 2, 2, 4200
+    dbar = D // g
+    cap = n + 8
+    keys = rng.standard_normal((batch, hkv, n, D)).astype(np.float16)
+    cen = (rng.standard_normal((hkv, g, c, dbar)) * 1.2).astype(np.float32)
+    cen[:, :, 7] = cen[:, :, 3]                                        # exact duplicates
+    cen[:, :, 40] = np.nextafter(cen[:, :, 41], np.float32(np.inf))      # one step apart
+    cen[:, :, 90] = np.nextafter(cen[:, :, 91], np.float32(-np.inf))
+    cen[:, :, 100:110] *= 9.0                                          # large norms
+    cen[:, :, 110:120] *= 1e-3                                         # tiny norms
+    cen[:, :, c - 1] = cen[:, :, c - 2]                                # a duplicate in the last, ragged tile
+    if big:
+        cen[:, :, 200:203] *= 400.0
+    kf = keys.reshape(hkv, n, g, dbar)
+    kf[:, 10] = 0.0
+    kf[:, 11] = np.float16(6e-8)                                       # subnormal
+    kf[:, 12, :, 0] = np.float16(np.inf)
+    kf[:, 13, :, 0] = np.float16(-np.inf)
+    kf[:, 14] = np.float16(300.0)                                      # beyond the shortlist's range
+    kf[:, 15, ::2] = np.float16(-250.0)
+    for t in range(20, 60):                                            # keys exactly on a centroid (as far as fp16 allows)
+        kf[:, t] = cen[:, :, (t * 13) % c].astype(np.float16)
+    kf[:, 60] = cen[:, :, 3].astype(np.float16)                        # on the duplicated centroid
+    kf[:, 61] = cen[:, :, 41].astype(np.float16)
+    keys = kf.reshape(batch, hkv, n, D)
+    R = batch * hkv
+    st = _State(B, batch, hkv * G, hkv, cap, g, c, cen, 64)
+    st.assign(torch.from_numpy(keys))
+    torch.cuda.synchronize()
+    oc = oracle.VQCache(R, cap, cen)
+    oracle.vq_assign(oc, keys.reshape(R, n, D))
+    Pg = st.P_rows()
+    bad = np.argwhere(Pg[:, :n] != oc.P[:, :n].astype(st.idx_dtype()))
+    assert len(bad) == 0, f"{len(bad)} indices differ, first (row, token, group): {bad[:5].tolist()}"
+
+
 @pytest.mark.parametrize("g,c", [(32, 256), (32, 8192), (64, 1024)])
 def test_blockwise_bulk_assign_equals_one_shot(B, oracle, g, c):
     """Block-wise prefill hands the keys over a block at a time (App. B): appending 40 000 tokens per row in blocks
