@@ -933,9 +933,18 @@ def prefill_blocks(w, sizes=(1024, 4096, 16384, 65536, 262144)):
         for T in sizes:
             total = max(total_cap, T)
             ms, nb = run(lambda blk, T_, n: B.hca_vq_assign(shape, cb, P, blk, T_, n), total, T)
-            tf = rows * T * g * c * (128 // g) * 3 / ms / 1e9
-            res.append({"block_tokens": T, "blocks": nb, "ms_per_block": ms, "tokens_per_s": w.batch * T / ms * 1e3,
-                        "TFLOPs": tf, "frac_of_fp32_vector_peak": tf / 157.3})
+            tf = rows * T * g * c * (128 // g) * 3 / ms / 1e9          # the exhaustive exact search's flops
+            r = {"block_tokens": T, "blocks": nb, "ms_per_block": ms, "tokens_per_s": w.batch * T / ms * 1e3}
+            if T >= 1024 and c >= 512 and T * c >= (1 << 21):
+                # the library's bulk form from this size on: two passes of v_mfma_f32_32x32x16_f16 over every
+                # (token, group, centroid), 16 products each, then the exact search on the shortlist only
+                mt = rows * T * g * c * 2 * 16 * 2 / ms / 1e9
+                r.update({"form": "matrix-core shortlist + exact chain on the shortlist", "matrix_TFLOPs": mt,
+                          "frac_of_f16_matrix_peak": mt / 2500.0, "exhaustive_search_equivalent_TFLOPs": tf})
+            else:
+                r.update({"form": "exact chain over every centroid (vector ALU)", "TFLOPs": tf,
+                          "frac_of_fp32_vector_peak": tf / 157.3})
+            res.append(r)
         out[f"codebook_g{g}_c{c}"] = res
         del P, cen
     del d, keys
@@ -1314,7 +1323,7 @@ def main():
     if not args.no_latency and args.config == 4:
         prefill = prefill_blocks(w)
         log("block-wise key compression, fraction of the bound by block size "
-            + "; ".join(f"{k_}: " + " ".join(f"{r.get('frac_of_hbm_peak', r.get('frac_of_fp32_vector_peak')):.2f}" for r in v_)
+            + "; ".join(f"{k_}: " + " ".join(f"{r.get('frac_of_hbm_peak', r.get('frac_of_fp32_vector_peak', r.get('frac_of_f16_matrix_peak'))):.2f}" for r in v_)
                         for k_, v_ in prefill.items() if isinstance(v_, list) and v_ and isinstance(v_[0], dict)))
     if not args.no_latency and args.config == 4:
         correlated = correlated_selection(w)
