@@ -270,6 +270,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4))) void v
     const _Float16 t2 = am_f16(r1);
     const _Float16 t3 = am_f16(r1 - (float)t2);
     if (kb == 1) { bop[tt][3] = t1; bop[tt][4] = t2; bop[tt][5] = t3; }
+    if (full[tt]) {
+      // no shortlist for this token: x = 0 and t = +1 make every result of pass 2 |c|^2 / 2 + 1 > 0
+      const _Float16 one = (_Float16)1.f, zero = (_Float16)0.f;
+      if (kb == 0) bop[tt] = v8h{zero, zero, zero, zero, zero, zero, zero, zero};
+      else bop[tt] = v8h{one, one, one, one, zero, zero, zero, zero};
+    }
   }
 
   // pass 2: the same products with the threshold folded in; negative results are candidates
