@@ -445,7 +445,15 @@ def test_native_step_driver_on_one_stream(H, oracle, Lr, n_sel, spare, fused, ho
     _step_driver_case(oracle, Lr, n_sel, spare, 0.0, fused, host, bits, gs, one_stream=True)
 
 
-def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs, one_stream=False):
+@pytest.mark.parametrize("Lr,n_sel,fused,host", [(5, 5, True, 2), (3, 3, True, 0), (4, 4, False, 0)])
+def test_native_step_driver_with_timing_on(H, oracle, Lr, n_sel, fused, host):
+    """The same steps with the driver's timing on - event brackets around the scan launches (in the paired form the
+    launch's completion event is the bracket's end and what the selection waits for) and per-wave clock stamps:
+    results unchanged, a positive duration for every timed launch, stamps in order."""
+    _step_driver_case(oracle, Lr, n_sel, False, 0.0, fused, host, 4, 32, timing=True)
+
+
+def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs, one_stream=False, timing=False):
     """hca_pipeline_step over 1 to 5 layers (score buffers shared between layers or one each), 12 decode
     steps, staggered eviction every 4 steps (sliced into a spare buffer set, or in place), top-k (as scan +
     top-k or fused as in hca_score_topk) or the cumulative-weight selection of Eq. 4 (tau > 0): every layer's
@@ -522,7 +530,12 @@ def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs, one_
     d.host_chunks, d.host_threads = host, 3
     # two scan streams, or one scan launch per two layers, wherever the mode allows it
     d.dual_scan = (2 if Lr in (5, 1) else 1) if (fused and n_sel >= Lr and Lr != 4) else 0
-    pl = B.hca_pipeline_create(shape, Lr, d, 0)
+    n_slots = 3 if timing else 0
+    if timing:
+        pairs = B.hca_scan_stamp_pairs(shape, cap)
+        stamps = torch.zeros(n_slots, Lr, pairs, 2, dtype=torch.int64, device=dev)
+        d.scan_stamps, d.scan_stamp_pairs, d.timing_layer_stride = stamps.data_ptr(), pairs, 1
+    pl = B.hca_pipeline_create(shape, Lr, d, n_slots)
     layers = (B.hca_layer * Lr)()
     for l in range(Lr):
         layers[l].kcache, layers[l].acc, layers[l].pos = kc[l].data_ptr(), acc[l].data_ptr(), pos[l].data_ptr()
@@ -539,8 +552,21 @@ def _step_driver_case(oracle, Lr, n_sel, spare, tau, fused, host, bits, gs, one_
         due = [(t + 1 + l) % E == 0 for l in range(Lr)]
         ev = (C.c_int64 * Lr)(*[n0 if x else 0 for x in due])
         torch.cuda.synchronize()
-        B.hca_pipeline_step(pl, layers, nres, n0 + t, w.k, n0, n0, vnew, sm, ev, E, -1)
+        B.hca_pipeline_step(pl, layers, nres, n0 + t, w.k, n0, n0, vnew, sm, ev, E, t % n_slots if timing else -1)
         torch.cuda.synchronize()
+        if timing:
+            ms = B.hca_pipeline_scan_ms(pl, t % n_slots, Lr)
+            paired = d.dual_scan == 2
+            for l in range(Lr):
+                if paired and l % 2 == 1:
+                    assert ms[l] == -1.0, f"step {t}: the second layer of a pair reports no launch of its own"
+                else:
+                    assert 0.0 < ms[l] < 100.0, f"step {t} layer {l}: scan bracket {ms[l]} ms"
+            st_ = stamps[t % n_slots].cpu().numpy()
+            for l in range(Lr):
+                used = st_[l][st_[l, :, 0] > 0]
+                assert len(used) > 0 and np.all(used[:, 1] >= used[:, 0]), f"step {t} layer {l}: wave stamps"
+            stamps[t % n_slots].zero_()
         for l in range(Lr):
             oc = ocs[l]
             n = int(oc.n[0])
