@@ -273,7 +273,9 @@ def test_evict_bit_exact_stagewise(H, oracle, bits, gs, n, M, Rp, mode):
 
 @pytest.mark.parametrize("with_list", [True, False])
 @pytest.mark.parametrize("bits,gs", [(4, 32), (2, 64)])
-@pytest.mark.parametrize("n,M,Rp", [(13000, 12000, 16), (13000, 12990, 16), (9000, 4100, 0)])
+@pytest.mark.parametrize("n,M,Rp", [(13000, 12000, 16), (13000, 12990, 16), (9000, 4100, 0),
+                                    # first dropped slot on a chunk edge of the ordered pass (8192) and just before it
+                                    (8300, 8208, 16), (8300, 8207, 16)])
 def test_evict_when_the_threshold_is_zero(H, oracle, bits, gs, n, M, Rp, with_list):
     """Rows whose accumulated scores are mostly exact zeros, as in a long context, with the number of positive
     entries just below, at and just above the number of slots to keep from the unprotected part (the cases on
