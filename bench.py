@@ -1461,6 +1461,10 @@ def main():
                 m = (gaps >= a) & (gaps < b)
                 hist.append(f"[{a},{b}): {int(m.sum())} gaps, {float(gaps[m].sum()) / args.steps:.0f} us/step")
             log("scan gap histogram: " + "; ".join(hist))
+            # mean pause before each launch of a step (launch 0: the pause across the step boundary), over the steps
+            nl_ = starts.shape[1]
+            by_launch = torch.cat([gaps.new_zeros(1), gaps]).reshape(args.steps, nl_)[1:].mean(0)
+            log("mean pause before launch i of a step, us: " + " ".join(f"{float(x):.0f}" for x in by_launch))
             gs = model.gstamps
             g_start = torch.where(gs[..., 0] > 0, gs[..., 0], torch.full_like(gs[..., 0], 1 << 62)).amin(-1).reshape(-1).double()
             g_end = gs[..., 1].amax(-1).reshape(-1).double()
@@ -1490,8 +1494,10 @@ def main():
             log("largest gather gaps (us @ step.layer): " + " ".join(
                 "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(gtop.values, gtop.indices)))
             top = torch.topk(gaps, 24)
-            log("largest gaps (us @ step.layer): " + " ".join(
-                "%.0f@%d.%d" % (float(v), (int(i) + 1) // L, (int(i) + 1) % L) for v, i in zip(top.values, top.indices)))
+            # a gap sits before launch (i + 1) of the flat list; a launch scans layers_per_launch layers
+            log("largest gaps (us @ step.first layer of the launch behind the gap): " + " ".join(
+                "%.0f@%d.%d" % (float(v), (int(i) + 1) // nl_, ((int(i) + 1) % nl_) * layers_per_launch)
+                for v, i in zip(top.values, top.indices)))
     else:
         layers_per_launch = 1
         events = [e for step_events in events for e in step_events]
