@@ -463,11 +463,14 @@ int32_t hca_pipeline_step(hca_pipeline* p, hca_layer* layers, int64_t* n_residen
     const void* qq[4];
     NRes nrs[4];
     SelectOut sos[4];
+    // layer_done events are recorded in layer order on the attend stream (not so with spare-buffer evictions, whose
+    // last slice records it later): the wait for the last of these layers then covers the others
+    const bool one_wait = !p->sel_waits && p->d.spare_kcache == nullptr;
     for (int l2 = 0; l2 < ns; ++l2) {
       int64_t m2;
       int32_t rc = lengths(l2, &nrs[l2], &m2);
       if (rc != HCA_OK) return rc;
-      rc = wait_layer(l2);
+      if (!one_wait || l2 == ns - 1) rc = wait_layer(l2);
       if (rc != HCA_OK) return rc;
       kc[l2] = layers[l2].kcache;
       qq[l2] = layers[l2].q;
